@@ -1,0 +1,176 @@
+#!/usr/bin/env python3
+"""Benchmark of the HARP rotation hot path on one MI355X.
+
+A step is one pass of the hot path over one batch of synthetic activations already resident
+in device memory: ``harp_apply`` (load + signs, every stage on chip, store) followed by
+``harp_apply_transpose`` on the same batch.  Each call transforms n rows, so a step counts
+2 n row-transforms.  Batches rotate through a pool larger than the 256 MB Infinity Cache so
+the timed launches read and write device memory, not a cache.
+
+Prints ONE JSON line (metric of the benchmark spec: rotation rows/s and achieved HBM GB/s as a
+fraction of the 8 TB/s peak), with a ``roofline`` object for the dominant kernel (timed
+with HIP events on the launch stream) and a ``cpu_baseline`` object (the float64 oracle
+timed on the host cores on a bounded sample of the same workload).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def cpu_baseline(w, sample_rows: int):
+    """The oracle as it stands (dense U by pushing the signed identity through the stages,
+    then X @ U and X @ U^T), float64 numpy, on `sample_rows` rows of the workload."""
+    import numpy as np
+    from oracle import harp_oracle as ho
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    X = w["X"][:sample_rows].astype(np.float64)
+    t0 = time.perf_counter()
+    U = ho.build_U(w["d"], w["radices"], w["blocks"], w["signs"])
+    t1 = time.perf_counter()
+    Y = X @ U
+    Z = X @ U.T
+    t2 = time.perf_counter()
+    assert Y.shape == Z.shape
+    total = (t1 - t0) + (t2 - t1)
+    return {
+        "value": 2 * sample_rows / total, "unit": "rows/s", "cores": int(cores), "kind": "oracle",
+        "sample": f"{sample_rows} of {w['n']} rows, apply + transpose; build dense U once "
+                  f"({t1 - t0:.2f} s) + two float64 matmuls ({t2 - t1:.2f} s)",
+        "seconds": total,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--workload", default="llama7b_4096_r2")
+    ap.add_argument("--rows", type=int, default=None, help="override n (default: the workload's)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--extra", action="store_true", help="also time the other shapes (stderr)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (rows shard across GPUs with no "
+              "communication; no multi-GPU figure is produced). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2605_29843_amd import harp, inputs as gi   # raises if libharp.so is missing
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    w = gi.workload(args.workload, n=args.rows)
+    n, d, radices = w["n"], w["d"], w["radices"]
+    bf16 = w["dtype"] == "bf16"
+    esz = 2 if bf16 else 4
+    plan = harp.Plan(d, radices, w["blocks"], w["signs"])
+
+    def dev(a):
+        if bf16:
+            return torch.from_numpy(gi.bf16_bits(a).view(np.int16).copy()).view(torch.bfloat16).cuda()
+        return torch.from_numpy(a).cuda()
+
+    # pool of batches: same distribution, rows permuted per batch; > 512 MB in total
+    batch_bytes = n * d * esz
+    nbuf = max(2, int(np.ceil(640e6 / (3 * batch_bytes))))
+    X0 = dev(w["X"])
+    pool = []
+    g = torch.Generator(device="cuda").manual_seed(0)
+    for i in range(nbuf):
+        Xi = X0 if i == 0 else X0[torch.randperm(n, device="cuda", generator=g)].contiguous()
+        pool.append((Xi, torch.empty_like(Xi), torch.empty_like(Xi)))
+
+    stream = torch.cuda.current_stream()
+
+    def step(i):
+        Xi, Yi, Zi = pool[i % nbuf]
+        harp.harp_apply(plan, Xi, Yi, stream)
+        harp.harp_apply_transpose(plan, Yi, Zi, stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    for i in range(args.steps):
+        step(args.warmup + i)
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ev_ms = ev0.elapsed_time(ev1)
+
+    # sanity of what was timed: round trip returns the input
+    Xi, Yi, Zi = pool[(args.warmup + args.steps - 1) % nbuf]
+    rt = float((Zi.float() - Xi.float()).abs().max() / Xi.float().abs().max())
+    assert rt < (3e-2 if bf16 else 1e-4), f"round trip error {rt}"
+
+    launches = 2 * args.steps
+    kernel_us = ev_ms * 1e3 / launches                       # average launch duration (HIP events)
+    param_bytes = plan.param_bytes()
+    alg_bytes = n * d * 2 * esz + param_bytes                # per launch: read X, write Y, params once
+    achieved = alg_bytes / (kernel_us * 1e-6) / 1e9
+    ms_per_step = wall * 1e3 / args.steps
+    rows_per_s = 2 * n * args.steps / wall
+
+    out = {
+        "metric": "HARP rotation rows/s (apply + apply_transpose), achieved HBM GB/s in roofline",
+        "value": rows_per_s, "unit": "rows/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "n": n, "d": d, "radices": radices,
+                   "io_dtype": w["dtype"], "kernel": plan.kernel_name(), "batches_in_pool": nbuf,
+                   "step": "harp_apply + harp_apply_transpose on one batch"},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "harp_tile_kernel", "avg_launch_us": kernel_us,
+                     "algorithmic_bytes_per_launch": alg_bytes, "param_bytes": param_bytes},
+    }
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(w, sample_rows=min(n, 2048))
+    if args.extra:
+        for name in ("llama7b_4096_r8", "down_11008_r2x8_43", "ffn_14336_r2x11_7", "ffn70b_28672_r2x12_7"):
+            try:
+                we = gi.workload(name)
+                pe = harp.Plan(we["d"], we["radices"], we["blocks"], we["signs"])
+                Xe = dev(we["X"])
+                Ye = torch.empty_like(Xe)
+                for _ in range(5):
+                    harp.harp_apply(pe, Xe, Ye, stream)
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                reps = 50
+                for _ in range(reps):
+                    harp.harp_apply(pe, Xe, Ye, stream)
+                e1.record(stream)
+                torch.cuda.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / reps
+                gb = (we["n"] * we["d"] * 4 + pe.param_bytes()) / (us * 1e-6) / 1e9
+                print(f"[extra] {name}: {us:.1f} us/apply, {gb:.0f} GB/s ({gb / HBM_PEAK_GBS:.1%}), "
+                      f"{we['n'] / (us * 1e-6):.3e} rows/s", file=sys.stderr, flush=True)
+                pe.destroy()
+            except Exception as e:  # noqa: BLE001
+                print(f"[extra] {name}: {e}", file=sys.stderr, flush=True)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

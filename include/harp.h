@@ -1,0 +1,161 @@
+/*
+ * libharp -- HARP structured orthogonal processors on AMD MI355X (gfx950).
+ *
+ * A HARP processor (paper Sec. 3, Eq. (6)-(8), Alg. 1) is a product of m sparse
+ * block-orthogonal stride stages under a Mixed-Radix schedule b = (b_0..b_{m-1}),
+ * prod b_t = d, together with a +-1 sign vector sigma (Sec. 3, "diagonal Rademacher
+ * sign flips"; Assumption 1(iv)).  With s_t = prod_{j<t} b_j and g_t = d / (b_t s_t),
+ * stage t takes, for every alpha < g_t and beta < s_t, the b_t coordinates
+ *
+ *        alpha * b_t * s_t + r * s_t + beta,      r = 0 .. b_t - 1     (App. A, Lemma 1)
+ *
+ * as a row vector v and replaces them by v * K_t[c], c = alpha * s_t + beta, where
+ * K_t[c] is a dense b_t x b_t block (Alg. 1, "view K_t as [g, s, b, b]").  Stage 0 is
+ * applied to the data first (Alg. 1 loop order).  The processor's matrix U is defined by
+ *
+ *        apply(x) = x U = T(x .* sigma),        T = stage_{m-1} o ... o stage_0,
+ *
+ * so U = diag(sigma) T, and apply_transpose(x) = x U^T = (x T^T) .* sigma (stages in
+ * reverse order, each block transposed).  With orthogonal blocks U is orthogonal and
+ * apply_transpose inverts apply; with arbitrary blocks both are still the linear maps
+ * just stated.  Conventions the paper leaves open and this library fixes: the row
+ * vector is on the left of the block, blocks are numbered alpha-major, and the signs
+ * act on the input coordinates of apply.
+ *
+ * All entry points return a status code; none throws, aborts or synchronises the
+ * device.  Argument errors are detected before any HIP call.  A plan is immutable
+ * after creation and may be used concurrently from several host threads and streams.
+ */
+#ifndef HARP_H_
+#define HARP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct harp_plan harp_plan_t; /* opaque */
+
+typedef enum {
+  HARP_OK = 0,
+  HARP_ERR_INVALID_ARG = 1,    /* NULL pointer, negative size, leading dim < d, bad enum    */
+  HARP_ERR_BAD_SCHEDULE = 2,   /* m < 1, some b_t < 2, or prod b_t != d   (Eq. (6))         */
+  HARP_ERR_NOT_ORTHOGONAL = 3, /* HARP_VALIDATE_ORTHO set and a block fails K^T K = I       */
+  HARP_ERR_UNSUPPORTED = 4,    /* radix > HARP_MAX_RADIX, or d too long for the on-chip tile */
+  HARP_ERR_OOM = 5,            /* host or device allocation failed                           */
+  HARP_ERR_DEVICE = 6          /* any other HIP runtime failure (including: no device)       */
+} harp_status_t;
+
+typedef enum {
+  HARP_F32 = 0, /* X, Y hold IEEE binary32                                                   */
+  HARP_BF16 = 1 /* X, Y hold bfloat16; arithmetic is fp32, one round-to-nearest-even at store */
+} harp_dtype_t;
+
+/* flags for harp_plan_create */
+enum {
+  HARP_VALIDATE_ORTHO = 1u,  /* reject blocks with max |K^T K - I| > 1e-5 (checked in float64) */
+  HARP_BLOCKS_ON_DEVICE = 2u /* blocks[t] and signs are device pointers (copied back to build) */
+};
+
+/* kernel selection, for tests and tuning (harp_plan_set_algo) */
+typedef enum {
+  HARP_ALGO_AUTO = 0,    /* fastest kernel that supports the plan                             */
+  HARP_ALGO_GENERIC = 1, /* every stage through the runtime-radix code path                   */
+  HARP_ALGO_FUSED = 2    /* radix-specialised passes; UNSUPPORTED if a stage has no such path */
+} harp_algo_t;
+
+#define HARP_MAX_RADIX 64
+#define HARP_MAX_STAGES 64
+
+/*
+ * Create a processor (Eq. (6)-(8); Alg. 1 REQUIRE lines).
+ *   out      receives the plan; untouched on failure.
+ *   d        transformed dimension, >= 2.
+ *   m        number of stages, 1 .. HARP_MAX_STAGES.
+ *   radices  m host ints, each >= 2 (<= HARP_MAX_RADIX), product == d.
+ *   blocks   m host pointers (device pointers with HARP_BLOCKS_ON_DEVICE); blocks[t]
+ *            holds D_t = d / b_t blocks of b_t * b_t float32, block c row-major:
+ *            blocks[t][c*b*b + r*b + r2] = K_t[c][r][r2], used as  v'[r2] = sum_r v[r] K[r][r2].
+ *   signs    d int8 values in {+1, -1}, or NULL for all +1.
+ *   flags    OR of HARP_VALIDATE_ORTHO, HARP_BLOCKS_ON_DEVICE.
+ * The plan copies everything it needs into device memory it owns (on the current HIP
+ * device); the caller's arrays may be freed on return.
+ */
+harp_status_t harp_plan_create(harp_plan_t **out, int64_t d, int32_t m, const int32_t *radices,
+                               const float *const *blocks, const int8_t *signs, uint32_t flags);
+
+/* Release the plan and its device memory.  NULL is accepted.  The caller must ensure
+ * no launch using the plan is still in flight. */
+harp_status_t harp_plan_destroy(harp_plan_t *plan);
+
+/*
+ * Y[n,d] = X[n,d] * U  (Alg. 1 on every row, signs first).
+ *   X, Y     caller-owned DEVICE pointers, row-major, leading dimensions ldx, ldy in
+ *            elements (>= d).  Y may be exactly X with ldy == ldx (in place); any other
+ *            overlap is undefined.
+ *   n        number of rows, >= 0 (0 is a no-op returning HARP_OK).
+ *   dt       element type of both X and Y.
+ *   stream   a hipStream_t passed as void* (NULL = the default stream).  The call only
+ *            enqueues work on it.
+ */
+harp_status_t harp_apply(const harp_plan_t *plan, const void *X, int64_t ldx, void *Y,
+                         int64_t ldy, int64_t n, harp_dtype_t dt, void *stream);
+
+/* Y[n,d] = X[n,d] * U^T  (the stages in reverse order with transposed blocks, signs last;
+ * the inverse of harp_apply when the blocks are orthogonal).  Same argument rules. */
+harp_status_t harp_apply_transpose(const harp_plan_t *plan, const void *X, int64_t ldx, void *Y,
+                                   int64_t ldy, int64_t n, harp_dtype_t dt, void *stream);
+
+/*
+ * Two-sided change of basis of a weight matrix (Sec. 2):  Wout = U_U^T * W * U_V,
+ * W and Wout [d_out, d_in] row-major DEVICE arrays with leading dimensions ldw, ldo.
+ * plan_U (dimension d_out) and plan_V (dimension d_in) may each be NULL = identity on
+ * that side; if both are NULL, d_out and d_in say how much to copy.  With plan_U given,
+ * d_out must equal its dimension, likewise d_in for plan_V.  Wout may be exactly W.
+ * workspace: device scratch of at least the size reported by
+ * harp_rotate_weight_workspace_size (may be NULL when that size is 0).
+ * The inverse map  W = U_U * Wout * U_V^T  is harp_rotate_weight_inverse.
+ */
+harp_status_t harp_rotate_weight_workspace_size(const harp_plan_t *plan_U,
+                                                const harp_plan_t *plan_V, int64_t d_out,
+                                                int64_t d_in, harp_dtype_t dt, size_t *bytes);
+harp_status_t harp_rotate_weight(const harp_plan_t *plan_U, const harp_plan_t *plan_V,
+                                 const void *W, int64_t ldw, void *Wout, int64_t ldo,
+                                 int64_t d_out, int64_t d_in, harp_dtype_t dt, void *workspace,
+                                 size_t workspace_bytes, void *stream);
+harp_status_t harp_rotate_weight_inverse(const harp_plan_t *plan_U, const harp_plan_t *plan_V,
+                                         const void *W, int64_t ldw, void *Wout, int64_t ldo,
+                                         int64_t d_out, int64_t d_in, harp_dtype_t dt,
+                                         void *workspace, size_t workspace_bytes, void *stream);
+
+/* Greedy Mixed-Radix schedule (appendix Alg. 2): peel b_base while it divides d, then the
+ * factors min(b_max, r) .. 2 in decreasing order, then any leftover as one last stage.
+ * out_radices must hold HARP_MAX_STAGES ints.  Host only; no HIP call. */
+harp_status_t harp_greedy_schedule(int64_t d, int32_t b_base, int32_t b_max, int32_t *out_radices,
+                                   int32_t *out_m);
+
+/* Introspection and tuning. */
+int64_t harp_plan_dim(const harp_plan_t *plan);          /* d, or -1 for NULL            */
+int32_t harp_plan_num_stages(const harp_plan_t *plan);   /* m, or -1 for NULL            */
+/* Eq. (13): number of free rotation parameters sum_t d (b_t - 1) / 2; -1 for NULL. */
+int64_t harp_plan_param_count(const harp_plan_t *plan);
+/* Bytes of stage parameters one launch reads from device memory (per row tile). */
+int64_t harp_plan_param_bytes(const harp_plan_t *plan);
+/* Choose the kernel family for later launches of this plan (not thread-safe against
+ * concurrent launches).  HARP_ERR_UNSUPPORTED leaves the previous choice in place. */
+harp_status_t harp_plan_set_algo(harp_plan_t *plan, harp_algo_t algo);
+/* Rows per workgroup tile for later launches; 0 restores the automatic choice.
+ * INVALID_ARG if the tile would not fit in the 160 KB LDS. */
+harp_status_t harp_plan_set_rows_per_tile(harp_plan_t *plan, int32_t rows);
+/* Short name of the kernel path harp_apply would take for n rows (static string). */
+const char *harp_plan_kernel_name(const harp_plan_t *plan, int64_t n, harp_dtype_t dt);
+
+const char *harp_status_string(harp_status_t status);
+const char *harp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HARP_H_ */

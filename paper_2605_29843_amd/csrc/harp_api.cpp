@@ -1,0 +1,541 @@
+// C ABI of libharp: plan construction (validation, pass grouping, parameter packing),
+// dispatch of apply / apply_transpose / rotate_weight, helpers.  Host code only; the
+// kernels and their launchers are in harp_kernels.hip.
+#include <algorithm>
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "harp_internal.h"
+
+using namespace harp;
+
+namespace {
+
+struct StageView {        // host copy of one stage's blocks, effective for a direction
+  const float *K;         // [D][b][b] as given by the caller
+  int32_t b;
+  int64_t s;
+  bool transposed;
+  inline float at(int64_t c, int r, int r2) const {
+    return transposed ? K[(c * b + r2) * b + r] : K[(c * b + r) * b + r2];
+  }
+};
+
+bool stage_all_rotations(const float *K, int64_t D) {
+  for (int64_t c = 0; c < D; ++c) {
+    const float *k = K + c * 4;
+    if (!(k[3] == k[0] && k[1] == -k[2])) return false;
+  }
+  return true;
+}
+
+// Split a run of `len` stages into ceil(len / kmax) nearly equal parts.
+void split_run(int len, int kmax, std::vector<int> &out) {
+  int parts = (len + kmax - 1) / kmax;
+  int base = len / parts, extra = len % parts;
+  for (int i = 0; i < parts; ++i) out.push_back(base + (i < extra ? 1 : 0));
+}
+
+int ilog2(int64_t v) {
+  int l = 0;
+  while ((int64_t(1) << l) < v) ++l;
+  return l;
+}
+
+// Build the pass list and the packed parameter image for one (algo, direction).
+// Layout of the image: per pass, V rows of nq floats (value v of sub-tensor q at v*nq + q),
+// so that consecutive threads (consecutive q) read consecutive addresses.
+bool build_program(const harp_plan *plan, const std::vector<const float *> &blocks, int algo,
+                   Direction dir, HostProgram &hp, std::vector<float> &image,
+                   std::vector<size_t> &offsets) {
+  const int m = plan->m;
+  const int64_t d = plan->d;
+  std::vector<int> order(m);
+  for (int i = 0; i < m; ++i) order[i] = (dir == DIR_FWD) ? i : m - 1 - i;
+
+  Program &pg = hp.prog;
+  pg.npass = 0;
+  pg.sign_at_load = (dir == DIR_FWD) ? 1 : 0;
+  pg.signs = nullptr;
+  image.clear();
+  offsets.clear();
+
+  auto stage = [&](int t) {
+    return StageView{blocks[t], plan->radices[t], plan->strides[t], dir == DIR_TRN};
+  };
+
+  int i = 0;
+  while (i < m) {
+    const int t = order[i];
+    const int b = plan->radices[t];
+    if (algo == HARP_ALGO_FUSED && b == 2) {
+      // maximal run of radix-2 stages that are adjacent digits, all rotations or all dense
+      const bool rot = stage_all_rotations(blocks[t], d / 2);
+      int len = 1;
+      while (i + len < m && plan->radices[order[i + len]] == 2 &&
+             stage_all_rotations(blocks[order[i + len]], d / 2) == rot)
+        ++len;
+      std::vector<int> parts;
+      split_run(len, rot ? 4 : 3, parts);
+      for (int k : parts) {
+        if (pg.npass >= kMaxPasses) return false;
+        PassDesc &pd = pg.pass[pg.npass++];
+        const int P = 1 << k;
+        int64_t S = plan->strides[order[i]];
+        for (int e = 0; e < k; ++e) S = std::min<int64_t>(S, plan->strides[order[i + e]]);
+        const int64_t nq = d / P;
+        const int per = rot ? 2 : 4;
+        pd.kind = rot ? PASS_POW2_ROT : PASS_POW2_DENSE;
+        pd.b = 2;
+        pd.k = k;
+        pd.desc = (dir == DIR_TRN) ? 1 : 0;
+        pd.P = P;
+        pd.S = (int32_t)S;
+        pd.nq = (int32_t)nq;
+        pd.V = k * (P / 2) * per;
+        offsets.push_back(image.size());
+        image.resize(image.size() + (size_t)pd.V * nq);
+        float *img = image.data() + offsets.back();
+        for (int e = 0; e < k; ++e) {
+          const StageView sv = stage(order[i + e]);
+          const int bp = ilog2(sv.s / S);
+          // the kernel assumes digit position e (ascending) or k-1-e (descending)
+          if (bp != (pd.desc ? k - 1 - e : e)) return false;
+          for (int64_t q = 0; q < nq; ++q) {
+            const int64_t hi = q / S, lo = q % S;
+            const int64_t base = hi * P * S + lo;
+            for (int p = 0; p < P / 2; ++p) {
+              const int j0 = ((p >> bp) << (bp + 1)) | (p & ((1 << bp) - 1));
+              const int64_t idx0 = base + (int64_t)j0 * S;
+              const int64_t beta = idx0 % sv.s, alpha = idx0 / (2 * sv.s);
+              const int64_t c = alpha * sv.s + beta;
+              const size_t v0 = (size_t)(e * (P / 2) + p) * per;
+              if (rot) {
+                img[(v0 + 0) * nq + q] = sv.at(c, 0, 0);
+                img[(v0 + 1) * nq + q] = sv.at(c, 1, 0);
+              } else {
+                img[(v0 + 0) * nq + q] = sv.at(c, 0, 0);
+                img[(v0 + 1) * nq + q] = sv.at(c, 0, 1);
+                img[(v0 + 2) * nq + q] = sv.at(c, 1, 0);
+                img[(v0 + 3) * nq + q] = sv.at(c, 1, 1);
+              }
+            }
+          }
+        }
+        i += k;
+      }
+      continue;
+    }
+    if (pg.npass >= kMaxPasses) return false;
+    if (b > HARP_MAX_RADIX) return false;
+    PassDesc &pd = pg.pass[pg.npass++];
+    const bool small = (algo == HARP_ALGO_FUSED && b >= 3 && b <= 8);
+    if (algo == HARP_ALGO_FUSED && !small && b != 2) {
+      // radices above 8 use the run-time radix path inside the fused family as well
+    }
+    const StageView sv = stage(t);
+    const int64_t nq = d / b;
+    pd.kind = small ? PASS_SMALL : PASS_GENERIC;
+    pd.b = b;
+    pd.k = 1;
+    pd.desc = 0;
+    pd.P = b;
+    pd.S = (int32_t)sv.s;
+    pd.nq = (int32_t)nq;
+    pd.V = b * b;
+    offsets.push_back(image.size());
+    image.resize(image.size() + (size_t)pd.V * nq);
+    float *img = image.data() + offsets.back();
+    // sub-tensor q = hi*S + lo is exactly block c = alpha*s + beta with alpha = hi, beta = lo
+    for (int64_t q = 0; q < nq; ++q)
+      for (int r = 0; r < b; ++r)
+        for (int r2 = 0; r2 < b; ++r2) img[(size_t)(r * b + r2) * nq + q] = sv.at(q, r, r2);
+    ++i;
+  }
+  hp.param_bytes = (int64_t)image.size() * 4;
+  hp.ok = true;
+  return true;
+}
+
+harp_status_t check_apply_args(const harp_plan_t *plan, const void *X, int64_t ldx, const void *Y,
+                               int64_t ldy, int64_t n, harp_dtype_t dt) {
+  if (!plan) return HARP_ERR_INVALID_ARG;
+  if (n < 0) return HARP_ERR_INVALID_ARG;
+  if (dt != HARP_F32 && dt != HARP_BF16) return HARP_ERR_INVALID_ARG;
+  if (n == 0) return HARP_OK;
+  if (!X || !Y) return HARP_ERR_INVALID_ARG;
+  if (ldx < plan->d || ldy < plan->d) return HARP_ERR_INVALID_ARG;
+  return HARP_OK;
+}
+
+harp_status_t apply_dir(const harp_plan_t *plan, Direction dir, const void *X, int64_t ldx,
+                        harp_dtype_t dt_in, void *Y, int64_t ldy, harp_dtype_t dt_out, int64_t n,
+                        void *stream) {
+  const HostProgram *hp = select_program(plan, dir, nullptr);
+  if (!hp) return HARP_ERR_UNSUPPORTED;
+  return launch_tile_kernel(plan, hp->dev, X, ldx, dt_in, Y, ldy, dt_out, n, (hipStream_t)stream);
+}
+
+size_t esize(harp_dtype_t dt) { return dt == HARP_BF16 ? 2 : 4; }
+
+harp_status_t rotate_impl(const harp_plan_t *pu, const harp_plan_t *pv, Direction dir,
+                          const void *W, int64_t ldw, void *Wout, int64_t ldo, int64_t d_out,
+                          int64_t d_in, harp_dtype_t dt, void *ws, size_t ws_bytes, void *stream) {
+  if (dt != HARP_F32 && dt != HARP_BF16) return HARP_ERR_INVALID_ARG;
+  if (d_out < 0 || d_in < 0) return HARP_ERR_INVALID_ARG;
+  if (pu && pu->d != d_out) return HARP_ERR_INVALID_ARG;
+  if (pv && pv->d != d_in) return HARP_ERR_INVALID_ARG;
+  if (d_out == 0 || d_in == 0) return HARP_OK;
+  if (!W || !Wout || ldw < d_in || ldo < d_in) return HARP_ERR_INVALID_ARG;
+  size_t need = 0;
+  harp_status_t st = harp_rotate_weight_workspace_size(pu, pv, d_out, d_in, dt, &need);
+  if (st != HARP_OK) return st;
+  if (need > 0 && (!ws || ws_bytes < need)) return HARP_ERR_INVALID_ARG;
+  hipStream_t s = (hipStream_t)stream;
+
+  if (!pu) {
+    if (!pv) {
+      if (W == Wout && ldw == ldo) return HARP_OK;
+      return launch_copy2d(W, ldw, Wout, ldo, d_out, d_in, dt, s);
+    }
+    // rows of W through plan_V only
+    return apply_dir(pv, dir, W, ldw, dt, Wout, ldo, dt, d_out, stream);
+  }
+  // Column side: (U^T M)^T = M^T U, i.e. the rows of M^T go through plan_U (same direction
+  // flag: the inverse map uses U M = (M^T U^T)^T).  Intermediates stay in float32 so that a
+  // bf16 matrix is rounded once, at the final store.
+  const size_t mat = (size_t)d_out * d_in * 4;
+  float *A = (float *)ws;                                   // [d_out, d_in] (only with plan_V)
+  float *B = pv ? (float *)((char *)ws + mat) : (float *)ws;  // [d_in, d_out]
+  if (pv) {
+    st = apply_dir(pv, dir, W, ldw, dt, A, d_in, HARP_F32, d_out, stream);
+    if (st != HARP_OK) return st;
+    st = launch_transpose(A, d_in, HARP_F32, B, d_out, HARP_F32, d_out, d_in, s);
+  } else {
+    st = launch_transpose(W, ldw, dt, B, d_out, HARP_F32, d_out, d_in, s);
+  }
+  if (st != HARP_OK) return st;
+  st = apply_dir(pu, dir, B, d_out, HARP_F32, B, d_out, HARP_F32, d_in, stream);
+  if (st != HARP_OK) return st;
+  return launch_transpose(B, d_out, HARP_F32, Wout, ldo, dt, d_in, d_out, s);
+}
+
+}  // namespace
+
+namespace harp {
+
+const HostProgram *select_program(const harp_plan *plan, Direction dir, const char **name) {
+  int algo = plan->algo;
+  if (algo == HARP_ALGO_AUTO) algo = plan->prog[HARP_ALGO_FUSED][dir].ok ? HARP_ALGO_FUSED : HARP_ALGO_GENERIC;
+  const HostProgram &hp = plan->prog[algo][dir];
+  if (!hp.ok) return nullptr;
+  if (name) *name = (algo == HARP_ALGO_FUSED) ? "tile_fused" : "tile_generic";
+  return &hp;
+}
+
+}  // namespace harp
+
+extern "C" {
+
+harp_status_t harp_plan_create(harp_plan_t **out, int64_t d, int32_t m, const int32_t *radices,
+                               const float *const *blocks, const int8_t *signs, uint32_t flags) {
+  if (!out || !radices || !blocks) return HARP_ERR_INVALID_ARG;
+  if (flags & ~(uint32_t)(HARP_VALIDATE_ORTHO | HARP_BLOCKS_ON_DEVICE)) return HARP_ERR_INVALID_ARG;
+  if (d < 2) return HARP_ERR_INVALID_ARG;
+  if (m < 1 || m > HARP_MAX_STAGES) return HARP_ERR_BAD_SCHEDULE;
+  int64_t prod = 1;
+  for (int t = 0; t < m; ++t) {
+    if (radices[t] < 2) return HARP_ERR_BAD_SCHEDULE;
+    if (prod > d) return HARP_ERR_BAD_SCHEDULE;
+    prod *= radices[t];
+  }
+  if (prod != d) return HARP_ERR_BAD_SCHEDULE;
+  for (int t = 0; t < m; ++t)
+    if (!blocks[t]) return HARP_ERR_INVALID_ARG;
+  for (int t = 0; t < m; ++t)
+    if (radices[t] > HARP_MAX_RADIX) return HARP_ERR_UNSUPPORTED;
+  if (d > (int64_t)1 << 24) return HARP_ERR_UNSUPPORTED;
+
+  harp_plan *plan = new (std::nothrow) harp_plan();
+  if (!plan) return HARP_ERR_OOM;
+  harp_status_t st = HARP_OK;
+  std::vector<std::vector<float>> host_copy;
+  std::vector<int8_t> host_signs;
+  std::vector<const float *> blk(m);
+  try {
+    plan->d = d;
+    plan->m = m;
+    plan->radices.assign(radices, radices + m);
+    plan->strides.resize(m);
+    int64_t s = 1;
+    for (int t = 0; t < m; ++t) {
+      plan->strides[t] = s;
+      s *= radices[t];
+    }
+    if (flags & HARP_BLOCKS_ON_DEVICE) {
+      host_copy.resize(m);
+      for (int t = 0; t < m && st == HARP_OK; ++t) {
+        host_copy[t].resize((size_t)d * radices[t]);
+        if (hipMemcpy(host_copy[t].data(), blocks[t], (size_t)d * radices[t] * 4,
+                      hipMemcpyDeviceToHost) != hipSuccess)
+          st = HARP_ERR_DEVICE;
+        blk[t] = host_copy[t].data();
+      }
+      if (st == HARP_OK && signs) {
+        host_signs.resize(d);
+        if (hipMemcpy(host_signs.data(), signs, (size_t)d, hipMemcpyDeviceToHost) != hipSuccess)
+          st = HARP_ERR_DEVICE;
+        signs = host_signs.data();
+      }
+    } else {
+      for (int t = 0; t < m; ++t) blk[t] = blocks[t];
+    }
+    if (st == HARP_OK && signs)
+      for (int64_t i = 0; i < d; ++i)
+        if (signs[i] != 1 && signs[i] != -1) {
+          st = HARP_ERR_INVALID_ARG;
+          break;
+        }
+    // every block entry must be finite; optionally orthogonal
+    for (int t = 0; t < m && st == HARP_OK; ++t) {
+      const int b = radices[t];
+      const int64_t D = d / b;
+      const float *K = blk[t];
+      for (int64_t i = 0; i < D * b * b; ++i)
+        if (!std::isfinite(K[i])) {
+          st = HARP_ERR_INVALID_ARG;
+          break;
+        }
+      if (st == HARP_OK && (flags & HARP_VALIDATE_ORTHO)) {
+        for (int64_t c = 0; c < D && st == HARP_OK; ++c) {
+          const float *k = K + c * b * b;
+          for (int i = 0; i < b && st == HARP_OK; ++i)
+            for (int j = i; j < b; ++j) {
+              double acc = 0.0;
+              for (int r = 0; r < b; ++r) acc += (double)k[r * b + i] * (double)k[r * b + j];
+              if (std::fabs(acc - (i == j ? 1.0 : 0.0)) > 1e-5) {
+                st = HARP_ERR_NOT_ORTHOGONAL;
+                break;
+              }
+            }
+        }
+      }
+    }
+    // ---- device side -------------------------------------------------------------
+    if (st == HARP_OK) {
+      int dev = 0;
+      hipDeviceProp_t prop;
+      if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+        st = HARP_ERR_DEVICE;
+      } else {
+        plan->device = dev;
+        plan->num_cu = prop.multiProcessorCount;
+        int lds = 0;
+        if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) !=
+            hipSuccess)
+          lds = (int)prop.sharedMemPerBlock;
+        plan->lds_bytes = lds;
+        if ((int64_t)d * 4 > lds) st = HARP_ERR_UNSUPPORTED;  // one row must fit in LDS
+      }
+    }
+    if (st == HARP_OK && signs) {
+      std::vector<float> sf(d);
+      bool any = false;
+      for (int64_t i = 0; i < d; ++i) {
+        sf[i] = (float)signs[i];
+        any |= signs[i] < 0;
+      }
+      if (any) {
+        if (hipMalloc((void **)&plan->dev_signs, (size_t)d * 4) != hipSuccess)
+          st = HARP_ERR_OOM;
+        else {
+          plan->dev_allocs.push_back(plan->dev_signs);
+          if (hipMemcpy(plan->dev_signs, sf.data(), (size_t)d * 4, hipMemcpyHostToDevice) !=
+              hipSuccess)
+            st = HARP_ERR_DEVICE;
+        }
+      }
+    }
+    for (int algo = HARP_ALGO_GENERIC; algo <= HARP_ALGO_FUSED && st == HARP_OK; ++algo)
+      for (int dir = 0; dir < 2 && st == HARP_OK; ++dir) {
+        HostProgram &hp = plan->prog[algo][dir];
+        std::vector<float> image;
+        std::vector<size_t> offsets;
+        if (!build_program(plan, blk, algo, (Direction)dir, hp, image, offsets)) {
+          hp.ok = false;
+          continue;
+        }
+        float *dimg = nullptr;
+        if (hipMalloc((void **)&dimg, image.size() * 4) != hipSuccess) {
+          st = HARP_ERR_OOM;
+          break;
+        }
+        plan->dev_allocs.push_back(dimg);
+        if (hipMemcpy(dimg, image.data(), image.size() * 4, hipMemcpyHostToDevice) != hipSuccess) {
+          st = HARP_ERR_DEVICE;
+          break;
+        }
+        for (int p = 0; p < hp.prog.npass; ++p) hp.prog.pass[p].params = dimg + offsets[p];
+        hp.prog.signs = plan->dev_signs;
+        Program *dprog = nullptr;
+        if (hipMalloc((void **)&dprog, sizeof(Program)) != hipSuccess) {
+          st = HARP_ERR_OOM;
+          break;
+        }
+        plan->dev_allocs.push_back(dprog);
+        if (hipMemcpy(dprog, &hp.prog, sizeof(Program), hipMemcpyHostToDevice) != hipSuccess) {
+          st = HARP_ERR_DEVICE;
+          break;
+        }
+        hp.dev = dprog;
+      }
+    if (st == HARP_OK && !plan->prog[HARP_ALGO_GENERIC][0].ok) st = HARP_ERR_UNSUPPORTED;
+  } catch (const std::bad_alloc &) {
+    st = HARP_ERR_OOM;
+  }
+  if (st != HARP_OK) {
+    harp_plan_destroy(plan);
+    return st;
+  }
+  *out = plan;
+  return HARP_OK;
+}
+
+harp_status_t harp_plan_destroy(harp_plan_t *plan) {
+  if (!plan) return HARP_OK;
+  harp_status_t st = HARP_OK;
+  for (void *p : plan->dev_allocs)
+    if (p && hipFree(p) != hipSuccess) st = HARP_ERR_DEVICE;
+  delete plan;
+  return st;
+}
+
+harp_status_t harp_apply(const harp_plan_t *plan, const void *X, int64_t ldx, void *Y, int64_t ldy,
+                         int64_t n, harp_dtype_t dt, void *stream) {
+  harp_status_t st = check_apply_args(plan, X, ldx, Y, ldy, n, dt);
+  if (st != HARP_OK || n == 0) return st;
+  return apply_dir(plan, DIR_FWD, X, ldx, dt, Y, ldy, dt, n, stream);
+}
+
+harp_status_t harp_apply_transpose(const harp_plan_t *plan, const void *X, int64_t ldx, void *Y,
+                                   int64_t ldy, int64_t n, harp_dtype_t dt, void *stream) {
+  harp_status_t st = check_apply_args(plan, X, ldx, Y, ldy, n, dt);
+  if (st != HARP_OK || n == 0) return st;
+  return apply_dir(plan, DIR_TRN, X, ldx, dt, Y, ldy, dt, n, stream);
+}
+
+harp_status_t harp_rotate_weight_workspace_size(const harp_plan_t *plan_U,
+                                                const harp_plan_t *plan_V, int64_t d_out,
+                                                int64_t d_in, harp_dtype_t dt, size_t *bytes) {
+  if (!bytes) return HARP_ERR_INVALID_ARG;
+  if (dt != HARP_F32 && dt != HARP_BF16) return HARP_ERR_INVALID_ARG;
+  if (d_out < 0 || d_in < 0) return HARP_ERR_INVALID_ARG;
+  if (plan_U && plan_U->d != d_out) return HARP_ERR_INVALID_ARG;
+  if (plan_V && plan_V->d != d_in) return HARP_ERR_INVALID_ARG;
+  const size_t mat = (size_t)d_out * (size_t)d_in * 4;
+  *bytes = !plan_U ? 0 : (plan_V ? 2 * mat : mat);
+  return HARP_OK;
+}
+
+harp_status_t harp_rotate_weight(const harp_plan_t *plan_U, const harp_plan_t *plan_V,
+                                 const void *W, int64_t ldw, void *Wout, int64_t ldo,
+                                 int64_t d_out, int64_t d_in, harp_dtype_t dt, void *workspace,
+                                 size_t workspace_bytes, void *stream) {
+  return rotate_impl(plan_U, plan_V, DIR_FWD, W, ldw, Wout, ldo, d_out, d_in, dt, workspace,
+                     workspace_bytes, stream);
+}
+
+harp_status_t harp_rotate_weight_inverse(const harp_plan_t *plan_U, const harp_plan_t *plan_V,
+                                         const void *W, int64_t ldw, void *Wout, int64_t ldo,
+                                         int64_t d_out, int64_t d_in, harp_dtype_t dt,
+                                         void *workspace, size_t workspace_bytes, void *stream) {
+  return rotate_impl(plan_U, plan_V, DIR_TRN, W, ldw, Wout, ldo, d_out, d_in, dt, workspace,
+                     workspace_bytes, stream);
+}
+
+harp_status_t harp_greedy_schedule(int64_t d, int32_t b_base, int32_t b_max, int32_t *out_radices,
+                                   int32_t *out_m) {
+  if (!out_radices || !out_m) return HARP_ERR_INVALID_ARG;
+  if (d < 2 || b_base < 2 || b_max < 2) return HARP_ERR_INVALID_ARG;
+  int32_t m = 0;
+  int64_t r = d;
+  auto push = [&](int64_t f) -> bool {
+    if (m >= HARP_MAX_STAGES || f > INT32_MAX) return false;
+    out_radices[m++] = (int32_t)f;
+    return true;
+  };
+  while (r % b_base == 0) {
+    if (!push(b_base)) return HARP_ERR_UNSUPPORTED;
+    r /= b_base;
+  }
+  for (int64_t f = std::min<int64_t>(b_max, r); f >= 2; --f)
+    while (r % f == 0) {
+      if (!push(f)) return HARP_ERR_UNSUPPORTED;
+      r /= f;
+    }
+  if (r != 1 && !push(r)) return HARP_ERR_UNSUPPORTED;
+  *out_m = m;
+  return HARP_OK;
+}
+
+int64_t harp_plan_dim(const harp_plan_t *plan) { return plan ? plan->d : -1; }
+int32_t harp_plan_num_stages(const harp_plan_t *plan) { return plan ? plan->m : -1; }
+
+int64_t harp_plan_param_count(const harp_plan_t *plan) {
+  if (!plan) return -1;
+  int64_t tot = 0;
+  for (int32_t b : plan->radices) tot += (plan->d / b) * ((int64_t)b * (b - 1) / 2);
+  return tot;
+}
+
+int64_t harp_plan_param_bytes(const harp_plan_t *plan) {
+  if (!plan) return -1;
+  const HostProgram *hp = select_program(plan, DIR_FWD, nullptr);
+  return hp ? hp->param_bytes : -1;
+}
+
+harp_status_t harp_plan_set_algo(harp_plan_t *plan, harp_algo_t algo) {
+  if (!plan) return HARP_ERR_INVALID_ARG;
+  if (algo != HARP_ALGO_AUTO && algo != HARP_ALGO_GENERIC && algo != HARP_ALGO_FUSED)
+    return HARP_ERR_INVALID_ARG;
+  if (algo != HARP_ALGO_AUTO && !(plan->prog[algo][0].ok && plan->prog[algo][1].ok))
+    return HARP_ERR_UNSUPPORTED;
+  plan->algo = algo;
+  return HARP_OK;
+}
+
+harp_status_t harp_plan_set_rows_per_tile(harp_plan_t *plan, int32_t rows) {
+  if (!plan || rows < 0) return HARP_ERR_INVALID_ARG;
+  if (rows > 0 && (int64_t)rows * plan->d * 4 > plan->lds_bytes) return HARP_ERR_INVALID_ARG;
+  plan->rows_override = rows;
+  return HARP_OK;
+}
+
+const char *harp_plan_kernel_name(const harp_plan_t *plan, int64_t n, harp_dtype_t dt) {
+  (void)n;
+  (void)dt;
+  if (!plan) return "none";
+  const char *nm = "none";
+  select_program(plan, DIR_FWD, &nm);
+  return nm;
+}
+
+const char *harp_status_string(harp_status_t status) {
+  switch (status) {
+    case HARP_OK: return "ok";
+    case HARP_ERR_INVALID_ARG: return "invalid argument";
+    case HARP_ERR_BAD_SCHEDULE: return "bad schedule (radix < 2, no stages, or product != d)";
+    case HARP_ERR_NOT_ORTHOGONAL: return "block is not orthogonal";
+    case HARP_ERR_UNSUPPORTED: return "unsupported shape or radix";
+    case HARP_ERR_OOM: return "out of memory";
+    case HARP_ERR_DEVICE: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+const char *harp_version(void) { return "libharp 0.1 (gfx950)"; }
+
+}  // extern "C"

@@ -1,0 +1,93 @@
+// Internal structures shared by the host-side plan builder and the HIP launchers.
+// Not part of the public interface.
+#ifndef HARP_INTERNAL_H_
+#define HARP_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "harp.h"
+
+namespace harp {
+
+// A *pass* is a run of consecutive stages that one thread executes on a register-resident
+// sub-tensor of the row: the P = prod(radices of the run) coordinates
+//     base + j * S,  j = 0..P-1,   base = hi * P * S + lo,   q = hi * S + lo  (q < d / P)
+// where S is the stride of the run's lowest digit.  Between passes the row tile lives in LDS.
+enum PassKind : int32_t {
+  PASS_POW2_DENSE = 0,    // k radix-2 stages, 4 values per 2x2 block
+  PASS_POW2_ROT = 1,      // k radix-2 stages, every block a rotation [[c,-s],[s,c]]: 2 values
+  PASS_SMALL = 2,         // one stage of radix 3..8, compile-time radix, block in registers
+  PASS_GENERIC = 3        // one stage of any radix <= HARP_MAX_RADIX, run-time radix
+};
+
+struct PassDesc {
+  int32_t kind;
+  int32_t b;     // radix of the stage (SMALL / GENERIC); 2 for POW2
+  int32_t k;     // number of stages in the pass (POW2), else 1
+  int32_t desc;  // POW2: 1 = digits executed from the highest to the lowest (transpose program)
+  int32_t P;     // coordinates per sub-tensor
+  int32_t S;     // stride of the lowest digit of the pass
+  int32_t nq;    // d / P sub-tensors per row
+  int32_t V;     // parameter values per sub-tensor
+  const float *params;  // device, [V][nq]: value v of sub-tensor q at params[v * nq + q]
+};
+
+constexpr int kMaxPasses = HARP_MAX_STAGES;
+
+struct Program {
+  int32_t npass;
+  int32_t sign_at_load;   // 1: multiply by signs while loading (apply); 0: while storing
+  const float *signs;     // device [d] of +-1.0f, or nullptr
+  PassDesc pass[kMaxPasses];
+};
+
+struct HostProgram {
+  Program prog{};
+  const Program *dev = nullptr;  // device copy of prog (what the kernels read)
+  int64_t param_bytes = 0;
+  bool ok = false;  // false: some stage has no code path in this family
+};
+
+enum Direction { DIR_FWD = 0, DIR_TRN = 1 };
+
+struct LaunchCfg {
+  int rows_per_tile;
+  int threads;
+};
+
+}  // namespace harp
+
+struct harp_plan {
+  int64_t d = 0;
+  int32_t m = 0;
+  std::vector<int32_t> radices;
+  std::vector<int64_t> strides;
+  harp::HostProgram prog[3][2];   // [algo (1 = generic, 2 = fused)][direction]
+  std::vector<void *> dev_allocs;
+  float *dev_signs = nullptr;
+  int algo = HARP_ALGO_AUTO;
+  int rows_override = 0;
+  int device = 0;
+  int lds_bytes = 0;   // usable LDS per workgroup
+  int num_cu = 0;
+};
+
+namespace harp {
+
+// launchers (harp_kernels.hip)
+harp_status_t launch_tile_kernel(const harp_plan *plan, const Program *dev_prog, const void *X,
+                                 int64_t ldx, harp_dtype_t dt_in, void *Y, int64_t ldy,
+                                 harp_dtype_t dt_out, int64_t n, hipStream_t stream);
+harp_status_t launch_transpose(const void *src, int64_t lds_, harp_dtype_t dt_src, void *dst,
+                               int64_t ldd, harp_dtype_t dt_dst, int64_t rows, int64_t cols,
+                               hipStream_t stream);
+harp_status_t launch_copy2d(const void *src, int64_t lds_, void *dst, int64_t ldd, int64_t rows,
+                            int64_t cols, harp_dtype_t dt, hipStream_t stream);
+LaunchCfg choose_launch(const harp_plan *plan, int64_t n);
+const HostProgram *select_program(const harp_plan *plan, Direction dir, const char **name);
+
+}  // namespace harp
+#endif

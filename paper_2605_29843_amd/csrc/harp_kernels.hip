@@ -1,0 +1,483 @@
+// HIP kernels for gfx950 and their launchers.
+//
+// harp_tile_kernel: one workgroup owns a tile of R rows.  The tile is loaded once from
+// device memory into LDS as float32 (bf16 widened, signs applied for the forward
+// direction), every stage of the processor is executed on that on-chip copy, and the tile
+// is written back once (signs applied here for the transposed direction, one
+// round-to-nearest-even to bf16).  Between the load and the store nothing touches device
+// memory except the stream of stage parameters.
+//
+// The stages are grouped into passes (see PassDesc).  Within a pass a thread owns one
+// sub-tensor position q of the row for several rows of the tile: it reads the parameters
+// of its 2x2 / bxb blocks into registers once and reuses them for every row it handles,
+// so the parameter stream is read once per tile, not once per row (Alg. 1's K_t[c] does not
+// depend on the row).  The stride permutation P_t of Eq. (7) is never materialised: a
+// stage's coordinates alpha*b*s + r*s + beta are addressed directly in LDS (Lemma 1).
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdlib.h>
+
+#include "harp_internal.h"
+
+namespace harp {
+
+namespace {
+
+// ------------------------------------------------------------------------------------------
+// element conversion
+__device__ __forceinline__ float widen_bf16(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  // hardware round-to-nearest-even conversion (v_cvt_pk_bf16_f32 on gfx950)
+  typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+  bf2 v;
+  v.x = (__bf16)lo;
+  v.y = (__bf16)hi;
+  return __builtin_bit_cast(uint32_t, v);
+}
+
+__device__ __forceinline__ uint16_t narrow_bf16(float f) {
+  __bf16 h = (__bf16)f;
+  return __builtin_bit_cast(uint16_t, h);
+}
+
+template <typename T>
+struct IoTraits;
+template <>
+struct IoTraits<float> {
+  static constexpr int kVec = 4;  // elements per 16-byte access
+};
+template <>
+struct IoTraits<uint16_t> {
+  static constexpr int kVec = 8;
+};
+
+__device__ __forceinline__ void load_vec(const float *p, float (&v)[4]) {
+  const float4 t = *reinterpret_cast<const float4 *>(p);
+  v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+}
+__device__ __forceinline__ void load_vec(const uint16_t *p, float (&v)[8]) {
+  const uint4 t = *reinterpret_cast<const uint4 *>(p);
+  v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xffff0000u);
+  v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xffff0000u);
+  v[4] = __uint_as_float(t.z << 16); v[5] = __uint_as_float(t.z & 0xffff0000u);
+  v[6] = __uint_as_float(t.w << 16); v[7] = __uint_as_float(t.w & 0xffff0000u);
+}
+__device__ __forceinline__ void store_vec(float *p, const float (&v)[4]) {
+  *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+}
+__device__ __forceinline__ void store_vec(uint16_t *p, const float (&v)[8]) {
+  uint4 t;
+  t.x = pack_bf16x2(v[0], v[1]);
+  t.y = pack_bf16x2(v[2], v[3]);
+  t.z = pack_bf16x2(v[4], v[5]);
+  t.w = pack_bf16x2(v[6], v[7]);
+  *reinterpret_cast<uint4 *>(p) = t;
+}
+__device__ __forceinline__ float load_one(const float *p) { return *p; }
+__device__ __forceinline__ float load_one(const uint16_t *p) { return widen_bf16(*p); }
+__device__ __forceinline__ void store_one(float *p, float v) { *p = v; }
+__device__ __forceinline__ void store_one(uint16_t *p, float v) { *p = narrow_bf16(v); }
+
+// ------------------------------------------------------------------------------------------
+// passes (all operate on the float32 LDS tile, row stride d)
+
+// K consecutive radix-2 stages on sub-tensors of P = 2^K coordinates.
+template <int K, bool DESC, bool ROT>
+__device__ __forceinline__ void pass_pow2(float *tile, int d, int nr, const PassDesc &pd, int tid,
+                                          int nt) {
+  constexpr int P = 1 << K;
+  constexpr int PER = ROT ? 2 : 4;
+  constexpr int NV = K * (P / 2) * PER;
+  const int nq = pd.nq, S = pd.S;
+  const float *__restrict__ params = pd.params;
+  int RG = 1;
+  if (nq < nt) {
+    RG = nt / nq;
+    if (RG > nr) RG = nr;
+  }
+  const int items = nq * RG;
+  for (int it = tid; it < items; it += nt) {
+    int q = it, rg = 0;
+    if (RG > 1) {
+      rg = it / nq;
+      q = it - rg * nq;
+    }
+    float prm[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) prm[v] = params[(size_t)v * nq + q];
+    const int hi = q / S, lo = q - hi * S;
+    float *tb = tile + hi * P * S + lo;
+    for (int row = rg; row < nr; row += RG) {
+      float *t = tb + row * d;
+      float x[P];
+#pragma unroll
+      for (int j = 0; j < P; ++j) x[j] = t[j * S];
+#pragma unroll
+      for (int e = 0; e < K; ++e) {
+        constexpr int dummy = 0;
+        (void)dummy;
+        const int bp = DESC ? K - 1 - e : e;
+#pragma unroll
+        for (int p = 0; p < P / 2; ++p) {
+          const int j0 = ((p >> bp) << (bp + 1)) | (p & ((1 << bp) - 1));
+          const int j1 = j0 | (1 << bp);
+          const float x0 = x[j0], x1 = x[j1];
+          if (ROT) {
+            const float c = prm[(e * (P / 2) + p) * 2 + 0], s = prm[(e * (P / 2) + p) * 2 + 1];
+            x[j0] = fmaf(s, x1, c * x0);
+            x[j1] = fmaf(c, x1, -(s * x0));
+          } else {
+            const float k00 = prm[(e * (P / 2) + p) * 4 + 0], k01 = prm[(e * (P / 2) + p) * 4 + 1];
+            const float k10 = prm[(e * (P / 2) + p) * 4 + 2], k11 = prm[(e * (P / 2) + p) * 4 + 3];
+            x[j0] = fmaf(x1, k10, x0 * k00);
+            x[j1] = fmaf(x1, k11, x0 * k01);
+          }
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < P; ++j) t[j * S] = x[j];
+    }
+  }
+}
+
+// One stage of compile-time radix B (3..8): the whole block lives in registers.
+template <int B>
+__device__ __forceinline__ void pass_small(float *tile, int d, int nr, const PassDesc &pd, int tid,
+                                           int nt) {
+  const int nq = pd.nq, S = pd.S;
+  const float *__restrict__ params = pd.params;
+  int RG = 1;
+  if (nq < nt) {
+    RG = nt / nq;
+    if (RG > nr) RG = nr;
+  }
+  const int items = nq * RG;
+  for (int it = tid; it < items; it += nt) {
+    int q = it, rg = 0;
+    if (RG > 1) {
+      rg = it / nq;
+      q = it - rg * nq;
+    }
+    float prm[B * B];
+#pragma unroll
+    for (int v = 0; v < B * B; ++v) prm[v] = params[(size_t)v * nq + q];
+    const int hi = q / S, lo = q - hi * S;
+    float *tb = tile + hi * B * S + lo;
+    for (int row = rg; row < nr; row += RG) {
+      float *t = tb + row * d;
+      float x[B], y[B];
+#pragma unroll
+      for (int r = 0; r < B; ++r) x[r] = t[r * S];
+#pragma unroll
+      for (int r2 = 0; r2 < B; ++r2) {
+        float acc = x[0] * prm[r2];
+#pragma unroll
+        for (int r = 1; r < B; ++r) acc = fmaf(x[r], prm[r * B + r2], acc);
+        y[r2] = acc;
+      }
+#pragma unroll
+      for (int r = 0; r < B; ++r) t[r * S] = y[r];
+    }
+  }
+}
+
+// One stage of run-time radix b <= BMAX: a thread owns one block of one row; the block's
+// coordinates are held in registers, the b*b parameters are streamed.
+template <int BMAX>
+__device__ __forceinline__ void pass_generic(float *tile, int d, int nr, const PassDesc &pd,
+                                             int tid, int nt) {
+  const int nq = pd.nq, S = pd.S, b = pd.b;
+  const float *__restrict__ params = pd.params;
+  const int items = nq * nr;
+  for (int it = tid; it < items; it += nt) {
+    const int row = it / nq, q = it - row * nq;
+    const int hi = q / S, lo = q - hi * S;
+    float *t = tile + row * d + hi * b * S + lo;
+    float x[BMAX];
+#pragma unroll
+    for (int r = 0; r < BMAX; ++r) x[r] = (r < b) ? t[r * S] : 0.0f;
+    for (int r2 = 0; r2 < b; ++r2) {
+      const float *pp = params + (size_t)r2 * nq + q;
+      float acc = 0.0f;
+#pragma unroll
+      for (int r = 0; r < BMAX; ++r)
+        if (r < b) acc = fmaf(x[r], pp[(size_t)r * b * nq], acc);
+      t[r2 * S] = acc;
+    }
+  }
+}
+
+template <bool DESC, bool ROT>
+__device__ __forceinline__ void dispatch_pow2(float *tile, int d, int nr, const PassDesc &pd,
+                                              int tid, int nt) {
+  switch (pd.k) {
+    case 1: pass_pow2<1, DESC, ROT>(tile, d, nr, pd, tid, nt); break;
+    case 2: pass_pow2<2, DESC, ROT>(tile, d, nr, pd, tid, nt); break;
+    case 3: pass_pow2<3, DESC, ROT>(tile, d, nr, pd, tid, nt); break;
+    case 4:
+      if (ROT) pass_pow2<4, DESC, true>(tile, d, nr, pd, tid, nt);
+      break;
+    default: break;
+  }
+}
+
+__device__ __forceinline__ void run_pass(float *tile, int d, int nr, const PassDesc &pd, int tid,
+                                         int nt) {
+  switch (pd.kind) {
+    case PASS_POW2_DENSE:
+      if (pd.desc) dispatch_pow2<true, false>(tile, d, nr, pd, tid, nt);
+      else dispatch_pow2<false, false>(tile, d, nr, pd, tid, nt);
+      break;
+    case PASS_POW2_ROT:
+      if (pd.desc) dispatch_pow2<true, true>(tile, d, nr, pd, tid, nt);
+      else dispatch_pow2<false, true>(tile, d, nr, pd, tid, nt);
+      break;
+    case PASS_SMALL:
+      switch (pd.b) {
+        case 3: pass_small<3>(tile, d, nr, pd, tid, nt); break;
+        case 4: pass_small<4>(tile, d, nr, pd, tid, nt); break;
+        case 5: pass_small<5>(tile, d, nr, pd, tid, nt); break;
+        case 6: pass_small<6>(tile, d, nr, pd, tid, nt); break;
+        case 7: pass_small<7>(tile, d, nr, pd, tid, nt); break;
+        case 8: pass_small<8>(tile, d, nr, pd, tid, nt); break;
+        default: break;
+      }
+      break;
+    default:
+      if (pd.b <= 8) pass_generic<8>(tile, d, nr, pd, tid, nt);
+      else if (pd.b <= 16) pass_generic<16>(tile, d, nr, pd, tid, nt);
+      else pass_generic<64>(tile, d, nr, pd, tid, nt);
+      break;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+template <typename TI, typename TO>
+__global__ __launch_bounds__(512) void harp_tile_kernel(const TI *__restrict__ X, int64_t ldx,
+                                                         TO *__restrict__ Y, int64_t ldy, int64_t n,
+                                                         int d, int R, int vec_in, int vec_out,
+                                                         const Program *__restrict__ progp) {
+  extern __shared__ float tile[];
+  const int tid = threadIdx.x, nt = blockDim.x;
+  const int64_t row0 = (int64_t)blockIdx.x * R;
+  const int nr = (int)((n - row0 < R) ? (n - row0) : R);
+  const Program &prog = *progp;   // uniform address: fetched with scalar loads
+  const float *__restrict__ sg = prog.signs;
+  const bool sign_in = sg != nullptr && prog.sign_at_load;
+  const bool sign_out = sg != nullptr && !prog.sign_at_load;
+
+  // ---- load: device memory -> LDS (float32)
+  if (vec_in) {
+    constexpr int VI = IoTraits<TI>::kVec;
+    const int cpr = d / VI;
+    int row = 0, ch = tid;
+    while (ch >= cpr) { ch -= cpr; ++row; }
+    while (row < nr) {
+      float v[VI];
+      load_vec(X + (row0 + row) * ldx + (int64_t)ch * VI, v);
+      if (sign_in) {
+#pragma unroll
+        for (int k = 0; k < VI; ++k) v[k] *= sg[ch * VI + k];
+      }
+      float *t = tile + row * d + ch * VI;
+#pragma unroll
+      for (int k = 0; k < VI; k += 4)
+        *reinterpret_cast<float4 *>(t + k) = make_float4(v[k], v[k + 1], v[k + 2], v[k + 3]);
+      ch += nt;
+      while (ch >= cpr) { ch -= cpr; ++row; }
+    }
+  } else {
+    for (int row = 0; row < nr; ++row)
+      for (int i = tid; i < d; i += nt) {
+        float v = load_one(X + (row0 + row) * ldx + i);
+        if (sign_in) v *= sg[i];
+        tile[row * d + i] = v;
+      }
+  }
+  __syncthreads();
+
+  // ---- all stages on chip
+  for (int p = 0; p < prog.npass; ++p) {
+    run_pass(tile, d, nr, prog.pass[p], tid, nt);
+    __syncthreads();
+  }
+
+  // ---- store: LDS -> device memory
+  if (vec_out) {
+    constexpr int VO = IoTraits<TO>::kVec;
+    const int cpr = d / VO;
+    int row = 0, ch = tid;
+    while (ch >= cpr) { ch -= cpr; ++row; }
+    while (row < nr) {
+      float v[VO];
+      const float *t = tile + row * d + ch * VO;
+#pragma unroll
+      for (int k = 0; k < VO; k += 4) {
+        const float4 f = *reinterpret_cast<const float4 *>(t + k);
+        v[k] = f.x; v[k + 1] = f.y; v[k + 2] = f.z; v[k + 3] = f.w;
+      }
+      if (sign_out) {
+#pragma unroll
+        for (int k = 0; k < VO; ++k) v[k] *= sg[ch * VO + k];
+      }
+      store_vec(Y + (row0 + row) * ldy + (int64_t)ch * VO, v);
+      ch += nt;
+      while (ch >= cpr) { ch -= cpr; ++row; }
+    }
+  } else {
+    for (int row = 0; row < nr; ++row)
+      for (int i = tid; i < d; i += nt) {
+        float v = tile[row * d + i];
+        if (sign_out) v *= sg[i];
+        store_one(Y + (row0 + row) * ldy + i, v);
+      }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// dst[c, r] = src[r, c] with conversion; 32 x 32 tiles through LDS.
+template <typename TS, typename TD>
+__global__ __launch_bounds__(256) void harp_transpose_kernel(const TS *__restrict__ src, int64_t lds_,
+                                                             TD *__restrict__ dst, int64_t ldd,
+                                                             int64_t rows, int64_t cols) {
+  __shared__ float buf[32][33];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+  const int64_t c0 = (int64_t)blockIdx.x * 32, r0 = (int64_t)blockIdx.y * 32;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int64_t r = r0 + ty + 8 * k, c = c0 + tx;
+    if (r < rows && c < cols) buf[ty + 8 * k][tx] = load_one(src + r * lds_ + c);
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int64_t c = c0 + ty + 8 * k, r = r0 + tx;
+    if (r < rows && c < cols) store_one(dst + c * ldd + r, buf[tx][ty + 8 * k]);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void harp_copy2d_kernel(const T *__restrict__ src, int64_t lds_,
+                                                          T *__restrict__ dst, int64_t ldd,
+                                                          int64_t rows, int64_t cols) {
+  const int64_t total = rows * cols;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+       i += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t r = i / cols, c = i - r * cols;
+    dst[r * ldd + c] = src[r * lds_ + c];
+  }
+}
+
+template <typename TI, typename TO>
+harp_status_t launch_tile_typed(const harp_plan *plan, const Program *dprog, const void *X,
+                                int64_t ldx, void *Y, int64_t ldy, int64_t n, hipStream_t stream) {
+  const LaunchCfg cfg = choose_launch(plan, n);
+  if (cfg.rows_per_tile < 1) return HARP_ERR_UNSUPPORTED;
+  const int d = (int)plan->d;
+  const size_t lds = (size_t)cfg.rows_per_tile * d * sizeof(float);
+  auto kern = harp_tile_kernel<TI, TO>;
+  static thread_local int attr_done_dev = -1;
+  if (attr_done_dev != plan->device) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                            hipFuncAttributeMaxDynamicSharedMemorySize,
+                            plan->lds_bytes) != hipSuccess)
+      (void)hipGetLastError();  // not fatal below 64 KB; a too-large launch fails cleanly later
+    attr_done_dev = plan->device;
+  }
+  constexpr int VI = IoTraits<TI>::kVec, VO = IoTraits<TO>::kVec;
+  const int vec_in = (d % VI == 0) && (ldx % VI == 0) && ((uintptr_t)X % 16 == 0);
+  const int vec_out = (d % VO == 0) && (ldy % VO == 0) && ((uintptr_t)Y % 16 == 0);
+  const int64_t tiles = (n + cfg.rows_per_tile - 1) / cfg.rows_per_tile;
+  if (tiles > 0x7fffffff) return HARP_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL(kern, dim3((unsigned)tiles), dim3(cfg.threads), lds, stream,
+                     (const TI *)X, ldx, (TO *)Y, ldy, n, d, cfg.rows_per_tile, vec_in, vec_out,
+                     dprog);
+  return hipGetLastError() == hipSuccess ? HARP_OK : HARP_ERR_DEVICE;
+}
+
+template <typename TS, typename TD>
+harp_status_t launch_transpose_typed(const void *src, int64_t lds_, void *dst, int64_t ldd,
+                                     int64_t rows, int64_t cols, hipStream_t stream) {
+  const dim3 grid((unsigned)((cols + 31) / 32), (unsigned)((rows + 31) / 32));
+  if ((rows + 31) / 32 > 65535 * 16) return HARP_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL((harp_transpose_kernel<TS, TD>), grid, dim3(256), 0, stream, (const TS *)src,
+                     lds_, (TD *)dst, ldd, rows, cols);
+  return hipGetLastError() == hipSuccess ? HARP_OK : HARP_ERR_DEVICE;
+}
+
+int env_int(const char *name, int dflt) {
+  const char *s = getenv(name);
+  if (!s || !*s) return dflt;
+  return atoi(s);
+}
+
+}  // namespace
+
+LaunchCfg choose_launch(const harp_plan *plan, int64_t n) {
+  LaunchCfg cfg{0, 256};
+  const int64_t d = plan->d;
+  const int rmax = (int)(plan->lds_bytes / (4 * d));
+  if (rmax < 1) return cfg;
+  int R = plan->rows_override > 0 ? plan->rows_override : (rmax < 8 ? rmax : 8);
+  if (R > rmax) R = rmax;
+  if (plan->rows_override == 0) {
+    // keep every compute unit busy: shrink the tile while there are fewer tiles than CUs
+    while (R > 1 && (n + R - 1) / R < plan->num_cu) R = (R + 1) / 2;
+  }
+  cfg.rows_per_tile = R;
+  int nt = env_int("HARP_THREADS", 0);
+  if (nt <= 0) {
+    const int64_t work = (int64_t)R * d / 16;
+    nt = 256;
+    while (nt < 512 && nt < work) nt *= 2;
+  }
+  if (nt < 64) nt = 64;
+  if (nt > 512) nt = 512;
+  nt = (nt / 64) * 64;
+  cfg.threads = nt;
+  return cfg;
+}
+
+harp_status_t launch_tile_kernel(const harp_plan *plan, const Program *prog, const void *X,
+                                 int64_t ldx, harp_dtype_t dt_in, void *Y, int64_t ldy,
+                                 harp_dtype_t dt_out, int64_t n, hipStream_t stream) {
+  if (n == 0) return HARP_OK;
+  if (dt_in == HARP_F32 && dt_out == HARP_F32)
+    return launch_tile_typed<float, float>(plan, prog, X, ldx, Y, ldy, n, stream);
+  if (dt_in == HARP_BF16 && dt_out == HARP_BF16)
+    return launch_tile_typed<uint16_t, uint16_t>(plan, prog, X, ldx, Y, ldy, n, stream);
+  if (dt_in == HARP_BF16 && dt_out == HARP_F32)
+    return launch_tile_typed<uint16_t, float>(plan, prog, X, ldx, Y, ldy, n, stream);
+  return launch_tile_typed<float, uint16_t>(plan, prog, X, ldx, Y, ldy, n, stream);
+}
+
+harp_status_t launch_transpose(const void *src, int64_t lds_, harp_dtype_t dt_src, void *dst,
+                               int64_t ldd, harp_dtype_t dt_dst, int64_t rows, int64_t cols,
+                               hipStream_t stream) {
+  if (rows == 0 || cols == 0) return HARP_OK;
+  if (dt_src == HARP_F32 && dt_dst == HARP_F32)
+    return launch_transpose_typed<float, float>(src, lds_, dst, ldd, rows, cols, stream);
+  if (dt_src == HARP_BF16 && dt_dst == HARP_F32)
+    return launch_transpose_typed<uint16_t, float>(src, lds_, dst, ldd, rows, cols, stream);
+  if (dt_src == HARP_F32 && dt_dst == HARP_BF16)
+    return launch_transpose_typed<float, uint16_t>(src, lds_, dst, ldd, rows, cols, stream);
+  return launch_transpose_typed<uint16_t, uint16_t>(src, lds_, dst, ldd, rows, cols, stream);
+}
+
+harp_status_t launch_copy2d(const void *src, int64_t lds_, void *dst, int64_t ldd, int64_t rows,
+                            int64_t cols, harp_dtype_t dt, hipStream_t stream) {
+  if (rows == 0 || cols == 0) return HARP_OK;
+  const int64_t total = rows * cols;
+  int64_t blocks = (total + 255) / 256;
+  if (blocks > 65536) blocks = 65536;
+  if (dt == HARP_F32)
+    hipLaunchKernelGGL((harp_copy2d_kernel<float>), dim3((unsigned)blocks), dim3(256), 0, stream,
+                       (const float *)src, lds_, (float *)dst, ldd, rows, cols);
+  else
+    hipLaunchKernelGGL((harp_copy2d_kernel<uint16_t>), dim3((unsigned)blocks), dim3(256), 0,
+                       stream, (const uint16_t *)src, lds_, (uint16_t *)dst, ldd, rows, cols);
+  return hipGetLastError() == hipSuccess ? HARP_OK : HARP_ERR_DEVICE;
+}
+
+}  // namespace harp

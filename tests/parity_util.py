@@ -1,0 +1,55 @@
+"""Helpers for the GPU parity tests: tensor marshalling and the elementwise tolerance.
+
+Tolerance (the spec bar, made precise with a row-scale floor because rotated outputs
+pass through zero): with rho_i = ||Yref[i,:]||_2 / sqrt(d),
+  float32 I/O :  |Y - Yref|_ij <= 1e-5 * max(|Yref_ij|, rho_i)
+  bfloat16 I/O:  |Y - Yref|_ij <= ulp_bf16(Yref_ij) + 4e-3 * max(|Yref_ij|, rho_i)
+where ulp_bf16(y) = 2^(floor(log2|y|) - 7) (spacing of bf16 numbers at y).
+"""
+import numpy as np
+
+from paper_2605_29843_amd import inputs as gi
+
+
+def to_device(a: np.ndarray, dtype: str):
+    import torch
+    if dtype == "bf16":
+        bits = gi.bf16_bits(a)
+        return torch.from_numpy(bits.view(np.int16).copy()).view(torch.bfloat16).cuda()
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+
+
+def to_host64(t) -> np.ndarray:
+    import torch
+    return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
+
+
+def ulp_bf16(y: np.ndarray) -> np.ndarray:
+    a = np.abs(y)
+    e = np.floor(np.log2(np.maximum(a, 1e-300)))
+    e = np.maximum(e, -126.0)
+    return np.where(a > 0, 2.0 ** (e - 7), 2.0 ** -133)
+
+
+def tolerance(Yref: np.ndarray, dtype: str) -> np.ndarray:
+    d = Yref.shape[1]
+    rho = np.linalg.norm(Yref, axis=1, keepdims=True) / np.sqrt(d)
+    floor = np.maximum(np.abs(Yref), rho)
+    if dtype == "bf16":
+        return ulp_bf16(Yref) + 4e-3 * floor
+    return 1e-5 * floor
+
+
+def assert_parity(Y: np.ndarray, Yref: np.ndarray, dtype: str, what: str = ""):
+    assert Y.shape == Yref.shape, (Y.shape, Yref.shape)
+    assert np.all(np.isfinite(Y)), f"{what}: non-finite output"
+    err = np.abs(Y - Yref)
+    tol = tolerance(Yref, dtype)
+    ratio = err / np.maximum(tol, 1e-300)
+    worst = np.unravel_index(np.argmax(ratio), ratio.shape) if ratio.size else None
+    if ratio.size and ratio[worst] > 1.0:
+        raise AssertionError(
+            f"{what}: |err|={err[worst]:.3e} > tol={tol[worst]:.3e} at {worst}, "
+            f"ref={Yref[worst]:.6e} got={Y[worst]:.6e}; "
+            f"normwise={np.linalg.norm(Y - Yref) / max(np.linalg.norm(Yref), 1e-300):.3e}")
+    return float(ratio.max()) if ratio.size else 0.0

@@ -1,0 +1,129 @@
+"""C-ABI boundary on a GPU-less host: the library loads, exports every declared symbol, and
+turns every argument error into its status code before touching HIP."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2605_29843_amd", "libharp.so")
+
+if not os.path.exists(LIB):   # built by __graft_entry__.build(); build on demand for local runs
+    from paper_2605_29843_amd import build as _b
+    _b.build(verbose=False)
+
+from paper_2605_29843_amd import harp  # noqa: E402
+from paper_2605_29843_amd import inputs as gi  # noqa: E402
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _have_gpu():
+    try:
+        import torch
+        return torch.cuda.is_available()
+    except Exception:
+        return False
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "harp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(harp_[a-z0-9_]+)\s*\(", text))
+    assert {"harp_plan_create", "harp_apply", "harp_apply_transpose", "harp_rotate_weight"} <= declared
+    lib = C.CDLL(LIB)
+    for name in sorted(declared):
+        assert hasattr(lib, name), f"{name} declared in harp.h but not exported"
+    assert declared == set(harp.EXPORTS), declared ^ set(harp.EXPORTS)
+
+
+def test_status_strings_and_version():
+    assert harp.harp_status_string(harp.HARP_OK) == "ok"
+    seen = {harp.harp_status_string(s) for s in range(7)}
+    assert len(seen) == 7
+    assert "gfx950" in harp.harp_version()
+
+
+def test_greedy_schedule_matches_printed_examples():
+    for line in open(os.path.join(GOLD, "greedy_schedule.txt")):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        d, v = line.split(":")
+        assert harp.harp_greedy_schedule(int(d)) == [int(x) for x in v.split()]
+    for line in open(os.path.join(GOLD, "radix_ablation_stage_counts.txt")):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        b, cnt = (int(x) for x in line.split(":"))
+        assert len(harp.harp_greedy_schedule(4096, b, b)) == cnt
+    # other Llama sizes: valid schedules, preferred radix first, leftover prime last
+    assert harp.harp_greedy_schedule(11008) == [8, 8, 4, 43]
+    assert harp.harp_greedy_schedule(14336) == [8, 8, 8, 7, 4]
+    assert harp.harp_greedy_schedule(28672) == [8, 8, 8, 8, 7]
+    for d in (2, 3, 97, 5120, 12288, 8192, 13824):
+        s = harp.harp_greedy_schedule(d)
+        assert int(np.prod(s)) == d and min(s) >= 2
+    with pytest.raises(harp.HarpError) as e:
+        harp.harp_greedy_schedule(1)
+    assert e.value.status == harp.HARP_ERR_INVALID_ARG
+
+
+def _status_of_create(d, radices, blocks, signs=None, flags=0):
+    try:
+        p = harp.Plan(d, radices, blocks, signs, flags)
+    except harp.HarpError as e:
+        return e.status
+    p.destroy()
+    return harp.HARP_OK
+
+
+def test_plan_create_rejects_bad_schedules_before_any_device_work():
+    rng = np.random.default_rng(0)
+    good = gi.make_blocks(16, [4, 4], "orth", rng)
+    assert _status_of_create(16, [4, 2], good) == harp.HARP_ERR_BAD_SCHEDULE      # product != d
+    assert _status_of_create(16, [16, 1], good) == harp.HARP_ERR_BAD_SCHEDULE     # radix < 2
+    assert _status_of_create(16, [], []) == harp.HARP_ERR_BAD_SCHEDULE            # no stage
+    assert _status_of_create(1, [1], good[:1]) == harp.HARP_ERR_INVALID_ARG       # d < 2
+    assert _status_of_create(16, [4, 4], [good[0], None]) == harp.HARP_ERR_INVALID_ARG
+    assert _status_of_create(16, [4, 4], good, flags=64) == harp.HARP_ERR_INVALID_ARG
+    bad_signs = np.array([1] * 15 + [0], dtype=np.int8)
+    assert _status_of_create(16, [4, 4], good, bad_signs) == harp.HARP_ERR_INVALID_ARG
+    nan_blocks = [good[0].copy(), good[1].copy()]
+    nan_blocks[1][2, 1, 1] = np.nan
+    assert _status_of_create(16, [4, 4], nan_blocks) == harp.HARP_ERR_INVALID_ARG
+    big = gi.make_blocks(2 * 67, [2, 67], "orth", rng)
+    assert _status_of_create(134, [2, 67], big) == harp.HARP_ERR_UNSUPPORTED      # radix > 64
+    # non-orthogonal block: accepted without the flag, rejected with it
+    skew = [good[0].copy(), good[1].copy()]
+    skew[0][1] *= 1.01
+    assert _status_of_create(16, [4, 4], skew, flags=harp.HARP_VALIDATE_ORTHO) == \
+        harp.HARP_ERR_NOT_ORTHOGONAL
+    ok = _status_of_create(16, [4, 4], good, flags=harp.HARP_VALIDATE_ORTHO)
+    assert ok == (harp.HARP_OK if _have_gpu() else harp.HARP_ERR_DEVICE)
+
+
+def test_null_plan_and_null_out_are_invalid_arguments():
+    lib = harp.lib
+    assert lib.harp_apply(None, None, 4, None, 4, 1, harp.HARP_F32, None) == harp.HARP_ERR_INVALID_ARG
+    assert lib.harp_apply_transpose(None, None, 4, None, 4, 1, 0, None) == harp.HARP_ERR_INVALID_ARG
+    assert lib.harp_plan_destroy(None) == harp.HARP_OK
+    assert lib.harp_plan_dim(None) == -1
+    assert lib.harp_plan_num_stages(None) == -1
+    assert lib.harp_plan_param_count(None) == -1
+    assert lib.harp_plan_set_algo(None, 0) == harp.HARP_ERR_INVALID_ARG
+    rad = (C.c_int32 * 1)(2)
+    ptr = (C.c_void_p * 1)(None)
+    assert lib.harp_plan_create(None, 2, 1, rad, ptr, None, 0) == harp.HARP_ERR_INVALID_ARG
+    b = C.c_size_t(123)
+    assert lib.harp_rotate_weight_workspace_size(None, None, 8, 8, 7, C.byref(b)) == \
+        harp.HARP_ERR_INVALID_ARG
+    assert lib.harp_rotate_weight_workspace_size(None, None, 8, 8, harp.HARP_BF16, C.byref(b)) == \
+        harp.HARP_OK and b.value == 0
+    # identity on both sides with nothing to copy is a no-op
+    assert lib.harp_rotate_weight(None, None, None, 0, None, 0, 0, 0, harp.HARP_F32, None, 0,
+                                  None) == harp.HARP_OK
+    assert lib.harp_rotate_weight(None, None, None, 8, None, 8, 8, 8, harp.HARP_F32, None, 0,
+                                  None) == harp.HARP_ERR_INVALID_ARG

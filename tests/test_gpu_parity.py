@@ -1,0 +1,326 @@
+"""GPU parity: libharp (through its C ABI) against the float64 CPU oracle, element by element,
+on the same seeded inputs.  Every test prints the case it is about to launch."""
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import harp_oracle as ho
+from paper_2605_29843_amd import inputs as gi
+from parity_util import assert_parity, to_device, to_host64
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def harp():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a device"
+    from paper_2605_29843_amd import harp as h     # raises if libharp.so is missing
+    return h
+
+
+def say(*a):
+    print("[case]", *a, flush=True)
+    sys.stdout.flush()
+
+
+def run_case(harp, d, radices, n, dtype, kind="orth", seed=0, algo=None, ld_pad=0, rows=None,
+             with_signs=True, act=None, both=True):
+    import torch
+    rng = np.random.default_rng(seed)
+    blocks = gi.make_blocks(d, radices, kind, rng)
+    signs = gi.make_signs(d, rng) if with_signs else None
+    X = rng.standard_normal((n, d)).astype(np.float32) if act is None else act
+    if dtype == "bf16":
+        X = gi.round_to_bf16(X)
+    plan = harp.Plan(d, radices, blocks, signs)
+    if algo is not None:
+        plan.set_algo(algo)
+    if rows is not None:
+        plan.set_rows_per_tile(rows)
+    say(f"d={d} radices={radices} n={n} {dtype} kind={kind} algo={algo} ld_pad={ld_pad} rows={rows} "
+        f"kernel={plan.kernel_name()}")
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    Xd_full = torch.zeros((n, d + ld_pad), dtype=tdt, device="cuda")
+    Xd = Xd_full[:, :d]
+    Xd.copy_(to_device(X, dtype))
+    Yd_full = torch.full((n, d + ld_pad), 7.0, dtype=tdt, device="cuda")
+    Yd = Yd_full[:, :d]
+    out = {}
+    harp.harp_apply(plan, Xd, Yd)
+    torch.cuda.synchronize()
+    Y = to_host64(Yd)
+    if n > 0:
+        Yref = ho.apply_staged(X, d, radices, blocks, signs)
+        out["apply"] = assert_parity(Y, Yref, dtype, "apply")
+    if ld_pad:
+        assert torch.all(Yd_full[:, d:] == 7.0), "padding columns were written"
+    if both:
+        Zd_full = torch.full((n, d + ld_pad), 7.0, dtype=tdt, device="cuda")
+        Zd = Zd_full[:, :d]
+        harp.harp_apply_transpose(plan, Xd, Zd)
+        torch.cuda.synchronize()
+        if n > 0:
+            Zref = ho.apply_transpose_staged(X, d, radices, blocks, signs)
+            out["transpose"] = assert_parity(to_host64(Zd), Zref, dtype, "apply_transpose")
+    plan.destroy()
+    return out
+
+
+# ------------------------------------------------------------------ config 1: tiny
+@pytest.mark.parametrize("algo", [1, 2])
+@pytest.mark.parametrize("kind", ["orth", "hadamard"])
+def test_tiny_256_radix2_fp32(harp, algo, kind):
+    w = gi.workload("tiny_256_r2", kind=kind)
+    import torch
+    plan = harp.Plan(w["d"], w["radices"], w["blocks"], w["signs"])
+    plan.set_algo(algo)
+    say("tiny_256_r2", kind, "algo", algo)
+    Xd = to_device(w["X"], "f32")
+    U = ho.build_U(w["d"], w["radices"], w["blocks"], w["signs"])     # the dense definition
+    Y = to_host64(harp.harp_apply(plan, Xd))
+    assert_parity(Y, w["X"].astype(np.float64) @ U, "f32", "apply")
+    Z = to_host64(harp.harp_apply_transpose(plan, Xd))
+    assert_parity(Z, w["X"].astype(np.float64) @ U.T, "f32", "transpose")
+    # round trip on the device
+    back = to_host64(harp.harp_apply_transpose(plan, harp.harp_apply(plan, Xd)))
+    assert np.max(np.abs(back - w["X"])) < 1e-5 * np.max(np.abs(w["X"])) * 4
+    torch.cuda.synchronize()
+    plan.destroy()
+
+
+# ------------------------------------------------------------------ every pass kind, ragged tiles
+SMALL_CASES = [
+    ([2] * 5 + [3], 13), ([4, 4, 4], 9), ([8, 8], 17), ([3, 5, 7], 11), ([2, 2, 7, 2], 5),
+    ([16, 4], 33), ([43, 2, 2], 7), ([2] * 8 + [43], 19), ([5, 2, 3], 1), ([2], 3), ([64], 4),
+    ([2] * 11, 10), ([6, 9, 11], 6), ([2, 2, 2, 2, 2, 2, 2], 70),
+]
+
+
+@pytest.mark.parametrize("radices,n", SMALL_CASES)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("algo", [1, 2])
+def test_small_schedules_all_kinds(harp, radices, n, dtype, algo):
+    d = int(np.prod(radices))
+    run_case(harp, d, radices, n, dtype, kind="orth", seed=d + n, algo=algo)
+
+
+@pytest.mark.parametrize("kind", ["qr", "hadamard"])
+def test_dense_2x2_blocks_and_reflections(harp, kind):
+    """'qr' radix-2 blocks include reflections -> the 4-value 2x2 path; non-orthogonal too."""
+    run_case(harp, 512, [2] * 9, 21, "f32", kind=kind, seed=5, algo=2)
+    run_case(harp, 96, [2, 2, 2, 2, 2, 3], 9, "bf16", kind=kind if kind == "qr" else "orth", seed=6, algo=2)
+
+
+def test_non_orthogonal_blocks_are_still_the_linear_map(harp):
+    import torch
+    d, radices, n = 120, [2, 3, 4, 5], 6
+    rng = np.random.default_rng(8)
+    blocks = [rng.standard_normal((d // b, b, b)).astype(np.float32) for b in radices]
+    signs = gi.make_signs(d, rng)
+    X = rng.standard_normal((n, d)).astype(np.float32)
+    for algo in (1, 2):
+        plan = harp.Plan(d, radices, blocks, signs)
+        plan.set_algo(algo)
+        say("non-orthogonal", radices, "algo", algo)
+        U = ho.U_explicit(d, radices, blocks, signs)
+        Y = to_host64(harp.harp_apply(plan, to_device(X, "f32")))
+        Z = to_host64(harp.harp_apply_transpose(plan, to_device(X, "f32")))
+        torch.cuda.synchronize()
+        scale = np.abs(X.astype(np.float64)) @ np.abs(U)        # magnitude of the summands
+        assert np.max(np.abs(Y - X @ U) / scale) < 2e-6
+        assert np.max(np.abs(Z - X @ U.T) / (np.abs(X.astype(np.float64)) @ np.abs(U.T))) < 2e-6
+        plan.destroy()
+
+
+# ------------------------------------------------------------------ layout edge cases
+def test_empty_batch_is_a_noop(harp):
+    run_case(harp, 64, [2] * 6, 0, "bf16", algo=2)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_leading_dimension_padding_and_unaligned_rows(harp, dtype):
+    run_case(harp, 256, [2] * 8, 19, dtype, ld_pad=24, seed=3)      # aligned padding
+    run_case(harp, 256, [2] * 8, 19, dtype, ld_pad=3, seed=4)       # rows not 16-byte aligned
+    run_case(harp, 105, [3, 5, 7], 8, dtype, ld_pad=1, seed=5)      # odd d: scalar I/O path
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_in_place(harp, dtype):
+    import torch
+    d, radices, n = 1024, [2] * 10, 37
+    rng = np.random.default_rng(12)
+    blocks = gi.make_blocks(d, radices, "orth", rng)
+    signs = gi.make_signs(d, rng)
+    X = rng.standard_normal((n, d)).astype(np.float32)
+    if dtype == "bf16":
+        X = gi.round_to_bf16(X)
+    plan = harp.Plan(d, radices, blocks, signs)
+    say("in place", d, n, dtype)
+    Xd = to_device(X, dtype)
+    harp.harp_apply(plan, Xd, Xd)
+    torch.cuda.synchronize()
+    assert_parity(to_host64(Xd), ho.apply_staged(X, d, radices, blocks, signs), dtype, "in place")
+    plan.destroy()
+
+
+@pytest.mark.parametrize("rows", [1, 2, 3, 5, 8])
+def test_rows_per_tile_override_with_ragged_tail(harp, rows):
+    run_case(harp, 2048, [2] * 11, 29, "bf16", seed=rows, rows=rows)
+
+
+# ------------------------------------------------------------------ config 2: d = 4096
+@pytest.mark.parametrize("radices", [[2] * 12, [8] * 4, [4] * 6, [16] * 3], ids=["r2", "r8", "r4", "r16"])
+def test_llama7b_hidden_4096_dense_oracle(harp, radices):
+    """n = 96 rows (several tiles + ragged tail) against the dense definition X @ U."""
+    import torch
+    d, n = 4096, 91
+    blocks, signs = gi.processor(d, radices, config=2)
+    X = gi.activations(n, d, config=2)
+    plan = harp.Plan(d, radices, blocks, signs)
+    say("4096 dense oracle", radices, plan.kernel_name())
+    U = ho.build_U(d, radices, blocks, signs)
+    Xd = to_device(X, "bf16")
+    Y = to_host64(harp.harp_apply(plan, Xd))
+    Z = to_host64(harp.harp_apply_transpose(plan, Xd))
+    torch.cuda.synchronize()
+    assert_parity(Y, X.astype(np.float64) @ U, "bf16", "apply")
+    assert_parity(Z, X.astype(np.float64) @ U.T, "bf16", "transpose")
+    plan.destroy()
+
+
+def _sampled_full_size(harp, name, n_sample=48, seed=0, transpose=True):
+    """Full-size workload in the launch configuration the benchmark uses; parity on sampled
+    rows (staged oracle, row by row) and norm preservation on every row."""
+    import torch
+    w = gi.workload(name)
+    d, n, radices = w["d"], w["n"], w["radices"]
+    plan = harp.Plan(d, radices, w["blocks"], w["signs"])
+    say("full size", name, f"n={n} d={d}", plan.kernel_name())
+    Xd = to_device(w["X"], "bf16")
+    Yd = harp.harp_apply(plan, Xd)
+    torch.cuda.synchronize()
+    rows = np.sort(np.random.default_rng(seed).choice(n, size=n_sample, replace=False))
+    rows = np.unique(np.concatenate([rows, [0, n - 1]]))
+    Xs = w["X"][rows]
+    Y = to_host64(Yd[torch.from_numpy(rows).cuda()])
+    assert_parity(Y, ho.apply_staged(Xs, d, radices, w["blocks"], w["signs"]), "bf16", name + " apply")
+    # property that holds at any size: every row keeps its norm (orthogonal U), up to bf16 rounding
+    nx = torch.linalg.vector_norm(Xd.float(), dim=1)
+    ny = torch.linalg.vector_norm(Yd.float(), dim=1)
+    assert float(torch.max(torch.abs(ny - nx) / nx)) < 2e-3
+    if transpose:
+        Zd = harp.harp_apply_transpose(plan, Xd)
+        torch.cuda.synchronize()
+        Z = to_host64(Zd[torch.from_numpy(rows).cuda()])
+        assert_parity(Z, ho.apply_transpose_staged(Xs, d, radices, w["blocks"], w["signs"]), "bf16",
+                      name + " transpose")
+        nz = torch.linalg.vector_norm(Zd.float(), dim=1)
+        assert float(torch.max(torch.abs(nz - nx) / nx)) < 2e-3
+    plan.destroy()
+
+
+@pytest.mark.parametrize("name", ["llama7b_4096_r2", "llama7b_4096_r8"])
+def test_full_size_4096(harp, name):
+    _sampled_full_size(harp, name)
+
+
+# ------------------------------------------------------------------ config 3: mixed radix
+@pytest.mark.parametrize("name", ["down_11008_r2x8_43", "ffn_14336_r2x11_7"])
+def test_full_size_mixed_radix(harp, name):
+    _sampled_full_size(harp, name, n_sample=24)
+
+
+@pytest.mark.parametrize("d,radices", [(11008, [8, 8, 4, 43]), (14336, [8, 8, 8, 7, 4]),
+                                       (5120, [8, 8, 8, 5, 2]), (12288, [2] * 12 + [3])])
+def test_paper_greedy_schedules(harp, d, radices):
+    run_case(harp, d, radices, 21, "bf16", seed=d, act=gi.activations(21, d, config=3))
+
+
+# ------------------------------------------------------------------ config 4: decode regime
+@pytest.mark.parametrize("n", [1, 8, 32, 64])
+@pytest.mark.parametrize("d,radices", [(4096, [2] * 12), (12288, [2] * 12 + [3]), (14336, [2] * 11 + [7])])
+def test_decode_regime(harp, n, d, radices):
+    X = gi.activations(n, d, config=4, dist="normal", outlier_frac=0.005, outlier_scale=50.0)
+    run_case(harp, d, radices, n, "bf16", seed=4000 + d + n, act=X, both=False)
+
+
+# ------------------------------------------------------------------ config 5: d = 28672, 8192
+def test_full_size_28672(harp):
+    _sampled_full_size(harp, "ffn70b_28672_r2x12_7", n_sample=12)
+
+
+def test_radix2_chain_8192(harp):
+    run_case(harp, 8192, [2] * 13, 40, "bf16", seed=13, act=gi.activations(40, 8192, config=5))
+
+
+# ------------------------------------------------------------------ rotate_weight
+def _plan_tuple(d, radices, blocks, signs):
+    return (d, radices, blocks, signs)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("do,ru,di,rv", [(24, [2, 3, 4], 40, [8, 5]), (64, [2] * 6, 48, [2, 2, 2, 2, 3]),
+                                         (256, [2] * 8, 344, [2, 2, 2, 43])])
+def test_rotate_weight_small_dense(harp, dtype, do, ru, di, rv):
+    import torch
+    rng = np.random.default_rng(do + di)
+    bu, bv = gi.make_blocks(do, ru, "orth", rng), gi.make_blocks(di, rv, "orth", rng)
+    su, sv = gi.make_signs(do, rng), gi.make_signs(di, rng)
+    W = rng.standard_normal((do, di)).astype(np.float32)
+    if dtype == "bf16":
+        W = gi.round_to_bf16(W)
+    pu, pv = harp.Plan(do, ru, bu, su), harp.Plan(di, rv, bv, sv)
+    say("rotate_weight", do, di, dtype)
+    Wd = to_device(W, dtype)
+    ref = ho.rotate_weight(W, _plan_tuple(do, ru, bu, su), _plan_tuple(di, rv, bv, sv))
+    out = harp.harp_rotate_weight(pu, pv, Wd)
+    torch.cuda.synchronize()
+    assert_parity(to_host64(out), ref, dtype, "U^T W V")
+    # one-sided
+    assert_parity(to_host64(harp.harp_rotate_weight(None, pv, Wd)),
+                  ho.rotate_weight(W, None, _plan_tuple(di, rv, bv, sv)), dtype, "W V")
+    assert_parity(to_host64(harp.harp_rotate_weight(pu, None, Wd)),
+                  ho.rotate_weight(W, _plan_tuple(do, ru, bu, su), None), dtype, "U^T W")
+    assert torch.equal(harp.harp_rotate_weight(None, None, Wd), Wd)
+    # inverse map on the float64-exact input: U (U^T W V) V^T = W
+    Uu, Uv = ho.build_U(do, ru, bu, su), ho.build_U(di, rv, bv, sv)
+    inv = to_host64(harp.harp_rotate_weight_inverse(pu, pv, Wd))
+    assert_parity(inv, Uu @ W.astype(np.float64) @ Uv.T, dtype, "U W V^T")
+    # in place
+    W2 = Wd.clone()
+    harp.harp_rotate_weight(pu, pv, W2, W2)
+    torch.cuda.synchronize()
+    assert torch.equal(W2, out)
+    pu.destroy()
+    pv.destroy()
+
+
+def test_rotate_weight_llama70b_shape_sampled(harp):
+    """W 8192 x 28672 bf16: rows of U^T W V recomputed one by one by the oracle."""
+    import torch
+    do, di = 8192, 28672
+    ru, rv = [2] * 13, [2] * 12 + [7]
+    bu, su = gi.processor(do, ru, config=5, salt=1)
+    bv, sv = gi.processor(di, rv, config=5, salt=2)
+    W = gi.weights(do, di, config=5)
+    pu, pv = harp.Plan(do, ru, bu, su), harp.Plan(di, rv, bv, sv)
+    say("rotate_weight 8192x28672 bf16")
+    Wd = to_device(W, "bf16")
+    out = harp.harp_rotate_weight(pu, pv, Wd)
+    torch.cuda.synchronize()
+    rows = [0, 1234, 8191]
+    E = np.zeros((len(rows), do))
+    E[np.arange(len(rows)), rows] = 1.0
+    # row i of U^T is e_i U^T
+    UtW = ho.apply_transpose_staged(E, do, ru, bu, su) @ W.astype(np.float64)
+    ref = ho.apply_staged(UtW, di, rv, bv, sv)
+    got = to_host64(out[torch.tensor(rows).cuda()])
+    assert_parity(got, ref, "bf16", "rotate_weight rows")
+    # Frobenius norm is preserved
+    nw = float(torch.linalg.matrix_norm(Wd.float()))
+    no = float(torch.linalg.matrix_norm(out.float()))
+    assert abs(no - nw) / nw < 1e-3
+    pu.destroy()
+    pv.destroy()
