@@ -146,8 +146,8 @@ int64_t harp_plan_param_bytes(const harp_plan_t *plan);
 /* Choose the kernel family for later launches of this plan (not thread-safe against
  * concurrent launches).  HARP_ERR_UNSUPPORTED leaves the previous choice in place. */
 harp_status_t harp_plan_set_algo(harp_plan_t *plan, harp_algo_t algo);
-/* Rows per workgroup tile for later launches; 0 restores the automatic choice.
- * INVALID_ARG if the tile would not fit in the 160 KB LDS. */
+/* Rows per workgroup tile for later launches; 0 restores the automatic choice.  Kernels that
+ * keep the whole tile in the 160 KB LDS clamp the value to what fits. */
 harp_status_t harp_plan_set_rows_per_tile(harp_plan_t *plan, int32_t rows);
 /* Short name of the kernel path harp_apply would take for n rows (static string). */
 const char *harp_plan_kernel_name(const harp_plan_t *plan, int64_t n, harp_dtype_t dt);

@@ -176,6 +176,9 @@ harp_status_t apply_dir(const harp_plan_t *plan, Direction dir, const void *X, i
                         void *stream) {
   const HostProgram *hp = select_program(plan, dir, nullptr);
   if (!hp) return HARP_ERR_UNSUPPORTED;
+  if (dt_in == HARP_BF16 && dt_out == HARP_BF16 && pipe_supported(plan, hp->prog, X, ldx, Y, ldy))
+    return launch_pipe_kernel(plan, *hp, X, ldx, Y, ldy, n, choose_pipe_rows(plan, n),
+                              (hipStream_t)stream);
   return launch_tile_kernel(plan, hp->dev, X, ldx, dt_in, Y, ldy, dt_out, n, (hipStream_t)stream);
 }
 
@@ -226,6 +229,17 @@ harp_status_t rotate_impl(const harp_plan_t *pu, const harp_plan_t *pv, Directio
 }  // namespace
 
 namespace harp {
+
+int choose_pipe_rows(const harp_plan *plan, int64_t n) {
+  if (plan->rows_override > 0) return plan->rows_override;
+  // one tile per compute unit while that keeps tiles at <= 32 rows; otherwise several waves
+  // of tiles of nearly equal size
+  const int64_t cu = plan->num_cu > 0 ? plan->num_cu : 256;
+  const int64_t waves = (n + cu * 32 - 1) / (cu * 32);
+  int64_t R = (n + cu * waves - 1) / (cu * waves);
+  if (R < 1) R = 1;
+  return (int)R;
+}
 
 const HostProgram *select_program(const harp_plan *plan, Direction dir, const char **name) {
   int algo = plan->algo;
@@ -509,7 +523,6 @@ harp_status_t harp_plan_set_algo(harp_plan_t *plan, harp_algo_t algo) {
 
 harp_status_t harp_plan_set_rows_per_tile(harp_plan_t *plan, int32_t rows) {
   if (!plan || rows < 0) return HARP_ERR_INVALID_ARG;
-  if (rows > 0 && (int64_t)rows * plan->d * 4 > plan->lds_bytes) return HARP_ERR_INVALID_ARG;
   plan->rows_override = rows;
   return HARP_OK;
 }
@@ -519,7 +532,9 @@ const char *harp_plan_kernel_name(const harp_plan_t *plan, int64_t n, harp_dtype
   (void)dt;
   if (!plan) return "none";
   const char *nm = "none";
-  select_program(plan, DIR_FWD, &nm);
+  const HostProgram *hp = select_program(plan, DIR_FWD, &nm);
+  if (hp && dt == HARP_BF16 && pipe_supported(plan, hp->prog, nullptr, 8, nullptr, 8))
+    return "pipe_radix2";
   return nm;
 }
 

@@ -190,6 +190,39 @@ def test_llama7b_hidden_4096_dense_oracle(harp, radices):
     plan.destroy()
 
 
+@pytest.mark.parametrize("n,rows", [(1, None), (2, None), (3, 2), (5, 1), (37, 7), (91, None), (300, 32),
+                                    (64, 64)])
+@pytest.mark.parametrize("with_signs", [True, False])
+def test_pipelined_radix2_kernel_4096(harp, n, rows, with_signs):
+    """d = 4096, twelve rotation stages, bf16: the row-pipelined kernel at ragged tile sizes
+    (fill/drain of the three-stage pipeline with fewer rows than pipeline stages, too)."""
+    X = gi.activations(n, 4096, config=2)
+    out = run_case(harp, 4096, [2] * 12, n, "bf16", seed=100 + n, rows=rows, with_signs=with_signs,
+                   act=X)
+    assert set(out) == {"apply", "transpose"}
+
+
+def test_pipelined_kernel_is_selected_and_in_place(harp):
+    import torch
+    d, radices, n = 4096, [2] * 12, 77
+    blocks, signs = gi.processor(d, radices, config=2)
+    X = gi.activations(n, d, config=2)
+    plan = harp.Plan(d, radices, blocks, signs)
+    assert plan.kernel_name() == "pipe_radix2"
+    say("pipe in place", n)
+    Xd = to_device(X, "bf16")
+    harp.harp_apply(plan, Xd, Xd)
+    torch.cuda.synchronize()
+    assert_parity(to_host64(Xd), ho.apply_staged(X, d, radices, blocks, signs), "bf16", "in place")
+    # forcing the generic family takes the other kernel and still matches
+    plan.set_algo(1)
+    assert plan.kernel_name() == "tile_generic"
+    Y = harp.harp_apply(plan, to_device(X, "bf16"))
+    torch.cuda.synchronize()
+    assert_parity(to_host64(Y), ho.apply_staged(X, d, radices, blocks, signs), "bf16", "generic")
+    plan.destroy()
+
+
 def _sampled_full_size(harp, name, n_sample=48, seed=0, transpose=True):
     """Full-size workload in the launch configuration the benchmark uses; parity on sampled
     rows (staged oracle, row by row) and norm preservation on every row."""
