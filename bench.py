@@ -25,6 +25,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+KERNEL_SYMBOL = {"pipe_radix2": "harp_pipe_bf16_kernel", "tile_fused": "harp_tile_kernel",
+                 "tile_generic": "harp_tile_kernel"}
 
 
 def cpu_baseline(w, sample_rows: int):
@@ -140,7 +142,7 @@ def main():
                    "step": "harp_apply + harp_apply_transpose on one batch"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "harp_tile_kernel", "avg_launch_us": kernel_us,
+                     "kernel": KERNEL_SYMBOL.get(plan.kernel_name(), plan.kernel_name()), "avg_launch_us": kernel_us,
                      "algorithmic_bytes_per_launch": alg_bytes, "param_bytes": param_bytes},
     }
     if not args.no_cpu:

@@ -14,22 +14,97 @@ using namespace harp;
 
 namespace {
 
-struct StageView {        // host copy of one stage's blocks, effective for a direction
-  const float *K;         // [D][b][b] as given by the caller
-  int32_t b;
-  int64_t s;
-  bool transposed;
-  inline float at(int64_t c, int r, int r2) const {
-    return transposed ? K[(c * b + r2) * b + r] : K[(c * b + r) * b + r2];
-  }
+// Effective form of one executed stage (a direction's program), after the +-1 signs of the
+// processor and the signs released by earlier lifted stages have been folded in.
+//
+// A 2x2 orthogonal block M (row vector on the left) factors as R * diag(d0, d1) with
+// R = [[C, -S], [S, C]], C >= 0, and R as three shears (lifting steps)
+//     x0 += a x1;  x1 += b x0;  x0 += a x1;      a = S / (1 + C),  b = -S,
+// which costs 3 fused multiply-adds per coordinate pair instead of 4 operations, with
+// |a|, |b| <= 1.  The output signs d0, d1 are not applied: they are pushed onto the input rows
+// of whichever later stage touches those coordinates.  A dense stage absorbs all pending
+// signs into the rows of its blocks.  The last stage of a program is always dense and also
+// takes the processor's output signs (transposed direction) on its columns, so no kernel
+// ever multiplies by a sign vector.
+struct StageEff {
+  int t = 0;
+  int32_t b = 0;
+  int64_t s = 0;
+  bool lifted = false;
+  std::vector<float> dense;   // [D][b][b], E'[c][r][r2]            (when !lifted)
+  std::vector<float> la, lb;  // [D] lifting coefficients             (when lifted)
 };
 
-bool stage_all_rotations(const float *K, int64_t D) {
+inline int64_t coord_of(int64_t c, int r, int32_t b, int64_t s) {
+  const int64_t alpha = c / s, beta = c % s;   // Lemma 1: alpha*b*s + r*s + beta
+  return alpha * b * s + (int64_t)r * s + beta;
+}
+
+// true when every 2x2 block is a rotation or a reflection to float32 rounding
+bool stage_orthogonal_2x2(const float *K, int64_t D) {
   for (int64_t c = 0; c < D; ++c) {
-    const float *k = K + c * 4;
-    if (!(k[3] == k[0] && k[1] == -k[2])) return false;
+    const double e00 = K[c * 4 + 0], e01 = K[c * 4 + 1], e10 = K[c * 4 + 2], e11 = K[c * 4 + 3];
+    if (std::fabs(e00 * e00 + e10 * e10 - 1.0) > 4e-7) return false;
+    const double rot = std::fabs(e01 + e10) + std::fabs(e11 - e00);   // [[c,-s],[s,c]]
+    const double ref = std::fabs(e01 - e10) + std::fabs(e11 + e00);   // [[c, s],[s,-c]]
+    if (std::min(rot, ref) > 3e-7) return false;
   }
   return true;
+}
+
+void build_effective(const harp_plan *plan, const std::vector<const float *> &blocks,
+                     const int8_t *signs, int algo, Direction dir, std::vector<StageEff> &out) {
+  const int m = plan->m;
+  const int64_t d = plan->d;
+  std::vector<float> tau(d, 1.0f);
+  if (dir == DIR_FWD && signs)
+    for (int64_t i = 0; i < d; ++i) tau[i] = (float)signs[i];
+  out.clear();
+  out.resize(m);
+  for (int i = 0; i < m; ++i) {
+    const int t = (dir == DIR_FWD) ? i : m - 1 - i;
+    StageEff &se = out[i];
+    se.t = t;
+    se.b = plan->radices[t];
+    se.s = plan->strides[t];
+    const int b = se.b;
+    const int64_t D = d / b;
+    const float *K = blocks[t];
+    const bool last = (i == m - 1);
+    auto E = [&](int64_t c, int r, int r2) -> double {   // block as used in this direction
+      return dir == DIR_TRN ? K[(c * b + r2) * b + r] : K[(c * b + r) * b + r2];
+    };
+    se.lifted = (algo == HARP_ALGO_FUSED && b == 2 && !last && stage_orthogonal_2x2(K, D));
+    if (se.lifted) {
+      se.la.resize(D);
+      se.lb.resize(D);
+      for (int64_t c = 0; c < D; ++c) {
+        const int64_t i0 = coord_of(c, 0, 2, se.s), i1 = coord_of(c, 1, 2, se.s);
+        const double m00 = tau[i0] * E(c, 0, 0), m01 = tau[i0] * E(c, 0, 1);
+        const double m10 = tau[i1] * E(c, 1, 0), m11 = tau[i1] * E(c, 1, 1);
+        const double d0 = (m00 >= 0.0) ? 1.0 : -1.0;
+        const double C = d0 * m00, S = d0 * m10;
+        const double d1 = (m11 * C - m01 * S >= 0.0) ? 1.0 : -1.0;
+        se.la[c] = (float)(S / (1.0 + C));
+        se.lb[c] = (float)(-S);
+        tau[i0] = (float)d0;
+        tau[i1] = (float)d1;
+      }
+    } else {
+      se.dense.resize((size_t)D * b * b);
+      for (int64_t c = 0; c < D; ++c) {
+        for (int r = 0; r < b; ++r) {
+          const int64_t ir = coord_of(c, r, b, se.s);
+          for (int r2 = 0; r2 < b; ++r2) {
+            double v = tau[ir] * E(c, r, r2);
+            if (last && dir == DIR_TRN && signs) v *= (double)signs[coord_of(c, r2, b, se.s)];
+            se.dense[((size_t)c * b + r) * b + r2] = (float)v;
+          }
+        }
+        for (int r = 0; r < b; ++r) tau[coord_of(c, r, b, se.s)] = 1.0f;
+      }
+    }
+  }
 }
 
 // Split a run of `len` stages into ceil(len / kmax) nearly equal parts.
@@ -48,61 +123,59 @@ int ilog2(int64_t v) {
 // Build the pass list and the packed parameter image for one (algo, direction).
 // Layout of the image: per pass, V rows of nq floats (value v of sub-tensor q at v*nq + q),
 // so that consecutive threads (consecutive q) read consecutive addresses.
-bool build_program(const harp_plan *plan, const std::vector<const float *> &blocks, int algo,
-                   Direction dir, HostProgram &hp, std::vector<float> &image,
-                   std::vector<size_t> &offsets) {
+bool build_program(const harp_plan *plan, const std::vector<const float *> &blocks,
+                   const int8_t *signs, int algo, Direction dir, HostProgram &hp,
+                   std::vector<float> &image, std::vector<size_t> &offsets) {
   const int m = plan->m;
   const int64_t d = plan->d;
-  std::vector<int> order(m);
-  for (int i = 0; i < m; ++i) order[i] = (dir == DIR_FWD) ? i : m - 1 - i;
+  std::vector<StageEff> eff;
+  build_effective(plan, blocks, signs, algo, dir, eff);
 
   Program &pg = hp.prog;
   pg.npass = 0;
-  pg.sign_at_load = (dir == DIR_FWD) ? 1 : 0;
-  pg.signs = nullptr;
   image.clear();
   offsets.clear();
 
-  auto stage = [&](int t) {
-    return StageView{blocks[t], plan->radices[t], plan->strides[t], dir == DIR_TRN};
-  };
-
   int i = 0;
   while (i < m) {
-    const int t = order[i];
-    const int b = plan->radices[t];
+    const int b = eff[i].b;
     if (algo == HARP_ALGO_FUSED && b == 2) {
-      // maximal run of radix-2 stages that are adjacent digits, all rotations or all dense
-      const bool rot = stage_all_rotations(blocks[t], d / 2);
+      // sub-run of radix-2 stages of one form; a lifted sub-run may end with the program's
+      // final (dense) stage
+      const bool lift = eff[i].lifted;
       int len = 1;
-      while (i + len < m && plan->radices[order[i + len]] == 2 &&
-             stage_all_rotations(blocks[order[i + len]], d / 2) == rot)
+      while (i + len < m && eff[i + len].b == 2 && eff[i + len].lifted == lift) ++len;
+      bool last_dense = false;
+      if (lift && i + len == m - 1 && eff[m - 1].b == 2) {
         ++len;
+        last_dense = true;
+      }
       std::vector<int> parts;
-      split_run(len, rot ? 4 : 3, parts);
-      for (int k : parts) {
+      split_run(len, lift ? 4 : 3, parts);
+      for (size_t pi = 0; pi < parts.size(); ++pi) {
+        const int k = parts[pi];
+        const bool ld = last_dense && pi + 1 == parts.size();
         if (pg.npass >= kMaxPasses) return false;
         PassDesc &pd = pg.pass[pg.npass++];
         const int P = 1 << k;
-        int64_t S = plan->strides[order[i]];
-        for (int e = 0; e < k; ++e) S = std::min<int64_t>(S, plan->strides[order[i + e]]);
+        int64_t S = eff[i].s;
+        for (int e = 0; e < k; ++e) S = std::min<int64_t>(S, eff[i + e].s);
         const int64_t nq = d / P;
-        const int per = rot ? 2 : 4;
-        pd.kind = rot ? PASS_POW2_ROT : PASS_POW2_DENSE;
+        pd.kind = lift ? (ld ? PASS_POW2_LIFT_LD : PASS_POW2_LIFT) : PASS_POW2_DENSE;
         pd.b = 2;
         pd.k = k;
         pd.desc = (dir == DIR_TRN) ? 1 : 0;
         pd.P = P;
         pd.S = (int32_t)S;
         pd.nq = (int32_t)nq;
-        pd.V = k * (P / 2) * per;
+        pd.V = lift ? (ld ? (k + 1) * P : k * P) : k * (P / 2) * 4;
         offsets.push_back(image.size());
         image.resize(image.size() + (size_t)pd.V * nq);
         float *img = image.data() + offsets.back();
         for (int e = 0; e < k; ++e) {
-          const StageView sv = stage(order[i + e]);
-          const int bp = ilog2(sv.s / S);
-          // the kernel assumes digit position e (ascending) or k-1-e (descending)
+          const StageEff &se = eff[i + e];
+          const int bp = ilog2(se.s / S);
+          // the kernels assume digit position e (ascending) or k-1-e (descending)
           if (bp != (pd.desc ? k - 1 - e : e)) return false;
           for (int64_t q = 0; q < nq; ++q) {
             const int64_t hi = q / S, lo = q % S;
@@ -110,17 +183,17 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
             for (int p = 0; p < P / 2; ++p) {
               const int j0 = ((p >> bp) << (bp + 1)) | (p & ((1 << bp) - 1));
               const int64_t idx0 = base + (int64_t)j0 * S;
-              const int64_t beta = idx0 % sv.s, alpha = idx0 / (2 * sv.s);
-              const int64_t c = alpha * sv.s + beta;
-              const size_t v0 = (size_t)(e * (P / 2) + p) * per;
-              if (rot) {
-                img[(v0 + 0) * nq + q] = sv.at(c, 0, 0);
-                img[(v0 + 1) * nq + q] = sv.at(c, 1, 0);
+              const int64_t beta = idx0 % se.s, alpha = idx0 / (2 * se.s);
+              const int64_t c = alpha * se.s + beta;
+              if (se.lifted) {
+                const size_t v0 = (size_t)(e * (P / 2) + p) * 2;
+                img[(v0 + 0) * nq + q] = se.la[c];
+                img[(v0 + 1) * nq + q] = se.lb[c];
               } else {
-                img[(v0 + 0) * nq + q] = sv.at(c, 0, 0);
-                img[(v0 + 1) * nq + q] = sv.at(c, 0, 1);
-                img[(v0 + 2) * nq + q] = sv.at(c, 1, 0);
-                img[(v0 + 3) * nq + q] = sv.at(c, 1, 1);
+                // dense 2x2: inside a lifted pass it follows k-1 lifted stages of P values each
+                const size_t v0 = lift ? (size_t)(k - 1) * P + (size_t)p * 4
+                                       : (size_t)(e * (P / 2) + p) * 4;
+                for (int w = 0; w < 4; ++w) img[(v0 + w) * nq + q] = se.dense[(size_t)c * 4 + w];
               }
             }
           }
@@ -133,17 +206,14 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
     if (b > HARP_MAX_RADIX) return false;
     PassDesc &pd = pg.pass[pg.npass++];
     const bool small = (algo == HARP_ALGO_FUSED && b >= 3 && b <= 8);
-    if (algo == HARP_ALGO_FUSED && !small && b != 2) {
-      // radices above 8 use the run-time radix path inside the fused family as well
-    }
-    const StageView sv = stage(t);
+    const StageEff &se = eff[i];
     const int64_t nq = d / b;
     pd.kind = small ? PASS_SMALL : PASS_GENERIC;
     pd.b = b;
     pd.k = 1;
     pd.desc = 0;
     pd.P = b;
-    pd.S = (int32_t)sv.s;
+    pd.S = (int32_t)se.s;
     pd.nq = (int32_t)nq;
     pd.V = b * b;
     offsets.push_back(image.size());
@@ -152,7 +222,8 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
     // sub-tensor q = hi*S + lo is exactly block c = alpha*s + beta with alpha = hi, beta = lo
     for (int64_t q = 0; q < nq; ++q)
       for (int r = 0; r < b; ++r)
-        for (int r2 = 0; r2 < b; ++r2) img[(size_t)(r * b + r2) * nq + q] = sv.at(q, r, r2);
+        for (int r2 = 0; r2 < b; ++r2)
+          img[(size_t)(r * b + r2) * nq + q] = se.dense[((size_t)q * b + r) * b + r2];
     ++i;
   }
   hp.param_bytes = (int64_t)image.size() * 4;
@@ -355,30 +426,12 @@ harp_status_t harp_plan_create(harp_plan_t **out, int64_t d, int32_t m, const in
         if ((int64_t)d * 4 > lds) st = HARP_ERR_UNSUPPORTED;  // one row must fit in LDS
       }
     }
-    if (st == HARP_OK && signs) {
-      std::vector<float> sf(d);
-      bool any = false;
-      for (int64_t i = 0; i < d; ++i) {
-        sf[i] = (float)signs[i];
-        any |= signs[i] < 0;
-      }
-      if (any) {
-        if (hipMalloc((void **)&plan->dev_signs, (size_t)d * 4) != hipSuccess)
-          st = HARP_ERR_OOM;
-        else {
-          plan->dev_allocs.push_back(plan->dev_signs);
-          if (hipMemcpy(plan->dev_signs, sf.data(), (size_t)d * 4, hipMemcpyHostToDevice) !=
-              hipSuccess)
-            st = HARP_ERR_DEVICE;
-        }
-      }
-    }
     for (int algo = HARP_ALGO_GENERIC; algo <= HARP_ALGO_FUSED && st == HARP_OK; ++algo)
       for (int dir = 0; dir < 2 && st == HARP_OK; ++dir) {
         HostProgram &hp = plan->prog[algo][dir];
         std::vector<float> image;
         std::vector<size_t> offsets;
-        if (!build_program(plan, blk, algo, (Direction)dir, hp, image, offsets)) {
+        if (!build_program(plan, blk, signs, algo, (Direction)dir, hp, image, offsets)) {
           hp.ok = false;
           continue;
         }
@@ -393,7 +446,6 @@ harp_status_t harp_plan_create(harp_plan_t **out, int64_t d, int32_t m, const in
           break;
         }
         for (int p = 0; p < hp.prog.npass; ++p) hp.prog.pass[p].params = dimg + offsets[p];
-        hp.prog.signs = plan->dev_signs;
         Program *dprog = nullptr;
         if (hipMalloc((void **)&dprog, sizeof(Program)) != hipSuccess) {
           st = HARP_ERR_OOM;

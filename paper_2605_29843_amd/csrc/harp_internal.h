@@ -18,9 +18,10 @@ namespace harp {
 // where S is the stride of the run's lowest digit.  Between passes the row tile lives in LDS.
 enum PassKind : int32_t {
   PASS_POW2_DENSE = 0,    // k radix-2 stages, 4 values per 2x2 block
-  PASS_POW2_ROT = 1,      // k radix-2 stages, every block a rotation [[c,-s],[s,c]]: 2 values
+  PASS_POW2_LIFT = 1,     // k radix-2 stages, orthogonal blocks as 3 lifting steps: 2 values
   PASS_SMALL = 2,         // one stage of radix 3..8, compile-time radix, block in registers
-  PASS_GENERIC = 3        // one stage of any radix <= HARP_MAX_RADIX, run-time radix
+  PASS_GENERIC = 3,       // one stage of any radix <= HARP_MAX_RADIX, run-time radix
+  PASS_POW2_LIFT_LD = 4   // as LIFT, but the k-th stage (the program's last) is a dense 2x2
 };
 
 struct PassDesc {
@@ -39,8 +40,7 @@ constexpr int kMaxPasses = HARP_MAX_STAGES;
 
 struct Program {
   int32_t npass;
-  int32_t sign_at_load;   // 1: multiply by signs while loading (apply); 0: while storing
-  const float *signs;     // device [d] of +-1.0f, or nullptr
+  int32_t reserved;
   PassDesc pass[kMaxPasses];
 };
 
@@ -67,7 +67,6 @@ struct harp_plan {
   std::vector<int64_t> strides;
   harp::HostProgram prog[3][2];   // [algo (1 = generic, 2 = fused)][direction]
   std::vector<void *> dev_allocs;
-  float *dev_signs = nullptr;
   int algo = HARP_ALGO_AUTO;
   int rows_override = 0;
   int device = 0;

@@ -1,11 +1,11 @@
 // HIP kernels for gfx950 and their launchers.
 //
 // harp_tile_kernel: one workgroup owns a tile of R rows.  The tile is loaded once from
-// device memory into LDS as float32 (bf16 widened, signs applied for the forward
-// direction), every stage of the processor is executed on that on-chip copy, and the tile
-// is written back once (signs applied here for the transposed direction, one
-// round-to-nearest-even to bf16).  Between the load and the store nothing touches device
-// memory except the stream of stage parameters.
+// device memory into LDS as float32 (bf16 widened), every stage of the processor is executed
+// on that on-chip copy, and the tile is written back once (one round-to-nearest-even to
+// bf16).  Between the load and the store nothing touches device memory except the stream of
+// stage parameters.  The processor's +-1 signs never appear here: the plan folds them into
+// the stage parameters.
 //
 // The stages are grouped into passes (see PassDesc).  Within a pass a thread owns one
 // sub-tensor position q of the row for several rows of the tile: it reads the parameters
@@ -83,12 +83,14 @@ __device__ __forceinline__ void store_one(uint16_t *p, float v) { *p = narrow_bf
 // passes (all operate on the float32 LDS tile, row stride d)
 
 // K consecutive radix-2 stages on sub-tensors of P = 2^K coordinates.
-template <int K, bool DESC, bool ROT>
+// FORM 0: dense 2x2 blocks, 4 values per pair.  FORM 1: orthogonal blocks as three lifting
+// steps, 2 values (a, b) per pair: x0 += a x1; x1 += b x0; x0 += a x1.  FORM 2: as FORM 1
+// but the K-th stage is dense (its 4-value pairs follow the (K-1) * P lifted values).
+template <int K, bool DESC, int FORM>
 __device__ __forceinline__ void pass_pow2(float *tile, int d, int nr, const PassDesc &pd, int tid,
                                           int nt) {
   constexpr int P = 1 << K;
-  constexpr int PER = ROT ? 2 : 4;
-  constexpr int NV = K * (P / 2) * PER;
+  constexpr int NV = (FORM == 0) ? K * (P / 2) * 4 : (FORM == 1 ? K * P : (K + 1) * P);
   const int nq = pd.nq, S = pd.S;
   const float *__restrict__ params = pd.params;
   int RG = 1;
@@ -115,21 +117,23 @@ __device__ __forceinline__ void pass_pow2(float *tile, int d, int nr, const Pass
       for (int j = 0; j < P; ++j) x[j] = t[j * S];
 #pragma unroll
       for (int e = 0; e < K; ++e) {
-        constexpr int dummy = 0;
-        (void)dummy;
         const int bp = DESC ? K - 1 - e : e;
+        const bool dense = (FORM == 0) || (FORM == 2 && e == K - 1);
 #pragma unroll
         for (int p = 0; p < P / 2; ++p) {
           const int j0 = ((p >> bp) << (bp + 1)) | (p & ((1 << bp) - 1));
           const int j1 = j0 | (1 << bp);
-          const float x0 = x[j0], x1 = x[j1];
-          if (ROT) {
-            const float c = prm[(e * (P / 2) + p) * 2 + 0], s = prm[(e * (P / 2) + p) * 2 + 1];
-            x[j0] = fmaf(s, x1, c * x0);
-            x[j1] = fmaf(c, x1, -(s * x0));
+          float x0 = x[j0], x1 = x[j1];
+          if (!dense) {
+            const float a = prm[(e * (P / 2) + p) * 2 + 0], b = prm[(e * (P / 2) + p) * 2 + 1];
+            x0 = fmaf(a, x1, x0);
+            x1 = fmaf(b, x0, x1);
+            x0 = fmaf(a, x1, x0);
+            x[j0] = x0;
+            x[j1] = x1;
           } else {
-            const float k00 = prm[(e * (P / 2) + p) * 4 + 0], k01 = prm[(e * (P / 2) + p) * 4 + 1];
-            const float k10 = prm[(e * (P / 2) + p) * 4 + 2], k11 = prm[(e * (P / 2) + p) * 4 + 3];
+            const int v0 = (FORM == 0) ? (e * (P / 2) + p) * 4 : (K - 1) * P + p * 4;
+            const float k00 = prm[v0 + 0], k01 = prm[v0 + 1], k10 = prm[v0 + 2], k11 = prm[v0 + 3];
             x[j0] = fmaf(x1, k10, x0 * k00);
             x[j1] = fmaf(x1, k11, x0 * k01);
           }
@@ -208,15 +212,15 @@ __device__ __forceinline__ void pass_generic(float *tile, int d, int nr, const P
   }
 }
 
-template <bool DESC, bool ROT>
+template <bool DESC, int FORM>
 __device__ __forceinline__ void dispatch_pow2(float *tile, int d, int nr, const PassDesc &pd,
                                               int tid, int nt) {
   switch (pd.k) {
-    case 1: pass_pow2<1, DESC, ROT>(tile, d, nr, pd, tid, nt); break;
-    case 2: pass_pow2<2, DESC, ROT>(tile, d, nr, pd, tid, nt); break;
-    case 3: pass_pow2<3, DESC, ROT>(tile, d, nr, pd, tid, nt); break;
+    case 1: pass_pow2<1, DESC, FORM>(tile, d, nr, pd, tid, nt); break;
+    case 2: pass_pow2<2, DESC, FORM>(tile, d, nr, pd, tid, nt); break;
+    case 3: pass_pow2<3, DESC, FORM>(tile, d, nr, pd, tid, nt); break;
     case 4:
-      if (ROT) pass_pow2<4, DESC, true>(tile, d, nr, pd, tid, nt);
+      if (FORM != 0) pass_pow2<4, DESC, (FORM == 0 ? 1 : FORM)>(tile, d, nr, pd, tid, nt);
       break;
     default: break;
   }
@@ -226,12 +230,16 @@ __device__ __forceinline__ void run_pass(float *tile, int d, int nr, const PassD
                                          int nt) {
   switch (pd.kind) {
     case PASS_POW2_DENSE:
-      if (pd.desc) dispatch_pow2<true, false>(tile, d, nr, pd, tid, nt);
-      else dispatch_pow2<false, false>(tile, d, nr, pd, tid, nt);
+      if (pd.desc) dispatch_pow2<true, 0>(tile, d, nr, pd, tid, nt);
+      else dispatch_pow2<false, 0>(tile, d, nr, pd, tid, nt);
       break;
-    case PASS_POW2_ROT:
-      if (pd.desc) dispatch_pow2<true, true>(tile, d, nr, pd, tid, nt);
-      else dispatch_pow2<false, true>(tile, d, nr, pd, tid, nt);
+    case PASS_POW2_LIFT:
+      if (pd.desc) dispatch_pow2<true, 1>(tile, d, nr, pd, tid, nt);
+      else dispatch_pow2<false, 1>(tile, d, nr, pd, tid, nt);
+      break;
+    case PASS_POW2_LIFT_LD:
+      if (pd.desc) dispatch_pow2<true, 2>(tile, d, nr, pd, tid, nt);
+      else dispatch_pow2<false, 2>(tile, d, nr, pd, tid, nt);
       break;
     case PASS_SMALL:
       switch (pd.b) {
@@ -263,9 +271,6 @@ __global__ __launch_bounds__(512) void harp_tile_kernel(const TI *__restrict__ X
   const int64_t row0 = (int64_t)blockIdx.x * R;
   const int nr = (int)((n - row0 < R) ? (n - row0) : R);
   const Program &prog = *progp;   // uniform address: fetched with scalar loads
-  const float *__restrict__ sg = prog.signs;
-  const bool sign_in = sg != nullptr && prog.sign_at_load;
-  const bool sign_out = sg != nullptr && !prog.sign_at_load;
 
   // ---- load: device memory -> LDS (float32)
   if (vec_in) {
@@ -276,10 +281,6 @@ __global__ __launch_bounds__(512) void harp_tile_kernel(const TI *__restrict__ X
     while (row < nr) {
       float v[VI];
       load_vec(X + (row0 + row) * ldx + (int64_t)ch * VI, v);
-      if (sign_in) {
-#pragma unroll
-        for (int k = 0; k < VI; ++k) v[k] *= sg[ch * VI + k];
-      }
       float *t = tile + row * d + ch * VI;
 #pragma unroll
       for (int k = 0; k < VI; k += 4)
@@ -290,9 +291,7 @@ __global__ __launch_bounds__(512) void harp_tile_kernel(const TI *__restrict__ X
   } else {
     for (int row = 0; row < nr; ++row)
       for (int i = tid; i < d; i += nt) {
-        float v = load_one(X + (row0 + row) * ldx + i);
-        if (sign_in) v *= sg[i];
-        tile[row * d + i] = v;
+        tile[row * d + i] = load_one(X + (row0 + row) * ldx + i);
       }
   }
   __syncthreads();
@@ -317,10 +316,6 @@ __global__ __launch_bounds__(512) void harp_tile_kernel(const TI *__restrict__ X
         const float4 f = *reinterpret_cast<const float4 *>(t + k);
         v[k] = f.x; v[k + 1] = f.y; v[k + 2] = f.z; v[k + 3] = f.w;
       }
-      if (sign_out) {
-#pragma unroll
-        for (int k = 0; k < VO; ++k) v[k] *= sg[ch * VO + k];
-      }
       store_vec(Y + (row0 + row) * ldy + (int64_t)ch * VO, v);
       ch += nt;
       while (ch >= cpr) { ch -= cpr; ++row; }
@@ -328,9 +323,7 @@ __global__ __launch_bounds__(512) void harp_tile_kernel(const TI *__restrict__ X
   } else {
     for (int row = 0; row < nr; ++row)
       for (int i = tid; i < d; i += nt) {
-        float v = tile[row * d + i];
-        if (sign_out) v *= sg[i];
-        store_one(Y + (row0 + row) * ldy + i, v);
+        store_one(Y + (row0 + row) * ldy + i, tile[row * d + i]);
       }
   }
 }

@@ -1,4 +1,7 @@
-// Row-pipelined kernel for pure radix-2 rotation chains, d = 2^(K0+K1+K2) <= 4096, bf16 I/O.
+// Row-pipelined kernel for pure radix-2 chains of orthogonal blocks, d = 2^(K0+K1+K2) <= 4096,
+// bf16 I/O.  Every stage but the last is executed as three lifting steps, the last as a dense
+// 2x2 that also carries all pending signs (see the plan builder), so the inner loop is fused
+// multiply-adds only.
 //
 // The 10..12 stages are cut into three passes of K0, K1, K2 consecutive stages.  A workgroup
 // has three wave groups of d/16 threads; group g executes pass g and nothing else, so a thread
@@ -6,8 +9,8 @@
 // whole launch (they are read from device memory exactly once per workgroup), and rows flow
 // through the groups like an assembly line:
 //
-//    step k:  group 0  loads row k from device memory (prefetched 4 rows ahead), applies the
-//                      signs and pass 0, writes the row to LDS buffer A[k & 1]
+//    step k:  group 0  takes row k (prefetched from device memory several rows ahead),
+//                      applies pass 0, writes the row to LDS buffer A[k & 1]
 //             group 1  reads row k-1 from A[(k-1) & 1], applies pass 1, writes B[k & 1]
 //             group 2  reads row k-2 from B[(k-1) & 1], applies pass 2, rounds to bf16 and
 //                      stores it to device memory
@@ -28,6 +31,11 @@ namespace harp {
 namespace {
 
 constexpr int kPrefetch = 4;
+// With READ_AHEAD groups 1 and 2 issue the LDS reads of their next row one step before they
+// compute it (two more pipeline steps per tile).  Measured on MI355X it does not pay: LDS
+// instructions and arithmetic of the waves of one SIMD overlap poorly either way, and tiles
+// of 8 rows lose more to the longer fill and drain than they gain.
+constexpr bool READ_AHEAD = false;
 
 // LDS position (in floats) of logical coordinate i of a row: 16 floats of padding per 256,
 // and the four 4-float chunks of every 16-float segment rotated by (segment / 2).
@@ -43,11 +51,13 @@ __device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, v);
 }
 
-// K rotation stages on SPT = 16 / 2^K sub-tensors held in x[16].  prm holds, per sub-tensor,
-// (c, s) of stage e, pair p at ((e * P/2 + p) * 2); y0 = c x0 + s x1, y1 = c x1 - s x0.
-template <int K, bool DESC>
-__device__ __forceinline__ void rot_stages(float (&x)[16], const float (&prm)[16 * K]) {
-  constexpr int P = 1 << K, SPT = 16 / P, NV = K * P;
+// K radix-2 stages on SPT = 16 / 2^K sub-tensors held in x[16].  Stages are lifted rotations
+// (x0 += a x1; x1 += b x0; x0 += a x1, values (a, b) at ((e * P/2 + p) * 2) of the
+// sub-tensor's block of parameters); with LD the K-th stage is a dense 2x2 whose four values
+// per pair follow the (K-1) * P lifted values.
+template <int K, bool DESC, bool LD>
+__device__ __forceinline__ void lift_stages(float (&x)[16], const float (&prm)[16 * (K + (LD ? 1 : 0))]) {
+  constexpr int P = 1 << K, SPT = 16 / P, NV = (K + (LD ? 1 : 0)) * P;
 #pragma unroll
   for (int u = 0; u < SPT; ++u) {
 #pragma unroll
@@ -57,34 +67,46 @@ __device__ __forceinline__ void rot_stages(float (&x)[16], const float (&prm)[16
       for (int p = 0; p < P / 2; ++p) {
         const int j0 = u * P + (((p >> bp) << (bp + 1)) | (p & ((1 << bp) - 1)));
         const int j1 = j0 | (1 << bp);
-        const float c = prm[u * NV + (e * (P / 2) + p) * 2 + 0];
-        const float s = prm[u * NV + (e * (P / 2) + p) * 2 + 1];
-        const float x0 = x[j0], x1 = x[j1];
-        x[j0] = fmaf(s, x1, c * x0);
-        x[j1] = fmaf(c, x1, -(s * x0));
+        float x0 = x[j0], x1 = x[j1];
+        if (LD && e == K - 1) {
+          const int v0 = u * NV + (K - 1) * P + p * 4;
+          x[j0] = fmaf(x1, prm[v0 + 2], x0 * prm[v0 + 0]);
+          x[j1] = fmaf(x1, prm[v0 + 3], x0 * prm[v0 + 1]);
+        } else {
+          const float a = prm[u * NV + (e * (P / 2) + p) * 2 + 0];
+          const float b = prm[u * NV + (e * (P / 2) + p) * 2 + 1];
+          x0 = fmaf(a, x1, x0);
+          x1 = fmaf(b, x0, x1);
+          x0 = fmaf(a, x1, x0);
+          x[j0] = x0;
+          x[j1] = x1;
+        }
       }
     }
   }
 }
 
 // Body of one wave group.  ROLE 0 = first pass (reads device memory), 1 = middle, 2 = last
-// (writes device memory).  LOGS = log2 of the stride of the pass's lowest digit; the pass with
-// LOGS == 0 touches 16 contiguous coordinates per thread (16-byte vector accesses and packed
-// sign masks), the others touch single coordinates.  Every group executes exactly nr + 2
-// barriers.
+// (writes device memory; its K-th stage is the program's last and is dense).  LOGS = log2 of
+// the stride of the pass's lowest digit; the pass with LOGS == 0 touches 16 contiguous
+// coordinates per thread (16-byte vector accesses), the others touch single coordinates.
+// Every group executes the same number of barriers (nr + 2, or nr + 4 with read-ahead).
 template <int K, int LOGS, bool DESC, int ROLE, int D>
 __device__ __forceinline__ void pipe_group(const PassDesc &pd, const int t, const float *rd_buf,
                                            float *wr_buf, const uint16_t *__restrict__ X,
                                            const int64_t ldx, uint16_t *__restrict__ Y,
-                                           const int64_t ldy, const int nr,
-                                           const float *__restrict__ signs) {
-  constexpr int P = 1 << K, SPT = 16 / P, TG = D / 16, NV = K * P, ROWBUF = (D / 256) * 272;
+                                           const int64_t ldy, const int nr) {
+  constexpr bool LD = (ROLE == 2);
+  constexpr int P = 1 << K, SPT = 16 / P, TG = D / 16, NV = (K + (LD ? 1 : 0)) * P;
+  constexpr int ROWBUF = (D / 256) * 272;
   constexpr int S = 1 << LOGS;
   constexpr bool CONTIG = (LOGS == 0);
+  constexpr int NRAW = CONTIG ? 8 : 16;            // dwords of raw input per row and thread
+  constexpr int PF = CONTIG ? kPrefetch : kPrefetch - 1;
   const int nq = pd.nq;
   const float *__restrict__ params = pd.params;
 
-  float prm[16 * K];
+  float prm[SPT * NV];
   unsigned base[SPT];
 #pragma unroll
   for (int u = 0; u < SPT; ++u) {
@@ -104,20 +126,9 @@ __device__ __forceinline__ void pipe_group(const PassDesc &pd, const int t, cons
     return base[u] | ((unsigned)j << LOGS);
   };
 
-  // packed sign masks for the contiguous side (pairs of bf16 in one dword)
-  uint32_t sgn[8];
-#pragma unroll
-  for (int m = 0; m < 8; ++m) sgn[m] = 0u;
-  if (CONTIG && ROLE != 1 && signs != nullptr) {
-#pragma unroll
-    for (int m = 0; m < 8; ++m) {
-      const float s0 = signs[glb_off(2 * m)], s1 = signs[glb_off(2 * m + 1)];
-      sgn[m] = (s0 < 0.0f ? 0x8000u : 0u) | (s1 < 0.0f ? 0x80000000u : 0u);
-    }
-  }
-
-  // ---- ROLE 0: prefetch the first rows (raw bf16 pairs, 8 dwords per row)
-  uint32_t pre[kPrefetch][8];
+  // ---- ROLE 0: prefetch the first rows.  Contiguous side: 8 dwords of bf16 pairs per row;
+  // strided side: one bf16 per dword (widened when consumed).
+  uint32_t pre[PF][NRAW];
   auto issue_load = [&](int slot, int row) {
     const uint16_t *xr = X + (int64_t)row * ldx;   // wave-uniform
     if (CONTIG) {
@@ -129,58 +140,70 @@ __device__ __forceinline__ void pipe_group(const PassDesc &pd, const int t, cons
       }
     } else {
 #pragma unroll
-      for (int m = 0; m < 8; ++m) {
-        const uint32_t a = xr[glb_off(2 * m)];
-        const uint32_t b = xr[glb_off(2 * m + 1)];
-        pre[slot][m] = a | (b << 16);
-      }
+      for (int e = 0; e < 16; ++e) pre[slot][e % NRAW] = xr[glb_off(e)];
     }
   };
   if (ROLE == 0) {
 #pragma unroll
-    for (int s = 0; s < kPrefetch; ++s)
+    for (int s = 0; s < PF; ++s)
       if (s < nr) issue_load(s, s);
   }
 
-  const int nsteps = nr + 2;
-  for (int k0 = 0; k0 < nsteps; k0 += kPrefetch) {
+  // The step loop is unrolled by UNR so that prefetch slots, buffer parities and the two
+  // register sets of the optional LDS read-ahead are static.  Without read-ahead group g
+  // reads and computes row k-g at step k (nr + 2 steps); with it group 1 reads row k-1 and
+  // computes row k-2, group 2 reads row k-3 and computes row k-4 (nr + 4 steps).  One barrier
+  // per step.
+  constexpr int UNR = (ROLE == 0) ? (PF % 2 ? 2 * PF : PF) : 2;
+  constexpr int RD_LAG = READ_AHEAD ? ((ROLE == 0) ? 0 : (ROLE == 1 ? 1 : 3)) : ROLE;
+  const int nsteps = nr + (READ_AHEAD ? 4 : 2);
+  float xa[16], xb[16];
+  for (int k0 = 0; k0 < nsteps; k0 += UNR) {
 #pragma unroll
-    for (int s = 0; s < kPrefetch; ++s) {
+    for (int s = 0; s < UNR; ++s) {
       const int k = k0 + s;
       if (k >= nsteps) break;
-      const int r = k - ROLE;
-      if (r >= 0 && r < nr) {
-        float x[16];
+      float(&xn)[16] = (s & 1) ? xb : xa;   // filled in this step
+      float(&xc)[16] = (ROLE == 0 || !READ_AHEAD) ? xn : ((s & 1) ? xa : xb);   // computed now
+      const int r_rd = k - RD_LAG;
+      const int r_cp = (ROLE == 0 || !READ_AHEAD) ? r_rd : r_rd - 1;
+      if (r_rd >= 0 && r_rd < nr) {
         if (ROLE == 0) {
+          const int slot = s % PF;
+          if (CONTIG) {
 #pragma unroll
-          for (int m = 0; m < 8; ++m) {
-            const uint32_t w = pre[s][m] ^ sgn[m];
-            x[2 * m] = __uint_as_float(w << 16);
-            x[2 * m + 1] = __uint_as_float(w & 0xffff0000u);
+            for (int m = 0; m < 8; ++m) {
+              const uint32_t w = pre[slot][m % NRAW];
+              xn[2 * m] = __uint_as_float(w << 16);
+              xn[2 * m + 1] = __uint_as_float(w & 0xffff0000u);
+            }
+          } else {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) xn[e] = __uint_as_float(pre[slot][e % NRAW] << 16);
           }
-          if (r + kPrefetch < nr) issue_load(s, r + kPrefetch);
+          if (r_rd + PF < nr) issue_load(slot, r_rd + PF);
         } else {
-          const float *b = rd_buf + ((s + 1) & 1) * ROWBUF;   // (k - 1) & 1, kPrefetch is even
+          const float *b = rd_buf + ((s + 1) & 1) * ROWBUF;   // written in step k - 1
           if (CONTIG) {
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
               const float4 f = *reinterpret_cast<const float4 *>(b + lds_off(4 * c));
-              x[4 * c] = f.x; x[4 * c + 1] = f.y; x[4 * c + 2] = f.z; x[4 * c + 3] = f.w;
+              xn[4 * c] = f.x; xn[4 * c + 1] = f.y; xn[4 * c + 2] = f.z; xn[4 * c + 3] = f.w;
             }
           } else {
 #pragma unroll
-            for (int e = 0; e < 16; ++e) x[e] = b[lds_off(e)];
+            for (int e = 0; e < 16; ++e) xn[e] = b[lds_off(e)];
           }
         }
-
-        rot_stages<K, DESC>(x, prm);
-
+      }
+      if (r_cp >= 0 && r_cp < nr) {
+        lift_stages<K, DESC, LD>(xc, prm);
         if (ROLE == 2) {
-          uint16_t *yr = Y + (int64_t)r * ldy;   // wave-uniform
+          uint16_t *yr = Y + (int64_t)r_cp * ldy;   // wave-uniform
           if (CONTIG) {
             uint32_t w[8];
 #pragma unroll
-            for (int m = 0; m < 8; ++m) w[m] = cvt_pk_bf16(x[2 * m], x[2 * m + 1]) ^ sgn[m];
+            for (int m = 0; m < 8; ++m) w[m] = cvt_pk_bf16(xc[2 * m], xc[2 * m + 1]);
 #pragma unroll
             for (int h = 0; h < 2; ++h)
               *reinterpret_cast<uint4 *>(yr + glb_off(8 * h)) =
@@ -188,21 +211,21 @@ __device__ __forceinline__ void pipe_group(const PassDesc &pd, const int t, cons
           } else {
 #pragma unroll
             for (int m = 0; m < 8; ++m) {
-              const uint32_t w = cvt_pk_bf16(x[2 * m], x[2 * m + 1]);
+              const uint32_t w = cvt_pk_bf16(xc[2 * m], xc[2 * m + 1]);
               yr[glb_off(2 * m)] = (uint16_t)(w & 0xffffu);
               yr[glb_off(2 * m + 1)] = (uint16_t)(w >> 16);
             }
           }
         } else {
-          float *b = wr_buf + (s & 1) * ROWBUF;               // k & 1
+          float *b = wr_buf + (s & 1) * ROWBUF;               // read by the next group in step k + 1
           if (CONTIG) {
 #pragma unroll
             for (int c = 0; c < 4; ++c)
               *reinterpret_cast<float4 *>(b + lds_off(4 * c)) =
-                  make_float4(x[4 * c], x[4 * c + 1], x[4 * c + 2], x[4 * c + 3]);
+                  make_float4(xc[4 * c], xc[4 * c + 1], xc[4 * c + 2], xc[4 * c + 3]);
           } else {
 #pragma unroll
-            for (int e = 0; e < 16; ++e) b[lds_off(e)] = x[e];
+            for (int e = 0; e < 16; ++e) b[lds_off(e)] = xc[e];
           }
         }
       }
@@ -225,18 +248,14 @@ __global__ __launch_bounds__(3 << (K0 + K1 + K2 - 4)) void harp_pipe_bf16_kernel
   const Program &prog = *progp;
   const uint16_t *Xt = X + row0 * ldx;
   uint16_t *Yt = Y + row0 * ldy;
-  const float *sg = prog.signs;
-  // signs act on the input of apply (first pass) and on the output of apply_transpose (last)
   // stride of each pass's lowest digit: ascending for apply, descending for apply_transpose
   constexpr int LS0 = TRN ? K1 + K2 : 0, LS1 = TRN ? K2 : K0, LS2 = TRN ? 0 : K0 + K1;
   if (g == 0)
-    pipe_group<K0, LS0, TRN, 0, D>(prog.pass[0], t, nullptr, bufA, Xt, ldx, Yt, ldy, nr,
-                                   TRN ? nullptr : sg);
+    pipe_group<K0, LS0, TRN, 0, D>(prog.pass[0], t, nullptr, bufA, Xt, ldx, Yt, ldy, nr);
   else if (g == 1)
-    pipe_group<K1, LS1, TRN, 1, D>(prog.pass[1], t, bufA, bufB, Xt, ldx, Yt, ldy, nr, nullptr);
+    pipe_group<K1, LS1, TRN, 1, D>(prog.pass[1], t, bufA, bufB, Xt, ldx, Yt, ldy, nr);
   else
-    pipe_group<K2, LS2, TRN, 2, D>(prog.pass[2], t, bufB, nullptr, Xt, ldx, Yt, ldy, nr,
-                                   TRN ? sg : nullptr);
+    pipe_group<K2, LS2, TRN, 2, D>(prog.pass[2], t, bufB, nullptr, Xt, ldx, Yt, ldy, nr);
 }
 
 template <int K0, int K1, int K2, bool TRN>
@@ -260,7 +279,8 @@ bool pipe_supported(const harp_plan *plan, const Program &hp, const void *X, int
   if (plan->algo == HARP_ALGO_GENERIC) return false;
   if (hp.npass != 3) return false;
   for (int p = 0; p < 3; ++p)
-    if (hp.pass[p].kind != PASS_POW2_ROT || hp.pass[p].k != 4) return false;
+    if (hp.pass[p].kind != (p == 2 ? PASS_POW2_LIFT_LD : PASS_POW2_LIFT) || hp.pass[p].k != 4)
+      return false;
   // pass strides must be the ones the kernel is compiled for (1, 16, 256 or reversed)
   const bool trn = hp.pass[0].desc != 0;
   for (int p = 0; p < 3; ++p)

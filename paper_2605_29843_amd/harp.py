@@ -19,7 +19,8 @@ import numpy as np
 import torch  # noqa: F401  (import order matters)
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libharp.so")
+# HARP_LIBRARY may name another build of the same library (e.g. a tuning variant)
+LIB_PATH = os.environ.get("HARP_LIBRARY") or os.path.join(_PKG, "libharp.so")
 
 HARP_OK, HARP_ERR_INVALID_ARG, HARP_ERR_BAD_SCHEDULE, HARP_ERR_NOT_ORTHOGONAL, \
     HARP_ERR_UNSUPPORTED, HARP_ERR_OOM, HARP_ERR_DEVICE = range(7)
