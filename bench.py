@@ -65,6 +65,9 @@ def main():
     ap.add_argument("--rows", type=int, default=None, help="override n (default: the workload's)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--extra", action="store_true", help="also time the other shapes (stderr)")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also launch the library's plain copy kernel on one batch (known bytes), "
+                         "the reference that scales rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (rows shard across GPUs with no "
@@ -123,6 +126,11 @@ def main():
     rt = float((Zi.float() - Xi.float()).abs().max() / Xi.float().abs().max())
     assert rt < (3e-2 if bf16 else 1e-4), f"round trip error {rt}"
 
+    if args.calib_copy:
+        for _ in range(3):   # harp_copy2d_kernel: reads and writes n*d*esz bytes each
+            harp.harp_rotate_weight(None, None, pool[1][0], pool[1][1], stream=stream)
+        torch.cuda.synchronize()
+
     launches = 2 * args.steps
     kernel_us = ev_ms * 1e3 / launches                       # average launch duration (HIP events)
     param_bytes = plan.param_bytes()
@@ -145,6 +153,12 @@ def main():
                      "kernel": KERNEL_SYMBOL.get(plan.kernel_name(), plan.kernel_name()), "avg_launch_us": kernel_us,
                      "algorithmic_bytes_per_launch": alg_bytes, "param_bytes": param_bytes},
     }
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{args.workload}.json")
+    if os.path.exists(tpath) and args.rows is None:
+        with open(tpath) as f:
+            tj = json.load(f)
+        out["roofline"]["traffic"] = tj.get("traffic_bytes_per_launch")
+        out["roofline"]["traffic_source"] = "profiles/" + os.path.basename(tpath)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(w, sample_rows=min(n, 2048))
     if args.extra:
