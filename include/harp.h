@@ -63,7 +63,10 @@ enum {
 typedef enum {
   HARP_ALGO_AUTO = 0,    /* fastest kernel that supports the plan                             */
   HARP_ALGO_GENERIC = 1, /* every stage through the runtime-radix code path                   */
-  HARP_ALGO_FUSED = 2    /* radix-specialised passes; UNSUPPORTED if a stage has no such path */
+  HARP_ALGO_FUSED = 2,   /* radix-specialised passes, whole rows on chip                      */
+  HARP_ALGO_SPLIT = 3    /* low digits (product <= 4096) fused on chip per row chunk, each pass on
+                            the digits above streamed through a float32 intermediate that the
+                            call allocates and frees on the stream (hipMallocAsync)            */
 } harp_algo_t;
 
 #define HARP_MAX_RADIX 64

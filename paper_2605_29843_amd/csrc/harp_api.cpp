@@ -74,7 +74,7 @@ void build_effective(const harp_plan *plan, const std::vector<const float *> &bl
     auto E = [&](int64_t c, int r, int r2) -> double {   // block as used in this direction
       return dir == DIR_TRN ? K[(c * b + r2) * b + r] : K[(c * b + r) * b + r2];
     };
-    se.lifted = (algo == HARP_ALGO_FUSED && b == 2 && !last && stage_orthogonal_2x2(K, D));
+    se.lifted = (algo != HARP_ALGO_GENERIC && b == 2 && !last && stage_orthogonal_2x2(K, D));
     if (se.lifted) {
       se.la.resize(D);
       se.lb.resize(D);
@@ -107,6 +107,9 @@ void build_effective(const harp_plan *plan, const std::vector<const float *> &bl
   }
 }
 
+constexpr int64_t kChunkCap = 4096;   // largest on-chip chunk of a split program
+constexpr int64_t kSplitMinRows = 64;  // AUTO: batches below this stay on the whole-row kernel
+
 // Split a run of `len` stages into ceil(len / kmax) nearly equal parts.
 void split_run(int len, int kmax, std::vector<int> &out) {
   int parts = (len + kmax - 1) / kmax;
@@ -136,17 +139,36 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
   image.clear();
   offsets.clear();
 
+  // Split programs: stages t < tb (product of their radices = chunk <= kChunkCap, maximal) are
+  // chunk-local; passes never mix stages from both sides of tb.
+  const bool fused = (algo != HARP_ALGO_GENERIC);
+  int tb = m;
+  int64_t chunk = d;
+  if (algo == HARP_ALGO_SPLIT) {
+    if (d <= kChunkCap) return false;   // nothing to split: the fused program covers it
+    tb = 0;
+    chunk = 1;
+    while (tb < m && chunk * plan->radices[tb] <= kChunkCap) chunk *= plan->radices[tb++];
+    if (tb == 0) return false;          // first radix alone exceeds the cap (cannot happen: <= 64)
+  }
+  auto local = [&](int i) { return eff[i].t < tb; };
+  hp.chunk = (int32_t)chunk;
+  hp.n_chunk = 0;
+  hp.chunk_first = (dir == DIR_FWD);
+
   int i = 0;
   while (i < m) {
     const int b = eff[i].b;
-    if (algo == HARP_ALGO_FUSED && b == 2) {
-      // sub-run of radix-2 stages of one form; a lifted sub-run may end with the program's
-      // final (dense) stage
+    if (fused && b == 2) {
+      // sub-run of radix-2 stages of one form (and one side of tb); a lifted sub-run may end
+      // with the program's final (dense) stage
       const bool lift = eff[i].lifted;
       int len = 1;
-      while (i + len < m && eff[i + len].b == 2 && eff[i + len].lifted == lift) ++len;
+      while (i + len < m && eff[i + len].b == 2 && eff[i + len].lifted == lift &&
+             local(i + len) == local(i))
+        ++len;
       bool last_dense = false;
-      if (lift && i + len == m - 1 && eff[m - 1].b == 2) {
+      if (lift && i + len == m - 1 && eff[m - 1].b == 2 && local(m - 1) == local(i)) {
         ++len;
         last_dense = true;
       }
@@ -157,6 +179,7 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
         const bool ld = last_dense && pi + 1 == parts.size();
         if (pg.npass >= kMaxPasses) return false;
         PassDesc &pd = pg.pass[pg.npass++];
+        if (local(i)) ++hp.n_chunk;
         const int P = 1 << k;
         int64_t S = eff[i].s;
         for (int e = 0; e < k; ++e) S = std::min<int64_t>(S, eff[i + e].s);
@@ -205,7 +228,8 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
     if (pg.npass >= kMaxPasses) return false;
     if (b > HARP_MAX_RADIX) return false;
     PassDesc &pd = pg.pass[pg.npass++];
-    const bool small = (algo == HARP_ALGO_FUSED && b >= 3 && b <= 8);
+    if (local(i)) ++hp.n_chunk;
+    const bool small = (fused && b >= 3 && b <= 8);
     const StageEff &se = eff[i];
     const int64_t nq = d / b;
     pd.kind = small ? PASS_SMALL : PASS_GENERIC;
@@ -242,18 +266,73 @@ harp_status_t check_apply_args(const harp_plan_t *plan, const void *X, int64_t l
   return HARP_OK;
 }
 
-harp_status_t apply_dir(const harp_plan_t *plan, Direction dir, const void *X, int64_t ldx,
-                        harp_dtype_t dt_in, void *Y, int64_t ldy, harp_dtype_t dt_out, int64_t n,
-                        void *stream) {
-  const HostProgram *hp = select_program(plan, dir, nullptr);
-  if (!hp) return HARP_ERR_UNSUPPORTED;
-  if (dt_in == HARP_BF16 && dt_out == HARP_BF16 && pipe_supported(plan, hp->prog, X, ldx, Y, ldy))
-    return launch_pipe_kernel(plan, *hp, X, ldx, Y, ldy, n, choose_pipe_rows(plan, n),
-                              (hipStream_t)stream);
-  return launch_tile_kernel(plan, hp->dev, X, ldx, dt_in, Y, ldy, dt_out, n, (hipStream_t)stream);
+size_t esize(harp_dtype_t dt) { return dt == HARP_BF16 ? 2 : 4; }
+
+// Passes [p0, p1) of the program on row chunks, fused on chip.
+harp_status_t run_chunk_passes(const harp_plan_t *plan, const HostProgram &hp, int p0, int p1,
+                               const void *X, int64_t ldx, harp_dtype_t dt_in, void *Y, int64_t ldy,
+                               harp_dtype_t dt_out, int64_t n, hipStream_t stream) {
+  if (p0 == 0 && p1 == hp.prog.npass && hp.chunk == plan->d && dt_in == HARP_BF16 &&
+      dt_out == HARP_BF16 && pipe_supported(plan, hp.prog, X, ldx, Y, ldy))
+    return launch_pipe_kernel(plan, hp, X, ldx, Y, ldy, n, choose_pipe_rows(plan, n), stream);
+  return launch_tile_kernel(plan, hp.dev, p0, p1, hp.chunk, X, ldx, dt_in, Y, ldy, dt_out, n,
+                            stream);
 }
 
-size_t esize(harp_dtype_t dt) { return dt == HARP_BF16 ? 2 : 4; }
+harp_status_t apply_dir(const harp_plan_t *plan, Direction dir, const void *X, int64_t ldx,
+                        harp_dtype_t dt_in, void *Y, int64_t ldy, harp_dtype_t dt_out, int64_t n,
+                        void *stream_) {
+  hipStream_t stream = (hipStream_t)stream_;
+  const HostProgram *hpp = select_program(plan, dir, n, nullptr);
+  if (!hpp) return HARP_ERR_UNSUPPORTED;
+  const HostProgram &hp = *hpp;
+  const int np = hp.prog.npass;
+  if (hp.n_chunk == np)   // everything on chip, one launch
+    return run_chunk_passes(plan, hp, 0, np, X, ldx, dt_in, Y, ldy, dt_out, n, stream);
+
+  // Split program: the chunk-local passes run fused on chip, every other pass is streamed
+  // through a float32 intermediate Z.  Rows are processed in slabs so that Z stays small
+  // (it is written by one launch and read by the next: cache resident).
+  const int64_t d = plan->d;
+  int64_t slab = (int64_t)(64u << 20) / (d * 4);
+  if (slab >= 512) slab = (slab / 256) * 256;
+  if (slab < 1) slab = 1;
+  if (slab > n) slab = n;
+  float *Z = nullptr;
+  if (hipMallocAsync((void **)&Z, (size_t)slab * d * 4, stream) != hipSuccess) {
+    (void)hipGetLastError();
+    return HARP_ERR_OOM;
+  }
+  const int nstream = np - hp.n_chunk;
+  const int nseg = nstream + 1;
+  harp_status_t st = HARP_OK;
+  for (int64_t r0 = 0; r0 < n && st == HARP_OK; r0 += slab) {
+    const int64_t nr = (n - r0 < slab) ? n - r0 : slab;
+    const void *src = (const char *)X + (size_t)r0 * ldx * esize(dt_in);
+    int64_t src_ld = ldx;
+    harp_dtype_t src_dt = dt_in;
+    for (int seg = 0; seg < nseg && st == HARP_OK; ++seg) {
+      const bool last = (seg == nseg - 1);
+      void *dst = last ? (void *)((char *)Y + (size_t)r0 * ldy * esize(dt_out)) : (void *)Z;
+      const int64_t dst_ld = last ? ldy : d;
+      const harp_dtype_t dst_dt = last ? dt_out : HARP_F32;
+      const bool is_chunk = hp.chunk_first ? (seg == 0) : last;
+      if (is_chunk) {
+        const int p0 = hp.chunk_first ? 0 : nstream;
+        st = run_chunk_passes(plan, hp, p0, p0 + hp.n_chunk, src, src_ld, src_dt, dst, dst_ld,
+                              dst_dt, nr, stream);
+      } else {
+        const int p = hp.chunk_first ? hp.n_chunk + (seg - 1) : seg;
+        st = launch_stream_pass(plan, hp, p, src, src_ld, src_dt, dst, dst_ld, dst_dt, nr, stream);
+      }
+      src = dst;
+      src_ld = dst_ld;
+      src_dt = dst_dt;
+    }
+  }
+  if (hipFreeAsync(Z, stream) != hipSuccess && st == HARP_OK) st = HARP_ERR_DEVICE;
+  return st;
+}
 
 harp_status_t rotate_impl(const harp_plan_t *pu, const harp_plan_t *pv, Direction dir,
                           const void *W, int64_t ldw, void *Wout, int64_t ldo, int64_t d_out,
@@ -312,12 +391,22 @@ int choose_pipe_rows(const harp_plan *plan, int64_t n) {
   return (int)R;
 }
 
-const HostProgram *select_program(const harp_plan *plan, Direction dir, const char **name) {
+const HostProgram *select_program(const harp_plan *plan, Direction dir, int64_t n,
+                                  const char **name) {
   int algo = plan->algo;
-  if (algo == HARP_ALGO_AUTO) algo = plan->prog[HARP_ALGO_FUSED][dir].ok ? HARP_ALGO_FUSED : HARP_ALGO_GENERIC;
+  if (algo == HARP_ALGO_AUTO) {
+    // rows longer than one on-chip chunk: split unless the batch is tiny (then the extra
+    // launches cost more than re-reading parameters per row does)
+    if (plan->prog[HARP_ALGO_SPLIT][dir].ok && (n >= kSplitMinRows || !plan->prog[HARP_ALGO_FUSED][dir].ok))
+      algo = HARP_ALGO_SPLIT;
+    else
+      algo = plan->prog[HARP_ALGO_FUSED][dir].ok ? HARP_ALGO_FUSED : HARP_ALGO_GENERIC;
+  }
   const HostProgram &hp = plan->prog[algo][dir];
   if (!hp.ok) return nullptr;
-  if (name) *name = (algo == HARP_ALGO_FUSED) ? "tile_fused" : "tile_generic";
+  if (name)
+    *name = (algo == HARP_ALGO_SPLIT) ? "split_chunk_stream"
+                                      : (algo == HARP_ALGO_FUSED ? "tile_fused" : "tile_generic");
   return &hp;
 }
 
@@ -423,15 +512,19 @@ harp_status_t harp_plan_create(harp_plan_t **out, int64_t d, int32_t m, const in
             hipSuccess)
           lds = (int)prop.sharedMemPerBlock;
         plan->lds_bytes = lds;
-        if ((int64_t)d * 4 > lds) st = HARP_ERR_UNSUPPORTED;  // one row must fit in LDS
       }
     }
-    for (int algo = HARP_ALGO_GENERIC; algo <= HARP_ALGO_FUSED && st == HARP_OK; ++algo)
+    for (int algo = HARP_ALGO_GENERIC; algo <= HARP_ALGO_SPLIT && st == HARP_OK; ++algo)
       for (int dir = 0; dir < 2 && st == HARP_OK; ++dir) {
         HostProgram &hp = plan->prog[algo][dir];
         std::vector<float> image;
         std::vector<size_t> offsets;
         if (!build_program(plan, blk, signs, algo, (Direction)dir, hp, image, offsets)) {
+          hp.ok = false;
+          continue;
+        }
+        // whole-row programs need one float32 row in LDS
+        if (algo != HARP_ALGO_SPLIT && (int64_t)d * 4 > plan->lds_bytes) {
           hp.ok = false;
           continue;
         }
@@ -458,7 +551,8 @@ harp_status_t harp_plan_create(harp_plan_t **out, int64_t d, int32_t m, const in
         }
         hp.dev = dprog;
       }
-    if (st == HARP_OK && !plan->prog[HARP_ALGO_GENERIC][0].ok) st = HARP_ERR_UNSUPPORTED;
+    if (st == HARP_OK && !plan->prog[HARP_ALGO_GENERIC][0].ok && !plan->prog[HARP_ALGO_SPLIT][0].ok)
+      st = HARP_ERR_UNSUPPORTED;
   } catch (const std::bad_alloc &) {
     st = HARP_ERR_OOM;
   }
@@ -559,13 +653,14 @@ int64_t harp_plan_param_count(const harp_plan_t *plan) {
 
 int64_t harp_plan_param_bytes(const harp_plan_t *plan) {
   if (!plan) return -1;
-  const HostProgram *hp = select_program(plan, DIR_FWD, nullptr);
+  const HostProgram *hp = select_program(plan, DIR_FWD, (int64_t)1 << 20, nullptr);
   return hp ? hp->param_bytes : -1;
 }
 
 harp_status_t harp_plan_set_algo(harp_plan_t *plan, harp_algo_t algo) {
   if (!plan) return HARP_ERR_INVALID_ARG;
-  if (algo != HARP_ALGO_AUTO && algo != HARP_ALGO_GENERIC && algo != HARP_ALGO_FUSED)
+  if (algo != HARP_ALGO_AUTO && algo != HARP_ALGO_GENERIC && algo != HARP_ALGO_FUSED &&
+      algo != HARP_ALGO_SPLIT)
     return HARP_ERR_INVALID_ARG;
   if (algo != HARP_ALGO_AUTO && !(plan->prog[algo][0].ok && plan->prog[algo][1].ok))
     return HARP_ERR_UNSUPPORTED;
@@ -580,12 +675,11 @@ harp_status_t harp_plan_set_rows_per_tile(harp_plan_t *plan, int32_t rows) {
 }
 
 const char *harp_plan_kernel_name(const harp_plan_t *plan, int64_t n, harp_dtype_t dt) {
-  (void)n;
-  (void)dt;
   if (!plan) return "none";
   const char *nm = "none";
-  const HostProgram *hp = select_program(plan, DIR_FWD, &nm);
-  if (hp && dt == HARP_BF16 && pipe_supported(plan, hp->prog, nullptr, 8, nullptr, 8))
+  const HostProgram *hp = select_program(plan, DIR_FWD, n, &nm);
+  if (hp && hp->n_chunk == hp->prog.npass && dt == HARP_BF16 &&
+      pipe_supported(plan, hp->prog, nullptr, 8, nullptr, 8))
     return "pipe_radix2";
   return nm;
 }

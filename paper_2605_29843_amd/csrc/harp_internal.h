@@ -44,11 +44,19 @@ struct Program {
   PassDesc pass[kMaxPasses];
 };
 
+// Execution plan of a program.  Unsplit: every pass runs on the on-chip row tile (chunk == d).
+// Split ("four-step"): the passes on the low digits (product `chunk` <= 4096) run fused on chip
+// on contiguous chunks of every row; each pass on the digits above is streamed through device
+// memory with a float32 intermediate.  In the forward program the chunk passes come first
+// ([0, n_chunk)), in the transposed program last ([npass - n_chunk, npass)).
 struct HostProgram {
   Program prog{};
   const Program *dev = nullptr;  // device copy of prog (what the kernels read)
   int64_t param_bytes = 0;
   bool ok = false;  // false: some stage has no code path in this family
+  int32_t chunk = 0;      // coordinates per on-chip chunk (== d when unsplit)
+  int32_t n_chunk = 0;    // number of chunk-local passes
+  bool chunk_first = true;
 };
 
 enum Direction { DIR_FWD = 0, DIR_TRN = 1 };
@@ -65,7 +73,7 @@ struct harp_plan {
   int32_t m = 0;
   std::vector<int32_t> radices;
   std::vector<int64_t> strides;
-  harp::HostProgram prog[3][2];   // [algo (1 = generic, 2 = fused)][direction]
+  harp::HostProgram prog[4][2];   // [algo (1 = generic, 2 = fused, 3 = split)][direction]
   std::vector<void *> dev_allocs;
   int algo = HARP_ALGO_AUTO;
   int rows_override = 0;
@@ -77,15 +85,21 @@ struct harp_plan {
 namespace harp {
 
 // launchers (harp_kernels.hip)
-harp_status_t launch_tile_kernel(const harp_plan *plan, const Program *dev_prog, const void *X,
-                                 int64_t ldx, harp_dtype_t dt_in, void *Y, int64_t ldy,
-                                 harp_dtype_t dt_out, int64_t n, hipStream_t stream);
+// passes [p0, p1) of the program on row chunks of `chunk` coordinates (chunk == d: whole rows)
+harp_status_t launch_tile_kernel(const harp_plan *plan, const Program *dev_prog, int p0, int p1,
+                                 int chunk, const void *X, int64_t ldx, harp_dtype_t dt_in,
+                                 void *Y, int64_t ldy, harp_dtype_t dt_out, int64_t n,
+                                 hipStream_t stream);
+// one pass streamed through device memory (sub-tensor per thread, parameters in registers)
+harp_status_t launch_stream_pass(const harp_plan *plan, const HostProgram &hp, int p,
+                                 const void *X, int64_t ldx, harp_dtype_t dt_in, void *Y,
+                                 int64_t ldy, harp_dtype_t dt_out, int64_t n, hipStream_t stream);
 harp_status_t launch_transpose(const void *src, int64_t lds_, harp_dtype_t dt_src, void *dst,
                                int64_t ldd, harp_dtype_t dt_dst, int64_t rows, int64_t cols,
                                hipStream_t stream);
 harp_status_t launch_copy2d(const void *src, int64_t lds_, void *dst, int64_t ldd, int64_t rows,
                             int64_t cols, harp_dtype_t dt, hipStream_t stream);
-LaunchCfg choose_launch(const harp_plan *plan, int64_t n);
+LaunchCfg choose_launch(const harp_plan *plan, int64_t chunk, int64_t nrows);
 // row-pipelined radix-2 kernel (harp_pipe.hip)
 bool pipe_supported(const harp_plan *plan, const Program &prog, const void *X, int64_t ldx,
                     const void *Y, int64_t ldy);
@@ -93,7 +107,8 @@ harp_status_t launch_pipe_kernel(const harp_plan *plan, const HostProgram &hp, c
                                  int64_t ldx, void *Y, int64_t ldy, int64_t n, int rows_per_tile,
                                  hipStream_t stream);
 int choose_pipe_rows(const harp_plan *plan, int64_t n);
-const HostProgram *select_program(const harp_plan *plan, Direction dir, const char **name);
+const HostProgram *select_program(const harp_plan *plan, Direction dir, int64_t n,
+                                  const char **name);
 
 }  // namespace harp
 #endif

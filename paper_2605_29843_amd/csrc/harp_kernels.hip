@@ -87,11 +87,13 @@ __device__ __forceinline__ void store_one(uint16_t *p, float v) { *p = narrow_bf
 // steps, 2 values (a, b) per pair: x0 += a x1; x1 += b x0; x0 += a x1.  FORM 2: as FORM 1
 // but the K-th stage is dense (its 4-value pairs follow the (K-1) * P lifted values).
 template <int K, bool DESC, int FORM>
-__device__ __forceinline__ void pass_pow2(float *tile, int d, int nr, const PassDesc &pd, int tid,
-                                          int nt) {
+__device__ __forceinline__ void pass_pow2(float *tile, int d, int nr, const PassDesc &pd, int kch,
+                                          int tid, int nt) {
   constexpr int P = 1 << K;
   constexpr int NV = (FORM == 0) ? K * (P / 2) * 4 : (FORM == 1 ? K * P : (K + 1) * P);
-  const int nq = pd.nq, S = pd.S;
+  // the tile rows are chunk `kch` (d coordinates) of the full rows: nq sub-tensors here,
+  // numbered qoff .. qoff + nq - 1 among the pd.nq sub-tensors of a full row
+  const int nq = d / P, S = pd.S, nqg = pd.nq, qoff = kch * nq;
   const float *__restrict__ params = pd.params;
   int RG = 1;
   if (nq < nt) {
@@ -107,7 +109,7 @@ __device__ __forceinline__ void pass_pow2(float *tile, int d, int nr, const Pass
     }
     float prm[NV];
 #pragma unroll
-    for (int v = 0; v < NV; ++v) prm[v] = params[(size_t)v * nq + q];
+    for (int v = 0; v < NV; ++v) prm[v] = params[(size_t)v * nqg + qoff + q];
     const int hi = q / S, lo = q - hi * S;
     float *tb = tile + hi * P * S + lo;
     for (int row = rg; row < nr; row += RG) {
@@ -147,9 +149,9 @@ __device__ __forceinline__ void pass_pow2(float *tile, int d, int nr, const Pass
 
 // One stage of compile-time radix B (3..8): the whole block lives in registers.
 template <int B>
-__device__ __forceinline__ void pass_small(float *tile, int d, int nr, const PassDesc &pd, int tid,
-                                           int nt) {
-  const int nq = pd.nq, S = pd.S;
+__device__ __forceinline__ void pass_small(float *tile, int d, int nr, const PassDesc &pd, int kch,
+                                           int tid, int nt) {
+  const int nq = d / B, S = pd.S, nqg = pd.nq, qoff = kch * nq;
   const float *__restrict__ params = pd.params;
   int RG = 1;
   if (nq < nt) {
@@ -165,7 +167,7 @@ __device__ __forceinline__ void pass_small(float *tile, int d, int nr, const Pas
     }
     float prm[B * B];
 #pragma unroll
-    for (int v = 0; v < B * B; ++v) prm[v] = params[(size_t)v * nq + q];
+    for (int v = 0; v < B * B; ++v) prm[v] = params[(size_t)v * nqg + qoff + q];
     const int hi = q / S, lo = q - hi * S;
     float *tb = tile + hi * B * S + lo;
     for (int row = rg; row < nr; row += RG) {
@@ -190,8 +192,8 @@ __device__ __forceinline__ void pass_small(float *tile, int d, int nr, const Pas
 // coordinates are held in registers, the b*b parameters are streamed.
 template <int BMAX>
 __device__ __forceinline__ void pass_generic(float *tile, int d, int nr, const PassDesc &pd,
-                                             int tid, int nt) {
-  const int nq = pd.nq, S = pd.S, b = pd.b;
+                                             int kch, int tid, int nt) {
+  const int S = pd.S, b = pd.b, nq = d / b, nqg = pd.nq, qoff = kch * nq;
   const float *__restrict__ params = pd.params;
   const int items = nq * nr;
   for (int it = tid; it < items; it += nt) {
@@ -202,11 +204,11 @@ __device__ __forceinline__ void pass_generic(float *tile, int d, int nr, const P
 #pragma unroll
     for (int r = 0; r < BMAX; ++r) x[r] = (r < b) ? t[r * S] : 0.0f;
     for (int r2 = 0; r2 < b; ++r2) {
-      const float *pp = params + (size_t)r2 * nq + q;
+      const float *pp = params + (size_t)r2 * nqg + qoff + q;
       float acc = 0.0f;
 #pragma unroll
       for (int r = 0; r < BMAX; ++r)
-        if (r < b) acc = fmaf(x[r], pp[(size_t)r * b * nq], acc);
+        if (r < b) acc = fmaf(x[r], pp[(size_t)r * b * nqg], acc);
       t[r2 * S] = acc;
     }
   }
@@ -214,48 +216,48 @@ __device__ __forceinline__ void pass_generic(float *tile, int d, int nr, const P
 
 template <bool DESC, int FORM>
 __device__ __forceinline__ void dispatch_pow2(float *tile, int d, int nr, const PassDesc &pd,
-                                              int tid, int nt) {
+                                              int kch, int tid, int nt) {
   switch (pd.k) {
-    case 1: pass_pow2<1, DESC, FORM>(tile, d, nr, pd, tid, nt); break;
-    case 2: pass_pow2<2, DESC, FORM>(tile, d, nr, pd, tid, nt); break;
-    case 3: pass_pow2<3, DESC, FORM>(tile, d, nr, pd, tid, nt); break;
+    case 1: pass_pow2<1, DESC, FORM>(tile, d, nr, pd, kch, tid, nt); break;
+    case 2: pass_pow2<2, DESC, FORM>(tile, d, nr, pd, kch, tid, nt); break;
+    case 3: pass_pow2<3, DESC, FORM>(tile, d, nr, pd, kch, tid, nt); break;
     case 4:
-      if (FORM != 0) pass_pow2<4, DESC, (FORM == 0 ? 1 : FORM)>(tile, d, nr, pd, tid, nt);
+      if (FORM != 0) pass_pow2<4, DESC, (FORM == 0 ? 1 : FORM)>(tile, d, nr, pd, kch, tid, nt);
       break;
     default: break;
   }
 }
 
-__device__ __forceinline__ void run_pass(float *tile, int d, int nr, const PassDesc &pd, int tid,
-                                         int nt) {
+__device__ __forceinline__ void run_pass(float *tile, int d, int nr, const PassDesc &pd, int kch,
+                                         int tid, int nt) {
   switch (pd.kind) {
     case PASS_POW2_DENSE:
-      if (pd.desc) dispatch_pow2<true, 0>(tile, d, nr, pd, tid, nt);
-      else dispatch_pow2<false, 0>(tile, d, nr, pd, tid, nt);
+      if (pd.desc) dispatch_pow2<true, 0>(tile, d, nr, pd, kch, tid, nt);
+      else dispatch_pow2<false, 0>(tile, d, nr, pd, kch, tid, nt);
       break;
     case PASS_POW2_LIFT:
-      if (pd.desc) dispatch_pow2<true, 1>(tile, d, nr, pd, tid, nt);
-      else dispatch_pow2<false, 1>(tile, d, nr, pd, tid, nt);
+      if (pd.desc) dispatch_pow2<true, 1>(tile, d, nr, pd, kch, tid, nt);
+      else dispatch_pow2<false, 1>(tile, d, nr, pd, kch, tid, nt);
       break;
     case PASS_POW2_LIFT_LD:
-      if (pd.desc) dispatch_pow2<true, 2>(tile, d, nr, pd, tid, nt);
-      else dispatch_pow2<false, 2>(tile, d, nr, pd, tid, nt);
+      if (pd.desc) dispatch_pow2<true, 2>(tile, d, nr, pd, kch, tid, nt);
+      else dispatch_pow2<false, 2>(tile, d, nr, pd, kch, tid, nt);
       break;
     case PASS_SMALL:
       switch (pd.b) {
-        case 3: pass_small<3>(tile, d, nr, pd, tid, nt); break;
-        case 4: pass_small<4>(tile, d, nr, pd, tid, nt); break;
-        case 5: pass_small<5>(tile, d, nr, pd, tid, nt); break;
-        case 6: pass_small<6>(tile, d, nr, pd, tid, nt); break;
-        case 7: pass_small<7>(tile, d, nr, pd, tid, nt); break;
-        case 8: pass_small<8>(tile, d, nr, pd, tid, nt); break;
+        case 3: pass_small<3>(tile, d, nr, pd, kch, tid, nt); break;
+        case 4: pass_small<4>(tile, d, nr, pd, kch, tid, nt); break;
+        case 5: pass_small<5>(tile, d, nr, pd, kch, tid, nt); break;
+        case 6: pass_small<6>(tile, d, nr, pd, kch, tid, nt); break;
+        case 7: pass_small<7>(tile, d, nr, pd, kch, tid, nt); break;
+        case 8: pass_small<8>(tile, d, nr, pd, kch, tid, nt); break;
         default: break;
       }
       break;
     default:
-      if (pd.b <= 8) pass_generic<8>(tile, d, nr, pd, tid, nt);
-      else if (pd.b <= 16) pass_generic<16>(tile, d, nr, pd, tid, nt);
-      else pass_generic<64>(tile, d, nr, pd, tid, nt);
+      if (pd.b <= 8) pass_generic<8>(tile, d, nr, pd, kch, tid, nt);
+      else if (pd.b <= 16) pass_generic<16>(tile, d, nr, pd, kch, tid, nt);
+      else pass_generic<64>(tile, d, nr, pd, kch, tid, nt);
       break;
   }
 }
@@ -264,13 +266,20 @@ __device__ __forceinline__ void run_pass(float *tile, int d, int nr, const PassD
 template <typename TI, typename TO>
 __global__ __launch_bounds__(512) void harp_tile_kernel(const TI *__restrict__ X, int64_t ldx,
                                                          TO *__restrict__ Y, int64_t ldy, int64_t n,
-                                                         int d, int R, int vec_in, int vec_out,
-                                                         const Program *__restrict__ progp) {
+                                                         int d, int nchunk, int R, int vec_in,
+                                                         int vec_out,
+                                                         const Program *__restrict__ progp, int p0,
+                                                         int p1) {
+  // d = coordinates of the on-chip chunk; a row has nchunk of them (1: the whole row).
+  // Workgroup -> (chunk kch, tile of R rows); passes p0 .. p1-1 are local to a chunk.
   extern __shared__ float tile[];
   const int tid = threadIdx.x, nt = blockDim.x;
-  const int64_t row0 = (int64_t)blockIdx.x * R;
+  const int kch = (int)(blockIdx.x % (unsigned)nchunk);
+  const int64_t row0 = (int64_t)(blockIdx.x / (unsigned)nchunk) * R;
   const int nr = (int)((n - row0 < R) ? (n - row0) : R);
   const Program &prog = *progp;   // uniform address: fetched with scalar loads
+  X += (int64_t)kch * d;
+  Y += (int64_t)kch * d;
 
   // ---- load: device memory -> LDS (float32)
   if (vec_in) {
@@ -297,8 +306,8 @@ __global__ __launch_bounds__(512) void harp_tile_kernel(const TI *__restrict__ X
   __syncthreads();
 
   // ---- all stages on chip
-  for (int p = 0; p < prog.npass; ++p) {
-    run_pass(tile, d, nr, prog.pass[p], tid, nt);
+  for (int p = p0; p < p1; ++p) {
+    run_pass(tile, d, nr, prog.pass[p], kch, tid, nt);
     __syncthreads();
   }
 
@@ -325,6 +334,155 @@ __global__ __launch_bounds__(512) void harp_tile_kernel(const TI *__restrict__ X
       for (int i = tid; i < d; i += nt) {
         store_one(Y + (row0 + row) * ldy + i, tile[row * d + i]);
       }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// One pass streamed through device memory: a thread owns sub-tensor q of the row (consecutive
+// threads = consecutive q = consecutive addresses for every j), keeps the pass parameters in
+// registers and walks down the rows of its row block.  Used for the passes on the digits above
+// the on-chip chunk of a split program.  No LDS, no barrier.
+template <int K, bool DESC, int FORM>
+struct OpPow2 {
+  static constexpr int P = 1 << K;
+  static constexpr int NV = (FORM == 0) ? K * (P / 2) * 4 : (FORM == 1 ? K * P : (K + 1) * P);
+  __device__ static __forceinline__ void apply(float (&x)[P], const float (&prm)[NV]) {
+#pragma unroll
+    for (int e = 0; e < K; ++e) {
+      const int bp = DESC ? K - 1 - e : e;
+      const bool dense = (FORM == 0) || (FORM == 2 && e == K - 1);
+#pragma unroll
+      for (int p = 0; p < P / 2; ++p) {
+        const int j0 = ((p >> bp) << (bp + 1)) | (p & ((1 << bp) - 1));
+        const int j1 = j0 | (1 << bp);
+        float x0 = x[j0], x1 = x[j1];
+        if (!dense) {
+          const float a = prm[(e * (P / 2) + p) * 2 + 0], b = prm[(e * (P / 2) + p) * 2 + 1];
+          x0 = fmaf(a, x1, x0);
+          x1 = fmaf(b, x0, x1);
+          x0 = fmaf(a, x1, x0);
+          x[j0] = x0;
+          x[j1] = x1;
+        } else {
+          const int v0 = (FORM == 0) ? (e * (P / 2) + p) * 4 : (K - 1) * P + p * 4;
+          x[j0] = fmaf(x1, prm[v0 + 2], x0 * prm[v0 + 0]);
+          x[j1] = fmaf(x1, prm[v0 + 3], x0 * prm[v0 + 1]);
+        }
+      }
+    }
+  }
+};
+
+template <int B>
+struct OpSmall {
+  static constexpr int P = B;
+  static constexpr int NV = B * B;
+  __device__ static __forceinline__ void apply(float (&x)[P], const float (&prm)[NV]) {
+    float y[B];
+#pragma unroll
+    for (int r2 = 0; r2 < B; ++r2) {
+      float acc = x[0] * prm[r2];
+#pragma unroll
+      for (int r = 1; r < B; ++r) acc = fmaf(x[r], prm[r * B + r2], acc);
+      y[r2] = acc;
+    }
+#pragma unroll
+    for (int r = 0; r < B; ++r) x[r] = y[r];
+  }
+};
+
+__device__ __forceinline__ float stream_load(const void *p, int64_t i, int bf16) {
+  return bf16 ? widen_bf16(static_cast<const uint16_t *>(p)[i]) : static_cast<const float *>(p)[i];
+}
+__device__ __forceinline__ void stream_store(void *p, int64_t i, int bf16, float v) {
+  if (bf16) static_cast<uint16_t *>(p)[i] = narrow_bf16(v);
+  else static_cast<float *>(p)[i] = v;
+}
+
+template <class OP>
+__global__ __launch_bounds__(256) void harp_stream_kernel(const void *__restrict__ X, int64_t ldx,
+                                                          int in_bf16, void *__restrict__ Y,
+                                                          int64_t ldy, int out_bf16, int64_t n,
+                                                          int rows_per_block, PassDesc pd) {
+  constexpr int P = OP::P, NV = OP::NV;
+  const int nq = pd.nq, S = pd.S;
+  const int q = blockIdx.x * 256 + threadIdx.x;
+  if (q >= nq) return;
+  float prm[NV];
+#pragma unroll
+  for (int v = 0; v < NV; ++v) prm[v] = pd.params[(size_t)v * nq + q];
+  const int hi = q / S, lo = q - hi * S;
+  const int64_t base = (int64_t)hi * P * S + lo;
+  const int64_t r0 = (int64_t)blockIdx.y * rows_per_block;
+  const int64_t r1 = (r0 + rows_per_block < n) ? r0 + rows_per_block : n;
+  for (int64_t row = r0; row < r1; ++row) {
+    float x[P];
+#pragma unroll
+    for (int j = 0; j < P; ++j) x[j] = stream_load(X, row * ldx + base + (int64_t)j * S, in_bf16);
+    OP::apply(x, prm);
+#pragma unroll
+    for (int j = 0; j < P; ++j) stream_store(Y, row * ldy + base + (int64_t)j * S, out_bf16, x[j]);
+  }
+}
+
+// run-time radix (9..64): parameters are re-read for every row (slow, correctness path)
+template <int BMAX>
+__global__ __launch_bounds__(256) void harp_stream_generic_kernel(
+    const void *__restrict__ X, int64_t ldx, int in_bf16, void *__restrict__ Y, int64_t ldy,
+    int out_bf16, int64_t n, int rows_per_block, PassDesc pd) {
+  const int nq = pd.nq, S = pd.S, b = pd.b;
+  const int q = blockIdx.x * 256 + threadIdx.x;
+  if (q >= nq) return;
+  const int hi = q / S, lo = q - hi * S;
+  const int64_t base = (int64_t)hi * b * S + lo;
+  const int64_t r0 = (int64_t)blockIdx.y * rows_per_block;
+  const int64_t r1 = (r0 + rows_per_block < n) ? r0 + rows_per_block : n;
+  for (int64_t row = r0; row < r1; ++row) {
+    float x[BMAX];
+#pragma unroll
+    for (int r = 0; r < BMAX; ++r)
+      x[r] = (r < b) ? stream_load(X, row * ldx + base + (int64_t)r * S, in_bf16) : 0.0f;
+    for (int r2 = 0; r2 < b; ++r2) {
+      const float *pp = pd.params + (size_t)r2 * nq + q;
+      float acc = 0.0f;
+#pragma unroll
+      for (int r = 0; r < BMAX; ++r)
+        if (r < b) acc = fmaf(x[r], pp[(size_t)r * b * nq], acc);
+      stream_store(Y, row * ldy + base + (int64_t)r2 * S, out_bf16, acc);
+    }
+  }
+}
+
+template <class KERN>
+harp_status_t launch_stream_inst(KERN kern, const harp_plan *plan, const PassDesc &pd,
+                                 const void *X, int64_t ldx, int in_bf16, void *Y, int64_t ldy,
+                                 int out_bf16, int64_t n, hipStream_t stream) {
+  const unsigned gx = (unsigned)((pd.nq + 255) / 256);
+  // about 8 workgroups per compute unit, at least 4 rows each so parameters are reused
+  int64_t gy = ((int64_t)plan->num_cu * 8 + gx - 1) / gx;
+  if (gy > (n + 3) / 4) gy = (n + 3) / 4;
+  if (gy < 1) gy = 1;
+  if (gy > 65535) gy = 65535;
+  const int rpb = (int)((n + gy - 1) / gy);
+  gy = (n + rpb - 1) / rpb;
+  hipLaunchKernelGGL(kern, dim3(gx, (unsigned)gy), dim3(256), 0, stream, X, ldx, in_bf16, Y, ldy,
+                     out_bf16, n, rpb, pd);
+  return hipGetLastError() == hipSuccess ? HARP_OK : HARP_ERR_DEVICE;
+}
+
+template <bool DESC, int FORM>
+harp_status_t launch_stream_pow2(const harp_plan *plan, const PassDesc &pd, const void *X,
+                                 int64_t ldx, int ib, void *Y, int64_t ldy, int ob, int64_t n,
+                                 hipStream_t st) {
+  switch (pd.k) {
+    case 1: return launch_stream_inst(harp_stream_kernel<OpPow2<1, DESC, FORM>>, plan, pd, X, ldx, ib, Y, ldy, ob, n, st);
+    case 2: return launch_stream_inst(harp_stream_kernel<OpPow2<2, DESC, FORM>>, plan, pd, X, ldx, ib, Y, ldy, ob, n, st);
+    case 3: return launch_stream_inst(harp_stream_kernel<OpPow2<3, DESC, FORM>>, plan, pd, X, ldx, ib, Y, ldy, ob, n, st);
+    case 4:
+      if (FORM != 0)
+        return launch_stream_inst(harp_stream_kernel<OpPow2<4, DESC, (FORM == 0 ? 1 : FORM)>>, plan, pd, X, ldx, ib, Y, ldy, ob, n, st);
+      return HARP_ERR_UNSUPPORTED;
+    default: return HARP_ERR_UNSUPPORTED;
   }
 }
 
@@ -363,11 +521,13 @@ __global__ __launch_bounds__(256) void harp_copy2d_kernel(const T *__restrict__ 
 }
 
 template <typename TI, typename TO>
-harp_status_t launch_tile_typed(const harp_plan *plan, const Program *dprog, const void *X,
-                                int64_t ldx, void *Y, int64_t ldy, int64_t n, hipStream_t stream) {
-  const LaunchCfg cfg = choose_launch(plan, n);
+harp_status_t launch_tile_typed(const harp_plan *plan, const Program *dprog, int p0, int p1,
+                                int chunk, const void *X, int64_t ldx, void *Y, int64_t ldy,
+                                int64_t n, hipStream_t stream) {
+  const int d = chunk;
+  const int nchunk = (int)(plan->d / chunk);
+  const LaunchCfg cfg = choose_launch(plan, chunk, n * nchunk);
   if (cfg.rows_per_tile < 1) return HARP_ERR_UNSUPPORTED;
-  const int d = (int)plan->d;
   const size_t lds = (size_t)cfg.rows_per_tile * d * sizeof(float);
   auto kern = harp_tile_kernel<TI, TO>;
   static thread_local int attr_done_dev = -1;
@@ -381,11 +541,11 @@ harp_status_t launch_tile_typed(const harp_plan *plan, const Program *dprog, con
   constexpr int VI = IoTraits<TI>::kVec, VO = IoTraits<TO>::kVec;
   const int vec_in = (d % VI == 0) && (ldx % VI == 0) && ((uintptr_t)X % 16 == 0);
   const int vec_out = (d % VO == 0) && (ldy % VO == 0) && ((uintptr_t)Y % 16 == 0);
-  const int64_t tiles = (n + cfg.rows_per_tile - 1) / cfg.rows_per_tile;
+  const int64_t tiles = ((n + cfg.rows_per_tile - 1) / cfg.rows_per_tile) * nchunk;
   if (tiles > 0x7fffffff) return HARP_ERR_UNSUPPORTED;
   hipLaunchKernelGGL(kern, dim3((unsigned)tiles), dim3(cfg.threads), lds, stream,
-                     (const TI *)X, ldx, (TO *)Y, ldy, n, d, cfg.rows_per_tile, vec_in, vec_out,
-                     dprog);
+                     (const TI *)X, ldx, (TO *)Y, ldy, n, d, nchunk, cfg.rows_per_tile, vec_in,
+                     vec_out, dprog, p0, p1);
   return hipGetLastError() == hipSuccess ? HARP_OK : HARP_ERR_DEVICE;
 }
 
@@ -407,10 +567,10 @@ int env_int(const char *name, int dflt) {
 
 }  // namespace
 
-LaunchCfg choose_launch(const harp_plan *plan, int64_t n) {
+// d = coordinates per on-chip row (chunk), n = number of such rows in the launch
+LaunchCfg choose_launch(const harp_plan *plan, int64_t d, int64_t n) {
   LaunchCfg cfg{0, 256};
-  const int64_t d = plan->d;
-  const int rmax = (int)(plan->lds_bytes / (4 * d));
+  const int rmax = (int)(plan->lds_bytes / (4 * d));   // rows of the tile that fit in LDS
   if (rmax < 1) return cfg;
   int R = plan->rows_override > 0 ? plan->rows_override : (rmax < 8 ? rmax : 8);
   if (R > rmax) R = rmax;
@@ -432,17 +592,55 @@ LaunchCfg choose_launch(const harp_plan *plan, int64_t n) {
   return cfg;
 }
 
-harp_status_t launch_tile_kernel(const harp_plan *plan, const Program *prog, const void *X,
-                                 int64_t ldx, harp_dtype_t dt_in, void *Y, int64_t ldy,
-                                 harp_dtype_t dt_out, int64_t n, hipStream_t stream) {
+harp_status_t launch_tile_kernel(const harp_plan *plan, const Program *prog, int p0, int p1,
+                                 int chunk, const void *X, int64_t ldx, harp_dtype_t dt_in,
+                                 void *Y, int64_t ldy, harp_dtype_t dt_out, int64_t n,
+                                 hipStream_t stream) {
   if (n == 0) return HARP_OK;
+  if (chunk < 1 || plan->d % chunk != 0 || (int64_t)chunk * 4 > plan->lds_bytes)
+    return HARP_ERR_UNSUPPORTED;
   if (dt_in == HARP_F32 && dt_out == HARP_F32)
-    return launch_tile_typed<float, float>(plan, prog, X, ldx, Y, ldy, n, stream);
+    return launch_tile_typed<float, float>(plan, prog, p0, p1, chunk, X, ldx, Y, ldy, n, stream);
   if (dt_in == HARP_BF16 && dt_out == HARP_BF16)
-    return launch_tile_typed<uint16_t, uint16_t>(plan, prog, X, ldx, Y, ldy, n, stream);
+    return launch_tile_typed<uint16_t, uint16_t>(plan, prog, p0, p1, chunk, X, ldx, Y, ldy, n,
+                                                 stream);
   if (dt_in == HARP_BF16 && dt_out == HARP_F32)
-    return launch_tile_typed<uint16_t, float>(plan, prog, X, ldx, Y, ldy, n, stream);
-  return launch_tile_typed<float, uint16_t>(plan, prog, X, ldx, Y, ldy, n, stream);
+    return launch_tile_typed<uint16_t, float>(plan, prog, p0, p1, chunk, X, ldx, Y, ldy, n,
+                                              stream);
+  return launch_tile_typed<float, uint16_t>(plan, prog, p0, p1, chunk, X, ldx, Y, ldy, n, stream);
+}
+
+harp_status_t launch_stream_pass(const harp_plan *plan, const HostProgram &hp, int p,
+                                 const void *X, int64_t ldx, harp_dtype_t dt_in, void *Y,
+                                 int64_t ldy, harp_dtype_t dt_out, int64_t n, hipStream_t stream) {
+  if (n == 0) return HARP_OK;
+  const PassDesc &pd = hp.prog.pass[p];
+  const int ib = dt_in == HARP_BF16, ob = dt_out == HARP_BF16;
+  switch (pd.kind) {
+    case PASS_POW2_DENSE:
+      return pd.desc ? launch_stream_pow2<true, 0>(plan, pd, X, ldx, ib, Y, ldy, ob, n, stream)
+                     : launch_stream_pow2<false, 0>(plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
+    case PASS_POW2_LIFT:
+      return pd.desc ? launch_stream_pow2<true, 1>(plan, pd, X, ldx, ib, Y, ldy, ob, n, stream)
+                     : launch_stream_pow2<false, 1>(plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
+    case PASS_POW2_LIFT_LD:
+      return pd.desc ? launch_stream_pow2<true, 2>(plan, pd, X, ldx, ib, Y, ldy, ob, n, stream)
+                     : launch_stream_pow2<false, 2>(plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
+    case PASS_SMALL:
+      switch (pd.b) {
+        case 3: return launch_stream_inst(harp_stream_kernel<OpSmall<3>>, plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
+        case 4: return launch_stream_inst(harp_stream_kernel<OpSmall<4>>, plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
+        case 5: return launch_stream_inst(harp_stream_kernel<OpSmall<5>>, plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
+        case 6: return launch_stream_inst(harp_stream_kernel<OpSmall<6>>, plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
+        case 7: return launch_stream_inst(harp_stream_kernel<OpSmall<7>>, plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
+        case 8: return launch_stream_inst(harp_stream_kernel<OpSmall<8>>, plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
+        default: return HARP_ERR_UNSUPPORTED;
+      }
+    default:
+      if (pd.b <= 16)
+        return launch_stream_inst(harp_stream_generic_kernel<16>, plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
+      return launch_stream_inst(harp_stream_generic_kernel<64>, plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
+  }
 }
 
 harp_status_t launch_transpose(const void *src, int64_t lds_, harp_dtype_t dt_src, void *dst,

@@ -26,7 +26,7 @@ HARP_OK, HARP_ERR_INVALID_ARG, HARP_ERR_BAD_SCHEDULE, HARP_ERR_NOT_ORTHOGONAL, \
     HARP_ERR_UNSUPPORTED, HARP_ERR_OOM, HARP_ERR_DEVICE = range(7)
 HARP_F32, HARP_BF16 = 0, 1
 HARP_VALIDATE_ORTHO, HARP_BLOCKS_ON_DEVICE = 1, 2
-HARP_ALGO_AUTO, HARP_ALGO_GENERIC, HARP_ALGO_FUSED = 0, 1, 2
+HARP_ALGO_AUTO, HARP_ALGO_GENERIC, HARP_ALGO_FUSED, HARP_ALGO_SPLIT = 0, 1, 2, 3
 HARP_MAX_RADIX, HARP_MAX_STAGES = 64, 64
 
 if not os.path.exists(LIB_PATH):

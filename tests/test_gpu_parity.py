@@ -271,6 +271,33 @@ def test_paper_greedy_schedules(harp, d, radices):
     run_case(harp, d, radices, 21, "bf16", seed=d, act=gi.activations(21, d, config=3))
 
 
+# ------------------------------------------------------------------ split programs (d > 4096)
+SPLIT_CASES = [
+    (8192, [2] * 13, 70), (5120, [8, 8, 8, 5, 2], 33), (11008, [2] * 8 + [43], 40),
+    (11008, [8, 8, 4, 43], 9), (12288, [2] * 12 + [3], 65), (14336, [2] * 11 + [7], 130),
+    (28672, [2] * 12 + [7], 37), (16384, [4] * 7, 12), (24576, [2] * 13 + [3], 5),
+    (65536, [2] * 16, 6), (3 * 4096 * 5, [2] * 12 + [3, 5], 4),
+]
+
+
+@pytest.mark.parametrize("d,radices,n", SPLIT_CASES)
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_split_program_chunk_plus_stream(harp, d, radices, n, dtype):
+    """Low digits fused on chip per chunk, digits above streamed through a float32
+    intermediate; also the only path for rows that do not fit in LDS (d = 65536)."""
+    X = gi.activations(n, d, config=3, bf16=(dtype == "bf16"))
+    run_case(harp, d, radices, n, dtype, seed=d + n, algo=3, act=X)
+
+
+def test_split_is_refused_when_there_is_nothing_to_split(harp):
+    rng = np.random.default_rng(1)
+    plan = harp.Plan(4096, [2] * 12, gi.make_blocks(4096, [2] * 12, "orth", rng))
+    with pytest.raises(harp.HarpError) as e:
+        plan.set_algo(harp.HARP_ALGO_SPLIT)
+    assert e.value.status == harp.HARP_ERR_UNSUPPORTED
+    plan.destroy()
+
+
 # ------------------------------------------------------------------ config 4: decode regime
 @pytest.mark.parametrize("n", [1, 8, 32, 64])
 @pytest.mark.parametrize("d,radices", [(4096, [2] * 12), (12288, [2] * 12 + [3]), (14336, [2] * 11 + [7])])
