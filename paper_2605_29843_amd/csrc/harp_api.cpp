@@ -272,9 +272,9 @@ size_t esize(harp_dtype_t dt) { return dt == HARP_BF16 ? 2 : 4; }
 harp_status_t run_chunk_passes(const harp_plan_t *plan, const HostProgram &hp, int p0, int p1,
                                const void *X, int64_t ldx, harp_dtype_t dt_in, void *Y, int64_t ldy,
                                harp_dtype_t dt_out, int64_t n, hipStream_t stream) {
-  if (p0 == 0 && p1 == hp.prog.npass && hp.chunk == plan->d && dt_in == HARP_BF16 &&
-      dt_out == HARP_BF16 && pipe_supported(plan, hp.prog, X, ldx, Y, ldy))
-    return launch_pipe_kernel(plan, hp, X, ldx, Y, ldy, n, choose_pipe_rows(plan, n), stream);
+  if (pipe_supported(plan, hp.prog, p0, p1 - p0, hp.chunk, X, ldx, Y, ldy))
+    return launch_pipe_kernel(plan, hp, p0, hp.chunk, X, ldx, dt_in, Y, ldy, dt_out, n,
+                              choose_pipe_rows(plan, n, plan->d / hp.chunk, hp.chunk), stream);
   return launch_tile_kernel(plan, hp.dev, p0, p1, hp.chunk, X, ldx, dt_in, Y, ldy, dt_out, n,
                             stream);
 }
@@ -380,13 +380,17 @@ harp_status_t rotate_impl(const harp_plan_t *pu, const harp_plan_t *pv, Directio
 
 namespace harp {
 
-int choose_pipe_rows(const harp_plan *plan, int64_t n) {
+// Rows per tile of the pipelined kernel: a workgroup handles R rows of one chunk, so a launch
+// has nchunk * ceil(n / R) workgroups.  Aim at one workgroup slot per compute unit (two for
+// the 2048-coordinate kernel, whose workgroups are half as large) with tiles of <= 32 rows,
+// otherwise several waves of nearly equal tiles.
+int choose_pipe_rows(const harp_plan *plan, int64_t n, int64_t nchunk, int chunk) {
   if (plan->rows_override > 0) return plan->rows_override;
-  // one tile per compute unit while that keeps tiles at <= 32 rows; otherwise several waves
-  // of tiles of nearly equal size
-  const int64_t cu = plan->num_cu > 0 ? plan->num_cu : 256;
-  const int64_t waves = (n + cu * 32 - 1) / (cu * 32);
-  int64_t R = (n + cu * waves - 1) / (cu * waves);
+  const int64_t slots = (int64_t)(plan->num_cu > 0 ? plan->num_cu : 256) * (chunk <= 2048 ? 2 : 1);
+  const int64_t waves = (n * nchunk + slots * 32 - 1) / (slots * 32);
+  int64_t per_chunk = (slots * waves) / nchunk;   // workgroups available to one chunk index
+  if (per_chunk < 1) per_chunk = 1;
+  int64_t R = (n + per_chunk - 1) / per_chunk;
   if (R < 1) R = 1;
   return (int)R;
 }
@@ -678,9 +682,15 @@ const char *harp_plan_kernel_name(const harp_plan_t *plan, int64_t n, harp_dtype
   if (!plan) return "none";
   const char *nm = "none";
   const HostProgram *hp = select_program(plan, DIR_FWD, n, &nm);
-  if (hp && hp->n_chunk == hp->prog.npass && dt == HARP_BF16 &&
-      pipe_supported(plan, hp->prog, nullptr, 8, nullptr, 8))
+  (void)dt;
+  if (hp && hp->n_chunk == hp->prog.npass &&
+      pipe_supported(plan, hp->prog, 0, hp->prog.npass, hp->chunk, nullptr, 8, nullptr, 8))
     return "pipe_radix2";
+  if (hp && hp->n_chunk != hp->prog.npass) {
+    const int p0 = hp->chunk_first ? 0 : hp->prog.npass - hp->n_chunk;
+    if (pipe_supported(plan, hp->prog, p0, hp->n_chunk, hp->chunk, nullptr, 8, nullptr, 8))
+      return "split_pipe_stream";
+  }
   return nm;
 }
 

@@ -100,13 +100,14 @@ harp_status_t launch_transpose(const void *src, int64_t lds_, harp_dtype_t dt_sr
 harp_status_t launch_copy2d(const void *src, int64_t lds_, void *dst, int64_t ldd, int64_t rows,
                             int64_t cols, harp_dtype_t dt, hipStream_t stream);
 LaunchCfg choose_launch(const harp_plan *plan, int64_t chunk, int64_t nrows);
-// row-pipelined radix-2 kernel (harp_pipe.hip)
-bool pipe_supported(const harp_plan *plan, const Program &prog, const void *X, int64_t ldx,
-                    const void *Y, int64_t ldy);
-harp_status_t launch_pipe_kernel(const harp_plan *plan, const HostProgram &hp, const void *X,
-                                 int64_t ldx, void *Y, int64_t ldy, int64_t n, int rows_per_tile,
+// row-pipelined radix-2 kernel (harp_pipe.hip): passes [p0, p0+np) on chunks of `chunk`
+bool pipe_supported(const harp_plan *plan, const Program &prog, int p0, int np, int chunk,
+                    const void *X, int64_t ldx, const void *Y, int64_t ldy);
+harp_status_t launch_pipe_kernel(const harp_plan *plan, const HostProgram &hp, int p0, int chunk,
+                                 const void *X, int64_t ldx, harp_dtype_t dt_in, void *Y,
+                                 int64_t ldy, harp_dtype_t dt_out, int64_t n, int rows_per_tile,
                                  hipStream_t stream);
-int choose_pipe_rows(const harp_plan *plan, int64_t n);
+int choose_pipe_rows(const harp_plan *plan, int64_t n, int64_t nchunk, int chunk);
 const HostProgram *select_program(const harp_plan *plan, Direction dir, int64_t n,
                                   const char **name);
 

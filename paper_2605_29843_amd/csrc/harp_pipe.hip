@@ -1,5 +1,5 @@
-// Row-pipelined kernel for pure radix-2 chains of orthogonal blocks, d = 2^(K0+K1+K2) <= 4096,
-// bf16 I/O.  Every stage but the last is executed as three lifting steps, the last as a dense
+// Row-pipelined kernel for radix-2 chains of orthogonal blocks on rows, or contiguous row
+// chunks, of 2^(K0+K1+K2) = 2048 or 4096 coordinates; bf16 or float32 on either side.  Every stage but the last is executed as three lifting steps, the last as a dense
 // 2x2 that also carries all pending signs (see the plan builder), so the inner loop is fused
 // multiply-adds only.
 //
@@ -86,24 +86,127 @@ __device__ __forceinline__ void lift_stages(float (&x)[16], const float (&prm)[1
   }
 }
 
+// Element I/O of the first and last group.  NRAW = dwords a thread keeps per prefetched row.
+template <typename T, bool CONTIG>
+struct RowIo;
+
+template <>
+struct RowIo<uint16_t, true> {      // 16 contiguous bf16 (or 2 x 8): two 16-byte accesses
+  static constexpr int NRAW = 8;
+  template <class OFF>
+  __device__ static __forceinline__ void load(const uint16_t *xr, OFF off, uint32_t (&raw)[NRAW]) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const uint4 v = *reinterpret_cast<const uint4 *>(xr + off(8 * h));
+      raw[4 * h + 0] = v.x; raw[4 * h + 1] = v.y; raw[4 * h + 2] = v.z; raw[4 * h + 3] = v.w;
+    }
+  }
+  __device__ static __forceinline__ void unpack(const uint32_t (&raw)[NRAW], float (&x)[16]) {
+#pragma unroll
+    for (int m = 0; m < 8; ++m) {
+      x[2 * m] = __uint_as_float(raw[m] << 16);
+      x[2 * m + 1] = __uint_as_float(raw[m] & 0xffff0000u);
+    }
+  }
+  template <class OFF>
+  __device__ static __forceinline__ void store(uint16_t *yr, OFF off, const float (&x)[16]) {
+    uint32_t w[8];
+#pragma unroll
+    for (int m = 0; m < 8; ++m) w[m] = cvt_pk_bf16(x[2 * m], x[2 * m + 1]);
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+      *reinterpret_cast<uint4 *>(yr + off(8 * h)) =
+          make_uint4(w[4 * h], w[4 * h + 1], w[4 * h + 2], w[4 * h + 3]);
+  }
+};
+
+template <>
+struct RowIo<uint16_t, false> {     // 16 single bf16 at the pass stride
+  static constexpr int NRAW = 16;
+  template <class OFF>
+  __device__ static __forceinline__ void load(const uint16_t *xr, OFF off, uint32_t (&raw)[NRAW]) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) raw[e] = xr[off(e)];
+  }
+  __device__ static __forceinline__ void unpack(const uint32_t (&raw)[NRAW], float (&x)[16]) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) x[e] = __uint_as_float(raw[e] << 16);
+  }
+  template <class OFF>
+  __device__ static __forceinline__ void store(uint16_t *yr, OFF off, const float (&x)[16]) {
+#pragma unroll
+    for (int m = 0; m < 8; ++m) {
+      const uint32_t w = cvt_pk_bf16(x[2 * m], x[2 * m + 1]);
+      yr[off(2 * m)] = (uint16_t)(w & 0xffffu);
+      yr[off(2 * m + 1)] = (uint16_t)(w >> 16);
+    }
+  }
+};
+
+template <>
+struct RowIo<float, true> {         // 16 contiguous floats (or 2 x 8): four 16-byte accesses
+  static constexpr int NRAW = 16;
+  template <class OFF>
+  __device__ static __forceinline__ void load(const float *xr, OFF off, uint32_t (&raw)[NRAW]) {
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+      const uint4 v = *reinterpret_cast<const uint4 *>(xr + off(4 * h));
+      raw[4 * h + 0] = v.x; raw[4 * h + 1] = v.y; raw[4 * h + 2] = v.z; raw[4 * h + 3] = v.w;
+    }
+  }
+  __device__ static __forceinline__ void unpack(const uint32_t (&raw)[NRAW], float (&x)[16]) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) x[e] = __uint_as_float(raw[e]);
+  }
+  template <class OFF>
+  __device__ static __forceinline__ void store(float *yr, OFF off, const float (&x)[16]) {
+#pragma unroll
+    for (int h = 0; h < 4; ++h)
+      *reinterpret_cast<float4 *>(yr + off(4 * h)) =
+          make_float4(x[4 * h], x[4 * h + 1], x[4 * h + 2], x[4 * h + 3]);
+  }
+};
+
+template <>
+struct RowIo<float, false> {        // 16 single floats at the pass stride
+  static constexpr int NRAW = 16;
+  template <class OFF>
+  __device__ static __forceinline__ void load(const float *xr, OFF off, uint32_t (&raw)[NRAW]) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) raw[e] = __float_as_uint(xr[off(e)]);
+  }
+  __device__ static __forceinline__ void unpack(const uint32_t (&raw)[NRAW], float (&x)[16]) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) x[e] = __uint_as_float(raw[e]);
+  }
+  template <class OFF>
+  __device__ static __forceinline__ void store(float *yr, OFF off, const float (&x)[16]) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) yr[off(e)] = x[e];
+  }
+};
+
 // Body of one wave group.  ROLE 0 = first pass (reads device memory), 1 = middle, 2 = last
-// (writes device memory; its K-th stage is the program's last and is dense).  LOGS = log2 of
-// the stride of the pass's lowest digit; the pass with LOGS == 0 touches 16 contiguous
-// coordinates per thread (16-byte vector accesses), the others touch single coordinates.
-// Every group executes the same number of barriers (nr + 2, or nr + 4 with read-ahead).
-template <int K, int LOGS, bool DESC, int ROLE, int D>
-__device__ __forceinline__ void pipe_group(const PassDesc &pd, const int t, const float *rd_buf,
-                                           float *wr_buf, const uint16_t *__restrict__ X,
-                                           const int64_t ldx, uint16_t *__restrict__ Y,
-                                           const int64_t ldy, const int nr) {
-  constexpr bool LD = (ROLE == 2);
+// (writes device memory; with LD its K-th stage is the program's last and is dense).  LOGS =
+// log2 of the stride of the pass's lowest digit; the pass with LOGS == 0 touches contiguous
+// coordinates (16-byte vector accesses), the others touch single coordinates.  kch = index of
+// the chunk of D coordinates this workgroup works on (0 when D is the whole row).  Every group
+// executes the same number of barriers (nr + 2, or nr + 4 with read-ahead).
+template <typename TI, typename TO, int K, int LOGS, bool DESC, int ROLE, bool LD, int D>
+__device__ __forceinline__ void pipe_group(const PassDesc &pd, const int t, const int kch,
+                                           const float *rd_buf, float *wr_buf,
+                                           const TI *__restrict__ X, const int64_t ldx,
+                                           TO *__restrict__ Y, const int64_t ldy, const int nr) {
   constexpr int P = 1 << K, SPT = 16 / P, TG = D / 16, NV = (K + (LD ? 1 : 0)) * P;
   constexpr int ROWBUF = (D / 256) * 272;
   constexpr int S = 1 << LOGS;
   constexpr bool CONTIG = (LOGS == 0);
-  constexpr int NRAW = CONTIG ? 8 : 16;            // dwords of raw input per row and thread
-  constexpr int PF = CONTIG ? kPrefetch : kPrefetch - 1;
-  const int nq = pd.nq;
+  using In = RowIo<TI, CONTIG>;
+  using Out = RowIo<TO, CONTIG>;
+  constexpr int NRAW = In::NRAW;
+  constexpr int PF = (NRAW == 8) ? kPrefetch : kPrefetch - 1;
+  const unsigned nq = (unsigned)pd.nq;
+  const unsigned qoff = (unsigned)kch * (D / P);
   const float *__restrict__ params = pd.params;
 
   float prm[SPT * NV];
@@ -112,7 +215,7 @@ __device__ __forceinline__ void pipe_group(const PassDesc &pd, const int t, cons
   for (int u = 0; u < SPT; ++u) {
     const unsigned q = (unsigned)t + u * TG;
 #pragma unroll
-    for (int v = 0; v < NV; ++v) prm[u * NV + v] = params[(unsigned)(v * nq) + q];
+    for (int v = 0; v < NV; ++v) prm[u * NV + v] = params[(unsigned)v * nq + qoff + q];
     const unsigned hi = q >> LOGS, lo = q & (S - 1);
     base[u] = ((hi << K) << LOGS) | lo;
   }
@@ -121,32 +224,17 @@ __device__ __forceinline__ void pipe_group(const PassDesc &pd, const int t, cons
     const int u = e / P, j = e % P;
     return phys_index((int)(base[u] | ((unsigned)j << LOGS)));
   };
-  auto glb_off = [&](int e) -> unsigned {   // element offset inside a row
+  auto glb_off = [&](int e) -> unsigned {   // element offset inside the chunk
     const int u = e / P, j = e % P;
     return base[u] | ((unsigned)j << LOGS);
   };
 
-  // ---- ROLE 0: prefetch the first rows.  Contiguous side: 8 dwords of bf16 pairs per row;
-  // strided side: one bf16 per dword (widened when consumed).
+  // ---- ROLE 0: prefetch the first rows (raw dwords, converted when consumed)
   uint32_t pre[PF][NRAW];
-  auto issue_load = [&](int slot, int row) {
-    const uint16_t *xr = X + (int64_t)row * ldx;   // wave-uniform
-    if (CONTIG) {
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const uint4 v = *reinterpret_cast<const uint4 *>(xr + glb_off(8 * h));
-        pre[slot][4 * h + 0] = v.x; pre[slot][4 * h + 1] = v.y;
-        pre[slot][4 * h + 2] = v.z; pre[slot][4 * h + 3] = v.w;
-      }
-    } else {
-#pragma unroll
-      for (int e = 0; e < 16; ++e) pre[slot][e % NRAW] = xr[glb_off(e)];
-    }
-  };
   if (ROLE == 0) {
 #pragma unroll
     for (int s = 0; s < PF; ++s)
-      if (s < nr) issue_load(s, s);
+      if (s < nr) In::load(X + (int64_t)s * ldx, glb_off, pre[s]);
   }
 
   // The step loop is unrolled by UNR so that prefetch slots, buffer parities and the two
@@ -170,18 +258,8 @@ __device__ __forceinline__ void pipe_group(const PassDesc &pd, const int t, cons
       if (r_rd >= 0 && r_rd < nr) {
         if (ROLE == 0) {
           const int slot = s % PF;
-          if (CONTIG) {
-#pragma unroll
-            for (int m = 0; m < 8; ++m) {
-              const uint32_t w = pre[slot][m % NRAW];
-              xn[2 * m] = __uint_as_float(w << 16);
-              xn[2 * m + 1] = __uint_as_float(w & 0xffff0000u);
-            }
-          } else {
-#pragma unroll
-            for (int e = 0; e < 16; ++e) xn[e] = __uint_as_float(pre[slot][e % NRAW] << 16);
-          }
-          if (r_rd + PF < nr) issue_load(slot, r_rd + PF);
+          In::unpack(pre[slot], xn);
+          if (r_rd + PF < nr) In::load(X + (int64_t)(r_rd + PF) * ldx, glb_off, pre[slot]);
         } else {
           const float *b = rd_buf + ((s + 1) & 1) * ROWBUF;   // written in step k - 1
           if (CONTIG) {
@@ -199,23 +277,7 @@ __device__ __forceinline__ void pipe_group(const PassDesc &pd, const int t, cons
       if (r_cp >= 0 && r_cp < nr) {
         lift_stages<K, DESC, LD>(xc, prm);
         if (ROLE == 2) {
-          uint16_t *yr = Y + (int64_t)r_cp * ldy;   // wave-uniform
-          if (CONTIG) {
-            uint32_t w[8];
-#pragma unroll
-            for (int m = 0; m < 8; ++m) w[m] = cvt_pk_bf16(xc[2 * m], xc[2 * m + 1]);
-#pragma unroll
-            for (int h = 0; h < 2; ++h)
-              *reinterpret_cast<uint4 *>(yr + glb_off(8 * h)) =
-                  make_uint4(w[4 * h], w[4 * h + 1], w[4 * h + 2], w[4 * h + 3]);
-          } else {
-#pragma unroll
-            for (int m = 0; m < 8; ++m) {
-              const uint32_t w = cvt_pk_bf16(xc[2 * m], xc[2 * m + 1]);
-              yr[glb_off(2 * m)] = (uint16_t)(w & 0xffffu);
-              yr[glb_off(2 * m + 1)] = (uint16_t)(w >> 16);
-            }
-          }
+          Out::store(Y + (int64_t)r_cp * ldy, glb_off, xc);
         } else {
           float *b = wr_buf + (s & 1) * ROWBUF;               // read by the next group in step k + 1
           if (CONTIG) {
@@ -234,68 +296,123 @@ __device__ __forceinline__ void pipe_group(const PassDesc &pd, const int t, cons
   }
 }
 
-template <int K0, int K1, int K2, bool TRN>
-__global__ __launch_bounds__(3 << (K0 + K1 + K2 - 4)) void harp_pipe_bf16_kernel(
-    const uint16_t *__restrict__ X, int64_t ldx, uint16_t *__restrict__ Y, int64_t ldy, int64_t n,
-    int R, const Program *__restrict__ progp) {
+// Workgroup -> (chunk kch, tile of R rows).  nchunk = chunks per row (1: D is the whole row).
+// The three chunk-local passes are prog.pass[p0 .. p0+2].
+template <typename TI, typename TO, int K0, int K1, int K2, bool TRN, bool LD>
+__global__ __launch_bounds__(3 << (K0 + K1 + K2 - 4)) void harp_pipe_kernel(
+    const TI *__restrict__ X, int64_t ldx, TO *__restrict__ Y, int64_t ldy, int64_t n, int R,
+    int nchunk, const Program *__restrict__ progp, int p0) {
   constexpr int D = 1 << (K0 + K1 + K2), TG = D / 16, ROWBUF = (D / 256) * 272;
   __shared__ float bufA[2 * ROWBUF];
   __shared__ float bufB[2 * ROWBUF];
   const int g = __builtin_amdgcn_readfirstlane((int)threadIdx.x / TG);  // wave-uniform
   const int t = (int)threadIdx.x % TG;
-  const int64_t row0 = (int64_t)blockIdx.x * R;
+  const int kch = (int)(blockIdx.x % (unsigned)nchunk);
+  const int64_t row0 = (int64_t)(blockIdx.x / (unsigned)nchunk) * R;
   const int nr = (int)((n - row0 < R) ? (n - row0) : R);
   const Program &prog = *progp;
-  const uint16_t *Xt = X + row0 * ldx;
-  uint16_t *Yt = Y + row0 * ldy;
+  const TI *Xt = X + row0 * ldx + (int64_t)kch * D;
+  TO *Yt = Y + row0 * ldy + (int64_t)kch * D;
   // stride of each pass's lowest digit: ascending for apply, descending for apply_transpose
   constexpr int LS0 = TRN ? K1 + K2 : 0, LS1 = TRN ? K2 : K0, LS2 = TRN ? 0 : K0 + K1;
   if (g == 0)
-    pipe_group<K0, LS0, TRN, 0, D>(prog.pass[0], t, nullptr, bufA, Xt, ldx, Yt, ldy, nr);
+    pipe_group<TI, TO, K0, LS0, TRN, 0, false, D>(prog.pass[p0], t, kch, nullptr, bufA, Xt, ldx,
+                                                  Yt, ldy, nr);
   else if (g == 1)
-    pipe_group<K1, LS1, TRN, 1, D>(prog.pass[1], t, bufA, bufB, Xt, ldx, Yt, ldy, nr);
+    pipe_group<TI, TO, K1, LS1, TRN, 1, false, D>(prog.pass[p0 + 1], t, kch, bufA, bufB, Xt, ldx,
+                                                  Yt, ldy, nr);
   else
-    pipe_group<K2, LS2, TRN, 2, D>(prog.pass[2], t, bufB, nullptr, Xt, ldx, Yt, ldy, nr);
+    pipe_group<TI, TO, K2, LS2, TRN, 2, LD, D>(prog.pass[p0 + 2], t, kch, bufB, nullptr, Xt, ldx,
+                                               Yt, ldy, nr);
 }
 
-template <int K0, int K1, int K2, bool TRN>
-harp_status_t launch_pipe_inst(const Program *dprog, const void *X, int64_t ldx, void *Y,
-                               int64_t ldy, int64_t n, int R, hipStream_t stream) {
+struct PipeArgs {
+  const Program *dprog;
+  int p0;
+  const void *X;
+  int64_t ldx;
+  void *Y;
+  int64_t ldy;
+  int64_t n;
+  int R;
+  int nchunk;
+  hipStream_t stream;
+};
+
+template <typename TI, typename TO, int K0, int K1, int K2, bool TRN, bool LD>
+harp_status_t launch_pipe_inst(const PipeArgs &a) {
   constexpr int NT = 3 << (K0 + K1 + K2 - 4);
-  const int64_t tiles = (n + R - 1) / R;
+  const int64_t tiles = ((a.n + a.R - 1) / a.R) * a.nchunk;
   if (tiles > 0x7fffffff) return HARP_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL((harp_pipe_bf16_kernel<K0, K1, K2, TRN>), dim3((unsigned)tiles), dim3(NT), 0,
-                     stream, (const uint16_t *)X, ldx, (uint16_t *)Y, ldy, n, R, dprog);
+  hipLaunchKernelGGL((harp_pipe_kernel<TI, TO, K0, K1, K2, TRN, LD>), dim3((unsigned)tiles),
+                     dim3(NT), 0, a.stream, (const TI *)a.X, a.ldx, (TO *)a.Y, a.ldy, a.n, a.R,
+                     a.nchunk, a.dprog, a.p0);
   return hipGetLastError() == hipSuccess ? HARP_OK : HARP_ERR_DEVICE;
+}
+
+template <typename TI, typename TO, int K0, int K1, int K2>
+harp_status_t launch_pipe_dir(const PipeArgs &a, bool trn, bool ld) {
+  if (trn) return ld ? launch_pipe_inst<TI, TO, K0, K1, K2, true, true>(a) : HARP_ERR_UNSUPPORTED;
+  return ld ? launch_pipe_inst<TI, TO, K0, K1, K2, false, true>(a)
+            : launch_pipe_inst<TI, TO, K0, K1, K2, false, false>(a);
+}
+
+template <typename TI, typename TO>
+harp_status_t launch_pipe_io(const PipeArgs &a, int logd, bool trn, bool ld) {
+  if (logd == 12) return launch_pipe_dir<TI, TO, 4, 4, 4>(a, trn, ld);
+  if (logd == 11) return launch_pipe_dir<TI, TO, 4, 4, 3>(a, trn, ld);
+  return HARP_ERR_UNSUPPORTED;
+}
+
+// Decode the three passes [p0, p0+3): lifted radix-2 passes of (4,4,4) or (4,4,3) stages on a
+// chunk of 2^12 / 2^11 coordinates with the strides the kernel is compiled for.
+bool pipe_decode(const Program &pg, int p0, int np, int chunk, int *logd, bool *trn, bool *ld) {
+  if (np != 3) return false;
+  const PassDesc *ps = pg.pass + p0;
+  const int k0 = ps[0].k, k1 = ps[1].k, k2 = ps[2].k;
+  if (!(k0 == 4 && k1 == 4 && (k2 == 4 || k2 == 3))) return false;
+  if (chunk != (1 << (k0 + k1 + k2))) return false;
+  if (ps[0].kind != PASS_POW2_LIFT || ps[1].kind != PASS_POW2_LIFT) return false;
+  if (ps[2].kind != PASS_POW2_LIFT && ps[2].kind != PASS_POW2_LIFT_LD) return false;
+  *ld = ps[2].kind == PASS_POW2_LIFT_LD;
+  *trn = ps[0].desc != 0;
+  if (ps[1].desc != ps[0].desc || ps[2].desc != ps[0].desc) return false;
+  if (*trn && !*ld) return false;   // a transposed program always ends inside the chunk
+  const int s0 = *trn ? (1 << (k1 + k2)) : 1, s1 = *trn ? (1 << k2) : (1 << k0);
+  const int s2 = *trn ? 1 : (1 << (k0 + k1));
+  if (ps[0].S != s0 || ps[1].S != s1 || ps[2].S != s2) return false;
+  *logd = k0 + k1 + k2;
+  return true;
 }
 
 }  // namespace
 
-// True when the program is three rotation passes on a power-of-two d that this file has an
-// instantiation for, and the buffers allow 16-byte row accesses.
-bool pipe_supported(const harp_plan *plan, const Program &hp, const void *X, int64_t ldx,
-                    const void *Y, int64_t ldy) {
-  if (plan->d != 4096) return false;
+bool pipe_supported(const harp_plan *plan, const Program &pg, int p0, int np, int chunk,
+                    const void *X, int64_t ldx, const void *Y, int64_t ldy) {
   if (plan->algo == HARP_ALGO_GENERIC) return false;
-  if (hp.npass != 3) return false;
-  for (int p = 0; p < 3; ++p)
-    if (hp.pass[p].kind != (p == 2 ? PASS_POW2_LIFT_LD : PASS_POW2_LIFT) || hp.pass[p].k != 4)
-      return false;
-  // pass strides must be the ones the kernel is compiled for (1, 16, 256 or reversed)
-  const bool trn = hp.pass[0].desc != 0;
-  for (int p = 0; p < 3; ++p)
-    if (hp.pass[p].S != (1 << (4 * (trn ? 2 - p : p)))) return false;
+  int logd;
+  bool trn, ld;
+  if (!pipe_decode(pg, p0, np, chunk, &logd, &trn, &ld)) return false;
+  // 16-byte row accesses for either element type
   if ((ldx % 8) || (ldy % 8) || ((uintptr_t)X % 16) || ((uintptr_t)Y % 16)) return false;
   return true;
 }
 
-harp_status_t launch_pipe_kernel(const harp_plan *plan, const HostProgram &hp, const void *X,
-                                 int64_t ldx, void *Y, int64_t ldy, int64_t n, int R,
+harp_status_t launch_pipe_kernel(const harp_plan *plan, const HostProgram &hp, int p0, int chunk,
+                                 const void *X, int64_t ldx, harp_dtype_t dt_in, void *Y,
+                                 int64_t ldy, harp_dtype_t dt_out, int64_t n, int R,
                                  hipStream_t stream) {
-  (void)plan;
-  const bool trn = hp.prog.pass[0].desc != 0;
-  if (trn) return launch_pipe_inst<4, 4, 4, true>(hp.dev, X, ldx, Y, ldy, n, R, stream);
-  return launch_pipe_inst<4, 4, 4, false>(hp.dev, X, ldx, Y, ldy, n, R, stream);
+  int logd;
+  bool trn, ld;
+  if (!pipe_decode(hp.prog, p0, 3, chunk, &logd, &trn, &ld)) return HARP_ERR_UNSUPPORTED;
+  PipeArgs a{hp.dev, p0, X, ldx, Y, ldy, n, R, (int)(plan->d / chunk), stream};
+  if (dt_in == HARP_BF16 && dt_out == HARP_BF16)
+    return launch_pipe_io<uint16_t, uint16_t>(a, logd, trn, ld);
+  if (dt_in == HARP_BF16 && dt_out == HARP_F32)
+    return launch_pipe_io<uint16_t, float>(a, logd, trn, ld);
+  if (dt_in == HARP_F32 && dt_out == HARP_BF16)
+    return launch_pipe_io<float, uint16_t>(a, logd, trn, ld);
+  return launch_pipe_io<float, float>(a, logd, trn, ld);
 }
 
 }  // namespace harp

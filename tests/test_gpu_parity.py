@@ -202,6 +202,17 @@ def test_pipelined_radix2_kernel_4096(harp, n, rows, with_signs):
     assert set(out) == {"apply", "transpose"}
 
 
+@pytest.mark.parametrize("d,dtype,n", [(2048, "bf16", 45), (2048, "f32", 19), (4096, "f32", 33),
+                                       (2048, "bf16", 1), (4096, "f32", 2)])
+def test_pipelined_kernel_other_sizes_and_types(harp, d, dtype, n):
+    radices = [2] * int(np.log2(d))
+    rng = np.random.default_rng(d + n)
+    plan = harp.Plan(d, radices, gi.make_blocks(d, radices, "orth", rng))
+    assert plan.kernel_name() == "pipe_radix2"
+    plan.destroy()
+    run_case(harp, d, radices, n, dtype, seed=d + n)
+
+
 def test_pipelined_kernel_is_selected_and_in_place(harp):
     import torch
     d, radices, n = 4096, [2] * 12, 77
