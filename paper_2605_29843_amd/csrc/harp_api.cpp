@@ -294,7 +294,9 @@ harp_status_t apply_dir(const harp_plan_t *plan, Direction dir, const void *X, i
   // through a float32 intermediate Z.  Rows are processed in slabs so that Z stays small
   // (it is written by one launch and read by the next: cache resident).
   const int64_t d = plan->d;
-  int64_t slab = (int64_t)(64u << 20) / (d * 4);
+  const char *slab_env = getenv("HARP_SLAB_MB");
+  const int64_t slab_mb = (slab_env && *slab_env) ? atoi(slab_env) : 128;
+  int64_t slab = (slab_mb << 20) / (d * 4);
   if (slab >= 512) slab = (slab / 256) * 256;
   if (slab < 1) slab = 1;
   if (slab > n) slab = n;

@@ -23,6 +23,12 @@ namespace harp {
 
 namespace {
 
+int env_int(const char *name, int dflt) {
+  const char *s = getenv(name);
+  if (!s || !*s) return dflt;
+  return atoi(s);
+}
+
 // ------------------------------------------------------------------------------------------
 // element conversion
 __device__ __forceinline__ float widen_bf16(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
@@ -399,29 +405,75 @@ __device__ __forceinline__ void stream_store(void *p, int64_t i, int bf16, float
   else static_cast<float *>(p)[i] = v;
 }
 
-template <class OP>
+// V adjacent sub-tensors (lo, lo+1) per thread: 4-byte bf16 pairs / 8-byte float pairs.
+template <int V>
+__device__ __forceinline__ void stream_load_v(const void *p, int64_t i, int bf16, float (&v)[V]);
+template <>
+__device__ __forceinline__ void stream_load_v<1>(const void *p, int64_t i, int bf16, float (&v)[1]) {
+  v[0] = stream_load(p, i, bf16);
+}
+template <>
+__device__ __forceinline__ void stream_load_v<2>(const void *p, int64_t i, int bf16, float (&v)[2]) {
+  if (bf16) {
+    const uint32_t w = *reinterpret_cast<const uint32_t *>(static_cast<const uint16_t *>(p) + i);
+    v[0] = __uint_as_float(w << 16);
+    v[1] = __uint_as_float(w & 0xffff0000u);
+  } else {
+    const float2 f = *reinterpret_cast<const float2 *>(static_cast<const float *>(p) + i);
+    v[0] = f.x;
+    v[1] = f.y;
+  }
+}
+template <int V>
+__device__ __forceinline__ void stream_store_v(void *p, int64_t i, int bf16, const float (&v)[V]);
+template <>
+__device__ __forceinline__ void stream_store_v<1>(void *p, int64_t i, int bf16, const float (&v)[1]) {
+  stream_store(p, i, bf16, v[0]);
+}
+template <>
+__device__ __forceinline__ void stream_store_v<2>(void *p, int64_t i, int bf16, const float (&v)[2]) {
+  if (bf16)
+    *reinterpret_cast<uint32_t *>(static_cast<uint16_t *>(p) + i) = pack_bf16x2(v[0], v[1]);
+  else
+    *reinterpret_cast<float2 *>(static_cast<float *>(p) + i) = make_float2(v[0], v[1]);
+}
+
+template <class OP, int V>
 __global__ __launch_bounds__(256) void harp_stream_kernel(const void *__restrict__ X, int64_t ldx,
                                                           int in_bf16, void *__restrict__ Y,
                                                           int64_t ldy, int out_bf16, int64_t n,
                                                           int rows_per_block, PassDesc pd) {
   constexpr int P = OP::P, NV = OP::NV;
   const int nq = pd.nq, S = pd.S;
-  const int q = blockIdx.x * 256 + threadIdx.x;
+  const int q = (blockIdx.x * 256 + threadIdx.x) * V;   // first of V adjacent sub-tensors
   if (q >= nq) return;
-  float prm[NV];
+  float prm[V][NV];
 #pragma unroll
-  for (int v = 0; v < NV; ++v) prm[v] = pd.params[(size_t)v * nq + q];
+  for (int u = 0; u < V; ++u)
+#pragma unroll
+    for (int v = 0; v < NV; ++v) prm[u][v] = pd.params[(size_t)v * nq + q + u];
   const int hi = q / S, lo = q - hi * S;
   const int64_t base = (int64_t)hi * P * S + lo;
   const int64_t r0 = (int64_t)blockIdx.y * rows_per_block;
   const int64_t r1 = (r0 + rows_per_block < n) ? r0 + rows_per_block : n;
   for (int64_t row = r0; row < r1; ++row) {
-    float x[P];
+    float x[V][P];
 #pragma unroll
-    for (int j = 0; j < P; ++j) x[j] = stream_load(X, row * ldx + base + (int64_t)j * S, in_bf16);
-    OP::apply(x, prm);
+    for (int j = 0; j < P; ++j) {
+      float v[V];
+      stream_load_v<V>(X, row * ldx + base + (int64_t)j * S, in_bf16, v);
 #pragma unroll
-    for (int j = 0; j < P; ++j) stream_store(Y, row * ldy + base + (int64_t)j * S, out_bf16, x[j]);
+      for (int u = 0; u < V; ++u) x[u][j] = v[u];
+    }
+#pragma unroll
+    for (int u = 0; u < V; ++u) OP::apply(x[u], prm[u]);
+#pragma unroll
+    for (int j = 0; j < P; ++j) {
+      float v[V];
+#pragma unroll
+      for (int u = 0; u < V; ++u) v[u] = x[u][j];
+      stream_store_v<V>(Y, row * ldy + base + (int64_t)j * S, out_bf16, v);
+    }
   }
 }
 
@@ -454,13 +506,14 @@ __global__ __launch_bounds__(256) void harp_stream_generic_kernel(
 }
 
 template <class KERN>
-harp_status_t launch_stream_inst(KERN kern, const harp_plan *plan, const PassDesc &pd,
+harp_status_t launch_stream_grid(KERN kern, int items, const harp_plan *plan, const PassDesc &pd,
                                  const void *X, int64_t ldx, int in_bf16, void *Y, int64_t ldy,
                                  int out_bf16, int64_t n, hipStream_t stream) {
-  const unsigned gx = (unsigned)((pd.nq + 255) / 256);
-  // about 8 workgroups per compute unit, at least 4 rows each so parameters are reused
-  int64_t gy = ((int64_t)plan->num_cu * 8 + gx - 1) / gx;
-  if (gy > (n + 3) / 4) gy = (n + 3) / 4;
+  const unsigned gx = (unsigned)((items + 255) / 256);
+  // about 8 workgroups per compute unit (occupancy hides the load latency), >= 4 rows each
+  const int wgs = env_int("HARP_STREAM_WGS_PER_CU", 8), minrows = env_int("HARP_STREAM_MIN_ROWS", 4);
+  int64_t gy = ((int64_t)plan->num_cu * wgs + gx - 1) / gx;
+  if (gy > (n + minrows - 1) / minrows) gy = (n + minrows - 1) / minrows;
   if (gy < 1) gy = 1;
   if (gy > 65535) gy = 65535;
   const int rpb = (int)((n + gy - 1) / gy);
@@ -470,17 +523,33 @@ harp_status_t launch_stream_inst(KERN kern, const harp_plan *plan, const PassDes
   return hipGetLastError() == hipSuccess ? HARP_OK : HARP_ERR_DEVICE;
 }
 
+template <class OP>
+harp_status_t launch_stream_op(const harp_plan *plan, const PassDesc &pd, const void *X,
+                               int64_t ldx, int ib, void *Y, int64_t ldy, int ob, int64_t n,
+                               hipStream_t stream) {
+  // pairs of adjacent sub-tensors when everything is 8-byte aligned and the registers allow it
+  const bool pair = OP::NV <= 80 && (pd.S % 2 == 0) && (pd.nq % 2 == 0) && (ldx % 2 == 0) &&
+                    (ldy % 2 == 0) && ((uintptr_t)X % 8 == 0) && ((uintptr_t)Y % 8 == 0) &&
+                    env_int("HARP_STREAM_PAIR", 0);
+  if (pair)
+    return launch_stream_grid(harp_stream_kernel<OP, 2>, pd.nq / 2, plan, pd, X, ldx, ib, Y, ldy,
+                              ob, n, stream);
+  return launch_stream_grid(harp_stream_kernel<OP, 1>, pd.nq, plan, pd, X, ldx, ib, Y, ldy, ob, n,
+                            stream);
+}
+
 template <bool DESC, int FORM>
 harp_status_t launch_stream_pow2(const harp_plan *plan, const PassDesc &pd, const void *X,
                                  int64_t ldx, int ib, void *Y, int64_t ldy, int ob, int64_t n,
                                  hipStream_t st) {
   switch (pd.k) {
-    case 1: return launch_stream_inst(harp_stream_kernel<OpPow2<1, DESC, FORM>>, plan, pd, X, ldx, ib, Y, ldy, ob, n, st);
-    case 2: return launch_stream_inst(harp_stream_kernel<OpPow2<2, DESC, FORM>>, plan, pd, X, ldx, ib, Y, ldy, ob, n, st);
-    case 3: return launch_stream_inst(harp_stream_kernel<OpPow2<3, DESC, FORM>>, plan, pd, X, ldx, ib, Y, ldy, ob, n, st);
+    case 1: return launch_stream_op<OpPow2<1, DESC, FORM>>(plan, pd, X, ldx, ib, Y, ldy, ob, n, st);
+    case 2: return launch_stream_op<OpPow2<2, DESC, FORM>>(plan, pd, X, ldx, ib, Y, ldy, ob, n, st);
+    case 3: return launch_stream_op<OpPow2<3, DESC, FORM>>(plan, pd, X, ldx, ib, Y, ldy, ob, n, st);
     case 4:
       if (FORM != 0)
-        return launch_stream_inst(harp_stream_kernel<OpPow2<4, DESC, (FORM == 0 ? 1 : FORM)>>, plan, pd, X, ldx, ib, Y, ldy, ob, n, st);
+        return launch_stream_op<OpPow2<4, DESC, (FORM == 0 ? 1 : FORM)>>(plan, pd, X, ldx, ib, Y,
+                                                                        ldy, ob, n, st);
       return HARP_ERR_UNSUPPORTED;
     default: return HARP_ERR_UNSUPPORTED;
   }
@@ -559,11 +628,6 @@ harp_status_t launch_transpose_typed(const void *src, int64_t lds_, void *dst, i
   return hipGetLastError() == hipSuccess ? HARP_OK : HARP_ERR_DEVICE;
 }
 
-int env_int(const char *name, int dflt) {
-  const char *s = getenv(name);
-  if (!s || !*s) return dflt;
-  return atoi(s);
-}
 
 }  // namespace
 
@@ -572,7 +636,12 @@ LaunchCfg choose_launch(const harp_plan *plan, int64_t d, int64_t n) {
   LaunchCfg cfg{0, 256};
   const int rmax = (int)(plan->lds_bytes / (4 * d));   // rows of the tile that fit in LDS
   if (rmax < 1) return cfg;
-  int R = plan->rows_override > 0 ? plan->rows_override : (rmax < 8 ? rmax : 8);
+  // 8 rows per tile, more for short chunks so that the parameters a tile reads (they are as
+  // many as one row has coordinates, per stage) are reused by at least 16K coordinates
+  int rwant = (int)(16384 / d);
+  if (rwant < 8) rwant = 8;
+  if (rwant > 64) rwant = 64;
+  int R = plan->rows_override > 0 ? plan->rows_override : (rmax < rwant ? rmax : rwant);
   if (R > rmax) R = rmax;
   if (plan->rows_override == 0) {
     // keep every compute unit busy: shrink the tile while there are fewer tiles than CUs
@@ -628,18 +697,18 @@ harp_status_t launch_stream_pass(const harp_plan *plan, const HostProgram &hp, i
                      : launch_stream_pow2<false, 2>(plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
     case PASS_SMALL:
       switch (pd.b) {
-        case 3: return launch_stream_inst(harp_stream_kernel<OpSmall<3>>, plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
-        case 4: return launch_stream_inst(harp_stream_kernel<OpSmall<4>>, plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
-        case 5: return launch_stream_inst(harp_stream_kernel<OpSmall<5>>, plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
-        case 6: return launch_stream_inst(harp_stream_kernel<OpSmall<6>>, plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
-        case 7: return launch_stream_inst(harp_stream_kernel<OpSmall<7>>, plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
-        case 8: return launch_stream_inst(harp_stream_kernel<OpSmall<8>>, plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
+        case 3: return launch_stream_op<OpSmall<3>>(plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
+        case 4: return launch_stream_op<OpSmall<4>>(plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
+        case 5: return launch_stream_op<OpSmall<5>>(plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
+        case 6: return launch_stream_op<OpSmall<6>>(plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
+        case 7: return launch_stream_op<OpSmall<7>>(plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
+        case 8: return launch_stream_op<OpSmall<8>>(plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
         default: return HARP_ERR_UNSUPPORTED;
       }
     default:
       if (pd.b <= 16)
-        return launch_stream_inst(harp_stream_generic_kernel<16>, plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
-      return launch_stream_inst(harp_stream_generic_kernel<64>, plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
+        return launch_stream_grid(harp_stream_generic_kernel<16>, pd.nq, plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
+      return launch_stream_grid(harp_stream_generic_kernel<64>, pd.nq, plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
   }
 }
 
