@@ -126,9 +126,42 @@ int ilog2(int64_t v) {
 // Build the pass list and the packed parameter image for one (algo, direction).
 // Layout of the image: per pass, V rows of nq floats (value v of sub-tensor q at v*nq + q),
 // so that consecutive threads (consecutive q) read consecutive addresses.
+uint16_t bf16_rne(float f) {
+  uint32_t u;
+  memcpy(&u, &f, 4);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+float bf16_to_float(uint16_t h) {
+  const uint32_t u = (uint32_t)h << 16;
+  float f;
+  memcpy(&f, &u, 4);
+  return f;
+}
+
+// A radix-b block (9 <= b <= 64) as operand tiles of v_mfma_f32_16x16x16_bf16: KT = ceil(b/16);
+// for tile (kt, nt), half h (0: bf16(v), 1: bf16(v - hi)), lane l, i < 4 the value is
+// K[k = 16 kt + 4 (l / 16) + i][n = 16 nt + l % 16], zero outside the block.
+void pack_mfma_block(const float *K, int b, uint16_t *out) {
+  const int KT = (b + 15) / 16;
+  for (int kt = 0; kt < KT; ++kt)
+    for (int nt = 0; nt < KT; ++nt)
+      for (int l = 0; l < 64; ++l)
+        for (int i = 0; i < 4; ++i) {
+          const int k = 16 * kt + 4 * (l / 16) + i, n = 16 * nt + l % 16;
+          const float v = (k < b && n < b) ? K[k * b + n] : 0.0f;
+          const uint16_t hi = bf16_rne(v);
+          const uint16_t lo = bf16_rne(v - bf16_to_float(hi));
+          const size_t t = (size_t)(kt * KT + nt) * 2;
+          out[((t + 0) * 64 + l) * 4 + i] = hi;
+          out[((t + 1) * 64 + l) * 4 + i] = lo;
+        }
+}
+
 bool build_program(const harp_plan *plan, const std::vector<const float *> &blocks,
                    const int8_t *signs, int algo, Direction dir, HostProgram &hp,
-                   std::vector<float> &image, std::vector<size_t> &offsets) {
+                   std::vector<float> &image, std::vector<size_t> &offsets,
+                   std::vector<std::vector<uint16_t>> &aux) {
   const int m = plan->m;
   const int64_t d = plan->d;
   std::vector<StageEff> eff;
@@ -138,6 +171,7 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
   pg.npass = 0;
   image.clear();
   offsets.clear();
+  aux.assign(kMaxPasses, std::vector<uint16_t>());
 
   // Split programs: stages t < tb (product of their radices = chunk <= kChunkCap, maximal) are
   // chunk-local; passes never mix stages from both sides of tb.
@@ -248,6 +282,14 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
       for (int r = 0; r < b; ++r)
         for (int r2 = 0; r2 < b; ++r2)
           img[(size_t)(r * b + r2) * nq + q] = se.dense[((size_t)q * b + r) * b + r2];
+    if (fused && !small && b >= 9) {   // matrix-core operand tiles for the streamed large radix
+      const int KT = (b + 15) / 16;
+      const size_t per = (size_t)KT * KT * 2 * 64 * 4;
+      std::vector<uint16_t> &a = aux[pg.npass - 1];
+      a.resize(per * nq);
+      for (int64_t q = 0; q < nq; ++q)
+        pack_mfma_block(se.dense.data() + (size_t)q * b * b, b, a.data() + per * q);
+    }
     ++i;
   }
   hp.param_bytes = (int64_t)image.size() * 4;
@@ -307,6 +349,7 @@ harp_status_t apply_dir(const harp_plan_t *plan, Direction dir, const void *X, i
   }
   const int nstream = np - hp.n_chunk;
   const int nseg = nstream + 1;
+  const bool allow_narrow = (dt_in == HARP_BF16 || dt_out == HARP_BF16);
   harp_status_t st = HARP_OK;
   for (int64_t r0 = 0; r0 < n && st == HARP_OK; r0 += slab) {
     const int64_t nr = (n - r0 < slab) ? n - r0 : slab;
@@ -325,7 +368,8 @@ harp_status_t apply_dir(const harp_plan_t *plan, Direction dir, const void *X, i
                               dst_dt, nr, stream);
       } else {
         const int p = hp.chunk_first ? hp.n_chunk + (seg - 1) : seg;
-        st = launch_stream_pass(plan, hp, p, src, src_ld, src_dt, dst, dst_ld, dst_dt, nr, stream);
+        st = launch_stream_pass(plan, hp, p, src, src_ld, src_dt, dst, dst_ld, dst_dt, nr,
+                                allow_narrow, stream);
       }
       src = dst;
       src_ld = dst_ld;
@@ -525,7 +569,8 @@ harp_status_t harp_plan_create(harp_plan_t **out, int64_t d, int32_t m, const in
         HostProgram &hp = plan->prog[algo][dir];
         std::vector<float> image;
         std::vector<size_t> offsets;
-        if (!build_program(plan, blk, signs, algo, (Direction)dir, hp, image, offsets)) {
+        std::vector<std::vector<uint16_t>> aux;
+        if (!build_program(plan, blk, signs, algo, (Direction)dir, hp, image, offsets, aux)) {
           hp.ok = false;
           continue;
         }
@@ -544,7 +589,25 @@ harp_status_t harp_plan_create(harp_plan_t **out, int64_t d, int32_t m, const in
           st = HARP_ERR_DEVICE;
           break;
         }
-        for (int p = 0; p < hp.prog.npass; ++p) hp.prog.pass[p].params = dimg + offsets[p];
+        for (int p = 0; p < hp.prog.npass; ++p) {
+          hp.prog.pass[p].params = dimg + offsets[p];
+          hp.prog.pass[p].aux = nullptr;
+          if (!aux[p].empty() && st == HARP_OK) {
+            void *da = nullptr;
+            if (hipMalloc(&da, aux[p].size() * 2) != hipSuccess) {
+              st = HARP_ERR_OOM;
+              break;
+            }
+            plan->dev_allocs.push_back(da);
+            if (hipMemcpy(da, aux[p].data(), aux[p].size() * 2, hipMemcpyHostToDevice) !=
+                hipSuccess) {
+              st = HARP_ERR_DEVICE;
+              break;
+            }
+            hp.prog.pass[p].aux = da;
+          }
+        }
+        if (st != HARP_OK) break;
         Program *dprog = nullptr;
         if (hipMalloc((void **)&dprog, sizeof(Program)) != hipSuccess) {
           st = HARP_ERR_OOM;

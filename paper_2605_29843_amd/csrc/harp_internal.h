@@ -34,6 +34,7 @@ struct PassDesc {
   int32_t nq;    // d / P sub-tensors per row
   int32_t V;     // parameter values per sub-tensor
   const float *params;  // device, [V][nq]: value v of sub-tensor q at params[v * nq + q]
+  const void *aux;      // GENERIC, radix >= 9: the blocks as bf16 hi/lo MFMA operand tiles, or null
 };
 
 constexpr int kMaxPasses = HARP_MAX_STAGES;
@@ -91,9 +92,18 @@ harp_status_t launch_tile_kernel(const harp_plan *plan, const Program *dev_prog,
                                  void *Y, int64_t ldy, harp_dtype_t dt_out, int64_t n,
                                  hipStream_t stream);
 // one pass streamed through device memory (sub-tensor per thread, parameters in registers)
+// allow_narrow: the caller's element type is bf16, so large-radix passes may use the MFMA
+// kernel with bf16-split operands
 harp_status_t launch_stream_pass(const harp_plan *plan, const HostProgram &hp, int p,
                                  const void *X, int64_t ldx, harp_dtype_t dt_in, void *Y,
-                                 int64_t ldy, harp_dtype_t dt_out, int64_t n, hipStream_t stream);
+                                 int64_t ldy, harp_dtype_t dt_out, int64_t n, bool allow_narrow,
+                                 hipStream_t stream);
+// large-radix stage on the matrix cores (harp_mfma.hip)
+bool mfma_pass_supported(const PassDesc &pd, const void *X, int64_t ldx, const void *Y,
+                         int64_t ldy);
+harp_status_t launch_mfma_pass(const harp_plan *plan, const PassDesc &pd, const void *X,
+                               int64_t ldx, harp_dtype_t dt_in, void *Y, int64_t ldy,
+                               harp_dtype_t dt_out, int64_t n, hipStream_t stream);
 harp_status_t launch_transpose(const void *src, int64_t lds_, harp_dtype_t dt_src, void *dst,
                                int64_t ldd, harp_dtype_t dt_dst, int64_t rows, int64_t cols,
                                hipStream_t stream);

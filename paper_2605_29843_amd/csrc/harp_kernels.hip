@@ -681,9 +681,12 @@ harp_status_t launch_tile_kernel(const harp_plan *plan, const Program *prog, int
 
 harp_status_t launch_stream_pass(const harp_plan *plan, const HostProgram &hp, int p,
                                  const void *X, int64_t ldx, harp_dtype_t dt_in, void *Y,
-                                 int64_t ldy, harp_dtype_t dt_out, int64_t n, hipStream_t stream) {
+                                 int64_t ldy, harp_dtype_t dt_out, int64_t n, bool allow_narrow,
+                                 hipStream_t stream) {
   if (n == 0) return HARP_OK;
   const PassDesc &pd = hp.prog.pass[p];
+  if (allow_narrow && env_int("HARP_NO_MFMA", 0) == 0 && mfma_pass_supported(pd, X, ldx, Y, ldy))
+    return launch_mfma_pass(plan, pd, X, ldx, dt_in, Y, ldy, dt_out, n, stream);
   const int ib = dt_in == HARP_BF16, ob = dt_out == HARP_BF16;
   switch (pd.kind) {
     case PASS_POW2_DENSE:

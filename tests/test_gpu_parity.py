@@ -300,6 +300,21 @@ def test_split_program_chunk_plus_stream(harp, d, radices, n, dtype):
     run_case(harp, d, radices, n, dtype, seed=d + n, algo=3, act=X)
 
 
+MFMA_CASES = [
+    (11008, [2] * 8 + [43], 300), (22528, [2] * 11 + [11], 40), (4096 * 33, [2] * 12 + [33], 5),
+    (65536, [4] * 5 + [64], 18), (8192 * 2, [8, 8, 8, 2, 16], 33), (11008, [8, 8, 4, 43], 17),
+]
+
+
+@pytest.mark.parametrize("d,radices,n", MFMA_CASES)
+def test_large_radix_stage_on_matrix_cores(harp, d, radices, n):
+    """bf16 I/O: the streamed radix >= 9 stage runs on MFMA with bf16-split operands (apply:
+    float32 in, bf16 out; transpose: bf16 in, float32 out); ragged row counts."""
+    X = gi.activations(n, d, config=3)
+    out = run_case(harp, d, radices, n, "bf16", seed=d + n, algo=3, act=X)
+    assert max(out.values()) < 0.8      # error stays well inside the bf16 tolerance
+
+
 def test_split_is_refused_when_there_is_nothing_to_split(harp):
     rng = np.random.default_rng(1)
     plan = harp.Plan(4096, [2] * 12, gi.make_blocks(4096, [2] * 12, "orth", rng))
