@@ -25,8 +25,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-KERNEL_SYMBOL = {"pipe_radix2": "harp_pipe_bf16_kernel", "tile_fused": "harp_tile_kernel",
-                 "tile_generic": "harp_tile_kernel"}
+KERNEL_SYMBOL = {"pipe_radix2": "harp_pipe_kernel", "tile_fused": "harp_tile_kernel",
+                 "tile_generic": "harp_tile_kernel", "split_pipe_stream": "harp_pipe_kernel",
+                 "split_chunk_stream": "harp_tile_kernel"}
 
 
 def cpu_baseline(w, sample_rows: int):
