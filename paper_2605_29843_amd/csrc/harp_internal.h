@@ -117,6 +117,13 @@ harp_status_t launch_pipe_kernel(const harp_plan *plan, const HostProgram &hp, i
                                  const void *X, int64_t ldx, harp_dtype_t dt_in, void *Y,
                                  int64_t ldy, harp_dtype_t dt_out, int64_t n, int rows_per_tile,
                                  hipStream_t stream);
+// wave-local radix-2 kernel for chunks of 256 / 512 / 1024 coordinates (harp_pipe.hip)
+bool wave_supported(const harp_plan *plan, const Program &prog, int p0, int np, int chunk,
+                    const void *X, int64_t ldx, const void *Y, int64_t ldy);
+harp_status_t launch_wave_kernel(const harp_plan *plan, const HostProgram &hp, int p0, int np,
+                                 int chunk, const void *X, int64_t ldx, harp_dtype_t dt_in,
+                                 void *Y, int64_t ldy, harp_dtype_t dt_out, int64_t n,
+                                 hipStream_t stream);
 int choose_pipe_rows(const harp_plan *plan, int64_t n, int64_t nchunk, int chunk);
 const HostProgram *select_program(const harp_plan *plan, Direction dir, int64_t n,
                                   const char **name);

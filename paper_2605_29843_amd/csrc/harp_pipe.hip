@@ -326,6 +326,197 @@ __global__ __launch_bounds__(3 << (K0 + K1 + K2 - 4)) void harp_pipe_kernel(
                                                Yt, ldy, nr);
 }
 
+// ------------------------------------------------------------------------------------------
+// Wave-local kernel for radix-2 chains on chunks of 256 / 512 / 1024 coordinates.
+//
+// One wave (a workgroup of 64 threads) owns a window of 1024 consecutive coordinates of the row
+// -- 4, 2 or 1 whole chunks -- and walks down R rows.  A thread keeps the parameters of ALL
+// passes of its 16 coordinates in registers (128..176 values), so they are read once per
+// workgroup; a row is loaded with 16-byte accesses (next row prefetched), goes through the 2 or
+// 3 passes with an LDS exchange between them (private to the wave: no other wave waits), and
+// is stored with 16-byte accesses.  Used for the 2^8 part of d = 11008 = 2^8 * 43 and for
+// short rows.
+template <int K, int LOGS, bool LD>
+struct WavePass {
+  static constexpr int P = 1 << K, SPT = 16 / P, NV = (K + (LD ? 1 : 0)) * P, S = 1 << LOGS;
+  float prm[SPT * NV];
+  unsigned base[SPT];
+  // window kg of the row; sub-tensors kg * (1024 / P) + t + 64 u of the row's pd.nq
+  __device__ __forceinline__ void init(const PassDesc &pd, int t, int kg, bool with_params) {
+    const unsigned nq = (unsigned)pd.nq;
+#pragma unroll
+    for (int u = 0; u < SPT; ++u) {
+      const unsigned ql = (unsigned)t + 64u * u;
+      const unsigned qg = (unsigned)kg * (1024 / P) + ql;
+      const bool ok = with_params && qg < nq;
+#pragma unroll
+      for (int v = 0; v < NV; ++v) prm[u * NV + v] = ok ? pd.params[(unsigned)v * nq + qg] : 0.0f;
+      const unsigned hi = ql >> LOGS, lo = ql & (S - 1);
+      base[u] = ((hi << K) << LOGS) | lo;
+    }
+  }
+  __device__ __forceinline__ unsigned coord(int e) const {
+    return base[e / P] | ((unsigned)(e % P) << LOGS);
+  }
+};
+
+// x leaves layout A and comes back in layout B through the wave's LDS buffer
+template <class PA, class PB>
+__device__ __forceinline__ void wave_exchange(float (&x)[16], float *buf, const PA &a, const PB &b) {
+  if (PA::S == 1 && PA::P >= 4) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+      *reinterpret_cast<float4 *>(buf + phys_index((int)a.coord(4 * c))) =
+          make_float4(x[4 * c], x[4 * c + 1], x[4 * c + 2], x[4 * c + 3]);
+  } else {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) buf[phys_index((int)a.coord(e))] = x[e];
+  }
+  __syncthreads();
+  if (PB::S == 1 && PB::P >= 4) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const float4 f = *reinterpret_cast<const float4 *>(buf + phys_index((int)b.coord(4 * c)));
+      x[4 * c] = f.x; x[4 * c + 1] = f.y; x[4 * c + 2] = f.z; x[4 * c + 3] = f.w;
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) x[e] = buf[phys_index((int)b.coord(e))];
+  }
+  __syncthreads();
+}
+
+template <typename TI, typename TO, int K0, int K1, int K2, bool TRN, bool LD>
+__global__ __launch_bounds__(64) void harp_wave_kernel(const TI *__restrict__ X, int64_t ldx,
+                                                       TO *__restrict__ Y, int64_t ldy, int64_t n,
+                                                       int R, int ngroups, int d,
+                                                       const Program *__restrict__ progp, int p0) {
+  constexpr bool THREE = (K2 != 0);
+  constexpr int LS0 = TRN ? K1 + K2 : 0, LS1 = TRN ? K2 : K0, LS2 = TRN ? 0 : K0 + K1;
+  __shared__ float buf[(1024 / 256) * 272];
+  const int t = threadIdx.x;
+  const int kg = (int)(blockIdx.x % (unsigned)ngroups);
+  const int64_t row0 = (int64_t)(blockIdx.x / (unsigned)ngroups) * R;
+  const int nr = (int)((n - row0 < R) ? (n - row0) : R);
+  const int w0 = kg * 1024;
+  const int valid = (d - w0 < 1024) ? d - w0 : 1024;   // coordinates of the window inside the row
+  const Program &prog = *progp;
+
+  WavePass<K0, LS0, (!THREE && false)> pa;                // first pass is never the dense-ended one
+  WavePass<K1, LS1, (!THREE && LD)> pb;
+  WavePass<(THREE ? K2 : 1), (THREE ? LS2 : 0), (THREE && LD)> pc;
+  WavePass<4, 0, false> io;                               // 16 contiguous coordinates per thread
+  pa.init(prog.pass[p0], t, kg, true);
+  pb.init(prog.pass[p0 + 1], t, kg, true);
+  if (THREE) pc.init(prog.pass[p0 + 2], t, kg, true);
+  io.init(prog.pass[p0], t, kg, false);
+  const bool active = 16 * t < valid;
+  auto goff = [&](int e) -> unsigned { return (unsigned)w0 + io.coord(e); };
+
+  using In = RowIo<TI, true>;
+  using Out = RowIo<TO, true>;
+  constexpr int NRAW = In::NRAW;
+  uint32_t pre[2][NRAW];
+#pragma unroll
+  for (int s = 0; s < 2; ++s) {
+#pragma unroll
+    for (int m = 0; m < NRAW; ++m) pre[s][m] = 0u;
+    if (active && s < nr) In::load(X + (row0 + s) * ldx, goff, pre[s]);
+  }
+
+  for (int r0 = 0; r0 < nr; r0 += 2) {
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      const int r = r0 + s;
+      if (r >= nr) break;
+      float x[16];
+      In::unpack(pre[s], x);
+      if (active && r + 2 < nr) In::load(X + (row0 + r + 2) * ldx, goff, pre[s]);
+
+      if (!(K0 == 4 && LS0 == 0)) wave_exchange(x, buf, io, pa);
+      lift_stages<K0, TRN, false>(x, pa.prm);
+      wave_exchange(x, buf, pa, pb);
+      lift_stages<K1, TRN, (!THREE && LD)>(x, pb.prm);
+      if (THREE) {
+        wave_exchange(x, buf, pb, pc);
+        lift_stages<(THREE ? K2 : 1), TRN, (THREE && LD)>(x, pc.prm);
+        if (!(K2 == 4 && LS2 == 0)) wave_exchange(x, buf, pc, io);
+      } else {
+        if (!(K1 == 4 && LS1 == 0)) wave_exchange(x, buf, pb, io);
+      }
+      if (active) Out::store(Y + (row0 + r) * ldy, goff, x);
+    }
+  }
+}
+
+struct WaveArgs {
+  const Program *dprog;
+  int p0;
+  const void *X;
+  int64_t ldx;
+  void *Y;
+  int64_t ldy;
+  int64_t n;
+  int R;
+  int d;
+  hipStream_t stream;
+};
+
+template <typename TI, typename TO, int K0, int K1, int K2, bool TRN, bool LD>
+harp_status_t launch_wave_inst(const WaveArgs &a) {
+  const int ngroups = (a.d + 1023) / 1024;
+  const int64_t tiles = ((a.n + a.R - 1) / a.R) * ngroups;
+  if (tiles > 0x7fffffff) return HARP_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL((harp_wave_kernel<TI, TO, K0, K1, K2, TRN, LD>), dim3((unsigned)tiles),
+                     dim3(64), 0, a.stream, (const TI *)a.X, a.ldx, (TO *)a.Y, a.ldy, a.n, a.R,
+                     ngroups, a.d, a.dprog, a.p0);
+  return hipGetLastError() == hipSuccess ? HARP_OK : HARP_ERR_DEVICE;
+}
+
+template <typename TI, typename TO, int K0, int K1, int K2>
+harp_status_t launch_wave_dir(const WaveArgs &a, bool trn, bool ld) {
+  if (trn) return ld ? launch_wave_inst<TI, TO, K0, K1, K2, true, true>(a) : HARP_ERR_UNSUPPORTED;
+  return ld ? launch_wave_inst<TI, TO, K0, K1, K2, false, true>(a)
+            : launch_wave_inst<TI, TO, K0, K1, K2, false, false>(a);
+}
+
+template <typename TI, typename TO>
+harp_status_t launch_wave_io(const WaveArgs &a, int logc, bool trn, bool ld) {
+  if (logc == 8) return launch_wave_dir<TI, TO, 4, 4, 0>(a, trn, ld);
+  if (logc == 9) return launch_wave_dir<TI, TO, 3, 3, 3>(a, trn, ld);
+  if (logc == 10) return launch_wave_dir<TI, TO, 4, 3, 3>(a, trn, ld);
+  return HARP_ERR_UNSUPPORTED;
+}
+
+// Passes [p0, p0+np) must be the lifted radix-2 passes (4,4), (3,3,3) or (4,3,3) of a chunk of
+// 256 / 512 / 1024 coordinates with the strides the kernel is compiled for.
+bool wave_decode(const Program &pg, int p0, int np, int chunk, int *logc, bool *trn, bool *ld) {
+  if (np != 2 && np != 3) return false;
+  const PassDesc *ps = pg.pass + p0;
+  const int k0 = ps[0].k, k1 = ps[1].k, k2 = (np == 3) ? ps[2].k : 0;
+  const int lc = k0 + k1 + k2;
+  if (!((lc == 8 && k0 == 4 && k1 == 4 && np == 2) || (lc == 9 && k0 == 3 && k1 == 3 && k2 == 3) ||
+        (lc == 10 && k0 == 4 && k1 == 3 && k2 == 3)))
+    return false;
+  if (chunk != (1 << lc)) return false;
+  for (int p = 0; p < np - 1; ++p)
+    if (ps[p].kind != PASS_POW2_LIFT) return false;
+  if (ps[np - 1].kind != PASS_POW2_LIFT && ps[np - 1].kind != PASS_POW2_LIFT_LD) return false;
+  *ld = ps[np - 1].kind == PASS_POW2_LIFT_LD;
+  *trn = ps[0].desc != 0;
+  for (int p = 1; p < np; ++p)
+    if (ps[p].desc != ps[0].desc) return false;
+  if (*trn && !*ld) return false;
+  int below = 0;   // log2 stride expected for each pass
+  for (int p = 0; p < np; ++p) {
+    const int pe = *trn ? np - 1 - p : p;   // passes from the lowest digits upwards
+    if (ps[pe].S != (1 << below)) return false;
+    below += ps[pe].k;
+  }
+  *logc = lc;
+  return true;
+}
+
 struct PipeArgs {
   const Program *dprog;
   int p0;
@@ -396,6 +587,41 @@ bool pipe_supported(const harp_plan *plan, const Program &pg, int p0, int np, in
   // 16-byte row accesses for either element type
   if ((ldx % 8) || (ldy % 8) || ((uintptr_t)X % 16) || ((uintptr_t)Y % 16)) return false;
   return true;
+}
+
+bool wave_supported(const harp_plan *plan, const Program &pg, int p0, int np, int chunk,
+                    const void *X, int64_t ldx, const void *Y, int64_t ldy) {
+  if (plan->algo == HARP_ALGO_GENERIC) return false;
+  int logc;
+  bool trn, ld;
+  if (!wave_decode(pg, p0, np, chunk, &logc, &trn, &ld)) return false;
+  if ((ldx % 8) || (ldy % 8) || ((uintptr_t)X % 16) || ((uintptr_t)Y % 16)) return false;
+  return true;
+}
+
+harp_status_t launch_wave_kernel(const harp_plan *plan, const HostProgram &hp, int p0, int np,
+                                 int chunk, const void *X, int64_t ldx, harp_dtype_t dt_in,
+                                 void *Y, int64_t ldy, harp_dtype_t dt_out, int64_t n,
+                                 hipStream_t stream) {
+  int logc;
+  bool trn, ld;
+  if (!wave_decode(hp.prog, p0, np, chunk, &logc, &trn, &ld)) return HARP_ERR_UNSUPPORTED;
+  const int64_t ngroups = (plan->d + 1023) / 1024;
+  // about 12 waves per compute unit; at least 4 rows per wave so its parameters are reused
+  int64_t R = plan->rows_override > 0 ? plan->rows_override
+                                      : (n * ngroups + (int64_t)plan->num_cu * 12 - 1) /
+                                            ((int64_t)plan->num_cu * 12);
+  if (plan->rows_override <= 0 && R < 4) R = 4;
+  if (R > n) R = n;
+  if (R < 1) R = 1;
+  WaveArgs a{hp.dev, p0, X, ldx, Y, ldy, n, (int)R, (int)plan->d, stream};
+  if (dt_in == HARP_BF16 && dt_out == HARP_BF16)
+    return launch_wave_io<uint16_t, uint16_t>(a, logc, trn, ld);
+  if (dt_in == HARP_BF16 && dt_out == HARP_F32)
+    return launch_wave_io<uint16_t, float>(a, logc, trn, ld);
+  if (dt_in == HARP_F32 && dt_out == HARP_BF16)
+    return launch_wave_io<float, uint16_t>(a, logc, trn, ld);
+  return launch_wave_io<float, float>(a, logc, trn, ld);
 }
 
 harp_status_t launch_pipe_kernel(const harp_plan *plan, const HostProgram &hp, int p0, int chunk,
