@@ -1,7 +1,9 @@
 // Row-pipelined kernel for radix-2 chains of orthogonal blocks on rows, or contiguous row
-// chunks, of 2^(K0+K1+K2) = 2048 or 4096 coordinates; bf16 or float32 on either side.  Every stage but the last is executed as three lifting steps, the last as a dense
-// 2x2 that also carries all pending signs (see the plan builder), so the inner loop is fused
-// multiply-adds only.
+// chunks, of 2^(K0+K1+K2) = 2048 or 4096 coordinates; bf16 or float32 on either side.  Every
+// stage but the last is executed as three lifting steps, the last as a dense 2x2 that also
+// carries all pending signs (see the plan builder), so the inner loop is fused multiply-adds
+// only.  The second kernel of this file covers chunks of 256 / 512 / 1024 coordinates with one
+// wave per window (see harp_wave_kernel below).
 //
 // The 10..12 stages are cut into three passes of K0, K1, K2 consecutive stages.  A workgroup
 // has three wave groups of d/16 threads; group g executes pass g and nothing else, so a thread
