@@ -26,13 +26,26 @@ namespace {
 // signs into the rows of its blocks.  The last stage of a program is always dense and also
 // takes the processor's output signs (transposed direction) on its columns, so no kernel
 // ever multiplies by a sign vector.
+//
+// Cheaper still, and the form tried first: any 2x2 block M = [[m00, m01], [m10, m11]] with a
+// non-zero diagonal factors as
+//     y0 = m00 (x0 + (m10 / m00) x1),     y1 = m11 (x1 + (m01 / m11) x0),
+// two independent fused multiply-adds per pair; the output scales m00, m11 are not applied
+// but pushed, like the signs above, onto the rows of whichever later stage touches the
+// coordinate (so a coordinate travels divided by a known scale until a dense stage - at the
+// latest the program's last - multiplies it back in).  The arithmetic is that of the dense
+// product carried out in scaled units, so rounding errors stay relative to the same
+// quantities.  A program takes this form only if every pending scale stays within
+// [2^-60, 2^60] (no overflow for |x| < 2^64); otherwise it falls back to lifting.
+enum StageForm { FORM_DENSE = 0, FORM_LIFT = 1, FORM_SCALED = 2 };
+
 struct StageEff {
   int t = 0;
   int32_t b = 0;
   int64_t s = 0;
-  bool lifted = false;
-  std::vector<float> dense;   // [D][b][b], E'[c][r][r2]            (when !lifted)
-  std::vector<float> la, lb;  // [D] lifting coefficients             (when lifted)
+  int form = FORM_DENSE;
+  std::vector<float> dense;   // [D][b][b], E'[c][r][r2]            (FORM_DENSE)
+  std::vector<float> la, lb;  // [D] lifting coefficients (a, b) or shear factors (m10/m00, m01/m11)
 };
 
 inline int64_t coord_of(int64_t c, int r, int32_t b, int64_t s) {
@@ -52,13 +65,17 @@ bool stage_orthogonal_2x2(const float *K, int64_t D) {
   return true;
 }
 
-void build_effective(const harp_plan *plan, const std::vector<const float *> &blocks,
-                     const int8_t *signs, int algo, Direction dir, std::vector<StageEff> &out) {
+// scaled == true: radix-2 stages before the last take the two-shear form; returns false when a
+// block has a (near-)zero diagonal or a pending scale leaves the safe range.
+bool build_effective(const harp_plan *plan, const std::vector<const float *> &blocks,
+                     const int8_t *signs, int algo, Direction dir, bool scaled,
+                     std::vector<StageEff> &out) {
   const int m = plan->m;
   const int64_t d = plan->d;
-  std::vector<float> tau(d, 1.0f);
+  const double kScaleMax = 1152921504606846976.0;   // 2^60
+  std::vector<double> tau(d, 1.0);
   if (dir == DIR_FWD && signs)
-    for (int64_t i = 0; i < d; ++i) tau[i] = (float)signs[i];
+    for (int64_t i = 0; i < d; ++i) tau[i] = (double)signs[i];
   out.clear();
   out.resize(m);
   for (int i = 0; i < m; ++i) {
@@ -74,8 +91,30 @@ void build_effective(const harp_plan *plan, const std::vector<const float *> &bl
     auto E = [&](int64_t c, int r, int r2) -> double {   // block as used in this direction
       return dir == DIR_TRN ? K[(c * b + r2) * b + r] : K[(c * b + r) * b + r2];
     };
-    se.lifted = (algo != HARP_ALGO_GENERIC && b == 2 && !last && stage_orthogonal_2x2(K, D));
-    if (se.lifted) {
+    const bool pow2_stage = (algo != HARP_ALGO_GENERIC && b == 2 && !last);
+    if (pow2_stage && scaled) {
+      se.form = FORM_SCALED;
+      se.la.resize(D);
+      se.lb.resize(D);
+      for (int64_t c = 0; c < D; ++c) {
+        const int64_t i0 = coord_of(c, 0, 2, se.s), i1 = coord_of(c, 1, 2, se.s);
+        const double m00 = tau[i0] * E(c, 0, 0), m01 = tau[i0] * E(c, 0, 1);
+        const double m10 = tau[i1] * E(c, 1, 0), m11 = tau[i1] * E(c, 1, 1);
+        const double a0 = std::fabs(m00), a1 = std::fabs(m11);
+        if (!(a0 >= 1.0 / kScaleMax && a0 <= kScaleMax && a1 >= 1.0 / kScaleMax &&
+              a1 <= kScaleMax))
+          return false;
+        const float f0 = (float)(m10 / m00), f1 = (float)(m01 / m11);
+        if (!std::isfinite(f0) || !std::isfinite(f1)) return false;
+        se.la[c] = f0;
+        se.lb[c] = f1;
+        tau[i0] = m00;
+        tau[i1] = m11;
+      }
+      continue;
+    }
+    se.form = (pow2_stage && stage_orthogonal_2x2(K, D)) ? FORM_LIFT : FORM_DENSE;
+    if (se.form == FORM_LIFT) {
       se.la.resize(D);
       se.lb.resize(D);
       for (int64_t c = 0; c < D; ++c) {
@@ -87,8 +126,8 @@ void build_effective(const harp_plan *plan, const std::vector<const float *> &bl
         const double d1 = (m11 * C - m01 * S >= 0.0) ? 1.0 : -1.0;
         se.la[c] = (float)(S / (1.0 + C));
         se.lb[c] = (float)(-S);
-        tau[i0] = (float)d0;
-        tau[i1] = (float)d1;
+        tau[i0] = d0;
+        tau[i1] = d1;
       }
     } else {
       se.dense.resize((size_t)D * b * b);
@@ -101,10 +140,11 @@ void build_effective(const harp_plan *plan, const std::vector<const float *> &bl
             se.dense[((size_t)c * b + r) * b + r2] = (float)v;
           }
         }
-        for (int r = 0; r < b; ++r) tau[coord_of(c, r, b, se.s)] = 1.0f;
+        for (int r = 0; r < b; ++r) tau[coord_of(c, r, b, se.s)] = 1.0;
       }
     }
   }
+  return true;
 }
 
 constexpr int64_t kChunkCap = 4096;   // largest on-chip chunk of a split program
@@ -165,7 +205,8 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
   const int m = plan->m;
   const int64_t d = plan->d;
   std::vector<StageEff> eff;
-  build_effective(plan, blocks, signs, algo, dir, eff);
+  if (!build_effective(plan, blocks, signs, algo, dir, true, eff))
+    build_effective(plan, blocks, signs, algo, dir, false, eff);
 
   Program &pg = hp.prog;
   pg.npass = 0;
@@ -196,9 +237,10 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
     if (fused && b == 2) {
       // sub-run of radix-2 stages of one form (and one side of tb); a lifted sub-run may end
       // with the program's final (dense) stage
-      const bool lift = eff[i].lifted;
+      const int form = eff[i].form;
+      const bool lift = (form != FORM_DENSE);   // two values per pair: lifting or scaled shears
       int len = 1;
-      while (i + len < m && eff[i + len].b == 2 && eff[i + len].lifted == lift &&
+      while (i + len < m && eff[i + len].b == 2 && eff[i + len].form == form &&
              local(i + len) == local(i))
         ++len;
       bool last_dense = false;
@@ -218,7 +260,10 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
         int64_t S = eff[i].s;
         for (int e = 0; e < k; ++e) S = std::min<int64_t>(S, eff[i + e].s);
         const int64_t nq = d / P;
-        pd.kind = lift ? (ld ? PASS_POW2_LIFT_LD : PASS_POW2_LIFT) : PASS_POW2_DENSE;
+        if (form == FORM_SCALED)
+          pd.kind = ld ? PASS_POW2_SCALED_LD : PASS_POW2_SCALED;
+        else
+          pd.kind = lift ? (ld ? PASS_POW2_LIFT_LD : PASS_POW2_LIFT) : PASS_POW2_DENSE;
         pd.b = 2;
         pd.k = k;
         pd.desc = (dir == DIR_TRN) ? 1 : 0;
@@ -242,7 +287,7 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
               const int64_t idx0 = base + (int64_t)j0 * S;
               const int64_t beta = idx0 % se.s, alpha = idx0 / (2 * se.s);
               const int64_t c = alpha * se.s + beta;
-              if (se.lifted) {
+              if (se.form != FORM_DENSE) {
                 const size_t v0 = (size_t)(e * (P / 2) + p) * 2;
                 img[(v0 + 0) * nq + q] = se.la[c];
                 img[(v0 + 1) * nq + q] = se.lb[c];

@@ -21,7 +21,11 @@ enum PassKind : int32_t {
   PASS_POW2_LIFT = 1,     // k radix-2 stages, orthogonal blocks as 3 lifting steps: 2 values
   PASS_SMALL = 2,         // one stage of radix 3..8, compile-time radix, block in registers
   PASS_GENERIC = 3,       // one stage of any radix <= HARP_MAX_RADIX, run-time radix
-  PASS_POW2_LIFT_LD = 4   // as LIFT, but the k-th stage (the program's last) is a dense 2x2
+  PASS_POW2_LIFT_LD = 4,  // as LIFT, but the k-th stage (the program's last) is a dense 2x2
+  // k radix-2 stages as two shears with deferred output scales, 2 values (f0, f1) per pair:
+  // (x0, x1) <- (x0 + f0 x1, x1 + f1 x0); _LD: the k-th stage is the program's dense last one
+  PASS_POW2_SCALED = 5,
+  PASS_POW2_SCALED_LD = 6
 };
 
 struct PassDesc {

@@ -92,11 +92,13 @@ __device__ __forceinline__ void store_one(uint16_t *p, float v) { *p = narrow_bf
 // FORM 0: dense 2x2 blocks, 4 values per pair.  FORM 1: orthogonal blocks as three lifting
 // steps, 2 values (a, b) per pair: x0 += a x1; x1 += b x0; x0 += a x1.  FORM 2: as FORM 1
 // but the K-th stage is dense (its 4-value pairs follow the (K-1) * P lifted values).
+// FORM 3 / 4: as FORM 1 / 2 with two shears per pair instead of three lifting steps:
+// (x0, x1) <- (x0 + a x1, x1 + b x0), output scales deferred by the plan.
 template <int K, bool DESC, int FORM>
 __device__ __forceinline__ void pass_pow2(float *tile, int d, int nr, const PassDesc &pd, int kch,
                                           int tid, int nt) {
   constexpr int P = 1 << K;
-  constexpr int NV = (FORM == 0) ? K * (P / 2) * 4 : (FORM == 1 ? K * P : (K + 1) * P);
+  constexpr int NV = (FORM == 0) ? K * (P / 2) * 4 : ((FORM == 1 || FORM == 3) ? K * P : (K + 1) * P);
   // the tile rows are chunk `kch` (d coordinates) of the full rows: nq sub-tensors here,
   // numbered qoff .. qoff + nq - 1 among the pd.nq sub-tensors of a full row
   const int nq = d / P, S = pd.S, nqg = pd.nq, qoff = kch * nq;
@@ -126,7 +128,7 @@ __device__ __forceinline__ void pass_pow2(float *tile, int d, int nr, const Pass
 #pragma unroll
       for (int e = 0; e < K; ++e) {
         const int bp = DESC ? K - 1 - e : e;
-        const bool dense = (FORM == 0) || (FORM == 2 && e == K - 1);
+        const bool dense = (FORM == 0) || ((FORM == 2 || FORM == 4) && e == K - 1);
 #pragma unroll
         for (int p = 0; p < P / 2; ++p) {
           const int j0 = ((p >> bp) << (bp + 1)) | (p & ((1 << bp) - 1));
@@ -134,11 +136,16 @@ __device__ __forceinline__ void pass_pow2(float *tile, int d, int nr, const Pass
           float x0 = x[j0], x1 = x[j1];
           if (!dense) {
             const float a = prm[(e * (P / 2) + p) * 2 + 0], b = prm[(e * (P / 2) + p) * 2 + 1];
-            x0 = fmaf(a, x1, x0);
-            x1 = fmaf(b, x0, x1);
-            x0 = fmaf(a, x1, x0);
-            x[j0] = x0;
-            x[j1] = x1;
+            if (FORM >= 3) {
+              x[j0] = fmaf(a, x1, x0);
+              x[j1] = fmaf(b, x0, x1);
+            } else {
+              x0 = fmaf(a, x1, x0);
+              x1 = fmaf(b, x0, x1);
+              x0 = fmaf(a, x1, x0);
+              x[j0] = x0;
+              x[j1] = x1;
+            }
           } else {
             const int v0 = (FORM == 0) ? (e * (P / 2) + p) * 4 : (K - 1) * P + p * 4;
             const float k00 = prm[v0 + 0], k01 = prm[v0 + 1], k10 = prm[v0 + 2], k11 = prm[v0 + 3];
@@ -249,6 +256,14 @@ __device__ __forceinline__ void run_pass(float *tile, int d, int nr, const PassD
       if (pd.desc) dispatch_pow2<true, 2>(tile, d, nr, pd, kch, tid, nt);
       else dispatch_pow2<false, 2>(tile, d, nr, pd, kch, tid, nt);
       break;
+    case PASS_POW2_SCALED:
+      if (pd.desc) dispatch_pow2<true, 3>(tile, d, nr, pd, kch, tid, nt);
+      else dispatch_pow2<false, 3>(tile, d, nr, pd, kch, tid, nt);
+      break;
+    case PASS_POW2_SCALED_LD:
+      if (pd.desc) dispatch_pow2<true, 4>(tile, d, nr, pd, kch, tid, nt);
+      else dispatch_pow2<false, 4>(tile, d, nr, pd, kch, tid, nt);
+      break;
     case PASS_SMALL:
       switch (pd.b) {
         case 3: pass_small<3>(tile, d, nr, pd, kch, tid, nt); break;
@@ -351,12 +366,12 @@ __global__ __launch_bounds__(512) void harp_tile_kernel(const TI *__restrict__ X
 template <int K, bool DESC, int FORM>
 struct OpPow2 {
   static constexpr int P = 1 << K;
-  static constexpr int NV = (FORM == 0) ? K * (P / 2) * 4 : (FORM == 1 ? K * P : (K + 1) * P);
+  static constexpr int NV = (FORM == 0) ? K * (P / 2) * 4 : ((FORM == 1 || FORM == 3) ? K * P : (K + 1) * P);
   __device__ static __forceinline__ void apply(float (&x)[P], const float (&prm)[NV]) {
 #pragma unroll
     for (int e = 0; e < K; ++e) {
       const int bp = DESC ? K - 1 - e : e;
-      const bool dense = (FORM == 0) || (FORM == 2 && e == K - 1);
+      const bool dense = (FORM == 0) || ((FORM == 2 || FORM == 4) && e == K - 1);
 #pragma unroll
       for (int p = 0; p < P / 2; ++p) {
         const int j0 = ((p >> bp) << (bp + 1)) | (p & ((1 << bp) - 1));
@@ -364,11 +379,16 @@ struct OpPow2 {
         float x0 = x[j0], x1 = x[j1];
         if (!dense) {
           const float a = prm[(e * (P / 2) + p) * 2 + 0], b = prm[(e * (P / 2) + p) * 2 + 1];
-          x0 = fmaf(a, x1, x0);
-          x1 = fmaf(b, x0, x1);
-          x0 = fmaf(a, x1, x0);
-          x[j0] = x0;
-          x[j1] = x1;
+          if (FORM >= 3) {
+            x[j0] = fmaf(a, x1, x0);
+            x[j1] = fmaf(b, x0, x1);
+          } else {
+            x0 = fmaf(a, x1, x0);
+            x1 = fmaf(b, x0, x1);
+            x0 = fmaf(a, x1, x0);
+            x[j0] = x0;
+            x[j1] = x1;
+          }
         } else {
           const int v0 = (FORM == 0) ? (e * (P / 2) + p) * 4 : (K - 1) * P + p * 4;
           x[j0] = fmaf(x1, prm[v0 + 2], x0 * prm[v0 + 0]);
@@ -698,6 +718,12 @@ harp_status_t launch_stream_pass(const harp_plan *plan, const HostProgram &hp, i
     case PASS_POW2_LIFT_LD:
       return pd.desc ? launch_stream_pow2<true, 2>(plan, pd, X, ldx, ib, Y, ldy, ob, n, stream)
                      : launch_stream_pow2<false, 2>(plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
+    case PASS_POW2_SCALED:
+      return pd.desc ? launch_stream_pow2<true, 3>(plan, pd, X, ldx, ib, Y, ldy, ob, n, stream)
+                     : launch_stream_pow2<false, 3>(plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
+    case PASS_POW2_SCALED_LD:
+      return pd.desc ? launch_stream_pow2<true, 4>(plan, pd, X, ldx, ib, Y, ldy, ob, n, stream)
+                     : launch_stream_pow2<false, 4>(plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
     case PASS_SMALL:
       switch (pd.b) {
         case 3: return launch_stream_op<OpSmall<3>>(plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);

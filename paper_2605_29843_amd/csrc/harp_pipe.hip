@@ -56,8 +56,9 @@ __device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
 // K radix-2 stages on SPT = 16 / 2^K sub-tensors held in x[16].  Stages are lifted rotations
 // (x0 += a x1; x1 += b x0; x0 += a x1, values (a, b) at ((e * P/2 + p) * 2) of the
 // sub-tensor's block of parameters); with LD the K-th stage is a dense 2x2 whose four values
-// per pair follow the (K-1) * P lifted values.
-template <int K, bool DESC, bool LD>
+// per pair follow the (K-1) * P lifted values.  With SC a stage is two shears with deferred
+// output scales instead: (x0, x1) <- (x0 + a x1, x1 + b x0), same parameter positions.
+template <int K, bool DESC, bool LD, bool SC>
 __device__ __forceinline__ void lift_stages(float (&x)[16], const float (&prm)[16 * (K + (LD ? 1 : 0))]) {
   constexpr int P = 1 << K, SPT = 16 / P, NV = (K + (LD ? 1 : 0)) * P;
 #pragma unroll
@@ -77,11 +78,16 @@ __device__ __forceinline__ void lift_stages(float (&x)[16], const float (&prm)[1
         } else {
           const float a = prm[u * NV + (e * (P / 2) + p) * 2 + 0];
           const float b = prm[u * NV + (e * (P / 2) + p) * 2 + 1];
-          x0 = fmaf(a, x1, x0);
-          x1 = fmaf(b, x0, x1);
-          x0 = fmaf(a, x1, x0);
-          x[j0] = x0;
-          x[j1] = x1;
+          if (SC) {
+            x[j0] = fmaf(a, x1, x0);
+            x[j1] = fmaf(b, x0, x1);
+          } else {
+            x0 = fmaf(a, x1, x0);
+            x1 = fmaf(b, x0, x1);
+            x0 = fmaf(a, x1, x0);
+            x[j0] = x0;
+            x[j1] = x1;
+          }
         }
       }
     }
@@ -194,7 +200,7 @@ struct RowIo<float, false> {        // 16 single floats at the pass stride
 // coordinates (16-byte vector accesses), the others touch single coordinates.  kch = index of
 // the chunk of D coordinates this workgroup works on (0 when D is the whole row).  Every group
 // executes the same number of barriers (nr + 2, or nr + 4 with read-ahead).
-template <typename TI, typename TO, int K, int LOGS, bool DESC, int ROLE, bool LD, int D>
+template <typename TI, typename TO, int K, int LOGS, bool DESC, int ROLE, bool LD, bool SC, int D>
 __device__ __forceinline__ void pipe_group(const PassDesc &pd, const int t, const int kch,
                                            const float *rd_buf, float *wr_buf,
                                            const TI *__restrict__ X, const int64_t ldx,
@@ -277,7 +283,7 @@ __device__ __forceinline__ void pipe_group(const PassDesc &pd, const int t, cons
         }
       }
       if (r_cp >= 0 && r_cp < nr) {
-        lift_stages<K, DESC, LD>(xc, prm);
+        lift_stages<K, DESC, LD, SC>(xc, prm);
         if (ROLE == 2) {
           Out::store(Y + (int64_t)r_cp * ldy, glb_off, xc);
         } else {
@@ -300,7 +306,7 @@ __device__ __forceinline__ void pipe_group(const PassDesc &pd, const int t, cons
 
 // Workgroup -> (chunk kch, tile of R rows).  nchunk = chunks per row (1: D is the whole row).
 // The three chunk-local passes are prog.pass[p0 .. p0+2].
-template <typename TI, typename TO, int K0, int K1, int K2, bool TRN, bool LD>
+template <typename TI, typename TO, int K0, int K1, int K2, bool TRN, bool LD, bool SC>
 __global__ __launch_bounds__(3 << (K0 + K1 + K2 - 4)) void harp_pipe_kernel(
     const TI *__restrict__ X, int64_t ldx, TO *__restrict__ Y, int64_t ldy, int64_t n, int R,
     int nchunk, const Program *__restrict__ progp, int p0) {
@@ -318,13 +324,13 @@ __global__ __launch_bounds__(3 << (K0 + K1 + K2 - 4)) void harp_pipe_kernel(
   // stride of each pass's lowest digit: ascending for apply, descending for apply_transpose
   constexpr int LS0 = TRN ? K1 + K2 : 0, LS1 = TRN ? K2 : K0, LS2 = TRN ? 0 : K0 + K1;
   if (g == 0)
-    pipe_group<TI, TO, K0, LS0, TRN, 0, false, D>(prog.pass[p0], t, kch, nullptr, bufA, Xt, ldx,
+    pipe_group<TI, TO, K0, LS0, TRN, 0, false, SC, D>(prog.pass[p0], t, kch, nullptr, bufA, Xt, ldx,
                                                   Yt, ldy, nr);
   else if (g == 1)
-    pipe_group<TI, TO, K1, LS1, TRN, 1, false, D>(prog.pass[p0 + 1], t, kch, bufA, bufB, Xt, ldx,
+    pipe_group<TI, TO, K1, LS1, TRN, 1, false, SC, D>(prog.pass[p0 + 1], t, kch, bufA, bufB, Xt, ldx,
                                                   Yt, ldy, nr);
   else
-    pipe_group<TI, TO, K2, LS2, TRN, 2, LD, D>(prog.pass[p0 + 2], t, kch, bufB, nullptr, Xt, ldx,
+    pipe_group<TI, TO, K2, LS2, TRN, 2, LD, SC, D>(prog.pass[p0 + 2], t, kch, bufB, nullptr, Xt, ldx,
                                                Yt, ldy, nr);
 }
 
@@ -388,7 +394,7 @@ __device__ __forceinline__ void wave_exchange(float (&x)[16], float *buf, const 
   __syncthreads();
 }
 
-template <typename TI, typename TO, int K0, int K1, int K2, bool TRN, bool LD>
+template <typename TI, typename TO, int K0, int K1, int K2, bool TRN, bool LD, bool SC>
 __global__ __launch_bounds__(64) void harp_wave_kernel(const TI *__restrict__ X, int64_t ldx,
                                                        TO *__restrict__ Y, int64_t ldy, int64_t n,
                                                        int R, int ngroups, int d,
@@ -436,12 +442,12 @@ __global__ __launch_bounds__(64) void harp_wave_kernel(const TI *__restrict__ X,
       if (active && r + 2 < nr) In::load(X + (row0 + r + 2) * ldx, goff, pre[s]);
 
       if (!(K0 == 4 && LS0 == 0)) wave_exchange(x, buf, io, pa);
-      lift_stages<K0, TRN, false>(x, pa.prm);
+      lift_stages<K0, TRN, false, SC>(x, pa.prm);
       wave_exchange(x, buf, pa, pb);
-      lift_stages<K1, TRN, (!THREE && LD)>(x, pb.prm);
+      lift_stages<K1, TRN, (!THREE && LD), SC>(x, pb.prm);
       if (THREE) {
         wave_exchange(x, buf, pb, pc);
-        lift_stages<(THREE ? K2 : 1), TRN, (THREE && LD)>(x, pc.prm);
+        lift_stages<(THREE ? K2 : 1), TRN, (THREE && LD), SC>(x, pc.prm);
         if (!(K2 == 4 && LS2 == 0)) wave_exchange(x, buf, pc, io);
       } else {
         if (!(K1 == 4 && LS1 == 0)) wave_exchange(x, buf, pb, io);
@@ -449,6 +455,20 @@ __global__ __launch_bounds__(64) void harp_wave_kernel(const TI *__restrict__ X,
       if (active) Out::store(Y + (row0 + r) * ldy, goff, x);
     }
   }
+}
+
+// Passes ps[0 .. np): all lifted, or all in the two-shear form; only the last may end with the
+// program's dense stage.
+bool pow2_family(const PassDesc *ps, int np, bool *ld, bool *sc) {
+  const int last = ps[np - 1].kind;
+  *sc = (last == PASS_POW2_SCALED || last == PASS_POW2_SCALED_LD);
+  const int plain = *sc ? PASS_POW2_SCALED : PASS_POW2_LIFT;
+  const int ended = *sc ? PASS_POW2_SCALED_LD : PASS_POW2_LIFT_LD;
+  for (int p = 0; p < np - 1; ++p)
+    if (ps[p].kind != plain) return false;
+  if (last != plain && last != ended) return false;
+  *ld = (last == ended);
+  return true;
 }
 
 struct WaveArgs {
@@ -464,35 +484,43 @@ struct WaveArgs {
   hipStream_t stream;
 };
 
-template <typename TI, typename TO, int K0, int K1, int K2, bool TRN, bool LD>
+template <typename TI, typename TO, int K0, int K1, int K2, bool TRN, bool LD, bool SC>
 harp_status_t launch_wave_inst(const WaveArgs &a) {
   const int ngroups = (a.d + 1023) / 1024;
   const int64_t tiles = ((a.n + a.R - 1) / a.R) * ngroups;
   if (tiles > 0x7fffffff) return HARP_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL((harp_wave_kernel<TI, TO, K0, K1, K2, TRN, LD>), dim3((unsigned)tiles),
+  hipLaunchKernelGGL((harp_wave_kernel<TI, TO, K0, K1, K2, TRN, LD, SC>), dim3((unsigned)tiles),
                      dim3(64), 0, a.stream, (const TI *)a.X, a.ldx, (TO *)a.Y, a.ldy, a.n, a.R,
                      ngroups, a.d, a.dprog, a.p0);
   return hipGetLastError() == hipSuccess ? HARP_OK : HARP_ERR_DEVICE;
 }
 
+template <typename TI, typename TO, int K0, int K1, int K2, bool SC>
+harp_status_t launch_wave_form(const WaveArgs &a, bool trn, bool ld) {
+  if (trn)
+    return ld ? launch_wave_inst<TI, TO, K0, K1, K2, true, true, SC>(a) : HARP_ERR_UNSUPPORTED;
+  return ld ? launch_wave_inst<TI, TO, K0, K1, K2, false, true, SC>(a)
+            : launch_wave_inst<TI, TO, K0, K1, K2, false, false, SC>(a);
+}
+
 template <typename TI, typename TO, int K0, int K1, int K2>
-harp_status_t launch_wave_dir(const WaveArgs &a, bool trn, bool ld) {
-  if (trn) return ld ? launch_wave_inst<TI, TO, K0, K1, K2, true, true>(a) : HARP_ERR_UNSUPPORTED;
-  return ld ? launch_wave_inst<TI, TO, K0, K1, K2, false, true>(a)
-            : launch_wave_inst<TI, TO, K0, K1, K2, false, false>(a);
+harp_status_t launch_wave_dir(const WaveArgs &a, bool trn, bool ld, bool sc) {
+  return sc ? launch_wave_form<TI, TO, K0, K1, K2, true>(a, trn, ld)
+            : launch_wave_form<TI, TO, K0, K1, K2, false>(a, trn, ld);
 }
 
 template <typename TI, typename TO>
-harp_status_t launch_wave_io(const WaveArgs &a, int logc, bool trn, bool ld) {
-  if (logc == 8) return launch_wave_dir<TI, TO, 4, 4, 0>(a, trn, ld);
-  if (logc == 9) return launch_wave_dir<TI, TO, 3, 3, 3>(a, trn, ld);
-  if (logc == 10) return launch_wave_dir<TI, TO, 4, 3, 3>(a, trn, ld);
+harp_status_t launch_wave_io(const WaveArgs &a, int logc, bool trn, bool ld, bool sc) {
+  if (logc == 8) return launch_wave_dir<TI, TO, 4, 4, 0>(a, trn, ld, sc);
+  if (logc == 9) return launch_wave_dir<TI, TO, 3, 3, 3>(a, trn, ld, sc);
+  if (logc == 10) return launch_wave_dir<TI, TO, 4, 3, 3>(a, trn, ld, sc);
   return HARP_ERR_UNSUPPORTED;
 }
 
 // Passes [p0, p0+np) must be the lifted radix-2 passes (4,4), (3,3,3) or (4,3,3) of a chunk of
 // 256 / 512 / 1024 coordinates with the strides the kernel is compiled for.
-bool wave_decode(const Program &pg, int p0, int np, int chunk, int *logc, bool *trn, bool *ld) {
+bool wave_decode(const Program &pg, int p0, int np, int chunk, int *logc, bool *trn, bool *ld,
+                 bool *sc) {
   if (np != 2 && np != 3) return false;
   const PassDesc *ps = pg.pass + p0;
   const int k0 = ps[0].k, k1 = ps[1].k, k2 = (np == 3) ? ps[2].k : 0;
@@ -501,10 +529,7 @@ bool wave_decode(const Program &pg, int p0, int np, int chunk, int *logc, bool *
         (lc == 10 && k0 == 4 && k1 == 3 && k2 == 3)))
     return false;
   if (chunk != (1 << lc)) return false;
-  for (int p = 0; p < np - 1; ++p)
-    if (ps[p].kind != PASS_POW2_LIFT) return false;
-  if (ps[np - 1].kind != PASS_POW2_LIFT && ps[np - 1].kind != PASS_POW2_LIFT_LD) return false;
-  *ld = ps[np - 1].kind == PASS_POW2_LIFT_LD;
+  if (!pow2_family(ps, np, ld, sc)) return false;
   *trn = ps[0].desc != 0;
   for (int p = 1; p < np; ++p)
     if (ps[p].desc != ps[0].desc) return false;
@@ -532,42 +557,48 @@ struct PipeArgs {
   hipStream_t stream;
 };
 
-template <typename TI, typename TO, int K0, int K1, int K2, bool TRN, bool LD>
+template <typename TI, typename TO, int K0, int K1, int K2, bool TRN, bool LD, bool SC>
 harp_status_t launch_pipe_inst(const PipeArgs &a) {
   constexpr int NT = 3 << (K0 + K1 + K2 - 4);
   const int64_t tiles = ((a.n + a.R - 1) / a.R) * a.nchunk;
   if (tiles > 0x7fffffff) return HARP_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL((harp_pipe_kernel<TI, TO, K0, K1, K2, TRN, LD>), dim3((unsigned)tiles),
+  hipLaunchKernelGGL((harp_pipe_kernel<TI, TO, K0, K1, K2, TRN, LD, SC>), dim3((unsigned)tiles),
                      dim3(NT), 0, a.stream, (const TI *)a.X, a.ldx, (TO *)a.Y, a.ldy, a.n, a.R,
                      a.nchunk, a.dprog, a.p0);
   return hipGetLastError() == hipSuccess ? HARP_OK : HARP_ERR_DEVICE;
 }
 
+template <typename TI, typename TO, int K0, int K1, int K2, bool SC>
+harp_status_t launch_pipe_form(const PipeArgs &a, bool trn, bool ld) {
+  if (trn)
+    return ld ? launch_pipe_inst<TI, TO, K0, K1, K2, true, true, SC>(a) : HARP_ERR_UNSUPPORTED;
+  return ld ? launch_pipe_inst<TI, TO, K0, K1, K2, false, true, SC>(a)
+            : launch_pipe_inst<TI, TO, K0, K1, K2, false, false, SC>(a);
+}
+
 template <typename TI, typename TO, int K0, int K1, int K2>
-harp_status_t launch_pipe_dir(const PipeArgs &a, bool trn, bool ld) {
-  if (trn) return ld ? launch_pipe_inst<TI, TO, K0, K1, K2, true, true>(a) : HARP_ERR_UNSUPPORTED;
-  return ld ? launch_pipe_inst<TI, TO, K0, K1, K2, false, true>(a)
-            : launch_pipe_inst<TI, TO, K0, K1, K2, false, false>(a);
+harp_status_t launch_pipe_dir(const PipeArgs &a, bool trn, bool ld, bool sc) {
+  return sc ? launch_pipe_form<TI, TO, K0, K1, K2, true>(a, trn, ld)
+            : launch_pipe_form<TI, TO, K0, K1, K2, false>(a, trn, ld);
 }
 
 template <typename TI, typename TO>
-harp_status_t launch_pipe_io(const PipeArgs &a, int logd, bool trn, bool ld) {
-  if (logd == 12) return launch_pipe_dir<TI, TO, 4, 4, 4>(a, trn, ld);
-  if (logd == 11) return launch_pipe_dir<TI, TO, 4, 4, 3>(a, trn, ld);
+harp_status_t launch_pipe_io(const PipeArgs &a, int logd, bool trn, bool ld, bool sc) {
+  if (logd == 12) return launch_pipe_dir<TI, TO, 4, 4, 4>(a, trn, ld, sc);
+  if (logd == 11) return launch_pipe_dir<TI, TO, 4, 4, 3>(a, trn, ld, sc);
   return HARP_ERR_UNSUPPORTED;
 }
 
 // Decode the three passes [p0, p0+3): lifted radix-2 passes of (4,4,4) or (4,4,3) stages on a
 // chunk of 2^12 / 2^11 coordinates with the strides the kernel is compiled for.
-bool pipe_decode(const Program &pg, int p0, int np, int chunk, int *logd, bool *trn, bool *ld) {
+bool pipe_decode(const Program &pg, int p0, int np, int chunk, int *logd, bool *trn, bool *ld,
+                 bool *sc) {
   if (np != 3) return false;
   const PassDesc *ps = pg.pass + p0;
   const int k0 = ps[0].k, k1 = ps[1].k, k2 = ps[2].k;
   if (!(k0 == 4 && k1 == 4 && (k2 == 4 || k2 == 3))) return false;
   if (chunk != (1 << (k0 + k1 + k2))) return false;
-  if (ps[0].kind != PASS_POW2_LIFT || ps[1].kind != PASS_POW2_LIFT) return false;
-  if (ps[2].kind != PASS_POW2_LIFT && ps[2].kind != PASS_POW2_LIFT_LD) return false;
-  *ld = ps[2].kind == PASS_POW2_LIFT_LD;
+  if (!pow2_family(ps, 3, ld, sc)) return false;
   *trn = ps[0].desc != 0;
   if (ps[1].desc != ps[0].desc || ps[2].desc != ps[0].desc) return false;
   if (*trn && !*ld) return false;   // a transposed program always ends inside the chunk
@@ -584,8 +615,8 @@ bool pipe_supported(const harp_plan *plan, const Program &pg, int p0, int np, in
                     const void *X, int64_t ldx, const void *Y, int64_t ldy) {
   if (plan->algo == HARP_ALGO_GENERIC) return false;
   int logd;
-  bool trn, ld;
-  if (!pipe_decode(pg, p0, np, chunk, &logd, &trn, &ld)) return false;
+  bool trn, ld, sc;
+  if (!pipe_decode(pg, p0, np, chunk, &logd, &trn, &ld, &sc)) return false;
   // 16-byte row accesses for either element type
   if ((ldx % 8) || (ldy % 8) || ((uintptr_t)X % 16) || ((uintptr_t)Y % 16)) return false;
   return true;
@@ -595,8 +626,8 @@ bool wave_supported(const harp_plan *plan, const Program &pg, int p0, int np, in
                     const void *X, int64_t ldx, const void *Y, int64_t ldy) {
   if (plan->algo == HARP_ALGO_GENERIC) return false;
   int logc;
-  bool trn, ld;
-  if (!wave_decode(pg, p0, np, chunk, &logc, &trn, &ld)) return false;
+  bool trn, ld, sc;
+  if (!wave_decode(pg, p0, np, chunk, &logc, &trn, &ld, &sc)) return false;
   if ((ldx % 8) || (ldy % 8) || ((uintptr_t)X % 16) || ((uintptr_t)Y % 16)) return false;
   return true;
 }
@@ -606,8 +637,8 @@ harp_status_t launch_wave_kernel(const harp_plan *plan, const HostProgram &hp, i
                                  void *Y, int64_t ldy, harp_dtype_t dt_out, int64_t n,
                                  hipStream_t stream) {
   int logc;
-  bool trn, ld;
-  if (!wave_decode(hp.prog, p0, np, chunk, &logc, &trn, &ld)) return HARP_ERR_UNSUPPORTED;
+  bool trn, ld, sc;
+  if (!wave_decode(hp.prog, p0, np, chunk, &logc, &trn, &ld, &sc)) return HARP_ERR_UNSUPPORTED;
   const int64_t ngroups = (plan->d + 1023) / 1024;
   // about 12 waves per compute unit; at least 4 rows per wave so its parameters are reused
   int64_t R = plan->rows_override > 0 ? plan->rows_override
@@ -618,12 +649,12 @@ harp_status_t launch_wave_kernel(const harp_plan *plan, const HostProgram &hp, i
   if (R < 1) R = 1;
   WaveArgs a{hp.dev, p0, X, ldx, Y, ldy, n, (int)R, (int)plan->d, stream};
   if (dt_in == HARP_BF16 && dt_out == HARP_BF16)
-    return launch_wave_io<uint16_t, uint16_t>(a, logc, trn, ld);
+    return launch_wave_io<uint16_t, uint16_t>(a, logc, trn, ld, sc);
   if (dt_in == HARP_BF16 && dt_out == HARP_F32)
-    return launch_wave_io<uint16_t, float>(a, logc, trn, ld);
+    return launch_wave_io<uint16_t, float>(a, logc, trn, ld, sc);
   if (dt_in == HARP_F32 && dt_out == HARP_BF16)
-    return launch_wave_io<float, uint16_t>(a, logc, trn, ld);
-  return launch_wave_io<float, float>(a, logc, trn, ld);
+    return launch_wave_io<float, uint16_t>(a, logc, trn, ld, sc);
+  return launch_wave_io<float, float>(a, logc, trn, ld, sc);
 }
 
 harp_status_t launch_pipe_kernel(const harp_plan *plan, const HostProgram &hp, int p0, int chunk,
@@ -631,16 +662,16 @@ harp_status_t launch_pipe_kernel(const harp_plan *plan, const HostProgram &hp, i
                                  int64_t ldy, harp_dtype_t dt_out, int64_t n, int R,
                                  hipStream_t stream) {
   int logd;
-  bool trn, ld;
-  if (!pipe_decode(hp.prog, p0, 3, chunk, &logd, &trn, &ld)) return HARP_ERR_UNSUPPORTED;
+  bool trn, ld, sc;
+  if (!pipe_decode(hp.prog, p0, 3, chunk, &logd, &trn, &ld, &sc)) return HARP_ERR_UNSUPPORTED;
   PipeArgs a{hp.dev, p0, X, ldx, Y, ldy, n, R, (int)(plan->d / chunk), stream};
   if (dt_in == HARP_BF16 && dt_out == HARP_BF16)
-    return launch_pipe_io<uint16_t, uint16_t>(a, logd, trn, ld);
+    return launch_pipe_io<uint16_t, uint16_t>(a, logd, trn, ld, sc);
   if (dt_in == HARP_BF16 && dt_out == HARP_F32)
-    return launch_pipe_io<uint16_t, float>(a, logd, trn, ld);
+    return launch_pipe_io<uint16_t, float>(a, logd, trn, ld, sc);
   if (dt_in == HARP_F32 && dt_out == HARP_BF16)
-    return launch_pipe_io<float, uint16_t>(a, logd, trn, ld);
-  return launch_pipe_io<float, float>(a, logd, trn, ld);
+    return launch_pipe_io<float, uint16_t>(a, logd, trn, ld, sc);
+  return launch_pipe_io<float, float>(a, logd, trn, ld, sc);
 }
 
 }  // namespace harp

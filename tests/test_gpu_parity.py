@@ -134,6 +134,56 @@ def test_non_orthogonal_blocks_are_still_the_linear_map(harp):
         plan.destroy()
 
 
+def _radix2_plan_with_special_blocks(d, m, special, seed):
+    """Random Givens blocks; in every stage every 7th block is replaced by `special(c)`."""
+    rng = np.random.default_rng(seed)
+    radices = [2] * m
+    blocks = gi.make_blocks(d, radices, "orth", rng)
+    for t in range(m):
+        for c in range(t % 7, d // 2, 7):
+            blocks[t][c] = special(c)
+    return radices, blocks, gi.make_signs(d, rng)
+
+
+@pytest.mark.parametrize("d", [256, 4096])
+@pytest.mark.parametrize("case", ["quarter_turn", "swap", "near_quarter_turn", "general"])
+def test_radix2_blocks_with_zero_or_tiny_diagonal(harp, d, case):
+    """The two-shear form divides by the diagonal of a block: blocks with an exactly zero
+    diagonal (quarter turns, swaps) must take the lifting fallback, nearly zero ones and
+    general invertible 2x2 blocks must stay accurate."""
+    import torch
+    m = int(np.log2(d))
+    eps = 3e-5
+    special = {
+        "quarter_turn": lambda c: np.array([[0, -1], [1, 0]] if c % 2 else [[0, 1], [-1, 0]], np.float32),
+        "swap": lambda c: np.array([[0, 1], [1, 0]], np.float32),
+        "near_quarter_turn": lambda c: np.array([[np.sin(eps), -np.cos(eps)], [np.cos(eps), np.sin(eps)]],
+                                                np.float32),
+        "general": lambda c: np.array([[1.5, 0.25 * (c % 5)], [-0.5, 0.75]], np.float32),
+    }[case]
+    radices, blocks, signs = _radix2_plan_with_special_blocks(d, m, special, seed=d + len(case))
+    n = 37
+    X = gi.round_to_bf16(np.random.default_rng(3).standard_normal((n, d)).astype(np.float32))
+    for dtype in ("bf16", "f32"):
+        plan = harp.Plan(d, radices, blocks, signs)
+        say(f"special blocks {case} d={d} {dtype} kernel={plan.kernel_name()}")
+        Xd = to_device(X, dtype)
+        Y = to_host64(harp.harp_apply(plan, Xd))
+        Z = to_host64(harp.harp_apply_transpose(plan, Xd))
+        torch.cuda.synchronize()
+        Yref = ho.apply_staged(X, d, radices, blocks, signs)
+        Zref = ho.apply_transpose_staged(X, d, radices, blocks, signs)
+        if case == "general":      # not orthogonal: error relative to the output's row scale
+            for got, ref in ((Y, Yref), (Z, Zref)):
+                rho = np.linalg.norm(ref, axis=1, keepdims=True) / np.sqrt(d)
+                tol = 1e-5 if dtype == "f32" else 8e-3
+                assert np.max(np.abs(got - ref) / np.maximum(np.abs(ref), rho)) < tol
+        else:
+            assert_parity(Y, Yref, dtype, "apply")
+            assert_parity(Z, Zref, dtype, "apply_transpose")
+        plan.destroy()
+
+
 # ------------------------------------------------------------------ layout edge cases
 def test_empty_batch_is_a_noop(harp):
     run_case(harp, 64, [2] * 6, 0, "bf16", algo=2)
