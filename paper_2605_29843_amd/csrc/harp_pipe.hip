@@ -1,8 +1,8 @@
 // Row-pipelined kernel for radix-2 chains of orthogonal blocks on rows, or contiguous row
 // chunks, of 2^(K0+K1+K2) = 2048 or 4096 coordinates; bf16 or float32 on either side.  Every
-// stage but the last is executed as three lifting steps, the last as a dense 2x2 that also
-// carries all pending signs (see the plan builder), so the inner loop is fused multiply-adds
-// only.  The second kernel of this file covers chunks of 256 / 512 / 1024 coordinates with one
+// stage but the last is executed as two shears with deferred output scales (or, as the plan
+// builder's fallback, three lifting steps), the last as a dense 2x2 that also carries all
+// pending scales and signs, so the inner loop is fused multiply-adds only.  The second kernel of this file covers chunks of 256 / 512 / 1024 coordinates with one
 // wave per window (see harp_wave_kernel below).
 //
 // The 10..12 stages are cut into three passes of K0, K1, K2 consecutive stages.  A workgroup
@@ -11,11 +11,11 @@
 // whole launch (they are read from device memory exactly once per workgroup), and rows flow
 // through the groups like an assembly line:
 //
-//    step k:  group 0  takes row k (prefetched from device memory several rows ahead),
-//                      applies pass 0, writes the row to LDS buffer A[k & 1]
-//             group 1  reads row k-1 from A[(k-1) & 1], applies pass 1, writes B[k & 1]
-//             group 2  reads row k-2 from B[(k-1) & 1], applies pass 2, rounds to bf16 and
-//                      stores it to device memory
+//    step k:  group 0  takes rows 2k, 2k+1 (prefetched from device memory up to two pairs
+//                      ahead), applies pass 0, writes them to LDS buffer A[k & 1]
+//             group 1  reads pair k-1 from A[(k-1) & 1], applies pass 1, writes B[k & 1]
+//             group 2  reads pair k-2 from B[(k-1) & 1], applies pass 2, rounds to the output
+//                      type and stores the rows to device memory
 //             one workgroup barrier
 //
 // so loads, the three passes and stores of different rows overlap, and the three groups give
@@ -32,12 +32,9 @@ namespace harp {
 
 namespace {
 
-constexpr int kPrefetch = 4;
-// With READ_AHEAD groups 1 and 2 issue the LDS reads of their next row one step before they
-// compute it (two more pipeline steps per tile).  Measured on MI355X it does not pay: LDS
-// instructions and arithmetic of the waves of one SIMD overlap poorly either way, and tiles
-// of 8 rows lose more to the longer fill and drain than they gain.
-constexpr bool READ_AHEAD = false;
+// parameter images live in device (global) memory: say so, so that the loads are global loads
+// with a scalar base rather than generic-address loads
+typedef const __attribute__((address_space(1))) float *gparams_t;
 
 // LDS position (in floats) of logical coordinate i of a row: 16 floats of padding per 256,
 // and the four 4-float chunks of every 16-float segment rotated by (segment / 2).
@@ -198,13 +195,16 @@ struct RowIo<float, false> {        // 16 single floats at the pass stride
 // (writes device memory; with LD its K-th stage is the program's last and is dense).  LOGS =
 // log2 of the stride of the pass's lowest digit; the pass with LOGS == 0 touches contiguous
 // coordinates (16-byte vector accesses), the others touch single coordinates.  kch = index of
-// the chunk of D coordinates this workgroup works on (0 when D is the whole row).  Every group
-// executes the same number of barriers (nr + 2, or nr + 4 with read-ahead).
+// the chunk of D coordinates this workgroup works on (0 when D is the whole row).
+// A step moves a PAIR of rows through every group: group g works on pair k - g at step k, one
+// barrier per step, npairs + 2 steps for every group.  Inside a wave the LDS reads of the
+// second row and the LDS writes of the first overlap with arithmetic.  Buffers hold two rows
+// per parity: row r of the pair at + r * ROWBUF.
 template <typename TI, typename TO, int K, int LOGS, bool DESC, int ROLE, bool LD, bool SC, int D>
 __device__ __forceinline__ void pipe_group(const PassDesc &pd, const int t, const int kch,
-                                           const float *rd_buf, float *wr_buf,
-                                           const TI *__restrict__ X, const int64_t ldx,
-                                           TO *__restrict__ Y, const int64_t ldy, const int nr) {
+                                            const float *rd_buf, float *wr_buf,
+                                            const TI *__restrict__ X, const int64_t ldx,
+                                            TO *__restrict__ Y, const int64_t ldy, const int nr) {
   constexpr int P = 1 << K, SPT = 16 / P, TG = D / 16, NV = (K + (LD ? 1 : 0)) * P;
   constexpr int ROWBUF = (D / 256) * 272;
   constexpr int S = 1 << LOGS;
@@ -212,91 +212,102 @@ __device__ __forceinline__ void pipe_group(const PassDesc &pd, const int t, cons
   using In = RowIo<TI, CONTIG>;
   using Out = RowIo<TO, CONTIG>;
   constexpr int NRAW = In::NRAW;
-  constexpr int PF = (NRAW == 8) ? kPrefetch : kPrefetch - 1;
+  constexpr int PFP = (NRAW == 8) ? 2 : 1;   // pairs of rows prefetched ahead
   const unsigned nq = (unsigned)pd.nq;
   const unsigned qoff = (unsigned)kch * (D / P);
   const float *__restrict__ params = pd.params;
 
-  float prm[SPT * NV];
   unsigned base[SPT];
+#pragma unroll
+  for (int u = 0; u < SPT; ++u) {
+    const unsigned q = (unsigned)t + u * TG;
+    const unsigned hi = q >> LOGS, lo = q & (S - 1);
+    base[u] = ((hi << K) << LOGS) | lo;
+  }
+  auto lds_off = [&](int e) -> int {
+    const int u = e / P, j = e % P;
+    return phys_index((int)(base[u] | ((unsigned)j << LOGS)));
+  };
+  auto glb_off = [&](int e) -> unsigned {
+    const int u = e / P, j = e % P;
+    return base[u] | ((unsigned)j << LOGS);
+  };
+
+  // first rows before the parameters: their device-memory latency is the longer one
+  uint32_t pre[2 * PFP][NRAW];
+  if (ROLE == 0) {
+#pragma unroll
+    for (int s = 0; s < 2 * PFP; ++s) {
+#pragma unroll
+      for (int m = 0; m < NRAW; ++m) pre[s][m] = 0u;
+      if (s < nr) In::load(X + (int64_t)s * ldx, glb_off, pre[s]);
+    }
+  }
+  float prm[SPT * NV];
 #pragma unroll
   for (int u = 0; u < SPT; ++u) {
     const unsigned q = (unsigned)t + u * TG;
 #pragma unroll
     for (int v = 0; v < NV; ++v) prm[u * NV + v] = params[(unsigned)v * nq + qoff + q];
-    const unsigned hi = q >> LOGS, lo = q & (S - 1);
-    base[u] = ((hi << K) << LOGS) | lo;
-  }
-  // logical coordinate of element (u, j): base[u] | (j << LOGS) (the bit fields are disjoint)
-  auto lds_off = [&](int e) -> int {
-    const int u = e / P, j = e % P;
-    return phys_index((int)(base[u] | ((unsigned)j << LOGS)));
-  };
-  auto glb_off = [&](int e) -> unsigned {   // element offset inside the chunk
-    const int u = e / P, j = e % P;
-    return base[u] | ((unsigned)j << LOGS);
-  };
-
-  // ---- ROLE 0: prefetch the first rows (raw dwords, converted when consumed)
-  uint32_t pre[PF][NRAW];
-  if (ROLE == 0) {
-#pragma unroll
-    for (int s = 0; s < PF; ++s)
-      if (s < nr) In::load(X + (int64_t)s * ldx, glb_off, pre[s]);
   }
 
-  // The step loop is unrolled by UNR so that prefetch slots, buffer parities and the two
-  // register sets of the optional LDS read-ahead are static.  Without read-ahead group g
-  // reads and computes row k-g at step k (nr + 2 steps); with it group 1 reads row k-1 and
-  // computes row k-2, group 2 reads row k-3 and computes row k-4 (nr + 4 steps).  One barrier
-  // per step.
-  constexpr int UNR = (ROLE == 0) ? (PF % 2 ? 2 * PF : PF) : 2;
-  constexpr int RD_LAG = READ_AHEAD ? ((ROLE == 0) ? 0 : (ROLE == 1 ? 1 : 3)) : ROLE;
-  const int nsteps = nr + (READ_AHEAD ? 4 : 2);
-  float xa[16], xb[16];
-  for (int k0 = 0; k0 < nsteps; k0 += UNR) {
+  auto lds_read = [&](const float *b, float (&x)[16]) {
+    if (CONTIG) {
 #pragma unroll
-    for (int s = 0; s < UNR; ++s) {
+      for (int c = 0; c < 4; ++c) {
+        const float4 f = *reinterpret_cast<const float4 *>(b + lds_off(4 * c));
+        x[4 * c] = f.x; x[4 * c + 1] = f.y; x[4 * c + 2] = f.z; x[4 * c + 3] = f.w;
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) x[e] = b[lds_off(e)];
+    }
+  };
+  auto lds_write = [&](float *b, const float (&x)[16]) {
+    if (CONTIG) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+        *reinterpret_cast<float4 *>(b + lds_off(4 * c)) =
+            make_float4(x[4 * c], x[4 * c + 1], x[4 * c + 2], x[4 * c + 3]);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) b[lds_off(e)] = x[e];
+    }
+  };
+
+  const int npairs = (nr + 1) >> 1;
+  const int nsteps = npairs + 2;   // group g works on pair k - g at step k; one barrier per step
+  for (int k0 = 0; k0 < nsteps; k0 += 2) {
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
       const int k = k0 + s;
       if (k >= nsteps) break;
-      float(&xn)[16] = (s & 1) ? xb : xa;   // filled in this step
-      float(&xc)[16] = (ROLE == 0 || !READ_AHEAD) ? xn : ((s & 1) ? xa : xb);   // computed now
-      const int r_rd = k - RD_LAG;
-      const int r_cp = (ROLE == 0 || !READ_AHEAD) ? r_rd : r_rd - 1;
-      if (r_rd >= 0 && r_rd < nr) {
+      const int pr = k - ROLE;
+      if (pr >= 0 && pr < npairs) {
+        const int r0 = 2 * pr;
+        const bool two = r0 + 1 < nr;
+        float xa[16], xb[16];
         if (ROLE == 0) {
-          const int slot = s % PF;
-          In::unpack(pre[slot], xn);
-          if (r_rd + PF < nr) In::load(X + (int64_t)(r_rd + PF) * ldx, glb_off, pre[slot]);
+          const int slot = (PFP == 2) ? 2 * s : 0;   // pair index parity == step parity here
+          In::unpack(pre[slot], xa);
+          In::unpack(pre[slot + 1], xb);
+          const int rn = r0 + 2 * PFP;
+          if (rn < nr) In::load(X + (int64_t)rn * ldx, glb_off, pre[slot]);
+          if (rn + 1 < nr) In::load(X + (int64_t)(rn + 1) * ldx, glb_off, pre[slot + 1]);
         } else {
-          const float *b = rd_buf + ((s + 1) & 1) * ROWBUF;   // written in step k - 1
-          if (CONTIG) {
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-              const float4 f = *reinterpret_cast<const float4 *>(b + lds_off(4 * c));
-              xn[4 * c] = f.x; xn[4 * c + 1] = f.y; xn[4 * c + 2] = f.z; xn[4 * c + 3] = f.w;
-            }
-          } else {
-#pragma unroll
-            for (int e = 0; e < 16; ++e) xn[e] = b[lds_off(e)];
-          }
+          const float *b = rd_buf + ((s + 1) & 1) * (2 * ROWBUF);   // written in step k - 1
+          lds_read(b, xa);
+          lds_read(b + ROWBUF, xb);
         }
-      }
-      if (r_cp >= 0 && r_cp < nr) {
-        lift_stages<K, DESC, LD, SC>(xc, prm);
+        float *wb = (ROLE == 2) ? nullptr : wr_buf + (s & 1) * (2 * ROWBUF);
+        lift_stages<K, DESC, LD, SC>(xa, prm);
+        if (ROLE == 2) Out::store(Y + (int64_t)r0 * ldy, glb_off, xa);
+        else lds_write(wb, xa);
+        lift_stages<K, DESC, LD, SC>(xb, prm);
         if (ROLE == 2) {
-          Out::store(Y + (int64_t)r_cp * ldy, glb_off, xc);
+          if (two) Out::store(Y + (int64_t)(r0 + 1) * ldy, glb_off, xb);
         } else {
-          float *b = wr_buf + (s & 1) * ROWBUF;               // read by the next group in step k + 1
-          if (CONTIG) {
-#pragma unroll
-            for (int c = 0; c < 4; ++c)
-              *reinterpret_cast<float4 *>(b + lds_off(4 * c)) =
-                  make_float4(xc[4 * c], xc[4 * c + 1], xc[4 * c + 2], xc[4 * c + 3]);
-          } else {
-#pragma unroll
-            for (int e = 0; e < 16; ++e) b[lds_off(e)] = xc[e];
-          }
+          lds_write(wb + ROWBUF, xb);
         }
       }
       __syncthreads();
@@ -311,8 +322,8 @@ __global__ __launch_bounds__(3 << (K0 + K1 + K2 - 4)) void harp_pipe_kernel(
     const TI *__restrict__ X, int64_t ldx, TO *__restrict__ Y, int64_t ldy, int64_t n, int R,
     int nchunk, const Program *__restrict__ progp, int p0) {
   constexpr int D = 1 << (K0 + K1 + K2), TG = D / 16, ROWBUF = (D / 256) * 272;
-  __shared__ float bufA[2 * ROWBUF];
-  __shared__ float bufB[2 * ROWBUF];
+  __shared__ float bufA[4 * ROWBUF];
+  __shared__ float bufB[4 * ROWBUF];
   const int g = __builtin_amdgcn_readfirstlane((int)threadIdx.x / TG);  // wave-uniform
   const int t = (int)threadIdx.x % TG;
   const int kch = (int)(blockIdx.x % (unsigned)nchunk);
@@ -324,14 +335,14 @@ __global__ __launch_bounds__(3 << (K0 + K1 + K2 - 4)) void harp_pipe_kernel(
   // stride of each pass's lowest digit: ascending for apply, descending for apply_transpose
   constexpr int LS0 = TRN ? K1 + K2 : 0, LS1 = TRN ? K2 : K0, LS2 = TRN ? 0 : K0 + K1;
   if (g == 0)
-    pipe_group<TI, TO, K0, LS0, TRN, 0, false, SC, D>(prog.pass[p0], t, kch, nullptr, bufA, Xt, ldx,
-                                                  Yt, ldy, nr);
+    pipe_group<TI, TO, K0, LS0, TRN, 0, false, SC, D>(prog.pass[p0], t, kch, nullptr, bufA, Xt,
+                                                       ldx, Yt, ldy, nr);
   else if (g == 1)
-    pipe_group<TI, TO, K1, LS1, TRN, 1, false, SC, D>(prog.pass[p0 + 1], t, kch, bufA, bufB, Xt, ldx,
-                                                  Yt, ldy, nr);
+    pipe_group<TI, TO, K1, LS1, TRN, 1, false, SC, D>(prog.pass[p0 + 1], t, kch, bufA, bufB, Xt,
+                                                       ldx, Yt, ldy, nr);
   else
-    pipe_group<TI, TO, K2, LS2, TRN, 2, LD, SC, D>(prog.pass[p0 + 2], t, kch, bufB, nullptr, Xt, ldx,
-                                               Yt, ldy, nr);
+    pipe_group<TI, TO, K2, LS2, TRN, 2, LD, SC, D>(prog.pass[p0 + 2], t, kch, bufB, nullptr, Xt,
+                                                    ldx, Yt, ldy, nr);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -358,7 +369,7 @@ struct WavePass {
       const unsigned qg = (unsigned)kg * (1024 / P) + ql;
       const bool ok = with_params && qg < nq;
 #pragma unroll
-      for (int v = 0; v < NV; ++v) prm[u * NV + v] = ok ? pd.params[(unsigned)v * nq + qg] : 0.0f;
+      for (int v = 0; v < NV; ++v) prm[u * NV + v] = ok ? ((gparams_t)pd.params)[(unsigned)v * nq + qg] : 0.0f;
       const unsigned hi = ql >> LOGS, lo = ql & (S - 1);
       base[u] = ((hi << K) << LOGS) | lo;
     }
