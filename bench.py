@@ -28,7 +28,8 @@ HBM_PEAK_GBS = 8000.0
 KERNEL_SYMBOL = {"pipe_radix2": "harp_pipe_kernel", "tile_fused": "harp_tile_kernel",
                  "tile_generic": "harp_tile_kernel", "split_pipe_stream": "harp_pipe_kernel",
                  "split_chunk_stream": "harp_tile_kernel", "wave_radix2": "harp_wave_kernel",
-                 "split_wave_stream": "harp_wave_kernel"}
+                 "split_wave_stream": "harp_wave_kernel", "radix_tile": "harp_radix_kernel",
+                 "split_radix_stream": "harp_radix_kernel"}
 
 
 def cpu_baseline(w, sample_rows: int):

@@ -365,6 +365,9 @@ harp_status_t run_chunk_passes(const harp_plan_t *plan, const HostProgram &hp, i
   if (wave_supported(plan, hp.prog, p0, p1 - p0, hp.chunk, X, ldx, Y, ldy))
     return launch_wave_kernel(plan, hp, p0, p1 - p0, hp.chunk, X, ldx, dt_in, Y, ldy, dt_out, n,
                               stream);
+  if (radix_supported(plan, hp.prog, p0, p1 - p0, hp.chunk, X, ldx, Y, ldy))
+    return launch_radix_kernel(plan, hp, p0, p1 - p0, hp.chunk, X, ldx, dt_in, Y, ldy, dt_out, n,
+                               stream);
   return launch_tile_kernel(plan, hp.dev, p0, p1, hp.chunk, X, ldx, dt_in, Y, ldy, dt_out, n,
                             stream);
 }
@@ -802,12 +805,17 @@ const char *harp_plan_kernel_name(const harp_plan_t *plan, int64_t n, harp_dtype
   if (hp && hp->n_chunk == hp->prog.npass &&
       wave_supported(plan, hp->prog, 0, hp->prog.npass, hp->chunk, nullptr, 8, nullptr, 8))
     return "wave_radix2";
+  if (hp && hp->n_chunk == hp->prog.npass &&
+      radix_supported(plan, hp->prog, 0, hp->prog.npass, hp->chunk, nullptr, 8, nullptr, 8))
+    return "radix_tile";
   if (hp && hp->n_chunk != hp->prog.npass) {
     const int p0 = hp->chunk_first ? 0 : hp->prog.npass - hp->n_chunk;
     if (pipe_supported(plan, hp->prog, p0, hp->n_chunk, hp->chunk, nullptr, 8, nullptr, 8))
       return "split_pipe_stream";
     if (wave_supported(plan, hp->prog, p0, hp->n_chunk, hp->chunk, nullptr, 8, nullptr, 8))
       return "split_wave_stream";
+    if (radix_supported(plan, hp->prog, p0, hp->n_chunk, hp->chunk, nullptr, 8, nullptr, 8))
+      return "split_radix_stream";
   }
   return nm;
 }

@@ -128,6 +128,13 @@ harp_status_t launch_wave_kernel(const harp_plan *plan, const HostProgram &hp, i
                                  int chunk, const void *X, int64_t ldx, harp_dtype_t dt_in,
                                  void *Y, int64_t ldy, harp_dtype_t dt_out, int64_t n,
                                  hipStream_t stream);
+// tile kernel for chains of equal radix 4 or 8 on chunks of 4^m / 8^m coordinates (harp_radix.hip)
+bool radix_supported(const harp_plan *plan, const Program &prog, int p0, int np, int chunk,
+                     const void *X, int64_t ldx, const void *Y, int64_t ldy);
+harp_status_t launch_radix_kernel(const harp_plan *plan, const HostProgram &hp, int p0, int np,
+                                  int chunk, const void *X, int64_t ldx, harp_dtype_t dt_in,
+                                  void *Y, int64_t ldy, harp_dtype_t dt_out, int64_t n,
+                                  hipStream_t stream);
 int choose_pipe_rows(const harp_plan *plan, int64_t n, int64_t nchunk, int chunk);
 const HostProgram *select_program(const harp_plan *plan, Direction dir, int64_t n,
                                   const char **name);

@@ -353,7 +353,8 @@ __global__ __launch_bounds__(3 << (K0 + K1 + K2 - 4)) void harp_pipe_kernel(
 // passes of its 16 coordinates in registers (128..176 values), so they are read once per
 // workgroup; a row is loaded with 16-byte accesses (next row prefetched), goes through the 2 or
 // 3 passes with an LDS exchange between them (private to the wave: no other wave waits), and
-// is stored with 16-byte accesses.  Used for the 2^8 part of d = 11008 = 2^8 * 43 and for
+// is stored with 16-byte accesses (when the last pass is a strided one, the last exchange puts
+// the row into a layout in which every store instruction writes 1 KB of consecutive addresses).  Used for the 2^8 part of d = 11008 = 2^8 * 43 and for
 // short rows.
 template <int K, int LOGS, bool LD>
 struct WavePass {
@@ -378,6 +379,46 @@ struct WavePass {
     return base[e / P] | ((unsigned)(e % P) << LOGS);
   }
 };
+
+// Store layout of the wave kernel: a thread's 16 elements are 16-byte pieces (PIECE = 4 float32
+// or 8 bf16 coordinates) placed so that one store instruction of the wave writes 1 KB of
+// consecutive addresses: element e <-> coordinate (e / PIECE) * 64 * PIECE + PIECE * t + e % PIECE
+// of the 1024-coordinate window.
+template <typename TO>
+struct WaveStoreLayout {
+  static constexpr int PIECE = 16 / (int)sizeof(TO), NP = 16 / PIECE;
+  static constexpr int S = 1, P = PIECE;   // contiguous groups of >= 4: 16-byte LDS reads
+  unsigned t;
+  __device__ __forceinline__ unsigned coord(int e) const {
+    return (unsigned)(e / PIECE) * (64u * PIECE) + (unsigned)PIECE * t + (unsigned)(e % PIECE);
+  }
+  // pieces whose coordinates lie inside the row (valid = coordinates of the window inside it)
+  __device__ __forceinline__ void store(TO *yw, const float (&x)[16], int valid) const;
+};
+template <>
+__device__ __forceinline__ void WaveStoreLayout<float>::store(float *yw, const float (&x)[16],
+                                                              int valid) const {
+#pragma unroll
+  for (int g = 0; g < NP; ++g) {
+    const unsigned c = coord(PIECE * g);
+    if ((int)c < valid)
+      *reinterpret_cast<float4 *>(yw + c) =
+          make_float4(x[4 * g], x[4 * g + 1], x[4 * g + 2], x[4 * g + 3]);
+  }
+}
+template <>
+__device__ __forceinline__ void WaveStoreLayout<uint16_t>::store(uint16_t *yw,
+                                                                 const float (&x)[16],
+                                                                 int valid) const {
+#pragma unroll
+  for (int g = 0; g < NP; ++g) {
+    const unsigned c = coord(PIECE * g);
+    if ((int)c < valid)
+      *reinterpret_cast<uint4 *>(yw + c) =
+          make_uint4(cvt_pk_bf16(x[8 * g], x[8 * g + 1]), cvt_pk_bf16(x[8 * g + 2], x[8 * g + 3]),
+                     cvt_pk_bf16(x[8 * g + 4], x[8 * g + 5]), cvt_pk_bf16(x[8 * g + 6], x[8 * g + 7]));
+  }
+}
 
 // x leaves layout A and comes back in layout B through the wave's LDS buffer
 template <class PA, class PB>
@@ -429,6 +470,9 @@ __global__ __launch_bounds__(64) void harp_wave_kernel(const TI *__restrict__ X,
   pb.init(prog.pass[p0 + 1], t, kg, true);
   if (THREE) pc.init(prog.pass[p0 + 2], t, kg, true);
   io.init(prog.pass[p0], t, kg, false);
+  WaveStoreLayout<TO> sl{(unsigned)t};
+  // the last pass leaves the row in the load layout only when it is the (4 stages, stride 1) one
+  constexpr bool kLastIsIo = THREE ? (K2 == 4 && LS2 == 0) : (K1 == 4 && LS1 == 0);
   const bool active = 16 * t < valid;
   auto goff = [&](int e) -> unsigned { return (unsigned)w0 + io.coord(e); };
 
@@ -459,11 +503,15 @@ __global__ __launch_bounds__(64) void harp_wave_kernel(const TI *__restrict__ X,
       if (THREE) {
         wave_exchange(x, buf, pb, pc);
         lift_stages<(THREE ? K2 : 1), TRN, (THREE && LD), SC>(x, pc.prm);
-        if (!(K2 == 4 && LS2 == 0)) wave_exchange(x, buf, pc, io);
+        if (!kLastIsIo) wave_exchange(x, buf, pc, sl);
       } else {
-        if (!(K1 == 4 && LS1 == 0)) wave_exchange(x, buf, pb, io);
+        if (!kLastIsIo) wave_exchange(x, buf, pb, sl);
       }
-      if (active) Out::store(Y + (row0 + r) * ldy, goff, x);
+      if (kLastIsIo) {
+        if (active) Out::store(Y + (row0 + r) * ldy, goff, x);
+      } else {
+        sl.store(Y + (row0 + r) * ldy + w0, x, valid);
+      }
     }
   }
 }

@@ -1,0 +1,362 @@
+// Tile kernel for chains of equal small radices (all stages radix 4 or all radix 8, e.g. the
+// 4 x radix-8 schedule of d = 4096): rows, or contiguous row chunks, of B^m coordinates.
+//
+// A dense B x B block costs B^2 parameters per B coordinates, so the parameters of a whole row
+// (0.5 MB for 4096 = 8^4) do not fit the register file of a compute unit: they are re-read for
+// every tile of R rows, and the kernel is organised to hide that.  A workgroup keeps R <= 8 rows
+// in LDS as float32; in stage t thread q owns block c = q of the stage (Alg. 1: coordinates
+// base(q) + j * S, S = B^t the stride of the stage), holds its B^2 values in registers for all
+// rows of the tile, and while it works on stage t the loads of its block of stage t+1 are
+// already in flight.  The first stage takes its inputs straight from device memory (all rows of
+// the tile requested at once) and the last stage stores straight to device memory, so a tile
+// makes m - 1 LDS round trips and m barriers.  LDS rows are padded by 8 floats per 64 so that
+// the stride-B accesses of the second stage fall into distinct banks.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "harp_internal.h"
+
+namespace harp {
+
+namespace {
+
+constexpr int kRMax = 8;   // rows per tile (compile-time bound of the prefetch registers)
+
+typedef const __attribute__((address_space(1))) float *gfloat_t;
+
+__device__ __forceinline__ int lds_pos(int i) { return i + ((i >> 6) << 3); }
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+  bf2 v;
+  v.x = (__bf16)lo;
+  v.y = (__bf16)hi;
+  return __builtin_bit_cast(uint32_t, v);
+}
+
+// B elements of one block of one row, from device memory: contiguous (S == 1) or at stride S
+template <typename T, int B>
+struct BlockIo;
+
+template <int B>
+struct BlockIo<uint16_t, B> {
+  static constexpr int NRAW = B;   // contiguous: B / 2 dwords used; strided: one element per dword
+  template <bool C>
+  __device__ static __forceinline__ void load(const uint16_t *p, int S, uint32_t (&raw)[NRAW]) {
+    if (C) {
+      if (B == 8) {
+        const uint4 v = *reinterpret_cast<const uint4 *>(p);
+        raw[0] = v.x; raw[1] = v.y; raw[2] = v.z; raw[3] = v.w;
+      } else {
+        const uint2 v = *reinterpret_cast<const uint2 *>(p);
+        raw[0] = v.x; raw[1] = v.y;
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < B; ++j) raw[j] = p[(size_t)j * S];
+    }
+  }
+  template <bool C>
+  __device__ static __forceinline__ void unpack(const uint32_t (&raw)[NRAW], float (&x)[B]) {
+    if (C) {
+#pragma unroll
+      for (int m = 0; m < B / 2; ++m) {
+        x[2 * m] = __uint_as_float(raw[m] << 16);
+        x[2 * m + 1] = __uint_as_float(raw[m] & 0xffff0000u);
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < B; ++j) x[j] = __uint_as_float(raw[j] << 16);
+    }
+  }
+  template <bool C>
+  __device__ static __forceinline__ void store(uint16_t *p, int S, const float (&y)[B]) {
+    uint32_t w[B / 2];
+#pragma unroll
+    for (int m = 0; m < B / 2; ++m) w[m] = pack_bf16(y[2 * m], y[2 * m + 1]);
+    if (C) {
+      if (B == 8) *reinterpret_cast<uint4 *>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+      else *reinterpret_cast<uint2 *>(p) = make_uint2(w[0], w[1]);
+    } else {
+#pragma unroll
+      for (int m = 0; m < B / 2; ++m) {
+        p[(size_t)(2 * m) * S] = (uint16_t)(w[m] & 0xffffu);
+        p[(size_t)(2 * m + 1) * S] = (uint16_t)(w[m] >> 16);
+      }
+    }
+  }
+};
+
+template <int B>
+struct BlockIo<float, B> {
+  static constexpr int NRAW = B;
+  template <bool C>
+  __device__ static __forceinline__ void load(const float *p, int S, uint32_t (&raw)[NRAW]) {
+    if (C) {
+#pragma unroll
+      for (int h = 0; h < B / 4; ++h) {
+        const uint4 v = *reinterpret_cast<const uint4 *>(p + 4 * h);
+        raw[4 * h] = v.x; raw[4 * h + 1] = v.y; raw[4 * h + 2] = v.z; raw[4 * h + 3] = v.w;
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < B; ++j) raw[j] = __float_as_uint(p[(size_t)j * S]);
+    }
+  }
+  template <bool C>
+  __device__ static __forceinline__ void unpack(const uint32_t (&raw)[NRAW], float (&x)[B]) {
+#pragma unroll
+    for (int j = 0; j < B; ++j) x[j] = __uint_as_float(raw[j]);
+  }
+  template <bool C>
+  __device__ static __forceinline__ void store(float *p, int S, const float (&y)[B]) {
+    if (C) {
+#pragma unroll
+      for (int h = 0; h < B / 4; ++h)
+        *reinterpret_cast<float4 *>(p + 4 * h) =
+            make_float4(y[4 * h], y[4 * h + 1], y[4 * h + 2], y[4 * h + 3]);
+    } else {
+#pragma unroll
+      for (int j = 0; j < B; ++j) p[(size_t)j * S] = y[j];
+    }
+  }
+};
+
+// y = x * K (row vector on the left), K row-major in prm
+template <int B>
+__device__ __forceinline__ void block_mul(const float (&x)[B], const float (&prm)[B * B],
+                                          float (&y)[B]) {
+#pragma unroll
+  for (int c = 0; c < B; ++c) y[c] = x[0] * prm[c];
+#pragma unroll
+  for (int r = 1; r < B; ++r)
+#pragma unroll
+    for (int c = 0; c < B; ++c) y[c] = fmaf(x[r], prm[r * B + c], y[c]);
+}
+
+// One stage on the rows of the tile.  MODE 0: inputs from the prefetched device-memory words
+// `raw`, outputs to LDS; 1: LDS in place; 2: inputs from LDS, outputs to device memory.
+// CONTIG: the stage's stride is 1 (16-byte accesses); it can only be the first or last stage.
+template <typename TI, typename TO, int B, int BPT, int MODE, bool CONTIG>
+__device__ __forceinline__ void radix_pass(float *tile, int dpad, int nr, int S, int tid, int NT,
+                                           const float (&prm)[BPT][B * B],
+                                           const uint32_t (&raw)[kRMax][BPT][B], TO *Yt,
+                                           int64_t ldy) {
+  using In = BlockIo<TI, B>;
+  using Out = BlockIo<TO, B>;
+  int base[BPT];
+#pragma unroll
+  for (int u = 0; u < BPT; ++u) {
+    const int q = tid + u * NT, hi = q / S, lo = q - hi * S;
+    base[u] = hi * B * S + lo;
+  }
+#pragma unroll
+  for (int r = 0; r < kRMax; ++r) {
+    if (r < nr) {
+      float *trow = tile + r * dpad;
+#pragma unroll
+      for (int u = 0; u < BPT; ++u) {
+        float x[B], y[B];
+        if (MODE == 0) {
+          In::template unpack<CONTIG>(raw[r][u], x);
+        } else if (CONTIG) {
+#pragma unroll
+          for (int h = 0; h < B / 4; ++h) {
+            const float4 f = *reinterpret_cast<const float4 *>(trow + lds_pos(base[u] + 4 * h));
+            x[4 * h] = f.x; x[4 * h + 1] = f.y; x[4 * h + 2] = f.z; x[4 * h + 3] = f.w;
+          }
+        } else {
+#pragma unroll
+          for (int j = 0; j < B; ++j) x[j] = trow[lds_pos(base[u] + j * S)];
+        }
+        block_mul<B>(x, prm[u], y);
+        if (MODE == 2) {
+          Out::template store<CONTIG>(Yt + (int64_t)r * ldy + base[u], S, y);
+        } else if (CONTIG) {
+#pragma unroll
+          for (int h = 0; h < B / 4; ++h)
+            *reinterpret_cast<float4 *>(trow + lds_pos(base[u] + 4 * h)) =
+                make_float4(y[4 * h], y[4 * h + 1], y[4 * h + 2], y[4 * h + 3]);
+        } else {
+#pragma unroll
+          for (int j = 0; j < B; ++j) trow[lds_pos(base[u] + j * S)] = y[j];
+        }
+      }
+    }
+  }
+}
+
+// Passes prog.pass[p0 .. p0+np), np >= 2, are single stages of radix B with strides that are
+// powers of B inside the chunk, ascending (TRN false: the first stage has stride 1) or
+// descending (TRN: the last one has).  blockDim.x * BPT = chunk / B blocks per stage and row.
+template <typename TI, typename TO, int B, int BPT, bool TRN>
+__global__ __launch_bounds__(512) void harp_radix_kernel(const TI *__restrict__ X, int64_t ldx,
+                                                         TO *__restrict__ Y, int64_t ldy,
+                                                         int64_t n, int R, int nchunk, int chunk,
+                                                         const Program *__restrict__ progp, int p0,
+                                                         int np) {
+  extern __shared__ float tile[];
+  constexpr int V = B * B;
+  using In = BlockIo<TI, B>;
+  const int tid = threadIdx.x, NT = blockDim.x;
+  const int kch = (int)(blockIdx.x % (unsigned)nchunk);
+  const int64_t row0 = (int64_t)(blockIdx.x / (unsigned)nchunk) * R;
+  const int nr = (int)((n - row0 < R) ? (n - row0) : R);
+  const int dpad = lds_pos(chunk);
+  const int nqc = chunk / B;   // blocks per stage in one chunk
+  const Program &prog = *progp;
+  const TI *Xt = X + row0 * ldx + (int64_t)kch * chunk;
+  TO *Yt = Y + row0 * ldy + (int64_t)kch * chunk;
+
+  float cur[BPT][V], nxt[BPT][V];
+  auto load_params = [&](const PassDesc &pd, float (&dst)[BPT][V]) {
+    const gfloat_t params = (gfloat_t)pd.params;
+    const unsigned nq = (unsigned)pd.nq;
+#pragma unroll
+    for (int u = 0; u < BPT; ++u) {
+      const unsigned qg = (unsigned)kch * nqc + tid + u * NT;
+#pragma unroll
+      for (int v = 0; v < V; ++v) dst[u][v] = params[(unsigned)v * nq + qg];
+    }
+  };
+
+  // first stage: every row of the tile is requested before the parameters are waited for
+  const int S0 = prog.pass[p0].S;
+  uint32_t raw[kRMax][BPT][B];
+#pragma unroll
+  for (int u = 0; u < BPT; ++u) {
+    const int q = tid + u * NT, hi = q / S0, lo = q - hi * S0;
+    const int base0 = hi * B * S0 + lo;
+#pragma unroll
+    for (int r = 0; r < kRMax; ++r) {
+#pragma unroll
+      for (int m = 0; m < B; ++m) raw[r][u][m] = 0u;
+      if (r < nr) In::template load<!TRN>(Xt + (int64_t)r * ldx + base0, S0, raw[r][u]);
+    }
+  }
+  load_params(prog.pass[p0], cur);
+  load_params(prog.pass[p0 + 1], nxt);     // in flight during the first stage
+  radix_pass<TI, TO, B, BPT, 0, !TRN>(tile, dpad, nr, S0, tid, NT, cur, raw, Yt, ldy);
+  __syncthreads();
+  for (int p = 1; p < np - 1; ++p) {
+#pragma unroll
+    for (int u = 0; u < BPT; ++u)
+#pragma unroll
+      for (int v = 0; v < V; ++v) cur[u][v] = nxt[u][v];
+    load_params(prog.pass[p0 + p + 1], nxt);
+    radix_pass<TI, TO, B, BPT, 1, false>(tile, dpad, nr, prog.pass[p0 + p].S, tid, NT, cur, raw, Yt, ldy);
+    __syncthreads();
+  }
+  radix_pass<TI, TO, B, BPT, 2, TRN>(tile, dpad, nr, prog.pass[p0 + np - 1].S, tid, NT, nxt, raw, Yt,
+                                ldy);
+}
+
+struct RadixShape {
+  int B, np, nt, bpt;
+  bool trn, ok;
+};
+
+RadixShape radix_decode(const Program &pg, int p0, int np, int chunk) {
+  RadixShape rs{0, np, 0, 0, false, false};
+  if (np < 2 || np > 6) return rs;
+  const PassDesc *ps = pg.pass + p0;
+  const int B = ps[0].b;
+  if (B != 4 && B != 8) return rs;
+  int64_t prod = 1;
+  for (int p = 0; p < np; ++p) {
+    if (ps[p].kind != PASS_SMALL || ps[p].b != B) return rs;
+    prod *= B;
+  }
+  if (prod != chunk) return rs;
+  // strides: the powers of B below the chunk, ascending or descending
+  rs.trn = ps[0].S != 1;
+  int64_t s = 1;
+  for (int p = 0; p < np; ++p) {
+    if (ps[rs.trn ? np - 1 - p : p].S != s) return rs;
+    s *= B;
+  }
+  const int nqc = chunk / B;
+  int nt = nqc < 512 ? nqc : 512;
+  if (nt < 64 || nqc % nt) return rs;
+  const int bpt = nqc / nt;
+  if (bpt != 1 && bpt != 2) return rs;
+  if (B == 8 && bpt != 1) return rs;
+  rs.B = B;
+  rs.nt = nt;
+  rs.bpt = bpt;
+  rs.ok = true;
+  return rs;
+}
+
+template <typename TI, typename TO, int B, int BPT, bool TRN>
+harp_status_t launch_radix_inst(const harp_plan *plan, const HostProgram &hp, int p0, int np,
+                                int chunk, int nt, const void *X, int64_t ldx, void *Y,
+                                int64_t ldy, int64_t n, hipStream_t stream) {
+  const int dpad = chunk + (chunk >> 6) * 8;
+  int R = kRMax;
+  while (R > 1 && (size_t)R * dpad * 4 > (size_t)plan->lds_bytes) --R;
+  if ((size_t)R * dpad * 4 > (size_t)plan->lds_bytes) return HARP_ERR_UNSUPPORTED;
+  if (plan->rows_override > 0 && plan->rows_override < R) R = plan->rows_override;
+  if (R > n) R = (int)n;
+  const int nchunk = (int)(plan->d / chunk);
+  const int64_t tiles = ((n + R - 1) / R) * nchunk;
+  if (tiles > 0x7fffffff) return HARP_ERR_UNSUPPORTED;
+  const size_t lds = (size_t)R * dpad * 4;
+  auto kern = harp_radix_kernel<TI, TO, B, BPT, TRN>;
+  static thread_local int attr_done_dev = -1;   // per instantiation
+  if (attr_done_dev != plan->device) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                            hipFuncAttributeMaxDynamicSharedMemorySize,
+                            plan->lds_bytes) != hipSuccess) {
+      (void)hipGetLastError();
+      return HARP_ERR_DEVICE;
+    }
+    attr_done_dev = plan->device;
+  }
+  hipLaunchKernelGGL(kern, dim3((unsigned)tiles), dim3(nt), lds, stream, (const TI *)X, ldx,
+                     (TO *)Y, ldy, n, R, nchunk, chunk, hp.dev, p0, np);
+  return hipGetLastError() == hipSuccess ? HARP_OK : HARP_ERR_DEVICE;
+}
+
+template <typename TI, typename TO>
+harp_status_t launch_radix_io(const harp_plan *plan, const HostProgram &hp, int p0,
+                              const RadixShape &rs, int chunk, const void *X, int64_t ldx, void *Y,
+                              int64_t ldy, int64_t n, hipStream_t stream) {
+#define HARP_RADIX_CASE(B_, BPT_)                                                              \
+  (rs.trn ? launch_radix_inst<TI, TO, B_, BPT_, true>(plan, hp, p0, rs.np, chunk, rs.nt, X, ldx, \
+                                                      Y, ldy, n, stream)                         \
+          : launch_radix_inst<TI, TO, B_, BPT_, false>(plan, hp, p0, rs.np, chunk, rs.nt, X,     \
+                                                       ldx, Y, ldy, n, stream))
+  if (rs.B == 8) return HARP_RADIX_CASE(8, 1);
+  if (rs.bpt == 1) return HARP_RADIX_CASE(4, 1);
+  return HARP_RADIX_CASE(4, 2);
+#undef HARP_RADIX_CASE
+}
+
+}  // namespace
+
+bool radix_supported(const harp_plan *plan, const Program &pg, int p0, int np, int chunk,
+                     const void *X, int64_t ldx, const void *Y, int64_t ldy) {
+  if (plan->algo == HARP_ALGO_GENERIC) return false;
+  if (!radix_decode(pg, p0, np, chunk).ok) return false;
+  // 16-byte accesses of the contiguous stage for either element type
+  if ((ldx % 8) || (ldy % 8) || ((uintptr_t)X % 16) || ((uintptr_t)Y % 16)) return false;
+  return (size_t)(chunk + (chunk >> 6) * 8) * 4 <= (size_t)plan->lds_bytes;
+}
+
+harp_status_t launch_radix_kernel(const harp_plan *plan, const HostProgram &hp, int p0, int np,
+                                  int chunk, const void *X, int64_t ldx, harp_dtype_t dt_in,
+                                  void *Y, int64_t ldy, harp_dtype_t dt_out, int64_t n,
+                                  hipStream_t stream) {
+  const RadixShape rs = radix_decode(hp.prog, p0, np, chunk);
+  if (!rs.ok) return HARP_ERR_UNSUPPORTED;
+  if (dt_in == HARP_BF16 && dt_out == HARP_BF16)
+    return launch_radix_io<uint16_t, uint16_t>(plan, hp, p0, rs, chunk, X, ldx, Y, ldy, n, stream);
+  if (dt_in == HARP_BF16 && dt_out == HARP_F32)
+    return launch_radix_io<uint16_t, float>(plan, hp, p0, rs, chunk, X, ldx, Y, ldy, n, stream);
+  if (dt_in == HARP_F32 && dt_out == HARP_BF16)
+    return launch_radix_io<float, uint16_t>(plan, hp, p0, rs, chunk, X, ldx, Y, ldy, n, stream);
+  return launch_radix_io<float, float>(plan, hp, p0, rs, chunk, X, ldx, Y, ldy, n, stream);
+}
+
+}  // namespace harp

@@ -388,6 +388,47 @@ def test_split_is_refused_when_there_is_nothing_to_split(harp):
 
 
 # ------------------------------------------------------------------ config 4: decode regime
+RADIX_TILE_CASES = [
+    (512, [8] * 3, 19), (4096, [8] * 4, 37), (4096, [8] * 4, 1), (256, [4] * 4, 9), (1024, [4] * 5, 21),
+    (4096, [4] * 6, 13), (4096, [8] * 4, 8),
+]
+
+
+@pytest.mark.parametrize("d,radices,n", RADIX_TILE_CASES)
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_equal_small_radix_tile_kernel(harp, d, radices, n, dtype):
+    """All stages radix 4 or all radix 8: the tile kernel with prefetched block parameters."""
+    blocks = gi.make_blocks(d, radices, "qr", np.random.default_rng(1))
+    plan = harp.Plan(d, radices, blocks, None)
+    assert plan.kernel_name(n) == "radix_tile", plan.kernel_name(n)
+    plan.destroy()
+    run_case(harp, d, radices, n, dtype, kind="qr", seed=d + n)
+    run_case(harp, d, radices, n, dtype, kind="orth", seed=d + n + 1, ld_pad=8, with_signs=False)
+    run_case(harp, d, radices, n, dtype, kind="qr", seed=d + n + 2, ld_pad=3)   # unaligned: fallback
+
+
+@pytest.mark.parametrize("d,radices,n", [(28672, [8, 8, 8, 8, 7], 70), (768, [4, 4, 4, 4, 3], 65),
+                                         (5120, [8, 8, 8, 5, 2], 66)])
+def test_split_program_with_small_radix_chunk(harp, d, radices, n):
+    run_case(harp, d, radices, n, "bf16", kind="qr", seed=d)
+
+
+def test_radix_tile_kernel_in_place(harp):
+    import torch
+    d, radices, n = 4096, [8] * 4, 11
+    rng = np.random.default_rng(12)
+    blocks = gi.make_blocks(d, radices, "qr", rng)
+    signs = gi.make_signs(d, rng)
+    X = gi.round_to_bf16(rng.standard_normal((n, d)).astype(np.float32))
+    plan = harp.Plan(d, radices, blocks, signs)
+    say("radix tile in place", plan.kernel_name(n))
+    Xd = to_device(X, "bf16")
+    harp.harp_apply(plan, Xd, Xd)
+    torch.cuda.synchronize()
+    assert_parity(to_host64(Xd), ho.apply_staged(X, d, radices, blocks, signs), "bf16", "apply in place")
+    plan.destroy()
+
+
 @pytest.mark.parametrize("n", [1, 8, 32, 64])
 @pytest.mark.parametrize("d,radices", [(4096, [2] * 12), (12288, [2] * 12 + [3]), (14336, [2] * 11 + [7])])
 def test_decode_regime(harp, n, d, radices):
