@@ -149,11 +149,11 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": args.workload, "n": n, "d": d, "radices": radices,
-                   "io_dtype": w["dtype"], "kernel": plan.kernel_name(), "batches_in_pool": nbuf,
+                   "io_dtype": w["dtype"], "kernel": plan.kernel_name(n), "batches_in_pool": nbuf,
                    "step": "harp_apply + harp_apply_transpose on one batch"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": KERNEL_SYMBOL.get(plan.kernel_name(), plan.kernel_name()), "avg_launch_us": kernel_us,
+                     "kernel": KERNEL_SYMBOL.get(plan.kernel_name(n), plan.kernel_name(n)), "avg_launch_us": kernel_us,
                      "algorithmic_bytes_per_launch": alg_bytes, "param_bytes": param_bytes},
     }
     tpath = os.path.join(ROOT, "profiles", f"traffic_{args.workload}.json")
