@@ -425,75 +425,50 @@ __device__ __forceinline__ void stream_store(void *p, int64_t i, int bf16, float
   else static_cast<float *>(p)[i] = v;
 }
 
-// V adjacent sub-tensors (lo, lo+1) per thread: 4-byte bf16 pairs / 8-byte float pairs.
-template <int V>
-__device__ __forceinline__ void stream_load_v(const void *p, int64_t i, int bf16, float (&v)[V]);
-template <>
-__device__ __forceinline__ void stream_load_v<1>(const void *p, int64_t i, int bf16, float (&v)[1]) {
-  v[0] = stream_load(p, i, bf16);
-}
-template <>
-__device__ __forceinline__ void stream_load_v<2>(const void *p, int64_t i, int bf16, float (&v)[2]) {
-  if (bf16) {
-    const uint32_t w = *reinterpret_cast<const uint32_t *>(static_cast<const uint16_t *>(p) + i);
-    v[0] = __uint_as_float(w << 16);
-    v[1] = __uint_as_float(w & 0xffff0000u);
-  } else {
-    const float2 f = *reinterpret_cast<const float2 *>(static_cast<const float *>(p) + i);
-    v[0] = f.x;
-    v[1] = f.y;
-  }
-}
-template <int V>
-__device__ __forceinline__ void stream_store_v(void *p, int64_t i, int bf16, const float (&v)[V]);
-template <>
-__device__ __forceinline__ void stream_store_v<1>(void *p, int64_t i, int bf16, const float (&v)[1]) {
-  stream_store(p, i, bf16, v[0]);
-}
-template <>
-__device__ __forceinline__ void stream_store_v<2>(void *p, int64_t i, int bf16, const float (&v)[2]) {
-  if (bf16)
-    *reinterpret_cast<uint32_t *>(static_cast<uint16_t *>(p) + i) = pack_bf16x2(v[0], v[1]);
-  else
-    *reinterpret_cast<float2 *>(static_cast<float *>(p) + i) = make_float2(v[0], v[1]);
-}
+// element access of the streamed kernels, by element type
+__device__ __forceinline__ float stream_get(const uint16_t *p) { return widen_bf16(*p); }
+__device__ __forceinline__ float stream_get(const float *p) { return *p; }
+__device__ __forceinline__ void stream_put(uint16_t *p, float v) { *p = narrow_bf16(v); }
+__device__ __forceinline__ void stream_put(float *p, float v) { *p = v; }
 
-template <class OP, int V>
-__global__ __launch_bounds__(256) void harp_stream_kernel(const void *__restrict__ X, int64_t ldx,
-                                                          int in_bf16, void *__restrict__ Y,
-                                                          int64_t ldy, int out_bf16, int64_t n,
-                                                          int rows_per_block, PassDesc pd) {
+// One thread per sub-tensor q, walking down its block of rows with the parameters in registers;
+// two rows in flight (the loads of row + 1 are issued before row is computed and stored).
+// Element types are template parameters and all offsets inside a row are 32-bit, so a row
+// costs the arithmetic of the stage plus two pointer increments.
+template <class OP, typename TI, typename TO>
+__global__ __launch_bounds__(256) void harp_stream_kernel(const TI *__restrict__ X, int64_t ldx,
+                                                          TO *__restrict__ Y, int64_t ldy,
+                                                          int64_t n, int rows_per_block,
+                                                          const float *__restrict__ params, int nq,
+                                                          int S) {
   constexpr int P = OP::P, NV = OP::NV;
-  const int nq = pd.nq, S = pd.S;
-  const int q = (blockIdx.x * 256 + threadIdx.x) * V;   // first of V adjacent sub-tensors
+  const int q = blockIdx.x * 256 + threadIdx.x;
   if (q >= nq) return;
-  float prm[V][NV];
+  float prm[NV];
 #pragma unroll
-  for (int u = 0; u < V; ++u)
-#pragma unroll
-    for (int v = 0; v < NV; ++v) prm[u][v] = pd.params[(size_t)v * nq + q + u];
+  for (int v = 0; v < NV; ++v) prm[v] = params[(size_t)v * nq + q];
   const int hi = q / S, lo = q - hi * S;
   const int64_t base = (int64_t)hi * P * S + lo;
   const int64_t r0 = (int64_t)blockIdx.y * rows_per_block;
-  const int64_t r1 = (r0 + rows_per_block < n) ? r0 + rows_per_block : n;
-  for (int64_t row = r0; row < r1; ++row) {
-    float x[V][P];
+  const int nr = (int)((r0 + rows_per_block < n) ? rows_per_block : n - r0);
+  const TI *xp = X + r0 * ldx + base;
+  TO *yp = Y + r0 * ldy + base;
+  float xn[P];
 #pragma unroll
-    for (int j = 0; j < P; ++j) {
-      float v[V];
-      stream_load_v<V>(X, row * ldx + base + (int64_t)j * S, in_bf16, v);
+  for (int j = 0; j < P; ++j) xn[j] = stream_get(xp + (unsigned)(j * S));
+  for (int r = 0; r < nr; ++r) {
+    float x[P];
 #pragma unroll
-      for (int u = 0; u < V; ++u) x[u][j] = v[u];
+    for (int j = 0; j < P; ++j) x[j] = xn[j];
+    xp += ldx;
+    if (r + 1 < nr) {
+#pragma unroll
+      for (int j = 0; j < P; ++j) xn[j] = stream_get(xp + (unsigned)(j * S));
     }
+    OP::apply(x, prm);
 #pragma unroll
-    for (int u = 0; u < V; ++u) OP::apply(x[u], prm[u]);
-#pragma unroll
-    for (int j = 0; j < P; ++j) {
-      float v[V];
-#pragma unroll
-      for (int u = 0; u < V; ++u) v[u] = x[u][j];
-      stream_store_v<V>(Y, row * ldy + base + (int64_t)j * S, out_bf16, v);
-    }
+    for (int j = 0; j < P; ++j) stream_put(yp + (unsigned)(j * S), x[j]);
+    yp += ldy;
   }
 }
 
@@ -525,10 +500,12 @@ __global__ __launch_bounds__(256) void harp_stream_generic_kernel(
   }
 }
 
-template <class KERN>
-harp_status_t launch_stream_grid(KERN kern, int items, const harp_plan *plan, const PassDesc &pd,
-                                 const void *X, int64_t ldx, int in_bf16, void *Y, int64_t ldy,
-                                 int out_bf16, int64_t n, hipStream_t stream) {
+// grid of the streamed kernels: x = blocks of 256 sub-tensors, y = blocks of rows
+struct StreamGrid {
+  unsigned gx, gy;
+  int rpb;
+};
+StreamGrid stream_grid(int items, const harp_plan *plan, int64_t n) {
   const unsigned gx = (unsigned)((items + 255) / 256);
   // about 8 workgroups per compute unit (occupancy hides the load latency), >= 4 rows each
   const int wgs = env_int("HARP_STREAM_WGS_PER_CU", 8), minrows = env_int("HARP_STREAM_MIN_ROWS", 4);
@@ -538,24 +515,40 @@ harp_status_t launch_stream_grid(KERN kern, int items, const harp_plan *plan, co
   if (gy > 65535) gy = 65535;
   const int rpb = (int)((n + gy - 1) / gy);
   gy = (n + rpb - 1) / rpb;
-  hipLaunchKernelGGL(kern, dim3(gx, (unsigned)gy), dim3(256), 0, stream, X, ldx, in_bf16, Y, ldy,
-                     out_bf16, n, rpb, pd);
+  return StreamGrid{gx, (unsigned)gy, rpb};
+}
+
+template <class KERN>
+harp_status_t launch_stream_grid(KERN kern, int items, const harp_plan *plan, const PassDesc &pd,
+                                 const void *X, int64_t ldx, int in_bf16, void *Y, int64_t ldy,
+                                 int out_bf16, int64_t n, hipStream_t stream) {
+  const StreamGrid g = stream_grid(items, plan, n);
+  hipLaunchKernelGGL(kern, dim3(g.gx, g.gy), dim3(256), 0, stream, X, ldx, in_bf16, Y, ldy,
+                     out_bf16, n, g.rpb, pd);
   return hipGetLastError() == hipSuccess ? HARP_OK : HARP_ERR_DEVICE;
 }
 
+template <class OP, typename TI, typename TO>
+harp_status_t launch_stream_typed(const harp_plan *plan, const PassDesc &pd, const void *X,
+                                  int64_t ldx, void *Y, int64_t ldy, int64_t n,
+                                  hipStream_t stream) {
+  const StreamGrid g = stream_grid(pd.nq, plan, n);
+  hipLaunchKernelGGL((harp_stream_kernel<OP, TI, TO>), dim3(g.gx, g.gy), dim3(256), 0, stream,
+                     (const TI *)X, ldx, (TO *)Y, ldy, n, g.rpb, pd.params, pd.nq, pd.S);
+  return hipGetLastError() == hipSuccess ? HARP_OK : HARP_ERR_DEVICE;
+}
+
+// A streamed pass is never both the first and the last segment of a split program, so bf16 on
+// both sides does not occur.
 template <class OP>
 harp_status_t launch_stream_op(const harp_plan *plan, const PassDesc &pd, const void *X,
                                int64_t ldx, int ib, void *Y, int64_t ldy, int ob, int64_t n,
                                hipStream_t stream) {
-  // pairs of adjacent sub-tensors when everything is 8-byte aligned and the registers allow it
-  const bool pair = OP::NV <= 80 && (pd.S % 2 == 0) && (pd.nq % 2 == 0) && (ldx % 2 == 0) &&
-                    (ldy % 2 == 0) && ((uintptr_t)X % 8 == 0) && ((uintptr_t)Y % 8 == 0) &&
-                    env_int("HARP_STREAM_PAIR", 0);
-  if (pair)
-    return launch_stream_grid(harp_stream_kernel<OP, 2>, pd.nq / 2, plan, pd, X, ldx, ib, Y, ldy,
-                              ob, n, stream);
-  return launch_stream_grid(harp_stream_kernel<OP, 1>, pd.nq, plan, pd, X, ldx, ib, Y, ldy, ob, n,
-                            stream);
+  if ((int64_t)pd.P * pd.S >= (int64_t)1 << 31) return HARP_ERR_UNSUPPORTED;
+  if (ib && !ob) return launch_stream_typed<OP, uint16_t, float>(plan, pd, X, ldx, Y, ldy, n, stream);
+  if (!ib && ob) return launch_stream_typed<OP, float, uint16_t>(plan, pd, X, ldx, Y, ldy, n, stream);
+  if (!ib && !ob) return launch_stream_typed<OP, float, float>(plan, pd, X, ldx, Y, ldy, n, stream);
+  return HARP_ERR_UNSUPPORTED;
 }
 
 template <bool DESC, int FORM>
