@@ -58,10 +58,11 @@ __device__ __forceinline__ void split4(const float (&x)[4], s4v &hi, s4v &lo) {
   lo = __builtin_bit_cast(s4v, lv);
 }
 
-template <int KT>
+template <int KT, typename TI, typename TO>
 __global__ __launch_bounds__(1024) void harp_stream_mfma_kernel(
-    const void *__restrict__ X, int64_t ldx, int in_bf16, void *__restrict__ Y, int64_t ldy,
-    int out_bf16, int64_t n, int rows_per_wg, int gx, int gy, PassDesc pd) {
+    const TI *__restrict__ X, int64_t ldx, TO *__restrict__ Y, int64_t ldy, int64_t n,
+    int rows_per_wg, int gx, int gy, PassDesc pd) {
+  constexpr bool in_bf16 = sizeof(TI) == 2, out_bf16 = sizeof(TO) == 2;
   constexpr int MAXG = (kRC * 16 * KT * 4 + 1023) / 1024;   // 4-coordinate groups per thread
   __shared__ float tile[16 * KT * kJS];
   const int tid = threadIdx.x;
@@ -101,24 +102,35 @@ __global__ __launch_bounds__(1024) void harp_stream_mfma_kernel(
   }
 
   const int ngroups = kRC * b * 4;   // (row, j, quarter of the 16 lo) per chunk
+  // this thread's 4-coordinate groups: offsets inside a chunk of 16 rows (32-bit) and LDS slots
+  unsigned offx[MAXG], offy[MAXG];
+  int grow[MAXG], gtile[MAXG];
+#pragma unroll
+  for (int u = 0; u < MAXG; ++u) {
+    const int gi = tid + u * 1024;
+    const int lo4 = gi & 3, rem = gi >> 2;
+    const int row = rem & (kRC - 1), j = rem >> 4;
+    grow[u] = (gi < ngroups) ? row : 0x7fffffff;   // never below the rows left: group unused
+    offx[u] = (unsigned)(row * (int)ldx + j * S + lo4 * 4);
+    offy[u] = (unsigned)(row * (int)ldy + j * S + lo4 * 4);
+    gtile[u] = j * kJS + (lo4 * 4) * kLS + row;
+  }
   float pre[MAXG][4];
   auto fetch = [&](int64_t r0) {
+    const TI *xc = X + r0 * ldx + base;
+    const int left = (int)(r_end - r0);
 #pragma unroll
     for (int u = 0; u < MAXG; ++u) {
-      const int gi = tid + u * 1024;
-      const int lo4 = gi & 3, rem = gi >> 2;
-      const int row = rem & (kRC - 1), j = rem >> 4;
       pre[u][0] = pre[u][1] = pre[u][2] = pre[u][3] = 0.0f;
-      if (gi < ngroups && r0 + row < r_end) {
-        const int64_t idx = (r0 + row) * ldx + base + (int64_t)j * S + lo4 * 4;
-        if (in_bf16) {
-          const uint2 v = *reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(X) + idx);
+      if (grow[u] < left) {
+        if constexpr (in_bf16) {
+          const uint2 v = *reinterpret_cast<const uint2 *>(xc + offx[u]);
           pre[u][0] = __uint_as_float(v.x << 16);
           pre[u][1] = __uint_as_float(v.x & 0xffff0000u);
           pre[u][2] = __uint_as_float(v.y << 16);
           pre[u][3] = __uint_as_float(v.y & 0xffff0000u);
         } else {
-          const float4 v = *reinterpret_cast<const float4 *>(static_cast<const float *>(X) + idx);
+          const float4 v = *reinterpret_cast<const float4 *>(xc + offx[u]);
           pre[u][0] = v.x; pre[u][1] = v.y; pre[u][2] = v.z; pre[u][3] = v.w;
         }
       }
@@ -127,11 +139,8 @@ __global__ __launch_bounds__(1024) void harp_stream_mfma_kernel(
   auto commit = [&]() {
 #pragma unroll
     for (int u = 0; u < MAXG; ++u) {
-      const int gi = tid + u * 1024;
-      const int lo4 = gi & 3, rem = gi >> 2;
-      const int row = rem & (kRC - 1), j = rem >> 4;
-      if (gi < ngroups) {
-        float *t = tile + j * kJS + (lo4 * 4) * kLS + row;
+      if (grow[u] != 0x7fffffff) {
+        float *t = tile + gtile[u];
 #pragma unroll
         for (int k = 0; k < 4; ++k) t[k * kLS] = pre[u][k];
       }
@@ -182,20 +191,19 @@ __global__ __launch_bounds__(1024) void harp_stream_mfma_kernel(
     __syncthreads();
 
     // ---- coalesced store of the chunk
+    {
+      TO *yc = Y + r0 * ldy + base;
+      const int left = (int)(r_end - r0);
 #pragma unroll
-    for (int u = 0; u < MAXG; ++u) {
-      const int gi = tid + u * 1024;
-      const int lo4 = gi & 3, rem = gi >> 2;
-      const int row = rem & (kRC - 1), j = rem >> 4;
-      if (gi < ngroups && r0 + row < r_end) {
-        const float *t = tile + j * kJS + (lo4 * 4) * kLS + row;
-        const float v0 = t[0], v1 = t[kLS], v2 = t[2 * kLS], v3 = t[3 * kLS];
-        const int64_t idx = (r0 + row) * ldy + base + (int64_t)j * S + lo4 * 4;
-        if (out_bf16)
-          *reinterpret_cast<uint2 *>(static_cast<uint16_t *>(Y) + idx) =
-              make_uint2(pk_bf16(v0, v1), pk_bf16(v2, v3));
-        else
-          *reinterpret_cast<float4 *>(static_cast<float *>(Y) + idx) = make_float4(v0, v1, v2, v3);
+      for (int u = 0; u < MAXG; ++u) {
+        if (grow[u] < left) {
+          const float *t = tile + gtile[u];
+          const float v0 = t[0], v1 = t[kLS], v2 = t[2 * kLS], v3 = t[3 * kLS];
+          if constexpr (out_bf16)
+            *reinterpret_cast<uint2 *>(yc + offy[u]) = make_uint2(pk_bf16(v0, v1), pk_bf16(v2, v3));
+          else
+            *reinterpret_cast<float4 *>(yc + offy[u]) = make_float4(v0, v1, v2, v3);
+        }
       }
     }
     __syncthreads();   // the tile is free again
@@ -206,10 +214,10 @@ __global__ __launch_bounds__(1024) void harp_stream_mfma_kernel(
   }
 }
 
-template <int KT>
-harp_status_t launch_mfma_inst(const harp_plan *plan, const PassDesc &pd, const void *X,
-                               int64_t ldx, int ib, void *Y, int64_t ldy, int ob, int64_t n,
-                               hipStream_t stream) {
+template <int KT, typename TI, typename TO>
+harp_status_t launch_mfma_typed(const harp_plan *plan, const PassDesc &pd, const void *X,
+                                int64_t ldx, void *Y, int64_t ldy, int64_t n,
+                                hipStream_t stream) {
   const unsigned gx = (unsigned)(pd.nq / 16);
   // one workgroup (16 waves) per compute unit and wave of the grid; rows in multiples of 16
   int64_t gy = (plan->num_cu + gx - 1) / gx;
@@ -220,9 +228,21 @@ harp_status_t launch_mfma_inst(const harp_plan *plan, const PassDesc &pd, const 
   int64_t total = (int64_t)gx * gy;
   if ((gx & 3) == 0) total = (total + 31) / 32 * 32;
   if (total > 0x7fffffff) return HARP_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL((harp_stream_mfma_kernel<KT>), dim3((unsigned)total), dim3(1024), 0, stream,
-                     X, ldx, ib, Y, ldy, ob, n, (int)rpw, (int)gx, (int)gy, pd);
+  hipLaunchKernelGGL((harp_stream_mfma_kernel<KT, TI, TO>), dim3((unsigned)total), dim3(1024), 0,
+                     stream, (const TI *)X, ldx, (TO *)Y, ldy, n, (int)rpw, (int)gx, (int)gy, pd);
   return hipGetLastError() == hipSuccess ? HARP_OK : HARP_ERR_DEVICE;
+}
+
+// the streamed stage sits between the caller's bf16 side and the float32 intermediate, or
+// between two float32 intermediates
+template <int KT>
+harp_status_t launch_mfma_inst(const harp_plan *plan, const PassDesc &pd, const void *X,
+                               int64_t ldx, int ib, void *Y, int64_t ldy, int ob, int64_t n,
+                               hipStream_t stream) {
+  if (ib && !ob) return launch_mfma_typed<KT, uint16_t, float>(plan, pd, X, ldx, Y, ldy, n, stream);
+  if (!ib && ob) return launch_mfma_typed<KT, float, uint16_t>(plan, pd, X, ldx, Y, ldy, n, stream);
+  if (!ib && !ob) return launch_mfma_typed<KT, float, float>(plan, pd, X, ldx, Y, ldy, n, stream);
+  return launch_mfma_typed<KT, uint16_t, uint16_t>(plan, pd, X, ldx, Y, ldy, n, stream);
 }
 
 }  // namespace
@@ -232,6 +252,7 @@ bool mfma_pass_supported(const PassDesc &pd, const void *X, int64_t ldx, const v
   if (pd.kind != PASS_GENERIC || pd.b < 9 || pd.b > 64 || pd.aux == nullptr) return false;
   if (pd.S % 16 != 0) return false;   // 16 consecutive blocks must be 16 consecutive coordinates
   if ((ldx % 4) || (ldy % 4) || ((uintptr_t)X % 16) || ((uintptr_t)Y % 16)) return false;
+  if (ldx >= ((int64_t)1 << 26) || ldy >= ((int64_t)1 << 26)) return false;   // 32-bit offsets per chunk
   return true;
 }
 
