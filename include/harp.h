@@ -65,8 +65,8 @@ typedef enum {
   HARP_ALGO_GENERIC = 1, /* every stage through the runtime-radix code path                   */
   HARP_ALGO_FUSED = 2,   /* radix-specialised passes, whole rows on chip                      */
   HARP_ALGO_SPLIT = 3    /* low digits (product <= 4096) fused on chip per row chunk, each pass on
-                            the digits above streamed through a float32 intermediate that the
-                            call allocates and frees on the stream (hipMallocAsync)            */
+                            the digits above streamed through a float32 intermediate owned
+                            by the plan (see harp_apply)                                       */
 } harp_algo_t;
 
 #define HARP_MAX_RADIX 64
@@ -102,6 +102,11 @@ harp_status_t harp_plan_destroy(harp_plan_t *plan);
  *   dt       element type of both X and Y.
  *   stream   a hipStream_t passed as void* (NULL = the default stream).  The call only
  *            enqueues work on it.
+ * Plans whose rows are longer than 4096 coordinates run in two or more launches through a
+ * float32 intermediate of at most 128 MB that the plan allocates (hipMalloc) the first time
+ * it is used on a stream and keeps, one per stream, until harp_plan_destroy.  That first
+ * call may therefore block; inside a stream capture it returns HARP_ERR_UNSUPPORTED instead
+ * (run the plan once on the stream before capturing).  HARP_ERR_OOM if it cannot be had.
  */
 harp_status_t harp_apply(const harp_plan_t *plan, const void *X, int64_t ldx, void *Y,
                          int64_t ldy, int64_t n, harp_dtype_t dt, void *stream);

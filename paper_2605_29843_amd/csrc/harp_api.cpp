@@ -149,7 +149,6 @@ bool build_effective(const harp_plan *plan, const std::vector<const float *> &bl
 }
 
 constexpr int64_t kChunkCap = 4096;   // largest on-chip chunk of a split program
-constexpr int64_t kSplitMinRows = 64;  // AUTO: batches below this stay on the whole-row kernel
 
 // Split a run of `len` stages into ceil(len / kmax) nearly equal parts.
 void split_run(int len, int kmax, std::vector<int> &out) {
@@ -356,36 +355,47 @@ harp_status_t check_apply_args(const harp_plan_t *plan, const void *X, int64_t l
 
 size_t esize(harp_dtype_t dt) { return dt == HARP_BF16 ? 2 : 4; }
 
-// Stream-ordered pool of the library for the intermediates of split programs, one per device.
-// Its release threshold is unlimited: a freed intermediate stays mapped in the pool and the
-// next call gets the same pages back.  (The device's default pool returns memory to the system
-// at every synchronisation, and writing freshly mapped pages ran at two thirds of the speed of
-// writing pages the process has already touched.)  Returns null if the pool cannot be created;
-// callers then use the default pool.
-hipMemPool_t scratch_pool(int device) {
-  static std::mutex mu;
-  static std::vector<hipMemPool_t> pools;
-  std::lock_guard<std::mutex> lock(mu);
-  if (device < 0) return nullptr;
-  if ((size_t)device >= pools.size()) pools.resize((size_t)device + 1, nullptr);
-  if (!pools[device]) {
-    hipMemPoolProps props;
-    memset(&props, 0, sizeof(props));
-    props.allocType = hipMemAllocationTypePinned;
-    props.handleTypes = hipMemHandleTypeNone;
-    props.location.type = hipMemLocationTypeDevice;
-    props.location.id = device;
-    hipMemPool_t pool = nullptr;
-    if (hipMemPoolCreate(&pool, &props) != hipSuccess) {
-      (void)hipGetLastError();
-      return nullptr;
-    }
-    uint64_t keep = UINT64_MAX;
-    if (hipMemPoolSetAttribute(pool, hipMemPoolAttrReleaseThreshold, &keep) != hipSuccess)
-      (void)hipGetLastError();
-    pools[device] = pool;
+// The plan's float32 intermediate for `stream`, at least `bytes` long.  Allocated on first use
+// (a synchronous hipMalloc, so not while the stream is being captured into a graph: warm the
+// plan up once before capturing) and kept until the plan is destroyed.  Per-call stream-ordered
+// allocation was measured first: it added two stream operations to every call, 29 us per call
+// on a 2-kernel program against 11 us of kernel time.
+harp_status_t plan_scratch(const harp_plan_t *plan, hipStream_t stream, size_t bytes, float **out) {
+  std::lock_guard<std::mutex> lock(plan->scratch_mu);
+  harp_plan::Scratch *slot = nullptr;
+  for (auto &sc : plan->scratch)
+    if (sc.stream == stream) slot = &sc;
+  if (slot && slot->bytes >= bytes) {
+    *out = slot->ptr;
+    return HARP_OK;
   }
-  return pools[device];
+  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(stream, &cs) != hipSuccess) {
+    (void)hipGetLastError();
+    return HARP_ERR_DEVICE;
+  }
+  if (cs != hipStreamCaptureStatusNone) return HARP_ERR_UNSUPPORTED;
+  if (slot) {   // too small: queued work on the stream may still use it
+    if (hipStreamSynchronize(stream) != hipSuccess || hipFree(slot->ptr) != hipSuccess) {
+      (void)hipGetLastError();
+      return HARP_ERR_DEVICE;
+    }
+    slot->ptr = nullptr;
+    slot->bytes = 0;
+  }
+  float *p = nullptr;
+  if (hipMalloc((void **)&p, bytes) != hipSuccess) {
+    (void)hipGetLastError();
+    return HARP_ERR_OOM;
+  }
+  if (slot) {
+    slot->ptr = p;
+    slot->bytes = bytes;
+  } else {
+    plan->scratch.push_back(harp_plan::Scratch{stream, p, bytes});
+  }
+  *out = p;
+  return HARP_OK;
 }
 
 // Passes [p0, p1) of the program on row chunks, fused on chip.
@@ -427,13 +437,8 @@ harp_status_t apply_dir(const harp_plan_t *plan, Direction dir, const void *X, i
   if (slab < 1) slab = 1;
   if (slab > n) slab = n;
   float *Z = nullptr;
-  hipMemPool_t pool = scratch_pool(plan->device);
-  const hipError_t merr = pool ? hipMallocFromPoolAsync((void **)&Z, (size_t)slab * d * 4, pool, stream)
-                               : hipMallocAsync((void **)&Z, (size_t)slab * d * 4, stream);
-  if (merr != hipSuccess) {
-    (void)hipGetLastError();
-    return HARP_ERR_OOM;
-  }
+  harp_status_t zst = plan_scratch(plan, stream, (size_t)slab * d * 4, &Z);
+  if (zst != HARP_OK) return zst;
   const int nstream = np - hp.n_chunk;
   const int nseg = nstream + 1;
   const bool allow_narrow = (dt_in == HARP_BF16 || dt_out == HARP_BF16);
@@ -463,7 +468,6 @@ harp_status_t apply_dir(const harp_plan_t *plan, Direction dir, const void *X, i
       src_dt = dst_dt;
     }
   }
-  if (hipFreeAsync(Z, stream) != hipSuccess && st == HARP_OK) st = HARP_ERR_DEVICE;
   return st;
 }
 
@@ -532,9 +536,9 @@ const HostProgram *select_program(const harp_plan *plan, Direction dir, int64_t 
                                   const char **name) {
   int algo = plan->algo;
   if (algo == HARP_ALGO_AUTO) {
-    // rows longer than one on-chip chunk: split unless the batch is tiny (then the extra
-    // launches cost more than re-reading parameters per row does)
-    if (plan->prog[HARP_ALGO_SPLIT][dir].ok && (n >= kSplitMinRows || !plan->prog[HARP_ALGO_FUSED][dir].ok))
+    // rows longer than one on-chip chunk: split at every batch size (measured down to one row:
+    // two short launches beat one workgroup per row re-reading the whole parameter image)
+    if (plan->prog[HARP_ALGO_SPLIT][dir].ok)
       algo = HARP_ALGO_SPLIT;
     else
       algo = plan->prog[HARP_ALGO_FUSED][dir].ok ? HARP_ALGO_FUSED : HARP_ALGO_GENERIC;
@@ -725,6 +729,8 @@ harp_status_t harp_plan_destroy(harp_plan_t *plan) {
   harp_status_t st = HARP_OK;
   for (void *p : plan->dev_allocs)
     if (p && hipFree(p) != hipSuccess) st = HARP_ERR_DEVICE;
+  for (auto &sc : plan->scratch)
+    if (sc.ptr && hipFree(sc.ptr) != hipSuccess) st = HARP_ERR_DEVICE;
   delete plan;
   return st;
 }

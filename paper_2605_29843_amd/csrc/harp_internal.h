@@ -6,6 +6,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
 #include <vector>
 
 #include "harp.h"
@@ -85,6 +86,16 @@ struct harp_plan {
   int device = 0;
   int lds_bytes = 0;   // usable LDS per workgroup
   int num_cu = 0;
+  // float32 intermediates of split programs, one per stream the plan has been used on (work
+  // on one stream is ordered, so consecutive calls can share the buffer); grow-only, freed
+  // with the plan
+  struct Scratch {
+    hipStream_t stream;
+    float *ptr;
+    size_t bytes;
+  };
+  mutable std::mutex scratch_mu;
+  mutable std::vector<Scratch> scratch;
 };
 
 namespace harp {

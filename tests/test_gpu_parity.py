@@ -363,6 +363,13 @@ def test_split_program_chunk_plus_stream(harp, d, radices, n, dtype):
     run_case(harp, d, radices, n, dtype, seed=d + n, algo=3, act=X)
 
 
+@pytest.mark.parametrize("d,radices,n", [(12288, [2] * 12 + [3], 3), (14336, [2] * 11 + [7], 2),
+                                         (11008, [2] * 8 + [43], 5)])
+def test_whole_row_tile_kernel_for_long_rows(harp, d, radices, n):
+    """The one-launch whole-row path (algo = fused) stays available for rows longer than a chunk."""
+    run_case(harp, d, radices, n, "bf16", seed=d + n, algo=2)
+
+
 MFMA_CASES = [
     (11008, [2] * 8 + [43], 300), (22528, [2] * 11 + [11], 40), (4096 * 33, [2] * 12 + [33], 5),
     (65536, [4] * 5 + [64], 18), (8192 * 2, [8, 8, 8, 2, 16], 33), (11008, [8, 8, 4, 43], 17),
@@ -388,6 +395,43 @@ def test_split_is_refused_when_there_is_nothing_to_split(harp):
 
 
 # ------------------------------------------------------------------ config 4: decode regime
+@pytest.mark.parametrize("d,radices,n", [(4096, [2] * 12, 24), (14336, [2] * 11 + [7], 70)])
+def test_graph_capture_and_replay(harp, d, radices, n):
+    """The launches of an apply can be captured into a HIP graph (split programs after one
+    eager call on the capturing stream, which allocates the plan's intermediate); every replay,
+    with eager work and synchronisations in between, reproduces the eager result."""
+    import torch
+    rng = np.random.default_rng(d)
+    blocks = gi.make_blocks(d, radices, "orth" if d == 4096 else "qr", rng)
+    signs = gi.make_signs(d, rng)
+    plan = harp.Plan(d, radices, blocks, signs)
+    say(f"graph capture d={d} n={n} kernel={plan.kernel_name(n)}")
+    X = gi.round_to_bf16(rng.standard_normal((n, d)).astype(np.float32))
+    Xd = to_device(X, "bf16")
+    Y_eager = harp.harp_apply(plan, Xd).clone()
+    Yg = torch.zeros_like(Xd)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        harp.harp_apply(plan, Xd, Yg, side)          # warm-up on the capturing stream
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            harp.harp_apply(plan, Xd, Yg, side)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        Yg.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(Yg, Y_eager), f"replay {rep} differs from the eager result"
+        other = harp.harp_apply_transpose(plan, Xd)   # eager work between replays
+        torch.cuda.synchronize()
+        assert other.shape == Xd.shape
+    assert_parity(to_host64(Yg), ho.apply_staged(X, d, radices, blocks, signs), "bf16", "graph replay")
+    plan.destroy()
+
+
 RADIX_TILE_CASES = [
     (512, [8] * 3, 19), (4096, [8] * 4, 37), (4096, [8] * 4, 1), (256, [4] * 4, 9), (1024, [4] * 5, 21),
     (4096, [4] * 6, 13), (4096, [8] * 4, 8),
