@@ -529,11 +529,13 @@ int choose_pipe_rows(const harp_plan *plan, int64_t n, int64_t nchunk, int chunk
   if (per_chunk < 1) per_chunk = 1;
   int64_t R = (n + per_chunk - 1) / per_chunk;
   if (R < 1) R = 1;
+  if (R > 1 && (R & 1)) ++R;   // the kernel moves rows in pairs
   return (int)R;
 }
 
 const HostProgram *select_program(const harp_plan *plan, Direction dir, int64_t n,
                                   const char **name) {
+  (void)n;
   int algo = plan->algo;
   if (algo == HARP_ALGO_AUTO) {
     // rows longer than one on-chip chunk: split at every batch size (measured down to one row:
