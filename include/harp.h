@@ -138,6 +138,42 @@ harp_status_t harp_rotate_weight_inverse(const harp_plan_t *plan_U, const harp_p
                                          int64_t d_out, int64_t d_in, harp_dtype_t dt,
                                          void *workspace, size_t workspace_bytes, void *stream);
 
+/* Base mixer G_b of a stage's block kernels (Sec. 3, "Hadamard-preconditioned block kernels"). */
+typedef enum {
+  HARP_MIXER_IDENTITY = 0, /* G = I: the block is Q(theta) itself                              */
+  HARP_MIXER_HADAMARD = 1, /* normalised Sylvester Hadamard matrix; power-of-two radices only  */
+  HARP_MIXER_CUSTOM = 2    /* the b x b row-major matrix mixers[t] (host), e.g. the QR fallback
+                              of a fixed Gaussian matrix the paper uses for other radices, whose
+                              seed it does not publish                                         */
+} harp_mixer_t;
+
+/*
+ * Block kernels from the rotation parameters: B_{t,c} = Q(theta_{t,c}) G_{b_t} (Sec. 3, block
+ * definition), in the layout harp_plan_create takes.  Host only, computed in float64.
+ *   theta        m host pointers or NULL (= all zero).  theta[t] is NULL (zeros: Q = I, the
+ *                paper's initialisation) or D_t * b_t (b_t - 1) / 2 floats, block c first:
+ *                for radix 2 the angle of [[cos, -sin], [sin, cos]]; for larger radices the
+ *                strict upper triangle, row by row ((0,1), (0,2), ..., (1,2), ...), of the
+ *                skew-symmetric A in the Cayley map Q = (I + A)^{-1} (I - A).
+ *   mixer_kinds  m harp_mixer_t values, or NULL for HARP_MIXER_HADAMARD at every stage.
+ *   mixers       m host pointers (read for HARP_MIXER_CUSTOM stages only), or NULL.
+ *   blocks_out   m host buffers of D_t * b_t * b_t floats each, written.
+ * The matrix product is taken as printed (Q on the left of G); the block then acts on row
+ * vectors like any other (harp_plan_create).  HARP_ERR_INVALID_ARG for a Hadamard mixer at
+ * a radix that is not a power of two, a missing custom mixer or a non-finite parameter.
+ */
+harp_status_t harp_blocks_from_theta(int64_t d, int32_t m, const int32_t *radices,
+                                     const float *const *theta, const int32_t *mixer_kinds,
+                                     const float *const *mixers, float *const *blocks_out);
+
+/* harp_blocks_from_theta followed by harp_plan_create (flags: HARP_VALIDATE_ORTHO only). With
+ * theta == NULL, Hadamard mixers and a power-of-two schedule the plan is the randomized
+ * Hadamard transform diag(signs) H_d / sqrt(d) (Sec. 3, "Exact initialization"). */
+harp_status_t harp_plan_create_from_theta(harp_plan_t **out, int64_t d, int32_t m,
+                                          const int32_t *radices, const float *const *theta,
+                                          const int32_t *mixer_kinds, const float *const *mixers,
+                                          const int8_t *signs, uint32_t flags);
+
 /* Greedy Mixed-Radix schedule (appendix Alg. 2): peel b_base while it divides d, then the
  * factors min(b_max, r) .. 2 in decreasing order, then any leftover as one last stage.
  * out_radices must hold HARP_MAX_STAGES ints.  Host only; no HIP call. */

@@ -36,7 +36,9 @@ form of a stage, Theta=0 power-of-two schedules equal the normalised Sylvester
 Hadamard (checked against scipy's hadamard), U^T U = I, norm preservation, round
 trip, brute force through Eq. (7) at d <= 172, transpose equals matrix transpose,
 loss invariance Eq. (3), the greedy schedule's printed examples (App. "Stage
-schedules", Alg. 2) and Table "radix ablation" stage counts, Eq. (13) parameter count.
+schedules", Alg. 2) and Table "radix ablation" stage counts, Eq. (13) parameter count;
+``blocks_from_theta``: Theta = 0 gives diag(sigma) H_d / sqrt(d) (scipy's hadamard), the
+radix-2 block written out, the radix-3 Cayley block against the Rodrigues rotation.
 Unpinned against the paper (values not published): the QR base mixer's fixed
 Gaussian and any trained processor -- "parity unpinned" for those; they are inputs
 to this library, not computed by it.
@@ -51,6 +53,7 @@ __all__ = [
     "apply_staged", "apply_transpose_staged", "rotate_weight",
     "stage_matrix_explicit", "U_explicit", "greedy_schedule",
     "sylvester_hadamard", "param_count", "givens_block", "cayley_block",
+    "blocks_from_theta",
 ]
 
 
@@ -274,3 +277,48 @@ def cayley_block(upper, b):
     A = A - A.T
     I = np.eye(b)
     return np.linalg.solve(I + A, I - A)
+
+
+def blocks_from_theta(d, radices, thetas, mixers=None):
+    """Block kernels B_{t,c} = Q(theta_{t,c}) G_{b_t} (Eq. (9)), as float64 arrays [D_t, b_t, b_t].
+
+    thetas[t]: None (all zeros: Q = I, Sec. 3 'Exact initialization'), or an array
+    [D_t, b_t (b_t - 1) / 2]: the rotation angle for b_t = 2 (Eq. (10)), the strict upper
+    triangle of the skew-symmetric A for b_t > 2 (Eq. (11)).  mixers[t]: None = the normalised
+    Sylvester Hadamard matrix (power-of-two radices only; also the string "hadamard"), the
+    string "identity", or an
+    explicit orthogonal b_t x b_t matrix (the paper's QR fallback for other radices is a seeded
+    matrix whose seed is not published, so it has to be supplied).  The product is taken as
+    printed, Q then G, and the block is used as v -> v B like any other block.
+    """
+    check_schedule(d, radices)
+    out = []
+    for t, b in enumerate(radices):
+        D = d // b
+        G = None if mixers is None else mixers[t]
+        if G is None or (isinstance(G, str) and G == "hadamard"):
+            if b & (b - 1):
+                raise ValueError("no default base mixer for a radix that is not a power of two")
+            G = sylvester_hadamard(b)
+        elif isinstance(G, str):
+            if G != "identity":
+                raise ValueError("unknown mixer")
+            G = np.eye(b)
+        else:
+            G = np.asarray(G, dtype=np.float64)
+            if G.shape != (b, b):
+                raise ValueError("mixer shape")
+        npar = b * (b - 1) // 2
+        th = None if thetas is None or thetas[t] is None else np.asarray(thetas[t], dtype=np.float64).reshape(D, npar)
+        K = np.empty((D, b, b))
+        for c in range(D):
+            if th is None:
+                Q = np.eye(b)
+            elif b == 2:
+                Q = givens_block(th[c, 0])
+            else:
+                Q = cayley_block(th[c], b)
+            K[c] = Q @ G
+        out.append(K)
+    return out
+

@@ -28,6 +28,7 @@ HARP_F32, HARP_BF16 = 0, 1
 HARP_VALIDATE_ORTHO, HARP_BLOCKS_ON_DEVICE = 1, 2
 HARP_ALGO_AUTO, HARP_ALGO_GENERIC, HARP_ALGO_FUSED, HARP_ALGO_SPLIT = 0, 1, 2, 3
 HARP_MAX_RADIX, HARP_MAX_STAGES = 64, 64
+HARP_MIXER_IDENTITY, HARP_MIXER_HADAMARD, HARP_MIXER_CUSTOM = 0, 1, 2
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2605_29843_amd.build` "
@@ -38,6 +39,10 @@ _vp, _i64, _i32, _u32, _sz = C.c_void_p, C.c_int64, C.c_int32, C.c_uint32, C.c_s
 _SIGS = {
     "harp_plan_create": (_i32, [C.POINTER(_vp), _i64, _i32, C.POINTER(_i32), C.POINTER(_vp), _vp, _u32]),
     "harp_plan_destroy": (_i32, [_vp]),
+    "harp_blocks_from_theta": (_i32, [_i64, _i32, C.POINTER(_i32), C.POINTER(_vp), C.POINTER(_i32),
+                                      C.POINTER(_vp), C.POINTER(_vp)]),
+    "harp_plan_create_from_theta": (_i32, [C.POINTER(_vp), _i64, _i32, C.POINTER(_i32), C.POINTER(_vp),
+                                           C.POINTER(_i32), C.POINTER(_vp), _vp, _u32]),
     "harp_apply": (_i32, [_vp, _vp, _i64, _vp, _i64, _i64, _i32, _vp]),
     "harp_apply_transpose": (_i32, [_vp, _vp, _i64, _vp, _i64, _i64, _i32, _vp]),
     "harp_rotate_weight_workspace_size": (_i32, [_vp, _vp, _i64, _i64, _i32, C.POINTER(_sz)]),
@@ -110,6 +115,50 @@ def _rowmajor_2d(t, what: str):
     return t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1])
 
 
+def _theta_args(d, radices, thetas, mixers, keep):
+    """ctypes arrays for the (theta, mixer_kinds, mixers) arguments.  thetas[t] / mixers[t]:
+    None, or a host array; mixers[t] may also be "identity" or "hadamard"."""
+    m = len(radices)
+    th = (_vp * max(m, 1))()
+    kinds = (_i32 * max(m, 1))()
+    mx = (_vp * max(m, 1))()
+    for t, b in enumerate(radices):
+        a = None if thetas is None else thetas[t]
+        if a is None:
+            th[t] = None
+        else:
+            a = np.ascontiguousarray(a, dtype=np.float32)
+            if a.size != (d // b) * (b * (b - 1) // 2):
+                raise ValueError(f"theta[{t}] must hold D_t * b (b - 1) / 2 values")
+            keep.append(a)
+            th[t] = a.ctypes.data
+        g = None if mixers is None else mixers[t]
+        if g is None or (isinstance(g, str) and g == "hadamard"):
+            kinds[t], mx[t] = HARP_MIXER_HADAMARD, None
+        elif isinstance(g, str) and g == "identity":
+            kinds[t], mx[t] = HARP_MIXER_IDENTITY, None
+        else:
+            g = np.ascontiguousarray(g, dtype=np.float32)
+            if g.shape != (b, b):
+                raise ValueError(f"mixers[{t}] must be {b} x {b}")
+            keep.append(g)
+            kinds[t], mx[t] = HARP_MIXER_CUSTOM, g.ctypes.data
+    return th, kinds, mx
+
+
+def harp_blocks_from_theta(d: int, radices, thetas=None, mixers=None) -> list:
+    """Host blocks B = Q(theta) G per stage, float32 arrays [D_t, b_t, b_t]."""
+    radices = [int(b) for b in radices]
+    m = len(radices)
+    keep = []
+    th, kinds, mx = _theta_args(int(d), radices, thetas, mixers, keep)
+    outs = [np.empty((max(int(d) // b, 0), b, b), dtype=np.float32) for b in radices]
+    op = (_vp * max(m, 1))(*[o.ctypes.data for o in outs])
+    rad = (_i32 * max(m, 1))(*radices)
+    _check(lib.harp_blocks_from_theta(int(d), m, rad, th, kinds, mx, op), "harp_blocks_from_theta")
+    return outs
+
+
 class Plan:
     """Owner of a ``harp_plan_t*``.  ``harp_plan_create`` with host numpy arrays."""
 
@@ -136,6 +185,27 @@ class Plan:
         _check(lib.harp_plan_create(C.byref(self._h), int(d), m, rad, ptrs, sp, int(flags)),
                "harp_plan_create")
         self._keep = []   # the plan copied everything it needs
+
+    @classmethod
+    def from_theta(cls, d: int, radices, thetas=None, mixers=None, signs=None, flags: int = 0):
+        """``harp_plan_create_from_theta``: rotation parameters instead of dense blocks."""
+        self = cls.__new__(cls)
+        radices = [int(b) for b in radices]
+        m = len(radices)
+        keep = []
+        th, kinds, mx = _theta_args(int(d), radices, thetas, mixers, keep)
+        rad = (_i32 * max(m, 1))(*radices)
+        sp = None
+        if signs is not None:
+            s = np.ascontiguousarray(signs, dtype=np.int8)
+            keep.append(s)
+            sp = s.ctypes.data
+        self._h = _vp(None)
+        self._keep = []
+        self.d, self.radices = int(d), radices
+        _check(lib.harp_plan_create_from_theta(C.byref(self._h), int(d), m, rad, th, kinds, mx, sp,
+                                               int(flags)), "harp_plan_create_from_theta")
+        return self
 
     # -- lifetime
     def destroy(self):

@@ -127,3 +127,36 @@ def test_null_plan_and_null_out_are_invalid_arguments():
                                   None) == harp.HARP_OK
     assert lib.harp_rotate_weight(None, None, None, 8, None, 8, 8, 8, harp.HARP_F32, None, 0,
                                   None) == harp.HARP_ERR_INVALID_ARG
+
+
+def test_blocks_from_theta_host_front_end_matches_the_oracle():
+    """The library's parameter front end runs on the host, so it is checked here without a GPU:
+    Givens (radix 2) and Cayley (radix > 2) blocks, Hadamard / identity / custom mixers."""
+    import numpy as np
+    from oracle import harp_oracle as ho
+    rng = np.random.default_rng(11)
+    d, radices = 480, [2, 8, 3, 2, 5]
+    G3 = np.linalg.qr(rng.standard_normal((3, 3)))[0].astype(np.float32)
+    thetas = [(1.5 * rng.standard_normal((d // b, b * (b - 1) // 2))).astype(np.float32) for b in radices]
+    thetas[3] = None
+    mixers = [None, "hadamard", G3, "identity", "identity"]
+    got = harp.harp_blocks_from_theta(d, radices, thetas, mixers)
+    ref = ho.blocks_from_theta(d, radices, thetas, mixers)
+    for g, r in zip(got, ref):
+        assert g.dtype == np.float32 and g.shape == r.shape
+        assert np.max(np.abs(g - r)) <= 2.0 ** -23          # one float32 rounding of an entry <= 1
+    # Theta = 0: exactly the normalised Hadamard block
+    H = harp.harp_blocks_from_theta(64, [8, 8])
+    np.testing.assert_array_equal(H[0][5], ho.sylvester_hadamard(8).astype(np.float32))
+    # argument errors
+    with pytest.raises(harp.HarpError) as e:
+        harp.harp_blocks_from_theta(6, [2, 3])              # Hadamard mixer at radix 3
+    assert e.value.status == harp.HARP_ERR_INVALID_ARG
+    bad = [np.full((3, 1), np.nan, np.float32), None]
+    with pytest.raises(harp.HarpError) as e:
+        harp.harp_blocks_from_theta(6, [2, 3], bad, [None, "identity"])
+    assert e.value.status == harp.HARP_ERR_INVALID_ARG
+    with pytest.raises(harp.HarpError) as e:
+        harp.harp_blocks_from_theta(10, [2, 3])
+    assert e.value.status == harp.HARP_ERR_BAD_SCHEDULE
+

@@ -432,6 +432,57 @@ def test_graph_capture_and_replay(harp, d, radices, n):
     plan.destroy()
 
 
+def test_plan_from_theta_zero_is_the_randomized_hadamard_transform(harp):
+    """Theta = 0, Hadamard mixers, power-of-two schedule: apply(x) = (x * sigma) H_d / sqrt(d),
+    checked against scipy's Sylvester matrix, not against the staged oracle."""
+    import torch
+    from scipy.linalg import hadamard
+    for d, radices in ((4096, [2] * 12), (4096, [8] * 4), (1024, [4, 2, 8, 16])):
+        rng = np.random.default_rng(d + len(radices))
+        signs = gi.make_signs(d, rng)
+        plan = harp.Plan.from_theta(d, radices, None, None, signs)
+        say(f"theta=0 d={d} radices={radices} kernel={plan.kernel_name(33)}")
+        X = rng.standard_normal((33, d)).astype(np.float32)
+        Y = to_host64(harp.harp_apply(plan, to_device(X, "f32")))
+        Z = to_host64(harp.harp_apply_transpose(plan, to_device(X, "f32")))
+        torch.cuda.synchronize()
+        H = hadamard(d).astype(np.float64) / np.sqrt(d)
+        assert_parity(Y, (X.astype(np.float64) * signs) @ H, "f32", "RHT apply")
+        assert_parity(Z, (X.astype(np.float64) @ H.T) * signs, "f32", "RHT transpose")
+        plan.destroy()
+
+
+@pytest.mark.parametrize("d,radices,mixers", [
+    (4096, [2] * 12, None), (4096, [8] * 4, None), (480, [2, 8, 3, 2, 5], "mixed"),
+    (14336, [2] * 11 + [7], "odd_last")])
+def test_plan_from_theta_matches_the_oracle_blocks(harp, d, radices, mixers):
+    import torch
+    rng = np.random.default_rng(d)
+    thetas = [(0.8 * rng.standard_normal((d // b, b * (b - 1) // 2))).astype(np.float32) for b in radices]
+    mix = None
+    if mixers is not None:
+        mix = []
+        for b in radices:
+            if b & (b - 1):      # the QR fallback of a seeded Gaussian (seed of the paper's unknown)
+                q, r = np.linalg.qr(rng.standard_normal((b, b)))
+                mix.append((q * np.sign(np.diag(r))).astype(np.float32))
+            else:
+                mix.append(None)
+    signs = gi.make_signs(d, rng)
+    plan = harp.Plan.from_theta(d, radices, thetas, mix, signs, flags=harp.HARP_VALIDATE_ORTHO)
+    n = 21
+    say(f"from theta d={d} radices={radices} kernel={plan.kernel_name(n)}")
+    X = gi.round_to_bf16(rng.standard_normal((n, d)).astype(np.float32))
+    blocks = ho.blocks_from_theta(d, radices, thetas, mix)
+    for dtype in ("f32", "bf16"):
+        Y = to_host64(harp.harp_apply(plan, to_device(X, dtype)))
+        Z = to_host64(harp.harp_apply_transpose(plan, to_device(X, dtype)))
+        torch.cuda.synchronize()
+        assert_parity(Y, ho.apply_staged(X, d, radices, blocks, signs), dtype, "apply")
+        assert_parity(Z, ho.apply_transpose_staged(X, d, radices, blocks, signs), dtype, "apply_transpose")
+    plan.destroy()
+
+
 RADIX_TILE_CASES = [
     (512, [8] * 3, 19), (4096, [8] * 4, 37), (4096, [8] * 4, 1), (256, [4] * 4, 9), (1024, [4] * 5, 21),
     (4096, [4] * 6, 13), (4096, [8] * 4, 8),

@@ -315,6 +315,55 @@ def test_givens_and_cayley_special_cases():
     np.testing.assert_allclose(Q, ho.givens_block(2 * np.arctan(a)), atol=1e-14)
 
 
+def test_cayley_radix3_is_the_rodrigues_rotation():
+    """(I+A)^{-1}(I-A) with A the cross-product matrix of w is the rotation about w by
+    -2 atan|w| (textbook closed form), which fixes the sign and the order of the triangle."""
+    a01, a02, a12 = 0.3, -0.45, 0.8
+    Q = ho.cayley_block([a01, a02, a12], 3)
+    w = np.array([-a12, a02, -a01])            # A = [w]_x
+    nw = np.linalg.norm(w)
+    K = np.array([[0, -w[2], w[1]], [w[2], 0, -w[0]], [-w[1], w[0], 0]]) / nw
+    phi = -2 * np.arctan(nw)
+    R = np.eye(3) + np.sin(phi) * K + (1 - np.cos(phi)) * (K @ K)
+    np.testing.assert_allclose(Q, R, atol=1e-14)
+    np.testing.assert_allclose(Q @ w, w, atol=1e-14)          # the axis is fixed
+
+
+@pytest.mark.parametrize("radices", [[2] * 6, [8, 8, 4], [4, 2, 8], [16, 4]])
+def test_blocks_from_theta_zero_is_the_hadamard_processor(radices):
+    """Theta = 0 with Hadamard mixers: every block is H_b and U = diag(sigma) H_d / sqrt(d)."""
+    from scipy.linalg import hadamard
+    d = int(np.prod(radices))
+    blocks = ho.blocks_from_theta(d, radices, None)
+    for b, K in zip(radices, blocks):
+        assert K.shape == (d // b, b, b)
+        np.testing.assert_allclose(K, np.broadcast_to(hadamard(b) / np.sqrt(b), K.shape), atol=1e-15)
+    sig = gi.make_signs(d, np.random.default_rng(7))
+    U = ho.build_U(d, radices, blocks, sig)
+    np.testing.assert_allclose(U, sig[:, None] * hadamard(d) / np.sqrt(d), atol=1e-13)
+
+
+def test_blocks_from_theta_forms_and_orthogonality():
+    rng = np.random.default_rng(3)
+    d, radices = 120, [2, 4, 3, 5]
+    G3 = np.linalg.qr(rng.standard_normal((3, 3)))[0]
+    thetas = [rng.standard_normal((d // b, b * (b - 1) // 2)) for b in radices]
+    blocks = ho.blocks_from_theta(d, radices, thetas, [None, None, G3, "identity"])
+    # radix 2: Q(theta) H_2 written out
+    th = thetas[0][:, 0]
+    c, s_ = np.cos(th), np.sin(th)
+    want = np.stack([np.stack([c - s_, c + s_], -1), np.stack([s_ + c, s_ - c], -1)], -2) / np.sqrt(2)
+    np.testing.assert_allclose(blocks[0], want, atol=1e-15)
+    # radix 3 with a custom mixer, radix 5 with the identity mixer
+    np.testing.assert_allclose(blocks[2][5], ho.cayley_block(thetas[2][5], 3) @ G3, atol=1e-15)
+    np.testing.assert_allclose(blocks[3][2], ho.cayley_block(thetas[3][2], 5), atol=1e-15)
+    for K in blocks:
+        np.testing.assert_allclose(np.einsum("cij,cik->cjk", K, K), np.broadcast_to(np.eye(K.shape[1]), K.shape),
+                                   atol=1e-12)
+    with pytest.raises(ValueError):
+        ho.blocks_from_theta(6, [2, 3], None)            # no default mixer for radix 3
+
+
 # ------------------------------------------------------------------ input generator sanity
 def test_bf16_rounding_is_rne_and_exact():
     x = np.array([1.0, 1.00390625, 1.0 + 2 ** -8, 1.0 + 3 * 2 ** -8, -2.5, 3.1415926], np.float32)
