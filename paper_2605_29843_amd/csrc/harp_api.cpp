@@ -327,6 +327,16 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
       for (int r = 0; r < b; ++r)
         for (int r2 = 0; r2 < b; ++r2)
           img[(size_t)(r * b + r2) * nq + q] = se.dense[((size_t)q * b + r) * b + r2];
+    if (small && (b == 4 || b == 8)) {
+      // second copy for the equal-radix tile kernel, four values per 16-byte load:
+      // value v = 4 * v4 + i of sub-tensor q at float index ((v4 * nq) + q) * 4 + i
+      std::vector<uint16_t> &a = aux[pg.npass - 1];
+      a.resize((size_t)pd.V * nq * 2);
+      float *a4 = reinterpret_cast<float *>(a.data());
+      for (int64_t q = 0; q < nq; ++q)
+        for (int v = 0; v < pd.V; ++v)
+          a4[((size_t)(v >> 2) * nq + q) * 4 + (v & 3)] = img[(size_t)v * nq + q];
+    }
     if (fused && !small && b >= 9) {   // matrix-core operand tiles for the streamed large radix
       const int KT = (b + 15) / 16;
       const size_t per = (size_t)KT * KT * 2 * 64 * 4;

@@ -39,7 +39,9 @@ struct PassDesc {
   int32_t nq;    // d / P sub-tensors per row
   int32_t V;     // parameter values per sub-tensor
   const float *params;  // device, [V][nq]: value v of sub-tensor q at params[v * nq + q]
-  const void *aux;      // GENERIC, radix >= 9: the blocks as bf16 hi/lo MFMA operand tiles, or null
+  // GENERIC, radix >= 9: the blocks as bf16 hi/lo MFMA operand tiles; SMALL, radix 4 / 8: a
+  // second copy of params, four values per 16-byte load ([V/4][nq][4] floats); else null
+  const void *aux;
 };
 
 constexpr int kMaxPasses = HARP_MAX_STAGES;

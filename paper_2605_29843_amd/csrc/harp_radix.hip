@@ -209,14 +209,20 @@ __global__ __launch_bounds__(512) void harp_radix_kernel(const TI *__restrict__ 
   TO *Yt = Y + row0 * ldy + (int64_t)kch * chunk;
 
   float cur[BPT][V], nxt[BPT][V];
+  // 16-byte loads from the four-values-per-load copy of the block parameters (pd.aux)
+  typedef float vec4f __attribute__((ext_vector_type(4)));
+  typedef const __attribute__((address_space(1))) vec4f *gfloat4_t;
   auto load_params = [&](const PassDesc &pd, float (&dst)[BPT][V]) {
-    const gfloat_t params = (gfloat_t)pd.params;
+    const gfloat4_t params = (gfloat4_t)pd.aux;
     const unsigned nq = (unsigned)pd.nq;
 #pragma unroll
     for (int u = 0; u < BPT; ++u) {
       const unsigned qg = (unsigned)kch * nqc + tid + u * NT;
 #pragma unroll
-      for (int v = 0; v < V; ++v) dst[u][v] = params[(unsigned)v * nq + qg];
+      for (int v4 = 0; v4 < V / 4; ++v4) {
+        const vec4f f = params[(unsigned)v4 * nq + qg];
+        dst[u][4 * v4] = f.x; dst[u][4 * v4 + 1] = f.y; dst[u][4 * v4 + 2] = f.z; dst[u][4 * v4 + 3] = f.w;
+      }
     }
   };
 
@@ -264,7 +270,7 @@ RadixShape radix_decode(const Program &pg, int p0, int np, int chunk) {
   if (B != 4 && B != 8) return rs;
   int64_t prod = 1;
   for (int p = 0; p < np; ++p) {
-    if (ps[p].kind != PASS_SMALL || ps[p].b != B) return rs;
+    if (ps[p].kind != PASS_SMALL || ps[p].b != B || ps[p].aux == nullptr) return rs;
     prod *= B;
   }
   if (prod != chunk) return rs;
