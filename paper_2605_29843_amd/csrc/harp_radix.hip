@@ -150,36 +150,47 @@ __device__ __forceinline__ void radix_pass(float *tile, int dpad, int nr, int S,
     const int q = tid + u * NT, hi = q / S, lo = q - hi * S;
     base[u] = hi * B * S + lo;
   }
+  // rows in pairs: the LDS reads of both rows are issued before the first is computed, and the
+  // writes of the first are in flight while the second is computed
 #pragma unroll
-  for (int r = 0; r < kRMax; ++r) {
+  for (int r = 0; r < kRMax; r += 2) {
     if (r < nr) {
-      float *trow = tile + r * dpad;
+      const bool two = r + 1 < nr;
+      float *trow[2] = {tile + r * dpad, tile + (two ? r + 1 : r) * dpad};
 #pragma unroll
       for (int u = 0; u < BPT; ++u) {
-        float x[B], y[B];
-        if (MODE == 0) {
-          In::template unpack<CONTIG>(raw[r][u], x);
-        } else if (CONTIG) {
+        float x[2][B], y[B];
 #pragma unroll
-          for (int h = 0; h < B / 4; ++h) {
-            const float4 f = *reinterpret_cast<const float4 *>(trow + lds_pos(base[u] + 4 * h));
-            x[4 * h] = f.x; x[4 * h + 1] = f.y; x[4 * h + 2] = f.z; x[4 * h + 3] = f.w;
+        for (int h2 = 0; h2 < 2; ++h2) {
+          if (MODE == 0) {
+            In::template unpack<CONTIG>(raw[r + h2][u], x[h2]);
+          } else if (CONTIG) {
+#pragma unroll
+            for (int h = 0; h < B / 4; ++h) {
+              const float4 f =
+                  *reinterpret_cast<const float4 *>(trow[h2] + lds_pos(base[u] + 4 * h));
+              x[h2][4 * h] = f.x; x[h2][4 * h + 1] = f.y; x[h2][4 * h + 2] = f.z; x[h2][4 * h + 3] = f.w;
+            }
+          } else {
+#pragma unroll
+            for (int j = 0; j < B; ++j) x[h2][j] = trow[h2][lds_pos(base[u] + j * S)];
           }
-        } else {
-#pragma unroll
-          for (int j = 0; j < B; ++j) x[j] = trow[lds_pos(base[u] + j * S)];
         }
-        block_mul<B>(x, prm[u], y);
-        if (MODE == 2) {
-          Out::template store<CONTIG>(Yt + (int64_t)r * ldy + base[u], S, y);
-        } else if (CONTIG) {
 #pragma unroll
-          for (int h = 0; h < B / 4; ++h)
-            *reinterpret_cast<float4 *>(trow + lds_pos(base[u] + 4 * h)) =
-                make_float4(y[4 * h], y[4 * h + 1], y[4 * h + 2], y[4 * h + 3]);
-        } else {
+        for (int h2 = 0; h2 < 2; ++h2) {
+          if (h2 == 1 && !two) break;
+          block_mul<B>(x[h2], prm[u], y);
+          if (MODE == 2) {
+            Out::template store<CONTIG>(Yt + (int64_t)(r + h2) * ldy + base[u], S, y);
+          } else if (CONTIG) {
 #pragma unroll
-          for (int j = 0; j < B; ++j) trow[lds_pos(base[u] + j * S)] = y[j];
+            for (int h = 0; h < B / 4; ++h)
+              *reinterpret_cast<float4 *>(trow[h2] + lds_pos(base[u] + 4 * h)) =
+                  make_float4(y[4 * h], y[4 * h + 1], y[4 * h + 2], y[4 * h + 3]);
+          } else {
+#pragma unroll
+            for (int j = 0; j < B; ++j) trow[h2][lds_pos(base[u] + j * S)] = y[j];
+          }
         }
       }
     }
