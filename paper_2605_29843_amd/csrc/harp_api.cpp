@@ -37,7 +37,8 @@ namespace {
 // latest the program's last - multiplies it back in).  The arithmetic is that of the dense
 // product carried out in scaled units, so rounding errors stay relative to the same
 // quantities.  A program takes this form only if every pending scale stays within
-// [2^-60, 2^60] (no overflow for |x| < 2^64); otherwise it falls back to lifting.
+// [2^-60, 2^60] and every shear factor within 2^40 in magnitude (no overflow for |x| < 2^64);
+// otherwise it falls back to lifting.
 enum StageForm { FORM_DENSE = 0, FORM_LIFT = 1, FORM_SCALED = 2 };
 
 struct StageEff {
@@ -106,7 +107,8 @@ bool build_effective(const harp_plan *plan, const std::vector<const float *> &bl
               a1 <= kScaleMax))
           return false;
         const float f0 = (float)(m10 / m00), f1 = (float)(m01 / m11);
-        if (!std::isfinite(f0) || !std::isfinite(f1)) return false;
+        // |shear factor| <= 2^40: with scales >= 2^-60 the sheared values of |x| < 2^64 stay finite
+        if (!(std::fabs(f0) <= 1099511627776.0f) || !(std::fabs(f1) <= 1099511627776.0f)) return false;
         se.la[c] = f0;
         se.lb[c] = f1;
         tau[i0] = m00;

@@ -146,7 +146,7 @@ def _radix2_plan_with_special_blocks(d, m, special, seed):
 
 
 @pytest.mark.parametrize("d", [256, 4096])
-@pytest.mark.parametrize("case", ["quarter_turn", "swap", "near_quarter_turn", "general"])
+@pytest.mark.parametrize("case", ["quarter_turn", "swap", "near_quarter_turn", "tiny_diagonal", "general"])
 def test_radix2_blocks_with_zero_or_tiny_diagonal(harp, d, case):
     """The two-shear form divides by the diagonal of a block: blocks with an exactly zero
     diagonal (quarter turns, swaps) must take the lifting fallback, nearly zero ones and
@@ -159,6 +159,8 @@ def test_radix2_blocks_with_zero_or_tiny_diagonal(harp, d, case):
         "swap": lambda c: np.array([[0, 1], [1, 0]], np.float32),
         "near_quarter_turn": lambda c: np.array([[np.sin(eps), -np.cos(eps)], [np.cos(eps), np.sin(eps)]],
                                                 np.float32),
+        # diagonal 1e-13: the shear factor would be 1e13, beyond the plan builder's bound
+        "tiny_diagonal": lambda c: np.array([[1e-13, -1.0], [1.0, 1e-13]], np.float32),
         "general": lambda c: np.array([[1.5, 0.25 * (c % 5)], [-0.5, 0.75]], np.float32),
     }[case]
     radices, blocks, signs = _radix2_plan_with_special_blocks(d, m, special, seed=d + len(case))
