@@ -14,6 +14,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <algorithm>
+
 #include "harp_internal.h"
 
 namespace harp {
@@ -71,18 +73,17 @@ struct BlockIo<uint16_t, B> {
   }
   template <bool C>
   __device__ static __forceinline__ void store(uint16_t *p, int S, const float (&y)[B]) {
-    uint32_t w[B / 2];
+    uint32_t w[(B + 1) / 2];
 #pragma unroll
-    for (int m = 0; m < B / 2; ++m) w[m] = pack_bf16(y[2 * m], y[2 * m + 1]);
+    for (int m = 0; m < (B + 1) / 2; ++m)
+      w[m] = pack_bf16(y[2 * m], (2 * m + 1 < B) ? y[2 * m + 1] : 0.0f);
     if (C) {
       if (B == 8) *reinterpret_cast<uint4 *>(p) = make_uint4(w[0], w[1], w[2], w[3]);
       else *reinterpret_cast<uint2 *>(p) = make_uint2(w[0], w[1]);
     } else {
 #pragma unroll
-      for (int m = 0; m < B / 2; ++m) {
-        p[(size_t)(2 * m) * S] = (uint16_t)(w[m] & 0xffffu);
-        p[(size_t)(2 * m + 1) * S] = (uint16_t)(w[m] >> 16);
-      }
+      for (int j = 0; j < B; ++j)
+        p[(size_t)j * S] = (uint16_t)((j & 1) ? (w[j / 2] >> 16) : (w[j / 2] & 0xffffu));
     }
   }
 };
@@ -137,9 +138,11 @@ __device__ __forceinline__ void block_mul(const float (&x)[B], const float (&prm
 // One stage on the rows of the tile.  MODE 0: inputs from the prefetched device-memory words
 // `raw`, outputs to LDS; 1: LDS in place; 2: inputs from LDS, outputs to device memory.
 // CONTIG: the stage's stride is 1 (16-byte accesses); it can only be the first or last stage.
-template <typename TI, typename TO, int B, int BPT, int MODE, bool CONTIG>
+// nqa: blocks of the stage in one chunk row; with GUARD, threads whose block index is beyond
+// it idle (kernels whose stages have different block counts).
+template <typename TI, typename TO, int B, int BPT, int MODE, bool CONTIG, bool GUARD = false>
 __device__ __forceinline__ void radix_pass(float *tile, int dpad, int nr, int S, int tid, int NT,
-                                           const float (&prm)[BPT][B * B],
+                                           int nqa, const float (&prm)[BPT][B * B],
                                            const uint32_t (&raw)[kRMax][BPT][B], TO *Yt,
                                            int64_t ldy) {
   using In = BlockIo<TI, B>;
@@ -159,6 +162,7 @@ __device__ __forceinline__ void radix_pass(float *tile, int dpad, int nr, int S,
       float *trow[2] = {tile + r * dpad, tile + (two ? r + 1 : r) * dpad};
 #pragma unroll
       for (int u = 0; u < BPT; ++u) {
+        if (GUARD && tid + u * NT >= nqa) continue;
         float x[2][B], y[B];
 #pragma unroll
         for (int h2 = 0; h2 < 2; ++h2) {
@@ -253,7 +257,7 @@ __global__ __launch_bounds__(512) void harp_radix_kernel(const TI *__restrict__ 
   }
   load_params(prog.pass[p0], cur);
   load_params(prog.pass[p0 + 1], nxt);     // in flight during the first stage
-  radix_pass<TI, TO, B, BPT, 0, !TRN>(tile, dpad, nr, S0, tid, NT, cur, raw, Yt, ldy);
+  radix_pass<TI, TO, B, BPT, 0, !TRN>(tile, dpad, nr, S0, tid, NT, nqc, cur, raw, Yt, ldy);
   __syncthreads();
   for (int p = 1; p < np - 1; ++p) {
 #pragma unroll
@@ -261,11 +265,176 @@ __global__ __launch_bounds__(512) void harp_radix_kernel(const TI *__restrict__ 
 #pragma unroll
       for (int v = 0; v < V; ++v) cur[u][v] = nxt[u][v];
     load_params(prog.pass[p0 + p + 1], nxt);
-    radix_pass<TI, TO, B, BPT, 1, false>(tile, dpad, nr, prog.pass[p0 + p].S, tid, NT, cur, raw, Yt, ldy);
+    radix_pass<TI, TO, B, BPT, 1, false>(tile, dpad, nr, prog.pass[p0 + p].S, tid, NT, nqc, cur, raw,
+                                         Yt, ldy);
     __syncthreads();
   }
-  radix_pass<TI, TO, B, BPT, 2, TRN>(tile, dpad, nr, prog.pass[p0 + np - 1].S, tid, NT, nxt, raw, Yt,
-                                ldy);
+  radix_pass<TI, TO, B, BPT, 2, TRN>(tile, dpad, nr, prog.pass[p0 + np - 1].S, tid, NT, nqc, nxt, raw,
+                                     Yt, ldy);
+}
+
+// ------------------------------------------------------------------------------------------
+// The same organisation for chunks whose stages have different radices in 3..8 (the greedy
+// schedules of the paper: (8,8,8,7) inside d = 14336, (8,8,8,5) inside 5120): the radix of a
+// stage is a run-time value dispatched to the compile-time bodies above, one block per thread
+// (blockDim.x = the largest number of blocks of any stage; threads beyond a stage's count idle).
+typedef float vec4f_t __attribute__((ext_vector_type(4)));
+
+template <int B>
+__device__ __forceinline__ void mixed_load_params(const PassDesc &pd, unsigned qg, bool active,
+                                                  float (&dst)[64]) {
+  if (!active) return;
+  const unsigned nq = (unsigned)pd.nq;
+  if (B == 4 || B == 8) {   // 16-byte loads from the four-values-per-load copy
+    const __attribute__((address_space(1))) vec4f_t *p4 =
+        (const __attribute__((address_space(1))) vec4f_t *)pd.aux;
+#pragma unroll
+    for (int v4 = 0; v4 < B * B / 4; ++v4) {
+      const vec4f_t f = p4[(unsigned)v4 * nq + qg];
+      dst[4 * v4] = f.x; dst[4 * v4 + 1] = f.y; dst[4 * v4 + 2] = f.z; dst[4 * v4 + 3] = f.w;
+    }
+  } else {
+    const gfloat_t p1 = (gfloat_t)pd.params;
+#pragma unroll
+    for (int v = 0; v < B * B; ++v) dst[v] = p1[(unsigned)v * nq + qg];
+  }
+}
+
+template <typename TI, typename TO, int B, int MODE, bool CONTIG>
+__device__ __forceinline__ void mixed_pass(float *tile, int dpad, int nr, int S, int tid, int NT,
+                                           int nqa, const float (&prm)[64], const TI *Xt,
+                                           int64_t ldx, TO *Yt, int64_t ldy) {
+  using In = BlockIo<TI, B>;
+  uint32_t raw[kRMax][1][B];
+  if (MODE == 0) {
+    const int hi = tid / S, lo = tid - hi * S;
+    const int base0 = hi * B * S + lo;
+#pragma unroll
+    for (int r = 0; r < kRMax; ++r) {
+#pragma unroll
+      for (int m = 0; m < B; ++m) raw[r][0][m] = 0u;
+      if (r < nr && tid < nqa) In::template load<CONTIG>(Xt + (int64_t)r * ldx + base0, S, raw[r][0]);
+    }
+  }
+  radix_pass<TI, TO, B, 1, MODE, CONTIG, true>(tile, dpad, nr, S, tid, NT, nqa,
+                                         reinterpret_cast<const float(&)[1][B * B]>(prm), raw, Yt,
+                                         ldy);
+}
+
+#define HARP_RADIX_SWITCH(b, STMT)                                        \
+  switch (b) {                                                             \
+    case 3: { constexpr int RB = 3; STMT; } break;                         \
+    case 4: { constexpr int RB = 4; STMT; } break;                         \
+    case 5: { constexpr int RB = 5; STMT; } break;                         \
+    case 6: { constexpr int RB = 6; STMT; } break;                         \
+    case 7: { constexpr int RB = 7; STMT; } break;                         \
+    default: { constexpr int RB = 8; STMT; } break;                        \
+  }
+
+template <typename TI, typename TO>
+__global__ __launch_bounds__(512) void harp_mixed_radix_kernel(
+    const TI *__restrict__ X, int64_t ldx, TO *__restrict__ Y, int64_t ldy, int64_t n, int R,
+    int nchunk, int chunk, const Program *__restrict__ progp, int p0, int np) {
+  extern __shared__ float tile[];
+  const int tid = threadIdx.x, NT = blockDim.x;
+  const int kch = (int)(blockIdx.x % (unsigned)nchunk);
+  const int64_t row0 = (int64_t)(blockIdx.x / (unsigned)nchunk) * R;
+  const int nr = (int)((n - row0 < R) ? (n - row0) : R);
+  const int dpad = lds_pos(chunk);
+  const Program &prog = *progp;
+  const TI *Xt = X + row0 * ldx + (int64_t)kch * chunk;
+  TO *Yt = Y + row0 * ldy + (int64_t)kch * chunk;
+
+  float cur[64], nxt[64];
+  auto load_any = [&](const PassDesc &pd, float (&dst)[64]) {
+    const int nqa = chunk / pd.b;
+    const unsigned qg = (unsigned)kch * nqa + tid;
+    HARP_RADIX_SWITCH(pd.b, mixed_load_params<RB>(pd, qg, tid < nqa, dst));
+  };
+  const PassDesc &first = prog.pass[p0];
+  const PassDesc &last = prog.pass[p0 + np - 1];
+  load_any(first, cur);
+  load_any(prog.pass[p0 + 1], nxt);
+  {
+    const int nqa = chunk / first.b;
+    if (first.S == 1 && first.b == 8)
+      mixed_pass<TI, TO, 8, 0, true>(tile, dpad, nr, 1, tid, NT, nqa, cur, Xt, ldx, Yt, ldy);
+    else if (first.S == 1 && first.b == 4)
+      mixed_pass<TI, TO, 4, 0, true>(tile, dpad, nr, 1, tid, NT, nqa, cur, Xt, ldx, Yt, ldy);
+    else
+      HARP_RADIX_SWITCH(first.b, (mixed_pass<TI, TO, RB, 0, false>(tile, dpad, nr, first.S, tid, NT,
+                                                                    nqa, cur, Xt, ldx, Yt, ldy)));
+  }
+  __syncthreads();
+  for (int p = 1; p < np - 1; ++p) {
+#pragma unroll
+    for (int v = 0; v < 64; ++v) cur[v] = nxt[v];
+    load_any(prog.pass[p0 + p + 1], nxt);
+    const PassDesc &pd = prog.pass[p0 + p];
+    const int nqa = chunk / pd.b;
+    HARP_RADIX_SWITCH(pd.b, (mixed_pass<TI, TO, RB, 1, false>(tile, dpad, nr, pd.S, tid, NT, nqa, cur,
+                                                              Xt, ldx, Yt, ldy)));
+    __syncthreads();
+  }
+  {
+    const int nqa = chunk / last.b;
+    if (last.S == 1 && last.b == 8)
+      mixed_pass<TI, TO, 8, 2, true>(tile, dpad, nr, 1, tid, NT, nqa, nxt, Xt, ldx, Yt, ldy);
+    else if (last.S == 1 && last.b == 4)
+      mixed_pass<TI, TO, 4, 2, true>(tile, dpad, nr, 1, tid, NT, nqa, nxt, Xt, ldx, Yt, ldy);
+    else
+      HARP_RADIX_SWITCH(last.b, (mixed_pass<TI, TO, RB, 2, false>(tile, dpad, nr, last.S, tid, NT, nqa,
+                                                                  nxt, Xt, ldx, Yt, ldy)));
+  }
+}
+#undef HARP_RADIX_SWITCH
+
+// stages of radices 3..8, not all equal, that tile the chunk; returns the workgroup size or 0
+int mixed_decode(const Program &pg, int p0, int np, int chunk) {
+  if (np < 2 || np > 8) return 0;
+  const PassDesc *ps = pg.pass + p0;
+  int64_t prod = 1;
+  int maxq = 0;
+  for (int p = 0; p < np; ++p) {
+    const int b = ps[p].b;
+    if (ps[p].kind != PASS_SMALL || b < 3 || b > 8) return 0;
+    if ((b == 4 || b == 8) && ps[p].aux == nullptr) return 0;
+    if (chunk % b || ps[p].S < 1 || (chunk / b) % ps[p].S) return 0;
+    prod *= b;
+    maxq = std::max(maxq, chunk / b);
+  }
+  if (prod != chunk || maxq > 512) return 0;
+  return (maxq + 63) / 64 * 64;
+}
+
+template <typename TI, typename TO>
+harp_status_t launch_mixed_io(const harp_plan *plan, const HostProgram &hp, int p0, int np,
+                              int chunk, int nt, const void *X, int64_t ldx, void *Y, int64_t ldy,
+                              int64_t n, hipStream_t stream) {
+  const int dpad = chunk + (chunk >> 6) * 8;
+  int R = kRMax;
+  while (R > 1 && (size_t)R * dpad * 4 > (size_t)plan->lds_bytes) --R;
+  if ((size_t)R * dpad * 4 > (size_t)plan->lds_bytes) return HARP_ERR_UNSUPPORTED;
+  if (plan->rows_override > 0 && plan->rows_override < R) R = plan->rows_override;
+  if (R > n) R = (int)n;
+  const int nchunk = (int)(plan->d / chunk);
+  const int64_t tiles = ((n + R - 1) / R) * nchunk;
+  if (tiles > 0x7fffffff) return HARP_ERR_UNSUPPORTED;
+  const size_t lds = (size_t)R * dpad * 4;
+  auto kern = harp_mixed_radix_kernel<TI, TO>;
+  static thread_local int attr_done_dev = -1;   // per instantiation
+  if (attr_done_dev != plan->device) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                            hipFuncAttributeMaxDynamicSharedMemorySize,
+                            plan->lds_bytes) != hipSuccess) {
+      (void)hipGetLastError();
+      return HARP_ERR_DEVICE;
+    }
+    attr_done_dev = plan->device;
+  }
+  hipLaunchKernelGGL(kern, dim3((unsigned)tiles), dim3(nt), lds, stream, (const TI *)X, ldx,
+                     (TO *)Y, ldy, n, R, nchunk, chunk, hp.dev, p0, np);
+  return hipGetLastError() == hipSuccess ? HARP_OK : HARP_ERR_DEVICE;
 }
 
 struct RadixShape {
@@ -355,7 +524,7 @@ harp_status_t launch_radix_io(const harp_plan *plan, const HostProgram &hp, int 
 bool radix_supported(const harp_plan *plan, const Program &pg, int p0, int np, int chunk,
                      const void *X, int64_t ldx, const void *Y, int64_t ldy) {
   if (plan->algo == HARP_ALGO_GENERIC) return false;
-  if (!radix_decode(pg, p0, np, chunk).ok) return false;
+  if (!radix_decode(pg, p0, np, chunk).ok && mixed_decode(pg, p0, np, chunk) == 0) return false;
   // 16-byte accesses of the contiguous stage for either element type
   if ((ldx % 8) || (ldy % 8) || ((uintptr_t)X % 16) || ((uintptr_t)Y % 16)) return false;
   return (size_t)(chunk + (chunk >> 6) * 8) * 4 <= (size_t)plan->lds_bytes;
@@ -366,7 +535,17 @@ harp_status_t launch_radix_kernel(const harp_plan *plan, const HostProgram &hp, 
                                   void *Y, int64_t ldy, harp_dtype_t dt_out, int64_t n,
                                   hipStream_t stream) {
   const RadixShape rs = radix_decode(hp.prog, p0, np, chunk);
-  if (!rs.ok) return HARP_ERR_UNSUPPORTED;
+  if (!rs.ok) {
+    const int nt = mixed_decode(hp.prog, p0, np, chunk);
+    if (nt == 0) return HARP_ERR_UNSUPPORTED;
+    if (dt_in == HARP_BF16 && dt_out == HARP_BF16)
+      return launch_mixed_io<uint16_t, uint16_t>(plan, hp, p0, np, chunk, nt, X, ldx, Y, ldy, n, stream);
+    if (dt_in == HARP_BF16 && dt_out == HARP_F32)
+      return launch_mixed_io<uint16_t, float>(plan, hp, p0, np, chunk, nt, X, ldx, Y, ldy, n, stream);
+    if (dt_in == HARP_F32 && dt_out == HARP_BF16)
+      return launch_mixed_io<float, uint16_t>(plan, hp, p0, np, chunk, nt, X, ldx, Y, ldy, n, stream);
+    return launch_mixed_io<float, float>(plan, hp, p0, np, chunk, nt, X, ldx, Y, ldy, n, stream);
+  }
   if (dt_in == HARP_BF16 && dt_out == HARP_BF16)
     return launch_radix_io<uint16_t, uint16_t>(plan, hp, p0, rs, chunk, X, ldx, Y, ldy, n, stream);
   if (dt_in == HARP_BF16 && dt_out == HARP_F32)

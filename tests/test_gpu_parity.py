@@ -510,6 +510,20 @@ def test_split_program_with_small_radix_chunk(harp, d, radices, n):
     run_case(harp, d, radices, n, "bf16", kind="qr", seed=d)
 
 
+MIXED_RADIX_CASES = [
+    (3584, [8, 8, 8, 7], 19), (2560, [8, 8, 8, 5], 9), (14336, [8, 8, 8, 7, 4], 37), (5120, [8, 8, 8, 5, 2], 21),
+    (1344, [8, 8, 7, 3], 5), (960, [4, 8, 5, 6], 13), (11008, [8, 8, 4, 43], 11),
+]
+
+
+@pytest.mark.parametrize("d,radices,n", MIXED_RADIX_CASES)
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_mixed_small_radix_tile_kernel(harp, d, radices, n, dtype):
+    """Chunks whose stages have different radices in 3..8 (the paper's greedy schedules)."""
+    run_case(harp, d, radices, n, dtype, kind="qr", seed=d + n)
+    run_case(harp, d, radices, n, dtype, kind="qr", seed=d + n + 1, ld_pad=8, rows=3)
+
+
 def test_radix_tile_kernel_in_place(harp):
     import torch
     d, radices, n = 4096, [8] * 4, 11
