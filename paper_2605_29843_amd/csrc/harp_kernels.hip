@@ -590,6 +590,71 @@ __global__ __launch_bounds__(256) void harp_transpose_kernel(const TS *__restric
   }
 }
 
+// Four consecutive elements at p (16-byte aligned for float, 8-byte for bf16).
+__device__ __forceinline__ void load_four(const float *p, float (&v)[4]) {
+  const float4 f = *reinterpret_cast<const float4 *>(p);
+  v[0] = f.x; v[1] = f.y; v[2] = f.z; v[3] = f.w;
+}
+__device__ __forceinline__ void load_four(const uint16_t *p, float (&v)[4]) {
+  const uint2 w = *reinterpret_cast<const uint2 *>(p);
+  v[0] = __uint_as_float(w.x << 16); v[1] = __uint_as_float(w.x & 0xffff0000u);
+  v[2] = __uint_as_float(w.y << 16); v[3] = __uint_as_float(w.y & 0xffff0000u);
+}
+__device__ __forceinline__ void store_four(float *p, const float (&v)[4]) {
+  *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+}
+__device__ __forceinline__ void store_four(uint16_t *p, const float (&v)[4]) {
+  *reinterpret_cast<uint2 *>(p) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+}
+
+// The same on 64 x 64 tiles with four elements per access on both sides (256-byte runs of a
+// float row); leading dimensions multiples of 4 and 16-byte aligned bases.  Vectors that
+// cross the matrix edge fall back to single elements.
+template <typename TS, typename TD>
+__global__ __launch_bounds__(256) void harp_transpose64_kernel(const TS *__restrict__ src,
+                                                               int64_t lds_, TD *__restrict__ dst,
+                                                               int64_t ldd, int64_t rows,
+                                                               int64_t cols) {
+  __shared__ float buf[64][65];
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;   // 16 vectors x 16 rows per sweep
+  const int64_t c0 = (int64_t)blockIdx.x * 64, r0 = (int64_t)blockIdx.y * 64;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int lr = ty + 16 * k;
+    const int64_t r = r0 + lr, c = c0 + 4 * tx;
+    if (r < rows) {
+      if (c + 3 < cols) {
+        float v[4];
+        load_four(src + r * lds_ + c, v);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) buf[lr][4 * tx + i] = v[i];
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (c + i < cols) buf[lr][4 * tx + i] = load_one(src + r * lds_ + c + i);
+      }
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int lc = ty + 16 * k;
+    const int64_t c = c0 + lc, r = r0 + 4 * tx;
+    if (c < cols) {
+      if (r + 3 < rows) {
+        float v[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = buf[4 * tx + i][lc];
+        store_four(dst + c * ldd + r, v);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (r + i < rows) store_one(dst + c * ldd + r + i, buf[4 * tx + i][lc]);
+      }
+    }
+  }
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void harp_copy2d_kernel(const T *__restrict__ src, int64_t lds_,
                                                           T *__restrict__ dst, int64_t ldd,
@@ -634,8 +699,14 @@ harp_status_t launch_tile_typed(const harp_plan *plan, const Program *dprog, int
 template <typename TS, typename TD>
 harp_status_t launch_transpose_typed(const void *src, int64_t lds_, void *dst, int64_t ldd,
                                      int64_t rows, int64_t cols, hipStream_t stream) {
-  const dim3 grid((unsigned)((cols + 31) / 32), (unsigned)((rows + 31) / 32));
   if ((rows + 31) / 32 > 65535 * 16) return HARP_ERR_UNSUPPORTED;
+  if (lds_ % 4 == 0 && ldd % 4 == 0 && (uintptr_t)src % 16 == 0 && (uintptr_t)dst % 16 == 0) {
+    const dim3 grid64((unsigned)((cols + 63) / 64), (unsigned)((rows + 63) / 64));
+    hipLaunchKernelGGL((harp_transpose64_kernel<TS, TD>), grid64, dim3(256), 0, stream,
+                       (const TS *)src, lds_, (TD *)dst, ldd, rows, cols);
+    return hipGetLastError() == hipSuccess ? HARP_OK : HARP_ERR_DEVICE;
+  }
+  const dim3 grid((unsigned)((cols + 31) / 32), (unsigned)((rows + 31) / 32));
   hipLaunchKernelGGL((harp_transpose_kernel<TS, TD>), grid, dim3(256), 0, stream, (const TS *)src,
                      lds_, (TD *)dst, ldd, rows, cols);
   return hipGetLastError() == hipSuccess ? HARP_OK : HARP_ERR_DEVICE;

@@ -563,6 +563,7 @@ def _plan_tuple(d, radices, blocks, signs):
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("do,ru,di,rv", [(24, [2, 3, 4], 40, [8, 5]), (64, [2] * 6, 48, [2, 2, 2, 2, 3]),
+                                         (14, [2, 7], 30, [2, 3, 5]), (192, [4, 6, 8], 130, [2, 5, 13]),
                                          (256, [2] * 8, 344, [2, 2, 2, 43])])
 def test_rotate_weight_small_dense(harp, dtype, do, ru, di, rv):
     import torch
