@@ -7,7 +7,7 @@ in device memory: ``harp_apply`` (load + signs, every stage on chip, store) foll
 2 n row-transforms.  Batches rotate through a pool larger than the 256 MB Infinity Cache so
 the timed launches read and write device memory, not a cache.
 
-Prints ONE JSON line (metric of the benchmark spec: rotation rows/s and achieved HBM GB/s as a
+Prints ONE JSON line (metric: rotation rows/s and achieved HBM GB/s as a
 fraction of the 8 TB/s peak), with a ``roofline`` object for the dominant kernel (timed
 with HIP events on the launch stream) and a ``cpu_baseline`` object (the float64 oracle
 timed on the host cores on a bounded sample of the same workload).
