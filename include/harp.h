@@ -174,6 +174,24 @@ harp_status_t harp_plan_create_from_theta(harp_plan_t **out, int64_t d, int32_t 
                                           const int32_t *mixer_kinds, const float *const *mixers,
                                           const int8_t *signs, uint32_t flags);
 
+/*
+ * Kronecker fallback (Sec. 3, "Mixed-Radix dimensions and Kronecker fallback", the equation
+ * T_d = (H~_K / sqrt(K)) (x) T_{n2}): expands a processor T_{n2} on n2 coordinates and a
+ * Hadamard-like table H~_K (K x K row-major, entries +-1, H~ H~^T = K I) into the schedule and
+ * blocks of the equivalent Mixed-Radix processor on d = K n2 coordinates: every stage of
+ * T_{n2} repeated for each of the K slices (tied parameters), then one stage of radix K at
+ * stride n2 whose blocks all equal H~_K / sqrt(K).  With x viewed as a K x n2 array (index
+ * k n2 + j) the result acts as x -> x (H~_K / sqrt(K) (x) T_{n2}).  Host only.
+ *   radices_out  m2 + 1 ints, written.
+ *   blocks_out   m2 + 1 host buffers: stage t < m2: K n2 b_t floats; stage m2: n2 K K floats.
+ * Pass the result to harp_plan_create with d = K n2, m = m2 + 1.  HARP_ERR_INVALID_ARG for a
+ * table entry other than +-1, HARP_ERR_NOT_ORTHOGONAL if H~ H~^T != K I, HARP_ERR_UNSUPPORTED
+ * for K > HARP_MAX_RADIX.
+ */
+harp_status_t harp_kronecker_blocks(int32_t K, const float *table, int64_t n2, int32_t m2,
+                                    const int32_t *radices2, const float *const *blocks2,
+                                    int32_t *radices_out, float *const *blocks_out);
+
 /* Greedy Mixed-Radix schedule (appendix Alg. 2): peel b_base while it divides d, then the
  * factors min(b_max, r) .. 2 in decreasing order, then any leftover as one last stage.
  * out_radices must hold HARP_MAX_STAGES ints.  Host only; no HIP call. */

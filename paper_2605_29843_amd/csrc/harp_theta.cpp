@@ -173,4 +173,38 @@ harp_status_t harp_plan_create_from_theta(harp_plan_t **out, int64_t d, int32_t 
   }
 }
 
+harp_status_t harp_kronecker_blocks(int32_t K, const float *table, int64_t n2, int32_t m2,
+                                    const int32_t *radices2, const float *const *blocks2,
+                                    int32_t *radices_out, float *const *blocks_out) {
+  if (!table || !blocks2 || !radices_out || !blocks_out) return HARP_ERR_INVALID_ARG;
+  if (K < 2) return HARP_ERR_INVALID_ARG;
+  harp_status_t st = check_schedule(n2, m2, radices2);
+  if (st != HARP_OK) return st;
+  if (K > HARP_MAX_RADIX || m2 + 1 > HARP_MAX_STAGES) return HARP_ERR_UNSUPPORTED;
+  for (int t = 0; t < m2; ++t)
+    if (!blocks2[t] || !blocks_out[t]) return HARP_ERR_INVALID_ARG;
+  if (!blocks_out[m2]) return HARP_ERR_INVALID_ARG;
+  // the table must be Hadamard-like: entries +-1 and H H^T = K I
+  for (int i = 0; i < K * K; ++i)
+    if (table[i] != 1.0f && table[i] != -1.0f) return HARP_ERR_INVALID_ARG;
+  for (int i = 0; i < K; ++i)
+    for (int j = 0; j < K; ++j) {
+      int acc = 0;
+      for (int k = 0; k < K; ++k) acc += (int)table[i * K + k] * (int)table[j * K + k];
+      if (acc != (i == j ? K : 0)) return HARP_ERR_NOT_ORTHOGONAL;
+    }
+  for (int t = 0; t < m2; ++t) {
+    const int b = radices2[t];
+    const size_t per = (size_t)(n2 / b) * b * b;   // one copy of the stage's blocks
+    radices_out[t] = b;
+    for (int k = 0; k < K; ++k)
+      for (size_t i = 0; i < per; ++i) blocks_out[t][(size_t)k * per + i] = blocks2[t][i];
+  }
+  radices_out[m2] = K;
+  const double s = 1.0 / std::sqrt((double)K);
+  for (int64_t c = 0; c < n2; ++c)
+    for (int i = 0; i < K * K; ++i) blocks_out[m2][(size_t)c * K * K + i] = (float)(table[i] * s);
+  return HARP_OK;
+}
+
 }  // extern "C"

@@ -41,6 +41,8 @@ _SIGS = {
     "harp_plan_destroy": (_i32, [_vp]),
     "harp_blocks_from_theta": (_i32, [_i64, _i32, C.POINTER(_i32), C.POINTER(_vp), C.POINTER(_i32),
                                       C.POINTER(_vp), C.POINTER(_vp)]),
+    "harp_kronecker_blocks": (_i32, [_i32, _vp, _i64, _i32, C.POINTER(_i32), C.POINTER(_vp),
+                                     C.POINTER(_i32), C.POINTER(_vp)]),
     "harp_plan_create_from_theta": (_i32, [C.POINTER(_vp), _i64, _i32, C.POINTER(_i32), C.POINTER(_vp),
                                            C.POINTER(_i32), C.POINTER(_vp), _vp, _u32]),
     "harp_apply": (_i32, [_vp, _vp, _i64, _vp, _i64, _i64, _i32, _vp]),
@@ -157,6 +159,26 @@ def harp_blocks_from_theta(d: int, radices, thetas=None, mixers=None) -> list:
     rad = (_i32 * max(m, 1))(*radices)
     _check(lib.harp_blocks_from_theta(int(d), m, rad, th, kinds, mx, op), "harp_blocks_from_theta")
     return outs
+
+
+def harp_kronecker_blocks(table, n2: int, radices2, blocks2):
+    """(radices, blocks) of the Mixed-Radix processor equal to (table / sqrt(K)) (x) T_{n2}."""
+    table = np.ascontiguousarray(table, dtype=np.float32)
+    K = int(table.shape[0])
+    if table.shape != (K, K):
+        raise ValueError("table must be square")
+    radices2 = [int(b) for b in radices2]
+    m2 = len(radices2)
+    ins = [np.ascontiguousarray(blocks2[t], dtype=np.float32) for t in range(m2)]
+    outs = [np.empty((K * (int(n2) // b), b, b), dtype=np.float32) for b in radices2]
+    outs.append(np.empty((int(n2), K, K), dtype=np.float32))
+    rad2 = (_i32 * max(m2, 1))(*radices2)
+    ip = (_vp * max(m2, 1))(*[a.ctypes.data for a in ins])
+    op = (_vp * (m2 + 1))(*[o.ctypes.data for o in outs])
+    rout = (_i32 * (m2 + 1))()
+    _check(lib.harp_kronecker_blocks(K, table.ctypes.data, int(n2), m2, rad2, ip, rout, op),
+           "harp_kronecker_blocks")
+    return [int(rout[i]) for i in range(m2 + 1)], outs
 
 
 class Plan:

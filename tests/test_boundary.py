@@ -160,3 +160,37 @@ def test_blocks_from_theta_host_front_end_matches_the_oracle():
         harp.harp_blocks_from_theta(10, [2, 3])
     assert e.value.status == harp.HARP_ERR_BAD_SCHEDULE
 
+
+def test_kronecker_blocks_expand_to_the_kronecker_product():
+    """Host expansion of the Kronecker fallback, checked through the oracle's explicit dense
+    construction: U_d == kron(table / sqrt(K), U_{n2})."""
+    import numpy as np
+    from oracle import harp_oracle as ho
+    rng = np.random.default_rng(5)
+    n2, radices2 = 16, [2, 4, 2]
+    blocks2 = gi.make_blocks(n2, radices2, "orth", rng)
+    # a 12 x 12 Hadamard-like table (Paley construction, q = 11) and the 2 x 2 one
+    q = 11
+    res = {(x * x) % q for x in range(1, q)}
+    Q = np.array([[0 if i == j else (1 if ((i - j) % q) in res else -1) for j in range(q)] for i in range(q)])
+    S = np.zeros((q + 1, q + 1), dtype=np.int64)
+    S[0, 1:] = 1
+    S[1:, 0] = -1
+    S[1:, 1:] = Q
+    H12 = (np.eye(q + 1, dtype=np.int64) + S).astype(np.float32)
+    assert np.array_equal(H12 @ H12.T, 12 * np.eye(12))
+    for table in (np.array([[1, 1], [1, -1]], np.float32), H12):
+        K = table.shape[0]
+        radices, blocks = harp.harp_kronecker_blocks(table, n2, radices2, blocks2)
+        assert radices == radices2 + [K]
+        U = ho.U_explicit(K * n2, radices, blocks)
+        U2 = ho.U_explicit(n2, radices2, blocks2)
+        np.testing.assert_allclose(U, np.kron(table.astype(np.float64) / np.sqrt(K), U2), atol=1e-6)
+    bad = np.array([[1, 1], [1, 1]], np.float32)
+    with pytest.raises(harp.HarpError) as e:
+        harp.harp_kronecker_blocks(bad, n2, radices2, blocks2)
+    assert e.value.status == harp.HARP_ERR_NOT_ORTHOGONAL
+    with pytest.raises(harp.HarpError) as e:
+        harp.harp_kronecker_blocks(np.array([[1, 0.5], [1, -1]], np.float32), n2, radices2, blocks2)
+    assert e.value.status == harp.HARP_ERR_INVALID_ARG
+

@@ -485,6 +485,36 @@ def test_plan_from_theta_matches_the_oracle_blocks(harp, d, radices, mixers):
     plan.destroy()
 
 
+def test_kronecker_fallback_plan(harp):
+    """d = 12 * 1024: T_d = (H~_12 / sqrt(12)) (x) T_1024 built by harp_kronecker_blocks."""
+    import torch
+    q = 11
+    res = {(x * x) % q for x in range(1, q)}
+    S = np.zeros((12, 12), dtype=np.int64)
+    S[0, 1:] = 1
+    S[1:, 0] = -1
+    S[1:, 1:] = [[0 if i == j else (1 if ((i - j) % q) in res else -1) for j in range(q)] for i in range(q)]
+    H12 = (np.eye(12, dtype=np.int64) + S).astype(np.float32)
+    n2, radices2 = 1024, [2] * 10
+    rng = np.random.default_rng(77)
+    blocks2 = gi.make_blocks(n2, radices2, "orth", rng)
+    radices, blocks = harp.harp_kronecker_blocks(H12, n2, radices2, blocks2)
+    d = 12 * n2
+    signs = gi.make_signs(d, rng)
+    plan = harp.Plan(d, radices, blocks, signs)
+    n = 19
+    say(f"kronecker d={d} radices={radices} kernel={plan.kernel_name(n)}")
+    X = gi.round_to_bf16(rng.standard_normal((n, d)).astype(np.float32))
+    Y = to_host64(harp.harp_apply(plan, to_device(X, "bf16")))
+    torch.cuda.synchronize()
+    # the definition: reshape to [K, n2], T_1024 along the last axis, H~/sqrt(K) across the first
+    T2 = ho.build_U(n2, radices2, blocks2)
+    Xs = (X.astype(np.float64) * signs).reshape(n, 12, n2)
+    ref = np.einsum("nkj,kl,jm->nlm", Xs, H12.astype(np.float64) / np.sqrt(12.0), T2).reshape(n, d)
+    assert_parity(Y, ref, "bf16", "kronecker apply")
+    plan.destroy()
+
+
 RADIX_TILE_CASES = [
     (512, [8] * 3, 19), (4096, [8] * 4, 37), (4096, [8] * 4, 1), (256, [4] * 4, 9), (1024, [4] * 5, 21),
     (4096, [4] * 6, 13), (4096, [8] * 4, 8),
