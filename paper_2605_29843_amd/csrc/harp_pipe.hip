@@ -277,6 +277,33 @@ __device__ __forceinline__ void pipe_group(const PassDesc &pd, const int t, cons
     }
   };
 
+  // Last group, float32 output, contiguous pass: a thread's 16-byte stores would sit 32 or 64
+  // bytes apart from its neighbours' (the one slow store pattern measured on this chip, about
+  // 60 % of the rate of any other), so the row goes once more through LDS -- through the
+  // positions this wave has just read its input from, which nobody else touches before the
+  // next barrier -- and leaves with 1 KB of consecutive addresses per store instruction.
+  constexpr bool kRelayout = (ROLE == 2) && CONTIG && (sizeof(TO) == 4);
+  auto store_relayout = [&](float *region, const float (&x)[16], TO *yrow) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+      *reinterpret_cast<float4 *>(region + lds_off(4 * c)) =
+          make_float4(x[4 * c], x[4 * c + 1], x[4 * c + 2], x[4 * c + 3]);
+    // the region is private to this wave and LDS serves a wave's accesses in order
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    const unsigned lane = (unsigned)t & 63u, w0 = (unsigned)t & ~63u;
+#pragma unroll
+    for (int u = 0; u < SPT; ++u) {
+      const unsigned run = (w0 + (unsigned)u * TG) * P;     // 64 * P consecutive coordinates
+#pragma unroll
+      for (int g = 0; g < P / 4; ++g) {
+        const unsigned coord = run + (unsigned)g * 256u + 4u * lane;
+        const float4 f = *reinterpret_cast<const float4 *>(region + phys_index((int)coord));
+        *reinterpret_cast<float4 *>(reinterpret_cast<float *>(yrow) + coord) = f;
+      }
+    }
+    asm volatile("" ::: "memory");
+  };
+
   const int npairs = (nr + 1) >> 1;
   const int nsteps = npairs + 2;   // group g works on pair k - g at step k; one barrier per step
   for (int k0 = 0; k0 < nsteps; k0 += 2) {
@@ -302,12 +329,22 @@ __device__ __forceinline__ void pipe_group(const PassDesc &pd, const int t, cons
           lds_read(b + ROWBUF, xb);
         }
         float *wb = (ROLE == 2) ? nullptr : wr_buf + (s & 1) * (2 * ROWBUF);
+        // input half of this step (groups 1, 2); reused as staging by the re-laid-out store
+        float *stage = (ROLE == 0) ? nullptr
+                                   : const_cast<float *>(rd_buf) + ((s + 1) & 1) * (2 * ROWBUF);
         lift_stages<K, DESC, LD, SC>(xa, prm);
-        if (ROLE == 2) Out::store(Y + (int64_t)r0 * ldy, glb_off, xa);
-        else lds_write(wb, xa);
+        if (ROLE == 2) {
+          if (kRelayout) store_relayout(stage, xa, Y + (int64_t)r0 * ldy);
+          else Out::store(Y + (int64_t)r0 * ldy, glb_off, xa);
+        } else {
+          lds_write(wb, xa);
+        }
         lift_stages<K, DESC, LD, SC>(xb, prm);
         if (ROLE == 2) {
-          if (two) Out::store(Y + (int64_t)(r0 + 1) * ldy, glb_off, xb);
+          if (two) {
+            if (kRelayout) store_relayout(stage + ROWBUF, xb, Y + (int64_t)(r0 + 1) * ldy);
+            else Out::store(Y + (int64_t)(r0 + 1) * ldy, glb_off, xb);
+          }
         } else {
           lds_write(wb + ROWBUF, xb);
         }
