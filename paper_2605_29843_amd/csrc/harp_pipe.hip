@@ -277,9 +277,11 @@ __device__ __forceinline__ void pipe_group(const PassDesc &pd, const int t, cons
     }
   };
 
-  // Last group, float32 output, contiguous pass: a thread's 16-byte stores would sit 32 or 64
-  // bytes apart from its neighbours' (the one slow store pattern measured on this chip, about
-  // 60 % of the rate of any other), so the row goes once more through LDS -- through the
+  // Last group, float32 output, contiguous pass: a thread's 16-byte stores would sit 64 bytes
+  // apart from its neighbours' (the one slow store pattern measured on this chip, about 60 % of
+  // the rate of any other; bf16 rows, 32 bytes apart, measured 7 % slower with the detour than
+  // without, and the same detour on the float32 LOADS of a contiguous first pass gained
+  // nothing), so the row goes once more through LDS -- through the
   // positions this wave has just read its input from, which nobody else touches before the
   // next barrier -- and leaves with 1 KB of consecutive addresses per store instruction.
   constexpr bool kRelayout = (ROLE == 2) && CONTIG && (sizeof(TO) == 4);
