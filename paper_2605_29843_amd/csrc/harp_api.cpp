@@ -506,9 +506,38 @@ harp_status_t rotate_impl(const harp_plan_t *pu, const harp_plan_t *pv, Directio
     // rows of W through plan_V only
     return apply_dir(pv, dir, W, ldw, dt, Wout, ldo, dt, d_out, stream);
   }
-  // Column side: (U^T M)^T = M^T U, i.e. the rows of M^T go through plan_U (same direction
-  // flag: the inverse map uses U M = (M^T U^T)^T).  Intermediates stay in float32 so that a
+  // Column side, radices up to 8: plan_U's stages run along the row index of the matrix in
+  // place of a transposed copy (the same direction flag as the row side: U^T M uses the
+  // forward stage order, U M the transposed one).  Intermediates stay in float32 so that a
   // bf16 matrix is rounded once, at the final store.
+  const std::vector<ColPassHost> &cps = pu->colpass[dir];
+  if (!cps.empty()) {
+    float *A = (float *)ws;   // [d_out, d_in] float32
+    const void *src = W;
+    int64_t src_ld = ldw;
+    harp_dtype_t src_dt = dt;
+    if (pv) {
+      st = apply_dir(pv, dir, W, ldw, dt, A, d_in, HARP_F32, d_out, stream);
+      if (st != HARP_OK) return st;
+      src = A;
+      src_ld = d_in;
+      src_dt = HARP_F32;
+    }
+    for (size_t p = 0; p < cps.size(); ++p) {
+      const bool last = (p + 1 == cps.size());
+      void *dst = last ? Wout : (void *)A;
+      const int64_t dst_ld = last ? ldo : d_in;
+      const harp_dtype_t dst_dt = last ? dt : HARP_F32;
+      st = launch_col_pass(pu, cps[p].dev, cps[p].pass, src, src_ld, src_dt, dst, dst_ld, dst_dt,
+                           d_out, d_in, s);
+      if (st != HARP_OK) return st;
+      src = dst;
+      src_ld = dst_ld;
+      src_dt = dst_dt;
+    }
+    return HARP_OK;
+  }
+  // Otherwise: (U^T M)^T = M^T U, i.e. the rows of M^T go through plan_U as a row processor.
   const size_t mat = (size_t)d_out * d_in * 4;
   float *A = (float *)ws;                                   // [d_out, d_in] (only with plan_V)
   float *B = pv ? (float *)((char *)ws + mat) : (float *)ws;  // [d_in, d_out]
@@ -727,6 +756,63 @@ harp_status_t harp_plan_create(harp_plan_t **out, int64_t d, int32_t m, const in
       }
     if (st == HARP_OK && !plan->prog[HARP_ALGO_GENERIC][0].ok && !plan->prog[HARP_ALGO_SPLIT][0].ok)
       st = HARP_ERR_UNSUPPORTED;
+    // Column-mode image (the plan as the U side of a weight rotation): per direction the dense
+    // effective blocks [d / b][b][b] of every stage in execution order, and the passes over them.
+    bool col_ok = true;
+    for (int t = 0; t < m; ++t) col_ok = col_ok && radices[t] <= 8;
+    for (int dir = 0; dir < 2 && st == HARP_OK && col_ok; ++dir) {
+      std::vector<StageEff> eff;
+      build_effective(plan, blk, signs, HARP_ALGO_GENERIC, (Direction)dir, false, eff);
+      size_t total = 0;
+      for (const StageEff &se : eff) total += se.dense.size();
+      std::vector<float> image(total);
+      float *dimg = nullptr;
+      if (hipMalloc((void **)&dimg, total * 4) != hipSuccess) {
+        st = HARP_ERR_OOM;
+        break;
+      }
+      plan->dev_allocs.push_back(dimg);
+      size_t off = 0;
+      for (const StageEff &se : eff) {
+        std::copy(se.dense.begin(), se.dense.end(), image.begin() + off);
+        plan->col[dir].push_back(ColStage{se.b, (int32_t)se.s, dimg + off});
+        off += se.dense.size();
+      }
+      if (hipMemcpy(dimg, image.data(), total * 4, hipMemcpyHostToDevice) != hipSuccess) {
+        st = HARP_ERR_DEVICE;
+        break;
+      }
+      if (!build_col_passes(plan, (Direction)dir, plan->colpass[dir])) {
+        plan->colpass[dir].clear();
+        continue;
+      }
+      ColPass *dp = nullptr;
+      const size_t np = plan->colpass[dir].size();
+      if (hipMalloc((void **)&dp, np * sizeof(ColPass)) != hipSuccess) {
+        st = HARP_ERR_OOM;
+        break;
+      }
+      plan->dev_allocs.push_back(dp);
+      for (size_t i = 0; i < np && st == HARP_OK; ++i) {
+        ColPassHost &ph = plan->colpass[dir][i];
+        uint32_t *dtab = nullptr;
+        if (hipMalloc((void **)&dtab, ph.ptab.size() * 4) != hipSuccess) {
+          st = HARP_ERR_OOM;
+          break;
+        }
+        plan->dev_allocs.push_back(dtab);
+        if (hipMemcpy(dtab, ph.ptab.data(), ph.ptab.size() * 4, hipMemcpyHostToDevice) !=
+            hipSuccess) {
+          st = HARP_ERR_DEVICE;
+          break;
+        }
+        ph.pass.ptab = dtab;
+        if (hipMemcpy(dp + i, &plan->colpass[dir][i].pass, sizeof(ColPass),
+                      hipMemcpyHostToDevice) != hipSuccess)
+          st = HARP_ERR_DEVICE;
+        plan->colpass[dir][i].dev = dp + i;
+      }
+    }
   } catch (const std::bad_alloc &) {
     st = HARP_ERR_OOM;
   }

@@ -1,0 +1,485 @@
+// Column-mode passes: the stages of a processor applied along the ROW index of a row-major
+// matrix, M <- U^T M (or U M), without transposing it (two-sided weight rotation W~ = U^T W V,
+// Section 3.1; stage arithmetic of Algorithm 1 with the matrix row as the coordinate).
+//
+// Stage t couples rows i = alpha b s + r s + beta, r < b, of EVERY column with the same block
+// K_t[alpha s + beta], so along a row the work is perfectly coalesced and a block's b*b values
+// are uniform over a wave: the blocks a tile needs (at most 9 KB) travel with it, requested
+// together with its rows and read from LDS as broadcasts.  A pass is a run of consecutive
+// stages whose radices multiply to P <= 128; a workgroup owns a tile of P rows (row0 + j S,
+// j < P, S = the run's lowest stride) x 128 columns in LDS as float32 (two columns per lane),
+// executes the run's stages on it (one barrier per step; up to three consecutive radix-2
+// stages share one LDS round trip, eight rows in registers) and writes it back.  Tiles are
+// disjoint, so a pass may run in place.  2^13 rows take two passes (7 + 6 stages): the matrix
+// moves through device memory twice instead of the five times of transpose / row kernels /
+// transpose.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string.h>
+
+#include <algorithm>
+
+#include "harp_internal.h"
+
+namespace harp {
+namespace {
+
+constexpr int kColCols = 128;      // columns per tile
+constexpr int kColThreads = 256;   // 4 waves
+constexpr int kColWaves = kColThreads / 64;
+constexpr int kColMaxP = 128;      // rows per tile (LDS: P * 128 * 4 bytes = 64 KB)
+constexpr int kColParPerThread = 9;
+constexpr int kColMaxPar = kColParPerThread * kColThreads;   // block values per tile (9 KB)
+
+__device__ __forceinline__ float bf16_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+__device__ __forceinline__ uint32_t f32_to_bf16(float f) {   // round to nearest even
+  // branch-free: a branch between the stores would hide their number from the compiler's
+  // count of outstanding memory operations
+  const uint32_t u = __float_as_uint(f);
+  const uint32_t rounded = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+  const uint32_t quiet = (u >> 16) | 0x40u;
+  return ((u & 0x7fffffffu) > 0x7f800000u) ? quiet : rounded;
+}
+
+// Two adjacent elements as loaded (no arithmetic on them until they are needed, so that the
+// loads of the next tile stay in flight during the work on the current one).
+template <typename T> struct ColRaw;
+template <> struct ColRaw<float> { float2 v; };
+template <> struct ColRaw<uint16_t> { uint32_t lo, hi; };   // VEC: both in lo
+
+template <typename T, bool VEC>
+__device__ __forceinline__ void col_load(ColRaw<T> &r, const T *p, bool v0, bool v1);
+template <>
+__device__ __forceinline__ void col_load<float, true>(ColRaw<float> &r, const float *p, bool v0, bool) {
+  r.v = v0 ? *reinterpret_cast<const float2 *>(p) : make_float2(0.f, 0.f);
+}
+template <>
+__device__ __forceinline__ void col_load<float, false>(ColRaw<float> &r, const float *p, bool v0, bool v1) {
+  r.v = make_float2(v0 ? p[0] : 0.f, v1 ? p[1] : 0.f);
+}
+template <>
+__device__ __forceinline__ void col_load<uint16_t, true>(ColRaw<uint16_t> &r, const uint16_t *p, bool v0, bool) {
+  r.lo = v0 ? *reinterpret_cast<const uint32_t *>(p) : 0u;
+  r.hi = 0u;
+}
+template <>
+__device__ __forceinline__ void col_load<uint16_t, false>(ColRaw<uint16_t> &r, const uint16_t *p, bool v0, bool v1) {
+  r.lo = v0 ? (uint32_t)p[0] : 0u;
+  r.hi = v1 ? (uint32_t)p[1] : 0u;
+}
+template <bool VEC>
+__device__ __forceinline__ float2 col_widen(const ColRaw<float> &r) { return r.v; }
+template <bool VEC>
+__device__ __forceinline__ float2 col_widen(const ColRaw<uint16_t> &r) {
+  if (VEC) return make_float2(__uint_as_float(r.lo << 16), __uint_as_float(r.lo & 0xffff0000u));
+  return make_float2(__uint_as_float(r.lo << 16), __uint_as_float(r.hi << 16));
+}
+
+template <typename T, bool VEC>
+__device__ __forceinline__ void col_store(T *p, float2 v, bool v0, bool v1);
+template <>
+__device__ __forceinline__ void col_store<float, true>(float *p, float2 v, bool v0, bool) {
+  if (v0) *reinterpret_cast<float2 *>(p) = v;
+}
+template <>
+__device__ __forceinline__ void col_store<float, false>(float *p, float2 v, bool v0, bool v1) {
+  if (v0) p[0] = v.x;
+  if (v1) p[1] = v.y;
+}
+template <>
+__device__ __forceinline__ void col_store<uint16_t, true>(uint16_t *p, float2 v, bool v0, bool) {
+  if (v0) *reinterpret_cast<uint32_t *>(p) = f32_to_bf16(v.x) | (f32_to_bf16(v.y) << 16);
+}
+template <>
+__device__ __forceinline__ void col_store<uint16_t, false>(uint16_t *p, float2 v, bool v0, bool v1) {
+  if (v0) p[0] = (uint16_t)f32_to_bf16(v.x);
+  if (v1) p[1] = (uint16_t)f32_to_bf16(v.y);
+}
+
+// One stage of compile-time radix B on the tile.  Wave w takes blocks w, w + 4, ...; block
+// (a, bp), a < P / (B sp), bp < sp, couples tile rows a B sp + r sp + bp; its values sit at
+// prm[(a sp + bp) * BBP ..] (BBP = B * B rounded up to a multiple of 4).
+template <int B>
+__device__ __forceinline__ void col_stage(float2 *tile, const float *prm, const ColOp &op, int P,
+                                          int wave, int lane) {
+  constexpr int BBP = (B * B + 3) & ~3;
+  const int sp = op.sp;
+  const int nblk = P / B;
+  const float *region = prm + op.poff[0];
+  int a = 0, bp = wave;
+  while (bp >= sp) { bp -= sp; ++a; }
+  for (int blk = wave; blk < nblk; blk += kColWaves) {
+    const int j0 = a * B * sp + bp;
+    const float *kb = region + (a * sp + bp) * BBP;
+    float K[BBP];
+#pragma unroll
+    for (int q = 0; q < BBP / 4; ++q) {
+      const float4 f = *reinterpret_cast<const float4 *>(kb + 4 * q);
+      K[4 * q] = f.x; K[4 * q + 1] = f.y; K[4 * q + 2] = f.z; K[4 * q + 3] = f.w;
+    }
+    float2 x[B], y[B];
+#pragma unroll
+    for (int r = 0; r < B; ++r) x[r] = tile[(j0 + r * sp) * 64 + lane];
+#pragma unroll
+    for (int r2 = 0; r2 < B; ++r2) {
+      float ax = 0.f, ay = 0.f;
+#pragma unroll
+      for (int r = 0; r < B; ++r) {
+        ax = fmaf(x[r].x, K[r * B + r2], ax);
+        ay = fmaf(x[r].y, K[r * B + r2], ay);
+      }
+      y[r2] = make_float2(ax, ay);
+    }
+#pragma unroll
+    for (int r = 0; r < B; ++r) tile[(j0 + r * sp) * 64 + lane] = y[r];
+    bp += kColWaves;
+    while (bp >= sp) { bp -= sp; ++a; }
+  }
+}
+
+// K consecutive radix-2 stages on items of 2^K rows (tile rows a 2^K sp + e sp + bp, e < 2^K).
+// Sub-stage i pairs e0 (bit dp clear) with e0 + 2^dp; with e0 = eh 2^(dp+1) + el its block is
+// number (a 2^(K-dp-1) + eh) * (sp 2^dp) + el sp + bp of the stage's P / 2 blocks in the tile.
+// ASC: the sub-stages act on digits 0, 1, .., K-1 in this order, else K-1, .., 0.
+template <int K, bool ASC>
+__device__ __forceinline__ void col_run2(float2 *tile, const float *prm, const ColOp &op, int P,
+                                         int wave, int lane) {
+  constexpr int E = 1 << K;
+  const int sp = op.sp;
+  const int nitem = P / E;
+  int a = 0, bp = wave;
+  while (bp >= sp) { bp -= sp; ++a; }
+  for (int it = wave; it < nitem; it += kColWaves) {
+    const int j0 = a * E * sp + bp;
+    float4 kq[K][E / 2];
+#pragma unroll
+    for (int i = 0; i < K; ++i) {
+      const int dp = ASC ? i : K - 1 - i;
+      const float *region = prm + op.poff[i];
+#pragma unroll
+      for (int p = 0; p < E / 2; ++p) {
+        const int eh = p >> dp, el = p & ((1 << dp) - 1);
+        const int q = ((a << (K - dp - 1)) + eh) * (sp << dp) + el * sp + bp;
+        kq[i][p] = *reinterpret_cast<const float4 *>(region + 4 * q);
+      }
+    }
+    float2 x[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) x[e] = tile[(j0 + e * sp) * 64 + lane];
+#pragma unroll
+    for (int i = 0; i < K; ++i) {
+      const int dp = ASC ? i : K - 1 - i;
+#pragma unroll
+      for (int p = 0; p < E / 2; ++p) {
+        const int eh = p >> dp, el = p & ((1 << dp) - 1);
+        const int e0 = (eh << (dp + 1)) | el, e1 = e0 | (1 << dp);
+        const float4 k = kq[i][p];   // k00 k01 k10 k11
+        const float2 u = x[e0], v = x[e1];
+        x[e0] = make_float2(fmaf(v.x, k.z, u.x * k.x), fmaf(v.y, k.z, u.y * k.x));
+        x[e1] = make_float2(fmaf(v.x, k.w, u.x * k.y), fmaf(v.y, k.w, u.y * k.y));
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < E; ++e) tile[(j0 + e * sp) * 64 + lane] = x[e];
+    bp += kColWaves;
+    while (bp >= sp) { bp -= sp; ++a; }
+  }
+}
+
+// A workgroup walks over `tpw` consecutive tiles; the rows of the next tile are requested into
+// registers (up to 32 rows per wave) before the work on the current one starts.
+// NRW > 0 (fast variant): P == 4 NRW exactly, every column tile is full and pairs of columns
+// are aligned, so every wave owns NRW rows and no access is conditional -- the compiler can
+// then count the outstanding loads and stores and waits for the rows of the next tile without
+// also waiting for the stores of the previous one (vector memory operations retire in
+// order).  NRW == 0: any P <= 128 and ragged column tiles, guarded.
+template <typename TI, typename TO, bool VEC, int NRW>
+__global__ __launch_bounds__(kColThreads) void harp_col_kernel(
+    const ColPass *__restrict__ passp, const TI *src, int64_t lds_, TO *dst, int64_t ldd,
+    int64_t ncols, unsigned ctiles, unsigned ntiles, unsigned tpw) {
+  extern __shared__ float2 tile[];   // [P][64] float2, then npar floats of block values
+  const ColPass &cp = *passp;
+  const int lane = (int)threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+  const int P = cp.P, S = cp.S;
+  constexpr int NR = NRW > 0 ? NRW : kColMaxP / kColWaves;   // rows per wave
+  constexpr bool GUARD = (NRW == 0);
+
+  struct TilePos {
+    int hi, lo;
+    int64_t row0, col;
+    bool v0, v1;
+  };
+  auto locate = [&](unsigned t) -> TilePos {
+    TilePos tp;
+    const unsigned ct = t % ctiles, rt = t / ctiles;   // rt = hi * S + lo
+    tp.hi = (int)(rt / (unsigned)S);
+    tp.lo = (int)(rt % (unsigned)S);
+    tp.row0 = (int64_t)tp.hi * P * S + tp.lo;
+    tp.col = (int64_t)ct * kColCols + 2 * lane;
+    tp.v0 = !GUARD || tp.col < ncols;
+    tp.v1 = !GUARD || tp.col + 1 < ncols;
+    return tp;
+  };
+  // Block values of a tile: value e of the pass's list is image[fix[e] + hi * fa[e] + lo * fb[e]]
+  // (table built with the plan); thread tid owns e = tid + 256 k and keeps its table entries
+  // in registers for the whole launch.
+  float *prm = reinterpret_cast<float *>(tile + P * 64);
+  // explicitly global: a generic pointer loaded from memory would make these FLAT loads,
+  // whose completion order against other memory operations is unknown to the compiler
+  typedef const __attribute__((address_space(1))) float *gfloat_t;
+  gfloat_t image = (gfloat_t)cp.image;
+  const int npar = cp.npar;
+  typedef const __attribute__((address_space(1))) uint32_t *gtab_t;
+  gtab_t ptab = (gtab_t)cp.ptab;
+  unsigned dfix[kColParPerThread], dfa[kColParPerThread], dfb[kColParPerThread];
+#pragma unroll
+  for (int k = 0; k < kColParPerThread; ++k) {
+    const int e = (int)threadIdx.x + kColThreads * k;
+    const bool ok = e < npar;
+    // entries past the list and padding entries (fa == 0xffffffff) read image[0]: harmless,
+    // and it keeps every load unconditional
+    const unsigned fa = ok ? ptab[npar + e] : 0xffffffffu;
+    const bool real = fa != 0xffffffffu;
+    dfix[k] = real ? ptab[e] : 0u;
+    dfa[k] = real ? fa : 0u;
+    dfb[k] = real ? ptab[2 * npar + e] : 0u;
+  }
+  float ppre[kColParPerThread];
+
+  ColRaw<TI> pre[NR];
+  // per-lane running pointers keep the address arithmetic out of the scalar registers
+  auto request = [&](const TilePos &tp) {
+#pragma unroll
+    for (int k = 0; k < kColParPerThread; ++k)
+      ppre[k] = image[dfix[k] + (unsigned)tp.hi * dfa[k] + (unsigned)tp.lo * dfb[k]];
+    const TI *rp = src + (tp.row0 + (int64_t)wave * S) * lds_ + tp.col;
+    const int64_t step = (int64_t)kColWaves * S * lds_;
+#pragma unroll
+    for (int u = 0; u < NR; ++u) {
+      if (!GUARD || wave + kColWaves * u < P) col_load<TI, VEC>(pre[u], rp, tp.v0, tp.v1);
+      rp += step;
+    }
+  };
+
+  const unsigned t0 = blockIdx.x * tpw;
+  const unsigned t1 = (t0 + tpw < ntiles) ? t0 + tpw : ntiles;
+  if (t0 >= t1) return;
+  // registers -> LDS: rows and block values of the tile whose request is outstanding
+  float2 *tp0 = tile + wave * 64 + lane;
+  auto to_lds = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int u = 0; u < NR; ++u)
+      if (!GUARD || wave + kColWaves * u < P) tp0[u * (kColWaves * 64)] = col_widen<VEC>(pre[u]);
+#pragma unroll
+    for (int k = 0; k < kColParPerThread; ++k) prm[(int)threadIdx.x + kColThreads * k] = ppre[k];
+  };
+  // the stages on the tile in LDS, then LDS -> device memory
+  auto work = [&](unsigned t) __attribute__((always_inline)) {
+    const TilePos cur = locate(t);
+    for (int oi = 0; oi < cp.nops; ++oi) {
+      const ColOp &op = cp.op[oi];
+      const bool asc = op.dp[0] == 0;
+      if (op.k == 3) {
+        if (asc) col_run2<3, true>(tile, prm, op, P, wave, lane);
+        else col_run2<3, false>(tile, prm, op, P, wave, lane);
+      } else if (op.k == 2) {
+        if (asc) col_run2<2, true>(tile, prm, op, P, wave, lane);
+        else col_run2<2, false>(tile, prm, op, P, wave, lane);
+      } else {
+        switch (op.b) {
+          case 2: col_stage<2>(tile, prm, op, P, wave, lane); break;
+          case 3: col_stage<3>(tile, prm, op, P, wave, lane); break;
+          case 4: col_stage<4>(tile, prm, op, P, wave, lane); break;
+          case 5: col_stage<5>(tile, prm, op, P, wave, lane); break;
+          case 6: col_stage<6>(tile, prm, op, P, wave, lane); break;
+          case 7: col_stage<7>(tile, prm, op, P, wave, lane); break;
+          default: col_stage<8>(tile, prm, op, P, wave, lane); break;
+        }
+      }
+      __syncthreads();
+    }
+    TO *wp = dst + (cur.row0 + (int64_t)wave * S) * ldd + cur.col;
+    const int64_t wstep = (int64_t)kColWaves * S * ldd;
+#pragma unroll
+    for (int u = 0; u < NR; ++u) {
+      if (!GUARD || wave + kColWaves * u < P)
+        col_store<TO, VEC>(wp, tp0[u * (kColWaves * 64)], cur.v0, cur.v1);
+      wp += wstep;
+    }
+  };
+  // Every wait for requested rows inside the loop follows the same sequence (request, stages,
+  // stores), so it is a wait for "all but the stores".
+  request(locate(t0));
+  to_lds();
+  for (unsigned t = t0; t + 1 < t1; ++t) {
+    __syncthreads();
+    request(locate(t + 1));
+    work(t);
+    __syncthreads();   // every wave has read its rows of the tile back
+    to_lds();
+  }
+  __syncthreads();
+  work(t1 - 1);
+}
+
+template <typename TI, typename TO>
+harp_status_t launch_col_tiles(const harp_plan *plan, const ColPass *dpass, const ColPass &hp,
+                               const TI *src, int64_t lds_, TO *dst, int64_t ldd, int64_t nrows,
+                               int64_t ncols, bool vec, bool fast, hipStream_t stream) {
+  const int64_t ctiles = (ncols + kColCols - 1) / kColCols;
+  const int64_t tiles = (nrows / hp.P) * ctiles;
+  if (tiles <= 0) return HARP_OK;
+  if (tiles > 0x7fffffff) return HARP_ERR_UNSUPPORTED;
+  const size_t shmem = (size_t)hp.P * 64 * sizeof(float2) + (size_t)kColMaxPar * sizeof(float);
+  if (shmem > (size_t)plan->lds_bytes) return HARP_ERR_UNSUPPORTED;
+  // about eight workgroups per resident slot (two 73 KB tiles fit a compute unit), at most 16
+  // tiles each
+  const int64_t slots = (int64_t)(plan->num_cu > 0 ? plan->num_cu : 256) * 2;
+  int64_t tpw = tiles / (slots * 8);
+  tpw = std::max<int64_t>(1, std::min<int64_t>(tpw, 16));
+  const int64_t grid = (tiles + tpw - 1) / tpw;
+  typedef void (*kern_t)(const ColPass *, const TI *, int64_t, TO *, int64_t, int64_t, unsigned,
+                         unsigned, unsigned);
+  static const kern_t table[5] = {harp_col_kernel<TI, TO, false, 0>, harp_col_kernel<TI, TO, true, 0>,
+                                  harp_col_kernel<TI, TO, true, 32>, harp_col_kernel<TI, TO, true, 16>,
+                                  harp_col_kernel<TI, TO, true, 8>};
+  const int which = !fast ? (vec ? 1 : 0) : (hp.P == 128 ? 2 : (hp.P == 64 ? 3 : 4));
+  const kern_t kern = table[which];
+  static thread_local int attr_done_dev[5] = {-1, -1, -1, -1, -1};   // per instantiation
+  if (attr_done_dev[which] != plan->device) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                            hipFuncAttributeMaxDynamicSharedMemorySize,
+                            plan->lds_bytes) != hipSuccess) {
+      (void)hipGetLastError();
+      return HARP_ERR_DEVICE;
+    }
+    attr_done_dev[which] = plan->device;
+  }
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kColThreads), shmem, stream, dpass, src, lds_,
+                     dst, ldd, ncols, (unsigned)ctiles, (unsigned)tiles, (unsigned)tpw);
+  return hipGetLastError() == hipSuccess ? HARP_OK : HARP_ERR_DEVICE;
+}
+
+// The full column tiles go to the fast variant when the shape allows it, the ragged last
+// column tile (and every other shape) to the guarded one.
+template <typename TI, typename TO>
+harp_status_t launch_col_typed(const harp_plan *plan, const ColPass *dpass, const ColPass &hp,
+                               const void *src, int64_t lds_, void *dst, int64_t ldd,
+                               int64_t nrows, int64_t ncols, hipStream_t stream) {
+  const size_t ei = sizeof(TI), eo = sizeof(TO);
+  const bool vec = (ncols % 2 == 0) && (lds_ % 2 == 0) && (ldd % 2 == 0) &&
+                   ((uintptr_t)src % (2 * ei) == 0) && ((uintptr_t)dst % (2 * eo) == 0);
+  const bool shape_ok = vec && (hp.P == 128 || hp.P == 64 || hp.P == 32);
+  const int64_t full = shape_ok ? (ncols / kColCols) * kColCols : 0;
+  harp_status_t st = HARP_OK;
+  if (full > 0)
+    st = launch_col_tiles<TI, TO>(plan, dpass, hp, (const TI *)src, lds_, (TO *)dst, ldd, nrows,
+                                  full, true, true, stream);
+  if (st == HARP_OK && full < ncols)
+    st = launch_col_tiles<TI, TO>(plan, dpass, hp, (const TI *)src + full, lds_, (TO *)dst + full,
+                                  ldd, nrows, ncols - full, vec, false, stream);
+  return st;
+}
+
+}  // namespace
+
+// Host side: group the stages of plan->col[dir] (execution order) into passes and steps, and
+// list for every pass the block values a tile needs.  Returns false when the plan has no
+// column-mode image (a radix above 8).
+bool build_col_passes(const harp_plan *plan, Direction dir, std::vector<ColPassHost> &out) {
+  const std::vector<ColStage> &st = plan->col[dir];
+  out.clear();
+  if (st.empty()) return false;
+  const int m = (int)st.size();
+  const float *image = st[0].blocks;   // one allocation, stages back to back
+  auto padded = [](int b) { return (b * b + 3) & ~3; };
+  int i = 0;
+  while (i < m) {
+    // the pass: stages i .. e-1 with prod(b) <= kColMaxP whose block values fit the budget
+    int e = i, P = 1;
+    while (e < m && P * st[e].b <= kColMaxP) {
+      const int Pn = P * st[e].b;
+      int par = 0;
+      for (int t = i; t <= e; ++t) par += (Pn / st[t].b) * padded(st[t].b);
+      if (par > kColMaxPar) break;
+      P = Pn;
+      ++e;
+    }
+    if (e == i) return false;
+    int S = st[i].s;
+    for (int t = i; t < e; ++t) S = std::min(S, st[t].s);
+    out.emplace_back();
+    ColPassHost &ph = out.back();
+    ph.dev = nullptr;
+    ColPass &cp = ph.pass;
+    memset(&cp, 0, sizeof(cp));
+    cp.P = P;
+    cp.S = S;
+    cp.image = image;
+    std::vector<uint32_t> fix, fa, fb;
+    int t = i;
+    while (t < e) {
+      if (cp.nops >= kColMaxOps) return false;
+      ColOp &op = cp.op[cp.nops++];
+      op.b = st[t].b;
+      int k = 1;
+      if (st[t].b == 2) {
+        // up to three radix-2 stages on adjacent digits, ascending or descending
+        while (k < 3 && t + k < e && st[t + k].b == 2 &&
+               (st[t + k].s == st[t + k - 1].s * 2 || st[t + k].s * 2 == st[t + k - 1].s) &&
+               (k == 1 || ((st[t + k].s > st[t + k - 1].s) == (st[t + 1].s > st[t].s))))
+          ++k;
+      }
+      op.k = k;
+      int smin = st[t].s;
+      for (int q = 0; q < k; ++q) smin = std::min(smin, st[t + q].s);
+      op.sp = smin / S;
+      for (int q = 0; q < k; ++q) {
+        const ColStage &cs = st[t + q];
+        int dp = 0;
+        while ((smin << dp) < cs.s) ++dp;
+        op.dp[q] = dp;
+        op.poff[q] = (int32_t)fix.size();
+        // blocks of this stage inside a tile: number j = a' s' + beta' (s' = s / S) is block
+        // c = hi (P / b) S + lo + a' s + beta' S of the stage
+        const int b = cs.b, bb = b * b, bbp = padded(b), sp = cs.s / S;
+        const uint32_t off = (uint32_t)(cs.blocks - image);
+        for (int j = 0; j < P / b; ++j) {
+          const int ap = j / sp, bt = j % sp;
+          for (int v = 0; v < bbp; ++v) {
+            const bool real = v < bb;
+            fix.push_back(real ? off + (uint32_t)((int64_t)ap * cs.s + (int64_t)bt * S) * bb + v : 0u);
+            fa.push_back(real ? (uint32_t)P * (uint32_t)S * (uint32_t)b : 0xffffffffu);
+            fb.push_back(real ? (uint32_t)bb : 0u);
+          }
+        }
+      }
+      t += k;
+    }
+    cp.npar = (int32_t)fix.size();
+    if (cp.npar > kColMaxPar) return false;
+    ph.ptab = fix;
+    ph.ptab.insert(ph.ptab.end(), fa.begin(), fa.end());
+    ph.ptab.insert(ph.ptab.end(), fb.begin(), fb.end());
+    i = e;
+  }
+  return true;
+}
+
+harp_status_t launch_col_pass(const harp_plan *plan, const ColPass *dpass, const ColPass &hp,
+                              const void *src,
+                              int64_t lds_, harp_dtype_t dt_src, void *dst, int64_t ldd,
+                              harp_dtype_t dt_dst, int64_t nrows, int64_t ncols,
+                              hipStream_t stream) {
+  if (nrows % hp.P != 0) return HARP_ERR_INVALID_ARG;
+  if (dt_src == HARP_F32 && dt_dst == HARP_F32)
+    return launch_col_typed<float, float>(plan, dpass, hp, src, lds_, dst, ldd, nrows, ncols, stream);
+  if (dt_src == HARP_BF16 && dt_dst == HARP_F32)
+    return launch_col_typed<uint16_t, float>(plan, dpass, hp, src, lds_, dst, ldd, nrows, ncols, stream);
+  if (dt_src == HARP_F32 && dt_dst == HARP_BF16)
+    return launch_col_typed<float, uint16_t>(plan, dpass, hp, src, lds_, dst, ldd, nrows, ncols, stream);
+  return launch_col_typed<uint16_t, uint16_t>(plan, dpass, hp, src, lds_, dst, ldd, nrows, ncols, stream);
+}
+
+}  // namespace harp

@@ -69,6 +69,44 @@ struct HostProgram {
 
 enum Direction { DIR_FWD = 0, DIR_TRN = 1 };
 
+// ---- column-mode passes (rotate_weight's plan_U side, harp_col.hip) ----
+constexpr int kColMaxOps = 8;
+// One step of a pass: a single stage of radix b (k == 1), or k <= 3 consecutive radix-2 stages
+// executed on 2^k rows in registers.  sp = in-tile stride (in tile rows) of the step's lowest
+// digit; sub-stage e (execution order) acts on digit dp[e] of the 2^k rows; poff[e] = where its
+// block values start in the tile's value list (floats).
+struct ColOp {
+  int32_t b, k, sp, pad;
+  int32_t dp[3];
+  int32_t poff[3];
+};
+
+struct ColPass {
+  int32_t nops;
+  int32_t P;      // rows per tile
+  int32_t S;      // row stride between consecutive tile rows
+  int32_t npar;   // block values per tile (padded blocks)
+  const float *image;     // device: every stage's dense blocks
+  // device, [3][npar]: value e of tile (hi, lo) is image[fix[e] + hi * fa[e] + lo * fb[e]];
+  // fa[e] == 0xffffffff marks padding
+  const uint32_t *ptab;
+  ColOp op[kColMaxOps];
+};
+struct ColPassHost {
+  ColPass pass;
+  const ColPass *dev;   // device copy
+  std::vector<uint32_t> ptab;
+};
+// stage of the column-mode image, execution order: dense blocks [d / b][b][b] with the signs
+// folded in (device memory)
+struct ColStage {
+  int32_t b;
+  int32_t s;
+  const float *blocks;
+};
+
+
+
 struct LaunchCfg {
   int rows_per_tile;
   int threads;
@@ -98,6 +136,9 @@ struct harp_plan {
   };
   mutable std::mutex scratch_mu;
   mutable std::vector<Scratch> scratch;
+  // column-mode image and passes per direction; empty when some radix exceeds 8
+  std::vector<harp::ColStage> col[2];
+  std::vector<harp::ColPassHost> colpass[2];
 };
 
 namespace harp {
@@ -148,6 +189,14 @@ harp_status_t launch_radix_kernel(const harp_plan *plan, const HostProgram &hp, 
                                   int chunk, const void *X, int64_t ldx, harp_dtype_t dt_in,
                                   void *Y, int64_t ldy, harp_dtype_t dt_out, int64_t n,
                                   hipStream_t stream);
+// column-mode passes (harp_col.hip): group plan->col[dir] into passes; launch one pass on a
+// row-major [nrows, ncols] matrix (nrows == plan->d; may run in place)
+bool build_col_passes(const harp_plan *plan, Direction dir, std::vector<ColPassHost> &out);
+harp_status_t launch_col_pass(const harp_plan *plan, const ColPass *dpass, const ColPass &hp,
+                              const void *src,
+                              int64_t lds_, harp_dtype_t dt_src, void *dst, int64_t ldd,
+                              harp_dtype_t dt_dst, int64_t nrows, int64_t ncols,
+                              hipStream_t stream);
 int choose_pipe_rows(const harp_plan *plan, int64_t n, int64_t nchunk, int chunk);
 const HostProgram *select_program(const harp_plan *plan, Direction dir, int64_t n,
                                   const char **name);

@@ -594,7 +594,13 @@ def _plan_tuple(d, radices, blocks, signs):
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("do,ru,di,rv", [(24, [2, 3, 4], 40, [8, 5]), (64, [2] * 6, 48, [2, 2, 2, 2, 3]),
                                          (14, [2, 7], 30, [2, 3, 5]), (192, [4, 6, 8], 130, [2, 5, 13]),
-                                         (256, [2] * 8, 344, [2, 2, 2, 43])])
+                                         (256, [2] * 8, 344, [2, 2, 2, 43]),
+                                         # plan_U in column mode: two passes, odd column count
+                                         (512, [2] * 9, 65, [5, 13]), (1024, [2] * 10, 96, [2] * 5 + [3]),
+                                         (240, [5, 6, 8], 34, [2, 17]), (96, [3, 2, 2, 2, 4], 130, [130 // 13, 13]),
+                                         (384, [2, 2, 3, 2, 2, 2, 2, 2], 258, [2, 3, 43]),
+                                         # plan_U with a radix above 8: transposed-copy path
+                                         (44, [2, 2, 11], 24, [2, 3, 4])])
 def test_rotate_weight_small_dense(harp, dtype, do, ru, di, rv):
     import torch
     rng = np.random.default_rng(do + di)
@@ -625,6 +631,40 @@ def test_rotate_weight_small_dense(harp, dtype, do, ru, di, rv):
     harp.harp_rotate_weight(pu, pv, W2, W2)
     torch.cuda.synchronize()
     assert torch.equal(W2, out)
+    pu.destroy()
+    pv.destroy()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_rotate_weight_views_with_padding_and_odd_offsets(harp, dtype):
+    """Matrices that are views into wider buffers (leading dimension above d_in, first element
+    at an odd offset): the column-mode passes then take their element-by-element path."""
+    import torch
+    do, ru, di, rv = 256, [2] * 8, 70, [2, 5, 7]
+    rng = np.random.default_rng(77)
+    bu, bv = gi.make_blocks(do, ru, "orth", rng), gi.make_blocks(di, rv, "orth", rng)
+    su, sv = gi.make_signs(do, rng), gi.make_signs(di, rng)
+    W = rng.standard_normal((do, di)).astype(np.float32)
+    if dtype == "bf16":
+        W = gi.round_to_bf16(W)
+    pu, pv = harp.Plan(do, ru, bu, su), harp.Plan(di, rv, bv, sv)
+    ref = ho.rotate_weight(W, _plan_tuple(do, ru, bu, su), _plan_tuple(di, rv, bv, sv))
+    ref_u = ho.rotate_weight(W, _plan_tuple(do, ru, bu, su), None)
+    Wd = to_device(W, dtype)
+    for pad, off in [(3, 1), (2, 0), (9, 5)]:
+        say("rotate_weight view", dtype, pad, off)
+        big_in = torch.zeros(do, di + pad + off, dtype=Wd.dtype, device="cuda")
+        big_out = torch.full((do, di + pad + off), 7.0, dtype=Wd.dtype, device="cuda")
+        vin, vout = big_in[:, off:off + di], big_out[:, off:off + di]
+        vin.copy_(Wd)
+        harp.harp_rotate_weight(pu, pv, vin, vout)
+        torch.cuda.synchronize()
+        assert_parity(to_host64(vout.contiguous()), ref, dtype, "U^T W V (view)")
+        harp.harp_rotate_weight(pu, None, vin, vout)
+        torch.cuda.synchronize()
+        assert_parity(to_host64(vout.contiguous()), ref_u, dtype, "U^T W (view)")
+        # nothing outside the view is written
+        assert bool((big_out[:, :off] == 7.0).all()) and bool((big_out[:, off + di:] == 7.0).all())
     pu.destroy()
     pv.destroy()
 
