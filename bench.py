@@ -198,6 +198,30 @@ def main():
                 pe.destroy()
             except Exception as e:  # noqa: BLE001
                 print(f"[extra] {name}: {e}", file=sys.stderr, flush=True)
+        try:   # two-sided weight rotation at the 70B FFN shape (weights drawn on the device)
+            do, di = 8192, 28672
+            bu, su = gi.processor(do, [2] * 13, config=5, salt=1)
+            bv, sv = gi.processor(di, [2] * 12 + [7], config=5, salt=2)
+            pu, pv = harp.Plan(do, [2] * 13, bu, su), harp.Plan(di, [2] * 12 + [7], bv, sv)
+            Wm = (torch.randn(do, di, device="cuda") * 0.02).to(torch.bfloat16)
+            Wo = torch.empty_like(Wm)
+            ws = torch.empty(harp.harp_rotate_weight_workspace_size(pu, pv, do, di, harp.HARP_BF16),
+                             dtype=torch.uint8, device="cuda")
+            for _ in range(3):
+                harp.harp_rotate_weight(pu, pv, Wm, Wo, ws, stream)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(5):
+                harp.harp_rotate_weight(pu, pv, Wm, Wo, ws, stream)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / 5
+            gb = 4 * do * di * 2 / (us * 1e-6) / 1e9   # two sides, each reads and writes W once
+            print(f"[extra] rotate_weight 8192 x 28672 bf16: {us:.0f} us, {gb:.0f} GB/s "
+                  f"({gb / HBM_PEAK_GBS:.1%})", file=sys.stderr, flush=True)
+        except Exception as e:  # noqa: BLE001
+            print(f"[extra] rotate_weight: {e}", file=sys.stderr, flush=True)
     print(json.dumps(out), flush=True)
 
 

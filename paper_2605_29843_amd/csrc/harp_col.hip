@@ -333,10 +333,10 @@ harp_status_t launch_col_tiles(const harp_plan *plan, const ColPass *dpass, cons
   if (tiles > 0x7fffffff) return HARP_ERR_UNSUPPORTED;
   const size_t shmem = (size_t)hp.P * 64 * sizeof(float2) + (size_t)kColMaxPar * sizeof(float);
   if (shmem > (size_t)plan->lds_bytes) return HARP_ERR_UNSUPPORTED;
-  // about eight workgroups per resident slot (two 73 KB tiles fit a compute unit), at most 16
-  // tiles each
+  // about four workgroups per resident slot (two 73 KB tiles fit a compute unit), at most 16
+  // tiles each (measured flat between 7 and 14 tiles per workgroup; 1 or 56 are 5-9 % slower)
   const int64_t slots = (int64_t)(plan->num_cu > 0 ? plan->num_cu : 256) * 2;
-  int64_t tpw = tiles / (slots * 8);
+  int64_t tpw = tiles / (slots * 4);
   tpw = std::max<int64_t>(1, std::min<int64_t>(tpw, 16));
   const int64_t grid = (tiles + tpw - 1) / tpw;
   typedef void (*kern_t)(const ColPass *, const TI *, int64_t, TO *, int64_t, int64_t, unsigned,
