@@ -175,6 +175,35 @@ harp_status_t harp_plan_create_from_theta(harp_plan_t **out, int64_t d, int32_t 
                                           const int8_t *signs, uint32_t flags);
 
 /*
+ * Int8 storage of the rotation parameters (Sec. 3, "Parameter quantization for deployment";
+ * appendix "Int8 storage of HARP parameters").  Per block c of stage t the p_t = b_t (b_t-1)/2
+ * parameters a (the strict upper triangle of the Cayley matrix, or the one Givens angle for
+ * radix 2; layout of theta[t] as in harp_blocks_from_theta) get one scale
+ *     s_{t,c} = max |a| / 127        and codes        q = round(a / s_{t,c}).
+ * The arithmetic that decides a code is float32 with ties to even; a block whose parameters
+ * are all zero gets s = 0 and codes 0 (the appendix leaves 0/0 open).  Reconstruction is
+ * a ~ s q in float32.  Host only; every pointer is a host pointer and must not be NULL.
+ *   codes[t]   D_t * p_t int8 values in [-127, 127];   scales[t]   D_t floats (>= 0).
+ * harp_theta_dequantize_int8 returns HARP_ERR_INVALID_ARG for a code of -128 or a negative or
+ * non-finite scale, harp_theta_quantize_int8 for a non-finite parameter.
+ * harp_plan_create_from_theta_int8 = dequantize, then harp_plan_create_from_theta: the
+ * orthogonal blocks are rebuilt once, when the plan is created (the kernels keep a block's
+ * values on chip for a whole launch, so rebuilding them per launch would save no traffic).
+ */
+harp_status_t harp_theta_quantize_int8(int64_t d, int32_t m, const int32_t *radices,
+                                       const float *const *theta, int8_t *const *codes_out,
+                                       float *const *scales_out);
+harp_status_t harp_theta_dequantize_int8(int64_t d, int32_t m, const int32_t *radices,
+                                         const int8_t *const *codes, const float *const *scales,
+                                         float *const *theta_out);
+harp_status_t harp_plan_create_from_theta_int8(harp_plan_t **out, int64_t d, int32_t m,
+                                               const int32_t *radices, const int8_t *const *codes,
+                                               const float *const *scales,
+                                               const int32_t *mixer_kinds,
+                                               const float *const *mixers, const int8_t *signs,
+                                               uint32_t flags);
+
+/*
  * Kronecker fallback (Sec. 3, "Mixed-Radix dimensions and Kronecker fallback", the equation
  * T_d = (H~_K / sqrt(K)) (x) T_{n2}): expands a processor T_{n2} on n2 coordinates and a
  * Hadamard-like table H~_K (K x K row-major, entries +-1, H~ H~^T = K I) into the schedule and

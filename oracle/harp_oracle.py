@@ -39,6 +39,8 @@ loss invariance Eq. (3), the greedy schedule's printed examples (App. "Stage
 schedules", Alg. 2) and Table "radix ablation" stage counts, Eq. (13) parameter count;
 ``blocks_from_theta``: Theta = 0 gives diag(sigma) H_d / sqrt(d) (scipy's hadamard), the
 radix-2 block written out, the radix-3 Cayley block against the Rodrigues rotation.
+``quantize_theta_int8`` (App. "Int8 storage of HARP parameters"): a hand-computed block, the
+largest parameter of a block mapping to +-127, |a - s q| <= s / 2, sign symmetry.
 Unpinned against the paper (values not published): the QR base mixer's fixed
 Gaussian and any trained processor -- "parity unpinned" for those; they are inputs
 to this library, not computed by it.
@@ -53,7 +55,7 @@ __all__ = [
     "apply_staged", "apply_transpose_staged", "rotate_weight",
     "stage_matrix_explicit", "U_explicit", "greedy_schedule",
     "sylvester_hadamard", "param_count", "givens_block", "cayley_block",
-    "blocks_from_theta",
+    "blocks_from_theta", "quantize_theta_int8", "dequantize_theta_int8",
 ]
 
 
@@ -322,3 +324,43 @@ def blocks_from_theta(d, radices, thetas, mixers=None):
         out.append(K)
     return out
 
+
+
+def quantize_theta_int8(d, radices, thetas):
+    """Int8 storage of the stage parameters (App. "Int8 storage of HARP parameters").
+
+    For block c of stage t with parameters a (the strict upper triangle of A for b_t > 2, the
+    Givens angle for b_t = 2):  s = max|a| / 127,  q = round(a / s).  The paper fixes neither the
+    precision nor the tie rule; both are taken as float32 and round-half-to-even (what the
+    float32 tensor code the paper describes would do), and a block of zeros gets s = 0, q = 0.
+    Returns (codes, scales): int8 arrays [D_t, p_t] and float32 arrays [D_t].
+    """
+    check_schedule(d, radices)
+    codes, scales = [], []
+    for t, b in enumerate(radices):
+        D, npar = d // b, b * (b - 1) // 2
+        a = np.asarray(thetas[t], dtype=np.float32).reshape(D, npar)
+        q = np.zeros((D, npar), dtype=np.int8)
+        s = np.zeros(D, dtype=np.float32)
+        for c in range(D):
+            amax = np.float32(np.max(np.abs(a[c])))
+            s[c] = amax / np.float32(127.0)
+            if s[c] > 0:
+                for i in range(npar):
+                    r = np.rint(np.float32(a[c, i]) / s[c])      # float32 quotient, ties to even
+                    q[c, i] = np.int8(min(127.0, max(-127.0, float(r))))
+        codes.append(q)
+        scales.append(s)
+    return codes, scales
+
+
+def dequantize_theta_int8(d, radices, codes, scales):
+    """a ~ s * q in float32 (same appendix), arrays [D_t, p_t] per stage."""
+    check_schedule(d, radices)
+    out = []
+    for t, b in enumerate(radices):
+        D, npar = d // b, b * (b - 1) // 2
+        q = np.asarray(codes[t], dtype=np.int8).reshape(D, npar)
+        s = np.asarray(scales[t], dtype=np.float32).reshape(D)
+        out.append((s[:, None] * q.astype(np.float32)).astype(np.float32))
+    return out

@@ -7,6 +7,7 @@
 // caller supplies.  Theta = 0 gives B = G, i.e. the randomized Hadamard processor for
 // power-of-two schedules ("Exact initialization").  The blocks come out in the layout
 // harp_plan_create takes.
+#include <algorithm>
 #include <cmath>
 #include <cstdint>
 #include <new>
@@ -168,6 +169,98 @@ harp_status_t harp_plan_create_from_theta(harp_plan_t **out, int64_t d, int32_t 
     st = harp_blocks_from_theta(d, m, radices, theta, mixer_kinds, mixers, outp.data());
     if (st != HARP_OK) return st;
     return harp_plan_create(out, d, m, radices, inp.data(), signs, flags);
+  } catch (const std::bad_alloc &) {
+    return HARP_ERR_OOM;
+  }
+}
+
+// Int8 storage of the stage parameters (appendix "Int8 storage of HARP parameters"): per block
+// a scale s = max|a| / 127 over its b(b-1)/2 parameters (the one Givens angle for radix 2) and
+// codes q = round(a / s).  The decision is taken in float32 with ties to even; a block whose
+// parameters are all zero gets s = 0 and codes 0.
+harp_status_t harp_theta_quantize_int8(int64_t d, int32_t m, const int32_t *radices,
+                                       const float *const *theta, int8_t *const *codes_out,
+                                       float *const *scales_out) {
+  harp_status_t st = check_schedule(d, m, radices);
+  if (st != HARP_OK) return st;
+  if (!theta || !codes_out || !scales_out) return HARP_ERR_INVALID_ARG;
+  for (int t = 0; t < m; ++t)
+    if (!theta[t] || !codes_out[t] || !scales_out[t]) return HARP_ERR_INVALID_ARG;
+  for (int t = 0; t < m; ++t) {
+    const int b = radices[t];
+    const int64_t D = d / b;
+    const int npar = b * (b - 1) / 2;
+    for (int64_t c = 0; c < D; ++c) {
+      const float *a = theta[t] + (size_t)c * npar;
+      float amax = 0.0f;
+      for (int i = 0; i < npar; ++i) {
+        if (!std::isfinite(a[i])) return HARP_ERR_INVALID_ARG;
+        amax = std::max(amax, std::fabs(a[i]));
+      }
+      const float s = amax / 127.0f;
+      scales_out[t][c] = s;
+      for (int i = 0; i < npar; ++i) {
+        float q = 0.0f;
+        if (s > 0.0f) q = std::nearbyintf(a[i] / s);   // default rounding mode: ties to even
+        if (!(q >= -127.0f)) q = -127.0f;              // also catches a quotient that overflowed
+        if (!(q <= 127.0f)) q = 127.0f;
+        codes_out[t][(size_t)c * npar + i] = (int8_t)q;
+      }
+    }
+  }
+  return HARP_OK;
+}
+
+// a = s * q in float32, the run-time reconstruction of the same appendix.
+harp_status_t harp_theta_dequantize_int8(int64_t d, int32_t m, const int32_t *radices,
+                                         const int8_t *const *codes, const float *const *scales,
+                                         float *const *theta_out) {
+  harp_status_t st = check_schedule(d, m, radices);
+  if (st != HARP_OK) return st;
+  if (!codes || !scales || !theta_out) return HARP_ERR_INVALID_ARG;
+  for (int t = 0; t < m; ++t)
+    if (!codes[t] || !scales[t] || !theta_out[t]) return HARP_ERR_INVALID_ARG;
+  for (int t = 0; t < m; ++t) {
+    const int b = radices[t];
+    const int64_t D = d / b;
+    const int npar = b * (b - 1) / 2;
+    for (int64_t c = 0; c < D; ++c) {
+      const float s = scales[t][c];
+      if (!std::isfinite(s) || s < 0.0f) return HARP_ERR_INVALID_ARG;
+      for (int i = 0; i < npar; ++i) {
+        const int8_t q = codes[t][(size_t)c * npar + i];
+        if (q == -128) return HARP_ERR_INVALID_ARG;   // not a code the quantizer produces
+        theta_out[t][(size_t)c * npar + i] = s * (float)q;
+      }
+    }
+  }
+  return HARP_OK;
+}
+
+harp_status_t harp_plan_create_from_theta_int8(harp_plan_t **out, int64_t d, int32_t m,
+                                               const int32_t *radices, const int8_t *const *codes,
+                                               const float *const *scales,
+                                               const int32_t *mixer_kinds,
+                                               const float *const *mixers, const int8_t *signs,
+                                               uint32_t flags) {
+  if (!out) return HARP_ERR_INVALID_ARG;
+  if (flags & HARP_BLOCKS_ON_DEVICE) return HARP_ERR_INVALID_ARG;   // codes are read on the host
+  harp_status_t st = check_schedule(d, m, radices);
+  if (st != HARP_OK) return st;
+  if (d > (int64_t)1 << 24) return HARP_ERR_UNSUPPORTED;
+  try {
+    std::vector<std::vector<float>> store((size_t)m);
+    std::vector<float *> outp((size_t)m);
+    std::vector<const float *> inp((size_t)m);
+    for (int t = 0; t < m; ++t) {
+      store[t].resize((size_t)(d / radices[t]) * (radices[t] * (radices[t] - 1) / 2));
+      outp[t] = store[t].data();
+      inp[t] = store[t].data();
+    }
+    st = harp_theta_dequantize_int8(d, m, radices, codes, scales, outp.data());
+    if (st != HARP_OK) return st;
+    return harp_plan_create_from_theta(out, d, m, radices, inp.data(), mixer_kinds, mixers, signs,
+                                       flags);
   } catch (const std::bad_alloc &) {
     return HARP_ERR_OOM;
   }

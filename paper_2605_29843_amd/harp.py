@@ -45,6 +45,13 @@ _SIGS = {
                                      C.POINTER(_i32), C.POINTER(_vp)]),
     "harp_plan_create_from_theta": (_i32, [C.POINTER(_vp), _i64, _i32, C.POINTER(_i32), C.POINTER(_vp),
                                            C.POINTER(_i32), C.POINTER(_vp), _vp, _u32]),
+    "harp_theta_quantize_int8": (_i32, [_i64, _i32, C.POINTER(_i32), C.POINTER(_vp), C.POINTER(_vp),
+                                        C.POINTER(_vp)]),
+    "harp_theta_dequantize_int8": (_i32, [_i64, _i32, C.POINTER(_i32), C.POINTER(_vp), C.POINTER(_vp),
+                                          C.POINTER(_vp)]),
+    "harp_plan_create_from_theta_int8": (_i32, [C.POINTER(_vp), _i64, _i32, C.POINTER(_i32),
+                                                C.POINTER(_vp), C.POINTER(_vp), C.POINTER(_i32),
+                                                C.POINTER(_vp), _vp, _u32]),
     "harp_apply": (_i32, [_vp, _vp, _i64, _vp, _i64, _i64, _i32, _vp]),
     "harp_apply_transpose": (_i32, [_vp, _vp, _i64, _vp, _i64, _i64, _i32, _vp]),
     "harp_rotate_weight_workspace_size": (_i32, [_vp, _vp, _i64, _i64, _i32, C.POINTER(_sz)]),
@@ -161,6 +168,53 @@ def harp_blocks_from_theta(d: int, radices, thetas=None, mixers=None) -> list:
     return outs
 
 
+def _npar(d, b):
+    return (int(d) // b) * (b * (b - 1) // 2)
+
+
+def harp_theta_quantize_int8(d: int, radices, thetas):
+    """(codes, scales) per stage: int8 arrays [D_t, p_t] and float32 arrays [D_t]."""
+    radices = [int(b) for b in radices]
+    m = len(radices)
+    ins = [np.ascontiguousarray(thetas[t], dtype=np.float32) for t in range(m)]
+    for t, b in enumerate(radices):
+        if ins[t].size != _npar(d, b):
+            raise ValueError(f"theta[{t}] must hold D_t * b (b - 1) / 2 values")
+    codes = [np.empty((int(d) // b, b * (b - 1) // 2), dtype=np.int8) for b in radices]
+    scales = [np.empty(int(d) // b, dtype=np.float32) for b in radices]
+    rad = (_i32 * max(m, 1))(*radices)
+    ip = (_vp * max(m, 1))(*[a.ctypes.data for a in ins])
+    cp = (_vp * max(m, 1))(*[a.ctypes.data for a in codes])
+    sp = (_vp * max(m, 1))(*[a.ctypes.data for a in scales])
+    _check(lib.harp_theta_quantize_int8(int(d), m, rad, ip, cp, sp), "harp_theta_quantize_int8")
+    return codes, scales
+
+
+def _int8_args(d, radices, codes, scales, keep):
+    m = len(radices)
+    cs = [np.ascontiguousarray(codes[t], dtype=np.int8) for t in range(m)]
+    ss = [np.ascontiguousarray(scales[t], dtype=np.float32) for t in range(m)]
+    for t, b in enumerate(radices):
+        if cs[t].size != _npar(d, b) or ss[t].size != int(d) // b:
+            raise ValueError(f"codes[{t}] / scales[{t}] have the wrong size")
+    keep.extend(cs + ss)
+    return ((_vp * max(m, 1))(*[a.ctypes.data for a in cs]),
+            (_vp * max(m, 1))(*[a.ctypes.data for a in ss]))
+
+
+def harp_theta_dequantize_int8(d: int, radices, codes, scales) -> list:
+    """theta ~ scale * code per stage, float32 arrays [D_t, p_t]."""
+    radices = [int(b) for b in radices]
+    m = len(radices)
+    keep = []
+    cp, sp = _int8_args(d, radices, codes, scales, keep)
+    outs = [np.empty((int(d) // b, b * (b - 1) // 2), dtype=np.float32) for b in radices]
+    op = (_vp * max(m, 1))(*[a.ctypes.data for a in outs])
+    rad = (_i32 * max(m, 1))(*radices)
+    _check(lib.harp_theta_dequantize_int8(int(d), m, rad, cp, sp, op), "harp_theta_dequantize_int8")
+    return outs
+
+
 def harp_kronecker_blocks(table, n2: int, radices2, blocks2):
     """(radices, blocks) of the Mixed-Radix processor equal to (table / sqrt(K)) (x) T_{n2}."""
     table = np.ascontiguousarray(table, dtype=np.float32)
@@ -227,6 +281,29 @@ class Plan:
         self.d, self.radices = int(d), radices
         _check(lib.harp_plan_create_from_theta(C.byref(self._h), int(d), m, rad, th, kinds, mx, sp,
                                                int(flags)), "harp_plan_create_from_theta")
+        return self
+
+    @classmethod
+    def from_theta_int8(cls, d: int, radices, codes, scales, mixers=None, signs=None, flags: int = 0):
+        """``harp_plan_create_from_theta_int8``: int8 codes and per-block scales."""
+        self = cls.__new__(cls)
+        radices = [int(b) for b in radices]
+        m = len(radices)
+        keep = []
+        _, kinds, mx = _theta_args(int(d), radices, None, mixers, keep)
+        cp, scp = _int8_args(int(d), radices, codes, scales, keep)
+        rad = (_i32 * max(m, 1))(*radices)
+        sp = None
+        if signs is not None:
+            s = np.ascontiguousarray(signs, dtype=np.int8)
+            keep.append(s)
+            sp = s.ctypes.data
+        self._h = _vp(None)
+        self._keep = []
+        self.d, self.radices = int(d), radices
+        _check(lib.harp_plan_create_from_theta_int8(C.byref(self._h), int(d), m, rad, cp, scp, kinds,
+                                                    mx, sp, int(flags)),
+               "harp_plan_create_from_theta_int8")
         return self
 
     # -- lifetime

@@ -161,6 +161,47 @@ def test_blocks_from_theta_host_front_end_matches_the_oracle():
     assert e.value.status == harp.HARP_ERR_BAD_SCHEDULE
 
 
+def test_theta_int8_host_front_end_matches_the_oracle_bit_for_bit():
+    """Codes and scales are decided in float32 on both sides, so they must agree exactly."""
+    import numpy as np
+    from oracle import harp_oracle as ho
+    rng = np.random.default_rng(23)
+    d, radices = 1680, [2, 8, 3, 5, 7]
+    thetas = [(rng.standard_normal((d // b, b * (b - 1) // 2)) * rng.uniform(1e-4, 4.0, (d // b, 1)))
+              .astype(np.float32) for b in radices]
+    thetas[2][7] = 0.0                                     # an all-zero block: scale 0, codes 0
+    thetas[0][3, 0] = np.float32(63.5 / 127.0)             # neighbours of rounding ties
+    codes, scales = harp.harp_theta_quantize_int8(d, radices, thetas)
+    rc, rs = ho.quantize_theta_int8(d, radices, thetas)
+    for t in range(len(radices)):
+        np.testing.assert_array_equal(codes[t], rc[t])
+        np.testing.assert_array_equal(scales[t], rs[t])
+    assert scales[2][7] == 0.0 and not codes[2][7].any()
+    back = harp.harp_theta_dequantize_int8(d, radices, codes, scales)
+    rb = ho.dequantize_theta_int8(d, radices, rc, rs)
+    for t in range(len(radices)):
+        np.testing.assert_array_equal(back[t], rb[t])
+    # argument errors: a code outside the quantiser's range, a negative scale, a NaN parameter
+    bad = [c.copy() for c in codes]
+    bad[1][0, 0] = -128
+    with pytest.raises(harp.HarpError) as e:
+        harp.harp_theta_dequantize_int8(d, radices, bad, scales)
+    assert e.value.status == harp.HARP_ERR_INVALID_ARG
+    bads = [x.copy() for x in scales]
+    bads[0][0] = -1.0
+    with pytest.raises(harp.HarpError) as e:
+        harp.harp_theta_dequantize_int8(d, radices, codes, bads)
+    assert e.value.status == harp.HARP_ERR_INVALID_ARG
+    nan = [x.copy() for x in thetas]
+    nan[4][0, 0] = np.nan
+    with pytest.raises(harp.HarpError) as e:
+        harp.harp_theta_quantize_int8(d, radices, nan)
+    assert e.value.status == harp.HARP_ERR_INVALID_ARG
+    with pytest.raises(harp.HarpError) as e:
+        harp.harp_theta_quantize_int8(10, [2, 3], [np.zeros((5, 1), np.float32), np.zeros((3, 3), np.float32)])
+    assert e.value.status == harp.HARP_ERR_BAD_SCHEDULE
+
+
 def test_kronecker_blocks_expand_to_the_kronecker_product():
     """Host expansion of the Kronecker fallback, checked through the oracle's explicit dense
     construction: U_d == kron(table / sqrt(K), U_{n2})."""

@@ -485,6 +485,31 @@ def test_plan_from_theta_matches_the_oracle_blocks(harp, d, radices, mixers):
     plan.destroy()
 
 
+@pytest.mark.parametrize("d,radices", [(4096, [2] * 12), (4096, [8] * 4), (1680, [2, 8, 3, 5, 7])])
+def test_plan_from_int8_theta(harp, d, radices):
+    """Int8-stored parameters: the plan built from codes and scales applies the processor whose
+    blocks the oracle rebuilds from the same codes (its own quantiser, dequantiser, Givens and
+    Cayley maps)."""
+    import torch
+    rng = np.random.default_rng(d + len(radices))
+    thetas = [(0.7 * rng.standard_normal((d // b, b * (b - 1) // 2))).astype(np.float32) for b in radices]
+    mix = ["identity" if b & (b - 1) else None for b in radices]
+    signs = gi.make_signs(d, rng)
+    codes, scales = ho.quantize_theta_int8(d, radices, thetas)
+    plan = harp.Plan.from_theta_int8(d, radices, codes, scales, mix, signs, flags=harp.HARP_VALIDATE_ORTHO)
+    n = 19
+    say(f"from int8 theta d={d} radices={radices} kernel={plan.kernel_name(n)}")
+    X = gi.round_to_bf16(rng.standard_normal((n, d)).astype(np.float32))
+    blocks = ho.blocks_from_theta(d, radices, ho.dequantize_theta_int8(d, radices, codes, scales), mix)
+    for dtype in ("f32", "bf16"):
+        Y = to_host64(harp.harp_apply(plan, to_device(X, dtype)))
+        Z = to_host64(harp.harp_apply_transpose(plan, to_device(X, dtype)))
+        torch.cuda.synchronize()
+        assert_parity(Y, ho.apply_staged(X, d, radices, blocks, signs), dtype, "apply")
+        assert_parity(Z, ho.apply_transpose_staged(X, d, radices, blocks, signs), dtype, "apply_transpose")
+    plan.destroy()
+
+
 def test_kronecker_fallback_plan(harp):
     """d = 12 * 1024: T_d = (H~_12 / sqrt(12)) (x) T_1024 built by harp_kronecker_blocks."""
     import torch

@@ -384,3 +384,49 @@ def test_generated_blocks_are_orthogonal():
         K = gi.make_blocks(b * 6, [b], "orth", rng)[0].astype(np.float64)
         err = np.max(np.abs(np.einsum("cij,cik->cjk", K, K) - np.eye(b)))
         assert err < 5e-7
+
+
+# ------------------------------------------------------------------ int8 storage of Theta
+def test_int8_theta_hand_computed_block():
+    """App. "Int8 storage of HARP parameters": s = max|a| / 127, q = round(a / s).  One radix-3
+    block (3 parameters) and radix-2 blocks (one angle each), worked by hand."""
+    a3 = np.array([[0.3, -1.0, 0.26],                             # s = 1/127: 38.1, -127, 33.02
+                   [2.54, 0.048, -1.0]], dtype=np.float32)        # s = 0.02: 127, 2.4, -50
+    a2 = np.array([[0.5], [-2.0], [0.0]], dtype=np.float32)       # single angle -> +-127, s = |a|/127
+    codes, scales = ho.quantize_theta_int8(6, [3, 2], [a3, a2])
+    np.testing.assert_array_equal(codes[0], [[38, -127, 33], [127, 2, -50]])
+    assert abs(float(scales[0][1]) - 0.02) < 1e-8
+    assert abs(float(scales[0][0]) - 1.0 / 127.0) < 1e-9
+    np.testing.assert_array_equal(codes[1], [[127], [-127], [0]])
+    np.testing.assert_allclose(scales[1], [0.5 / 127, 2.0 / 127, 0.0], rtol=1e-7)
+    back = ho.dequantize_theta_int8(6, [3, 2], codes, scales)
+    np.testing.assert_allclose(back[0], [[38 / 127, -1.0, 33 / 127], [2.54, 0.04, -1.0]], rtol=1e-6)
+    np.testing.assert_allclose(back[1], [[0.5], [-2.0], [0.0]], rtol=1e-6)
+
+
+def test_int8_theta_error_bound_extremes_and_symmetry():
+    rng = np.random.default_rng(5)
+    d, radices = 960, [8, 5, 2, 4, 3]
+    thetas = [(rng.standard_normal((d // b, b * (b - 1) // 2)) * rng.uniform(1e-3, 3.0, (d // b, 1)))
+              .astype(np.float32) for b in radices]
+    codes, scales = ho.quantize_theta_int8(d, radices, thetas)
+    back = ho.dequantize_theta_int8(d, radices, codes, scales)
+    neg_codes, neg_scales = ho.quantize_theta_int8(d, radices, [-t for t in thetas])
+    for t, b in enumerate(radices):
+        assert codes[t].dtype == np.int8 and scales[t].dtype == np.float32
+        assert codes[t].min() >= -127
+        # the largest parameter of every block sits at +-127
+        assert np.all(np.max(np.abs(codes[t].astype(np.int32)), axis=1) == 127)
+        # rounding error at most half a step (plus float32 rounding of the quotient and product)
+        err = np.abs(back[t].astype(np.float64) - thetas[t].astype(np.float64))
+        assert np.all(err <= 0.5 * scales[t][:, None].astype(np.float64) * (1 + 1e-5))
+        # odd symmetry of round-half-even
+        np.testing.assert_array_equal(neg_codes[t], -codes[t])
+        np.testing.assert_array_equal(neg_scales[t], scales[t])
+    # the reconstructed blocks are orthogonal and close to the unquantised ones
+    Kq = ho.blocks_from_theta(d, radices, back, ["hadamard", "identity", None, None, "identity"])
+    K = ho.blocks_from_theta(d, radices, thetas, ["hadamard", "identity", None, None, "identity"])
+    for kq, k in zip(Kq, K):
+        eye = np.einsum("cij,ckj->cik", kq, kq)
+        assert np.max(np.abs(eye - np.eye(kq.shape[1]))) < 1e-12
+        assert np.max(np.abs(kq - k)) < 0.2
