@@ -41,6 +41,9 @@ schedules", Alg. 2) and Table "radix ablation" stage counts, Eq. (13) parameter 
 radix-2 block written out, the radix-3 Cayley block against the Rodrigues rotation.
 ``quantize_theta_int8`` (App. "Int8 storage of HARP parameters"): a hand-computed block, the
 largest parameter of a block mapping to +-127, |a - s q| <= s / 2, sign symmetry.
+``grad_blocks`` (the gradient that Alg. 3's update needs, by the chain rule through Alg. 1):
+central finite differences of <apply(X), G> in every block entry at small d, dX = G U^T
+through the dense U, the single-stage closed form X_sigma[:, idx]^T G[:, idx], linearity in G.
 Unpinned against the paper (values not published): the QR base mixer's fixed
 Gaussian and any trained processor -- "parity unpinned" for those; they are inputs
 to this library, not computed by it.
@@ -55,7 +58,7 @@ __all__ = [
     "apply_staged", "apply_transpose_staged", "rotate_weight",
     "stage_matrix_explicit", "U_explicit", "greedy_schedule",
     "sylvester_hadamard", "param_count", "givens_block", "cayley_block",
-    "blocks_from_theta", "quantize_theta_int8", "dequantize_theta_int8",
+    "blocks_from_theta", "quantize_theta_int8", "dequantize_theta_int8", "grad_blocks",
 ]
 
 
@@ -364,3 +367,42 @@ def dequantize_theta_int8(d, radices, codes, scales):
         s = np.asarray(scales[t], dtype=np.float32).reshape(D)
         out.append((s[:, None] * q.astype(np.float32)).astype(np.float32))
     return out
+
+
+def grad_blocks(X, G, d, radices, blocks, signs=None):
+    """Gradient of a loss through ``Y = apply(X)`` with respect to every block entry and to X,
+    given ``G = dL/dY`` -- what the update of Alg. 3 (layerwise fitting) differentiates.
+
+    Chain rule through Alg. 1, stage by stage.  Forward: ``x_0 = X * sigma``, ``x_{t+1} =
+    stage_t(x_t)``.  Backward from ``g_m = G``: for block c of stage t with coordinates idx,
+    ``dK_t[c] = x_t[:, idx]^T @ g_{t+1}[:, idx]`` (sum over the rows) and
+    ``g_t[:, idx] = g_{t+1}[:, idx] @ K_t[c]^T``; finally ``dX = g_0 * sigma``.
+    Returns (dK, dX): a list of float64 arrays [D_t, b_t, b_t], and [n, d].
+    """
+    radices = check_schedule(d, radices)
+    K = _as_blocks(d, radices, blocks)
+    sg = _as_signs(d, signs)
+    st = strides(radices)
+    m = len(radices)
+    x = [np.array(X, dtype=np.float64) * sg[None, :]]
+    for t, b in enumerate(radices):
+        x.append(stage_apply_rows(x[t].copy(), b, st[t], K[t]))
+    g = np.array(G, dtype=np.float64)
+    if g.shape != x[0].shape:
+        raise ValueError("G must have the shape of X")
+    dK = [None] * m
+    for t in range(m - 1, -1, -1):
+        b, s = radices[t], st[t]
+        D = d // b
+        dKt = np.empty((D, b, b))
+        r = np.arange(b)
+        gn = np.empty_like(g)
+        for alpha in range(d // (b * s)):
+            for beta in range(s):
+                c = alpha * s + beta
+                idx = alpha * b * s + r * s + beta
+                dKt[c] = x[t][:, idx].T @ g[:, idx]
+                gn[:, idx] = g[:, idx] @ K[t][c].T
+        dK[t] = dKt
+        g = gn
+    return dK, g * sg[None, :]

@@ -430,3 +430,73 @@ def test_int8_theta_error_bound_extremes_and_symmetry():
         eye = np.einsum("cij,ckj->cik", kq, kq)
         assert np.max(np.abs(eye - np.eye(kq.shape[1]))) < 1e-12
         assert np.max(np.abs(kq - k)) < 0.2
+
+
+# ------------------------------------------------------------------ gradient through the stages
+def _loss(X, G, d, radices, blocks, signs):
+    return float(np.sum(ho.apply(X, d, radices, blocks, signs) * G))
+
+
+@pytest.mark.parametrize("d,radices", [(12, [2, 3, 2]), (16, [4, 2, 2]), (30, [5, 2, 3])])
+def test_grad_blocks_against_central_finite_differences(d, radices):
+    """L = <apply(X), G> is linear in every block entry, so a central difference is exact up to
+    rounding: every entry of every dK, and every entry of dX, is checked."""
+    rng = np.random.default_rng(d)
+    blocks = [rng.standard_normal((d // b, b, b)) for b in radices]       # not orthogonal on purpose
+    signs = rng.choice([-1, 1], size=d).astype(np.int8)
+    X, G = rng.standard_normal((5, d)), rng.standard_normal((5, d))
+    dK, dX = ho.grad_blocks(X, G, d, radices, blocks, signs)
+    h = 1e-3
+    for t, b in enumerate(radices):
+        for c in range(d // b):
+            for r in range(b):
+                for r2 in range(b):
+                    bp = [k.copy() for k in blocks]
+                    bm = [k.copy() for k in blocks]
+                    bp[t][c, r, r2] += h
+                    bm[t][c, r, r2] -= h
+                    fd = (_loss(X, G, d, radices, bp, signs) - _loss(X, G, d, radices, bm, signs)) / (2 * h)
+                    assert abs(fd - dK[t][c, r, r2]) < 1e-8 * (1 + abs(fd)), (t, c, r, r2)
+    for i in range(X.shape[0]):
+        for j in range(d):
+            Xp, Xm = X.copy(), X.copy()
+            Xp[i, j] += h
+            Xm[i, j] -= h
+            fd = (_loss(Xp, G, d, radices, blocks, signs) - _loss(Xm, G, d, radices, blocks, signs)) / (2 * h)
+            assert abs(fd - dX[i, j]) < 1e-8 * (1 + abs(fd))
+
+
+def test_grad_blocks_closed_forms_and_linearity():
+    rng = np.random.default_rng(3)
+    d, radices = 48, [4, 3, 2, 2]
+    blocks = gi.make_blocks(d, radices, "orth", rng)
+    signs = gi.make_signs(d, rng)
+    X, G = rng.standard_normal((9, d)), rng.standard_normal((9, d))
+    dK, dX = ho.grad_blocks(X, G, d, radices, blocks, signs)
+    # dX = G U^T through the dense matrix
+    U = ho.build_U(d, radices, blocks, signs)
+    np.testing.assert_allclose(dX, G @ U.T, atol=1e-12)
+    # a single stage (b = d, one block): dK = (X * sigma)^T G
+    d1 = 6
+    K1 = [rng.standard_normal((1, d1, d1))]
+    s1 = rng.choice([-1, 1], size=d1).astype(np.int8)
+    X1, G1 = rng.standard_normal((7, d1)), rng.standard_normal((7, d1))
+    dK1, dX1 = ho.grad_blocks(X1, G1, d1, [d1], K1, s1)
+    np.testing.assert_allclose(dK1[0][0], (X1 * s1).T @ G1, atol=1e-12)
+    np.testing.assert_allclose(dX1, (G1 @ K1[0][0].T) * s1, atol=1e-12)
+    # the last stage of a longer schedule: its input is the transform by the earlier stages
+    xin = X * signs
+    stv = ho.strides(radices)
+    for t in range(len(radices) - 1):
+        xin = ho.stage_apply_rows(xin.copy(), radices[t], stv[t], np.asarray(blocks[t], dtype=np.float64))
+    bl, sl = radices[-1], stv[-1]
+    for c in (0, d // bl - 1):
+        idx = (c // sl) * bl * sl + np.arange(bl) * sl + c % sl
+        np.testing.assert_allclose(dK[-1][c], xin[:, idx].T @ G[:, idx], atol=1e-12)
+    # linear in G, and rows add up
+    dK2, _ = ho.grad_blocks(X, 2.0 * G, d, radices, blocks, signs)
+    dKa, _ = ho.grad_blocks(X[:4], G[:4], d, radices, blocks, signs)
+    dKb, _ = ho.grad_blocks(X[4:], G[4:], d, radices, blocks, signs)
+    for t in range(len(radices)):
+        np.testing.assert_allclose(dK2[t], 2.0 * dK[t], atol=1e-12)
+        np.testing.assert_allclose(dKa[t] + dKb[t], dK[t], atol=1e-12)
