@@ -175,6 +175,32 @@ harp_status_t harp_plan_create_from_theta(harp_plan_t **out, int64_t d, int32_t 
                                           const int8_t *signs, uint32_t flags);
 
 /*
+ * Gradient through Y = X U for fitting (the update of the layerwise fitting procedure,
+ * appendix "Layerwise fitting of HARP for a linear layer", differentiates the rotated weights
+ * with respect to the processors' parameters; this is the chain rule through Algorithm 1).
+ * With x_0 = X diag(signs), x_{t+1} = stage_t(x_t) and G = dL/dY:
+ *     dK[t][c][r][r2] = sum over the n rows of  x_t[i(c, r)] * g_{t+1}[i(c, r2)],
+ *     g_t = g_{t+1} through stage t with every block transposed,   g_m = G,
+ *     dX = g_0 diag(signs)  (= G U^T),
+ * i(c, r) = the r-th coordinate of block c of stage t.  The blocks need not be orthogonal.
+ * The gradient for the two-sided rotation follows by calling this with X = W (plan_V) and
+ * with X = (W V)^T (plan_U).
+ *   X, G   device, [n, d] row-major, element type dt, leading dimensions ldx, ldg >= d.
+ *   dK     host array of m DEVICE pointers; dK[t] receives D_t * b_t * b_t float32 values in
+ *          the layout of harp_plan_create's blocks[t] (overwritten; zeros when n == 0).
+ *   dX     device, [n, d] of type dt with leading dimension lddx, or NULL to skip it.
+ *   workspace  device memory of at least harp_grad_blocks_workspace_size bytes ((m + 1) float32
+ *          copies of the batch plus partial sums); may be NULL when that size is 0.
+ * Float32 arithmetic; the sum over rows is taken in a fixed order (bit-reproducible for the same
+ * n).  Asynchronous on `stream`.  HARP_ERR_UNSUPPORTED for a schedule with a radix above 8.
+ */
+harp_status_t harp_grad_blocks_workspace_size(const harp_plan_t *plan, int64_t n, size_t *bytes);
+harp_status_t harp_grad_blocks(const harp_plan_t *plan, const void *X, int64_t ldx, const void *G,
+                               int64_t ldg, int64_t n, harp_dtype_t dt, float *const *dK, void *dX,
+                               int64_t lddx, void *workspace, size_t workspace_bytes,
+                               void *stream);
+
+/*
  * Int8 storage of the rotation parameters (Sec. 3, "Parameter quantization for deployment";
  * appendix "Int8 storage of HARP parameters").  Per block c of stage t the p_t = b_t (b_t-1)/2
  * parameters a (the strict upper triangle of the Cayley matrix, or the one Givens angle for

@@ -756,6 +756,16 @@ harp_status_t harp_plan_create(harp_plan_t **out, int64_t d, int32_t m, const in
       }
     if (st == HARP_OK && !plan->prog[HARP_ALGO_GENERIC][0].ok && !plan->prog[HARP_ALGO_SPLIT][0].ok)
       st = HARP_ERR_UNSUPPORTED;
+    if (st == HARP_OK && signs) {
+      int8_t *ds = nullptr;
+      if (hipMalloc((void **)&ds, (size_t)d) != hipSuccess) {
+        st = HARP_ERR_OOM;
+      } else {
+        plan->dev_allocs.push_back(ds);
+        if (hipMemcpy(ds, signs, (size_t)d, hipMemcpyHostToDevice) != hipSuccess) st = HARP_ERR_DEVICE;
+        plan->dev_signs = ds;
+      }
+    }
     // Column-mode image (the plan as the U side of a weight rotation): per direction the dense
     // effective blocks [d / b][b][b] of every stage in execution order, and the passes over them.
     bool col_ok = true;
@@ -876,6 +886,33 @@ harp_status_t harp_rotate_weight_inverse(const harp_plan_t *plan_U, const harp_p
                                          void *workspace, size_t workspace_bytes, void *stream) {
   return rotate_impl(plan_U, plan_V, DIR_TRN, W, ldw, Wout, ldo, d_out, d_in, dt, workspace,
                      workspace_bytes, stream);
+}
+
+harp_status_t harp_grad_blocks_workspace_size(const harp_plan_t *plan, int64_t n, size_t *bytes) {
+  if (!plan || !bytes || n < 0) return HARP_ERR_INVALID_ARG;
+  if (plan->col[DIR_FWD].empty()) return HARP_ERR_UNSUPPORTED;
+  *bytes = n == 0 ? 0 : grad_workspace_bytes(plan, n);
+  return HARP_OK;
+}
+
+harp_status_t harp_grad_blocks(const harp_plan_t *plan, const void *X, int64_t ldx, const void *G,
+                               int64_t ldg, int64_t n, harp_dtype_t dt, float *const *dK, void *dX,
+                               int64_t lddx, void *workspace, size_t workspace_bytes,
+                               void *stream) {
+  if (!plan || !dK || n < 0) return HARP_ERR_INVALID_ARG;
+  if (dt != HARP_F32 && dt != HARP_BF16) return HARP_ERR_INVALID_ARG;
+  for (int t = 0; t < plan->m; ++t)
+    if (!dK[t]) return HARP_ERR_INVALID_ARG;
+  if (n > 0) {
+    if (!X || !G || ldx < plan->d || ldg < plan->d) return HARP_ERR_INVALID_ARG;
+    if (dX && lddx < plan->d) return HARP_ERR_INVALID_ARG;
+  }
+  if (plan->col[DIR_FWD].empty()) return HARP_ERR_UNSUPPORTED;
+  size_t need = 0;
+  harp_status_t st = harp_grad_blocks_workspace_size(plan, n, &need);
+  if (st != HARP_OK) return st;
+  if (need > 0 && (!workspace || workspace_bytes < need)) return HARP_ERR_INVALID_ARG;
+  return launch_grad(plan, X, ldx, G, ldg, n, dt, dK, dX, lddx, workspace, (hipStream_t)stream);
 }
 
 harp_status_t harp_greedy_schedule(int64_t d, int32_t b_base, int32_t b_max, int32_t *out_radices,

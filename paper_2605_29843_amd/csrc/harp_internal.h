@@ -139,6 +139,7 @@ struct harp_plan {
   // column-mode image and passes per direction; empty when some radix exceeds 8
   std::vector<harp::ColStage> col[2];
   std::vector<harp::ColPassHost> colpass[2];
+  const int8_t *dev_signs = nullptr;   // device copy of the signs (null: all +1)
 };
 
 namespace harp {
@@ -197,6 +198,11 @@ harp_status_t launch_col_pass(const harp_plan *plan, const ColPass *dpass, const
                               int64_t lds_, harp_dtype_t dt_src, void *dst, int64_t ldd,
                               harp_dtype_t dt_dst, int64_t nrows, int64_t ncols,
                               hipStream_t stream);
+// gradient with respect to the blocks (harp_grad.hip); needs plan->col[DIR_FWD]
+size_t grad_workspace_bytes(const harp_plan *plan, int64_t n);
+harp_status_t launch_grad(const harp_plan *plan, const void *X, int64_t ldx, const void *G,
+                          int64_t ldg, int64_t n, harp_dtype_t dt, float *const *dK, void *dX,
+                          int64_t lddx, void *ws, hipStream_t st);
 int choose_pipe_rows(const harp_plan *plan, int64_t n, int64_t nchunk, int chunk);
 const HostProgram *select_program(const harp_plan *plan, Direction dir, int64_t n,
                                   const char **name);

@@ -57,6 +57,9 @@ _SIGS = {
     "harp_rotate_weight_workspace_size": (_i32, [_vp, _vp, _i64, _i64, _i32, C.POINTER(_sz)]),
     "harp_rotate_weight": (_i32, [_vp, _vp, _vp, _i64, _vp, _i64, _i64, _i64, _i32, _vp, _sz, _vp]),
     "harp_rotate_weight_inverse": (_i32, [_vp, _vp, _vp, _i64, _vp, _i64, _i64, _i64, _i32, _vp, _sz, _vp]),
+    "harp_grad_blocks_workspace_size": (_i32, [_vp, _i64, C.POINTER(_sz)]),
+    "harp_grad_blocks": (_i32, [_vp, _vp, _i64, _vp, _i64, _i64, _i32, C.POINTER(_vp), _vp, _i64, _vp,
+                                _sz, _vp]),
     "harp_greedy_schedule": (_i32, [_i64, _i32, _i32, C.POINTER(_i32), C.POINTER(_i32)]),
     "harp_plan_dim": (_i64, [_vp]),
     "harp_plan_num_stages": (_i32, [_vp]),
@@ -375,6 +378,39 @@ def harp_apply(plan: Plan, X, Y=None, stream=None):
 def harp_apply_transpose(plan: Plan, X, Y=None, stream=None):
     """Y = X U^T."""
     return _apply(lib.harp_apply_transpose, "harp_apply_transpose", plan, X, Y, stream)
+
+
+def harp_grad_blocks_workspace_size(plan, n: int) -> int:
+    b = _sz(0)
+    _check(lib.harp_grad_blocks_workspace_size(plan.handle, int(n), C.byref(b)),
+           "harp_grad_blocks_workspace_size")
+    return int(b.value)
+
+
+def harp_grad_blocks(plan, X, G, want_dX: bool = True, workspace=None, stream=None):
+    """(dK, dX): gradients of a loss with dL/dY = G through Y = X U.  dK[t] is a float32 device
+    tensor [D_t, b_t, b_t]; dX has the shape and type of X (None when want_dX is false)."""
+    import torch
+    if X.shape != G.shape or X.dtype != G.dtype:
+        raise ValueError("X and G must have the same shape and dtype")
+    ldx, ldg = _rowmajor_2d(X, "X"), _rowmajor_2d(G, "G")
+    n, d = X.shape
+    if d != plan.d:
+        raise ValueError("X has the wrong number of columns")
+    dt = _dtype_code(X)
+    dK = [torch.empty((plan.d // b, b, b), dtype=torch.float32, device=X.device) for b in plan.radices]
+    dX = torch.empty_like(X) if want_dX else None
+    need = harp_grad_blocks_workspace_size(plan, n)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    ptrs = (_vp * max(len(dK), 1))(*[t.data_ptr() for t in dK])
+    _check(lib.harp_grad_blocks(plan.handle, X.data_ptr(), ldx, G.data_ptr(), ldg, n, dt, ptrs,
+                                dX.data_ptr() if dX is not None else None,
+                                _rowmajor_2d(dX, "dX") if dX is not None else 0, ws_ptr, ws_bytes,
+                                _stream_ptr(stream)), "harp_grad_blocks")
+    return dK, dX
 
 
 def harp_rotate_weight_workspace_size(plan_U, plan_V, d_out, d_in, dtype_code) -> int:

@@ -129,6 +129,14 @@ def test_null_plan_and_null_out_are_invalid_arguments():
                                   None) == harp.HARP_ERR_INVALID_ARG
 
 
+def test_grad_blocks_argument_errors_without_a_gpu():
+    lib = harp.lib
+    b = C.c_size_t(5)
+    assert lib.harp_grad_blocks_workspace_size(None, 4, C.byref(b)) == harp.HARP_ERR_INVALID_ARG
+    assert lib.harp_grad_blocks(None, None, 0, None, 0, 0, harp.HARP_F32, None, None, 0, None, 0,
+                                None) == harp.HARP_ERR_INVALID_ARG
+
+
 def test_blocks_from_theta_host_front_end_matches_the_oracle():
     """The library's parameter front end runs on the host, so it is checked here without a GPU:
     Givens (radix 2) and Cayley (radix > 2) blocks, Hadamard / identity / custom mixers."""
