@@ -222,6 +222,26 @@ def main():
                   f"({gb / HBM_PEAK_GBS:.1%})", file=sys.stderr, flush=True)
         except Exception as e:  # noqa: BLE001
             print(f"[extra] rotate_weight: {e}", file=sys.stderr, flush=True)
+        try:   # gradient with respect to the blocks at the benchmark shape
+            Gd = torch.randn(n, d, device="cuda").to(X0.dtype)
+            wsz = harp.harp_grad_blocks_workspace_size(plan, n)
+            wsg = torch.empty(wsz, dtype=torch.uint8, device="cuda")
+            for _ in range(3):
+                harp.harp_grad_blocks(plan, X0, Gd, True, wsg, stream)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(10):
+                harp.harp_grad_blocks(plan, X0, Gd, True, wsg, stream)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / 10
+            # algorithmic bytes: read X and G, write dX (caller's type) and the block gradients
+            gb = (3 * n * d * esz + sum(d * b for b in radices) * 4) / (us * 1e-6) / 1e9
+            print(f"[extra] grad_blocks {n} x {d} {w['dtype']}: {us:.0f} us, {gb:.0f} GB/s algorithmic "
+                  f"({gb / HBM_PEAK_GBS:.1%})", file=sys.stderr, flush=True)
+        except Exception as e:  # noqa: BLE001
+            print(f"[extra] grad_blocks: {e}", file=sys.stderr, flush=True)
     print(json.dumps(out), flush=True)
 
 

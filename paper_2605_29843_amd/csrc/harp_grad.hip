@@ -125,8 +125,19 @@ __global__ __launch_bounds__(kGradThreads) void harp_grad_reduce_kernel(
   for (int64_t i = (int64_t)blockIdx.x * kGradThreads + threadIdx.x; i < total;
        i += (int64_t)gridDim.x * kGradThreads) {
     const int v = (int)(i / D), c = (int)(i % D);     // consecutive threads: consecutive c
+    // loads eight chunks ahead, additions in ascending chunk order
+    const float *p = partial + (size_t)v * D + c;
+    const size_t step = (size_t)bb * D;
     float sum = 0.f;
-    for (int k = 0; k < nchunks; ++k) sum += partial[((size_t)k * bb + v) * D + c];
+    int k = 0;
+    for (; k + 8 <= nchunks; k += 8) {
+      float t[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) t[u] = p[(size_t)(k + u) * step];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) sum += t[u];
+    }
+    for (; k < nchunks; ++k) sum += p[(size_t)k * step];
     if (signs) sum *= (float)signs[(size_t)c * b + v / b];
     dK[(size_t)c * bb + v] = sum;
   }
