@@ -10,12 +10,16 @@
 // per stage that updates g in place and leaves per-row-chunk partial sums of dK, and a
 // reduction kernel adds the chunks in a fixed order (no atomics: results are reproducible).
 // One thread owns one block c for a chunk of rows: its b*b kernel values and b*b accumulators
-// stay in registers.  Radices up to 8 (the plan's dense per-stage image with the signs folded
-// into stage 0 is the one the column-mode passes use).
+// stay in registers.  Up to three consecutive radix-2 stages share one kernel: a thread owns
+// the 2^k coordinates base + e s and the k 2^(k-1) blocks that act on them, the forward kernel
+// stores only the run's output, and the backward kernel recomputes the run's inner activations
+// in registers.  Radices up to 8 (the plan's dense per-stage image with the signs folded into
+// stage 0 is the one the column-mode passes use).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 #include <algorithm>
+#include <vector>
 
 #include "harp_internal.h"
 
@@ -115,31 +119,199 @@ __global__ __launch_bounds__(kGradThreads) void harp_grad_bwd_kernel(
     partial[((size_t)blockIdx.y * (B * B) + v) * D + c] = acc[v];
 }
 
-// dK[c][v] = sum over chunks (ascending) of partial[(chunk * BB + v) * D + c]; for stage 0 the
-// image holds diag(sigma) K_0, so row r of its gradient takes the sign of coordinate c b + r.
+// Run of K radix-2 stages with strides s, 2s, .., 2^(K-1) s.  Item q = hi s + lo owns the
+// coordinates base + e s, e < 2^K, base = hi 2^K s + lo.  Stage i pairs e0 (bit i clear) with
+// e0 + 2^i; that pair is block c = (i0 / (2 s_i)) s_i + i0 % s_i of the stage, i0 = base + e0 s,
+// s_i = 2^i s.
+struct GradRun {
+  const float *blocks[3];
+};
+
+template <int K>
+__device__ __forceinline__ void grad_run_blocks(const GradRun &run, int base, int s, int D,
+                                                float (&kv)[K][1 << (K - 1)][4],
+                                                int (&cidx)[K][1 << (K - 1)]) {
+#pragma unroll
+  for (int i = 0; i < K; ++i) {
+    const int si = s << i;
+#pragma unroll
+    for (int p = 0; p < (1 << (K - 1)); ++p) {
+      const int eh = p >> i, el = p & ((1 << i) - 1);
+      const int e0 = (eh << (i + 1)) | el;
+      const int i0 = base + e0 * s;
+      const int c = (i0 / (2 * si)) * si + i0 % si;
+      cidx[i][p] = c;
+      const float4 f = *reinterpret_cast<const float4 *>(run.blocks[i] + (size_t)c * 4);
+      kv[i][p][0] = f.x; kv[i][p][1] = f.y; kv[i][p][2] = f.z; kv[i][p][3] = f.w;
+    }
+  }
+  (void)D;
+}
+
+template <int K>
+__global__ __launch_bounds__(kGradThreads) void harp_grad_fwd_run_kernel(
+    const float *__restrict__ X, float *__restrict__ Y, int64_t ld, int64_t n, int rows,
+    GradRun run, int nitems, int s) {
+  constexpr int E = 1 << K, H = E / 2;
+  const int q = blockIdx.x * kGradThreads + threadIdx.x;
+  if (q >= nitems) return;
+  const int base = (q / s) * E * s + q % s;
+  float kv[K][H][4];
+  int cidx[K][H];
+  grad_run_blocks<K>(run, base, s, 0, kv, cidx);
+  const int64_t r0 = (int64_t)blockIdx.y * rows;
+  const int64_t r1 = (r0 + rows < n) ? r0 + rows : n;
+  // the next row is requested before the work on the current one
+  float nx[E];
+#pragma unroll
+  for (int e = 0; e < E; ++e) nx[e] = (r0 < r1) ? X[r0 * ld + base + (size_t)e * s] : 0.f;
+  for (int64_t row = r0; row < r1; ++row) {
+    float *y = Y + row * ld + base;
+    float v[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) v[e] = nx[e];
+    if (row + 1 < r1) {
+      const float *x = X + (row + 1) * ld + base;
+#pragma unroll
+      for (int e = 0; e < E; ++e) nx[e] = x[(size_t)e * s];
+    }
+#pragma unroll
+    for (int i = 0; i < K; ++i)
+#pragma unroll
+      for (int p = 0; p < H; ++p) {
+        const int eh = p >> i, el = p & ((1 << i) - 1);
+        const int e0 = (eh << (i + 1)) | el, e1 = e0 | (1 << i);
+        const float a = v[e0], b = v[e1];
+        v[e0] = fmaf(b, kv[i][p][2], a * kv[i][p][0]);
+        v[e1] = fmaf(b, kv[i][p][3], a * kv[i][p][1]);
+      }
+#pragma unroll
+    for (int e = 0; e < E; ++e) y[(size_t)e * s] = v[e];
+  }
+}
+
+// partial sums of sub-stage i go to partial[i * pstride + (chunk * 4 + v) * D + c], D = d / 2
+template <int K>
+__global__ __launch_bounds__(kGradThreads) void harp_grad_bwd_run_kernel(
+    const float *__restrict__ X, float *__restrict__ Gm, int64_t ld, int64_t n, int rows,
+    GradRun run, int nitems, int s, int D, float *__restrict__ partial, size_t pstride) {
+  constexpr int E = 1 << K, H = E / 2;
+  const int q = blockIdx.x * kGradThreads + threadIdx.x;
+  if (q >= nitems) return;
+  const int base = (q / s) * E * s + q % s;
+  float kv[K][H][4], acc[K][H][4];
+  int cidx[K][H];
+  grad_run_blocks<K>(run, base, s, D, kv, cidx);
+#pragma unroll
+  for (int i = 0; i < K; ++i)
+#pragma unroll
+    for (int p = 0; p < H; ++p)
+#pragma unroll
+      for (int w = 0; w < 4; ++w) acc[i][p][w] = 0.f;
+  const int64_t r0 = (int64_t)blockIdx.y * rows;
+  const int64_t r1 = (r0 + rows < n) ? r0 + rows : n;
+  float nx[E], ng[E];
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    nx[e] = (r0 < r1) ? X[r0 * ld + base + (size_t)e * s] : 0.f;
+    ng[e] = (r0 < r1) ? Gm[r0 * ld + base + (size_t)e * s] : 0.f;
+  }
+  for (int64_t row = r0; row < r1; ++row) {
+    float *g = Gm + row * ld + base;
+    float xs[K][E], gv[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      xs[0][e] = nx[e];
+      gv[e] = ng[e];
+    }
+    if (row + 1 < r1) {   // the next row (its g is not written by anyone before this thread does)
+      const float *x = X + (row + 1) * ld + base;
+      const float *gn = Gm + (row + 1) * ld + base;
+#pragma unroll
+      for (int e = 0; e < E; ++e) {
+        nx[e] = x[(size_t)e * s];
+        ng[e] = gn[(size_t)e * s];
+      }
+    }
+    // inputs of the inner stages, recomputed
+#pragma unroll
+    for (int i = 0; i + 1 < K; ++i) {
+#pragma unroll
+      for (int p = 0; p < H; ++p) {
+        const int eh = p >> i, el = p & ((1 << i) - 1);
+        const int e0 = (eh << (i + 1)) | el, e1 = e0 | (1 << i);
+        const float a = xs[i][e0], b = xs[i][e1];
+        xs[i + 1][e0] = fmaf(b, kv[i][p][2], a * kv[i][p][0]);
+        xs[i + 1][e1] = fmaf(b, kv[i][p][3], a * kv[i][p][1]);
+      }
+    }
+#pragma unroll
+    for (int i = K - 1; i >= 0; --i) {
+#pragma unroll
+      for (int p = 0; p < H; ++p) {
+        const int eh = p >> i, el = p & ((1 << i) - 1);
+        const int e0 = (eh << (i + 1)) | el, e1 = e0 | (1 << i);
+        const float x0 = xs[i][e0], x1 = xs[i][e1], g0 = gv[e0], g1 = gv[e1];
+        acc[i][p][0] = fmaf(x0, g0, acc[i][p][0]);
+        acc[i][p][1] = fmaf(x0, g1, acc[i][p][1]);
+        acc[i][p][2] = fmaf(x1, g0, acc[i][p][2]);
+        acc[i][p][3] = fmaf(x1, g1, acc[i][p][3]);
+        gv[e0] = fmaf(g1, kv[i][p][1], g0 * kv[i][p][0]);   // g K^T, row 0: k00 g0 + k01 g1
+        gv[e1] = fmaf(g1, kv[i][p][3], g0 * kv[i][p][2]);
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < E; ++e) g[(size_t)e * s] = gv[e];
+  }
+#pragma unroll
+  for (int i = 0; i < K; ++i)
+#pragma unroll
+    for (int p = 0; p < H; ++p)
+#pragma unroll
+      for (int w = 0; w < 4; ++w)
+        partial[(size_t)i * pstride + ((size_t)blockIdx.y * 4 + w) * D + cidx[i][p]] = acc[i][p][w];
+}
+
+// dK[c][v] = sum over the chunks of partial[(chunk * BB + v) * D + c], in a fixed order: eight
+// threads per value each add a contiguous eighth of the chunks (ascending), then the eight
+// sums are added in ascending order.  For stage 0 the image holds diag(sigma) K_0, so row r of
+// its gradient takes the sign of coordinate c b + r.
 __global__ __launch_bounds__(kGradThreads) void harp_grad_reduce_kernel(
     const float *__restrict__ partial, int nchunks, int D, int b, const int8_t *__restrict__ signs,
     float *__restrict__ dK) {
+  __shared__ float part[8][32];
   const int bb = b * b;
   const int64_t total = (int64_t)D * bb;
-  for (int64_t i = (int64_t)blockIdx.x * kGradThreads + threadIdx.x; i < total;
-       i += (int64_t)gridDim.x * kGradThreads) {
-    const int v = (int)(i / D), c = (int)(i % D);     // consecutive threads: consecutive c
-    // loads eight chunks ahead, additions in ascending chunk order
-    const float *p = partial + (size_t)v * D + c;
-    const size_t step = (size_t)bb * D;
+  const int lane = threadIdx.x & 31, slice = threadIdx.x >> 5;
+  const int per = (nchunks + 7) / 8;
+  const int k0 = slice * per, k1 = (k0 + per < nchunks) ? k0 + per : nchunks;
+  const size_t step = (size_t)bb * D;
+  for (int64_t i0 = (int64_t)blockIdx.x * 32; i0 < total; i0 += (int64_t)gridDim.x * 32) {
+    const int64_t i = i0 + lane;
+    const int v = (int)(i / D), c = (int)(i % D);     // consecutive lanes: consecutive c
     float sum = 0.f;
-    int k = 0;
-    for (; k + 8 <= nchunks; k += 8) {
-      float t[8];
+    if (i < total) {
+      const float *p = partial + (size_t)v * D + c;
+      int k = k0;
+      for (; k + 8 <= k1; k += 8) {
+        float t[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) t[u] = p[(size_t)(k + u) * step];
+        for (int u = 0; u < 8; ++u) t[u] = p[(size_t)(k + u) * step];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) sum += t[u];
+        for (int u = 0; u < 8; ++u) sum += t[u];
+      }
+      for (; k < k1; ++k) sum += p[(size_t)k * step];
     }
-    for (; k < nchunks; ++k) sum += p[(size_t)k * step];
-    if (signs) sum *= (float)signs[(size_t)c * b + v / b];
-    dK[(size_t)c * bb + v] = sum;
+    part[slice][lane] = sum;
+    __syncthreads();
+    if (slice == 0 && i < total) {
+      float tot = part[0][lane];
+#pragma unroll
+      for (int u = 1; u < 8; ++u) tot += part[u][lane];
+      if (signs) tot *= (float)signs[(size_t)c * b + v / b];
+      dK[(size_t)c * bb + v] = tot;
+    }
+    __syncthreads();
   }
 }
 
@@ -181,30 +353,58 @@ void launch_convert(const TS *src, int64_t lds_, TD *dst, int64_t ldd, int64_t n
 
 }  // namespace
 
+// Row chunks per launch: a fused run of three stages has only d / 8 threads per row, so the
+// rows have to supply the parallelism (d = 4096: 2 workgroups x 256 chunks).
 int grad_chunks(int64_t n) {
-  const int64_t c = (n + 31) / 32;
-  return (int)std::max<int64_t>(1, std::min<int64_t>(c, 128));
+  const int64_t c = (n + 7) / 8;
+  return (int)std::max<int64_t>(1, std::min<int64_t>(c, 256));
+}
+
+// Segments of the backward pass: runs of up to three radix-2 stages, single stages otherwise.
+struct GradSegment {
+  int t0, k;
+};
+static std::vector<GradSegment> grad_segments(const harp_plan *plan) {
+  std::vector<GradSegment> seg;
+  const int m = plan->m;
+  int t = 0;
+  while (t < m) {
+    int k = 1;
+    if (plan->radices[t] == 2)
+      while (k < 3 && t + k < m && plan->radices[t + k] == 2) ++k;
+    seg.push_back(GradSegment{t, k});
+    t += k;
+  }
+  return seg;
 }
 
 size_t grad_workspace_bytes(const harp_plan *plan, int64_t n) {
-  int bmax = 2;
+  int bmax = 6;   // a run of three radix-2 stages leaves 3 * (d / 2) * 4 partial values per chunk
   for (int32_t b : plan->radices) bmax = std::max(bmax, (int)b);
   const size_t mat = (size_t)n * (size_t)plan->d * 4;
-  return (size_t)(plan->m + 1) * mat + (size_t)grad_chunks(n) * (size_t)plan->d * bmax * 4;
+  const size_t nseg = grad_segments(plan).size();
+  return (nseg + 1) * mat + (size_t)grad_chunks(n) * (size_t)plan->d * bmax * 4;
 }
 
 harp_status_t launch_grad(const harp_plan *plan, const void *X, int64_t ldx, const void *G,
                           int64_t ldg, int64_t n, harp_dtype_t dt, float *const *dK, void *dX,
                           int64_t lddx, void *ws, hipStream_t st) {
   const std::vector<ColStage> &stages = plan->col[DIR_FWD];
-  const int m = plan->m;
+  const std::vector<GradSegment> seg = grad_segments(plan);
+  const int nseg = (int)seg.size();
   const int64_t d = plan->d;
   const int nchunks = grad_chunks(n);
   const int rows = (int)((n + nchunks - 1) / nchunks);
   const size_t mat = (size_t)n * (size_t)d;
-  float *act = (float *)ws;                 // act[t] = input of stage t, t < m
-  float *g = act + (size_t)m * mat;         // gradient, updated in place
+  float *act = (float *)ws;                 // act[i] = input of segment i
+  float *g = act + (size_t)nseg * mat;      // gradient, updated in place
   float *partial = g + mat;
+  const size_t pstride = (size_t)nchunks * 4 * (size_t)(d / 2);   // one radix-2 stage's partials
+  auto run_of = [&](const GradSegment &sg) {
+    GradRun run;
+    for (int i = 0; i < 3; ++i) run.blocks[i] = stages[sg.t0 + std::min(i, sg.k - 1)].blocks;
+    return run;
+  };
   if (n > 0) {
     if (dt == HARP_BF16) {
       launch_convert((const uint16_t *)X, ldx, act, d, n, d, st);
@@ -213,28 +413,57 @@ harp_status_t launch_grad(const harp_plan *plan, const void *X, int64_t ldx, con
       launch_convert((const float *)X, ldx, act, d, n, d, st);
       launch_convert((const float *)G, ldg, g, d, n, d, st);
     }
-    for (int t = 0; t + 1 < m; ++t) {
-      const ColStage &cs = stages[t];
-      const int D = (int)(d / cs.b);
-#define HARP_GRAD_FWD(BB) \
-  launch_fwd<BB>(act + (size_t)t * mat, act + (size_t)(t + 1) * mat, d, n, rows, nchunks, cs.blocks, D, cs.s, st)
-      HARP_GRAD_SWITCH(cs.b, HARP_GRAD_FWD)
+    for (int i = 0; i + 1 < nseg; ++i) {
+      const ColStage &cs = stages[seg[i].t0];
+      const float *in = act + (size_t)i * mat;
+      float *out = act + (size_t)(i + 1) * mat;
+      if (seg[i].k > 1) {
+        const int nitems = (int)(d >> seg[i].k);
+        const dim3 grid((nitems + kGradThreads - 1) / kGradThreads, nchunks);
+        if (seg[i].k == 3)
+          hipLaunchKernelGGL((harp_grad_fwd_run_kernel<3>), grid, dim3(kGradThreads), 0, st, in, out,
+                             d, n, rows, run_of(seg[i]), nitems, cs.s);
+        else
+          hipLaunchKernelGGL((harp_grad_fwd_run_kernel<2>), grid, dim3(kGradThreads), 0, st, in, out,
+                             d, n, rows, run_of(seg[i]), nitems, cs.s);
+      } else {
+        const int D = (int)(d / cs.b);
+#define HARP_GRAD_FWD(BB) launch_fwd<BB>(in, out, d, n, rows, nchunks, cs.blocks, D, cs.s, st)
+        HARP_GRAD_SWITCH(cs.b, HARP_GRAD_FWD)
 #undef HARP_GRAD_FWD
+      }
     }
   }
-  for (int t = m - 1; t >= 0; --t) {
-    const ColStage &cs = stages[t];
-    const int D = (int)(d / cs.b);
+  for (int i = nseg - 1; i >= 0; --i) {
+    const ColStage &cs = stages[seg[i].t0];
+    const float *in = act + (size_t)i * mat;
     if (n > 0) {
-#define HARP_GRAD_BWD(BB) \
-  launch_bwd<BB>(act + (size_t)t * mat, g, d, n, rows, nchunks, cs.blocks, D, cs.s, partial, st)
-      HARP_GRAD_SWITCH(cs.b, HARP_GRAD_BWD)
+      if (seg[i].k > 1) {
+        const int nitems = (int)(d >> seg[i].k);
+        const dim3 grid((nitems + kGradThreads - 1) / kGradThreads, nchunks);
+        if (seg[i].k == 3)
+          hipLaunchKernelGGL((harp_grad_bwd_run_kernel<3>), grid, dim3(kGradThreads), 0, st, in, g, d,
+                             n, rows, run_of(seg[i]), nitems, cs.s, (int)(d / 2), partial, pstride);
+        else
+          hipLaunchKernelGGL((harp_grad_bwd_run_kernel<2>), grid, dim3(kGradThreads), 0, st, in, g, d,
+                             n, rows, run_of(seg[i]), nitems, cs.s, (int)(d / 2), partial, pstride);
+      } else {
+        const int D = (int)(d / cs.b);
+#define HARP_GRAD_BWD(BB) launch_bwd<BB>(in, g, d, n, rows, nchunks, cs.blocks, D, cs.s, partial, st)
+        HARP_GRAD_SWITCH(cs.b, HARP_GRAD_BWD)
 #undef HARP_GRAD_BWD
+      }
     }
-    const int64_t total = (int64_t)D * cs.b * cs.b;
-    const unsigned gx = (unsigned)std::min<int64_t>((total + kGradThreads - 1) / kGradThreads, 4096);
-    hipLaunchKernelGGL(harp_grad_reduce_kernel, dim3(gx), dim3(kGradThreads), 0, st, partial,
-                       n > 0 ? nchunks : 0, D, cs.b, t == 0 ? plan->dev_signs : nullptr, dK[t]);
+    for (int j = 0; j < seg[i].k; ++j) {
+      const int t = seg[i].t0 + j;
+      const int b = stages[t].b;
+      const int D = (int)(d / b);
+      const int64_t total = (int64_t)D * b * b;
+      const unsigned gx = (unsigned)std::min<int64_t>((total + 31) / 32, 8192);
+      hipLaunchKernelGGL(harp_grad_reduce_kernel, dim3(gx), dim3(kGradThreads), 0, st,
+                         partial + (size_t)j * pstride, n > 0 ? nchunks : 0, D, b,
+                         t == 0 ? plan->dev_signs : nullptr, dK[t]);
+    }
   }
   if (dX && n > 0) {
     if (dt == HARP_BF16) launch_convert(g, d, (uint16_t *)dX, lddx, n, d, st);
