@@ -513,9 +513,60 @@ harp_status_t rotate_impl(const harp_plan_t *pu, const harp_plan_t *pv, Directio
   const std::vector<ColPassHost> &cps = pu->colpass[dir];
   if (!cps.empty()) {
     float *A = (float *)ws;   // [d_out, d_in] float32
+    // plan_V as a split program with one streamed small-radix stage: that stage acts on the
+    // columns and commutes with plan_U's stages, so it rides along with one column pass instead
+    // of taking its own trip through device memory.  Forward: chunk passes of plan_V, then the
+    // column passes; inverse: the column passes, then plan_V's chunk passes.
+    const HostProgram *vhp = pv ? select_program(pv, dir, d_out, nullptr) : nullptr;
+    int fuse = -1;
+    const PassDesc *vp = nullptr;
+    if (vhp && vhp->n_chunk + 1 == vhp->prog.npass && !getenv("HARP_NO_COLROW")) {
+      vp = &vhp->prog.pass[vhp->chunk_first ? vhp->n_chunk : 0];
+      for (int p = (int)cps.size() - 1; p >= 0 && fuse < 0; --p) {
+        const bool first = (p == 0), last = (p + 1 == (int)cps.size());
+        // what this pass reads and writes in the fused order
+        const bool reads_w = (dir == DIR_TRN) && first;
+        const bool writes_out = (dir == DIR_FWD) && last;
+        const void *src = reads_w ? W : (const void *)A;
+        const void *dst = writes_out ? (const void *)Wout : (const void *)A;
+        if (colrow_supported(pu, cps[p].pass, *vp, src, reads_w ? ldw : d_in,
+                             reads_w ? dt : HARP_F32, dst, writes_out ? ldo : d_in,
+                             writes_out ? dt : HARP_F32, d_out, d_in))
+          fuse = p;
+      }
+    }
     const void *src = W;
     int64_t src_ld = ldw;
     harp_dtype_t src_dt = dt;
+    if (fuse >= 0) {
+      const int c0 = vhp->chunk_first ? 0 : 1;
+      if (dir == DIR_FWD) {
+        st = run_chunk_passes(pv, *vhp, c0, c0 + vhp->n_chunk, W, ldw, dt, A, d_in, HARP_F32, d_out, s);
+        if (st != HARP_OK) return st;
+        src = A;
+        src_ld = d_in;
+        src_dt = HARP_F32;
+      }
+      for (size_t p = 0; p < cps.size(); ++p) {
+        const bool to_out = (dir == DIR_FWD) && (p + 1 == cps.size());
+        void *dst = to_out ? Wout : (void *)A;
+        const int64_t dst_ld = to_out ? ldo : d_in;
+        const harp_dtype_t dst_dt = to_out ? dt : HARP_F32;
+        if ((int)p == fuse)
+          st = launch_colrow_pass(pu, cps[p].dev, cps[p].pass, *vp, src, src_ld, src_dt, dst, dst_ld,
+                                  dst_dt, d_out, d_in, s);
+        else
+          st = launch_col_pass(pu, cps[p].dev, cps[p].pass, src, src_ld, src_dt, dst, dst_ld, dst_dt,
+                               d_out, d_in, s);
+        if (st != HARP_OK) return st;
+        src = dst;
+        src_ld = dst_ld;
+        src_dt = dst_dt;
+      }
+      if (dir == DIR_TRN)
+        st = run_chunk_passes(pv, *vhp, c0, c0 + vhp->n_chunk, A, d_in, HARP_F32, Wout, ldo, dt, d_out, s);
+      return st;
+    }
     if (pv) {
       st = apply_dir(pv, dir, W, ldw, dt, A, d_in, HARP_F32, d_out, stream);
       if (st != HARP_OK) return st;

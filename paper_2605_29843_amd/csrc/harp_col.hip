@@ -99,9 +99,11 @@ __device__ __forceinline__ void col_store<uint16_t, false>(uint16_t *p, float2 v
 // One stage of compile-time radix B on the tile.  Wave w takes blocks w, w + 4, ...; block
 // (a, bp), a < P / (B sp), bp < sp, couples tile rows a B sp + r sp + bp; its values sit at
 // prm[(a sp + bp) * BBP ..] (BBP = B * B rounded up to a multiple of 4).
-template <int B>
+// RP = row pitch of the tile in float2, cidx[cc] = this lane's float2 index inside a tile row
+// for each of the NCC column chunks (plain tiles: RP = 64, one chunk, cidx = lane).
+template <int B, int RP, int NCC>
 __device__ __forceinline__ void col_stage(float2 *tile, const float *prm, const ColOp &op, int P,
-                                          int wave, int lane) {
+                                          int wave, const int (&cidx)[NCC]) {
   constexpr int BBP = (B * B + 3) & ~3;
   const int sp = op.sp;
   const int nblk = P / B;
@@ -117,21 +119,24 @@ __device__ __forceinline__ void col_stage(float2 *tile, const float *prm, const 
       const float4 f = *reinterpret_cast<const float4 *>(kb + 4 * q);
       K[4 * q] = f.x; K[4 * q + 1] = f.y; K[4 * q + 2] = f.z; K[4 * q + 3] = f.w;
     }
-    float2 x[B], y[B];
 #pragma unroll
-    for (int r = 0; r < B; ++r) x[r] = tile[(j0 + r * sp) * 64 + lane];
+    for (int cc = 0; cc < NCC; ++cc) {
+      float2 x[B], y[B];
 #pragma unroll
-    for (int r2 = 0; r2 < B; ++r2) {
-      float ax = 0.f, ay = 0.f;
+      for (int r = 0; r < B; ++r) x[r] = tile[(j0 + r * sp) * RP + cidx[cc]];
 #pragma unroll
-      for (int r = 0; r < B; ++r) {
-        ax = fmaf(x[r].x, K[r * B + r2], ax);
-        ay = fmaf(x[r].y, K[r * B + r2], ay);
+      for (int r2 = 0; r2 < B; ++r2) {
+        float ax = 0.f, ay = 0.f;
+#pragma unroll
+        for (int r = 0; r < B; ++r) {
+          ax = fmaf(x[r].x, K[r * B + r2], ax);
+          ay = fmaf(x[r].y, K[r * B + r2], ay);
+        }
+        y[r2] = make_float2(ax, ay);
       }
-      y[r2] = make_float2(ax, ay);
-    }
 #pragma unroll
-    for (int r = 0; r < B; ++r) tile[(j0 + r * sp) * 64 + lane] = y[r];
+      for (int r = 0; r < B; ++r) tile[(j0 + r * sp) * RP + cidx[cc]] = y[r];
+    }
     bp += kColWaves;
     while (bp >= sp) { bp -= sp; ++a; }
   }
@@ -141,9 +146,9 @@ __device__ __forceinline__ void col_stage(float2 *tile, const float *prm, const 
 // Sub-stage i pairs e0 (bit dp clear) with e0 + 2^dp; with e0 = eh 2^(dp+1) + el its block is
 // number (a 2^(K-dp-1) + eh) * (sp 2^dp) + el sp + bp of the stage's P / 2 blocks in the tile.
 // ASC: the sub-stages act on digits 0, 1, .., K-1 in this order, else K-1, .., 0.
-template <int K, bool ASC>
+template <int K, bool ASC, int RP, int NCC>
 __device__ __forceinline__ void col_run2(float2 *tile, const float *prm, const ColOp &op, int P,
-                                         int wave, int lane) {
+                                         int wave, const int (&cidx)[NCC]) {
   constexpr int E = 1 << K;
   const int sp = op.sp;
   const int nitem = P / E;
@@ -163,26 +168,58 @@ __device__ __forceinline__ void col_run2(float2 *tile, const float *prm, const C
         kq[i][p] = *reinterpret_cast<const float4 *>(region + 4 * q);
       }
     }
-    float2 x[E];
 #pragma unroll
-    for (int e = 0; e < E; ++e) x[e] = tile[(j0 + e * sp) * 64 + lane];
+    for (int cc = 0; cc < NCC; ++cc) {
+      float2 x[E];
 #pragma unroll
-    for (int i = 0; i < K; ++i) {
-      const int dp = ASC ? i : K - 1 - i;
+      for (int e = 0; e < E; ++e) x[e] = tile[(j0 + e * sp) * RP + cidx[cc]];
 #pragma unroll
-      for (int p = 0; p < E / 2; ++p) {
-        const int eh = p >> dp, el = p & ((1 << dp) - 1);
-        const int e0 = (eh << (dp + 1)) | el, e1 = e0 | (1 << dp);
-        const float4 k = kq[i][p];   // k00 k01 k10 k11
-        const float2 u = x[e0], v = x[e1];
-        x[e0] = make_float2(fmaf(v.x, k.z, u.x * k.x), fmaf(v.y, k.z, u.y * k.x));
-        x[e1] = make_float2(fmaf(v.x, k.w, u.x * k.y), fmaf(v.y, k.w, u.y * k.y));
+      for (int i = 0; i < K; ++i) {
+        const int dp = ASC ? i : K - 1 - i;
+#pragma unroll
+        for (int p = 0; p < E / 2; ++p) {
+          const int eh = p >> dp, el = p & ((1 << dp) - 1);
+          const int e0 = (eh << (dp + 1)) | el, e1 = e0 | (1 << dp);
+          const float4 k = kq[i][p];   // k00 k01 k10 k11
+          const float2 u = x[e0], v = x[e1];
+          x[e0] = make_float2(fmaf(v.x, k.z, u.x * k.x), fmaf(v.y, k.z, u.y * k.x));
+          x[e1] = make_float2(fmaf(v.x, k.w, u.x * k.y), fmaf(v.y, k.w, u.y * k.y));
+        }
       }
-    }
 #pragma unroll
-    for (int e = 0; e < E; ++e) tile[(j0 + e * sp) * 64 + lane] = x[e];
+      for (int e = 0; e < E; ++e) tile[(j0 + e * sp) * RP + cidx[cc]] = x[e];
+    }
     bp += kColWaves;
     while (bp >= sp) { bp -= sp; ++a; }
+  }
+}
+
+// every step of a pass on the tile in LDS, one barrier after each
+template <int RP, int NCC>
+__device__ __forceinline__ void col_ops(float2 *tile, const float *prm, const ColPass &cp, int wave,
+                                        const int (&cidx)[NCC]) {
+  const int P = cp.P;
+  for (int oi = 0; oi < cp.nops; ++oi) {
+    const ColOp &op = cp.op[oi];
+    const bool asc = op.dp[0] == 0;
+    if (op.k == 3) {
+      if (asc) col_run2<3, true, RP, NCC>(tile, prm, op, P, wave, cidx);
+      else col_run2<3, false, RP, NCC>(tile, prm, op, P, wave, cidx);
+    } else if (op.k == 2) {
+      if (asc) col_run2<2, true, RP, NCC>(tile, prm, op, P, wave, cidx);
+      else col_run2<2, false, RP, NCC>(tile, prm, op, P, wave, cidx);
+    } else {
+      switch (op.b) {
+        case 2: col_stage<2, RP, NCC>(tile, prm, op, P, wave, cidx); break;
+        case 3: col_stage<3, RP, NCC>(tile, prm, op, P, wave, cidx); break;
+        case 4: col_stage<4, RP, NCC>(tile, prm, op, P, wave, cidx); break;
+        case 5: col_stage<5, RP, NCC>(tile, prm, op, P, wave, cidx); break;
+        case 6: col_stage<6, RP, NCC>(tile, prm, op, P, wave, cidx); break;
+        case 7: col_stage<7, RP, NCC>(tile, prm, op, P, wave, cidx); break;
+        default: col_stage<8, RP, NCC>(tile, prm, op, P, wave, cidx); break;
+      }
+    }
+    __syncthreads();
   }
 }
 
@@ -277,28 +314,8 @@ __global__ __launch_bounds__(kColThreads) void harp_col_kernel(
   // the stages on the tile in LDS, then LDS -> device memory
   auto work = [&](unsigned t) __attribute__((always_inline)) {
     const TilePos cur = locate(t);
-    for (int oi = 0; oi < cp.nops; ++oi) {
-      const ColOp &op = cp.op[oi];
-      const bool asc = op.dp[0] == 0;
-      if (op.k == 3) {
-        if (asc) col_run2<3, true>(tile, prm, op, P, wave, lane);
-        else col_run2<3, false>(tile, prm, op, P, wave, lane);
-      } else if (op.k == 2) {
-        if (asc) col_run2<2, true>(tile, prm, op, P, wave, lane);
-        else col_run2<2, false>(tile, prm, op, P, wave, lane);
-      } else {
-        switch (op.b) {
-          case 2: col_stage<2>(tile, prm, op, P, wave, lane); break;
-          case 3: col_stage<3>(tile, prm, op, P, wave, lane); break;
-          case 4: col_stage<4>(tile, prm, op, P, wave, lane); break;
-          case 5: col_stage<5>(tile, prm, op, P, wave, lane); break;
-          case 6: col_stage<6>(tile, prm, op, P, wave, lane); break;
-          case 7: col_stage<7>(tile, prm, op, P, wave, lane); break;
-          default: col_stage<8>(tile, prm, op, P, wave, lane); break;
-        }
-      }
-      __syncthreads();
-    }
+    const int cidx[1] = {lane};
+    col_ops<64, 1>(tile, prm, cp, wave, cidx);
     TO *wp = dst + (cur.row0 + (int64_t)wave * S) * ldd + cur.col;
     const int64_t wstep = (int64_t)kColWaves * S * ldd;
 #pragma unroll
@@ -321,6 +338,137 @@ __global__ __launch_bounds__(kColThreads) void harp_col_kernel(
   }
   __syncthreads();
   work(t1 - 1);
+}
+
+// Column pass fused with ONE stage of the row-side processor (plan_V's streamed stage of radix
+// BV on the top digit: it couples the columns lo + r Sv, r < BV, of a row with block lo, and
+// commutes with every stage of plan_U).  A tile is P rows x BV segments of 32 columns (row
+// pitch BV * 16 float2, two chunks of 64 lanes for BV > 4; lanes past the end of the row
+// mirror its last pair -- same address, same value -- so that no access is conditional).  Tiles
+// of a workgroup share their column position, so a thread keeps the BV x BV block of its column
+// (thread = column j of 32, row group of 8) in registers for the whole launch.  The row stage
+// runs on the LDS copy before the column steps.
+template <typename TI, typename TO, int BV, int NRW>
+__global__ __launch_bounds__(kColThreads, 2) void harp_colrow_kernel(
+    const ColPass *__restrict__ passp, const TI *src, int64_t lds_, TO *dst, int64_t ldd,
+    const float *__restrict__ vparams, int vnq, int Sv, unsigned nrt, unsigned nct, unsigned tpw) {
+  extern __shared__ float2 tile[];   // [P][BV * 16] float2, then the block values of the column steps
+  constexpr int RP = BV * 16, NCC = (RP + 63) / 64;
+  const ColPass &cp = *passp;
+  const int lane = (int)threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+  const int P = cp.P, S = cp.S;   // P == 4 * NRW
+
+  // Workgroup -> (column position ct, tpw consecutive row tiles).  Consecutive workgroups take
+  // consecutive column positions, so the 128-byte pieces that are in flight at the same time
+  // are neighbours in memory; tiles are numbered t = ct * nrt + rt inside the kernel.
+  const unsigned ct = blockIdx.x % nct;
+  const unsigned t0 = ct * nrt + (blockIdx.x / nct) * tpw;
+  const int c0 = (int)ct * 32;
+  int cidx[NCC];
+  int64_t gcol[NCC];
+#pragma unroll
+  for (int cc = 0; cc < NCC; ++cc) {
+    const int i = cc * 64 + lane;
+    cidx[cc] = i < RP ? i : RP - 1;
+    gcol[cc] = (int64_t)(cidx[cc] / 16) * Sv + c0 + 2 * (cidx[cc] % 16);
+  }
+  // block of the row stage for column c0 + j (value v of block q at vparams[v * vnq + q])
+  const int j = (int)threadIdx.x & 31, rg = (int)threadIdx.x >> 5;
+  float Kv[BV * BV];
+#pragma unroll
+  for (int v = 0; v < BV * BV; ++v) Kv[v] = vparams[(size_t)v * vnq + c0 + j];
+
+  float *prm = reinterpret_cast<float *>(tile + P * RP);
+  typedef const __attribute__((address_space(1))) float *gfloat_t;
+  typedef const __attribute__((address_space(1))) uint32_t *gtab_t;
+  gfloat_t image = (gfloat_t)cp.image;
+  gtab_t ptab = (gtab_t)cp.ptab;
+  const int npar = cp.npar;
+  unsigned dfix[kColParPerThread], dfa[kColParPerThread], dfb[kColParPerThread];
+#pragma unroll
+  for (int k = 0; k < kColParPerThread; ++k) {
+    const int e = (int)threadIdx.x + kColThreads * k;
+    const bool ok = e < npar;
+    const unsigned fa = ok ? ptab[npar + e] : 0xffffffffu;
+    const bool real = fa != 0xffffffffu;
+    dfix[k] = real ? ptab[e] : 0u;
+    dfa[k] = real ? fa : 0u;
+    dfb[k] = real ? ptab[2 * npar + e] : 0u;
+  }
+  float ppre[kColParPerThread];
+  ColRaw<TI> pre[NRW][NCC];
+
+  auto request = [&](unsigned t) __attribute__((always_inline)) {
+    const unsigned rt = t % nrt;
+    const int hi = (int)(rt / (unsigned)S), lo = (int)(rt % (unsigned)S);
+    const int64_t row0 = (int64_t)hi * P * S + lo;
+#pragma unroll
+    for (int k = 0; k < kColParPerThread; ++k)
+      ppre[k] = image[dfix[k] + (unsigned)hi * dfa[k] + (unsigned)lo * dfb[k]];
+    const TI *rp = src + (row0 + (int64_t)wave * S) * lds_;
+    const int64_t step = (int64_t)kColWaves * S * lds_;
+#pragma unroll
+    for (int u = 0; u < NRW; ++u) {
+#pragma unroll
+      for (int cc = 0; cc < NCC; ++cc) col_load<TI, true>(pre[u][cc], rp + gcol[cc], true, true);
+      rp += step;
+    }
+  };
+  float2 *tp0 = tile + wave * RP;
+  auto to_lds = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int u = 0; u < NRW; ++u)
+#pragma unroll
+      for (int cc = 0; cc < NCC; ++cc)
+        tp0[u * (kColWaves * RP) + cidx[cc]] = col_widen<true>(pre[u][cc]);
+#pragma unroll
+    for (int k = 0; k < kColParPerThread; ++k) prm[(int)threadIdx.x + kColThreads * k] = ppre[k];
+  };
+  auto work = [&](unsigned t) __attribute__((always_inline)) {
+    // row stage: rows rg, rg + 8, ...; column j of every segment
+    float *tf = reinterpret_cast<float *>(tile);
+    for (int row = rg; row < P; row += 8) {
+      float *rowp = tf + row * (2 * RP) + j;
+      float x[BV], y[BV];
+#pragma unroll
+      for (int r = 0; r < BV; ++r) x[r] = rowp[r * 32];
+#pragma unroll
+      for (int r2 = 0; r2 < BV; ++r2) {
+        float acc = 0.f;
+#pragma unroll
+        for (int r = 0; r < BV; ++r) acc = fmaf(x[r], Kv[r * BV + r2], acc);
+        y[r2] = acc;
+      }
+#pragma unroll
+      for (int r = 0; r < BV; ++r) rowp[r * 32] = y[r];
+    }
+    __syncthreads();
+    col_ops<RP, NCC>(tile, prm, cp, wave, cidx);
+    const unsigned rt = t % nrt;
+    const int hi = (int)(rt / (unsigned)S), lo = (int)(rt % (unsigned)S);
+    const int64_t row0 = (int64_t)hi * P * S + lo;
+    TO *wp = dst + (row0 + (int64_t)wave * S) * ldd;
+    const int64_t wstep = (int64_t)kColWaves * S * ldd;
+#pragma unroll
+    for (int u = 0; u < NRW; ++u) {
+#pragma unroll
+      for (int cc = 0; cc < NCC; ++cc)
+        col_store<TO, true>(wp + gcol[cc], tp0[u * (kColWaves * RP) + cidx[cc]], true, true);
+      wp += wstep;
+    }
+  };
+  request(t0);
+  to_lds();
+  for (unsigned t = t0; t + 1 < t0 + tpw; ++t) {
+    __syncthreads();
+    request(t + 1);
+    work(t);
+    __syncthreads();
+    to_lds();
+  }
+  __syncthreads();
+  work(t0 + tpw - 1);
 }
 
 template <typename TI, typename TO>
@@ -380,6 +528,56 @@ harp_status_t launch_col_typed(const harp_plan *plan, const ColPass *dpass, cons
     st = launch_col_tiles<TI, TO>(plan, dpass, hp, (const TI *)src + full, lds_, (TO *)dst + full,
                                   ldd, nrows, ncols - full, vec, false, stream);
   return st;
+}
+
+template <typename TI, typename TO, int BV>
+harp_status_t launch_colrow_bv(const harp_plan *plan, const ColPass *dpass, const ColPass &hp,
+                               const PassDesc &vp, const TI *src, int64_t lds_, TO *dst,
+                               int64_t ldd, int64_t nrows, int64_t ncols, hipStream_t stream) {
+  constexpr int RP = BV * 16;
+  const int64_t nrt = nrows / hp.P, nct = vp.S / 32;
+  const size_t shmem = (size_t)hp.P * RP * sizeof(float2) + (size_t)kColMaxPar * sizeof(float);
+  if (shmem > (size_t)plan->lds_bytes) return HARP_ERR_UNSUPPORTED;
+  int64_t tpw = 1;
+  for (int64_t c = 16; c >= 1; --c)
+    if (nrt % c == 0) { tpw = c; break; }
+  const int64_t grid = (nrt / tpw) * nct;
+  if (grid <= 0 || grid > 0x7fffffff) return HARP_ERR_UNSUPPORTED;
+  typedef void (*kern_t)(const ColPass *, const TI *, int64_t, TO *, int64_t, const float *, int, int,
+                         unsigned, unsigned, unsigned);
+  const kern_t kern = hp.P == 64 ? (kern_t)harp_colrow_kernel<TI, TO, BV, 16>
+                                 : (kern_t)harp_colrow_kernel<TI, TO, BV, 8>;
+  static thread_local int attr_done_dev[2] = {-1, -1};   // per instantiation
+  const int which = hp.P == 64 ? 0 : 1;
+  if (attr_done_dev[which] != plan->device) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                            hipFuncAttributeMaxDynamicSharedMemorySize,
+                            plan->lds_bytes) != hipSuccess) {
+      (void)hipGetLastError();
+      return HARP_ERR_DEVICE;
+    }
+    attr_done_dev[which] = plan->device;
+  }
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kColThreads), shmem, stream, dpass, src, lds_,
+                     dst, ldd, vp.params, (int)vp.nq, (int)vp.S, (unsigned)nrt, (unsigned)nct,
+                     (unsigned)tpw);
+  (void)ncols;
+  return hipGetLastError() == hipSuccess ? HARP_OK : HARP_ERR_DEVICE;
+}
+
+template <typename TI, typename TO>
+harp_status_t launch_colrow_typed(const harp_plan *plan, const ColPass *dpass, const ColPass &hp,
+                                  const PassDesc &vp, const void *src, int64_t lds_, void *dst,
+                                  int64_t ldd, int64_t nrows, int64_t ncols, hipStream_t stream) {
+  switch (vp.b) {
+    case 3: return launch_colrow_bv<TI, TO, 3>(plan, dpass, hp, vp, (const TI *)src, lds_, (TO *)dst, ldd, nrows, ncols, stream);
+    case 4: return launch_colrow_bv<TI, TO, 4>(plan, dpass, hp, vp, (const TI *)src, lds_, (TO *)dst, ldd, nrows, ncols, stream);
+    case 5: return launch_colrow_bv<TI, TO, 5>(plan, dpass, hp, vp, (const TI *)src, lds_, (TO *)dst, ldd, nrows, ncols, stream);
+    case 6: return launch_colrow_bv<TI, TO, 6>(plan, dpass, hp, vp, (const TI *)src, lds_, (TO *)dst, ldd, nrows, ncols, stream);
+    case 7: return launch_colrow_bv<TI, TO, 7>(plan, dpass, hp, vp, (const TI *)src, lds_, (TO *)dst, ldd, nrows, ncols, stream);
+    case 8: return launch_colrow_bv<TI, TO, 8>(plan, dpass, hp, vp, (const TI *)src, lds_, (TO *)dst, ldd, nrows, ncols, stream);
+    default: return HARP_ERR_UNSUPPORTED;
+  }
 }
 
 }  // namespace
@@ -480,6 +678,36 @@ harp_status_t launch_col_pass(const harp_plan *plan, const ColPass *dpass, const
   if (dt_src == HARP_F32 && dt_dst == HARP_BF16)
     return launch_col_typed<float, uint16_t>(plan, dpass, hp, src, lds_, dst, ldd, nrows, ncols, stream);
   return launch_col_typed<uint16_t, uint16_t>(plan, dpass, hp, src, lds_, dst, ldd, nrows, ncols, stream);
+}
+
+// The fused launch applies when: the column pass has exactly 32 or 64 rows per tile; the row
+// stage is a dense small-radix stage (3..8) on the top digit of a processor on ncols coordinates
+// whose stride is a multiple of 32; pairs of columns are aligned in both matrices.
+bool colrow_supported(const harp_plan *plan, const ColPass &hp, const PassDesc &vp, const void *src,
+                      int64_t lds_, harp_dtype_t dt_src, const void *dst, int64_t ldd,
+                      harp_dtype_t dt_dst, int64_t nrows, int64_t ncols) {
+  if (hp.P != 64 && hp.P != 32) return false;
+  if (hp.P == 64 && vp.b == 8) return false;   // would not fit 256 vector registers
+  if (nrows % hp.P != 0) return false;
+  if (vp.kind != PASS_SMALL || vp.b < 3 || vp.b > 8) return false;
+  if ((int64_t)vp.b * vp.S != ncols || vp.nq != vp.S || vp.S % 32 != 0) return false;
+  const size_t ei = dt_src == HARP_BF16 ? 2 : 4, eo = dt_dst == HARP_BF16 ? 2 : 4;
+  if (lds_ % 2 || ldd % 2 || (uintptr_t)src % (2 * ei) || (uintptr_t)dst % (2 * eo)) return false;
+  const size_t shmem = (size_t)hp.P * vp.b * 16 * sizeof(float2) + (size_t)kColMaxPar * sizeof(float);
+  return shmem <= (size_t)plan->lds_bytes;
+}
+
+harp_status_t launch_colrow_pass(const harp_plan *plan, const ColPass *dpass, const ColPass &hp,
+                                 const PassDesc &vp, const void *src, int64_t lds_,
+                                 harp_dtype_t dt_src, void *dst, int64_t ldd, harp_dtype_t dt_dst,
+                                 int64_t nrows, int64_t ncols, hipStream_t stream) {
+  if (dt_src == HARP_F32 && dt_dst == HARP_F32)
+    return launch_colrow_typed<float, float>(plan, dpass, hp, vp, src, lds_, dst, ldd, nrows, ncols, stream);
+  if (dt_src == HARP_BF16 && dt_dst == HARP_F32)
+    return launch_colrow_typed<uint16_t, float>(plan, dpass, hp, vp, src, lds_, dst, ldd, nrows, ncols, stream);
+  if (dt_src == HARP_F32 && dt_dst == HARP_BF16)
+    return launch_colrow_typed<float, uint16_t>(plan, dpass, hp, vp, src, lds_, dst, ldd, nrows, ncols, stream);
+  return launch_colrow_typed<uint16_t, uint16_t>(plan, dpass, hp, vp, src, lds_, dst, ldd, nrows, ncols, stream);
 }
 
 }  // namespace harp

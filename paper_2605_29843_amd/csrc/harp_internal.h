@@ -198,6 +198,14 @@ harp_status_t launch_col_pass(const harp_plan *plan, const ColPass *dpass, const
                               int64_t lds_, harp_dtype_t dt_src, void *dst, int64_t ldd,
                               harp_dtype_t dt_dst, int64_t nrows, int64_t ncols,
                               hipStream_t stream);
+// column pass fused with the row-side processor's streamed small-radix stage (harp_col.hip)
+bool colrow_supported(const harp_plan *plan, const ColPass &hp, const PassDesc &vp, const void *src,
+                      int64_t lds_, harp_dtype_t dt_src, const void *dst, int64_t ldd,
+                      harp_dtype_t dt_dst, int64_t nrows, int64_t ncols);
+harp_status_t launch_colrow_pass(const harp_plan *plan, const ColPass *dpass, const ColPass &hp,
+                                 const PassDesc &vp, const void *src, int64_t lds_,
+                                 harp_dtype_t dt_src, void *dst, int64_t ldd, harp_dtype_t dt_dst,
+                                 int64_t nrows, int64_t ncols, hipStream_t stream);
 // gradient with respect to the blocks (harp_grad.hip); needs plan->col[DIR_FWD]
 size_t grad_workspace_bytes(const harp_plan *plan, int64_t n);
 harp_status_t launch_grad(const harp_plan *plan, const void *X, int64_t ldx, const void *G,

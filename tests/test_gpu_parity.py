@@ -694,6 +694,51 @@ def test_rotate_weight_views_with_padding_and_odd_offsets(harp, dtype):
     pv.destroy()
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("do,ru,di,rv", [
+    (64, [2] * 6, 12288, [2] * 12 + [3]),            # one column pass of 64 rows, radix-3 row stage
+    (32, [4, 8], 20480, [2] * 12 + [5]),             # 32 rows, radix 5
+    (4096, [2] * 12, 28672, [2] * 12 + [7]),         # two column passes (128 + 32 rows), radix 7
+    (192, [3, 8, 8], 8192 * 3, [2] * 13 + [3])])     # passes of 24 and 8 rows: not fusable
+def test_rotate_weight_with_streamed_row_stage(harp, dtype, do, ru, di, rv):
+    """plan_V longer than one on-chip chunk with a small-radix top stage: that stage is executed
+    inside one of plan_U's column passes.  Rows of the result are recomputed by the oracle."""
+    import torch
+    rng = np.random.default_rng(do + di)
+    bu, bv = gi.make_blocks(do, ru, "orth", rng), gi.make_blocks(di, rv, "orth", rng)
+    su, sv = gi.make_signs(do, rng), gi.make_signs(di, rng)
+    W = (rng.standard_normal((do, di)) * 0.1).astype(np.float32)
+    if dtype == "bf16":
+        W = gi.round_to_bf16(W)
+    pu, pv = harp.Plan(do, ru, bu, su), harp.Plan(di, rv, bv, sv)
+    say("rotate_weight with streamed row stage", do, di, dtype)
+    Wd = to_device(W, dtype)
+    out = harp.harp_rotate_weight(pu, pv, Wd)
+    inv = harp.harp_rotate_weight_inverse(pu, pv, Wd)
+    torch.cuda.synchronize()
+    rows = sorted(set([0, 1, do // 3, do - 1]))
+    E = np.zeros((len(rows), do))
+    E[np.arange(len(rows)), rows] = 1.0
+    W64 = W.astype(np.float64)
+    # row i of U^T W V = (e_i U^T) W V;  row i of U W V^T = (e_i U) W V^T
+    ref = ho.apply_staged(ho.apply_transpose_staged(E, do, ru, bu, su) @ W64, di, rv, bv, sv)
+    refi = ho.apply_transpose_staged(ho.apply_staged(E, do, ru, bu, su) @ W64, di, rv, bv, sv)
+    idx = torch.tensor(rows).cuda()
+    assert_parity(to_host64(out[idx]), ref, dtype, "U^T W V rows")
+    assert_parity(to_host64(inv[idx]), refi, dtype, "U W V^T rows")
+    # in place, and round trip back to W
+    W2 = Wd.clone()
+    harp.harp_rotate_weight(pu, pv, W2, W2)
+    torch.cuda.synchronize()
+    assert torch.equal(W2, out)
+    back = harp.harp_rotate_weight_inverse(pu, pv, out)
+    torch.cuda.synchronize()
+    err = float((back.float() - Wd.float()).abs().max()) / float(Wd.float().abs().max())
+    assert err < (2e-2 if dtype == "bf16" else 1e-4), err
+    pu.destroy()
+    pv.destroy()
+
+
 def test_rotate_weight_llama70b_shape_sampled(harp):
     """W 8192 x 28672 bf16: rows of U^T W V recomputed one by one by the oracle."""
     import torch
