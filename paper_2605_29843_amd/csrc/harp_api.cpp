@@ -442,8 +442,7 @@ harp_status_t apply_dir(const harp_plan_t *plan, Direction dir, const void *X, i
   // through a float32 intermediate Z.  Rows are processed in slabs so that Z stays small
   // (it is written by one launch and read by the next: cache resident).
   const int64_t d = plan->d;
-  const char *slab_env = getenv("HARP_SLAB_MB");
-  const int64_t slab_mb = (slab_env && *slab_env) ? atoi(slab_env) : 128;
+  const int64_t slab_mb = 128;   // measured optimum of 32 .. 512 MB on the 14336 / 28672 shapes
   int64_t slab = (slab_mb << 20) / (d * 4);
   if (slab >= 512) slab = (slab / 256) * 256;
   if (slab < 1) slab = 1;
@@ -520,7 +519,7 @@ harp_status_t rotate_impl(const harp_plan_t *pu, const harp_plan_t *pv, Directio
     const HostProgram *vhp = pv ? select_program(pv, dir, d_out, nullptr) : nullptr;
     int fuse = -1;
     const PassDesc *vp = nullptr;
-    if (vhp && vhp->n_chunk + 1 == vhp->prog.npass && !getenv("HARP_NO_COLROW")) {
+    if (vhp && vhp->n_chunk + 1 == vhp->prog.npass) {
       vp = &vhp->prog.pass[vhp->chunk_first ? vhp->n_chunk : 0];
       for (int p = (int)cps.size() - 1; p >= 0 && fuse < 0; --p) {
         const bool first = (p == 0), last = (p + 1 == (int)cps.size());

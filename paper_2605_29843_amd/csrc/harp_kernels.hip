@@ -508,7 +508,7 @@ struct StreamGrid {
 StreamGrid stream_grid(int items, const harp_plan *plan, int64_t n) {
   const unsigned gx = (unsigned)((items + 255) / 256);
   // about 8 workgroups per compute unit (occupancy hides the load latency), >= 4 rows each
-  const int wgs = env_int("HARP_STREAM_WGS_PER_CU", 8), minrows = env_int("HARP_STREAM_MIN_ROWS", 4);
+  const int wgs = 8, minrows = 4;
   int64_t gy = ((int64_t)plan->num_cu * wgs + gx - 1) / gx;
   if (gy > (n + minrows - 1) / minrows) gy = (n + minrows - 1) / minrows;
   if (gy < 1) gy = 1;
@@ -732,12 +732,9 @@ LaunchCfg choose_launch(const harp_plan *plan, int64_t d, int64_t n) {
     while (R > 1 && (n + R - 1) / R < plan->num_cu) R = (R + 1) / 2;
   }
   cfg.rows_per_tile = R;
-  int nt = env_int("HARP_THREADS", 0);
-  if (nt <= 0) {
-    const int64_t work = (int64_t)R * d / 16;
-    nt = 256;
-    while (nt < 512 && nt < work) nt *= 2;
-  }
+  const int64_t work = (int64_t)R * d / 16;
+  int nt = 256;
+  while (nt < 512 && nt < work) nt *= 2;
   if (nt < 64) nt = 64;
   if (nt > 512) nt = 512;
   nt = (nt / 64) * 64;
