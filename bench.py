@@ -78,6 +78,9 @@ def main():
     ap.add_argument("--rows", type=int, default=None, help="override n (default: the workload's)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--extra", action="store_true", help="also time the other shapes (stderr)")
+    ap.add_argument("--decode", action="store_true",
+                    help="also time the decode regime (n = 1..64 rows; stderr): median of 1000 "
+                         "launches and the per-launch time of a HIP graph of 20 launches")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also launch the library's plain copy kernel on one batch (known bytes), "
                          "the reference that scales rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
@@ -242,6 +245,51 @@ def main():
                   f"({gb / HBM_PEAK_GBS:.1%})", file=sys.stderr, flush=True)
         except Exception as e:  # noqa: BLE001
             print(f"[extra] grad_blocks: {e}", file=sys.stderr, flush=True)
+    if args.decode:
+        for dd, rr in ((4096, [2] * 12), (12288, [2] * 12 + [3]), (14336, [2] * 11 + [7])):
+            bb, ss = gi.processor(dd, rr, config=4)
+            pd_ = harp.Plan(dd, rr, bb, ss)
+            for nn in (1, 8, 32, 64):
+                Xd = torch.randn(nn, dd, device="cuda").to(torch.bfloat16)
+                Yd = torch.empty_like(Xd)
+                for _ in range(20):
+                    harp.harp_apply(pd_, Xd, Yd, stream)
+                torch.cuda.synchronize()
+                evs = [torch.cuda.Event(enable_timing=True) for _ in range(1001)]
+                evs[0].record(stream)
+                for i in range(1000):
+                    harp.harp_apply(pd_, Xd, Yd, stream)
+                    evs[i + 1].record(stream)
+                torch.cuda.synchronize()
+                med = float(np.median([evs[i].elapsed_time(evs[i + 1]) for i in range(1000)])) * 1e3
+                tg = float("nan")
+                try:
+                    side = torch.cuda.Stream()
+                    side.wait_stream(stream)
+                    with torch.cuda.stream(side):
+                        harp.harp_apply(pd_, Xd, Yd, side)    # warms the plan's intermediate on it
+                    stream.wait_stream(side)
+                    g = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(g, stream=side):      # capture on the warmed stream
+                        for _ in range(20):
+                            harp.harp_apply(pd_, Xd, Yd, side)
+                    for _ in range(5):
+                        g.replay()
+                    torch.cuda.synchronize()
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    for _ in range(50):
+                        g.replay()
+                    e1.record()
+                    torch.cuda.synchronize()
+                    tg = e0.elapsed_time(e1) * 1e3 / (50 * 20)
+                except Exception as e:  # noqa: BLE001
+                    print(f"[decode] graph capture failed: {str(e)[:100]}", file=sys.stderr, flush=True)
+                byt = nn * dd * 4 + pd_.param_bytes()      # parameters dominate at these sizes
+                print(f"[decode] d={dd} n={nn} {pd_.kernel_name(nn)}: median {med:.2f} us/call "
+                      f"({byt / (med * 1e-6) / 1e9:.0f} GB/s incl. parameters), "
+                      f"in a HIP graph {tg:.2f} us/launch", file=sys.stderr, flush=True)
+            pd_.destroy()
     print(json.dumps(out), flush=True)
 
 
