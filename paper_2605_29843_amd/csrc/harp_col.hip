@@ -1,6 +1,6 @@
 // Column-mode passes: the stages of a processor applied along the ROW index of a row-major
 // matrix, M <- U^T M (or U M), without transposing it (two-sided weight rotation W~ = U^T W V,
-// Section 3.1; stage arithmetic of Algorithm 1 with the matrix row as the coordinate).
+// Sec. 2; stage arithmetic of Algorithm 1 with the matrix row as the coordinate).
 //
 // Stage t couples rows i = alpha b s + r s + beta, r < b, of EVERY column with the same block
 // K_t[alpha s + beta], so along a row the work is perfectly coalesced and a block's b*b values
