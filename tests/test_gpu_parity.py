@@ -434,6 +434,46 @@ def test_graph_capture_and_replay(harp, d, radices, n):
     plan.destroy()
 
 
+def test_one_plan_on_two_streams_and_two_host_threads(harp):
+    """A plan is immutable after create: two host threads drive it on two streams at the same
+    time (a split program, whose float32 intermediate is kept per stream) and both reproduce the
+    single-stream result bit for bit."""
+    import threading
+    import torch
+    d, radices, n = 14336, [2] * 11 + [7], 300
+    rng = np.random.default_rng(8)
+    plan = harp.Plan(d, radices, gi.make_blocks(d, radices, "orth", rng), gi.make_signs(d, rng))
+    Xs = [to_device(gi.round_to_bf16(rng.standard_normal((n, d)).astype(np.float32)), "bf16") for _ in range(2)]
+    ref = [harp.harp_apply(plan, x).clone() for x in Xs]
+    reft = [harp.harp_apply_transpose(plan, x).clone() for x in Xs]
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    outs = [[torch.zeros_like(Xs[i]), torch.zeros_like(Xs[i])] for i in range(2)]
+    torch.cuda.synchronize()
+    errors = []
+
+    def worker(i):
+        try:
+            for rep in range(20):
+                harp.harp_apply(plan, Xs[i], outs[i][0], stream=streams[i])
+                harp.harp_apply_transpose(plan, Xs[i], outs[i][1], stream=streams[i])
+            streams[i].synchronize()
+        except Exception as e:  # noqa: BLE001
+            errors.append(e)
+
+    say("two streams, two host threads")
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for i in range(2):
+        assert torch.equal(outs[i][0], ref[i]) and torch.equal(outs[i][1], reft[i])
+    plan.destroy()
+
+
 def test_plan_from_theta_zero_is_the_randomized_hadamard_transform(harp):
     """Theta = 0, Hadamard mixers, power-of-two schedule: apply(x) = (x * sigma) H_d / sqrt(d),
     checked against scipy's Sylvester matrix, not against the staged oracle."""
