@@ -151,7 +151,7 @@ __device__ __forceinline__ void grad_run_blocks(const GradRun &run, int base, in
 template <int K>
 __global__ __launch_bounds__(kGradThreads) void harp_grad_fwd_run_kernel(
     const float *__restrict__ X, float *__restrict__ Y, int64_t ld, int64_t n, int rows,
-    GradRun run, int nitems, int s) {
+    GradRun run, int nitems, int s, int aligned) {
   constexpr int E = 1 << K, H = E / 2;
   const int q = blockIdx.x * kGradThreads + threadIdx.x;
   if (q >= nitems) return;
@@ -162,19 +162,30 @@ __global__ __launch_bounds__(kGradThreads) void harp_grad_fwd_run_kernel(
   const int64_t r0 = (int64_t)blockIdx.y * rows;
   const int64_t r1 = (r0 + rows < n) ? r0 + rows : n;
   // the next row is requested before the work on the current one
+  // stride 1: the item's coordinates are contiguous (16-byte accesses when the row allows it)
+  const bool vec = aligned && (s == 1) && (E % 4 == 0) && (ld % 4 == 0);
+  auto load_item = [&](const float *x, float (&v)[E]) {
+    if (vec) {
+#pragma unroll
+      for (int q = 0; q < E / 4; ++q) {
+        const float4 f = *reinterpret_cast<const float4 *>(x + 4 * q);
+        v[4 * q] = f.x; v[4 * q + 1] = f.y; v[4 * q + 2] = f.z; v[4 * q + 3] = f.w;
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < E; ++e) v[e] = x[(size_t)e * s];
+    }
+  };
   float nx[E];
 #pragma unroll
-  for (int e = 0; e < E; ++e) nx[e] = (r0 < r1) ? X[r0 * ld + base + (size_t)e * s] : 0.f;
+  for (int e = 0; e < E; ++e) nx[e] = 0.f;
+  if (r0 < r1) load_item(X + r0 * ld + base, nx);
   for (int64_t row = r0; row < r1; ++row) {
     float *y = Y + row * ld + base;
     float v[E];
 #pragma unroll
     for (int e = 0; e < E; ++e) v[e] = nx[e];
-    if (row + 1 < r1) {
-      const float *x = X + (row + 1) * ld + base;
-#pragma unroll
-      for (int e = 0; e < E; ++e) nx[e] = x[(size_t)e * s];
-    }
+    if (row + 1 < r1) load_item(X + (row + 1) * ld + base, nx);
 #pragma unroll
     for (int i = 0; i < K; ++i)
 #pragma unroll
@@ -185,8 +196,14 @@ __global__ __launch_bounds__(kGradThreads) void harp_grad_fwd_run_kernel(
         v[e0] = fmaf(b, kv[i][p][2], a * kv[i][p][0]);
         v[e1] = fmaf(b, kv[i][p][3], a * kv[i][p][1]);
       }
+    if (vec) {
 #pragma unroll
-    for (int e = 0; e < E; ++e) y[(size_t)e * s] = v[e];
+      for (int q = 0; q < E / 4; ++q)
+        *reinterpret_cast<float4 *>(y + 4 * q) = make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
+    } else {
+#pragma unroll
+      for (int e = 0; e < E; ++e) y[(size_t)e * s] = v[e];
+    }
   }
 }
 
@@ -194,7 +211,8 @@ __global__ __launch_bounds__(kGradThreads) void harp_grad_fwd_run_kernel(
 template <int K>
 __global__ __launch_bounds__(kGradThreads) void harp_grad_bwd_run_kernel(
     const float *__restrict__ X, float *__restrict__ Gm, int64_t ld, int64_t n, int rows,
-    GradRun run, int nitems, int s, int D, float *__restrict__ partial, size_t pstride) {
+    GradRun run, int nitems, int s, int D, float *__restrict__ partial, size_t pstride,
+    int aligned) {
   constexpr int E = 1 << K, H = E / 2;
   const int q = blockIdx.x * kGradThreads + threadIdx.x;
   if (q >= nitems) return;
@@ -210,11 +228,25 @@ __global__ __launch_bounds__(kGradThreads) void harp_grad_bwd_run_kernel(
       for (int w = 0; w < 4; ++w) acc[i][p][w] = 0.f;
   const int64_t r0 = (int64_t)blockIdx.y * rows;
   const int64_t r1 = (r0 + rows < n) ? r0 + rows : n;
+  const bool vec = aligned && (s == 1) && (E % 4 == 0) && (ld % 4 == 0);
+  auto load_item = [&](const float *x, float (&v)[E]) {
+    if (vec) {
+#pragma unroll
+      for (int q = 0; q < E / 4; ++q) {
+        const float4 f = *reinterpret_cast<const float4 *>(x + 4 * q);
+        v[4 * q] = f.x; v[4 * q + 1] = f.y; v[4 * q + 2] = f.z; v[4 * q + 3] = f.w;
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < E; ++e) v[e] = x[(size_t)e * s];
+    }
+  };
   float nx[E], ng[E];
 #pragma unroll
-  for (int e = 0; e < E; ++e) {
-    nx[e] = (r0 < r1) ? X[r0 * ld + base + (size_t)e * s] : 0.f;
-    ng[e] = (r0 < r1) ? Gm[r0 * ld + base + (size_t)e * s] : 0.f;
+  for (int e = 0; e < E; ++e) nx[e] = ng[e] = 0.f;
+  if (r0 < r1) {
+    load_item(X + r0 * ld + base, nx);
+    load_item(Gm + r0 * ld + base, ng);
   }
   for (int64_t row = r0; row < r1; ++row) {
     float *g = Gm + row * ld + base;
@@ -225,13 +257,8 @@ __global__ __launch_bounds__(kGradThreads) void harp_grad_bwd_run_kernel(
       gv[e] = ng[e];
     }
     if (row + 1 < r1) {   // the next row (its g is not written by anyone before this thread does)
-      const float *x = X + (row + 1) * ld + base;
-      const float *gn = Gm + (row + 1) * ld + base;
-#pragma unroll
-      for (int e = 0; e < E; ++e) {
-        nx[e] = x[(size_t)e * s];
-        ng[e] = gn[(size_t)e * s];
-      }
+      load_item(X + (row + 1) * ld + base, nx);
+      load_item(Gm + (row + 1) * ld + base, ng);
     }
     // inputs of the inner stages, recomputed
 #pragma unroll
@@ -260,8 +287,15 @@ __global__ __launch_bounds__(kGradThreads) void harp_grad_bwd_run_kernel(
         gv[e1] = fmaf(g1, kv[i][p][3], g0 * kv[i][p][2]);
       }
     }
+    if (vec) {
 #pragma unroll
-    for (int e = 0; e < E; ++e) g[(size_t)e * s] = gv[e];
+      for (int q = 0; q < E / 4; ++q)
+        *reinterpret_cast<float4 *>(g + 4 * q) =
+            make_float4(gv[4 * q], gv[4 * q + 1], gv[4 * q + 2], gv[4 * q + 3]);
+    } else {
+#pragma unroll
+      for (int e = 0; e < E; ++e) g[(size_t)e * s] = gv[e];
+    }
   }
 #pragma unroll
   for (int i = 0; i < K; ++i)
@@ -400,6 +434,8 @@ harp_status_t launch_grad(const harp_plan *plan, const void *X, int64_t ldx, con
   float *g = act + (size_t)nseg * mat;      // gradient, updated in place
   float *partial = g + mat;
   const size_t pstride = (size_t)nchunks * 4 * (size_t)(d / 2);   // one radix-2 stage's partials
+  // 16-byte accesses of the stride-1 runs need the float32 copies on 16-byte boundaries
+  const int aligned = ((uintptr_t)ws % 16 == 0) && (mat % 4 == 0);
   auto run_of = [&](const GradSegment &sg) {
     GradRun run;
     for (int i = 0; i < 3; ++i) run.blocks[i] = stages[sg.t0 + std::min(i, sg.k - 1)].blocks;
@@ -422,10 +458,10 @@ harp_status_t launch_grad(const harp_plan *plan, const void *X, int64_t ldx, con
         const dim3 grid((nitems + kGradThreads - 1) / kGradThreads, nchunks);
         if (seg[i].k == 3)
           hipLaunchKernelGGL((harp_grad_fwd_run_kernel<3>), grid, dim3(kGradThreads), 0, st, in, out,
-                             d, n, rows, run_of(seg[i]), nitems, cs.s);
+                             d, n, rows, run_of(seg[i]), nitems, cs.s, aligned);
         else
           hipLaunchKernelGGL((harp_grad_fwd_run_kernel<2>), grid, dim3(kGradThreads), 0, st, in, out,
-                             d, n, rows, run_of(seg[i]), nitems, cs.s);
+                             d, n, rows, run_of(seg[i]), nitems, cs.s, aligned);
       } else {
         const int D = (int)(d / cs.b);
 #define HARP_GRAD_FWD(BB) launch_fwd<BB>(in, out, d, n, rows, nchunks, cs.blocks, D, cs.s, st)
@@ -443,10 +479,10 @@ harp_status_t launch_grad(const harp_plan *plan, const void *X, int64_t ldx, con
         const dim3 grid((nitems + kGradThreads - 1) / kGradThreads, nchunks);
         if (seg[i].k == 3)
           hipLaunchKernelGGL((harp_grad_bwd_run_kernel<3>), grid, dim3(kGradThreads), 0, st, in, g, d,
-                             n, rows, run_of(seg[i]), nitems, cs.s, (int)(d / 2), partial, pstride);
+                             n, rows, run_of(seg[i]), nitems, cs.s, (int)(d / 2), partial, pstride, aligned);
         else
           hipLaunchKernelGGL((harp_grad_bwd_run_kernel<2>), grid, dim3(kGradThreads), 0, st, in, g, d,
-                             n, rows, run_of(seg[i]), nitems, cs.s, (int)(d / 2), partial, pstride);
+                             n, rows, run_of(seg[i]), nitems, cs.s, (int)(d / 2), partial, pstride, aligned);
       } else {
         const int D = (int)(d / cs.b);
 #define HARP_GRAD_BWD(BB) launch_bwd<BB>(in, g, d, n, rows, nchunks, cs.blocks, D, cs.s, partial, st)
