@@ -38,13 +38,45 @@ __device__ __forceinline__ void grad_narrow(float v, uint16_t *p) {
   *p = (uint16_t)(((u & 0x7fffffffu) > 0x7f800000u) ? quiet : rounded);
 }
 
-// dst[r, c] = convert(src[r, c])
-template <typename TS, typename TD>
+// dst[r, c] = convert(src[r, c]); VEC: eight elements per thread with 16-byte accesses on the
+// two-byte side (d a multiple of 8, rows and pointers on 16-byte boundaries)
+template <typename TS, typename TD, bool VEC>
 __global__ __launch_bounds__(kGradThreads) void harp_grad_convert_kernel(
     const TS *__restrict__ src, int64_t lds_, TD *__restrict__ dst, int64_t ldd, int64_t n, int d) {
   const int64_t row = blockIdx.y;
-  for (int c = blockIdx.x * kGradThreads + threadIdx.x; c < d; c += gridDim.x * kGradThreads)
-    grad_narrow(grad_widen(src[row * lds_ + c]), dst + row * ldd + c);
+  if (VEC) {
+    for (int c = 8 * (blockIdx.x * kGradThreads + threadIdx.x); c < d; c += 8 * gridDim.x * kGradThreads) {
+      float v[8];
+      const TS *sp = src + row * lds_ + c;
+      TD *dp = dst + row * ldd + c;
+      if (sizeof(TS) == 2) {
+        const uint4 raw = *reinterpret_cast<const uint4 *>(sp);
+        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          v[2 * i] = __uint_as_float(w[i] << 16);
+          v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+      } else {
+        const float4 a = *reinterpret_cast<const float4 *>(sp), b = *reinterpret_cast<const float4 *>(sp + 4);
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+      }
+      if (sizeof(TD) == 2) {
+        uint16_t h[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) grad_narrow(v[i], reinterpret_cast<uint16_t *>(&h[i]));
+        *reinterpret_cast<uint4 *>(dp) =
+            make_uint4(h[0] | ((uint32_t)h[1] << 16), h[2] | ((uint32_t)h[3] << 16),
+                       h[4] | ((uint32_t)h[5] << 16), h[6] | ((uint32_t)h[7] << 16));
+      } else {
+        *reinterpret_cast<float4 *>(dp) = make_float4(v[0], v[1], v[2], v[3]);
+        *reinterpret_cast<float4 *>(reinterpret_cast<float *>(dp) + 4) = make_float4(v[4], v[5], v[6], v[7]);
+      }
+    }
+  } else {
+    for (int c = blockIdx.x * kGradThreads + threadIdx.x; c < d; c += gridDim.x * kGradThreads)
+      grad_narrow(grad_widen(src[row * lds_ + c]), dst + row * ldd + c);
+  }
   (void)n;
 }
 
@@ -376,12 +408,19 @@ void launch_bwd(const float *X, float *G, int64_t ld, int64_t n, int rows, int n
 template <typename TS, typename TD>
 void launch_convert(const TS *src, int64_t lds_, TD *dst, int64_t ldd, int64_t n, int64_t d,
                     hipStream_t st) {
+  const bool vec = (d % 8 == 0) && (lds_ % 8 == 0) && (ldd % 8 == 0) && ((uintptr_t)src % 16 == 0) &&
+                   ((uintptr_t)dst % 16 == 0);
+  const int64_t per = vec ? 8 * kGradThreads : kGradThreads;
   // the row index is blockIdx.y (at most 65535 per launch)
   for (int64_t r0 = 0; r0 < n; r0 += 65535) {
     const int64_t nr = std::min<int64_t>(65535, n - r0);
-    const unsigned gx = (unsigned)std::min<int64_t>((d + kGradThreads - 1) / kGradThreads, 64);
-    hipLaunchKernelGGL((harp_grad_convert_kernel<TS, TD>), dim3(gx, (unsigned)nr), dim3(kGradThreads),
-                       0, st, src + r0 * lds_, lds_, dst + r0 * ldd, ldd, nr, (int)d);
+    const unsigned gx = (unsigned)std::min<int64_t>((d + per - 1) / per, 64);
+    if (vec)
+      hipLaunchKernelGGL((harp_grad_convert_kernel<TS, TD, true>), dim3(gx, (unsigned)nr),
+                         dim3(kGradThreads), 0, st, src + r0 * lds_, lds_, dst + r0 * ldd, ldd, nr, (int)d);
+    else
+      hipLaunchKernelGGL((harp_grad_convert_kernel<TS, TD, false>), dim3(gx, (unsigned)nr),
+                         dim3(kGradThreads), 0, st, src + r0 * lds_, lds_, dst + r0 * ldd, ldd, nr, (int)d);
   }
 }
 
