@@ -110,9 +110,10 @@ harp_status_t harp_plan_destroy(harp_plan_t *plan);
  * Arithmetic is float32 with one rounding at a bf16 store, with one exception: when dt is
  * HARP_BF16, a stage of radix 9..64 of such a plan runs on the matrix cores with every float32
  * operand split into two bf16 terms (x_hi K_hi + x_lo K_hi + x_hi K_lo accumulated in float32,
- * about 16 significant bits per product -- below the bf16 rounding of the result).  HARP_F32
- * callers always get the float32 vector path; setting the environment variable HARP_NO_MFMA=1
- * selects it for bf16 callers too.
+ * about 16 significant bits per product -- below the bf16 rounding of the result).  For
+ * HARP_F32 callers that stage runs on the float32 matrix instruction with unsplit operands
+ * (float32 products and sums, in another order than the vector path).  Setting the
+ * environment variable HARP_NO_MFMA=1 selects the float32 vector path for every caller.
  */
 harp_status_t harp_apply(const harp_plan_t *plan, const void *X, int64_t ldx, void *Y,
                          int64_t ldy, int64_t n, harp_dtype_t dt, void *stream);

@@ -183,8 +183,10 @@ float bf16_to_float(uint16_t h) {
 
 // A radix-b block (9 <= b <= 64) as operand tiles of v_mfma_f32_16x16x16_bf16: KT = ceil(b/16);
 // for tile (kt, nt), half h (0: bf16(v), 1: bf16(v - hi)), lane l, i < 4 the value is
-// K[k = 16 kt + 4 (l / 16) + i][n = 16 nt + l % 16], zero outside the block.
-void pack_mfma_block(const float *K, int b, uint16_t *out) {
+// K[k = 16 kt + 4 (l / 16) + i][n = 16 nt + l % 16], zero outside the block.  out32 takes the
+// same tiles unsplit in float32, [tile][lane][i], for v_mfma_f32_16x16x4_f32 (instruction i of
+// a tile sums the four k of index i).
+void pack_mfma_block(const float *K, int b, uint16_t *out, float *out32) {
   const int KT = (b + 15) / 16;
   for (int kt = 0; kt < KT; ++kt)
     for (int nt = 0; nt < KT; ++nt)
@@ -197,6 +199,7 @@ void pack_mfma_block(const float *K, int b, uint16_t *out) {
           const size_t t = (size_t)(kt * KT + nt) * 2;
           out[((t + 0) * 64 + l) * 4 + i] = hi;
           out[((t + 1) * 64 + l) * 4 + i] = lo;
+          out32[((size_t)(kt * KT + nt) * 64 + l) * 4 + i] = v;
         }
 }
 
@@ -341,11 +344,14 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
     }
     if (fused && !small && b >= 9) {   // matrix-core operand tiles for the streamed large radix
       const int KT = (b + 15) / 16;
-      const size_t per = (size_t)KT * KT * 2 * 64 * 4;
+      const size_t per = (size_t)KT * KT * 2 * 64 * 4;   // bf16 values per block
+      const size_t per32 = (size_t)KT * KT * 64 * 4;     // float32 values per block
       std::vector<uint16_t> &a = aux[pg.npass - 1];
-      a.resize(per * nq);
+      a.resize(per * nq + 2 * per32 * nq);               // [nq] bf16 tiles, then [nq] float32 tiles
+      float *a32 = reinterpret_cast<float *>(a.data() + per * nq);
       for (int64_t q = 0; q < nq; ++q)
-        pack_mfma_block(se.dense.data() + (size_t)q * b * b, b, a.data() + per * q);
+        pack_mfma_block(se.dense.data() + (size_t)q * b * b, b, a.data() + per * q,
+                        a32 + per32 * q);
     }
     ++i;
   }

@@ -39,7 +39,8 @@ struct PassDesc {
   int32_t nq;    // d / P sub-tensors per row
   int32_t V;     // parameter values per sub-tensor
   const float *params;  // device, [V][nq]: value v of sub-tensor q at params[v * nq + q]
-  // GENERIC, radix >= 9: the blocks as bf16 hi/lo MFMA operand tiles; SMALL, radix 4 / 8: a
+  // GENERIC, radix >= 9: the blocks as bf16 hi/lo MFMA operand tiles of all sub-tensors,
+  // followed by the same tiles in float32; SMALL, radix 4 / 8: a
   // second copy of params, four values per 16-byte load ([V/4][nq][4] floats); else null
   const void *aux;
 };
@@ -162,7 +163,7 @@ bool mfma_pass_supported(const PassDesc &pd, const void *X, int64_t ldx, const v
                          int64_t ldy);
 harp_status_t launch_mfma_pass(const harp_plan *plan, const PassDesc &pd, const void *X,
                                int64_t ldx, harp_dtype_t dt_in, void *Y, int64_t ldy,
-                               harp_dtype_t dt_out, int64_t n, hipStream_t stream);
+                               harp_dtype_t dt_out, int64_t n, bool narrow, hipStream_t stream);
 harp_status_t launch_transpose(const void *src, int64_t lds_, harp_dtype_t dt_src, void *dst,
                                int64_t ldd, harp_dtype_t dt_dst, int64_t rows, int64_t cols,
                                hipStream_t stream);

@@ -766,8 +766,8 @@ harp_status_t launch_stream_pass(const harp_plan *plan, const HostProgram &hp, i
                                  hipStream_t stream) {
   if (n == 0) return HARP_OK;
   const PassDesc &pd = hp.prog.pass[p];
-  if (allow_narrow && env_int("HARP_NO_MFMA", 0) == 0 && mfma_pass_supported(pd, X, ldx, Y, ldy))
-    return launch_mfma_pass(plan, pd, X, ldx, dt_in, Y, ldy, dt_out, n, stream);
+  if (env_int("HARP_NO_MFMA", 0) == 0 && mfma_pass_supported(pd, X, ldx, Y, ldy))
+    return launch_mfma_pass(plan, pd, X, ldx, dt_in, Y, ldy, dt_out, n, allow_narrow, stream);
   const int ib = dt_in == HARP_BF16, ob = dt_out == HARP_BF16;
   switch (pd.kind) {
     case PASS_POW2_DENSE:

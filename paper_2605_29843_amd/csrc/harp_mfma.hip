@@ -8,8 +8,10 @@
 // sustain at memory speed.  It runs on v_mfma_f32_16x16x16_bf16 with float32 accumulation.
 // Operand narrowing (documented approximation): each float32 operand is split into two bf16
 // terms, x = x_hi + x_lo, and x_hi*K_hi + x_lo*K_hi + x_hi*K_lo is accumulated (about 16
-// significant bits per product).  The launcher only takes this path when the caller's element
-// type is bf16.
+// significant bits per product).  The launcher only takes this form when the caller's element
+// type is bf16.  With float32 on both sides of the call the same kernel runs on
+// v_mfma_f32_16x16x4_f32 with unsplit float32 operands (F32 = true): a quarter of the k extent
+// per instruction, still far below the time the rows take to stream.
 //
 // A workgroup of 16 waves owns 16 consecutive blocks q (same hi, consecutive lo: 64-byte
 // contiguous runs in memory for every row and j) and walks down its rows 16 at a time:
@@ -58,7 +60,7 @@ __device__ __forceinline__ void split4(const float (&x)[4], s4v &hi, s4v &lo) {
   lo = __builtin_bit_cast(s4v, lv);
 }
 
-template <int KT, typename TI, typename TO>
+template <int KT, typename TI, typename TO, bool F32>
 __global__ __launch_bounds__(1024) void harp_stream_mfma_kernel(
     const TI *__restrict__ X, int64_t ldx, TO *__restrict__ Y, int64_t ldy, int64_t n,
     int rows_per_wg, int gx, int gy, PassDesc pd) {
@@ -88,9 +90,20 @@ __global__ __launch_bounds__(1024) void harp_stream_mfma_kernel(
   const int64_t r_begin = (int64_t)ry * rows_per_wg;
   const int64_t r_end = (r_begin + rows_per_wg < n) ? r_begin + rows_per_wg : n;
 
-  // this wave's block, packed by the plan in lane layout: tile (kt, nt), half 0 = hi, 1 = lo
-  s4v bh[KT][KT], bl[KT][KT];
-  {
+  // this wave's block, packed by the plan in lane layout: tile (kt, nt), half 0 = hi, 1 = lo;
+  // the float32 copy of the same tiles (one float4 per lane and tile) follows the bf16 tiles
+  // of all nq blocks
+  s4v bh[F32 ? 1 : KT][F32 ? 1 : KT], bl[F32 ? 1 : KT][F32 ? 1 : KT];
+  f4v bf[F32 ? KT : 1][F32 ? KT : 1];
+  if constexpr (F32) {
+    const f4v *bp = reinterpret_cast<const f4v *>(static_cast<const s4v *>(pd.aux) +
+                                                  (size_t)pd.nq * KT * KT * 2 * 64) +
+                    (size_t)(q0 + w) * KT * KT * 64 + l;
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+      for (int nt = 0; nt < KT; ++nt) bf[kt][nt] = bp[(kt * KT + nt) * 64];
+  } else {
     const s4v *bp = static_cast<const s4v *>(pd.aux) + (size_t)(q0 + w) * KT * KT * 2 * 64 + l;
 #pragma unroll
     for (int kt = 0; kt < KT; ++kt)
@@ -167,13 +180,22 @@ __global__ __launch_bounds__(1024) void harp_stream_mfma_kernel(
         const int j = 16 * kt + 4 * g + i;
         a[i] = (j < b) ? tile[j * kJS + w * kLS + c16] : 0.0f;
       }
-      s4v ah, al;
-      split4(a, ah, al);
+      if constexpr (F32) {
+        // k = 16 kt + 4 g + i is summed by instruction i: operand lanes (row | column, g)
 #pragma unroll
-      for (int nt = 0; nt < KT; ++nt) {
-        acc[nt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(al, bh[kt][nt], acc[nt], 0, 0, 0);
-        acc[nt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ah, bl[kt][nt], acc[nt], 0, 0, 0);
-        acc[nt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ah, bh[kt][nt], acc[nt], 0, 0, 0);
+        for (int nt = 0; nt < KT; ++nt)
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            acc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[i], bf[kt][nt][i], acc[nt], 0, 0, 0);
+      } else {
+        s4v ah, al;
+        split4(a, ah, al);
+#pragma unroll
+        for (int nt = 0; nt < KT; ++nt) {
+          acc[nt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(al, bh[kt][nt], acc[nt], 0, 0, 0);
+          acc[nt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ah, bl[kt][nt], acc[nt], 0, 0, 0);
+          acc[nt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ah, bh[kt][nt], acc[nt], 0, 0, 0);
+        }
       }
     }
     __syncthreads();   // every wave has read its inputs
@@ -214,7 +236,7 @@ __global__ __launch_bounds__(1024) void harp_stream_mfma_kernel(
   }
 }
 
-template <int KT, typename TI, typename TO>
+template <int KT, typename TI, typename TO, bool F32>
 harp_status_t launch_mfma_typed(const harp_plan *plan, const PassDesc &pd, const void *X,
                                 int64_t ldx, void *Y, int64_t ldy, int64_t n,
                                 hipStream_t stream) {
@@ -228,7 +250,7 @@ harp_status_t launch_mfma_typed(const harp_plan *plan, const PassDesc &pd, const
   int64_t total = (int64_t)gx * gy;
   if ((gx & 3) == 0) total = (total + 31) / 32 * 32;
   if (total > 0x7fffffff) return HARP_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL((harp_stream_mfma_kernel<KT, TI, TO>), dim3((unsigned)total), dim3(1024), 0,
+  hipLaunchKernelGGL((harp_stream_mfma_kernel<KT, TI, TO, F32>), dim3((unsigned)total), dim3(1024), 0,
                      stream, (const TI *)X, ldx, (TO *)Y, ldy, n, (int)rpw, (int)gx, (int)gy, pd);
   return hipGetLastError() == hipSuccess ? HARP_OK : HARP_ERR_DEVICE;
 }
@@ -238,11 +260,18 @@ harp_status_t launch_mfma_typed(const harp_plan *plan, const PassDesc &pd, const
 template <int KT>
 harp_status_t launch_mfma_inst(const harp_plan *plan, const PassDesc &pd, const void *X,
                                int64_t ldx, int ib, void *Y, int64_t ldy, int ob, int64_t n,
-                               hipStream_t stream) {
-  if (ib && !ob) return launch_mfma_typed<KT, uint16_t, float>(plan, pd, X, ldx, Y, ldy, n, stream);
-  if (!ib && ob) return launch_mfma_typed<KT, float, uint16_t>(plan, pd, X, ldx, Y, ldy, n, stream);
-  if (!ib && !ob) return launch_mfma_typed<KT, float, float>(plan, pd, X, ldx, Y, ldy, n, stream);
-  return launch_mfma_typed<KT, uint16_t, uint16_t>(plan, pd, X, ldx, Y, ldy, n, stream);
+                               bool narrow, hipStream_t stream) {
+  if (!narrow) {   // float32 on both sides of the call: every segment is float32
+    if (ib || ob) return HARP_ERR_INVALID_ARG;
+    return launch_mfma_typed<KT, float, float, true>(plan, pd, X, ldx, Y, ldy, n, stream);
+  }
+  if (ib && !ob)
+    return launch_mfma_typed<KT, uint16_t, float, false>(plan, pd, X, ldx, Y, ldy, n, stream);
+  if (!ib && ob)
+    return launch_mfma_typed<KT, float, uint16_t, false>(plan, pd, X, ldx, Y, ldy, n, stream);
+  if (!ib && !ob)
+    return launch_mfma_typed<KT, float, float, false>(plan, pd, X, ldx, Y, ldy, n, stream);
+  return launch_mfma_typed<KT, uint16_t, uint16_t, false>(plan, pd, X, ldx, Y, ldy, n, stream);
 }
 
 }  // namespace
@@ -258,15 +287,15 @@ bool mfma_pass_supported(const PassDesc &pd, const void *X, int64_t ldx, const v
 
 harp_status_t launch_mfma_pass(const harp_plan *plan, const PassDesc &pd, const void *X,
                                int64_t ldx, harp_dtype_t dt_in, void *Y, int64_t ldy,
-                               harp_dtype_t dt_out, int64_t n, hipStream_t stream) {
+                               harp_dtype_t dt_out, int64_t n, bool narrow, hipStream_t stream) {
   if (n == 0) return HARP_OK;
   const int ib = dt_in == HARP_BF16, ob = dt_out == HARP_BF16;
   const int kt = (pd.b + 15) / 16;
   switch (kt) {
-    case 1: return launch_mfma_inst<1>(plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
-    case 2: return launch_mfma_inst<2>(plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
-    case 3: return launch_mfma_inst<3>(plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
-    case 4: return launch_mfma_inst<4>(plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
+    case 1: return launch_mfma_inst<1>(plan, pd, X, ldx, ib, Y, ldy, ob, n, narrow, stream);
+    case 2: return launch_mfma_inst<2>(plan, pd, X, ldx, ib, Y, ldy, ob, n, narrow, stream);
+    case 3: return launch_mfma_inst<3>(plan, pd, X, ldx, ib, Y, ldy, ob, n, narrow, stream);
+    case 4: return launch_mfma_inst<4>(plan, pd, X, ldx, ib, Y, ldy, ob, n, narrow, stream);
     default: return HARP_ERR_UNSUPPORTED;
   }
 }

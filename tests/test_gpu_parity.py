@@ -387,6 +387,14 @@ def test_large_radix_stage_on_matrix_cores(harp, d, radices, n):
     assert max(out.values()) < 0.8      # error stays well inside the bf16 tolerance
 
 
+@pytest.mark.parametrize("d,radices,n", MFMA_CASES)
+def test_large_radix_stage_on_matrix_cores_float32(harp, d, radices, n):
+    """float32 I/O: the same stage runs on the float32 MFMA instruction with unsplit
+    operands and has to meet the float32 tolerance."""
+    X = gi.activations(n, d, config=3, bf16=False)
+    run_case(harp, d, radices, n, "f32", seed=d + n + 1, algo=3, act=X)
+
+
 def test_split_is_refused_when_there_is_nothing_to_split(harp):
     rng = np.random.default_rng(1)
     plan = harp.Plan(4096, [2] * 12, gi.make_blocks(4096, [2] * 12, "orth", rng))
