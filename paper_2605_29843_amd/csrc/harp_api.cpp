@@ -219,17 +219,26 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
   offsets.clear();
   aux.assign(kMaxPasses, std::vector<uint16_t>());
 
-  // Split programs: stages t < tb (product of their radices = chunk <= kChunkCap, maximal) are
-  // chunk-local; passes never mix stages from both sides of tb.
+  // Split programs: stages t < tb (product of their radices = chunk <= kChunkCap, maximal unless
+  // a large-radix stage ends it earlier) are chunk-local; passes never mix stages from both
+  // sides of tb.
   const bool fused = (algo != HARP_ALGO_GENERIC);
   int tb = m;
   int64_t chunk = d;
   if (algo == HARP_ALGO_SPLIT) {
-    if (d <= kChunkCap) return false;   // nothing to split: the fused program covers it
     tb = 0;
     chunk = 1;
-    while (tb < m && chunk * plan->radices[tb] <= kChunkCap) chunk *= plan->radices[tb++];
-    if (tb == 0) return false;          // first radix alone exceeds the cap (cannot happen: <= 64)
+    bool small_only = true;   // every stage of the chunk so far has radix <= 8
+    while (tb < m && chunk * plan->radices[tb] <= kChunkCap) {
+      // A stage of radix >= 9 that the matrix-core kernel can stream (its stride, the chunk so
+      // far, a multiple of 16) ends a chunk of small-radix stages: on chip such a stage only
+      // has the run-time-radix body, which re-reads its block for every row.
+      const bool large = plan->radices[tb] >= 9;
+      if (large && small_only && chunk >= 64 && chunk % 16 == 0) break;
+      if (large) small_only = false;
+      chunk *= plan->radices[tb++];
+    }
+    if (tb == 0 || tb == m) return false;   // nothing to split: the fused program covers it
   }
   auto local = [&](int i) { return eff[i].t < tb; };
   hp.chunk = (int32_t)chunk;

@@ -15,6 +15,8 @@
 // stage's coordinates alpha*b*s + r*s + beta are addressed directly in LDS (Lemma 1).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <type_traits>
 #include <stdlib.h>
 
 #include "harp_internal.h"
@@ -426,8 +428,8 @@ __device__ __forceinline__ void stream_store(void *p, int64_t i, int bf16, float
 }
 
 // element access of the streamed kernels, by element type
-__device__ __forceinline__ float stream_get(const uint16_t *p) { return widen_bf16(*p); }
-__device__ __forceinline__ float stream_get(const float *p) { return *p; }
+__device__ __forceinline__ float stream_widen(uint32_t v) { return __uint_as_float(v << 16); }
+__device__ __forceinline__ float stream_widen(float v) { return v; }
 __device__ __forceinline__ void stream_put(uint16_t *p, float v) { *p = narrow_bf16(v); }
 __device__ __forceinline__ void stream_put(float *p, float v) { *p = v; }
 
@@ -453,22 +455,45 @@ __global__ __launch_bounds__(256) void harp_stream_kernel(const TI *__restrict__
   const int nr = (int)((r0 + rows_per_block < n) ? rows_per_block : n - r0);
   const TI *xp = X + r0 * ldx + base;
   TO *yp = Y + r0 * ldy + base;
-  float xn[P];
+  // Two rows in flight in two named buffers (a: even rows of the block, b: odd rows), each as
+  // loaded (bf16 zero-extended to 32 bits, widened only when its turn comes).  Every load and
+  // store is unconditional -- past the last row the pointers stop moving, so the last row is
+  // loaded, computed and stored a second time with the same bits -- and the scheduling barriers
+  // keep the order written here: a wait for a buffer then always follows the same 2 P younger
+  // operations and is a wait for that buffer only, not for the stores issued since.
+  typedef typename std::conditional<sizeof(TI) == 2, uint32_t, float>::type Raw;
+  Raw a[P], b[P];
 #pragma unroll
-  for (int j = 0; j < P; ++j) xn[j] = stream_get(xp + (unsigned)(j * S));
-  for (int r = 0; r < nr; ++r) {
-    float x[P];
+  for (int j = 0; j < P; ++j) a[j] = (Raw)xp[(unsigned)(j * S)];
+  for (int r = 0; r < nr; r += 2) {
+    const TI *xb = (r + 1 < nr) ? xp + ldx : xp;
+    TO *yb = (r + 1 < nr) ? yp + ldy : yp;
 #pragma unroll
-    for (int j = 0; j < P; ++j) x[j] = xn[j];
-    xp += ldx;
-    if (r + 1 < nr) {
+    for (int j = 0; j < P; ++j) b[j] = (Raw)xb[(unsigned)(j * S)];
+    __builtin_amdgcn_sched_barrier(0);
+    {
+      float x[P];
 #pragma unroll
-      for (int j = 0; j < P; ++j) xn[j] = stream_get(xp + (unsigned)(j * S));
+      for (int j = 0; j < P; ++j) x[j] = stream_widen(a[j]);
+      OP::apply(x, prm);
+#pragma unroll
+      for (int j = 0; j < P; ++j) stream_put(yp + (unsigned)(j * S), x[j]);
     }
-    OP::apply(x, prm);
+    __builtin_amdgcn_sched_barrier(0);
+    xp = (r + 2 < nr) ? xb + ldx : xb;
 #pragma unroll
-    for (int j = 0; j < P; ++j) stream_put(yp + (unsigned)(j * S), x[j]);
-    yp += ldy;
+    for (int j = 0; j < P; ++j) a[j] = (Raw)xp[(unsigned)(j * S)];
+    __builtin_amdgcn_sched_barrier(0);
+    {
+      float x[P];
+#pragma unroll
+      for (int j = 0; j < P; ++j) x[j] = stream_widen(b[j]);
+      OP::apply(x, prm);
+#pragma unroll
+      for (int j = 0; j < P; ++j) stream_put(yb + (unsigned)(j * S), x[j]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    yp = yb + ldy;
   }
 }
 

@@ -395,6 +395,24 @@ def test_large_radix_stage_on_matrix_cores_float32(harp, d, radices, n):
     run_case(harp, d, radices, n, "f32", seed=d + n + 1, algo=3, act=X)
 
 
+@pytest.mark.parametrize("d,radices,n", [
+    (2816, [8, 8, 4, 11], 37), (1408, [8, 8, 2, 11], 20), (2752, [8, 8, 43], 33),
+    (4096, [8, 8, 64], 18), (8192, [8, 8, 16, 8], 9), (4096, [2] * 8 + [16], 70),
+    (2304, [4, 4, 4, 4, 9], 5)])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_large_radix_stage_ends_the_chunk(harp, d, radices, n, dtype):
+    """Rows of at most one chunk whose schedule ends in a leftover prime (or any radix >= 9)
+    behind small stages: the default program streams that stage on the matrix cores instead of
+    running it on chip; the one-launch program stays selectable and agrees."""
+    rng = np.random.default_rng(d)
+    plan = harp.Plan(d, radices, gi.make_blocks(d, radices, "orth", rng))
+    assert plan.kernel_name(n).startswith("split"), plan.kernel_name(n)
+    plan.destroy()
+    X = gi.activations(n, d, config=3, bf16=(dtype == "bf16"))
+    run_case(harp, d, radices, n, dtype, seed=d + n, act=X)
+    run_case(harp, d, radices, n, dtype, seed=d + n, algo=2, act=X)
+
+
 def test_split_is_refused_when_there_is_nothing_to_split(harp):
     rng = np.random.default_rng(1)
     plan = harp.Plan(4096, [2] * 12, gi.make_blocks(4096, [2] * 12, "orth", rng))
