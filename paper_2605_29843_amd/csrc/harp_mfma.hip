@@ -28,6 +28,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "harp_internal.h"
 
 namespace harp {
@@ -115,27 +117,30 @@ __global__ __launch_bounds__(1024) void harp_stream_mfma_kernel(
   }
 
   const int ngroups = kRC * b * 4;   // (row, j, quarter of the 16 lo) per chunk
-  // this thread's 4-coordinate groups: offsets inside a chunk of 16 rows (32-bit) and LDS slots
+  // This thread's 4-coordinate groups: offsets inside a chunk of 16 rows (32-bit) and LDS slots.
+  // A thread whose group index lies beyond the chunk takes the group of another thread a second
+  // time (same loads, same values to the same LDS slots and addresses), so that inside full
+  // chunks no access is conditional.
   unsigned offx[MAXG], offy[MAXG];
   int grow[MAXG], gtile[MAXG];
 #pragma unroll
   for (int u = 0; u < MAXG; ++u) {
-    const int gi = tid + u * 1024;
+    const int gi = (tid + u * 1024) % ngroups;
     const int lo4 = gi & 3, rem = gi >> 2;
     const int row = rem & (kRC - 1), j = rem >> 4;
-    grow[u] = (gi < ngroups) ? row : 0x7fffffff;   // never below the rows left: group unused
+    grow[u] = row;
     offx[u] = (unsigned)(row * (int)ldx + j * S + lo4 * 4);
     offy[u] = (unsigned)(row * (int)ldy + j * S + lo4 * 4);
     gtile[u] = j * kJS + (lo4 * 4) * kLS + row;
   }
   float pre[MAXG][4];
-  auto fetch = [&](int64_t r0) {
+  // rows [r0, r0 + left) of the chunk exist; FULL: left == 16 and nothing is tested
+  auto fetch = [&](int64_t r0, int left, auto full) {
     const TI *xc = X + r0 * ldx + base;
-    const int left = (int)(r_end - r0);
 #pragma unroll
     for (int u = 0; u < MAXG; ++u) {
-      pre[u][0] = pre[u][1] = pre[u][2] = pre[u][3] = 0.0f;
-      if (grow[u] < left) {
+      if (!decltype(full)::value) pre[u][0] = pre[u][1] = pre[u][2] = pre[u][3] = 0.0f;
+      if (decltype(full)::value || grow[u] < left) {
         if constexpr (in_bf16) {
           const uint2 v = *reinterpret_cast<const uint2 *>(xc + offx[u]);
           pre[u][0] = __uint_as_float(v.x << 16);
@@ -152,23 +157,14 @@ __global__ __launch_bounds__(1024) void harp_stream_mfma_kernel(
   auto commit = [&]() {
 #pragma unroll
     for (int u = 0; u < MAXG; ++u) {
-      if (grow[u] != 0x7fffffff) {
-        float *t = tile + gtile[u];
+      float *t = tile + gtile[u];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) t[k * kLS] = pre[u][k];
-      }
+      for (int k = 0; k < 4; ++k) t[k * kLS] = pre[u][k];
     }
   };
-
-  fetch(r_begin);
-  commit();
-  __syncthreads();
-
-  for (int64_t r0 = r_begin; r0 < r_end; r0 += kRC) {
-    const bool more = r0 + kRC < r_end;
-    if (more) fetch(r0 + kRC);   // loads in flight while this chunk is computed
-
-    // ---- A operand: lane (row = c16, k = 4g + i) of this wave's block, split to bf16 hi/lo
+  // the chunk in the tile times this wave's block, results back into the same tile positions
+  auto multiply = [&]() {
+    // ---- A operand: lane (row = c16, k = 4g + i) of this wave's block
     f4v acc[KT];
 #pragma unroll
     for (int nt = 0; nt < KT; ++nt) acc[nt] = (f4v){0.0f, 0.0f, 0.0f, 0.0f};
@@ -188,7 +184,7 @@ __global__ __launch_bounds__(1024) void harp_stream_mfma_kernel(
           for (int i = 0; i < 4; ++i)
             acc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[i], bf[kt][nt][i], acc[nt], 0, 0, 0);
       } else {
-        s4v ah, al;
+        s4v ah, al;   // split to bf16 hi/lo
         split4(a, ah, al);
 #pragma unroll
         for (int nt = 0; nt < KT; ++nt) {
@@ -199,8 +195,7 @@ __global__ __launch_bounds__(1024) void harp_stream_mfma_kernel(
       }
     }
     __syncthreads();   // every wave has read its inputs
-
-    // ---- results back into the tile: lane holds rows 4g..4g+3 of output coordinate 16nt + c16
+    // ---- lane holds rows 4g..4g+3 of output coordinate 16nt + c16
 #pragma unroll
     for (int nt = 0; nt < KT; ++nt) {
       const int j2 = 16 * nt + c16;
@@ -211,28 +206,51 @@ __global__ __launch_bounds__(1024) void harp_stream_mfma_kernel(
       }
     }
     __syncthreads();
-
-    // ---- coalesced store of the chunk
-    {
-      TO *yc = Y + r0 * ldy + base;
-      const int left = (int)(r_end - r0);
+  };
+  // coalesced store of the chunk in the tile
+  auto put = [&](int64_t r0, int left, auto full) {
+    TO *yc = Y + r0 * ldy + base;
 #pragma unroll
-      for (int u = 0; u < MAXG; ++u) {
-        if (grow[u] < left) {
-          const float *t = tile + gtile[u];
-          const float v0 = t[0], v1 = t[kLS], v2 = t[2 * kLS], v3 = t[3 * kLS];
-          if constexpr (out_bf16)
-            *reinterpret_cast<uint2 *>(yc + offy[u]) = make_uint2(pk_bf16(v0, v1), pk_bf16(v2, v3));
-          else
-            *reinterpret_cast<float4 *>(yc + offy[u]) = make_float4(v0, v1, v2, v3);
-        }
+    for (int u = 0; u < MAXG; ++u) {
+      if (decltype(full)::value || grow[u] < left) {
+        const float *t = tile + gtile[u];
+        const float v0 = t[0], v1 = t[kLS], v2 = t[2 * kLS], v3 = t[3 * kLS];
+        if constexpr (out_bf16)
+          *reinterpret_cast<uint2 *>(yc + offy[u]) = make_uint2(pk_bf16(v0, v1), pk_bf16(v2, v3));
+        else
+          *reinterpret_cast<float4 *>(yc + offy[u]) = make_float4(v0, v1, v2, v3);
       }
     }
-    __syncthreads();   // the tile is free again
-    if (more) {
+  };
+  const std::true_type kFull;
+  const std::false_type kGuarded;
+
+  // Full chunks: the next chunk is requested while this one is computed (after the last one
+  // that chunk itself once more), so that the wait for it, before it goes into the tile, always
+  // follows this chunk's stores and nothing else: it need not wait for those stores.
+  const int nfull = (int)((r_end - r_begin) / kRC);
+  const int tail = (int)(r_end - r_begin) - nfull * kRC;
+  if (nfull > 0) {
+    fetch(r_begin, kRC, kFull);
+    commit();
+    __syncthreads();
+    for (int c = 0; c < nfull; ++c) {
+      const int64_t r0 = r_begin + (int64_t)c * kRC;
+      fetch((c + 1 < nfull) ? r0 + kRC : r0, kRC, kFull);
+      multiply();
+      put(r0, kRC, kFull);
+      __syncthreads();   // the tile is free again
       commit();
       __syncthreads();
     }
+  }
+  if (tail > 0) {   // the rows left over at the end of the matrix
+    const int64_t r0 = r_begin + (int64_t)nfull * kRC;
+    fetch(r0, tail, kGuarded);
+    commit();
+    __syncthreads();
+    multiply();
+    put(r0, tail, kGuarded);
   }
 }
 
