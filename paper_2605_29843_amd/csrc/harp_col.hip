@@ -225,11 +225,12 @@ __device__ __forceinline__ void col_ops(float2 *tile, const float *prm, const Co
 
 // A workgroup walks over `tpw` consecutive tiles; the rows of the next tile are requested into
 // registers (up to 32 rows per wave) before the work on the current one starts.
-// NRW > 0 (fast variant): P == 4 NRW exactly, every column tile is full and pairs of columns
-// are aligned, so every wave owns NRW rows and no access is conditional -- the compiler can
-// then count the outstanding loads and stores and waits for the rows of the next tile without
-// also waiting for the stores of the previous one (vector memory operations retire in
-// order).  NRW == 0: any P <= 128 and ragged column tiles, guarded.
+// NRW > 0 (fast variant): 4 <= P <= 4 NRW, every column tile is full and pairs of columns are
+// aligned; every wave takes NRW row steps (those past its last row repeat that row) and no
+// access is conditional -- the compiler can then count the outstanding loads and stores and
+// waits for the rows of the next tile without also waiting for the stores of the previous one
+// (vector memory operations retire in order).  NRW == 0: any P <= 128 and ragged column
+// tiles, guarded.
 template <typename TI, typename TO, bool VEC, int NRW>
 __global__ __launch_bounds__(kColThreads) void harp_col_kernel(
     const ColPass *__restrict__ passp, const TI *src, int64_t lds_, TO *dst, int64_t ldd,
@@ -241,6 +242,13 @@ __global__ __launch_bounds__(kColThreads) void harp_col_kernel(
   const int P = cp.P, S = cp.S;
   constexpr int NR = NRW > 0 ? NRW : kColMaxP / kColWaves;   // rows per wave
   constexpr bool GUARD = (NRW == 0);
+  // Unguarded variants (4 <= P <= 4 * NRW): wave w owns the rows w + 4 u, u <= ulast; the steps
+  // u > ulast repeat row w + 4 ulast (same address, same LDS slot, same value), so that no
+  // access is conditional whatever P is.  The running pointers and LDS slots are clamped
+  // per lane (vector arithmetic: one clamp value per tile instead of a scalar per step);
+  // P == 4 * NRW takes the plain increments.
+  const bool exact = GUARD || (P == kColWaves * NR);
+  const int ulast_v = (P - 1 - ((int)threadIdx.x >> 6)) >> 2;   // per lane on purpose
 
   struct TilePos {
     int hi, lo;
@@ -292,10 +300,19 @@ __global__ __launch_bounds__(kColThreads) void harp_col_kernel(
       ppre[k] = image[dfix[k] + (unsigned)tp.hi * dfa[k] + (unsigned)tp.lo * dfb[k]];
     const TI *rp = src + (tp.row0 + (int64_t)wave * S) * lds_ + tp.col;
     const int64_t step = (int64_t)kColWaves * S * lds_;
+    if (exact) {
 #pragma unroll
-    for (int u = 0; u < NR; ++u) {
-      if (!GUARD || wave + kColWaves * u < P) col_load<TI, VEC>(pre[u], rp, tp.v0, tp.v1);
-      rp += step;
+      for (int u = 0; u < NR; ++u) {
+        if (!GUARD || wave + kColWaves * u < P) col_load<TI, VEC>(pre[u], rp, tp.v0, tp.v1);
+        rp += step;
+      }
+    } else {
+      const TI *rlast = rp + (int64_t)ulast_v * step;
+#pragma unroll
+      for (int u = 0; u < NR; ++u) {
+        col_load<TI, VEC>(pre[u], rp, tp.v0, tp.v1);
+        rp = (rp + step < rlast) ? rp + step : rlast;
+      }
     }
   };
 
@@ -305,9 +322,18 @@ __global__ __launch_bounds__(kColThreads) void harp_col_kernel(
   // registers -> LDS: rows and block values of the tile whose request is outstanding
   float2 *tp0 = tile + wave * 64 + lane;
   auto to_lds = [&]() __attribute__((always_inline)) {
+    if (exact) {
 #pragma unroll
-    for (int u = 0; u < NR; ++u)
-      if (!GUARD || wave + kColWaves * u < P) tp0[u * (kColWaves * 64)] = col_widen<VEC>(pre[u]);
+      for (int u = 0; u < NR; ++u)
+        if (!GUARD || wave + kColWaves * u < P) tp0[u * (kColWaves * 64)] = col_widen<VEC>(pre[u]);
+    } else {
+      int su = 0;
+#pragma unroll
+      for (int u = 0; u < NR; ++u) {
+        tp0[su * (kColWaves * 64)] = col_widen<VEC>(pre[u]);
+        su = (su + 1 < ulast_v) ? su + 1 : ulast_v;
+      }
+    }
 #pragma unroll
     for (int k = 0; k < kColParPerThread; ++k) prm[(int)threadIdx.x + kColThreads * k] = ppre[k];
   };
@@ -318,11 +344,22 @@ __global__ __launch_bounds__(kColThreads) void harp_col_kernel(
     col_ops<64, 1>(tile, prm, cp, wave, cidx);
     TO *wp = dst + (cur.row0 + (int64_t)wave * S) * ldd + cur.col;
     const int64_t wstep = (int64_t)kColWaves * S * ldd;
+    if (exact) {
 #pragma unroll
-    for (int u = 0; u < NR; ++u) {
-      if (!GUARD || wave + kColWaves * u < P)
-        col_store<TO, VEC>(wp, tp0[u * (kColWaves * 64)], cur.v0, cur.v1);
-      wp += wstep;
+      for (int u = 0; u < NR; ++u) {
+        if (!GUARD || wave + kColWaves * u < P)
+          col_store<TO, VEC>(wp, tp0[u * (kColWaves * 64)], cur.v0, cur.v1);
+        wp += wstep;
+      }
+    } else {
+      TO *wlast = wp + (int64_t)ulast_v * wstep;
+      int su = 0;
+#pragma unroll
+      for (int u = 0; u < NR; ++u) {
+        col_store<TO, VEC>(wp, tp0[su * (kColWaves * 64)], cur.v0, cur.v1);
+        wp = (wp + wstep < wlast) ? wp + wstep : wlast;
+        su = (su + 1 < ulast_v) ? su + 1 : ulast_v;
+      }
     }
   };
   // Every wait for requested rows inside the loop follows the same sequence (request, stages,
@@ -489,12 +526,15 @@ harp_status_t launch_col_tiles(const harp_plan *plan, const ColPass *dpass, cons
   const int64_t grid = (tiles + tpw - 1) / tpw;
   typedef void (*kern_t)(const ColPass *, const TI *, int64_t, TO *, int64_t, int64_t, unsigned,
                          unsigned, unsigned);
-  static const kern_t table[5] = {harp_col_kernel<TI, TO, false, 0>, harp_col_kernel<TI, TO, true, 0>,
+  static const kern_t table[7] = {harp_col_kernel<TI, TO, false, 0>, harp_col_kernel<TI, TO, true, 0>,
                                   harp_col_kernel<TI, TO, true, 32>, harp_col_kernel<TI, TO, true, 16>,
-                                  harp_col_kernel<TI, TO, true, 8>};
-  const int which = !fast ? (vec ? 1 : 0) : (hp.P == 128 ? 2 : (hp.P == 64 ? 3 : 4));
+                                  harp_col_kernel<TI, TO, true, 8>,  harp_col_kernel<TI, TO, true, 4>,
+                                  harp_col_kernel<TI, TO, true, 2>};
+  // unguarded: the variant with the fewest row steps per wave that covers P
+  const int which = !fast ? (vec ? 1 : 0)
+                          : (hp.P > 64 ? 2 : (hp.P > 32 ? 3 : (hp.P > 16 ? 4 : (hp.P > 8 ? 5 : 6))));
   const kern_t kern = table[which];
-  static thread_local int attr_done_dev[5] = {-1, -1, -1, -1, -1};   // per instantiation
+  static thread_local int attr_done_dev[7] = {-1, -1, -1, -1, -1, -1, -1};   // per instantiation
   if (attr_done_dev[which] != plan->device) {
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                             hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -518,7 +558,7 @@ harp_status_t launch_col_typed(const harp_plan *plan, const ColPass *dpass, cons
   const size_t ei = sizeof(TI), eo = sizeof(TO);
   const bool vec = (ncols % 2 == 0) && (lds_ % 2 == 0) && (ldd % 2 == 0) &&
                    ((uintptr_t)src % (2 * ei) == 0) && ((uintptr_t)dst % (2 * eo) == 0);
-  const bool shape_ok = vec && (hp.P == 128 || hp.P == 64 || hp.P == 32);
+  const bool shape_ok = vec && hp.P >= kColWaves && hp.P <= kColMaxP;
   const int64_t full = shape_ok ? (ncols / kColCols) * kColCols : 0;
   harp_status_t st = HARP_OK;
   if (full > 0)
@@ -592,19 +632,44 @@ bool build_col_passes(const harp_plan *plan, Direction dir, std::vector<ColPassH
   const int m = (int)st.size();
   const float *image = st[0].blocks;   // one allocation, stages back to back
   auto padded = [](int b) { return (b * b + 3) & ~3; };
+  // Partition of the stages into passes (stages i .. e-1 with prod(b) <= kColMaxP whose block
+  // values fit the budget): as few passes as possible -- each one reads and writes the whole
+  // matrix -- and among those partitions the one whose smallest tile is tallest (a greedy
+  // "fill every pass" split leaves the last pass with whatever remains, down to 2 or 3 rows
+  // per tile: 28672 = 7 * 2^12 ended in a pass of P = 2 that took three times as long as the
+  // other two together).  Ties go to the taller first pass.
+  auto fits = [&](int i0, int e0, int &Pout) {
+    int P = 1;
+    for (int t = i0; t < e0; ++t) {
+      if (P * st[t].b > kColMaxP) return false;
+      P *= st[t].b;
+    }
+    int par = 0;
+    for (int t = i0; t < e0; ++t) par += (P / st[t].b) * padded(st[t].b);
+    Pout = P;
+    return par <= kColMaxPar;
+  };
+  std::vector<int> best_n(m + 1, 1 << 20), best_min(m + 1, 0), best_e(m + 1, -1);
+  best_n[m] = 0;
+  best_min[m] = 1 << 30;
+  for (int i0 = m - 1; i0 >= 0; --i0) {
+    for (int e0 = m; e0 > i0; --e0) {
+      int P = 0;
+      if (!fits(i0, e0, P) || best_n[e0] >= (1 << 20)) continue;
+      const int n = best_n[e0] + 1, mn = std::min(P, best_min[e0]);
+      if (n < best_n[i0] || (n == best_n[i0] && mn > best_min[i0])) {
+        best_n[i0] = n;
+        best_min[i0] = mn;
+        best_e[i0] = e0;
+      }
+    }
+  }
+  if (best_e[0] < 0) return false;
   int i = 0;
   while (i < m) {
-    // the pass: stages i .. e-1 with prod(b) <= kColMaxP whose block values fit the budget
-    int e = i, P = 1;
-    while (e < m && P * st[e].b <= kColMaxP) {
-      const int Pn = P * st[e].b;
-      int par = 0;
-      for (int t = i; t <= e; ++t) par += (Pn / st[t].b) * padded(st[t].b);
-      if (par > kColMaxPar) break;
-      P = Pn;
-      ++e;
-    }
-    if (e == i) return false;
+    const int e = best_e[i];
+    int P = 0;
+    if (e <= i || !fits(i, e, P)) return false;
     int S = st[i].s;
     for (int t = i; t < e; ++t) S = std::min(S, st[t].s);
     out.emplace_back();

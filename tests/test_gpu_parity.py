@@ -691,7 +691,13 @@ def _plan_tuple(d, radices, blocks, signs):
                                          (240, [5, 6, 8], 34, [2, 17]), (96, [3, 2, 2, 2, 4], 130, [130 // 13, 13]),
                                          (384, [2, 2, 3, 2, 2, 2, 2, 2], 258, [2, 3, 43]),
                                          # plan_U with a radix above 8: transposed-copy path
-                                         (44, [2, 2, 11], 24, [2, 3, 4])])
+                                         (44, [2, 2, 11], 24, [2, 3, 4]),
+                                         # column passes whose tile height is not 32 / 64 / 128
+                                         # (28, 27, 21, 48 rows): unguarded kernel with repeated rows
+                                         (896, [2] * 7 + [7], 256, [2] * 8),
+                                         (1728, [8, 8, 3, 3, 3], 128, [2] * 7),
+                                         (1344, [7, 3, 8, 8], 384, [2] * 7 + [3]),
+                                         (1536, [3] + [2] * 9, 130, [2, 5, 13])])
 def test_rotate_weight_small_dense(harp, dtype, do, ru, di, rv):
     import torch
     rng = np.random.default_rng(do + di)
