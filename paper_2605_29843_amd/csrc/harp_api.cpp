@@ -238,6 +238,18 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
       if (large) small_only = false;
       chunk *= plan->radices[tb++];
     }
+    // A chunk of radix-2 stages followed by other small radices has no kernel of its own (the
+    // pipelined and wave kernels take radix-2 chains, the radix kernels radices 3..8): end it
+    // behind the radix-2 stages when those alone make a chunk of 256 or more, and stream the
+    // rest (13824 = 2^9 * 27, n = 2048: 193 -> 136 us).  Only for rows longer than the cap: up
+    // to 4096 the one-launch tile kernel measured as fast or faster (1536 .. 3840, and 3 us
+    // less at small batch sizes).
+    int t2 = 0;
+    while (t2 < tb && plan->radices[t2] == 2) ++t2;
+    if (d > kChunkCap && t2 < tb && t2 >= 8 && small_only) {
+      tb = t2;
+      chunk = (int64_t)1 << t2;
+    }
     if (tb == 0 || tb == m) return false;   // nothing to split: the fused program covers it
   }
   auto local = [&](int i) { return eff[i].t < tb; };
