@@ -94,6 +94,11 @@ def main():
     ap.add_argument("--decode", action="store_true",
                     help="also time the decode regime (n = 1..64 rows; stderr): median of 1000 "
                          "launches and the per-launch time of a HIP graph of 20 launches")
+    ap.add_argument("--survey", action="store_true",
+                    help="also time apply and apply_transpose (n = 2048, bf16 and f32) over the "
+                         "layer widths of the Llama-2 / Llama-3 families under the radix-2 and "
+                         "the greedy radix-8 schedules, and rotate_weight over their layer "
+                         "shapes (stderr)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also launch the library's plain copy kernel on one batch (known bytes), "
                          "the reference that scales rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
@@ -263,6 +268,64 @@ def main():
                   f"({gb / HBM_PEAK_GBS:.1%})", file=sys.stderr, flush=True)
         except Exception as e:  # noqa: BLE001
             print(f"[extra] grad_blocks: {e}", file=sys.stderr, flush=True)
+    if args.survey:
+        r2 = {4096: [2] * 12, 5120: [2] * 10 + [5], 8192: [2] * 13, 11008: [2] * 8 + [43],
+              13824: [2] * 9 + [3, 3, 3], 14336: [2] * 11 + [7], 28672: [2] * 12 + [7]}
+        g8 = {4096: [8] * 4, 5120: [8, 8, 8, 5, 2], 8192: [8, 8, 8, 8, 2], 11008: [8, 8, 4, 43],
+              13824: [8, 8, 8, 3, 3, 3], 14336: [8, 8, 8, 7, 4], 28672: [8, 8, 8, 8, 7]}
+        rng = np.random.default_rng(0)
+
+        def timed(fn, reps):
+            warm_clocks(fn, seconds=0.03)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(reps):
+                fn()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) * 1e3 / reps
+
+        for fam, sched in (("radix-2", r2), ("greedy-8", g8)):
+            for dd, rr in sched.items():
+                ps = harp.Plan(dd, rr, gi.make_blocks(dd, rr, "orth", rng), gi.make_signs(dd, rng))
+                for tdt in (torch.bfloat16, torch.float32):
+                    nb = max(2, min(8, int(400e6 / (2048 * dd * tdt.itemsize))))
+                    Xs = [torch.randn(2048, dd, device="cuda").to(tdt) for _ in range(nb)]
+                    Ys = [torch.empty_like(x) for x in Xs]
+                    cnt = [0]
+
+                    def fwd():
+                        harp.harp_apply(ps, Xs[cnt[0] % nb], Ys[cnt[0] % nb], stream)
+                        cnt[0] += 1
+
+                    def trn():
+                        harp.harp_apply_transpose(ps, Xs[cnt[0] % nb], Ys[cnt[0] % nb], stream)
+                        cnt[0] += 1
+                    tf, tt = timed(fwd, 100), timed(trn, 100)
+                    gbs = 2 * 2048 * dd * tdt.itemsize / 1e3   # bytes read + written, per us -> GB/s
+                    print(f"[survey] {fam:8s} d={dd:6d} {str(tdt)[6:]:8s} apply {tf:7.1f} us "
+                          f"({gbs / tf:5.0f} GB/s)  transpose {tt:7.1f} us ({gbs / tt:5.0f} GB/s)  "
+                          f"[{ps.kernel_name(2048)}]", file=sys.stderr, flush=True)
+                    del Xs, Ys
+                ps.destroy()
+            for do, di in ((4096, 4096), (11008, 4096), (4096, 11008), (5120, 13824), (13824, 5120),
+                           (14336, 4096), (4096, 14336), (8192, 28672), (28672, 8192)):
+                pu = harp.Plan(do, sched[do], gi.make_blocks(do, sched[do], "orth", rng),
+                               gi.make_signs(do, rng))
+                pv = harp.Plan(di, sched[di], gi.make_blocks(di, sched[di], "orth", rng),
+                               gi.make_signs(di, rng))
+                Wm = (torch.randn(do, di, device="cuda") * 0.02).to(torch.bfloat16)
+                Wo = torch.empty_like(Wm)
+                ws = torch.empty(max(1, harp.harp_rotate_weight_workspace_size(pu, pv, do, di,
+                                                                               harp.HARP_BF16)),
+                                 dtype=torch.uint8, device="cuda")
+                tf = timed(lambda: harp.harp_rotate_weight(pu, pv, Wm, Wo, ws, stream), 10)
+                ti = timed(lambda: harp.harp_rotate_weight_inverse(pu, pv, Wm, Wo, ws, stream), 10)
+                print(f"[survey] {fam:8s} rotate_weight W[{do} x {di}] bf16 {tf:7.0f} us  "
+                      f"inverse {ti:7.0f} us", file=sys.stderr, flush=True)
+                del Wm, Wo, ws
+                pu.destroy()
+                pv.destroy()
     if args.decode:
         for dd, rr in ((4096, [2] * 12), (12288, [2] * 12 + [3]), (14336, [2] * 11 + [7])):
             bb, ss = gi.processor(dd, rr, config=4)
