@@ -198,10 +198,11 @@ harp_status_t harp_plan_create_from_theta(harp_plan_t **out, int64_t d, int32_t 
  *   dK     host array of m DEVICE pointers; dK[t] receives D_t * b_t * b_t float32 values in
  *          the layout of harp_plan_create's blocks[t] (overwritten; zeros when n == 0).
  *   dX     device, [n, d] of type dt with leading dimension lddx, or NULL to skip it.
- *   workspace  device memory of at least harp_grad_blocks_workspace_size bytes ((m + 1) float32
- *          copies of the batch plus partial sums); may be NULL when that size is 0.
+ *   workspace  device memory of at least harp_grad_blocks_workspace_size bytes (up to m + 2
+ *          float32 copies of the batch plus partial sums); may be NULL when that size is 0.
  * Float32 arithmetic; the sum over rows is taken in a fixed order (bit-reproducible for the same
- * n).  Asynchronous on `stream`.  HARP_ERR_UNSUPPORTED for a schedule with a radix above 8.
+ * n).  Asynchronous on `stream`.  Every radix up to HARP_MAX_RADIX; stages of radix above 8 run
+ * on a plain one-value-per-thread kernel (correct, not tuned).
  */
 harp_status_t harp_grad_blocks_workspace_size(const harp_plan_t *plan, int64_t n, size_t *bytes);
 harp_status_t harp_grad_blocks(const harp_plan_t *plan, const void *X, int64_t ldx, const void *G,

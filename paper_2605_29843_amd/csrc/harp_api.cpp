@@ -843,11 +843,12 @@ harp_status_t harp_plan_create(harp_plan_t **out, int64_t d, int32_t m, const in
         plan->dev_signs = ds;
       }
     }
-    // Column-mode image (the plan as the U side of a weight rotation): per direction the dense
-    // effective blocks [d / b][b][b] of every stage in execution order, and the passes over them.
+    // Column-mode image (the plan as the U side of a weight rotation, and the blocks the
+    // gradient kernels read): per direction the dense effective blocks [d / b][b][b] of every
+    // stage in execution order, and -- when every radix is at most 8 -- the passes over them.
     bool col_ok = true;
     for (int t = 0; t < m; ++t) col_ok = col_ok && radices[t] <= 8;
-    for (int dir = 0; dir < 2 && st == HARP_OK && col_ok; ++dir) {
+    for (int dir = 0; dir < 2 && st == HARP_OK; ++dir) {
       std::vector<StageEff> eff;
       build_effective(plan, blk, signs, HARP_ALGO_GENERIC, (Direction)dir, false, eff);
       size_t total = 0;
@@ -869,7 +870,7 @@ harp_status_t harp_plan_create(harp_plan_t **out, int64_t d, int32_t m, const in
         st = HARP_ERR_DEVICE;
         break;
       }
-      if (!build_col_passes(plan, (Direction)dir, plan->colpass[dir])) {
+      if (!col_ok || !build_col_passes(plan, (Direction)dir, plan->colpass[dir])) {
         plan->colpass[dir].clear();
         continue;
       }

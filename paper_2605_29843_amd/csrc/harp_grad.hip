@@ -151,6 +151,60 @@ __global__ __launch_bounds__(kGradThreads) void harp_grad_bwd_kernel(
     partial[((size_t)blockIdx.y * (B * B) + v) * D + c] = acc[v];
 }
 
+// Radix 9..64 (the leftover prime of a schedule): a block no longer fits one thread's registers,
+// so thread (c, j) owns one column or row of it.  TR false: y[j] = sum_r x[r] K[r][j] (the stage
+// itself); TR true: y[j] = sum_r x[r] K[j][r] (the gradient passed back through it).  Out of
+// place.  Workgroup = 64 consecutive blocks c x 4 values of j; blockIdx.z covers the other j.
+template <bool TR>
+__global__ __launch_bounds__(kGradThreads) void harp_grad_apply_big_kernel(
+    const float *__restrict__ X, float *__restrict__ Y, int64_t ld, int64_t n, int rows,
+    const float *__restrict__ blocks, int D, int s, int b) {
+  const int c = blockIdx.x * 64 + (threadIdx.x & 63);
+  const int j = blockIdx.z * 4 + (threadIdx.x >> 6);
+  if (c >= D || j >= b) return;
+  float kv[HARP_MAX_RADIX];
+  const float *kb = blocks + (size_t)c * b * b;
+#pragma unroll
+  for (int r = 0; r < HARP_MAX_RADIX; ++r) kv[r] = (r < b) ? (TR ? kb[j * b + r] : kb[r * b + j]) : 0.f;
+  const int base = (c / s) * b * s + c % s;
+  const int64_t r0 = (int64_t)blockIdx.y * rows;
+  const int64_t r1 = (r0 + rows < n) ? r0 + rows : n;
+  for (int64_t row = r0; row < r1; ++row) {
+    const float *x = X + row * ld + base;
+    float acc = 0.f;
+#pragma unroll
+    for (int r = 0; r < HARP_MAX_RADIX; ++r)
+      if (r < b) acc = fmaf(x[(size_t)r * s], kv[r], acc);
+    Y[row * ld + base + (size_t)j * s] = acc;
+  }
+}
+
+// Thread (c, r2) accumulates column r2 of dK[c] over the rows of chunk blockIdx.y:
+// acc[r] += x[idx_r] g[idx_r2]; partial sums in the layout of the small-radix kernel.
+__global__ __launch_bounds__(kGradThreads) void harp_grad_dk_big_kernel(
+    const float *__restrict__ X, const float *__restrict__ Gm, int64_t ld, int64_t n, int rows,
+    int D, int s, int b, float *__restrict__ partial) {
+  const int c = blockIdx.x * 64 + (threadIdx.x & 63);
+  const int r2 = blockIdx.z * 4 + (threadIdx.x >> 6);
+  if (c >= D || r2 >= b) return;
+  float acc[HARP_MAX_RADIX];
+#pragma unroll
+  for (int r = 0; r < HARP_MAX_RADIX; ++r) acc[r] = 0.f;
+  const int base = (c / s) * b * s + c % s;
+  const int64_t r0 = (int64_t)blockIdx.y * rows;
+  const int64_t r1 = (r0 + rows < n) ? r0 + rows : n;
+  for (int64_t row = r0; row < r1; ++row) {
+    const float *x = X + row * ld + base;
+    const float gv = Gm[row * ld + base + (size_t)r2 * s];
+#pragma unroll
+    for (int r = 0; r < HARP_MAX_RADIX; ++r)
+      if (r < b) acc[r] = fmaf(x[(size_t)r * s], gv, acc[r]);
+  }
+#pragma unroll
+  for (int r = 0; r < HARP_MAX_RADIX; ++r)
+    if (r < b) partial[((size_t)blockIdx.y * (b * b) + r * b + r2) * D + c] = acc[r];
+}
+
 // Run of K radix-2 stages with strides s, 2s, .., 2^(K-1) s.  Item q = hi s + lo owns the
 // coordinates base + e s, e < 2^K, base = hi 2^K s + lo.  Stage i pairs e0 (bit i clear) with
 // e0 + 2^i; that pair is block c = (i0 / (2 s_i)) s_i + i0 % s_i of the stage, i0 = base + e0 s,
@@ -456,7 +510,8 @@ size_t grad_workspace_bytes(const harp_plan *plan, int64_t n) {
   for (int32_t b : plan->radices) bmax = std::max(bmax, (int)b);
   const size_t mat = (size_t)n * (size_t)plan->d * 4;
   const size_t nseg = grad_segments(plan).size();
-  return (nseg + 1) * mat + (size_t)grad_chunks(n) * (size_t)plan->d * bmax * 4;
+  // a stage of radix above 8 passes the gradient back out of place: one more matrix
+  return (nseg + 1 + (bmax > 8 ? 1 : 0)) * mat + (size_t)grad_chunks(n) * (size_t)plan->d * bmax * 4;
 }
 
 harp_status_t launch_grad(const harp_plan *plan, const void *X, int64_t ldx, const void *G,
@@ -469,9 +524,12 @@ harp_status_t launch_grad(const harp_plan *plan, const void *X, int64_t ldx, con
   const int nchunks = grad_chunks(n);
   const int rows = (int)((n + nchunks - 1) / nchunks);
   const size_t mat = (size_t)n * (size_t)d;
+  int bmax = 0;
+  for (int32_t b : plan->radices) bmax = std::max(bmax, (int)b);
   float *act = (float *)ws;                 // act[i] = input of segment i
-  float *g = act + (size_t)nseg * mat;      // gradient, updated in place
-  float *partial = g + mat;
+  float *g = act + (size_t)nseg * mat;      // gradient, updated in place (radix <= 8) ...
+  float *g2 = g + mat;                      // ... or into the other of two matrices (radix >= 9)
+  float *partial = g + (bmax > 8 ? 2 : 1) * mat;
   const size_t pstride = (size_t)nchunks * 4 * (size_t)(d / 2);   // one radix-2 stage's partials
   // 16-byte accesses of the stride-1 runs need the float32 copies on 16-byte boundaries
   const int aligned = ((uintptr_t)ws % 16 == 0) && (mat % 4 == 0);
@@ -501,6 +559,11 @@ harp_status_t launch_grad(const harp_plan *plan, const void *X, int64_t ldx, con
         else
           hipLaunchKernelGGL((harp_grad_fwd_run_kernel<2>), grid, dim3(kGradThreads), 0, st, in, out,
                              d, n, rows, run_of(seg[i]), nitems, cs.s, aligned);
+      } else if (cs.b > 8) {
+        const int D = (int)(d / cs.b);
+        hipLaunchKernelGGL((harp_grad_apply_big_kernel<false>),
+                           dim3((D + 63) / 64, nchunks, (cs.b + 3) / 4), dim3(kGradThreads), 0, st, in,
+                           out, d, n, rows, cs.blocks, D, cs.s, cs.b);
       } else {
         const int D = (int)(d / cs.b);
 #define HARP_GRAD_FWD(BB) launch_fwd<BB>(in, out, d, n, rows, nchunks, cs.blocks, D, cs.s, st)
@@ -522,6 +585,14 @@ harp_status_t launch_grad(const harp_plan *plan, const void *X, int64_t ldx, con
         else
           hipLaunchKernelGGL((harp_grad_bwd_run_kernel<2>), grid, dim3(kGradThreads), 0, st, in, g, d,
                              n, rows, run_of(seg[i]), nitems, cs.s, (int)(d / 2), partial, pstride, aligned);
+      } else if (cs.b > 8) {
+        const int D = (int)(d / cs.b);
+        const dim3 grid((D + 63) / 64, nchunks, (cs.b + 3) / 4);
+        hipLaunchKernelGGL(harp_grad_dk_big_kernel, grid, dim3(kGradThreads), 0, st, in, g, d, n, rows,
+                           D, cs.s, cs.b, partial);
+        hipLaunchKernelGGL((harp_grad_apply_big_kernel<true>), grid, dim3(kGradThreads), 0, st, g, g2,
+                           d, n, rows, cs.blocks, D, cs.s, cs.b);
+        std::swap(g, g2);
       } else {
         const int D = (int)(d / cs.b);
 #define HARP_GRAD_BWD(BB) launch_bwd<BB>(in, g, d, n, rows, nchunks, cs.blocks, D, cs.s, partial, st)

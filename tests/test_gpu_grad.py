@@ -44,7 +44,10 @@ def assert_dk_parity(dK, ref, X, G, what):
 @pytest.mark.parametrize("d,radices,n,kind", [
     (256, [2] * 8, 64, "orth"), (240, [5, 6, 8], 37, "orth"), (96, [3, 2, 2, 2, 4], 1, "generic"),
     (1024, [8, 8, 4, 4], 200, "orth"), (672, [7, 2, 2, 2, 2, 2, 3], 33, "generic"),
-    (4096, [2] * 12, 130, "orth")])
+    (4096, [2] * 12, 130, "orth"),
+    # a stage of radix above 8 (leftover prime): first, last, in the middle, with signs on it
+    (44, [4, 11], 9, "generic"), (344, [2, 2, 2, 43], 70, "orth"), (572, [13, 4, 11], 21, "generic"),
+    (1376, [2] * 5 + [43], 130, "orth"), (128, [2, 64], 5, "generic")])
 def test_grad_blocks_matches_the_oracle(harp, d, radices, n, kind, dtype):
     import torch
     rng = np.random.default_rng(d + n)
@@ -92,7 +95,7 @@ def test_grad_blocks_without_signs_and_with_padded_rows(harp):
     plan.destroy()
 
 
-def test_grad_blocks_empty_batch_and_unsupported_radix(harp):
+def test_grad_blocks_empty_batch(harp):
     import torch
     d, radices = 64, [4, 4, 4]
     rng = np.random.default_rng(1)
@@ -102,13 +105,6 @@ def test_grad_blocks_empty_batch_and_unsupported_radix(harp):
     torch.cuda.synchronize()
     assert all(float(k.abs().max()) == 0.0 for k in dK) and dX.shape == (0, d)
     plan.destroy()
-    d2, r2 = 44, [4, 11]
-    plan2 = harp.Plan(d2, r2, gi.make_blocks(d2, r2, "orth", rng), None)
-    X2 = torch.zeros(3, d2, device="cuda")
-    with pytest.raises(harp.HarpError) as e:
-        harp.harp_grad_blocks(plan2, X2, X2.clone())
-    assert e.value.status == harp.HARP_ERR_UNSUPPORTED
-    plan2.destroy()
 
 
 def test_grad_blocks_llama7b_shape_sampled(harp):
