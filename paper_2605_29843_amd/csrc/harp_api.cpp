@@ -151,6 +151,7 @@ bool build_effective(const harp_plan *plan, const std::vector<const float *> &bl
 }
 
 constexpr int64_t kChunkCap = 4096;   // largest on-chip chunk of a split program
+constexpr int kChainMax = 2;          // radix-3 stages per streamed trip
 
 // Split a run of `len` stages into ceil(len / kmax) nearly equal parts.
 void split_run(int len, int kmax, std::vector<int> &out) {
@@ -332,6 +333,56 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
     }
     if (pg.npass >= kMaxPasses) return false;
     if (b > HARP_MAX_RADIX) return false;
+    // Streamed part of a split program: two consecutive radix-3 stages make one trip through
+    // device memory instead of one each (13824 = 2^9 * 27: three trips become two).
+    if (fused && b == 3 && !local(i)) {
+      int kc = 1;
+      while (kc < kChainMax && i + kc < m && eff[i + kc].b == 3 && !local(i + kc) &&
+             (eff[i + kc].s == eff[i + kc - 1].s * 3 || eff[i + kc].s * 3 == eff[i + kc - 1].s) &&
+             (kc == 1 || ((eff[i + kc].s > eff[i + kc - 1].s) == (eff[i + 1].s > eff[i].s))))
+        ++kc;
+      if (kc >= 2) {
+        PassDesc &pc = pg.pass[pg.npass++];
+        const bool desc = eff[i + 1].s < eff[i].s;
+        int P = 1;
+        for (int e = 0; e < kc; ++e) P *= 3;
+        int64_t S = eff[i].s;
+        for (int e = 0; e < kc; ++e) S = std::min<int64_t>(S, eff[i + e].s);
+        const int NB = P / 3;
+        const int64_t nq = d / P;
+        pc.kind = PASS_SMALL_CHAIN;
+        pc.b = 3;
+        pc.k = kc;
+        pc.desc = desc ? 1 : 0;
+        pc.P = P;
+        pc.S = (int32_t)S;
+        pc.nq = (int32_t)nq;
+        pc.V = kc * NB * 9;
+        offsets.push_back(image.size());
+        image.resize(image.size() + (size_t)pc.V * nq);
+        float *img = image.data() + offsets.back();
+        for (int64_t q = 0; q < nq; ++q) {
+          const int64_t hi = q / S, lo = q % S;
+          const int64_t base = hi * P * S + lo;
+          for (int k = 0; k < kc; ++k) {
+            const StageEff &se = eff[i + k];   // execution order
+            int pdig = 0;                      // its digit inside the sub-tensor
+            for (int64_t t = S; t < se.s; t *= 3) ++pdig;
+            int sp = 1;
+            for (int e = 0; e < pdig; ++e) sp *= 3;
+            for (int o = 0; o < NB; ++o) {
+              const int j0 = (o / sp) * sp * 3 + o % sp;
+              const int64_t i0 = base + (int64_t)j0 * S;
+              const int64_t c = (i0 / (3 * se.s)) * se.s + i0 % se.s;
+              for (int v = 0; v < 9; ++v)
+                img[(size_t)((k * NB + o) * 9 + v) * nq + q] = se.dense[(size_t)c * 9 + v];
+            }
+          }
+        }
+        i += kc;
+        continue;
+      }
+    }
     PassDesc &pd = pg.pass[pg.npass++];
     if (local(i)) ++hp.n_chunk;
     const bool small = (fused && b >= 3 && b <= 8);

@@ -26,7 +26,13 @@ enum PassKind : int32_t {
   // k radix-2 stages as two shears with deferred output scales, 2 values (f0, f1) per pair:
   // (x0, x1) <- (x0 + f0 x1, x1 + f1 x0); _LD: the k-th stage is the program's dense last one
   PASS_POW2_SCALED = 5,
-  PASS_POW2_SCALED_LD = 6
+  PASS_POW2_SCALED_LD = 6,
+  // k = 2 consecutive radix-3 stages (adjacent digits) of a split program's streamed part
+  // in one trip: P = 3^k coordinates per sub-tensor, value ((e * 3^(k-1) + o) * 9 + r * 3 + r2)
+  // = entry [r][r2] of the block that the e-th stage in execution order uses for the
+  // combination o of the other digits (ascending); desc = 1: the stages run from the highest
+  // digit down
+  PASS_SMALL_CHAIN = 7
 };
 
 struct PassDesc {

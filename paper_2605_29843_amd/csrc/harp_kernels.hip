@@ -419,6 +419,39 @@ struct OpSmall {
   }
 };
 
+// K stages of radix B on adjacent digits of a sub-tensor of B^K coordinates (element j of the
+// thread = digits (e_0 .. e_{K-1}) of j in base B, digit p at stride B^p), in execution order
+// k = 0 .. K-1 on digit p = k (DESC: K-1-k).
+template <int B, int K, bool DESC>
+struct OpSmallChain {
+  static constexpr int ipow(int b, int k) { return k == 0 ? 1 : b * ipow(b, k - 1); }
+  static constexpr int P = ipow(B, K);
+  static constexpr int NB = P / B;           // blocks per stage inside the sub-tensor
+  static constexpr int NV = K * NB * B * B;
+  __device__ static __forceinline__ void apply(float (&x)[P], const float (&prm)[NV]) {
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+      const int p = DESC ? K - 1 - k : k;
+      const int sp = ipow(B, p);
+#pragma unroll
+      for (int o = 0; o < NB; ++o) {
+        const int j0 = (o / sp) * sp * B + o % sp;   // digit p = 0, the others = o
+        const float *kb = prm + (k * NB + o) * B * B;
+        float y[B];
+#pragma unroll
+        for (int r2 = 0; r2 < B; ++r2) {
+          float acc = x[j0] * kb[r2];
+#pragma unroll
+          for (int r = 1; r < B; ++r) acc = fmaf(x[j0 + r * sp], kb[r * B + r2], acc);
+          y[r2] = acc;
+        }
+#pragma unroll
+        for (int r = 0; r < B; ++r) x[j0 + r * sp] = y[r];
+      }
+    }
+  }
+};
+
 __device__ __forceinline__ float stream_load(const void *p, int64_t i, int bf16) {
   return bf16 ? widen_bf16(static_cast<const uint16_t *>(p)[i]) : static_cast<const float *>(p)[i];
 }
@@ -810,6 +843,14 @@ harp_status_t launch_stream_pass(const harp_plan *plan, const HostProgram &hp, i
     case PASS_POW2_SCALED_LD:
       return pd.desc ? launch_stream_pow2<true, 4>(plan, pd, X, ldx, ib, Y, ldy, ob, n, stream)
                      : launch_stream_pow2<false, 4>(plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
+    case PASS_SMALL_CHAIN:
+      if (pd.b != 3) return HARP_ERR_UNSUPPORTED;
+      if (pd.k == 2)
+        return pd.desc ? launch_stream_op<OpSmallChain<3, 2, true>>(plan, pd, X, ldx, ib, Y, ldy, ob, n, stream)
+                       : launch_stream_op<OpSmallChain<3, 2, false>>(plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);
+      // three stages per trip (27 coordinates and 243 block values per thread) were measured
+      // too: the kernel needs the whole register file and is slower than two trips
+      return HARP_ERR_UNSUPPORTED;
     case PASS_SMALL:
       switch (pd.b) {
         case 3: return launch_stream_op<OpSmall<3>>(plan, pd, X, ldx, ib, Y, ldy, ob, n, stream);

@@ -353,8 +353,9 @@ SPLIT_CASES = [
     (11008, [8, 8, 4, 43], 9), (12288, [2] * 12 + [3], 65), (14336, [2] * 11 + [7], 130),
     (28672, [2] * 12 + [7], 37), (16384, [4] * 7, 12), (24576, [2] * 13 + [3], 5),
     (65536, [2] * 16, 6), (3 * 4096 * 5, [2] * 12 + [3, 5], 4),
-    # chunk ends behind the radix-2 stages (512), three streamed radix-3 stages
-    (13824, [2] * 9 + [3, 3, 3], 21),
+    # chunk ends behind the radix-2 stages (512); streamed radix-3 stages, two per trip
+    (13824, [2] * 9 + [3, 3, 3], 21), (13824, [8, 8, 8, 3, 3, 3], 10), (4608, [2] * 9 + [3, 3], 33),
+    (41472, [2] * 9 + [3, 3, 3, 3], 3),
 ]
 
 
