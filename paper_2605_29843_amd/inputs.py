@@ -162,6 +162,11 @@ WORKLOADS = {
                                act=dict(dist="student_t", outlier_frac=0.01, outlier_scale=20.0)),
     "ffn_14336_r2x11_7": dict(config=3, n=2048, d=14336, radices=[2] * 11 + [7], dtype="bf16",
                               act=dict(dist="student_t", outlier_frac=0.01, outlier_scale=20.0)),
+    # Llama-2-13B widths (hidden 5120 = 2^10 * 5, FFN 13824 = 2^9 * 27): same recipe as config 3
+    "llama13b_5120_r2x10_5": dict(config=3, n=2048, d=5120, radices=[2] * 10 + [5], dtype="bf16",
+                                  act=dict(dist="student_t", outlier_frac=0.01, outlier_scale=20.0)),
+    "ffn13b_13824_r2x9_27": dict(config=3, n=2048, d=13824, radices=[2] * 9 + [3, 3, 3], dtype="bf16",
+                                 act=dict(dist="student_t", outlier_frac=0.01, outlier_scale=20.0)),
     "ffn70b_28672_r2x12_7": dict(config=5, n=4096, d=28672, radices=[2] * 12 + [7], dtype="bf16",
                                  act=dict(dist="student_t", outlier_frac=0.01, outlier_scale=20.0)),
 }

@@ -336,7 +336,8 @@ def test_full_size_4096(harp, name):
 
 
 # ------------------------------------------------------------------ config 3: mixed radix
-@pytest.mark.parametrize("name", ["down_11008_r2x8_43", "ffn_14336_r2x11_7"])
+@pytest.mark.parametrize("name", ["down_11008_r2x8_43", "ffn_14336_r2x11_7", "llama13b_5120_r2x10_5",
+                                  "ffn13b_13824_r2x9_27"])
 def test_full_size_mixed_radix(harp, name):
     _sampled_full_size(harp, name, n_sample=24)
 
