@@ -94,6 +94,10 @@ def main():
     ap.add_argument("--decode", action="store_true",
                     help="also time the decode regime (n = 1..64 rows; stderr): median of 1000 "
                          "launches and the per-launch time of a HIP graph of 20 launches")
+    ap.add_argument("--x8", action="store_true",
+                    help="add roofline.at_8x_rows: the same step on the batch repeated 8 times "
+                         "(off by default so that a profile of the default command holds "
+                         "launches of one size only)")
     ap.add_argument("--survey", action="store_true",
                     help="also time apply and apply_transpose (n = 2048, bf16 and f32) over the "
                          "layer widths of the Llama-2 / Llama-3 families under the radix-2 and "
@@ -187,7 +191,7 @@ def main():
                      "kernel": KERNEL_SYMBOL.get(plan.kernel_name(n), plan.kernel_name(n)), "avg_launch_us": kernel_us,
                      "algorithmic_bytes_per_launch": alg_bytes, "param_bytes": param_bytes},
     }
-    if args.rows is None and n * 8 * d * esz * 6 < 4e9:
+    if args.x8 and args.rows is None and n * 8 * d * esz * 6 < 4e9:
         # The same kernel on 8 n rows (the batch repeated): 8 times the rows per workgroup, so the
         # start-up of a launch weighs an eighth as much.  Context for `frac`, not the headline.
         nb8 = 2
