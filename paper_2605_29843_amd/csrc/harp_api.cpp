@@ -243,13 +243,17 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
     // pipelined and wave kernels take radix-2 chains, the radix kernels radices 3..8): end it
     // behind the radix-2 stages when those alone make a chunk of 256 or more, and stream the
     // rest (13824 = 2^9 * 27, n = 2048: 193 -> 136 us).  Only for rows longer than the cap: up
-    // to 4096 the one-launch tile kernel measured as fast or faster (1536 .. 3840, and 3 us
-    // less at small batch sizes).
+    // to 4096 the one-launch tile kernel measured as fast or faster (2304 .. 3840 with tails
+    // of radix 5, 7, 3*3, 3*5; every transposed program; and 3 us less at small batch sizes).
     int t2 = 0;
     while (t2 < tb && plan->radices[t2] == 2) ++t2;
-    if (d > kChunkCap && t2 < tb && t2 >= 8 && small_only) {
+    // [2 .. 2, 3] up to 4096 (768, 1536, 3072): kept as a second program for large forward
+    // batches (n = 2048: 19 -> 12, 21.5 -> 16.3, 27.9 -> 23.2 us).
+    const bool tail3 = (d <= kChunkCap && t2 == m - 1 && plan->radices[m - 1] == 3);
+    if ((d > kChunkCap || tail3) && t2 < tb && t2 >= 8 && small_only) {
       tb = t2;
       chunk = (int64_t)1 << t2;
+      hp.optional = tail3;
     }
     if (tb == 0 || tb == m) return false;   // nothing to split: the fused program covers it
   }
@@ -704,12 +708,12 @@ int choose_pipe_rows(const harp_plan *plan, int64_t n, int64_t nchunk, int chunk
 
 const HostProgram *select_program(const harp_plan *plan, Direction dir, int64_t n,
                                   const char **name) {
-  (void)n;
   int algo = plan->algo;
   if (algo == HARP_ALGO_AUTO) {
     // rows longer than one on-chip chunk: split at every batch size (measured down to one row:
     // two short launches beat one workgroup per row re-reading the whole parameter image)
-    if (plan->prog[HARP_ALGO_SPLIT][dir].ok)
+    const HostProgram &sp = plan->prog[HARP_ALGO_SPLIT][dir];
+    if (sp.ok && (!sp.optional || (dir == DIR_FWD && n >= 512)))
       algo = HARP_ALGO_SPLIT;
     else
       algo = plan->prog[HARP_ALGO_FUSED][dir].ok ? HARP_ALGO_FUSED : HARP_ALGO_GENERIC;

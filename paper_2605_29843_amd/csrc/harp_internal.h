@@ -72,6 +72,9 @@ struct HostProgram {
   int32_t chunk = 0;      // coordinates per on-chip chunk (== d when unsplit)
   int32_t n_chunk = 0;    // number of chunk-local passes
   bool chunk_first = true;
+  // split program of a row that also fits one chunk (radix-2 stages + one radix-3 stage): it
+  // only pays for large forward batches, see select_program
+  bool optional = false;
 };
 
 enum Direction { DIR_FWD = 0, DIR_TRN = 1 };
@@ -143,7 +146,7 @@ struct harp_plan {
   };
   mutable std::mutex scratch_mu;
   mutable std::vector<Scratch> scratch;
-  // column-mode image and passes per direction; empty when some radix exceeds 8
+  // column-mode image (every plan) and passes (empty when some radix exceeds 8) per direction
   std::vector<harp::ColStage> col[2];
   std::vector<harp::ColPassHost> colpass[2];
   const int8_t *dev_signs = nullptr;   // device copy of the signs (null: all +1)

@@ -417,6 +417,22 @@ def test_large_radix_stage_ends_the_chunk(harp, d, radices, n, dtype):
     run_case(harp, d, radices, n, dtype, seed=d + n, algo=2, act=X)
 
 
+@pytest.mark.parametrize("d,k", [(768, 8), (1536, 9), (3072, 10)])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_radix2_chain_with_a_radix3_tail_up_to_4096(harp, d, k, dtype):
+    """[2]*k + [3] in one chunk: large forward batches take the split program (wave kernel on the
+    radix-2 chunk + streamed radix-3 stage), small ones and the transposed direction the
+    one-launch kernel; both agree with the oracle."""
+    radices = [2] * k + [3]
+    rng = np.random.default_rng(d)
+    plan = harp.Plan(d, radices, gi.make_blocks(d, radices, "orth", rng))
+    assert plan.kernel_name(2048).startswith("split"), plan.kernel_name(2048)
+    assert not plan.kernel_name(64).startswith("split"), plan.kernel_name(64)
+    plan.destroy()
+    run_case(harp, d, radices, 600, dtype, seed=d + 1, act=gi.activations(600, d, config=3, bf16=(dtype == "bf16")))
+    run_case(harp, d, radices, 37, dtype, seed=d + 2, act=gi.activations(37, d, config=3, bf16=(dtype == "bf16")))
+
+
 def test_split_is_refused_when_there_is_nothing_to_split(harp):
     rng = np.random.default_rng(1)
     plan = harp.Plan(4096, [2] * 12, gi.make_blocks(4096, [2] * 12, "orth", rng))
