@@ -104,7 +104,8 @@ harp_status_t harp_plan_destroy(harp_plan_t *plan);
  *            enqueues work on it.
  * Plans whose rows are longer than 4096 coordinates, and plans in which a stage of radix >= 9
  * follows stages of radix <= 8 with a product that is a multiple of 16 and at least 64 (a
- * leftover prime at the end of the schedule), run in two or more launches through a
+ * leftover prime at the end of the schedule), and -- for forward calls with n >= 512 -- plans of
+ * radix-2 stages followed by one radix-3 stage, run in two or more launches through a
  * float32 intermediate of at most 128 MB that the plan allocates (hipMalloc) the first time
  * it is used on a stream and keeps, one per stream, until harp_plan_destroy.  That first
  * call may therefore block; inside a stream capture it returns HARP_ERR_UNSUPPORTED instead
