@@ -281,6 +281,12 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
       }
       std::vector<int> parts;
       split_run(len, lift ? 4 : 3, parts);
+      // Ten stages split (4, 3, 3).  In a transposed program the digits run downwards, so the
+      // pass on the four lowest digits -- the one whose layout is 16 consecutive coordinates
+      // per thread, in which the wave kernel can store without a further exchange -- has to
+      // come last: (3, 3, 4).
+      if (dir == DIR_TRN && lift && len == 10 && local(i) && chunk == 1024)
+        std::reverse(parts.begin(), parts.end());
       for (size_t pi = 0; pi < parts.size(); ++pi) {
         const int k = parts[pi];
         const bool ld = last_dense && pi + 1 == parts.size();

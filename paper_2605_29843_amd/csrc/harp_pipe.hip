@@ -595,42 +595,51 @@ harp_status_t launch_wave_inst(const WaveArgs &a) {
   return hipGetLastError() == hipSuccess ? HARP_OK : HARP_ERR_DEVICE;
 }
 
-template <typename TI, typename TO, int K0, int K1, int K2, bool SC>
-harp_status_t launch_wave_form(const WaveArgs &a, bool trn, bool ld) {
-  if (trn)
-    return ld ? launch_wave_inst<TI, TO, K0, K1, K2, true, true, SC>(a) : HARP_ERR_UNSUPPORTED;
-  return ld ? launch_wave_inst<TI, TO, K0, K1, K2, false, true, SC>(a)
-            : launch_wave_inst<TI, TO, K0, K1, K2, false, false, SC>(a);
+template <typename TI, typename TO, int K0, int K1, int K2, bool SC, bool TRN>
+harp_status_t launch_wave_form(const WaveArgs &a, bool ld) {
+  if (TRN)
+    return ld ? launch_wave_inst<TI, TO, K0, K1, K2, TRN, true, SC>(a) : HARP_ERR_UNSUPPORTED;
+  return ld ? launch_wave_inst<TI, TO, K0, K1, K2, TRN, true, SC>(a)
+            : launch_wave_inst<TI, TO, K0, K1, K2, TRN, (TRN ? true : false), SC>(a);
 }
 
-template <typename TI, typename TO, int K0, int K1, int K2>
-harp_status_t launch_wave_dir(const WaveArgs &a, bool trn, bool ld, bool sc) {
-  return sc ? launch_wave_form<TI, TO, K0, K1, K2, true>(a, trn, ld)
-            : launch_wave_form<TI, TO, K0, K1, K2, false>(a, trn, ld);
+template <typename TI, typename TO, int K0, int K1, int K2, bool TRN>
+harp_status_t launch_wave_dir(const WaveArgs &a, bool ld, bool sc) {
+  return sc ? launch_wave_form<TI, TO, K0, K1, K2, true, TRN>(a, ld)
+            : launch_wave_form<TI, TO, K0, K1, K2, false, TRN>(a, ld);
 }
 
 template <typename TI, typename TO>
 harp_status_t launch_wave_io(const WaveArgs &a, int logc, bool trn, bool ld, bool sc) {
-  if (logc == 8) return launch_wave_dir<TI, TO, 4, 4, 0>(a, trn, ld, sc);
-  if (logc == 9) return launch_wave_dir<TI, TO, 3, 3, 3>(a, trn, ld, sc);
-  if (logc == 10) return launch_wave_dir<TI, TO, 4, 3, 3>(a, trn, ld, sc);
+  if (logc == 8)
+    return trn ? launch_wave_dir<TI, TO, 4, 4, 0, true>(a, ld, sc)
+               : launch_wave_dir<TI, TO, 4, 4, 0, false>(a, ld, sc);
+  if (logc == 9)
+    return trn ? launch_wave_dir<TI, TO, 3, 3, 3, true>(a, ld, sc)
+               : launch_wave_dir<TI, TO, 3, 3, 3, false>(a, ld, sc);
+  if (logc == 10)   // the pass on the four lowest digits comes first going up, last going down
+    return trn ? launch_wave_dir<TI, TO, 3, 3, 4, true>(a, ld, sc)
+               : launch_wave_dir<TI, TO, 4, 3, 3, false>(a, ld, sc);
   return HARP_ERR_UNSUPPORTED;
 }
 
-// Passes [p0, p0+np) must be the lifted radix-2 passes (4,4), (3,3,3) or (4,3,3) of a chunk of
-// 256 / 512 / 1024 coordinates with the strides the kernel is compiled for.
+// Passes [p0, p0+np) must be the lifted radix-2 passes (4,4), (3,3,3) or (4,3,3) -- (3,3,4) in a
+// transposed program -- of a chunk of 256 / 512 / 1024 coordinates with the strides the kernel
+// is compiled for.
 bool wave_decode(const Program &pg, int p0, int np, int chunk, int *logc, bool *trn, bool *ld,
                  bool *sc) {
   if (np != 2 && np != 3) return false;
   const PassDesc *ps = pg.pass + p0;
   const int k0 = ps[0].k, k1 = ps[1].k, k2 = (np == 3) ? ps[2].k : 0;
   const int lc = k0 + k1 + k2;
+  const bool down = ps[0].desc != 0;
   if (!((lc == 8 && k0 == 4 && k1 == 4 && np == 2) || (lc == 9 && k0 == 3 && k1 == 3 && k2 == 3) ||
-        (lc == 10 && k0 == 4 && k1 == 3 && k2 == 3)))
+        (lc == 10 && !down && k0 == 4 && k1 == 3 && k2 == 3) ||
+        (lc == 10 && down && k0 == 3 && k1 == 3 && k2 == 4)))
     return false;
   if (chunk != (1 << lc)) return false;
   if (!pow2_family(ps, np, ld, sc)) return false;
-  *trn = ps[0].desc != 0;
+  *trn = down;
   for (int p = 1; p < np; ++p)
     if (ps[p].desc != ps[0].desc) return false;
   if (*trn && !*ld) return false;
