@@ -488,7 +488,7 @@ __device__ __forceinline__ void wave_exchange(float (&x)[16], float *buf, const 
 }
 
 template <typename TI, typename TO, int K0, int K1, int K2, bool TRN, bool LD, bool SC>
-__global__ __launch_bounds__(64) void harp_wave_kernel(const TI *__restrict__ X, int64_t ldx,
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void harp_wave_kernel(const TI *__restrict__ X, int64_t ldx,
                                                        TO *__restrict__ Y, int64_t ldy, int64_t n,
                                                        int R, int ngroups, int d,
                                                        const Program *__restrict__ progp, int p0) {
@@ -520,22 +520,27 @@ __global__ __launch_bounds__(64) void harp_wave_kernel(const TI *__restrict__ X,
   using In = RowIo<TI, true>;
   using Out = RowIo<TO, true>;
   constexpr int NRAW = In::NRAW;
-  uint32_t pre[2][NRAW];
+  // Rows requested ahead: two, but one when the input is float32 and there are three passes.
+  // That combination (the transposed chunk kernels of split programs) otherwise needs 264 to
+  // 277 registers per thread, past the 256 at which a second wave still fits on a SIMD, and ran
+  // 30-45 % slower than its forward counterpart for that reason alone.
+  constexpr int PF = (sizeof(TI) == 4 && THREE) ? 1 : 2;
+  uint32_t pre[PF][NRAW];
 #pragma unroll
-  for (int s = 0; s < 2; ++s) {
+  for (int s = 0; s < PF; ++s) {
 #pragma unroll
     for (int m = 0; m < NRAW; ++m) pre[s][m] = 0u;
     if (active && s < nr) In::load(X + (row0 + s) * ldx, goff, pre[s]);
   }
 
-  for (int r0 = 0; r0 < nr; r0 += 2) {
+  for (int r0 = 0; r0 < nr; r0 += PF) {
 #pragma unroll
-    for (int s = 0; s < 2; ++s) {
+    for (int s = 0; s < PF; ++s) {
       const int r = r0 + s;
       if (r >= nr) break;
       float x[16];
       In::unpack(pre[s], x);
-      if (active && r + 2 < nr) In::load(X + (row0 + r + 2) * ldx, goff, pre[s]);
+      if (active && r + PF < nr) In::load(X + (row0 + r + PF) * ldx, goff, pre[s]);
 
       if (!(K0 == 4 && LS0 == 0)) wave_exchange(x, buf, io, pa);
       lift_stages<K0, TRN, false, SC>(x, pa.prm);
