@@ -98,7 +98,7 @@ def main():
                     help="add roofline.at_8x_rows: the same step on the batch repeated 8 times "
                          "(off by default so that a profile of the default command holds "
                          "launches of one size only)")
-    ap.add_argument("--survey", action="store_true",
+    ap.add_argument("--shapes", action="store_true",
                     help="also time apply and apply_transpose (n = 2048, bf16 and f32) over the "
                          "layer widths of the Llama-2 / Llama-3 families under the radix-2 and "
                          "the greedy radix-8 schedules, and rotate_weight over their layer "
@@ -301,7 +301,7 @@ def main():
                   f"({gb / HBM_PEAK_GBS:.1%})", file=sys.stderr, flush=True)
         except Exception as e:  # noqa: BLE001
             print(f"[extra] grad_blocks: {e}", file=sys.stderr, flush=True)
-    if args.survey:
+    if args.shapes:
         r2 = {4096: [2] * 12, 5120: [2] * 10 + [5], 8192: [2] * 13, 11008: [2] * 8 + [43],
               13824: [2] * 9 + [3, 3, 3], 14336: [2] * 11 + [7], 28672: [2] * 12 + [7]}
         g8 = {4096: [8] * 4, 5120: [8, 8, 8, 5, 2], 8192: [8, 8, 8, 8, 2], 11008: [8, 8, 4, 43],
@@ -336,7 +336,7 @@ def main():
                         cnt[0] += 1
                     tf, tt = timed(fwd, 100), timed(trn, 100)
                     gbs = 2 * 2048 * dd * tdt.itemsize / 1e3   # bytes read + written, per us -> GB/s
-                    print(f"[survey] {fam:8s} d={dd:6d} {str(tdt)[6:]:8s} apply {tf:7.1f} us "
+                    print(f"[shapes] {fam:8s} d={dd:6d} {str(tdt)[6:]:8s} apply {tf:7.1f} us "
                           f"({gbs / tf:5.0f} GB/s)  transpose {tt:7.1f} us ({gbs / tt:5.0f} GB/s)  "
                           f"[{ps.kernel_name(2048)}]", file=sys.stderr, flush=True)
                     del Xs, Ys
@@ -354,7 +354,7 @@ def main():
                                  dtype=torch.uint8, device="cuda")
                 tf = timed(lambda: harp.harp_rotate_weight(pu, pv, Wm, Wo, ws, stream), 10)
                 ti = timed(lambda: harp.harp_rotate_weight_inverse(pu, pv, Wm, Wo, ws, stream), 10)
-                print(f"[survey] {fam:8s} rotate_weight W[{do} x {di}] bf16 {tf:7.0f} us  "
+                print(f"[shapes] {fam:8s} rotate_weight W[{do} x {di}] bf16 {tf:7.0f} us  "
                       f"inverse {ti:7.0f} us", file=sys.stderr, flush=True)
                 del Wm, Wo, ws
                 pu.destroy()
