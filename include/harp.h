@@ -203,7 +203,7 @@ harp_status_t harp_plan_create_from_theta(harp_plan_t **out, int64_t d, int32_t 
  *          float32 copies of the batch plus partial sums); may be NULL when that size is 0.
  * Float32 arithmetic; the sum over rows is taken in a fixed order (bit-reproducible for the same
  * n).  Asynchronous on `stream`.  Every radix up to HARP_MAX_RADIX; stages of radix above 8 run
- * on a plain one-value-per-thread kernel (correct, not tuned).
+ * on a plain one-value-per-thread kernel.
  */
 harp_status_t harp_grad_blocks_workspace_size(const harp_plan_t *plan, int64_t n, size_t *bytes);
 harp_status_t harp_grad_blocks(const harp_plan_t *plan, const void *X, int64_t ldx, const void *G,

@@ -155,55 +155,77 @@ __global__ __launch_bounds__(kGradThreads) void harp_grad_bwd_kernel(
 // so thread (c, j) owns one column or row of it.  TR false: y[j] = sum_r x[r] K[r][j] (the stage
 // itself); TR true: y[j] = sum_r x[r] K[j][r] (the gradient passed back through it).  Out of
 // place.  Workgroup = 64 consecutive blocks c x 4 values of j; blockIdx.z covers the other j.
-template <bool TR>
+// BMAX = the radix rounded up to a multiple of 16: the loads of a row are unconditional (index
+// clamped to the last coordinate of the block, value replaced by zero), so that all of them are
+// in flight together; under a per-load condition each one was waited for before the next was
+// issued and the three launches of the radix-43 stage of 11008 took 1 ms each.
+template <int BMAX, bool TR>
 __global__ __launch_bounds__(kGradThreads) void harp_grad_apply_big_kernel(
     const float *__restrict__ X, float *__restrict__ Y, int64_t ld, int64_t n, int rows,
     const float *__restrict__ blocks, int D, int s, int b) {
   const int c = blockIdx.x * 64 + (threadIdx.x & 63);
   const int j = blockIdx.z * 4 + (threadIdx.x >> 6);
   if (c >= D || j >= b) return;
-  float kv[HARP_MAX_RADIX];
+  float kv[BMAX];
   const float *kb = blocks + (size_t)c * b * b;
 #pragma unroll
-  for (int r = 0; r < HARP_MAX_RADIX; ++r) kv[r] = (r < b) ? (TR ? kb[j * b + r] : kb[r * b + j]) : 0.f;
+  for (int r = 0; r < BMAX; ++r) {
+    const int rc = r < b ? r : b - 1;
+    const float v = TR ? kb[j * b + rc] : kb[rc * b + j];
+    kv[r] = r < b ? v : 0.f;
+  }
   const int base = (c / s) * b * s + c % s;
   const int64_t r0 = (int64_t)blockIdx.y * rows;
   const int64_t r1 = (r0 + rows < n) ? r0 + rows : n;
   for (int64_t row = r0; row < r1; ++row) {
     const float *x = X + row * ld + base;
+    float xv[BMAX];
+#pragma unroll
+    for (int r = 0; r < BMAX; ++r) xv[r] = x[(size_t)(r < b ? r : b - 1) * s];
     float acc = 0.f;
 #pragma unroll
-    for (int r = 0; r < HARP_MAX_RADIX; ++r)
-      if (r < b) acc = fmaf(x[(size_t)r * s], kv[r], acc);
+    for (int r = 0; r < BMAX; ++r) acc = fmaf(r < b ? xv[r] : 0.f, kv[r], acc);
     Y[row * ld + base + (size_t)j * s] = acc;
   }
 }
 
 // Thread (c, r2) accumulates column r2 of dK[c] over the rows of chunk blockIdx.y:
 // acc[r] += x[idx_r] g[idx_r2]; partial sums in the layout of the small-radix kernel.
+template <int BMAX>
 __global__ __launch_bounds__(kGradThreads) void harp_grad_dk_big_kernel(
     const float *__restrict__ X, const float *__restrict__ Gm, int64_t ld, int64_t n, int rows,
     int D, int s, int b, float *__restrict__ partial) {
   const int c = blockIdx.x * 64 + (threadIdx.x & 63);
   const int r2 = blockIdx.z * 4 + (threadIdx.x >> 6);
   if (c >= D || r2 >= b) return;
-  float acc[HARP_MAX_RADIX];
+  float acc[BMAX];
 #pragma unroll
-  for (int r = 0; r < HARP_MAX_RADIX; ++r) acc[r] = 0.f;
+  for (int r = 0; r < BMAX; ++r) acc[r] = 0.f;
   const int base = (c / s) * b * s + c % s;
   const int64_t r0 = (int64_t)blockIdx.y * rows;
   const int64_t r1 = (r0 + rows < n) ? r0 + rows : n;
   for (int64_t row = r0; row < r1; ++row) {
     const float *x = X + row * ld + base;
     const float gv = Gm[row * ld + base + (size_t)r2 * s];
+    float xv[BMAX];
 #pragma unroll
-    for (int r = 0; r < HARP_MAX_RADIX; ++r)
-      if (r < b) acc[r] = fmaf(x[(size_t)r * s], gv, acc[r]);
+    for (int r = 0; r < BMAX; ++r) xv[r] = x[(size_t)(r < b ? r : b - 1) * s];
+#pragma unroll
+    for (int r = 0; r < BMAX; ++r) acc[r] = fmaf(xv[r], gv, acc[r]);   // r >= b: never stored
   }
 #pragma unroll
-  for (int r = 0; r < HARP_MAX_RADIX; ++r)
+  for (int r = 0; r < BMAX; ++r)
     if (r < b) partial[((size_t)blockIdx.y * (b * b) + r * b + r2) * D + c] = acc[r];
 }
+
+// the instantiation whose BMAX covers radix b
+#define HARP_GRAD_BIG(b, CALL)            \
+  do {                                    \
+    if ((b) <= 16) { CALL(16); }          \
+    else if ((b) <= 32) { CALL(32); }     \
+    else if ((b) <= 48) { CALL(48); }     \
+    else { CALL(64); }                    \
+  } while (0)
 
 // Run of K radix-2 stages with strides s, 2s, .., 2^(K-1) s.  Item q = hi s + lo owns the
 // coordinates base + e s, e < 2^K, base = hi 2^K s + lo.  Stage i pairs e0 (bit i clear) with
@@ -505,13 +527,27 @@ static std::vector<GradSegment> grad_segments(const harp_plan *plan) {
   return seg;
 }
 
+// Stages of radix above 8 take longer row chunks: blockIdx.z already supplies parallelism, and a
+// chunk costs one read of the block column per thread and b * b partial sums per block.
+static int grad_big_rows(int64_t n) {
+  const int nchunks = grad_chunks(n);
+  return std::max((int)((n + nchunks - 1) / nchunks), 64);
+}
+static int grad_big_chunks(int64_t n) {
+  const int rb = grad_big_rows(n);
+  return (int)std::max<int64_t>(1, (n + rb - 1) / rb);
+}
+
 size_t grad_workspace_bytes(const harp_plan *plan, int64_t n) {
-  int bmax = 6;   // a run of three radix-2 stages leaves 3 * (d / 2) * 4 partial values per chunk
-  for (int32_t b : plan->radices) bmax = std::max(bmax, (int)b);
+  int bsmall = 6;   // a run of three radix-2 stages leaves 3 * (d / 2) * 4 partial values per chunk
+  int bbig = 0;
+  for (int32_t b : plan->radices) (b > 8 ? bbig : bsmall) = std::max(b > 8 ? bbig : bsmall, (int)b);
   const size_t mat = (size_t)n * (size_t)plan->d * 4;
   const size_t nseg = grad_segments(plan).size();
+  const size_t partial = std::max((size_t)grad_chunks(n) * bsmall, (size_t)grad_big_chunks(n) * bbig) *
+                         (size_t)plan->d * 4;
   // a stage of radix above 8 passes the gradient back out of place: one more matrix
-  return (nseg + 1 + (bmax > 8 ? 1 : 0)) * mat + (size_t)grad_chunks(n) * (size_t)plan->d * bmax * 4;
+  return (nseg + 1 + (bbig > 0 ? 1 : 0)) * mat + partial;
 }
 
 harp_status_t launch_grad(const harp_plan *plan, const void *X, int64_t ldx, const void *G,
@@ -523,6 +559,8 @@ harp_status_t launch_grad(const harp_plan *plan, const void *X, int64_t ldx, con
   const int64_t d = plan->d;
   const int nchunks = grad_chunks(n);
   const int rows = (int)((n + nchunks - 1) / nchunks);
+  const int rows_big = grad_big_rows(n);
+  const int nchunks_big = grad_big_chunks(n);
   const size_t mat = (size_t)n * (size_t)d;
   int bmax = 0;
   for (int32_t b : plan->radices) bmax = std::max(bmax, (int)b);
@@ -561,9 +599,12 @@ harp_status_t launch_grad(const harp_plan *plan, const void *X, int64_t ldx, con
                              d, n, rows, run_of(seg[i]), nitems, cs.s, aligned);
       } else if (cs.b > 8) {
         const int D = (int)(d / cs.b);
-        hipLaunchKernelGGL((harp_grad_apply_big_kernel<false>),
-                           dim3((D + 63) / 64, nchunks, (cs.b + 3) / 4), dim3(kGradThreads), 0, st, in,
-                           out, d, n, rows, cs.blocks, D, cs.s, cs.b);
+#define HARP_GRAD_BIG_FWD(BM)                                                                     \
+  hipLaunchKernelGGL((harp_grad_apply_big_kernel<BM, false>),                                     \
+                     dim3((D + 63) / 64, nchunks_big, (cs.b + 3) / 4), dim3(kGradThreads), 0, st, \
+                     in, out, d, n, rows_big, cs.blocks, D, cs.s, cs.b)
+        HARP_GRAD_BIG(cs.b, HARP_GRAD_BIG_FWD);
+#undef HARP_GRAD_BIG_FWD
       } else {
         const int D = (int)(d / cs.b);
 #define HARP_GRAD_FWD(BB) launch_fwd<BB>(in, out, d, n, rows, nchunks, cs.blocks, D, cs.s, st)
@@ -587,11 +628,14 @@ harp_status_t launch_grad(const harp_plan *plan, const void *X, int64_t ldx, con
                              n, rows, run_of(seg[i]), nitems, cs.s, (int)(d / 2), partial, pstride, aligned);
       } else if (cs.b > 8) {
         const int D = (int)(d / cs.b);
-        const dim3 grid((D + 63) / 64, nchunks, (cs.b + 3) / 4);
-        hipLaunchKernelGGL(harp_grad_dk_big_kernel, grid, dim3(kGradThreads), 0, st, in, g, d, n, rows,
-                           D, cs.s, cs.b, partial);
-        hipLaunchKernelGGL((harp_grad_apply_big_kernel<true>), grid, dim3(kGradThreads), 0, st, g, g2,
-                           d, n, rows, cs.blocks, D, cs.s, cs.b);
+        const dim3 grid((D + 63) / 64, nchunks_big, (cs.b + 3) / 4);
+#define HARP_GRAD_BIG_BWD(BM)                                                                      \
+  hipLaunchKernelGGL((harp_grad_dk_big_kernel<BM>), grid, dim3(kGradThreads), 0, st, in, g, d, n,  \
+                     rows_big, D, cs.s, cs.b, partial);                                            \
+  hipLaunchKernelGGL((harp_grad_apply_big_kernel<BM, true>), grid, dim3(kGradThreads), 0, st, g,   \
+                     g2, d, n, rows_big, cs.blocks, D, cs.s, cs.b)
+        HARP_GRAD_BIG(cs.b, HARP_GRAD_BIG_BWD);
+#undef HARP_GRAD_BIG_BWD
         std::swap(g, g2);
       } else {
         const int D = (int)(d / cs.b);
@@ -607,7 +651,8 @@ harp_status_t launch_grad(const harp_plan *plan, const void *X, int64_t ldx, con
       const int64_t total = (int64_t)D * b * b;
       const unsigned gx = (unsigned)std::min<int64_t>((total + 31) / 32, 8192);
       hipLaunchKernelGGL(harp_grad_reduce_kernel, dim3(gx), dim3(kGradThreads), 0, st,
-                         partial + (size_t)j * pstride, n > 0 ? nchunks : 0, D, b,
+                         partial + (size_t)j * pstride,
+                         n > 0 ? (b > 8 ? nchunks_big : nchunks) : 0, D, b,
                          t == 0 ? plan->dev_signs : nullptr, dK[t]);
     }
   }
