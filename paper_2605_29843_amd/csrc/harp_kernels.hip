@@ -222,8 +222,8 @@ __device__ __forceinline__ void pass_generic(float *tile, int d, int nr, const P
       const float *pp = params + (size_t)r2 * nqg + qoff + q;
       float acc = 0.0f;
 #pragma unroll
-      for (int r = 0; r < BMAX; ++r)
-        if (r < b) acc = fmaf(x[r], pp[(size_t)r * b * nqg], acc);
+      for (int r = 0; r < BMAX; ++r)   // unconditional loads (x[r] is zero past the radix): all in flight
+        acc = fmaf(x[r], pp[(size_t)(r < b ? r : b - 1) * b * nqg], acc);
       t[r2 * S] = acc;
     }
   }
@@ -280,6 +280,8 @@ __device__ __forceinline__ void run_pass(float *tile, int d, int nr, const PassD
     default:
       if (pd.b <= 8) pass_generic<8>(tile, d, nr, pd, kch, tid, nt);
       else if (pd.b <= 16) pass_generic<16>(tile, d, nr, pd, kch, tid, nt);
+      else if (pd.b <= 32) pass_generic<32>(tile, d, nr, pd, kch, tid, nt);
+      else if (pd.b <= 48) pass_generic<48>(tile, d, nr, pd, kch, tid, nt);
       else pass_generic<64>(tile, d, nr, pd, kch, tid, nt);
       break;
   }
@@ -545,14 +547,16 @@ __global__ __launch_bounds__(256) void harp_stream_generic_kernel(
   for (int64_t row = r0; row < r1; ++row) {
     float x[BMAX];
 #pragma unroll
-    for (int r = 0; r < BMAX; ++r)
-      x[r] = (r < b) ? stream_load(X, row * ldx + base + (int64_t)r * S, in_bf16) : 0.0f;
+    for (int r = 0; r < BMAX; ++r) {
+      const float v = stream_load(X, row * ldx + base + (int64_t)(r < b ? r : b - 1) * S, in_bf16);
+      x[r] = (r < b) ? v : 0.0f;
+    }
     for (int r2 = 0; r2 < b; ++r2) {
       const float *pp = pd.params + (size_t)r2 * nq + q;
       float acc = 0.0f;
 #pragma unroll
-      for (int r = 0; r < BMAX; ++r)
-        if (r < b) acc = fmaf(x[r], pp[(size_t)r * b * nq], acc);
+      for (int r = 0; r < BMAX; ++r)   // unconditional loads (x[r] is zero past the radix)
+        acc = fmaf(x[r], pp[(size_t)(r < b ? r : b - 1) * b * nq], acc);
       stream_store(Y, row * ldy + base + (int64_t)r2 * S, out_bf16, acc);
     }
   }
