@@ -433,6 +433,17 @@ def test_radix2_chain_with_a_radix3_tail_up_to_4096(harp, d, k, dtype):
     run_case(harp, d, radices, 37, dtype, seed=d + 2, act=gi.activations(37, d, config=3, bf16=(dtype == "bf16")))
 
 
+def test_chunk_of_a_llama13b_ffn_row_ends_behind_its_radix2_stages(harp):
+    """13824 = 2^9 * 27: the default program is the wave kernel on 512-coordinate chunks plus
+    streamed radix-3 stages (two of them in one trip), not the general tile kernel on 1536."""
+    d, radices = 13824, [2] * 9 + [3, 3, 3]
+    rng = np.random.default_rng(7)
+    plan = harp.Plan(d, radices, gi.make_blocks(d, radices, "orth", rng))
+    assert plan.kernel_name(2048) == "split_wave_stream", plan.kernel_name(2048)
+    plan.destroy()
+    run_case(harp, d, radices, 19, "f32", seed=77, act=gi.activations(19, d, config=3, bf16=False))
+
+
 def test_split_is_refused_when_there_is_nothing_to_split(harp):
     rng = np.random.default_rng(1)
     plan = harp.Plan(4096, [2] * 12, gi.make_blocks(4096, [2] * 12, "orth", rng))
