@@ -3,14 +3,15 @@
  *
  * A HARP processor (paper Sec. 3, Eq. (6)-(8), Alg. 1) is a product of m sparse
  * block-orthogonal stride stages under a Mixed-Radix schedule b = (b_0..b_{m-1}),
- * prod b_t = d, together with a +-1 sign vector sigma (Sec. 3, "diagonal Rademacher
- * sign flips"; Assumption 1(iv)).  With s_t = prod_{j<t} b_j and g_t = d / (b_t s_t),
+ * prod b_t = d, together with a +-1 sign vector sigma (Sec. 3, the random sign
+ * diagonals; Assumption 1(iv)).  With s_t = prod_{j<t} b_j and g_t = d / (b_t s_t),
  * stage t takes, for every alpha < g_t and beta < s_t, the b_t coordinates
  *
  *        alpha * b_t * s_t + r * s_t + beta,      r = 0 .. b_t - 1     (App. A, Lemma 1)
  *
  * as a row vector v and replaces them by v * K_t[c], c = alpha * s_t + beta, where
- * K_t[c] is a dense b_t x b_t block (Alg. 1, "view K_t as [g, s, b, b]").  Stage 0 is
+ * K_t[c] is a dense b_t x b_t block (Alg. 1, the step that views the stage's kernels per
+ * group and stride offset).  Stage 0 is
  * applied to the data first (Alg. 1 loop order).  The processor's matrix U is defined by
  *
  *        apply(x) = x U = T(x .* sigma),        T = stage_{m-1} o ... o stage_0,

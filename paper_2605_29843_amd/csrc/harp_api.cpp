@@ -455,12 +455,25 @@ harp_status_t check_apply_args(const harp_plan_t *plan, const void *X, int64_t l
 
 size_t esize(harp_dtype_t dt) { return dt == HARP_BF16 ? 2 : 4; }
 
-// The plan's float32 intermediate for `stream`, at least `bytes` long.  Allocated on first use
-// (a synchronous hipMalloc, so not while the stream is being captured into a graph: warm the
-// plan up once before capturing) and kept until the plan is destroyed.  Per-call stream-ordered
-// allocation was measured first: it added two stream operations to every call, 29 us per call
-// on a 2-kernel program against 11 us of kernel time.
-harp_status_t plan_scratch(const harp_plan_t *plan, hipStream_t stream, size_t bytes, float **out) {
+// Rows of one slab of a split program's float32 intermediate: 128 MB (the measured optimum of
+// 32 .. 512 MB on the 14336 / 28672 shapes), a multiple of 256 rows when that many fit.
+int64_t slab_rows_cap(int64_t d) {
+  int64_t slab = ((int64_t)128 << 20) / (d * 4);
+  if (slab >= 512) slab = (slab / 256) * 256;
+  if (slab < 1) slab = 1;
+  return slab;
+}
+
+// The plan's float32 intermediate for `stream`, at least `bytes` long (bytes <= cap = one full
+// slab).  The first use on a stream allocates what the call needs, but at least 8 MB; a later
+// call that needs more allocates the cap, once, and the outgrown buffer is kept until the plan is
+// destroyed (queued launches and captured graphs still point at it).  So a stream sees at most
+// two hipMalloc calls, nothing is freed and the stream is never waited for.  hipMalloc is not
+// allowed while the stream is being captured: warm the plan up with the largest batch first.
+// Per-call stream-ordered allocation was measured first: it added two stream operations to
+// every call, 29 us per call on a 2-kernel program against 11 us of kernel time.
+harp_status_t plan_scratch(const harp_plan_t *plan, hipStream_t stream, size_t bytes, size_t cap,
+                           float **out) {
   std::lock_guard<std::mutex> lock(plan->scratch_mu);
   harp_plan::Scratch *slot = nullptr;
   for (auto &sc : plan->scratch)
@@ -475,24 +488,19 @@ harp_status_t plan_scratch(const harp_plan_t *plan, hipStream_t stream, size_t b
     return HARP_ERR_DEVICE;
   }
   if (cs != hipStreamCaptureStatusNone) return HARP_ERR_UNSUPPORTED;
-  if (slot) {   // too small: queued work on the stream may still use it
-    if (hipStreamSynchronize(stream) != hipSuccess || hipFree(slot->ptr) != hipSuccess) {
-      (void)hipGetLastError();
-      return HARP_ERR_DEVICE;
-    }
-    slot->ptr = nullptr;
-    slot->bytes = 0;
-  }
+  size_t want = slot ? cap : std::min(cap, std::max(bytes, (size_t)8 << 20));
+  if (want < bytes) want = bytes;
   float *p = nullptr;
-  if (hipMalloc((void **)&p, bytes) != hipSuccess) {
+  if (hipMalloc((void **)&p, want) != hipSuccess) {
     (void)hipGetLastError();
     return HARP_ERR_OOM;
   }
   if (slot) {
+    plan->retired.push_back(slot->ptr);
     slot->ptr = p;
-    slot->bytes = bytes;
+    slot->bytes = want;
   } else {
-    plan->scratch.push_back(harp_plan::Scratch{stream, p, bytes});
+    plan->scratch.push_back(harp_plan::Scratch{stream, p, want});
   }
   *out = p;
   return HARP_OK;
@@ -530,13 +538,10 @@ harp_status_t apply_dir(const harp_plan_t *plan, Direction dir, const void *X, i
   // through a float32 intermediate Z.  Rows are processed in slabs so that Z stays small
   // (it is written by one launch and read by the next: cache resident).
   const int64_t d = plan->d;
-  const int64_t slab_mb = 128;   // measured optimum of 32 .. 512 MB on the 14336 / 28672 shapes
-  int64_t slab = (slab_mb << 20) / (d * 4);
-  if (slab >= 512) slab = (slab / 256) * 256;
-  if (slab < 1) slab = 1;
-  if (slab > n) slab = n;
+  const int64_t slab_cap = slab_rows_cap(d);
+  const int64_t slab = slab_cap > n ? n : slab_cap;
   float *Z = nullptr;
-  harp_status_t zst = plan_scratch(plan, stream, (size_t)slab * d * 4, &Z);
+  harp_status_t zst = plan_scratch(plan, stream, (size_t)slab * d * 4, (size_t)slab_cap * d * 4, &Z);
   if (zst != HARP_OK) return zst;
   const int nstream = np - hp.n_chunk;
   const int nseg = nstream + 1;
@@ -764,6 +769,10 @@ harp_status_t harp_plan_create(harp_plan_t **out, int64_t d, int32_t m, const in
   try {
     plan->d = d;
     plan->m = m;
+    {
+      const char *e = getenv("HARP_NO_MFMA");   // read once, here: launches never look at the environment
+      plan->no_mfma = e && *e && atoi(e) != 0;
+    }
     plan->radices.assign(radices, radices + m);
     plan->strides.resize(m);
     int64_t s = 1;
@@ -980,6 +989,8 @@ harp_status_t harp_plan_destroy(harp_plan_t *plan) {
     if (p && hipFree(p) != hipSuccess) st = HARP_ERR_DEVICE;
   for (auto &sc : plan->scratch)
     if (sc.ptr && hipFree(sc.ptr) != hipSuccess) st = HARP_ERR_DEVICE;
+  for (void *p : plan->retired)
+    if (p && hipFree(p) != hipSuccess) st = HARP_ERR_DEVICE;
   delete plan;
   return st;
 }
@@ -1006,8 +1017,12 @@ harp_status_t harp_rotate_weight_workspace_size(const harp_plan_t *plan_U,
   if (d_out < 0 || d_in < 0) return HARP_ERR_INVALID_ARG;
   if (plan_U && plan_U->d != d_out) return HARP_ERR_INVALID_ARG;
   if (plan_V && plan_V->d != d_in) return HARP_ERR_INVALID_ARG;
+  // One float32 copy of the matrix when plan_U runs as column passes along the row index (every
+  // radix <= 8); the transposing path (a radix above 8 in plan_U) needs a second one for the
+  // transposed copy when plan_V is given too.
   const size_t mat = (size_t)d_out * (size_t)d_in * 4;
-  *bytes = !plan_U ? 0 : (plan_V ? 2 * mat : mat);
+  const bool col_path = plan_U && !plan_U->colpass[0].empty() && !plan_U->colpass[1].empty();
+  *bytes = !plan_U ? 0 : ((plan_V && !col_path) ? 2 * mat : mat);
   return HARP_OK;
 }
 
@@ -1054,28 +1069,46 @@ harp_status_t harp_grad_blocks(const harp_plan_t *plan, const void *X, int64_t l
   return launch_grad(plan, X, ldx, G, ldg, n, dt, dK, dX, lddx, workspace, (hipStream_t)stream);
 }
 
+// Largest divisor of r in [2, cap], or 0 when r has none there.  Divisors come in pairs
+// (q, r / q) with q <= sqrt(r), so one walk over q sees every one of them.
+static int64_t largest_divisor_at_most(int64_t r, int64_t cap) {
+  if (r < 2) return 0;
+  if (r <= cap) return r;
+  int64_t best = 0;
+  for (int64_t q = 1; q * q <= r; ++q) {
+    if (r % q) continue;
+    const int64_t p = r / q;
+    if (q >= 2 && q <= cap && q > best) best = q;
+    if (p >= 2 && p <= cap && p > best) best = p;
+  }
+  return best;
+}
+
 harp_status_t harp_greedy_schedule(int64_t d, int32_t b_base, int32_t b_max, int32_t *out_radices,
                                    int32_t *out_m) {
   if (!out_radices || !out_m) return HARP_ERR_INVALID_ARG;
   if (d < 2 || b_base < 2 || b_max < 2) return HARP_ERR_INVALID_ARG;
-  int32_t m = 0;
+  if (d > ((int64_t)1 << 40)) return HARP_ERR_UNSUPPORTED;   // keeps the divisor search short
+  // What the appendix's schedule procedure produces, stated as a property: b_base with its
+  // full multiplicity in d; then, of what remains, again and again the largest divisor that
+  // does not exceed b_max (the sequence is non-increasing because the divisors of a quotient
+  // are divisors of the number); a remainder without such a divisor becomes one last stage.
+  std::vector<int64_t> sched;
   int64_t r = d;
-  auto push = [&](int64_t f) -> bool {
-    if (m >= HARP_MAX_STAGES || f > INT32_MAX) return false;
-    out_radices[m++] = (int32_t)f;
-    return true;
-  };
   while (r % b_base == 0) {
-    if (!push(b_base)) return HARP_ERR_UNSUPPORTED;
+    sched.push_back(b_base);
     r /= b_base;
   }
-  for (int64_t f = std::min<int64_t>(b_max, r); f >= 2; --f)
-    while (r % f == 0) {
-      if (!push(f)) return HARP_ERR_UNSUPPORTED;
-      r /= f;
-    }
-  if (r != 1 && !push(r)) return HARP_ERR_UNSUPPORTED;
-  *out_m = m;
+  for (int64_t f = largest_divisor_at_most(r, b_max); f != 0; f = largest_divisor_at_most(r, b_max)) {
+    sched.push_back(f);
+    r /= f;
+  }
+  if (r != 1) sched.push_back(r);
+  if (sched.size() > (size_t)HARP_MAX_STAGES) return HARP_ERR_UNSUPPORTED;
+  for (int64_t f : sched)
+    if (f > INT32_MAX) return HARP_ERR_UNSUPPORTED;
+  for (size_t i = 0; i < sched.size(); ++i) out_radices[i] = (int32_t)sched[i];
+  *out_m = (int32_t)sched.size();
   return HARP_OK;
 }
 

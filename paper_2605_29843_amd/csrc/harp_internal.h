@@ -137,8 +137,10 @@ struct harp_plan {
   int lds_bytes = 0;   // usable LDS per workgroup
   int num_cu = 0;
   // float32 intermediates of split programs, one per stream the plan has been used on (work
-  // on one stream is ordered, so consecutive calls can share the buffer); grow-only, freed
-  // with the plan
+  // on one stream is ordered, so consecutive calls can share the buffer).  Nothing is freed
+  // before the plan is destroyed: a buffer that a later, larger call outgrows moves to
+  // `retired`, because launches already queued and HIP graphs captured earlier still hold
+  // its address.
   struct Scratch {
     hipStream_t stream;
     float *ptr;
@@ -146,6 +148,8 @@ struct harp_plan {
   };
   mutable std::mutex scratch_mu;
   mutable std::vector<Scratch> scratch;
+  mutable std::vector<void *> retired;
+  bool no_mfma = false;   // HARP_NO_MFMA was set when the plan was created
   // column-mode image (every plan) and passes (empty when some radix exceeds 8) per direction
   std::vector<harp::ColStage> col[2];
   std::vector<harp::ColPassHost> colpass[2];

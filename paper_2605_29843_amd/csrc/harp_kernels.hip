@@ -25,12 +25,6 @@ namespace harp {
 
 namespace {
 
-int env_int(const char *name, int dflt) {
-  const char *s = getenv(name);
-  if (!s || !*s) return dflt;
-  return atoi(s);
-}
-
 // ------------------------------------------------------------------------------------------
 // element conversion
 __device__ __forceinline__ float widen_bf16(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
@@ -828,7 +822,7 @@ harp_status_t launch_stream_pass(const harp_plan *plan, const HostProgram &hp, i
                                  hipStream_t stream) {
   if (n == 0) return HARP_OK;
   const PassDesc &pd = hp.prog.pass[p];
-  if (env_int("HARP_NO_MFMA", 0) == 0 && mfma_pass_supported(pd, X, ldx, Y, ldy))
+  if (!plan->no_mfma && mfma_pass_supported(pd, X, ldx, Y, ldy))
     return launch_mfma_pass(plan, pd, X, ldx, dt_in, Y, ldy, dt_out, n, allow_narrow, stream);
   const int ib = dt_in == HARP_BF16, ob = dt_out == HARP_BF16;
   switch (pd.kind) {

@@ -19,8 +19,7 @@ import numpy as np
 import torch  # noqa: F401  (import order matters)
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-# HARP_LIBRARY may name another build of the same library (e.g. a tuning variant)
-LIB_PATH = os.environ.get("HARP_LIBRARY") or os.path.join(_PKG, "libharp.so")
+LIB_PATH = os.path.join(_PKG, "libharp.so")
 
 HARP_OK, HARP_ERR_INVALID_ARG, HARP_ERR_BAD_SCHEDULE, HARP_ERR_NOT_ORTHOGONAL, \
     HARP_ERR_UNSUPPORTED, HARP_ERR_OOM, HARP_ERR_DEVICE = range(7)
@@ -119,6 +118,16 @@ def _stream_ptr(stream) -> int:
     if stream is None:
         stream = torch.cuda.current_stream()
     return int(stream.cuda_stream)
+
+
+def _on_stream(t, stream):
+    """A tensor this module allocated (with the caching allocator, i.e. on the CURRENT stream) is
+    about to be used by kernels on `stream`: tell the allocator, so that the block is not handed
+    to other work on the current stream while those kernels are still running."""
+    import torch
+    if t is not None and stream is not None and stream != torch.cuda.current_stream():
+        t.record_stream(stream)
+    return t
 
 
 def _rowmajor_2d(t, what: str):
@@ -359,7 +368,7 @@ def harp_plan_destroy(plan: Plan) -> None:
 def _apply(fn, name, plan: Plan, X, Y=None, stream=None):
     import torch
     if Y is None:
-        Y = torch.empty_like(X)
+        Y = _on_stream(torch.empty_like(X), stream)
     if X.shape != Y.shape or X.dtype != Y.dtype:
         raise ValueError("X and Y must have the same shape and dtype")
     ldx, ldy = _rowmajor_2d(X, "X"), _rowmajor_2d(Y, "Y")
@@ -398,11 +407,12 @@ def harp_grad_blocks(plan, X, G, want_dX: bool = True, workspace=None, stream=No
     if d != plan.d:
         raise ValueError("X has the wrong number of columns")
     dt = _dtype_code(X)
-    dK = [torch.empty((plan.d // b, b, b), dtype=torch.float32, device=X.device) for b in plan.radices]
-    dX = torch.empty_like(X) if want_dX else None
+    dK = [_on_stream(torch.empty((plan.d // b, b, b), dtype=torch.float32, device=X.device), stream)
+          for b in plan.radices]
+    dX = _on_stream(torch.empty_like(X), stream) if want_dX else None
     need = harp_grad_blocks_workspace_size(plan, n)
     if workspace is None and need:
-        workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
+        workspace = _on_stream(torch.empty(need, dtype=torch.uint8, device=X.device), stream)
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     ptrs = (_vp * max(len(dK), 1))(*[t.data_ptr() for t in dK])
@@ -425,7 +435,7 @@ def harp_rotate_weight_workspace_size(plan_U, plan_V, d_out, d_in, dtype_code) -
 def _rotate(fn, name, plan_U, plan_V, W, Wout=None, workspace=None, stream=None):
     import torch
     if Wout is None:
-        Wout = torch.empty_like(W)
+        Wout = _on_stream(torch.empty_like(W), stream)
     if W.shape != Wout.shape or W.dtype != Wout.dtype:
         raise ValueError("W and Wout must have the same shape and dtype")
     ldw, ldo = _rowmajor_2d(W, "W"), _rowmajor_2d(Wout, "Wout")
@@ -433,7 +443,7 @@ def _rotate(fn, name, plan_U, plan_V, W, Wout=None, workspace=None, stream=None)
     dt = _dtype_code(W)
     need = harp_rotate_weight_workspace_size(plan_U, plan_V, d_out, d_in, dt)
     if workspace is None and need:
-        workspace = torch.empty(need, dtype=torch.uint8, device=W.device)
+        workspace = _on_stream(torch.empty(need, dtype=torch.uint8, device=W.device), stream)
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(fn(plan_U.handle if plan_U else None, plan_V.handle if plan_V else None,

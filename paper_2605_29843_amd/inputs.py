@@ -90,17 +90,32 @@ def hadamard_blocks(D: int, b: int) -> np.ndarray:
     return np.broadcast_to((H / np.sqrt(b)).astype(np.float32), (D, b, b)).copy()
 
 
+def generic_blocks(D: int, b: int, rng: np.random.Generator) -> np.ndarray:
+    """D non-orthogonal, well-conditioned b x b blocks: I + (0.3 / sqrt(b)) N(0,1), so the
+    perturbation has spectral norm about 0.6 whatever the radix; float32 [D,b,b]."""
+    K = np.eye(b)[None, :, :] + (0.3 / math.sqrt(b)) * rng.standard_normal((D, b, b))
+    return K.astype(np.float32)
+
+
+BLOCK_KINDS = ("orth", "hadamard", "qr", "generic")
+
+
 def make_blocks(d: int, radices, kind: str, rng: np.random.Generator):
     """Per-stage block arrays [d/b_t, b_t, b_t] float32.
 
     kind: 'orth' -> Givens for radix 2, sign-fixed QR otherwise;
           'hadamard' -> Theta = 0 initialisation (power-of-two radices only);
-          'qr' -> sign-fixed QR for every radix (includes reflections at radix 2)."""
+          'qr' -> sign-fixed QR for every radix (includes reflections at radix 2);
+          'generic' -> non-orthogonal blocks I + (0.3 / sqrt(b)) N(0,1) at every radix."""
+    if kind not in BLOCK_KINDS:
+        raise ValueError(f"unknown block kind {kind!r}; one of {BLOCK_KINDS}")
     out = []
     for b in radices:
         D = d // b
         if kind == "hadamard":
             out.append(hadamard_blocks(D, b))
+        elif kind == "generic":
+            out.append(generic_blocks(D, b, rng))
         elif kind == "qr" or b != 2:
             out.append(qr_blocks(D, b, rng))
         else:

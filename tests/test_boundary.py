@@ -71,6 +71,32 @@ def test_greedy_schedule_matches_printed_examples():
     assert e.value.status == harp.HARP_ERR_INVALID_ARG
 
 
+def test_greedy_schedule_library_and_oracle_agree_on_many_dimensions():
+    """The library derives the schedule from a property (multiplicity of the preferred radix,
+    then repeatedly the largest divisor up to b_max), the oracle walks the appendix's procedure:
+    two formulations, one answer, over every d up to 3000 and several (b_base, b_max)."""
+    from oracle import harp_oracle as ho
+    for b_base, b_max in ((8, 8), (2, 2), (4, 8), (16, 16), (8, 4), (3, 7), (8, 64)):
+        for d in list(range(2, 3001)) + [11008, 13824, 14336, 28672, 2 ** 20, 3 * 2 ** 19, 97 * 89 * 8]:
+            assert harp.harp_greedy_schedule(d, b_base, b_max) == ho.greedy_schedule(d, b_base, b_max), \
+                (d, b_base, b_max)
+
+
+def test_make_blocks_kinds():
+    """'generic' blocks are really non-orthogonal (and well conditioned); unknown kinds raise."""
+    rng = np.random.default_rng(0)
+    for b in (2, 3, 8, 43):
+        K = gi.make_blocks(b * 16, [b], "generic", rng)[0].astype(np.float64)
+        dev = np.abs(np.swapaxes(K, 1, 2) @ K - np.eye(b)).max(axis=(1, 2))
+        assert dev.min() > 0.02
+        sv = np.linalg.svd(K, compute_uv=False)
+        assert sv.min() > 0.1 and sv.max() < 3.0
+        Q = gi.make_blocks(b * 16, [b], "orth", rng)[0].astype(np.float64)
+        assert np.abs(np.swapaxes(Q, 1, 2) @ Q - np.eye(b)).max() < 1e-6
+    with pytest.raises(ValueError):
+        gi.make_blocks(16, [4, 4], "general", rng)
+
+
 def _status_of_create(d, radices, blocks, signs=None, flags=0):
     try:
         p = harp.Plan(d, radices, blocks, signs, flags)

@@ -7,7 +7,7 @@ import pytest
 
 from oracle import harp_oracle as ho
 from paper_2605_29843_amd import inputs as gi
-from parity_util import assert_parity, to_device, to_host64
+from parity_util import assert_parity, summand_magnitude, to_device, to_host64
 
 pytestmark = pytest.mark.gpu
 
@@ -28,7 +28,9 @@ def assert_dk_parity(dK, ref, X, G, what):
     """dK is a float32 sum of n products of float32 numbers.  Per entry the oracle's value is
     bounded by sqrt(sum x^2 sum g^2) <= ||X||_max-col ||G||_max-col; the float32 path (one rounding
     per product and per partial sum, chunks of <= 32..n/128 rows, then <= 128 chunk sums) stays
-    within 2e-5 of that scale for the n used here, and must be finite."""
+    within 2e-5 of that scale for the n used here, and must be finite.  With non-orthogonal blocks
+    the inner activations x_t and gradients g_t are no longer of the size of X and G; the largest
+    entry of the stage's own reference then joins the scale."""
     scale = float(np.sqrt((X.astype(np.float64) ** 2).sum(axis=0).max() *
                           (G.astype(np.float64) ** 2).sum(axis=0).max()))
     for t, (a, r) in enumerate(zip(dK, ref)):
@@ -36,7 +38,7 @@ def assert_dk_parity(dK, ref, X, G, what):
         assert a.shape == r.shape, (a.shape, r.shape)
         assert np.all(np.isfinite(a))
         err = np.abs(a - r)
-        tol = 2e-5 * scale + 1e-5 * np.abs(r)
+        tol = 2e-5 * max(scale, float(np.abs(r).max())) + 1e-5 * np.abs(r)
         assert np.all(err <= tol), f"{what}: stage {t}: max err {err.max():.3e} vs tol {tol.min():.3e}"
 
 
@@ -63,10 +65,14 @@ def test_grad_blocks_matches_the_oracle(harp, d, radices, n, kind, dtype):
     torch.cuda.synchronize()
     rK, rX = ho.grad_blocks(X, G, d, radices, blocks, signs)
     assert_dk_parity(dK, rK, X, G, "dK")
-    assert_parity(to_host64(dX), rX, dtype, "dX")
+    mag = None
+    if kind == "generic":    # the blocks really are non-orthogonal, and the tolerance follows the summands
+        assert max(float(np.abs(np.swapaxes(K, 1, 2) @ K - np.eye(K.shape[1])).max()) for K in blocks) > 0.05
+        mag = summand_magnitude(G, d, radices, blocks, transpose=True)
+    assert_parity(to_host64(dX), rX, dtype, "dX", mag=mag)
     # dX is apply_transpose of G
     Z = harp.harp_apply_transpose(plan, to_device(G, dtype))
-    assert_parity(to_host64(Z), rX, dtype, "apply_transpose(G)")
+    assert_parity(to_host64(Z), rX, dtype, "apply_transpose(G)", mag=mag)
     # the same call again gives the same bits (fixed summation order)
     dK2, _ = harp.harp_grad_blocks(plan, to_device(X, dtype), to_device(G, dtype), want_dX=False)
     torch.cuda.synchronize()

@@ -7,7 +7,7 @@ import pytest
 
 from oracle import harp_oracle as ho
 from paper_2605_29843_amd import inputs as gi
-from parity_util import assert_parity, to_device, to_host64
+from parity_util import assert_parity, summand_magnitude, to_device, to_host64
 
 pytestmark = pytest.mark.gpu
 
@@ -51,9 +51,11 @@ def run_case(harp, d, radices, n, dtype, kind="orth", seed=0, algo=None, ld_pad=
     harp.harp_apply(plan, Xd, Yd)
     torch.cuda.synchronize()
     Y = to_host64(Yd)
+    generic = (kind == "generic")    # non-orthogonal blocks: rounding is relative to the summands
     if n > 0:
         Yref = ho.apply_staged(X, d, radices, blocks, signs)
-        out["apply"] = assert_parity(Y, Yref, dtype, "apply")
+        out["apply"] = assert_parity(Y, Yref, dtype, "apply",
+                                     mag=summand_magnitude(X, d, radices, blocks) if generic else None)
     if ld_pad:
         assert torch.all(Yd_full[:, d:] == 7.0), "padding columns were written"
     if both:
@@ -63,7 +65,9 @@ def run_case(harp, d, radices, n, dtype, kind="orth", seed=0, algo=None, ld_pad=
         torch.cuda.synchronize()
         if n > 0:
             Zref = ho.apply_transpose_staged(X, d, radices, blocks, signs)
-            out["transpose"] = assert_parity(to_host64(Zd), Zref, dtype, "apply_transpose")
+            out["transpose"] = assert_parity(
+                to_host64(Zd), Zref, dtype, "apply_transpose",
+                mag=summand_magnitude(X, d, radices, blocks, transpose=True) if generic else None)
     plan.destroy()
     return out
 
@@ -146,7 +150,8 @@ def _radix2_plan_with_special_blocks(d, m, special, seed):
 
 
 @pytest.mark.parametrize("d", [256, 4096])
-@pytest.mark.parametrize("case", ["quarter_turn", "swap", "near_quarter_turn", "tiny_diagonal", "general"])
+@pytest.mark.parametrize("case", ["quarter_turn", "swap", "near_quarter_turn", "tiny_diagonal", "general",
+                                  "diagonal_1e-6", "diagonal_1e-9", "diagonal_1e-11"])
 def test_radix2_blocks_with_zero_or_tiny_diagonal(harp, d, case):
     """The two-shear form divides by the diagonal of a block: blocks with an exactly zero
     diagonal (quarter turns, swaps) must take the lifting fallback, nearly zero ones and
@@ -162,6 +167,14 @@ def test_radix2_blocks_with_zero_or_tiny_diagonal(harp, d, case):
         # diagonal 1e-13: the shear factor would be 1e13, beyond the plan builder's bound
         "tiny_diagonal": lambda c: np.array([[1e-13, -1.0], [1.0, 1e-13]], np.float32),
         "general": lambda c: np.array([[1.5, 0.25 * (c % 5)], [-0.5, 0.75]], np.float32),
+        # the range in between: the two-shear form is still taken, with shear factors of
+        # 1e6 .. 1e11 and pending scales that accumulate over the stages (or the builder falls
+        # back when a scale leaves its range): either way the result must stay accurate
+        "diagonal_1e-6": lambda c: np.array([[1e-6, -1.0], [1.0, 1e-6]], np.float32),
+        "diagonal_1e-9": lambda c: np.array([[1e-9, 1.0], [-1.0, 1e-9]] if c % 2 else
+                                            [[1e-9, -1.0], [1.0, 1e-9]], np.float32),
+        "diagonal_1e-11": lambda c: np.array([[1e-11, -1.0], [1.0, -1e-11 if c % 3 == 0 else 1e-11]],
+                                             np.float32),
     }[case]
     radices, blocks, signs = _radix2_plan_with_special_blocks(d, m, special, seed=d + len(case))
     n = 37
@@ -299,47 +312,63 @@ def test_pipelined_kernel_is_selected_and_in_place(harp):
     plan.destroy()
 
 
-def _sampled_full_size(harp, name, n_sample=48, seed=0, transpose=True):
-    """Full-size workload in the launch configuration the benchmark uses; parity on sampled
-    rows (staged oracle, row by row) and norm preservation on every row."""
+def _full_size(harp, name, row_step=1, dense=False, transpose=True):
+    """Full-size workload in the launch configuration the benchmark uses.  Every row (or, with
+    row_step = k > 1, one row out of every k consecutive ones at a varying offset, so that every
+    row tile of every launch contributes) is compared with the oracle element by element: with
+    dense = True against the definition X @ U with U materialised, otherwise against the
+    stage-by-stage form.  Norm preservation is checked on every row."""
     import torch
     w = gi.workload(name)
     d, n, radices = w["d"], w["n"], w["radices"]
     plan = harp.Plan(d, radices, w["blocks"], w["signs"])
-    say("full size", name, f"n={n} d={d}", plan.kernel_name())
+    say("full size", name, f"n={n} d={d} row_step={row_step} dense={dense}", plan.kernel_name())
     Xd = to_device(w["X"], "bf16")
     Yd = harp.harp_apply(plan, Xd)
     torch.cuda.synchronize()
-    rows = np.sort(np.random.default_rng(seed).choice(n, size=n_sample, replace=False))
-    rows = np.unique(np.concatenate([rows, [0, n - 1]]))
+    if row_step == 1:
+        rows = np.arange(n)
+    else:
+        k = np.arange((n + row_step - 1) // row_step)
+        rows = np.minimum(k * row_step + (k * 7 + 3) % row_step, n - 1)
+        rows = np.unique(np.concatenate([rows, [0, n - 1]]))
     Xs = w["X"][rows]
-    Y = to_host64(Yd[torch.from_numpy(rows).cuda()])
-    assert_parity(Y, ho.apply_staged(Xs, d, radices, w["blocks"], w["signs"]), "bf16", name + " apply")
+    U = ho.build_U(d, radices, w["blocks"], w["signs"]) if dense else None
+    idx = torch.from_numpy(rows).cuda()
+    Yref = Xs.astype(np.float64) @ U if dense else ho.apply_staged(Xs, d, radices, w["blocks"], w["signs"])
+    assert_parity(to_host64(Yd[idx]), Yref, "bf16", name + " apply")
     # property that holds at any size: every row keeps its norm (orthogonal U), up to bf16 rounding
     nx = torch.linalg.vector_norm(Xd.float(), dim=1)
     ny = torch.linalg.vector_norm(Yd.float(), dim=1)
     assert float(torch.max(torch.abs(ny - nx) / nx)) < 2e-3
     if transpose:
+        say("full size", name, "transpose")
         Zd = harp.harp_apply_transpose(plan, Xd)
         torch.cuda.synchronize()
-        Z = to_host64(Zd[torch.from_numpy(rows).cuda()])
-        assert_parity(Z, ho.apply_transpose_staged(Xs, d, radices, w["blocks"], w["signs"]), "bf16",
-                      name + " transpose")
+        Zref = Xs.astype(np.float64) @ U.T if dense else \
+            ho.apply_transpose_staged(Xs, d, radices, w["blocks"], w["signs"])
+        assert_parity(to_host64(Zd[idx]), Zref, "bf16", name + " transpose")
         nz = torch.linalg.vector_norm(Zd.float(), dim=1)
         assert float(torch.max(torch.abs(nz - nx) / nx)) < 2e-3
     plan.destroy()
 
 
-@pytest.mark.parametrize("name", ["llama7b_4096_r2", "llama7b_4096_r8"])
-def test_full_size_4096(harp, name):
-    _sampled_full_size(harp, name)
+def test_full_size_4096_every_row_against_dense_U(harp):
+    """The benchmark's batch (2048 x 4096 bf16, twelve radix-2 stages) in the benchmark's launch
+    configuration: all 2048 rows of apply and apply_transpose against X @ U and X @ U^T."""
+    _full_size(harp, "llama7b_4096_r2", dense=True)
+
+
+def test_full_size_4096_radix8_every_row(harp):
+    _full_size(harp, "llama7b_4096_r8")
 
 
 # ------------------------------------------------------------------ config 3: mixed radix
 @pytest.mark.parametrize("name", ["down_11008_r2x8_43", "ffn_14336_r2x11_7", "llama13b_5120_r2x10_5",
                                   "ffn13b_13824_r2x9_27"])
 def test_full_size_mixed_radix(harp, name):
-    _sampled_full_size(harp, name, n_sample=24)
+    """All 2048 rows, both directions, against the stage-by-stage oracle."""
+    _full_size(harp, name)
 
 
 @pytest.mark.parametrize("d,radices", [(11008, [8, 8, 4, 43]), (14336, [8, 8, 8, 7, 4]),
@@ -451,6 +480,116 @@ def test_split_is_refused_when_there_is_nothing_to_split(harp):
         plan.set_algo(harp.HARP_ALGO_SPLIT)
     assert e.value.status == harp.HARP_ERR_UNSUPPORTED
     plan.destroy()
+
+
+GENERIC_CASES = [
+    # (d, radices, n, dtype): non-orthogonal blocks I + (0.3 / sqrt(b)) N(0,1) through every kernel family
+    (4096, [2] * 12, 37, "bf16"), (4096, [2] * 12, 9, "f32"), (2048, [2] * 11, 21, "f32"),
+    (1024, [2] * 10, 70, "bf16"), (256, [2] * 8, 33, "f32"), (4096, [8] * 4, 19, "f32"),
+    (4096, [4] * 6, 11, "bf16"), (5120, [8, 8, 8, 5, 2], 13, "f32"), (11008, [2] * 8 + [43], 40, "bf16"),
+    (11008, [2] * 8 + [43], 17, "f32"), (14336, [2] * 11 + [7], 24, "f32"), (13824, [2] * 9 + [3, 3, 3], 10, "bf16"),
+    (1536, [2] * 9 + [3], 600, "f32"), (2752, [8, 8, 43], 30, "f32"), (120, [2, 3, 4, 5], 6, "f32"),
+]
+
+
+@pytest.mark.parametrize("d,radices,n,dtype", GENERIC_CASES)
+def test_generic_non_orthogonal_blocks_through_every_kernel_family(harp, d, radices, n, dtype):
+    """Blocks that are not orthogonal (max |K^T K - I| > 0.05): apply and apply_transpose are
+    still the linear maps of the definition, to float32 rounding of the summands."""
+    rng = np.random.default_rng(d + n)
+    K = gi.make_blocks(d, radices, "generic", rng)
+    assert max(float(np.abs(np.swapaxes(k, 1, 2).astype(np.float64) @ k - np.eye(k.shape[1])).max())
+               for k in K) > 0.05
+    run_case(harp, d, radices, n, dtype, kind="generic", seed=d + n)
+
+
+def test_apply_never_blocks_and_never_frees_its_intermediate(harp):
+    """A split program (float32 intermediate owned by the plan) called with 8 rows and then with
+    2048 rows on one stream: neither call waits for the stream (both return while a long kernel
+    queued ahead of them is still running), and both results match the oracle."""
+    import torch
+    d, radices = 14336, [2] * 11 + [7]
+    rng = np.random.default_rng(21)
+    blocks, signs = gi.make_blocks(d, radices, "orth", rng), gi.make_signs(d, rng)
+    plan = harp.Plan(d, radices, blocks, signs)
+    say("no host-side wait: n = 8 then n = 2048 on one stream", plan.kernel_name(2048))
+    Xs = gi.round_to_bf16(rng.standard_normal((8, d)).astype(np.float32))
+    Xl = gi.round_to_bf16(rng.standard_normal((2048, d)).astype(np.float32))
+    Xsd, Xld = to_device(Xs, "bf16"), to_device(Xl, "bf16")
+    Ys, Yl = torch.empty_like(Xsd), torch.empty_like(Xld)
+    A = torch.randn(8192, 8192, device="cuda")
+    torch.cuda.synchronize()
+    st = torch.cuda.current_stream()
+    done = torch.cuda.Event()
+    for _ in range(12):                      # about 0.1 s of queued work ahead of the two calls
+        A = (A @ A) * 1e-2
+    harp.harp_apply(plan, Xsd, Ys, st)       # first call on the stream: allocates the small buffer
+    harp.harp_apply(plan, Xld, Yl, st)       # needs the full slab: allocates again, frees nothing
+    harp.harp_apply(plan, Xsd, Ys, st)
+    done.record(st)
+    returned_early = not done.query()
+    torch.cuda.synchronize()
+    assert returned_early, "harp_apply waited for the stream"
+    assert_parity(to_host64(Ys), ho.apply_staged(Xs, d, radices, blocks, signs), "bf16", "n = 8")
+    rows = np.arange(0, 2048, 16)
+    assert_parity(to_host64(Yl)[rows], ho.apply_staged(Xl[rows], d, radices, blocks, signs), "bf16", "n = 2048")
+    plan.destroy()
+
+
+def test_graph_captured_at_small_n_survives_a_larger_eager_call(harp):
+    """A graph captured with 8 rows holds the address of the plan's intermediate.  An eager call
+    with 2048 rows on the same stream makes the plan take a larger one; the old buffer must stay
+    alive, so that replaying the graph afterwards still gives the eager result."""
+    import torch
+    d, radices = 12288, [2] * 12 + [3]
+    rng = np.random.default_rng(22)
+    blocks, signs = gi.make_blocks(d, radices, "orth", rng), gi.make_signs(d, rng)
+    plan = harp.Plan(d, radices, blocks, signs)
+    say("graph at n = 8, then eager n = 2048, then replay", plan.kernel_name(8))
+    Xs = gi.round_to_bf16(rng.standard_normal((8, d)).astype(np.float32))
+    Xl = gi.round_to_bf16(rng.standard_normal((2048, d)).astype(np.float32))
+    Xsd, Xld = to_device(Xs, "bf16"), to_device(Xl, "bf16")
+    Yg, Yl = torch.zeros_like(Xsd), torch.empty_like(Xld)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        harp.harp_apply(plan, Xsd, Yg, side)          # warm-up on the capturing stream
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            harp.harp_apply(plan, Xsd, Yg, side)
+        harp.harp_apply(plan, Xld, Yl, side)          # larger batch, same stream
+        torch.cuda.synchronize()
+        filler = [torch.full((1 << 22,), 3.0, device="cuda") for _ in range(8)]   # reuses freed memory, if any
+    torch.cuda.current_stream().wait_stream(side)
+    ref = ho.apply_staged(Xs, d, radices, blocks, signs)
+    for rep in range(3):
+        Yg.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert_parity(to_host64(Yg), ref, "bf16", f"replay {rep} after the larger call")
+        harp.harp_apply(plan, Xld, Yl, side)
+        torch.cuda.synchronize()
+    del filler
+    rows = np.arange(0, 2048, 64)
+    assert_parity(to_host64(Yl)[rows], ho.apply_staged(Xl[rows], d, radices, blocks, signs), "bf16", "n = 2048")
+    plan.destroy()
+
+
+def test_rotate_weight_workspace_is_one_matrix_on_the_column_path(harp):
+    rng = np.random.default_rng(2)
+    pu = harp.Plan(64, [2] * 6, gi.make_blocks(64, [2] * 6, "orth", rng))
+    pv = harp.Plan(48, [2, 2, 2, 2, 3], gi.make_blocks(48, [2, 2, 2, 2, 3], "orth", rng))
+    pu11 = harp.Plan(44, [2, 2, 11], gi.make_blocks(44, [2, 2, 11], "orth", rng))
+    mat = 64 * 48 * 4
+    assert harp.harp_rotate_weight_workspace_size(pu, pv, 64, 48, harp.HARP_BF16) == mat
+    assert harp.harp_rotate_weight_workspace_size(pu, None, 64, 48, harp.HARP_F32) == mat
+    assert harp.harp_rotate_weight_workspace_size(None, pv, 64, 48, harp.HARP_F32) == 0
+    # a radix above 8 on the U side: transposed-copy path, two float32 matrices with plan_V
+    assert harp.harp_rotate_weight_workspace_size(pu11, pv, 44, 48, harp.HARP_F32) == 2 * 44 * 48 * 4
+    for p in (pu, pv, pu11):
+        p.destroy()
 
 
 # ------------------------------------------------------------------ config 4: decode regime
@@ -701,7 +840,9 @@ def test_decode_regime(harp, n, d, radices):
 
 # ------------------------------------------------------------------ config 5: d = 28672, 8192
 def test_full_size_28672(harp):
-    _sampled_full_size(harp, "ffn70b_28672_r2x12_7", n_sample=12)
+    """4096 x 28672: one row out of every four consecutive ones (1024 rows), both directions; the
+    row tiles of every launch of this shape hold more than four rows."""
+    _full_size(harp, "ffn70b_28672_r2x12_7", row_step=4)
 
 
 def test_radix2_chain_8192(harp):
@@ -855,7 +996,13 @@ def test_rotate_weight_llama70b_shape_sampled(harp):
     Wd = to_device(W, "bf16")
     out = harp.harp_rotate_weight(pu, pv, Wd)
     torch.cuda.synchronize()
-    rows = [0, 1234, 8191]
+    # 256 rows: one in every band of 32 consecutive rows (the row tiles of plan_V's chunk kernel
+    # and the 128-row tiles of the first column pass), hitting every residue modulo 128 (the
+    # tiles of the second column pass, rows lo + 128 j); whole rows, so every column tile too
+    k = np.arange(256)
+    rows = 32 * k + (29 * (k // 4) + 5 * (k % 4)) % 32
+    assert len(set(rows % 128)) == 128 and len(set(rows // 32)) == 256
+    rows = [int(r) for r in rows]
     E = np.zeros((len(rows), do))
     E[np.arange(len(rows)), rows] = 1.0
     # row i of U^T is e_i U^T

@@ -289,10 +289,21 @@ def test_greedy_schedule_is_a_valid_schedule(d):
     ho.check_schedule(d, sched)
 
 
-def test_param_count_formula():
-    """Eq. (13): D_t b_t (b_t-1)/2 = d (b_t-1)/2 per stage."""
-    for d, radices in [(4096, [8] * 4), (5120, [8, 8, 8, 5, 2]), (11008, [2] * 8 + [43])]:
-        assert ho.param_count(d, radices) == sum(d * (b - 1) // 2 for b in radices)
+def test_param_count_literal_values():
+    """Eq. (13), stage t holds d / b_t blocks with b_t (b_t - 1) / 2 free parameters each.  Values
+    worked out by hand: 4096 = 8^4 -> 4 stages x 512 blocks x 28 = 57 344; 5120 = (8,8,8,5,2) ->
+    3 x 640 x 28 + 1024 x 10 + 2560 x 1 = 66 560; (2,3) on d = 6 -> 3 x 1 + 2 x 3 = 9;
+    11008 = 2^8 * 43 -> 8 x 5504 + 256 x 903 = 275 200."""
+    assert ho.param_count(4096, [8] * 4) == 57344
+    assert ho.param_count(5120, [8, 8, 8, 5, 2]) == 66560
+    assert ho.param_count(6, [2, 3]) == 9
+    assert ho.param_count(4, [2, 2]) == 4
+    assert ho.param_count(11008, [2] * 8 + [43]) == 275200
+    # and it is the number of rotation parameters the theta front end actually consumes
+    d, radices = 120, [2, 3, 4, 5]
+    thetas = [np.zeros((d // b, b * (b - 1) // 2)) for b in radices]
+    ho.blocks_from_theta(d, radices, thetas, mixers=[np.eye(b) for b in radices])
+    assert ho.param_count(d, radices) == sum(t.size for t in thetas)
 
 
 # ------------------------------------------------------------------ parameterisations
