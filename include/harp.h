@@ -128,6 +128,28 @@ harp_status_t harp_apply_transpose(const harp_plan_t *plan, const void *X, int64
                                    int64_t ldy, int64_t n, harp_dtype_t dt, void *stream);
 
 /*
+ * harp_apply (transpose == 0) or harp_apply_transpose (transpose == 1) for callers that cannot
+ * allocate device memory: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, same kernels and bit-identical results, but the call never
+ * allocates, frees or synchronises: the float32 intermediate that a plan of two or more launches
+ * needs (see harp_apply) is a 32 MiB array that belongs to the loaded library itself -- one per
+ * GPU, held until the process ends -- instead of a buffer the plan allocates.  A batch whose
+ * intermediate n * d * 4 bytes exceeds that array is refused with HARP_ERR_UNSUPPORTED
+ * (harp_apply_noalloc_max_rows gives the limit for a plan; plans that run in one launch use no
+ * intermediate and take any n).  The plan's device must be the current device
+ * (HARP_ERR_INVALID_ARG otherwise).  Every call on a GPU shares that GPU's one array, so two
+ * calls that overlap in time on one GPU -- different streams or host threads -- race on it:
+ * order them on one stream.  Nothing in the array has to start at zero (a call writes every
+ * element before it reads it), so it is never cleared.
+ */
+harp_status_t harp_apply_noalloc(const harp_plan_t *plan, const void *X, int64_t ldx, void *Y,
+                                 int64_t ldy, int64_t n, harp_dtype_t dt, int32_t transpose,
+                                 void *stream);
+/* Largest n harp_apply_noalloc accepts for this plan (INT64_MAX when the plan needs no
+ * intermediate); -1 for NULL. */
+int64_t harp_apply_noalloc_max_rows(const harp_plan_t *plan);
+
+/*
  * Two-sided change of basis of a weight matrix (Sec. 2):  Wout = U_U^T * W * U_V,
  * W and Wout [d_out, d_in] row-major DEVICE arrays with leading dimensions ldw, ldo.
  * plan_U (dimension d_out) and plan_V (dimension d_in) may each be NULL = identity on

@@ -13,7 +13,34 @@
 
 using namespace harp;
 
+// Intermediate of harp_apply_noalloc: device memory that belongs to the loaded library, one copy
+// per GPU, held until the process ends.  In host code the name stands for the symbol, not for
+// a device address: the address is looked up once per device (noalloc_scratch below) and only
+// that pointer is ever handed to a kernel.
+#define HARP_NOALLOC_SCRATCH_BYTES ((size_t)32 << 20)
+static __device__ __align__(256) float scratch[HARP_NOALLOC_SCRATCH_BYTES / sizeof(float)];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_noalloc_mu;
+float *g_noalloc_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (looked up at the first call on it).
+harp_status_t noalloc_scratch(int dev, float **out) {
+  if (dev < 0 || dev >= kMaxDevices) return HARP_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_noalloc_mu);
+  if (!g_noalloc_ptr[dev]) {
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+      (void)hipGetLastError();
+      return HARP_ERR_DEVICE;
+    }
+    g_noalloc_ptr[dev] = (float *)p;
+  }
+  *out = g_noalloc_ptr[dev];
+  return HARP_OK;
+}
 
 // Effective form of one executed stage (a direction's program), after the +-1 signs of the
 // processor and the signs released by earlier lifted stages have been folded in.
@@ -523,6 +550,14 @@ harp_status_t run_chunk_passes(const harp_plan_t *plan, const HostProgram &hp, i
                             stream);
 }
 
+// Split program on rows [0, n): the chunk-local passes run fused on chip, every other pass is
+// streamed through the float32 intermediate Z, which holds `slab` rows; rows are processed slab
+// by slab so that Z stays small (it is written by one launch and read by the next: cache
+// resident).
+harp_status_t run_split(const harp_plan_t *plan, const HostProgram &hp, const void *X, int64_t ldx,
+                        harp_dtype_t dt_in, void *Y, int64_t ldy, harp_dtype_t dt_out, int64_t n,
+                        float *Z, int64_t slab, hipStream_t stream);
+
 harp_status_t apply_dir(const harp_plan_t *plan, Direction dir, const void *X, int64_t ldx,
                         harp_dtype_t dt_in, void *Y, int64_t ldy, harp_dtype_t dt_out, int64_t n,
                         void *stream_) {
@@ -533,16 +568,20 @@ harp_status_t apply_dir(const harp_plan_t *plan, Direction dir, const void *X, i
   const int np = hp.prog.npass;
   if (hp.n_chunk == np)   // everything on chip, one launch
     return run_chunk_passes(plan, hp, 0, np, X, ldx, dt_in, Y, ldy, dt_out, n, stream);
-
-  // Split program: the chunk-local passes run fused on chip, every other pass is streamed
-  // through a float32 intermediate Z.  Rows are processed in slabs so that Z stays small
-  // (it is written by one launch and read by the next: cache resident).
   const int64_t d = plan->d;
   const int64_t slab_cap = slab_rows_cap(d);
   const int64_t slab = slab_cap > n ? n : slab_cap;
   float *Z = nullptr;
   harp_status_t zst = plan_scratch(plan, stream, (size_t)slab * d * 4, (size_t)slab_cap * d * 4, &Z);
   if (zst != HARP_OK) return zst;
+  return run_split(plan, hp, X, ldx, dt_in, Y, ldy, dt_out, n, Z, slab, stream);
+}
+
+harp_status_t run_split(const harp_plan_t *plan, const HostProgram &hp, const void *X, int64_t ldx,
+                        harp_dtype_t dt_in, void *Y, int64_t ldy, harp_dtype_t dt_out, int64_t n,
+                        float *Z, int64_t slab, hipStream_t stream) {
+  const int64_t d = plan->d;
+  const int np = hp.prog.npass;
   const int nstream = np - hp.n_chunk;
   const int nseg = nstream + 1;
   const bool allow_narrow = (dt_in == HARP_BF16 || dt_out == HARP_BF16);
@@ -1007,6 +1046,43 @@ harp_status_t harp_apply_transpose(const harp_plan_t *plan, const void *X, int64
   harp_status_t st = check_apply_args(plan, X, ldx, Y, ldy, n, dt);
   if (st != HARP_OK || n == 0) return st;
   return apply_dir(plan, DIR_TRN, X, ldx, dt, Y, ldy, dt, n, stream);
+}
+
+harp_status_t harp_apply_noalloc(const harp_plan_t *plan, const void *X, int64_t ldx, void *Y,
+                                 int64_t ldy, int64_t n, harp_dtype_t dt, int32_t transpose,
+                                 void *stream) {
+  harp_status_t st = check_apply_args(plan, X, ldx, Y, ldy, n, dt);
+  if (st != HARP_OK || n == 0) return st;
+  if (transpose != 0 && transpose != 1) return HARP_ERR_INVALID_ARG;
+  const Direction dir = transpose ? DIR_TRN : DIR_FWD;
+  const HostProgram *hpp = select_program(plan, dir, n, nullptr);
+  if (!hpp) return HARP_ERR_UNSUPPORTED;
+  const HostProgram &hp = *hpp;
+  if (hp.n_chunk == hp.prog.npass)   // one launch, no intermediate at all
+    return run_chunk_passes(plan, hp, 0, hp.prog.npass, X, ldx, dt, Y, ldy, dt, n, (hipStream_t)stream);
+  // the whole batch has to fit the library's own array: no slab loop, a clear refusal instead
+  if ((size_t)n > HARP_NOALLOC_SCRATCH_BYTES / ((size_t)plan->d * 4)) return HARP_ERR_UNSUPPORTED;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) {
+    (void)hipGetLastError();
+    return HARP_ERR_DEVICE;
+  }
+  if (dev != plan->device) return HARP_ERR_INVALID_ARG;   // the plan's images live on its own device
+  float *Z = nullptr;
+  st = noalloc_scratch(dev, &Z);
+  if (st != HARP_OK) return st;
+  return run_split(plan, hp, X, ldx, dt, Y, ldy, dt, n, Z, n, (hipStream_t)stream);
+}
+
+int64_t harp_apply_noalloc_max_rows(const harp_plan_t *plan) {
+  if (!plan) return -1;
+  const HostProgram *hpp = select_program(plan, DIR_FWD, 1, nullptr);
+  const HostProgram *hpt = select_program(plan, DIR_TRN, 1, nullptr);
+  if (!hpp || !hpt) return -1;
+  const bool split = hpp->n_chunk != hpp->prog.npass || hpt->n_chunk != hpt->prog.npass ||
+                     plan->prog[HARP_ALGO_SPLIT][DIR_FWD].ok;
+  if (!split) return INT64_MAX;
+  return (int64_t)(HARP_NOALLOC_SCRATCH_BYTES / ((size_t)plan->d * 4));
 }
 
 harp_status_t harp_rotate_weight_workspace_size(const harp_plan_t *plan_U,

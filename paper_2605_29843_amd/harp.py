@@ -53,6 +53,8 @@ _SIGS = {
                                                 C.POINTER(_vp), _vp, _u32]),
     "harp_apply": (_i32, [_vp, _vp, _i64, _vp, _i64, _i64, _i32, _vp]),
     "harp_apply_transpose": (_i32, [_vp, _vp, _i64, _vp, _i64, _i64, _i32, _vp]),
+    "harp_apply_noalloc": (_i32, [_vp, _vp, _i64, _vp, _i64, _i64, _i32, _i32, _vp]),
+    "harp_apply_noalloc_max_rows": (_i64, [_vp]),
     "harp_rotate_weight_workspace_size": (_i32, [_vp, _vp, _i64, _i64, _i32, C.POINTER(_sz)]),
     "harp_rotate_weight": (_i32, [_vp, _vp, _vp, _i64, _vp, _i64, _i64, _i64, _i32, _vp, _sz, _vp]),
     "harp_rotate_weight_inverse": (_i32, [_vp, _vp, _vp, _i64, _vp, _i64, _i64, _i64, _i32, _vp, _sz, _vp]),
@@ -387,6 +389,23 @@ def harp_apply(plan: Plan, X, Y=None, stream=None):
 def harp_apply_transpose(plan: Plan, X, Y=None, stream=None):
     """Y = X U^T."""
     return _apply(lib.harp_apply_transpose, "harp_apply_transpose", plan, X, Y, stream)
+
+
+def harp_apply_noalloc(plan: Plan, X, Y, transpose: bool = False, stream=None):
+    """``harp_apply`` / ``harp_apply_transpose`` without any allocation: Y must be given."""
+    if X.shape != Y.shape or X.dtype != Y.dtype:
+        raise ValueError("X and Y must have the same shape and dtype")
+    ldx, ldy = _rowmajor_2d(X, "X"), _rowmajor_2d(Y, "Y")
+    if X.shape[1] != plan.d:
+        raise ValueError(f"X has {X.shape[1]} columns, plan dimension is {plan.d}")
+    _check(lib.harp_apply_noalloc(plan.handle, X.data_ptr(), ldx, Y.data_ptr(), ldy, X.shape[0],
+                                  _dtype_code(X), 1 if transpose else 0, _stream_ptr(stream)),
+           "harp_apply_noalloc")
+    return Y
+
+
+def harp_apply_noalloc_max_rows(plan: Plan) -> int:
+    return int(lib.harp_apply_noalloc_max_rows(plan.handle))
 
 
 def harp_grad_blocks_workspace_size(plan, n: int) -> int:
