@@ -25,11 +25,18 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-KERNEL_SYMBOL = {"pipe_radix2": "harp_pipe_kernel", "tile_fused": "harp_tile_kernel",
+KERNEL_SYMBOL = {"dpp_radix2": "harp_dpp_kernel", "split_dpp_stream": "harp_dpp_kernel",
+                 "pipe_radix2": "harp_pipe_kernel", "tile_fused": "harp_tile_kernel",
                  "tile_generic": "harp_tile_kernel", "split_pipe_stream": "harp_pipe_kernel",
                  "split_chunk_stream": "harp_tile_kernel", "wave_radix2": "harp_wave_kernel",
                  "split_wave_stream": "harp_wave_kernel", "radix_tile": "harp_radix_kernel",
                  "split_radix_stream": "harp_radix_kernel"}
+
+
+# kernels one call of harp_apply launches, by the path name harp_plan_kernel_name reports
+KERNELS_OF = {"split_dpp_stream": ["harp_dpp_kernel", "harp_stream_kernel"],
+              "split_wave_stream": ["harp_wave_kernel", "harp_stream_mfma_kernel"],
+              "split_pipe_stream": ["harp_pipe_kernel", "harp_stream_kernel"]}
 
 
 def cpu_baseline(w, sample_rows: int):
@@ -103,6 +110,12 @@ def main():
                          "layer widths of the Llama-2 / Llama-3 families under the radix-2 and "
                          "the greedy radix-8 schedules, and rotate_weight over their layer "
                          "shapes (stderr)")
+    ap.add_argument("--settle-ms", type=float, default=100.0,
+                    help="untimed set-up before the warm-up steps: the same step run for this many "
+                         "milliseconds so that the shader clock has settled whatever --warmup is "
+                         "(0 switches it off); reported as config.clock_settle_ms")
+    ap.add_argument("--no-shapes-line", action="store_true",
+                    help="skip roofline.shapes['11008'] (the second width of the headline metric)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also launch the library's plain copy kernel on one batch (known bytes), "
                          "the reference that scales rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
@@ -146,6 +159,13 @@ def main():
         harp.harp_apply(plan, Xi, Yi, stream)
         harp.harp_apply_transpose(plan, Yi, Zi, stream)
 
+    if args.settle_ms > 0:
+        cnt0 = [0]
+
+        def one0():
+            step(cnt0[0])
+            cnt0[0] += 1
+        warm_clocks(one0, seconds=args.settle_ms * 1e-3)
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -169,6 +189,17 @@ def main():
             harp.harp_rotate_weight(None, None, pool[1][0], pool[1][1], stream=stream)
         torch.cuda.synchronize()
 
+    def timed_us(fn, reps, settle=0.05):
+        """Average duration of fn()'s launches, HIP events on the launch stream."""
+        warm_clocks(fn, seconds=settle)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            fn()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / reps
+
     launches = 2 * args.steps
     kernel_us = ev_ms * 1e3 / launches                       # average launch duration (HIP events)
     param_bytes = plan.param_bytes()
@@ -185,12 +216,60 @@ def main():
         "data": "synthetic",
         "config": {"workload": args.workload, "n": n, "d": d, "radices": radices,
                    "io_dtype": w["dtype"], "kernel": plan.kernel_name(n), "batches_in_pool": nbuf,
+                   "clock_settle_ms": args.settle_ms,
                    "step": "harp_apply + harp_apply_transpose on one batch"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None,
                      "kernel": KERNEL_SYMBOL.get(plan.kernel_name(n), plan.kernel_name(n)), "avg_launch_us": kernel_us,
                      "algorithmic_bytes_per_launch": alg_bytes, "param_bytes": param_bytes},
     }
+    # Copy ceiling of this machine at this batch size: the library's plain copy kernel (reads and
+    # writes n*d*esz bytes) on the same rotating batches, same event method.
+    ccnt = [0]
+
+    def copy_once():
+        Xi, Yi, _ = pool[ccnt[0] % nbuf]
+        harp.harp_rotate_weight(None, None, Xi, Yi, stream=stream)
+        ccnt[0] += 1
+    copy_us = timed_us(copy_once, 400)
+    copy_gbs = 2 * n * d * esz / (copy_us * 1e-6) / 1e9
+    out["roofline"]["copy_ceiling_gbs"] = copy_gbs
+    out["roofline"]["copy_launch_us"] = copy_us
+    out["roofline"]["frac_of_copy"] = achieved / copy_gbs
+    out["roofline"]["shapes"] = {str(d): {
+        "workload": args.workload, "n": n, "avg_launch_us": kernel_us, "achieved": achieved,
+        "frac": achieved / HBM_PEAK_GBS, "kernels": [out["roofline"]["kernel"]], "launches_per_call": 1,
+        "traffic_ratio": None}}
+    if not args.no_shapes_line and args.rows is None and args.workload == "llama7b_4096_r2":
+        # The other width the headline metric is quoted at: 2048 x 11008 = 2^8 * 43, bf16, apply
+        # and apply_transpose on rotating batches (> 640 MB of inputs and outputs).
+        w2 = gi.workload("down_11008_r2x8_43")
+        p2 = harp.Plan(w2["d"], w2["radices"], w2["blocks"], w2["signs"])
+        X2 = dev(w2["X"])
+        nb2 = max(2, int(np.ceil(640e6 / (3 * X2.numel() * X2.element_size()))))
+        pool2 = [(X2 if i == 0 else X2.roll(i, 0).contiguous(), torch.empty_like(X2), torch.empty_like(X2))
+                 for i in range(nb2)]
+        c2 = [0]
+
+        def step2():
+            Xi, Yi, Zi = pool2[c2[0] % nb2]
+            harp.harp_apply(p2, Xi, Yi, stream)
+            harp.harp_apply_transpose(p2, Yi, Zi, stream)
+            c2[0] += 1
+        us2 = timed_us(step2, 300, settle=0.08) / 2          # per call (apply or transpose)
+        Xi, Yi, Zi = pool2[(c2[0] - 1) % nb2]
+        rt2 = float((Zi.float() - Xi.float()).abs().max() / Xi.float().abs().max())
+        assert rt2 < 3e-2, f"11008 round trip error {rt2}"
+        alg2 = w2["n"] * w2["d"] * 4 + p2.param_bytes()
+        ach2 = alg2 / (us2 * 1e-6) / 1e9
+        kname2 = p2.kernel_name(w2["n"])
+        out["roofline"]["shapes"][str(w2["d"])] = {
+            "workload": "down_11008_r2x8_43", "n": w2["n"], "avg_launch_us": us2, "achieved": ach2,
+            "frac": ach2 / HBM_PEAK_GBS, "rows_per_s": w2["n"] / (us2 * 1e-6),
+            "kernels": KERNELS_OF.get(kname2, [kname2]), "path": kname2,
+            "algorithmic_bytes_per_call": alg2, "traffic_ratio": None}
+        del pool2, X2
+        p2.destroy()
     if args.x8 and args.rows is None and n * 8 * d * esz * 6 < 4e9:
         # The same kernel on 8 n rows (the batch repeated): 8 times the rows per workgroup, so the
         # start-up of a launch weighs an eighth as much.  Context for `frac`, not the headline.
@@ -225,6 +304,16 @@ def main():
             tj = json.load(f)
         out["roofline"]["traffic"] = tj.get("traffic_bytes_per_launch")
         out["roofline"]["traffic_source"] = "profiles/" + os.path.basename(tpath)
+        if out["roofline"]["traffic"]:
+            out["roofline"]["shapes"][str(d)]["traffic_ratio"] = out["roofline"]["traffic"] / alg_bytes
+    for key, sh in out["roofline"]["shapes"].items():
+        tp = os.path.join(ROOT, "profiles", f"traffic_{sh['workload']}.json")
+        if key != str(d) and os.path.exists(tp):
+            with open(tp) as f:
+                tj = json.load(f)
+            if tj.get("traffic_bytes_per_launch"):
+                sh["traffic_ratio"] = tj["traffic_bytes_per_launch"] / sh["algorithmic_bytes_per_call"]
+                sh["traffic_source"] = "profiles/" + os.path.basename(tp)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(w, sample_rows=min(n, 2048))
     if args.extra:

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libharp.so")
 
-SOURCES = ["harp_api.cpp", "harp_theta.cpp", "harp_kernels.hip", "harp_pipe.hip", "harp_mfma.hip",
+SOURCES = ["harp_api.cpp", "harp_theta.cpp", "harp_kernels.hip", "harp_pipe.hip", "harp_dpp.hip", "harp_mfma.hip",
            "harp_radix.hip", "harp_col.hip", "harp_grad.hip"]
 HEADERS = [os.path.join(ROOT, "include", "harp.h"), os.path.join(CSRC, "harp_internal.h")]
 

@@ -231,6 +231,74 @@ void pack_mfma_block(const float *K, int b, uint16_t *out, float *out32) {
         }
 }
 
+// Image of the two-group DPP kernel for the chunk-local stages of a program: exactly twelve
+// radix-2 stages on the digits 0..11 (ascending in a forward program, descending in a
+// transposed one), all in the two-shear form except that the last may be the program's dense
+// last stage.  eff[i0 .. i0 + 12) are those stages in execution order.  Appends to `image`.
+void build_dpp_image(const harp_plan *plan, const std::vector<StageEff> &eff, int i0, Direction dir,
+                     HostProgram &hp, std::vector<float> &image) {
+  constexpr int L = 12, D = 1 << L, TG = D / 16;
+  hp.dpp = DppImage();
+  const int m = plan->m;
+  if (i0 < 0 || i0 + L > m || plan->d % D) return;
+  bool ld = false;
+  for (int e = 0; e < L; ++e) {
+    const StageEff &se = eff[i0 + e];
+    const int digit = (dir == DIR_FWD) ? e : L - 1 - e;
+    if (se.b != 2 || se.s != ((int64_t)1 << digit)) return;
+    if (se.form == FORM_SCALED) continue;
+    if (se.form == FORM_DENSE && e == L - 1 && i0 + e == m - 1) {
+      ld = true;
+      continue;
+    }
+    return;
+  }
+  if (dir == DIR_TRN && !ld) return;
+  const bool trn = (dir == DIR_TRN);
+  const int nsa = trn ? 4 : 8;                 // shear stages of group A
+  const int nsb = L - nsa - (ld ? 1 : 0);      // shear stages of group B
+  const int64_t nchunk = plan->d / D;
+  const int64_t strideA = (int64_t)nsa * D, strideB = (int64_t)(nsb + (ld ? 2 : 0)) * D;
+  const size_t off = image.size();
+  image.resize(off + (size_t)nchunk * (strideA + strideB));
+  float *base = image.data() + off;
+  // factor of global coordinate i in execution stage e: the member with digit value 0 holds
+  // m10 / m00 (it receives the other member), the member with digit value 1 holds m01 / m11
+  auto block_of = [&](const StageEff &se, int64_t i) { return (i / (2 * se.s)) * se.s + i % se.s; };
+  for (int64_t kch = 0; kch < nchunk; ++kch)
+    for (int grp = 0; grp < 2; ++grp) {
+      // group A works in the low layout going up and in the high layout going down; B the other
+      const bool high = (grp == 0) ? trn : !trn;
+      float *g = base + (grp == 0 ? kch * strideA : nchunk * strideA + kch * strideB);
+      const int e0 = grp == 0 ? 0 : nsa, ne = grp == 0 ? nsa : nsb + (ld ? 1 : 0);
+      for (int ee = 0; ee < ne; ++ee) {
+        const StageEff &se = eff[i0 + e0 + ee];
+        const bool dense = (se.form == FORM_DENSE);
+        for (int k = 0; k < 4; ++k)
+          for (int t = 0; t < TG; ++t)
+            for (int q = 0; q < 4; ++q) {
+              const int64_t i = kch * D + 16 * (int64_t)dpp_segment_of(high, (unsigned)t) + 4 * k + q;
+              const int64_t c = block_of(se, i);
+              const int r = (int)((i / se.s) & 1);
+              const size_t slot = ((size_t)(ee * 4 + k) * TG + t) * 4 + q;
+              if (!dense) {
+                g[slot] = r == 0 ? se.la[c] : se.lb[c];
+              } else {
+                // y_r = x_r E[r][r] + x_(1-r) E[1-r][r]
+                g[slot] = se.dense[(size_t)c * 4 + r * 2 + r];
+                g[slot + (size_t)D] = se.dense[(size_t)c * 4 + (1 - r) * 2 + r];
+              }
+            }
+      }
+    }
+  hp.dpp.host_off = (int64_t)off;
+  hp.dpp.offB = nchunk * strideA;
+  hp.dpp.strideA = strideA;
+  hp.dpp.strideB = strideB;
+  hp.dpp.trn = trn;
+  hp.dpp.ld = ld;
+}
+
 bool build_program(const harp_plan *plan, const std::vector<const float *> &blocks,
                    const int8_t *signs, int algo, Direction dir, HostProgram &hp,
                    std::vector<float> &image, std::vector<size_t> &offsets,
@@ -465,6 +533,10 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
     ++i;
   }
   hp.param_bytes = (int64_t)image.size() * 4;
+  // second image of the same chunk-local stages for the two-group DPP kernel (chunks of 4096)
+  hp.dpp = DppImage();
+  if (fused && chunk == 4096 && tb == 12)
+    build_dpp_image(plan, eff, dir == DIR_FWD ? 0 : m - 12, dir, hp, image);
   hp.ok = true;
   return true;
 }
@@ -537,6 +609,9 @@ harp_status_t plan_scratch(const harp_plan_t *plan, hipStream_t stream, size_t b
 harp_status_t run_chunk_passes(const harp_plan_t *plan, const HostProgram &hp, int p0, int p1,
                                const void *X, int64_t ldx, harp_dtype_t dt_in, void *Y, int64_t ldy,
                                harp_dtype_t dt_out, int64_t n, hipStream_t stream) {
+  if (p1 - p0 == hp.n_chunk && dpp_supported(plan, hp.dpp, hp.chunk, X, ldx, Y, ldy))
+    return launch_dpp_kernel(plan, hp.dpp, X, ldx, dt_in, Y, ldy, dt_out, n,
+                             choose_pipe_rows(plan, n, plan->d / hp.chunk, hp.chunk), stream);
   if (pipe_supported(plan, hp.prog, p0, p1 - p0, hp.chunk, X, ldx, Y, ldy))
     return launch_pipe_kernel(plan, hp, p0, hp.chunk, X, ldx, dt_in, Y, ldy, dt_out, n,
                               choose_pipe_rows(plan, n, plan->d / hp.chunk, hp.chunk), stream);
@@ -909,6 +984,7 @@ harp_status_t harp_plan_create(harp_plan_t **out, int64_t d, int32_t m, const in
           st = HARP_ERR_DEVICE;
           break;
         }
+        if (hp.dpp.host_off >= 0) hp.dpp.img = dimg + hp.dpp.host_off;
         for (int p = 0; p < hp.prog.npass; ++p) {
           hp.prog.pass[p].params = dimg + offsets[p];
           hp.prog.pass[p].aux = nullptr;
@@ -1226,6 +1302,8 @@ const char *harp_plan_kernel_name(const harp_plan_t *plan, int64_t n, harp_dtype
   const char *nm = "none";
   const HostProgram *hp = select_program(plan, DIR_FWD, n, &nm);
   (void)dt;
+  if (hp && hp->n_chunk == hp->prog.npass && dpp_supported(plan, hp->dpp, hp->chunk, nullptr, 8, nullptr, 8))
+    return "dpp_radix2";
   if (hp && hp->n_chunk == hp->prog.npass &&
       pipe_supported(plan, hp->prog, 0, hp->prog.npass, hp->chunk, nullptr, 8, nullptr, 8))
     return "pipe_radix2";
@@ -1237,6 +1315,7 @@ const char *harp_plan_kernel_name(const harp_plan_t *plan, int64_t n, harp_dtype
     return "radix_tile";
   if (hp && hp->n_chunk != hp->prog.npass) {
     const int p0 = hp->chunk_first ? 0 : hp->prog.npass - hp->n_chunk;
+    if (dpp_supported(plan, hp->dpp, hp->chunk, nullptr, 8, nullptr, 8)) return "split_dpp_stream";
     if (pipe_supported(plan, hp->prog, p0, hp->n_chunk, hp->chunk, nullptr, 8, nullptr, 8))
       return "split_pipe_stream";
     if (wave_supported(plan, hp->prog, p0, hp->n_chunk, hp->chunk, nullptr, 8, nullptr, 8))

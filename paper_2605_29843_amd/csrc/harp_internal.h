@@ -64,7 +64,21 @@ struct Program {
 // on contiguous chunks of every row; each pass on the digits above is streamed through device
 // memory with a float32 intermediate.  In the forward program the chunk passes come first
 // ([0, n_chunk)), in the transposed program last ([npass - n_chunk, npass)).
+// Parameter image of the two-group DPP kernel (harp_dpp.hip) for the chunk-local radix-2 stages
+// of a program, all in the two-shear form (the program's last stage, if among them, dense).
+// Per chunk and group: stage e (execution order), 16-byte piece k, thread t, value q at
+// ((e * 4 + k) * 256 + t) * 4 + q = the factor of coordinate 16 * segment(t) + 4 k + q; the dense
+// stage takes two such slots (own-coordinate factors, then partner factors).
+struct DppImage {
+  const float *img = nullptr;   // device; null: the program has no such image
+  int64_t host_off = -1;        // offset (floats) inside the program's host image, -1: none
+  int64_t offB = 0;             // group B's part starts here (floats)
+  int64_t strideA = 0, strideB = 0;   // floats per chunk
+  bool trn = false, ld = false;
+};
+
 struct HostProgram {
+  DppImage dpp;
   Program prog{};
   const Program *dev = nullptr;  // device copy of prog (what the kernels read)
   int64_t param_bytes = 0;
@@ -190,6 +204,14 @@ harp_status_t launch_pipe_kernel(const harp_plan *plan, const HostProgram &hp, i
                                  const void *X, int64_t ldx, harp_dtype_t dt_in, void *Y,
                                  int64_t ldy, harp_dtype_t dt_out, int64_t n, int rows_per_tile,
                                  hipStream_t stream);
+// two-group DPP kernel for radix-2 chains in the two-shear form on chunks of 4096 (harp_dpp.hip)
+unsigned dpp_segment_of(bool high_layout, unsigned t);
+bool dpp_supported(const harp_plan *plan, const DppImage &di, int chunk, const void *X, int64_t ldx,
+                   const void *Y, int64_t ldy);
+harp_status_t launch_dpp_kernel(const harp_plan *plan, const DppImage &di, const void *X,
+                                int64_t ldx, harp_dtype_t dt_in, void *Y, int64_t ldy,
+                                harp_dtype_t dt_out, int64_t n, int rows_per_tile,
+                                hipStream_t stream);
 // wave-local radix-2 kernel for chunks of 256 / 512 / 1024 coordinates (harp_pipe.hip)
 bool wave_supported(const harp_plan *plan, const Program &prog, int p0, int np, int chunk,
                     const void *X, int64_t ldx, const void *Y, int64_t ldy);

@@ -19,6 +19,8 @@
 #include <type_traits>
 #include <stdlib.h>
 
+#include <algorithm>
+
 #include "harp_internal.h"
 
 namespace harp {
@@ -723,6 +725,30 @@ __global__ __launch_bounds__(256) void harp_copy2d_kernel(const T *__restrict__ 
   }
 }
 
+// Plain copy of a row-major matrix whose rows are whole 16-byte pieces at 16-byte aligned
+// addresses: four pieces per thread, all four loads issued before the first store.  rowp =
+// pieces per row, lds16 / ldd16 = leading dimensions in pieces.
+__global__ __launch_bounds__(256) void harp_copy2d_vec_kernel(const uint4 *__restrict__ src,
+                                                              uint32_t lds16, uint4 *__restrict__ dst,
+                                                              uint32_t ldd16, uint32_t rowp,
+                                                              uint32_t total) {
+  const uint32_t i0 = blockIdx.x * 1024u + threadIdx.x;
+  uint4 v[4];
+  uint32_t so[4], dof[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    uint32_t i = i0 + 256u * k;
+    if (i >= total) i = total - 1;            // clamped: the extra lanes repeat the last piece
+    const uint32_t r = i / rowp, c = i - r * rowp;
+    so[k] = r * lds16 + c;
+    dof[k] = r * ldd16 + c;
+  }
+#pragma unroll
+  for (int k = 0; k < 4; ++k) v[k] = src[so[k]];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) dst[dof[k]] = v[k];
+}
+
 template <typename TI, typename TO>
 harp_status_t launch_tile_typed(const harp_plan *plan, const Program *dprog, int p0, int p1,
                                 int chunk, const void *X, int64_t ldx, void *Y, int64_t ldy,
@@ -883,6 +909,17 @@ harp_status_t launch_copy2d(const void *src, int64_t lds_, void *dst, int64_t ld
                             int64_t cols, harp_dtype_t dt, hipStream_t stream) {
   if (rows == 0 || cols == 0) return HARP_OK;
   const int64_t total = rows * cols;
+  const int64_t es = dt == HARP_F32 ? 4 : 2;
+  // rows of whole, aligned 16-byte pieces and 32-bit piece offsets: the vector kernel
+  if ((cols * es) % 16 == 0 && (lds_ * es) % 16 == 0 && (ldd * es) % 16 == 0 &&
+      (uintptr_t)src % 16 == 0 && (uintptr_t)dst % 16 == 0 && src != dst &&
+      rows * std::max(lds_, ldd) * es / 16 < ((int64_t)1 << 32)) {
+    const int64_t rowp = cols * es / 16, pieces = rows * rowp;
+    hipLaunchKernelGGL(harp_copy2d_vec_kernel, dim3((unsigned)((pieces + 1023) / 1024)), dim3(256), 0,
+                       stream, (const uint4 *)src, (uint32_t)(lds_ * es / 16), (uint4 *)dst,
+                       (uint32_t)(ldd * es / 16), (uint32_t)rowp, (uint32_t)pieces);
+    return hipGetLastError() == hipSuccess ? HARP_OK : HARP_ERR_DEVICE;
+  }
   int64_t blocks = (total + 255) / 256;
   if (blocks > 65536) blocks = 65536;
   if (dt == HARP_F32)

@@ -273,7 +273,8 @@ def test_pipelined_kernel_other_sizes_and_types(harp, d, dtype, n):
     radices = [2] * int(np.log2(d))
     rng = np.random.default_rng(d + n)
     plan = harp.Plan(d, radices, gi.make_blocks(d, radices, "orth", rng))
-    assert plan.kernel_name() == "pipe_radix2"
+    # 4096: two wave groups with in-wave (DPP) digit exchanges; 2048: three wave groups
+    assert plan.kernel_name() == ("dpp_radix2" if d == 4096 else "pipe_radix2")
     plan.destroy()
     run_case(harp, d, radices, n, dtype, seed=d + n)
 
@@ -297,7 +298,7 @@ def test_pipelined_kernel_is_selected_and_in_place(harp):
     blocks, signs = gi.processor(d, radices, config=2)
     X = gi.activations(n, d, config=2)
     plan = harp.Plan(d, radices, blocks, signs)
-    assert plan.kernel_name() == "pipe_radix2"
+    assert plan.kernel_name() == "dpp_radix2"
     say("pipe in place", n)
     Xd = to_device(X, "bf16")
     harp.harp_apply(plan, Xd, Xd)
@@ -575,6 +576,24 @@ def test_graph_captured_at_small_n_survives_a_larger_eager_call(harp):
     rows = np.arange(0, 2048, 64)
     assert_parity(to_host64(Yl)[rows], ho.apply_staged(Xl[rows], d, radices, blocks, signs), "bf16", "n = 2048")
     plan.destroy()
+
+
+@pytest.mark.parametrize("rows,cols,pad_in,pad_out,dtype", [(300, 4096, 8, 16, "bf16"), (33, 130, 0, 3, "f32"),
+                                                           (1, 8, 0, 0, "bf16"), (2048, 4096, 0, 0, "bf16"),
+                                                           (65, 1028, 4, 0, "f32"), (7, 24, 0, 8, "bf16")])
+def test_identity_on_both_sides_is_a_plain_copy(harp, rows, cols, pad_in, pad_out, dtype):
+    """rotate_weight with no processor on either side copies the matrix (16-byte pieces when rows
+    and leading dimensions allow it, element by element otherwise) and leaves padding alone."""
+    import torch
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    say("plain copy", rows, cols, pad_in, pad_out, dtype)
+    src = torch.randn(rows, cols + pad_in, device="cuda").to(tdt)
+    dst = torch.full((rows, cols + pad_out), 9.0, dtype=tdt, device="cuda")
+    harp.harp_rotate_weight(None, None, src[:, :cols], dst[:, :cols])
+    torch.cuda.synchronize()
+    assert torch.equal(dst[:, :cols], src[:, :cols])
+    if pad_out:
+        assert bool((dst[:, cols:] == 9.0).all())
 
 
 def test_rotate_weight_workspace_is_one_matrix_on_the_column_path(harp):
