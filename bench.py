@@ -25,7 +25,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-KERNEL_SYMBOL = {"dpp_radix2": "harp_dpp_kernel", "split_dpp_stream": "harp_dpp_kernel",
+KERNEL_SYMBOL = {"dpp_radix2": "harp_dpp_kernel",
                  "pipe_radix2": "harp_pipe_kernel", "tile_fused": "harp_tile_kernel",
                  "tile_generic": "harp_tile_kernel", "split_pipe_stream": "harp_pipe_kernel",
                  "split_chunk_stream": "harp_tile_kernel", "wave_radix2": "harp_wave_kernel",
@@ -34,8 +34,7 @@ KERNEL_SYMBOL = {"dpp_radix2": "harp_dpp_kernel", "split_dpp_stream": "harp_dpp_
 
 
 # kernels one call of harp_apply launches, by the path name harp_plan_kernel_name reports
-KERNELS_OF = {"split_dpp_stream": ["harp_dpp_kernel", "harp_stream_kernel"],
-              "split_wave_stream": ["harp_wave_kernel", "harp_stream_mfma_kernel"],
+KERNELS_OF = {"split_wave_stream": ["harp_wave_kernel", "harp_stream_mfma_kernel"],
               "split_pipe_stream": ["harp_pipe_kernel", "harp_stream_kernel"]}
 
 

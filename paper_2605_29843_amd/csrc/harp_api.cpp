@@ -535,8 +535,8 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
   hp.param_bytes = (int64_t)image.size() * 4;
   // second image of the same chunk-local stages for the two-group DPP kernel (chunks of 4096)
   hp.dpp = DppImage();
-  if (fused && chunk == 4096 && tb == 12)
-    build_dpp_image(plan, eff, dir == DIR_FWD ? 0 : m - 12, dir, hp, image);
+  if (algo == HARP_ALGO_FUSED && chunk == 4096 && tb == 12 && m == 12)
+    build_dpp_image(plan, eff, 0, dir, hp, image);
   hp.ok = true;
   return true;
 }
@@ -609,7 +609,7 @@ harp_status_t plan_scratch(const harp_plan_t *plan, hipStream_t stream, size_t b
 harp_status_t run_chunk_passes(const harp_plan_t *plan, const HostProgram &hp, int p0, int p1,
                                const void *X, int64_t ldx, harp_dtype_t dt_in, void *Y, int64_t ldy,
                                harp_dtype_t dt_out, int64_t n, hipStream_t stream) {
-  if (p1 - p0 == hp.n_chunk && dpp_supported(plan, hp.dpp, hp.chunk, X, ldx, Y, ldy))
+  if (p1 - p0 == hp.n_chunk && dpp_supported(plan, hp.dpp, hp.chunk, X, ldx, dt_in, Y, ldy, dt_out))
     return launch_dpp_kernel(plan, hp.dpp, X, ldx, dt_in, Y, ldy, dt_out, n,
                              choose_pipe_rows(plan, n, plan->d / hp.chunk, hp.chunk), stream);
   if (pipe_supported(plan, hp.prog, p0, p1 - p0, hp.chunk, X, ldx, Y, ldy))
@@ -1301,8 +1301,8 @@ const char *harp_plan_kernel_name(const harp_plan_t *plan, int64_t n, harp_dtype
   if (!plan) return "none";
   const char *nm = "none";
   const HostProgram *hp = select_program(plan, DIR_FWD, n, &nm);
-  (void)dt;
-  if (hp && hp->n_chunk == hp->prog.npass && dpp_supported(plan, hp->dpp, hp->chunk, nullptr, 8, nullptr, 8))
+  if (hp && hp->n_chunk == hp->prog.npass &&
+      dpp_supported(plan, hp->dpp, hp->chunk, nullptr, 8, dt, nullptr, 8, dt))
     return "dpp_radix2";
   if (hp && hp->n_chunk == hp->prog.npass &&
       pipe_supported(plan, hp->prog, 0, hp->prog.npass, hp->chunk, nullptr, 8, nullptr, 8))
@@ -1315,7 +1315,6 @@ const char *harp_plan_kernel_name(const harp_plan_t *plan, int64_t n, harp_dtype
     return "radix_tile";
   if (hp && hp->n_chunk != hp->prog.npass) {
     const int p0 = hp->chunk_first ? 0 : hp->prog.npass - hp->n_chunk;
-    if (dpp_supported(plan, hp->dpp, hp->chunk, nullptr, 8, nullptr, 8)) return "split_dpp_stream";
     if (pipe_supported(plan, hp->prog, p0, hp->n_chunk, hp->chunk, nullptr, 8, nullptr, 8))
       return "split_pipe_stream";
     if (wave_supported(plan, hp->prog, p0, hp->n_chunk, hp->chunk, nullptr, 8, nullptr, 8))

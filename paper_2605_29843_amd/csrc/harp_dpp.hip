@@ -453,8 +453,13 @@ unsigned dpp_segment_of(bool high_layout, unsigned t) {
 }
 
 bool dpp_supported(const harp_plan *plan, const DppImage &di, int chunk, const void *X, int64_t ldx,
-                   const void *Y, int64_t ldy) {
+                   harp_dtype_t dt_in, const void *Y, int64_t ldy, harp_dtype_t dt_out) {
   if (plan->algo == HARP_ALGO_GENERIC || !di.img || chunk != kD) return false;
+  // bf16 rows on both sides only: a thread's 16 float32 coordinates are four 16-byte pieces 64
+  // bytes apart from its neighbours', the one slow access pattern of this chip (measured:
+  // float32 rows 18.2 -> 21.7 us, the float32 intermediate of a 28672-wide split program
+  // 250 -> 297 us); those cases keep the three-group kernel, which re-lays rows out in LDS
+  if (dt_in != HARP_BF16 || dt_out != HARP_BF16) return false;
   // 16-byte row accesses for either element type
   if ((ldx % 8) || (ldy % 8) || ((uintptr_t)X % 16) || ((uintptr_t)Y % 16)) return false;
   return true;

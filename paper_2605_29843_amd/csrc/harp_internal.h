@@ -207,7 +207,7 @@ harp_status_t launch_pipe_kernel(const harp_plan *plan, const HostProgram &hp, i
 // two-group DPP kernel for radix-2 chains in the two-shear form on chunks of 4096 (harp_dpp.hip)
 unsigned dpp_segment_of(bool high_layout, unsigned t);
 bool dpp_supported(const harp_plan *plan, const DppImage &di, int chunk, const void *X, int64_t ldx,
-                   const void *Y, int64_t ldy);
+                   harp_dtype_t dt_in, const void *Y, int64_t ldy, harp_dtype_t dt_out);
 harp_status_t launch_dpp_kernel(const harp_plan *plan, const DppImage &di, const void *X,
                                 int64_t ldx, harp_dtype_t dt_in, void *Y, int64_t ldy,
                                 harp_dtype_t dt_out, int64_t n, int rows_per_tile,
