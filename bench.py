@@ -447,6 +447,50 @@ def main():
                 del Wm, Wo, ws
                 pu.destroy()
                 pv.destroy()
+    if args.shapes:
+        # Kronecker fallback against Mixed-Radix (speed only; the paper compares their accuracy):
+        # (H~_K / sqrt(K)) (x) T_{n2} as a plan with tied parameters, the same processor expanded to
+        # an ordinary plan, and the Mixed-Radix radix-2 chain of the same width; bf16, n = 2048.
+        rngk = np.random.default_rng(1)
+
+        def timed2(fn, reps=100):
+            warm_clocks(fn, seconds=0.03)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(reps):
+                fn()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) * 1e3 / reps
+
+        for dd, K, n2, mixed in ((12288, 12, 1024, [2] * 12 + [3]), (14336, 28, 512, [2] * 11 + [7]),
+                                 (28672, 28, 1024, [2] * 12 + [7])):
+            r2k = [2] * int(np.log2(n2))
+            b2 = gi.make_blocks(n2, r2k, "orth", rngk)
+            sg = gi.make_signs(dd, rngk)
+            Hk = gi.hadamard_table(K)
+            rk, bk = harp.harp_kronecker_blocks(Hk, n2, r2k, b2)
+            plans = (("kronecker tied", harp.Plan.kronecker(Hk, n2, r2k, b2, sg)),
+                     ("kronecker expanded", harp.Plan(dd, rk, bk, sg)),
+                     ("mixed-radix", harp.Plan(dd, mixed, gi.make_blocks(dd, mixed, "orth", rngk), sg)))
+            nb = max(2, min(8, int(400e6 / (2048 * dd * 2))))
+            Xs = [torch.randn(2048, dd, device="cuda").to(torch.bfloat16) for _ in range(nb)]
+            Ys = [torch.empty_like(x) for x in Xs]
+            cnt = [0]
+            for nm, pk in plans:
+                def fwd():
+                    harp.harp_apply(pk, Xs[cnt[0] % nb], Ys[cnt[0] % nb], stream)
+                    cnt[0] += 1
+
+                def trn():
+                    harp.harp_apply_transpose(pk, Xs[cnt[0] % nb], Ys[cnt[0] % nb], stream)
+                    cnt[0] += 1
+                tf, tt = timed2(fwd), timed2(trn)
+                print(f"[shapes] d={dd:6d} = {K} x {n2} {nm:19s} apply {tf:7.1f} us  transpose {tt:7.1f} us  "
+                      f"parameters {pk.param_bytes() / 1e6:6.2f} MB  [{pk.kernel_name(2048)}]",
+                      file=sys.stderr, flush=True)
+                pk.destroy()
+            del Xs, Ys
     if args.decode:
         for dd, rr in ((4096, [2] * 12), (12288, [2] * 12 + [3]), (14336, [2] * 11 + [7])):
             bb, ss = gi.processor(dd, rr, config=4)

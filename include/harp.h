@@ -281,6 +281,27 @@ harp_status_t harp_kronecker_blocks(int32_t K, const float *table, int64_t n2, i
                                     const int32_t *radices2, const float *const *blocks2,
                                     int32_t *radices_out, float *const *blocks_out);
 
+/*
+ * The same processor as a plan whose parameters stay tied (the point of the Kronecker fallback:
+ * one T_{n2} serves all K slices, and the last stage is one table).  Arguments as for
+ * harp_kronecker_blocks; signs: d = K n2 values in {+1, -1} or NULL; flags: HARP_VALIDATE_ORTHO
+ * only.  The plan equals harp_plan_create on the expansion (same apply / apply_transpose), but
+ * when the slices are radix-2 chains of 256, 512 or 1024 coordinates in the two-shear form and
+ * 9 <= K <= HARP_MAX_RADIX, its device image holds ONE slice's stage parameters and ONE K x K
+ * table (parameter volume divided by K; harp_plan_param_bytes reports it, harp_plan_tied_slices
+ * returns K), read by every slice modulo the slice length, and the signs are applied inside the
+ * first (apply) or last (apply_transpose) kernel instead of being folded into the parameters.
+ * Such a plan has the two-launch program only: X and Y must be 16-byte aligned with leading
+ * dimensions that are multiples of 8 (HARP_ERR_UNSUPPORTED otherwise), harp_plan_set_algo
+ * accepts HARP_ALGO_AUTO and HARP_ALGO_SPLIT, it cannot be plan_U of a column-mode weight
+ * rotation (the transposing path is taken) and has no block gradients.  For every other shape
+ * the call falls back to the expanded plan (harp_plan_tied_slices returns 0).
+ */
+harp_status_t harp_plan_create_kronecker(harp_plan_t **out, int32_t K, const float *table,
+                                         int64_t n2, int32_t m2, const int32_t *radices2,
+                                         const float *const *blocks2, const int8_t *signs,
+                                         uint32_t flags);
+
 /* Greedy Mixed-Radix schedule (appendix Alg. 2): peel b_base while it divides d, then the
  * factors min(b_max, r) .. 2 in decreasing order, then any leftover as one last stage.
  * out_radices must hold HARP_MAX_STAGES ints.  Host only; no HIP call. */
@@ -290,6 +311,8 @@ harp_status_t harp_greedy_schedule(int64_t d, int32_t b_base, int32_t b_max, int
 /* Introspection and tuning. */
 int64_t harp_plan_dim(const harp_plan_t *plan);          /* d, or -1 for NULL            */
 int32_t harp_plan_num_stages(const harp_plan_t *plan);   /* m, or -1 for NULL            */
+int32_t harp_plan_tied_slices(const harp_plan_t *plan);  /* K of a tied Kronecker plan, 0 for
+                                                            any other plan, -1 for NULL     */
 /* Eq. (13): number of free rotation parameters sum_t d (b_t - 1) / 2; -1 for NULL. */
 int64_t harp_plan_param_count(const harp_plan_t *plan);
 /* Bytes of stage parameters one launch reads from device memory (per row tile). */

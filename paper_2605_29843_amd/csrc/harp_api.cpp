@@ -120,7 +120,11 @@ bool build_effective(const harp_plan *plan, const std::vector<const float *> &bl
     auto E = [&](int64_t c, int r, int r2) -> double {   // block as used in this direction
       return dir == DIR_TRN ? K[(c * b + r2) * b + r] : K[(c * b + r) * b + r2];
     };
-    const bool pow2_stage = (algo != HARP_ALGO_GENERIC && b == 2 && !last);
+    // Tied parameters, forward: the last stage of the slices is dense as well, so that no
+    // pending scale (a function of the coordinate inside the slice) reaches the table, whose
+    // blocks then really are one matrix.
+    const bool slice_end = (plan->tied_K > 0 && dir == DIR_FWD && t == m - 2);
+    const bool pow2_stage = (algo != HARP_ALGO_GENERIC && b == 2 && !last && !slice_end);
     if (pow2_stage && scaled) {
       se.form = FORM_SCALED;
       se.la.resize(D);
@@ -305,9 +309,16 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
                    std::vector<std::vector<uint16_t>> &aux) {
   const int m = plan->m;
   const int64_t d = plan->d;
+  // A plan with tied parameters has the split program only; its signs are applied by the wave
+  // kernel (folded into the stage parameters they would make every slice's image different).
+  const bool tied = plan->tied_K > 0;
+  if (tied && algo != HARP_ALGO_SPLIT) return false;
+  if (tied) signs = nullptr;
   std::vector<StageEff> eff;
-  if (!build_effective(plan, blocks, signs, algo, dir, true, eff))
+  if (!build_effective(plan, blocks, signs, algo, dir, true, eff)) {
+    if (tied) return false;
     build_effective(plan, blocks, signs, algo, dir, false, eff);
+  }
 
   Program &pg = hp.prog;
   pg.npass = 0;
@@ -351,6 +362,8 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
       hp.optional = tail3;
     }
     if (tb == 0 || tb == m) return false;   // nothing to split: the fused program covers it
+    // tied: the chunk is exactly one slice, the table is the one streamed stage (matrix cores)
+    if (tied && (chunk != plan->tied_n2 || tb != m - 1 || plan->radices[m - 1] < 9)) return false;
   }
   auto local = [&](int i) { return eff[i].t < tb; };
   hp.chunk = (int32_t)chunk;
@@ -370,7 +383,10 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
              local(i + len) == local(i))
         ++len;
       bool last_dense = false;
-      if (lift && i + len == m - 1 && eff[m - 1].b == 2 && local(m - 1) == local(i)) {
+      // (tied parameters, forward: the dense stage that ends the slices, see build_effective)
+      const int dense_at = (tied && dir == DIR_FWD) ? m - 2 : m - 1;
+      if (lift && i + len == dense_at && eff[dense_at].b == 2 && eff[dense_at].form == FORM_DENSE &&
+          local(dense_at) == local(i)) {
         ++len;
         last_dense = true;
       }
@@ -392,6 +408,8 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
         int64_t S = eff[i].s;
         for (int e = 0; e < k; ++e) S = std::min<int64_t>(S, eff[i + e].s);
         const int64_t nq = d / P;
+        const int64_t nqp = tied ? chunk / P : nq;   // sub-tensors in the image
+        if (tied && (!local(i) || form != FORM_SCALED)) return false;
         if (form == FORM_SCALED)
           pd.kind = ld ? PASS_POW2_SCALED_LD : PASS_POW2_SCALED;
         else
@@ -402,16 +420,18 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
         pd.P = P;
         pd.S = (int32_t)S;
         pd.nq = (int32_t)nq;
+        pd.nqp = (int32_t)nqp;
+        pd.tied = tied ? 1 : 0;
         pd.V = lift ? (ld ? (k + 1) * P : k * P) : k * (P / 2) * 4;
         offsets.push_back(image.size());
-        image.resize(image.size() + (size_t)pd.V * nq);
+        image.resize(image.size() + (size_t)pd.V * nqp);
         float *img = image.data() + offsets.back();
         for (int e = 0; e < k; ++e) {
           const StageEff &se = eff[i + e];
           const int bp = ilog2(se.s / S);
           // the kernels assume digit position e (ascending) or k-1-e (descending)
           if (bp != (pd.desc ? k - 1 - e : e)) return false;
-          for (int64_t q = 0; q < nq; ++q) {
+          for (int64_t q = 0; q < nqp; ++q) {
             const int64_t hi = q / S, lo = q % S;
             const int64_t base = hi * P * S + lo;
             for (int p = 0; p < P / 2; ++p) {
@@ -421,13 +441,13 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
               const int64_t c = alpha * se.s + beta;
               if (se.form != FORM_DENSE) {
                 const size_t v0 = (size_t)(e * (P / 2) + p) * 2;
-                img[(v0 + 0) * nq + q] = se.la[c];
-                img[(v0 + 1) * nq + q] = se.lb[c];
+                img[(v0 + 0) * nqp + q] = se.la[c];
+                img[(v0 + 1) * nqp + q] = se.lb[c];
               } else {
                 // dense 2x2: inside a lifted pass it follows k-1 lifted stages of P values each
                 const size_t v0 = lift ? (size_t)(k - 1) * P + (size_t)p * 4
                                        : (size_t)(e * (P / 2) + p) * 4;
-                for (int w = 0; w < 4; ++w) img[(v0 + w) * nq + q] = se.dense[(size_t)c * 4 + w];
+                for (int w = 0; w < 4; ++w) img[(v0 + w) * nqp + q] = se.dense[(size_t)c * 4 + w];
               }
             }
           }
@@ -462,6 +482,8 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
         pc.P = P;
         pc.S = (int32_t)S;
         pc.nq = (int32_t)nq;
+        pc.nqp = (int32_t)nq;
+        pc.tied = 0;
         pc.V = kc * NB * 9;
         offsets.push_back(image.size());
         image.resize(image.size() + (size_t)pc.V * nq);
@@ -499,16 +521,20 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
     pd.desc = 0;
     pd.P = b;
     pd.S = (int32_t)se.s;
+    if (tied && (local(i) || b < 9)) return false;   // tied: only the table is streamed
+    const int64_t nqp = tied ? 1 : nq;
     pd.nq = (int32_t)nq;
+    pd.nqp = (int32_t)nqp;
+    pd.tied = tied ? 1 : 0;
     pd.V = b * b;
     offsets.push_back(image.size());
-    image.resize(image.size() + (size_t)pd.V * nq);
+    image.resize(image.size() + (size_t)pd.V * nqp);
     float *img = image.data() + offsets.back();
     // sub-tensor q = hi*S + lo is exactly block c = alpha*s + beta with alpha = hi, beta = lo
-    for (int64_t q = 0; q < nq; ++q)
+    for (int64_t q = 0; q < nqp; ++q)
       for (int r = 0; r < b; ++r)
         for (int r2 = 0; r2 < b; ++r2)
-          img[(size_t)(r * b + r2) * nq + q] = se.dense[((size_t)q * b + r) * b + r2];
+          img[(size_t)(r * b + r2) * nqp + q] = se.dense[((size_t)q * b + r) * b + r2];
     if (small && (b == 4 || b == 8)) {
       // second copy for the equal-radix tile kernel, four values per 16-byte load:
       // value v = 4 * v4 + i of sub-tensor q at float index ((v4 * nq) + q) * 4 + i
@@ -524,9 +550,9 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
       const size_t per = (size_t)KT * KT * 2 * 64 * 4;   // bf16 values per block
       const size_t per32 = (size_t)KT * KT * 64 * 4;     // float32 values per block
       std::vector<uint16_t> &a = aux[pg.npass - 1];
-      a.resize(per * nq + 2 * per32 * nq);               // [nq] bf16 tiles, then [nq] float32 tiles
-      float *a32 = reinterpret_cast<float *>(a.data() + per * nq);
-      for (int64_t q = 0; q < nq; ++q)
+      a.resize(per * nqp + 2 * per32 * nqp);             // [nqp] bf16 tiles, then [nqp] float32 tiles
+      float *a32 = reinterpret_cast<float *>(a.data() + per * nqp);
+      for (int64_t q = 0; q < nqp; ++q)
         pack_mfma_block(se.dense.data() + (size_t)q * b * b, b, a.data() + per * q,
                         a32 + per32 * q);
     }
@@ -618,6 +644,8 @@ harp_status_t run_chunk_passes(const harp_plan_t *plan, const HostProgram &hp, i
   if (wave_supported(plan, hp.prog, p0, p1 - p0, hp.chunk, X, ldx, Y, ldy))
     return launch_wave_kernel(plan, hp, p0, p1 - p0, hp.chunk, X, ldx, dt_in, Y, ldy, dt_out, n,
                               stream);
+  // tied parameters and in-kernel signs exist in the wave kernel only (16-byte aligned rows)
+  if (plan->tied_K > 0) return HARP_ERR_UNSUPPORTED;
   if (radix_supported(plan, hp.prog, p0, p1 - p0, hp.chunk, X, ldx, Y, ldy))
     return launch_radix_kernel(plan, hp, p0, p1 - p0, hp.chunk, X, ldx, dt_in, Y, ldy, dt_out, n,
                                stream);
@@ -853,10 +881,9 @@ const HostProgram *select_program(const harp_plan *plan, Direction dir, int64_t 
 
 }  // namespace harp
 
-extern "C" {
-
-harp_status_t harp_plan_create(harp_plan_t **out, int64_t d, int32_t m, const int32_t *radices,
-                               const float *const *blocks, const int8_t *signs, uint32_t flags) {
+harp_status_t harp::plan_create_impl(harp_plan **out, int64_t d, int32_t m, const int32_t *radices,
+                                     const float *const *blocks, const int8_t *signs,
+                                     uint32_t flags, int32_t tied_K) {
   if (!out || !radices || !blocks) return HARP_ERR_INVALID_ARG;
   if (flags & ~(uint32_t)(HARP_VALIDATE_ORTHO | HARP_BLOCKS_ON_DEVICE)) return HARP_ERR_INVALID_ARG;
   if (d < 2) return HARP_ERR_INVALID_ARG;
@@ -883,6 +910,10 @@ harp_status_t harp_plan_create(harp_plan_t **out, int64_t d, int32_t m, const in
   try {
     plan->d = d;
     plan->m = m;
+    if (tied_K > 0) {
+      plan->tied_K = tied_K;
+      plan->tied_n2 = d / tied_K;
+    }
     {
       const char *e = getenv("HARP_NO_MFMA");   // read once, here: launches never look at the environment
       plan->no_mfma = e && *e && atoi(e) != 0;
@@ -1018,6 +1049,19 @@ harp_status_t harp_plan_create(harp_plan_t **out, int64_t d, int32_t m, const in
       }
     if (st == HARP_OK && !plan->prog[HARP_ALGO_GENERIC][0].ok && !plan->prog[HARP_ALGO_SPLIT][0].ok)
       st = HARP_ERR_UNSUPPORTED;
+    if (st == HARP_OK && tied_K > 0) {
+      // both directions as wave kernel on the slices + matrix-core kernel for the table
+      bool ok = !plan->no_mfma;
+      for (int dir = 0; dir < 2 && ok; ++dir) {
+        const HostProgram &hp = plan->prog[HARP_ALGO_SPLIT][dir];
+        ok = hp.ok && hp.n_chunk + 1 == hp.prog.npass;
+        if (!ok) break;
+        const int p0 = hp.chunk_first ? 0 : 1, ps = hp.chunk_first ? hp.n_chunk : 0;
+        ok = wave_supported(plan, hp.prog, p0, hp.n_chunk, hp.chunk, nullptr, 8, nullptr, 8) &&
+             mfma_pass_supported(hp.prog.pass[ps], nullptr, 8, nullptr, 8);
+      }
+      if (!ok) st = HARP_ERR_UNSUPPORTED;
+    }
     if (st == HARP_OK && signs) {
       int8_t *ds = nullptr;
       if (hipMalloc((void **)&ds, (size_t)d) != hipSuccess) {
@@ -1033,7 +1077,9 @@ harp_status_t harp_plan_create(harp_plan_t **out, int64_t d, int32_t m, const in
     // stage in execution order, and -- when every radix is at most 8 -- the passes over them.
     bool col_ok = true;
     for (int t = 0; t < m; ++t) col_ok = col_ok && radices[t] <= 8;
-    for (int dir = 0; dir < 2 && st == HARP_OK; ++dir) {
+    // (a plan with tied parameters keeps no expanded per-stage images: it cannot be the U side of
+    // a column-mode rotation and has no block gradients)
+    for (int dir = 0; dir < 2 && st == HARP_OK && tied_K == 0; ++dir) {
       std::vector<StageEff> eff;
       build_effective(plan, blk, signs, HARP_ALGO_GENERIC, (Direction)dir, false, eff);
       size_t total = 0;
@@ -1095,6 +1141,13 @@ harp_status_t harp_plan_create(harp_plan_t **out, int64_t d, int32_t m, const in
   }
   *out = plan;
   return HARP_OK;
+}
+
+extern "C" {
+
+harp_status_t harp_plan_create(harp_plan_t **out, int64_t d, int32_t m, const int32_t *radices,
+                               const float *const *blocks, const int8_t *signs, uint32_t flags) {
+  return plan_create_impl(out, d, m, radices, blocks, signs, flags, 0);
 }
 
 harp_status_t harp_plan_destroy(harp_plan_t *plan) {
@@ -1265,6 +1318,7 @@ harp_status_t harp_greedy_schedule(int64_t d, int32_t b_base, int32_t b_max, int
 }
 
 int64_t harp_plan_dim(const harp_plan_t *plan) { return plan ? plan->d : -1; }
+int32_t harp_plan_tied_slices(const harp_plan_t *plan) { return plan ? plan->tied_K : -1; }
 int32_t harp_plan_num_stages(const harp_plan_t *plan) { return plan ? plan->m : -1; }
 
 int64_t harp_plan_param_count(const harp_plan_t *plan) {

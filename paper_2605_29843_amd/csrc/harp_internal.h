@@ -44,7 +44,13 @@ struct PassDesc {
   int32_t S;     // stride of the lowest digit of the pass
   int32_t nq;    // d / P sub-tensors per row
   int32_t V;     // parameter values per sub-tensor
-  const float *params;  // device, [V][nq]: value v of sub-tensor q at params[v * nq + q]
+  // Sub-tensors in the parameter image: nq, or -- in a plan with tied parameters (the Kronecker
+  // fallback, Eq. (12): every slice of n2 coordinates shares one T_{n2}, and all blocks of the
+  // last stage are one table) -- the n2 / P sub-tensors of one slice (a power of two; sub-tensor
+  // q reads entry q mod nqp), or 1 for the shared table.
+  int32_t nqp;
+  int32_t tied;  // 1: parameters indexed modulo nqp
+  const float *params;  // device, [V][nqp]: value v of sub-tensor q at params[v * nqp + q mod nqp]
   // GENERIC, radix >= 9: the blocks as bf16 hi/lo MFMA operand tiles of all sub-tensors,
   // followed by the same tiles in float32; SMALL, radix 4 / 8: a
   // second copy of params, four values per 16-byte load ([V/4][nq][4] floats); else null
@@ -164,6 +170,11 @@ struct harp_plan {
   mutable std::vector<Scratch> scratch;
   mutable std::vector<void *> retired;
   bool no_mfma = false;   // HARP_NO_MFMA was set when the plan was created
+  // Kronecker plan with tied parameters (harp_plan_create_kronecker): K slices of n2 coordinates;
+  // 0: an ordinary plan.  Such a plan has the split program only (wave kernel on the slices +
+  // matrix-core stage for the table); the signs are applied inside the wave kernel.
+  int32_t tied_K = 0;
+  int64_t tied_n2 = 0;
   // column-mode image (every plan) and passes (empty when some radix exceeds 8) per direction
   std::vector<harp::ColStage> col[2];
   std::vector<harp::ColPassHost> colpass[2];
@@ -219,6 +230,10 @@ harp_status_t launch_wave_kernel(const harp_plan *plan, const HostProgram &hp, i
                                  int chunk, const void *X, int64_t ldx, harp_dtype_t dt_in,
                                  void *Y, int64_t ldy, harp_dtype_t dt_out, int64_t n,
                                  hipStream_t stream);
+// extern "C" body of harp_plan_create with the Kronecker tying as an extra argument (harp_api.cpp)
+harp_status_t plan_create_impl(harp_plan **out, int64_t d, int32_t m, const int32_t *radices,
+                               const float *const *blocks, const int8_t *signs, uint32_t flags,
+                               int32_t tied_K);
 // tile kernel for chains of equal radix 4 or 8 on chunks of 4^m / 8^m coordinates (harp_radix.hip)
 bool radix_supported(const harp_plan *plan, const Program &prog, int p0, int np, int chunk,
                      const void *X, int64_t ldx, const void *Y, int64_t ldy);

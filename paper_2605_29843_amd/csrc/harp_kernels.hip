@@ -850,6 +850,7 @@ harp_status_t launch_stream_pass(const harp_plan *plan, const HostProgram &hp, i
   const PassDesc &pd = hp.prog.pass[p];
   if (!plan->no_mfma && mfma_pass_supported(pd, X, ldx, Y, ldy))
     return launch_mfma_pass(plan, pd, X, ldx, dt_in, Y, ldy, dt_out, n, allow_narrow, stream);
+  if (pd.tied) return HARP_ERR_UNSUPPORTED;   // only the matrix-core kernel reads a tied table
   const int ib = dt_in == HARP_BF16, ob = dt_out == HARP_BF16;
   switch (pd.kind) {
     case PASS_POW2_DENSE:

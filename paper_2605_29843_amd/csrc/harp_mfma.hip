@@ -97,16 +97,18 @@ __global__ __launch_bounds__(1024) void harp_stream_mfma_kernel(
   // of all nq blocks
   s4v bh[F32 ? 1 : KT][F32 ? 1 : KT], bl[F32 ? 1 : KT][F32 ? 1 : KT];
   f4v bf[F32 ? KT : 1][F32 ? KT : 1];
+  // block of this wave in the plan's packed image (tied parameters: the one shared table)
+  const size_t qb = pd.tied ? 0 : (size_t)(q0 + w);
   if constexpr (F32) {
     const f4v *bp = reinterpret_cast<const f4v *>(static_cast<const s4v *>(pd.aux) +
-                                                  (size_t)pd.nq * KT * KT * 2 * 64) +
-                    (size_t)(q0 + w) * KT * KT * 64 + l;
+                                                  (size_t)pd.nqp * KT * KT * 2 * 64) +
+                    qb * KT * KT * 64 + l;
 #pragma unroll
     for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
       for (int nt = 0; nt < KT; ++nt) bf[kt][nt] = bp[(kt * KT + nt) * 64];
   } else {
-    const s4v *bp = static_cast<const s4v *>(pd.aux) + (size_t)(q0 + w) * KT * KT * 2 * 64 + l;
+    const s4v *bp = static_cast<const s4v *>(pd.aux) + qb * KT * KT * 2 * 64 + l;
 #pragma unroll
     for (int kt = 0; kt < KT; ++kt)
 #pragma unroll

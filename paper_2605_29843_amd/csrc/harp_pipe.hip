@@ -404,14 +404,16 @@ struct WavePass {
   unsigned base[SPT];
   // window kg of the row; sub-tensors kg * (1024 / P) + t + 64 u of the row's pd.nq
   __device__ __forceinline__ void init(const PassDesc &pd, int t, int kg, bool with_params) {
-    const unsigned nq = (unsigned)pd.nq;
+    const unsigned nq = (unsigned)pd.nq, nqp = (unsigned)pd.nqp;
 #pragma unroll
     for (int u = 0; u < SPT; ++u) {
       const unsigned ql = (unsigned)t + 64u * u;
       const unsigned qg = (unsigned)kg * (1024 / P) + ql;
       const bool ok = with_params && qg < nq;
+      // tied parameters (Kronecker plans): every slice reads the one image, nqp a power of two
+      const unsigned qp = pd.tied ? (qg & (nqp - 1u)) : qg;
 #pragma unroll
-      for (int v = 0; v < NV; ++v) prm[u * NV + v] = ok ? ((gparams_t)pd.params)[(unsigned)v * nq + qg] : 0.0f;
+      for (int v = 0; v < NV; ++v) prm[u * NV + v] = ok ? ((gparams_t)pd.params)[(unsigned)v * nqp + qp] : 0.0f;
       const unsigned hi = ql >> LOGS, lo = ql & (S - 1);
       base[u] = ((hi << K) << LOGS) | lo;
     }
@@ -487,11 +489,14 @@ __device__ __forceinline__ void wave_exchange(float (&x)[16], float *buf, const 
   __syncthreads();
 }
 
-template <typename TI, typename TO, int K0, int K1, int K2, bool TRN, bool LD, bool SC>
+// SGN: the +-1 signs of the processor applied here instead of being folded into the stage
+// parameters (plans with tied parameters): 1 = on the coordinates as loaded, 2 = as stored.
+template <typename TI, typename TO, int K0, int K1, int K2, bool TRN, bool LD, bool SC, int SGN = 0>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void harp_wave_kernel(const TI *__restrict__ X, int64_t ldx,
                                                        TO *__restrict__ Y, int64_t ldy, int64_t n,
                                                        int R, int ngroups, int d,
-                                                       const Program *__restrict__ progp, int p0) {
+                                                       const Program *__restrict__ progp, int p0,
+                                                       const int8_t *__restrict__ signs = nullptr) {
   constexpr bool THREE = (K2 != 0);
   constexpr int LS0 = TRN ? K1 + K2 : 0, LS1 = TRN ? K2 : K0, LS2 = TRN ? 0 : K0 + K1;
   __shared__ float buf[(1024 / 256) * 272];
@@ -516,6 +521,19 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void ha
   constexpr bool kLastIsIo = THREE ? (K2 == 4 && LS2 == 0) : (K1 == 4 && LS1 == 0);
   const bool active = 16 * t < valid;
   auto goff = [&](int e) -> unsigned { return (unsigned)w0 + io.coord(e); };
+  // sign bit of each of the thread's 16 coordinates, in the layout the signs are applied in
+  uint32_t sgn[SGN ? 16 : 1];
+  if (SGN) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const unsigned c = (SGN == 1 || kLastIsIo) ? io.coord(e) : sl.coord(e);
+      sgn[e] = ((int)c < valid && signs[(unsigned)w0 + c] < 0) ? 0x80000000u : 0u;
+    }
+  }
+  auto flip = [&](float (&x)[16]) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) x[e] = __uint_as_float(__float_as_uint(x[e]) ^ sgn[SGN ? e : 0]);
+  };
 
   using In = RowIo<TI, true>;
   using Out = RowIo<TO, true>;
@@ -541,6 +559,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void ha
       float x[16];
       In::unpack(pre[s], x);
       if (active && r + PF < nr) In::load(X + (row0 + r + PF) * ldx, goff, pre[s]);
+      if (SGN == 1) flip(x);
 
       if (!(K0 == 4 && LS0 == 0)) wave_exchange(x, buf, io, pa);
       lift_stages<K0, TRN, false, SC>(x, pa.prm);
@@ -553,6 +572,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void ha
       } else {
         if (!kLastIsIo) wave_exchange(x, buf, pb, sl);
       }
+      if (SGN == 2) flip(x);
       if (kLastIsIo) {
         if (active) Out::store(Y + (row0 + r) * ldy, goff, x);
       } else {
@@ -587,17 +607,39 @@ struct WaveArgs {
   int R;
   int d;
   hipStream_t stream;
+  const int8_t *signs;
 };
 
-template <typename TI, typename TO, int K0, int K1, int K2, bool TRN, bool LD, bool SC>
+template <typename TI, typename TO, int K0, int K1, int K2, bool TRN, bool LD, bool SC, int SGN = 0>
 harp_status_t launch_wave_inst(const WaveArgs &a) {
   const int ngroups = (a.d + 1023) / 1024;
   const int64_t tiles = ((a.n + a.R - 1) / a.R) * ngroups;
   if (tiles > 0x7fffffff) return HARP_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL((harp_wave_kernel<TI, TO, K0, K1, K2, TRN, LD, SC>), dim3((unsigned)tiles),
+  hipLaunchKernelGGL((harp_wave_kernel<TI, TO, K0, K1, K2, TRN, LD, SC, SGN>), dim3((unsigned)tiles),
                      dim3(64), 0, a.stream, (const TI *)a.X, a.ldx, (TO *)a.Y, a.ldy, a.n, a.R,
-                     ngroups, a.d, a.dprog, a.p0);
+                     ngroups, a.d, a.dprog, a.p0, a.signs);
   return hipGetLastError() == hipSuccess ? HARP_OK : HARP_ERR_DEVICE;
+}
+
+// Plans with tied parameters: two-shear form with a dense stage at the end of the slices in both
+// directions; forward = the slices come first (signs on the loaded coordinates), transposed =
+// the slices come last (signs on the stored coordinates).  sgn = false: the plan has no signs.
+template <typename TI, typename TO, int K0, int K1, int K2>
+harp_status_t launch_wave_tied(const WaveArgs &a, bool trn, bool sgn) {
+  if (trn)
+    return sgn ? launch_wave_inst<TI, TO, K0, K1, K2, true, true, true, 2>(a)
+               : launch_wave_inst<TI, TO, K0, K1, K2, true, true, true, 0>(a);
+  return sgn ? launch_wave_inst<TI, TO, K0, K1, K2, false, true, true, 1>(a)
+             : launch_wave_inst<TI, TO, K0, K1, K2, false, true, true, 0>(a);
+}
+
+template <typename TI, typename TO>
+harp_status_t launch_wave_tied_io(const WaveArgs &a, int logc, bool trn, bool sgn) {
+  if (logc == 8) return launch_wave_tied<TI, TO, 4, 4, 0>(a, trn, sgn);
+  if (logc == 9) return launch_wave_tied<TI, TO, 3, 3, 3>(a, trn, sgn);
+  if (logc == 10)
+    return trn ? launch_wave_tied<TI, TO, 3, 3, 4>(a, trn, sgn) : launch_wave_tied<TI, TO, 4, 3, 3>(a, trn, sgn);
+  return HARP_ERR_UNSUPPORTED;
 }
 
 template <typename TI, typename TO, int K0, int K1, int K2, bool SC, bool TRN>
@@ -763,7 +805,16 @@ harp_status_t launch_wave_kernel(const harp_plan *plan, const HostProgram &hp, i
   if (plan->rows_override <= 0 && R > 16) R = 16;
   if (R > n) R = n;
   if (R < 1) R = 1;
-  WaveArgs a{hp.dev, p0, X, ldx, Y, ldy, n, (int)R, (int)plan->d, stream};
+  WaveArgs a{hp.dev, p0, X, ldx, Y, ldy, n, (int)R, (int)plan->d, stream, plan->dev_signs};
+  if (plan->tied_K > 0) {
+    // shear form with a dense stage at the end of the slices, in both directions
+    if (!sc || !ld) return HARP_ERR_UNSUPPORTED;
+    const bool sgn = plan->dev_signs != nullptr;
+    if (dt_in == HARP_BF16 && dt_out == HARP_BF16) return launch_wave_tied_io<uint16_t, uint16_t>(a, logc, trn, sgn);
+    if (dt_in == HARP_BF16 && dt_out == HARP_F32) return launch_wave_tied_io<uint16_t, float>(a, logc, trn, sgn);
+    if (dt_in == HARP_F32 && dt_out == HARP_BF16) return launch_wave_tied_io<float, uint16_t>(a, logc, trn, sgn);
+    return launch_wave_tied_io<float, float>(a, logc, trn, sgn);
+  }
   if (dt_in == HARP_BF16 && dt_out == HARP_BF16)
     return launch_wave_io<uint16_t, uint16_t>(a, logc, trn, ld, sc);
   if (dt_in == HARP_BF16 && dt_out == HARP_F32)

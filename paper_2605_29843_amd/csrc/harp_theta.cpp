@@ -13,7 +13,7 @@
 #include <new>
 #include <vector>
 
-#include "harp.h"
+#include "harp_internal.h"
 
 namespace {
 
@@ -298,6 +298,41 @@ harp_status_t harp_kronecker_blocks(int32_t K, const float *table, int64_t n2, i
   for (int64_t c = 0; c < n2; ++c)
     for (int i = 0; i < K * K; ++i) blocks_out[m2][(size_t)c * K * K + i] = (float)(table[i] * s);
   return HARP_OK;
+}
+
+harp_status_t harp_plan_create_kronecker(harp_plan_t **out, int32_t K, const float *table,
+                                         int64_t n2, int32_t m2, const int32_t *radices2,
+                                         const float *const *blocks2, const int8_t *signs,
+                                         uint32_t flags) {
+  if (!out || !table || !radices2 || !blocks2) return HARP_ERR_INVALID_ARG;
+  if (flags & ~(uint32_t)HARP_VALIDATE_ORTHO) return HARP_ERR_INVALID_ARG;
+  if (K < 2 || n2 < 2 || m2 < 1) return HARP_ERR_INVALID_ARG;
+  if (K > HARP_MAX_RADIX || m2 + 1 > HARP_MAX_STAGES) return HARP_ERR_UNSUPPORTED;
+  if (n2 > ((int64_t)1 << 24) / K) return HARP_ERR_UNSUPPORTED;
+  harp_status_t st = check_schedule(n2, m2, radices2);
+  if (st != HARP_OK) return st;
+  try {
+    // the equivalent Mixed-Radix processor (host copies of every slice's blocks: what the oracle
+    // and the untied kernels consume; the tied plan keeps one slice's image on the device)
+    std::vector<int32_t> radices(m2 + 1);
+    std::vector<std::vector<float>> store(m2 + 1);
+    std::vector<float *> outs(m2 + 1);
+    for (int t = 0; t < m2; ++t) store[t].resize((size_t)K * n2 * radices2[t]);
+    store[m2].resize((size_t)n2 * K * K);
+    for (int t = 0; t <= m2; ++t) outs[t] = store[t].data();
+    st = harp_kronecker_blocks(K, table, n2, m2, radices2, blocks2, radices.data(), outs.data());
+    if (st != HARP_OK) return st;
+    std::vector<const float *> blk(outs.begin(), outs.end());
+    const int64_t d = (int64_t)K * n2;
+    st = harp::plan_create_impl(out, d, m2 + 1, radices.data(), blk.data(), signs, flags, K);
+    // no kernel reads a tied image for this shape (slices other than 256 / 512 / 1024 radix-2
+    // coordinates, a table below order 9, blocks outside the two-shear form): the expansion
+    if (st == HARP_ERR_UNSUPPORTED)
+      st = harp::plan_create_impl(out, d, m2 + 1, radices.data(), blk.data(), signs, flags, 0);
+    return st;
+  } catch (const std::bad_alloc &) {
+    return HARP_ERR_OOM;
+  }
 }
 
 }  // extern "C"

@@ -42,6 +42,9 @@ _SIGS = {
                                       C.POINTER(_vp), C.POINTER(_vp)]),
     "harp_kronecker_blocks": (_i32, [_i32, _vp, _i64, _i32, C.POINTER(_i32), C.POINTER(_vp),
                                      C.POINTER(_i32), C.POINTER(_vp)]),
+    "harp_plan_create_kronecker": (_i32, [C.POINTER(_vp), _i32, _vp, _i64, _i32, C.POINTER(_i32),
+                                          C.POINTER(_vp), _vp, _u32]),
+    "harp_plan_tied_slices": (_i32, [_vp]),
     "harp_plan_create_from_theta": (_i32, [C.POINTER(_vp), _i64, _i32, C.POINTER(_i32), C.POINTER(_vp),
                                            C.POINTER(_i32), C.POINTER(_vp), _vp, _u32]),
     "harp_theta_quantize_int8": (_i32, [_i64, _i32, C.POINTER(_i32), C.POINTER(_vp), C.POINTER(_vp),
@@ -319,6 +322,35 @@ class Plan:
                                                     mx, sp, int(flags)),
                "harp_plan_create_from_theta_int8")
         return self
+
+    @classmethod
+    def kronecker(cls, table, n2: int, radices2, blocks2, signs=None, flags: int = 0):
+        """``harp_plan_create_kronecker``: (table / sqrt(K)) (x) T_{n2} with tied parameters."""
+        self = cls.__new__(cls)
+        table = np.ascontiguousarray(table, dtype=np.float32)
+        K = int(table.shape[0])
+        if table.shape != (K, K):
+            raise ValueError("table must be square")
+        radices2 = [int(b) for b in radices2]
+        m2 = len(radices2)
+        ins = [np.ascontiguousarray(blocks2[t], dtype=np.float32) for t in range(m2)]
+        rad2 = (_i32 * max(m2, 1))(*radices2)
+        ip = (_vp * max(m2, 1))(*[a.ctypes.data for a in ins])
+        sp = None
+        if signs is not None:
+            s = np.ascontiguousarray(signs, dtype=np.int8)
+            if s.size != K * int(n2):
+                raise ValueError("signs must hold K * n2 values")
+            sp = s.ctypes.data
+        self._h = _vp(None)
+        self._keep = []
+        self.d, self.radices = K * int(n2), radices2 + [K]
+        _check(lib.harp_plan_create_kronecker(C.byref(self._h), K, table.ctypes.data, int(n2), m2, rad2,
+                                              ip, sp, int(flags)), "harp_plan_create_kronecker")
+        return self
+
+    def tied_slices(self) -> int:
+        return int(lib.harp_plan_tied_slices(self._h))
 
     # -- lifetime
     def destroy(self):

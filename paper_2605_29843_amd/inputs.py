@@ -123,6 +123,49 @@ def make_blocks(d: int, radices, kind: str, rng: np.random.Generator):
     return out
 
 
+def hadamard_table(K: int) -> np.ndarray:
+    """A K x K matrix with entries +-1 and H H^T = K I (float32), by Paley's constructions:
+    order q + 1 for a prime q = 3 (mod 4), order 2 (q + 1) for a prime q = 1 (mod 4), doubled
+    (Sylvester) as often as needed.  Covers 2, 4, 8, 12, 16, 20, 24, 28, 32, 36, 40, 44, 48, 56, 60, 64."""
+    def is_prime(q):
+        return q >= 2 and all(q % p for p in range(2, int(q ** 0.5) + 1))
+
+    def jacobsthal(q):
+        res = {(x * x) % q for x in range(1, q)}
+        return np.array([[0 if i == j else (1 if ((i - j) % q) in res else -1) for j in range(q)]
+                         for i in range(q)], dtype=np.int64)
+
+    def build(k):
+        if k == 1:
+            return np.ones((1, 1), dtype=np.int64)
+        if k == 2:
+            return np.array([[1, 1], [1, -1]], dtype=np.int64)
+        q = k - 1
+        if k % 4 == 0 and is_prime(q) and q % 4 == 3:           # Paley I
+            S = np.zeros((k, k), dtype=np.int64)
+            S[0, 1:] = 1
+            S[1:, 0] = -1
+            S[1:, 1:] = jacobsthal(q)
+            return np.eye(k, dtype=np.int64) + S
+        q = k // 2 - 1
+        if k % 4 == 0 and is_prime(q) and q % 4 == 1:           # Paley II
+            C0 = np.zeros((q + 1, q + 1), dtype=np.int64)       # symmetric conference matrix
+            C0[0, 1:] = 1
+            C0[1:, 0] = 1
+            C0[1:, 1:] = jacobsthal(q)
+            A = np.array([[1, 1], [1, -1]], dtype=np.int64)
+            B = np.array([[1, -1], [-1, -1]], dtype=np.int64)
+            return np.kron(C0, A) + np.kron(np.eye(q + 1, dtype=np.int64), B)
+        if k % 2 == 0:
+            h = build(k // 2)
+            return np.block([[h, h], [h, -h]])
+        raise ValueError(f"no construction for a Hadamard matrix of order {k} here")
+
+    H = build(int(K))
+    assert np.array_equal(H @ H.T, K * np.eye(K, dtype=np.int64)), K
+    return H.astype(np.float32)
+
+
 def make_signs(d: int, rng: np.random.Generator) -> np.ndarray:
     return (rng.integers(0, 2, size=d).astype(np.int8) * 2 - 1).astype(np.int8)
 

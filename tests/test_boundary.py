@@ -82,6 +82,42 @@ def test_greedy_schedule_library_and_oracle_agree_on_many_dimensions():
                 (d, b_base, b_max)
 
 
+def test_kronecker_plan_argument_errors_come_before_any_device_work():
+    lib = harp.lib
+    H = gi.hadamard_table(12)
+    rad = (C.c_int32 * 8)(*([2] * 8))
+    blocks2 = gi.make_blocks(256, [2] * 8, "orth", np.random.default_rng(0))
+    bp = (C.c_void_p * 8)(*[b.ctypes.data for b in blocks2])
+    out = C.c_void_p(None)
+
+    def call(K, table, n2=256, m2=8, flags=0):
+        return lib.harp_plan_create_kronecker(C.byref(out), K, table.ctypes.data if table is not None else None,
+                                              n2, m2, rad, bp, None, flags)
+    assert call(12, None) == harp.HARP_ERR_INVALID_ARG
+    assert call(1, H) == harp.HARP_ERR_INVALID_ARG
+    assert call(12, H, flags=harp.HARP_BLOCKS_ON_DEVICE) == harp.HARP_ERR_INVALID_ARG
+    assert call(12, H, n2=250) == harp.HARP_ERR_BAD_SCHEDULE
+    bad = H.copy()
+    bad[3, 4] = 0.5
+    assert call(12, bad) == harp.HARP_ERR_INVALID_ARG
+    notorth = H.copy()
+    notorth[0, :] = 1.0
+    notorth[1, :] = 1.0
+    assert call(12, notorth) == harp.HARP_ERR_NOT_ORTHOGONAL
+    assert call(65, np.ones((65, 65), np.float32)) == harp.HARP_ERR_UNSUPPORTED
+    assert out.value is None
+    assert lib.harp_plan_tied_slices(None) == -1
+
+
+def test_hadamard_table_generator():
+    for K in (2, 4, 12, 20, 28, 36, 64):
+        H = gi.hadamard_table(K).astype(np.float64)
+        assert set(np.unique(H)) <= {-1.0, 1.0}
+        np.testing.assert_array_equal(H @ H.T, K * np.eye(K))
+    with pytest.raises(ValueError):
+        gi.hadamard_table(6)
+
+
 def test_make_blocks_kinds():
     """'generic' blocks are really non-orthogonal (and well conditioned); unknown kinds raise."""
     rng = np.random.default_rng(0)

@@ -795,6 +795,104 @@ def test_kronecker_fallback_plan(harp):
     plan.destroy()
 
 
+@pytest.mark.parametrize("K,n2,n,dtype,with_signs", [
+    (12, 1024, 19, "bf16", True), (28, 512, 33, "f32", True), (20, 256, 70, "bf16", False),
+    (28, 1024, 40, "bf16", True), (12, 1024, 5, "f32", False), (36, 256, 130, "bf16", True),
+    (64, 512, 3, "f32", True)])
+def test_kronecker_plan_with_tied_parameters(harp, K, n2, n, dtype, with_signs):
+    """harp_plan_create_kronecker: one slice's parameters and one table on the device, read by
+    every slice; apply and apply_transpose against the definition (H~/sqrt(K)) (x) T_{n2} with
+    the signs on the input coordinates, and against the expanded (untied) plan."""
+    import torch
+    H = gi.hadamard_table(K)
+    radices2 = [2] * int(np.log2(n2))
+    rng = np.random.default_rng(K * n2 + n)
+    blocks2 = gi.make_blocks(n2, radices2, "orth", rng)
+    d = K * n2
+    signs = gi.make_signs(d, rng) if with_signs else None
+    plan = harp.Plan.kronecker(H, n2, radices2, blocks2, signs)
+    radices, blocks = harp.harp_kronecker_blocks(H, n2, radices2, blocks2)
+    full = harp.Plan(d, radices, blocks, signs)
+    say(f"tied kronecker K={K} n2={n2} n={n} {dtype} signs={with_signs} kernel={plan.kernel_name(n)} "
+        f"param bytes {plan.param_bytes()} vs {full.param_bytes()}")
+    assert plan.tied_slices() == K and full.tied_slices() == 0
+    assert plan.param_bytes() * (K // 2) < full.param_bytes()
+    X = rng.standard_normal((n, d)).astype(np.float32)
+    if dtype == "bf16":
+        X = gi.round_to_bf16(X)
+    Xd = to_device(X, dtype)
+    Y, Z = harp.harp_apply(plan, Xd), harp.harp_apply_transpose(plan, Xd)
+    Yf, Zf = harp.harp_apply(full, Xd), harp.harp_apply_transpose(full, Xd)
+    torch.cuda.synchronize()
+    T2 = ho.build_U(n2, radices2, blocks2)
+    Hn = H.astype(np.float64) / np.sqrt(float(K))
+    sg = np.ones(d) if signs is None else signs.astype(np.float64)
+    X64 = X.astype(np.float64)
+    ref = np.einsum("nkj,kl,jm->nlm", (X64 * sg).reshape(n, K, n2), Hn, T2).reshape(n, d)
+    reft = np.einsum("nlm,kl,jm->nkj", X64.reshape(n, K, n2), Hn, T2).reshape(n, d) * sg
+    assert_parity(to_host64(Y), ref, dtype, "tied apply")
+    assert_parity(to_host64(Z), reft, dtype, "tied apply_transpose")
+    assert_parity(to_host64(Yf), ref, dtype, "expanded apply")
+    assert_parity(to_host64(Zf), reft, dtype, "expanded apply_transpose")
+    # padded leading dimension (a multiple of 8) and in place
+    big = torch.zeros(n, d + 16, dtype=Xd.dtype, device="cuda")
+    big[:, :d] = Xd
+    harp.harp_apply(plan, big[:, :d], big[:, :d])
+    torch.cuda.synchronize()
+    assert_parity(to_host64(big[:, :d]), ref, dtype, "tied apply in place, padded")
+    assert bool((big[:, d:] == 0).all())
+    plan.destroy()
+    full.destroy()
+
+
+def test_kronecker_plan_falls_back_to_the_expansion_and_refuses_unaligned_rows(harp):
+    import torch
+    rng = np.random.default_rng(5)
+    # a table of order 4 (below 9) and slices with a radix other than 2: no tied kernel, same results
+    for K, n2, radices2 in ((4, 1024, [2] * 10), (12, 192, [4, 6, 8])):
+        H = gi.hadamard_table(K)
+        blocks2 = gi.make_blocks(n2, radices2, "orth", rng)
+        d = K * n2
+        signs = gi.make_signs(d, rng)
+        plan = harp.Plan.kronecker(H, n2, radices2, blocks2, signs)
+        assert plan.tied_slices() == 0
+        X = gi.round_to_bf16(rng.standard_normal((7, d)).astype(np.float32))
+        Y = to_host64(harp.harp_apply(plan, to_device(X, "bf16")))
+        torch.cuda.synchronize()
+        T2 = ho.build_U(n2, radices2, blocks2)
+        ref = np.einsum("nkj,kl,jm->nlm", (X.astype(np.float64) * signs).reshape(7, K, n2),
+                        H.astype(np.float64) / np.sqrt(float(K)), T2).reshape(7, d)
+        assert_parity(Y, ref, "bf16", "fallback apply")
+        plan.destroy()
+    # tied plan: rows that are not 16-byte aligned are refused, not mis-read
+    H = gi.hadamard_table(12)
+    blocks2 = gi.make_blocks(256, [2] * 8, "orth", rng)
+    plan = harp.Plan.kronecker(H, 256, [2] * 8, blocks2, None)
+    assert plan.tied_slices() == 12
+    big = torch.zeros(4, 12 * 256 + 3, dtype=torch.float32, device="cuda")
+    with pytest.raises(harp.HarpError) as e:
+        harp.harp_apply(plan, big[:, 1:1 + 12 * 256])
+    assert e.value.status == harp.HARP_ERR_UNSUPPORTED
+    with pytest.raises(harp.HarpError) as e:
+        plan.set_algo(harp.HARP_ALGO_FUSED)
+    assert e.value.status == harp.HARP_ERR_UNSUPPORTED
+    # as the row-side processor of a weight rotation
+    W = rng.standard_normal((24, 12 * 256)).astype(np.float32)
+    pu = harp.Plan(24, [2, 3, 4], gi.make_blocks(24, [2, 3, 4], "orth", rng))
+    out = harp.harp_rotate_weight(pu, plan, to_device(W, "f32"))
+    torch.cuda.synchronize()
+    T2 = ho.build_U(256, [2] * 8, blocks2)
+    Uu = ho.build_U(24, [2, 3, 4], gi.make_blocks(24, [2, 3, 4], "orth", np.random.default_rng(0)))
+    del Uu
+    radices, blocks = harp.harp_kronecker_blocks(H, 256, [2] * 8, blocks2)
+    full = harp.Plan(12 * 256, radices, blocks, None)
+    ref = harp.harp_rotate_weight(pu, full, to_device(W, "f32"))
+    torch.cuda.synchronize()
+    assert float((out - ref).abs().max()) <= 2e-6 * float(ref.abs().max())
+    for p_ in (plan, full, pu):
+        p_.destroy()
+
+
 RADIX_TILE_CASES = [
     (512, [8] * 3, 19), (4096, [8] * 4, 37), (4096, [8] * 4, 1), (256, [4] * 4, 9), (1024, [4] * 5, 21),
     (4096, [4] * 6, 13), (4096, [8] * 4, 8),
