@@ -123,6 +123,18 @@ struct RowIo<uint16_t, true> {      // 16 contiguous bf16 (or 2 x 8): two 16-byt
       *reinterpret_cast<uint4 *>(yr + off(8 * h)) =
           make_uint4(w[4 * h], w[4 * h + 1], w[4 * h + 2], w[4 * h + 3]);
   }
+  // the same with the sign bits of the packed elements flipped where flip[m] has them set
+  template <class OFF>
+  __device__ static __forceinline__ void store_flipped(uint16_t *yr, OFF off, const float (&x)[16],
+                                                       const uint32_t (&flip)[8]) {
+    uint32_t w[8];
+#pragma unroll
+    for (int m = 0; m < 8; ++m) w[m] = cvt_pk_bf16(x[2 * m], x[2 * m + 1]) ^ flip[m];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+      *reinterpret_cast<uint4 *>(yr + off(8 * h)) =
+          make_uint4(w[4 * h], w[4 * h + 1], w[4 * h + 2], w[4 * h + 3]);
+  }
 };
 
 template <>
@@ -437,6 +449,20 @@ struct WaveStoreLayout {
   }
   // pieces whose coordinates lie inside the row (valid = coordinates of the window inside it)
   __device__ __forceinline__ void store(TO *yw, const float (&x)[16], int valid) const;
+  // bf16 only: sign bits of the packed elements flipped where flip[m] has them set
+  __device__ __forceinline__ void store_flipped(uint16_t *yw, const float (&x)[16], int valid,
+                                                const uint32_t (&flip)[8]) const {
+#pragma unroll
+    for (int g = 0; g < 2; ++g) {
+      const unsigned c = coord(8 * g);
+      if ((int)c < valid)
+        *reinterpret_cast<uint4 *>(yw + c) =
+            make_uint4(cvt_pk_bf16(x[8 * g], x[8 * g + 1]) ^ flip[4 * g],
+                       cvt_pk_bf16(x[8 * g + 2], x[8 * g + 3]) ^ flip[4 * g + 1],
+                       cvt_pk_bf16(x[8 * g + 4], x[8 * g + 5]) ^ flip[4 * g + 2],
+                       cvt_pk_bf16(x[8 * g + 6], x[8 * g + 7]) ^ flip[4 * g + 3]);
+    }
+  }
 };
 template <>
 __device__ __forceinline__ void WaveStoreLayout<float>::store(float *yw, const float (&x)[16],
@@ -521,20 +547,30 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void ha
   constexpr bool kLastIsIo = THREE ? (K2 == 4 && LS2 == 0) : (K1 == 4 && LS1 == 0);
   const bool active = 16 * t < valid;
   auto goff = [&](int e) -> unsigned { return (unsigned)w0 + io.coord(e); };
-  // sign bit of each of the thread's 16 coordinates, in the layout the signs are applied in
-  uint32_t sgn[SGN ? 16 : 1];
+  // Signs of the thread's 16 coordinates in the layout they are applied in.  bf16 side: as
+  // flip words for the packed pairs (bit 15 = element 2m, bit 31 = element 2m + 1), one
+  // exclusive-or per two coordinates; float32 side: one bit per element in a single register
+  // (sixteen flip words would push the three-pass instances past 256 registers).
+  constexpr bool kFlipIn = (SGN == 1), kFlipOut = (SGN == 2);
+  constexpr bool kPackedFlip = (kFlipIn && sizeof(TI) == 2) || (kFlipOut && sizeof(TO) == 2);
+  uint32_t sgw[kPackedFlip ? 8 : 1] = {};
+  uint32_t sgm = 0;
   if (SGN) {
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
-      const unsigned c = (SGN == 1 || kLastIsIo) ? io.coord(e) : sl.coord(e);
-      sgn[e] = ((int)c < valid && signs[(unsigned)w0 + c] < 0) ? 0x80000000u : 0u;
+      const unsigned c = (kFlipIn || kLastIsIo) ? io.coord(e) : sl.coord(e);
+      const uint32_t neg = ((int)c < valid && signs[(unsigned)w0 + c] < 0) ? 1u : 0u;
+      if (kPackedFlip) sgw[kPackedFlip ? e / 2 : 0] |= neg << (15 + 16 * (e & 1));
+      else sgm |= neg << e;
     }
   }
-  auto flip = [&](float (&x)[16]) {
+  auto flip_f32 = [&](float (&x)[16]) {   // sign from (x ^ shifted mask), magnitude from x
 #pragma unroll
-    for (int e = 0; e < 16; ++e) x[e] = __uint_as_float(__float_as_uint(x[e]) ^ sgn[SGN ? e : 0]);
+    for (int e = 0; e < 16; ++e) {
+      const uint32_t u = __float_as_uint(x[e]);
+      x[e] = __uint_as_float((u & 0x7fffffffu) | ((u ^ (sgm << (31 - e))) & 0x80000000u));
+    }
   };
-
   using In = RowIo<TI, true>;
   using Out = RowIo<TO, true>;
   constexpr int NRAW = In::NRAW;
@@ -557,9 +593,16 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void ha
       const int r = r0 + s;
       if (r >= nr) break;
       float x[16];
-      In::unpack(pre[s], x);
+      if constexpr (kFlipIn && kPackedFlip) {
+        uint32_t w[NRAW];
+#pragma unroll
+        for (int m = 0; m < NRAW; ++m) w[m] = pre[s][m] ^ sgw[m & 7];
+        In::unpack(w, x);
+      } else {
+        In::unpack(pre[s], x);
+      }
       if (active && r + PF < nr) In::load(X + (row0 + r + PF) * ldx, goff, pre[s]);
-      if (SGN == 1) flip(x);
+      if (kFlipIn && !kPackedFlip) flip_f32(x);
 
       if (!(K0 == 4 && LS0 == 0)) wave_exchange(x, buf, io, pa);
       lift_stages<K0, TRN, false, SC>(x, pa.prm);
@@ -572,8 +615,14 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void ha
       } else {
         if (!kLastIsIo) wave_exchange(x, buf, pb, sl);
       }
-      if (SGN == 2) flip(x);
-      if (kLastIsIo) {
+      if (kFlipOut && !kPackedFlip) flip_f32(x);
+      if constexpr (kFlipOut && kPackedFlip) {
+        if (kLastIsIo) {
+          if (active) Out::store_flipped(Y + (row0 + r) * ldy, goff, x, sgw);
+        } else {
+          sl.store_flipped(Y + (row0 + r) * ldy + w0, x, valid, sgw);
+        }
+      } else if (kLastIsIo) {
         if (active) Out::store(Y + (row0 + r) * ldy, goff, x);
       } else {
         sl.store(Y + (row0 + r) * ldy + w0, x, valid);
@@ -624,21 +673,20 @@ harp_status_t launch_wave_inst(const WaveArgs &a) {
 // Plans with tied parameters: two-shear form with a dense stage at the end of the slices in both
 // directions; forward = the slices come first (signs on the loaded coordinates), transposed =
 // the slices come last (signs on the stored coordinates).  sgn = false: the plan has no signs.
-template <typename TI, typename TO, int K0, int K1, int K2>
-harp_status_t launch_wave_tied(const WaveArgs &a, bool trn, bool sgn) {
-  if (trn)
-    return sgn ? launch_wave_inst<TI, TO, K0, K1, K2, true, true, true, 2>(a)
-               : launch_wave_inst<TI, TO, K0, K1, K2, true, true, true, 0>(a);
-  return sgn ? launch_wave_inst<TI, TO, K0, K1, K2, false, true, true, 1>(a)
-             : launch_wave_inst<TI, TO, K0, K1, K2, false, true, true, 0>(a);
+template <typename TI, typename TO, int K0, int K1, int K2, bool TRN>
+harp_status_t launch_wave_tied(const WaveArgs &a, bool sgn) {
+  return sgn ? launch_wave_inst<TI, TO, K0, K1, K2, TRN, true, true, (TRN ? 2 : 1)>(a)
+             : launch_wave_inst<TI, TO, K0, K1, K2, TRN, true, true, 0>(a);
 }
 
 template <typename TI, typename TO>
 harp_status_t launch_wave_tied_io(const WaveArgs &a, int logc, bool trn, bool sgn) {
-  if (logc == 8) return launch_wave_tied<TI, TO, 4, 4, 0>(a, trn, sgn);
-  if (logc == 9) return launch_wave_tied<TI, TO, 3, 3, 3>(a, trn, sgn);
+  if (logc == 8)
+    return trn ? launch_wave_tied<TI, TO, 4, 4, 0, true>(a, sgn) : launch_wave_tied<TI, TO, 4, 4, 0, false>(a, sgn);
+  if (logc == 9)
+    return trn ? launch_wave_tied<TI, TO, 3, 3, 3, true>(a, sgn) : launch_wave_tied<TI, TO, 3, 3, 3, false>(a, sgn);
   if (logc == 10)
-    return trn ? launch_wave_tied<TI, TO, 3, 3, 4>(a, trn, sgn) : launch_wave_tied<TI, TO, 4, 3, 3>(a, trn, sgn);
+    return trn ? launch_wave_tied<TI, TO, 3, 3, 4, true>(a, sgn) : launch_wave_tied<TI, TO, 4, 3, 3, false>(a, sgn);
   return HARP_ERR_UNSUPPORTED;
 }
 
