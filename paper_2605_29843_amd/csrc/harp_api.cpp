@@ -563,6 +563,32 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
   hp.dpp = DppImage();
   if (algo == HARP_ALGO_FUSED && chunk == 4096 && tb == 12 && m == 12)
     build_dpp_image(plan, eff, 0, dir, hp, image);
+  // Transposed split program of twelve radix-2 stages below one dense stage of radix 3 or 5
+  // (12288, 20480; radix 7 measured no gain): that stage runs first and is executed by the DPP kernel's first
+  // group on the way in (harp_dpp_top_kernel).  Its factors: for output chunk kch, input chunk
+  // j and coordinate c of the chunk, entry [j][kch] of block c as this direction uses it.
+  if (algo == HARP_ALGO_SPLIT && dir == DIR_TRN && !tied && chunk == 4096 && tb == 12 && m == 13 &&
+      (eff[0].b == 3 || eff[0].b == 5) && eff[0].form == FORM_DENSE &&
+      eff[0].s == 4096 && d == 4096 * (int64_t)eff[0].b) {
+    build_dpp_image(plan, eff, 1, dir, hp, image);
+    if (hp.dpp.host_off >= 0) {
+      const int b = eff[0].b;
+      const size_t off = image.size();
+      image.resize(off + (size_t)b * b * 4096);
+      float *tp = image.data() + off;
+      for (int kch = 0; kch < b; ++kch)
+        for (int j = 0; j < b; ++j)
+          for (int k = 0; k < 4; ++k)
+            for (int t = 0; t < 256; ++t)
+              for (int q = 0; q < 4; ++q) {
+                const int64_t c = 16 * (int64_t)dpp_segment_of(true, (unsigned)t) + 4 * k + q;
+                tp[((((size_t)kch * b + j) * 4 + k) * 256 + t) * 4 + q] =
+                    eff[0].dense[((size_t)c * b + j) * b + kch];
+              }
+      hp.dpp.topB = b;
+      hp.dpp.offT = (int64_t)off - hp.dpp.host_off;
+    }
+  }
   hp.ok = true;
   return true;
 }
@@ -671,6 +697,11 @@ harp_status_t apply_dir(const harp_plan_t *plan, Direction dir, const void *X, i
   const int np = hp.prog.npass;
   if (hp.n_chunk == np)   // everything on chip, one launch
     return run_chunk_passes(plan, hp, 0, np, X, ldx, dt_in, Y, ldy, dt_out, n, stream);
+  // transposed, one small dense stage above twelve radix-2 stages, bf16 rows: one launch, no
+  // intermediate
+  if (dpp_top_supported(plan, hp.dpp, X, ldx, dt_in, Y, ldy, dt_out))
+    return launch_dpp_top_kernel(plan, hp.dpp, X, ldx, Y, ldy, n,
+                                 choose_pipe_rows(plan, n, plan->d / hp.chunk, hp.chunk), stream);
   const int64_t d = plan->d;
   const int64_t slab_cap = slab_rows_cap(d);
   const int64_t slab = slab_cap > n ? n : slab_cap;
@@ -1189,6 +1220,10 @@ harp_status_t harp_apply_noalloc(const harp_plan_t *plan, const void *X, int64_t
   const HostProgram &hp = *hpp;
   if (hp.n_chunk == hp.prog.npass)   // one launch, no intermediate at all
     return run_chunk_passes(plan, hp, 0, hp.prog.npass, X, ldx, dt, Y, ldy, dt, n, (hipStream_t)stream);
+  if (dpp_top_supported(plan, hp.dpp, X, ldx, dt, Y, ldy, dt))   // one launch, no intermediate
+    return launch_dpp_top_kernel(plan, hp.dpp, X, ldx, Y, ldy, n,
+                                 choose_pipe_rows(plan, n, plan->d / hp.chunk, hp.chunk),
+                                 (hipStream_t)stream);
   // the whole batch has to fit the library's own array: no slab loop, a clear refusal instead
   if ((size_t)n > HARP_NOALLOC_SCRATCH_BYTES / ((size_t)plan->d * 4)) return HARP_ERR_UNSUPPORTED;
   int dev = -1;

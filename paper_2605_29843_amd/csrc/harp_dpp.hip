@@ -420,6 +420,113 @@ __global__ __launch_bounds__(2 * kTG) void harp_dpp_kernel(const TI *__restrict_
     group_B<TO, TRN, LD>(imgB + kch * strideB, t, buf, Y + row0 * ldy + (int64_t)kch * kD, ldy, nr);
 }
 
+// ------------------------------------------------------------------------------------------
+// Transposed split programs whose one streamed stage is a dense stage of radix B = 3 or 5 on the
+// digit above the chunk (12288 = 4096 * 3, 20480 = 4096 * 5): that stage runs first, so it is
+// executed on the way in instead of taking its own trip through a float32 intermediate in
+// device memory.  For the workgroup's chunk k the first group reads its 16 coordinates from ALL
+// B chunks of the row and forms z[i] = sum_j x[j * 4096 + i] * K_i[j][k] with the B factors of
+// each coordinate in registers (the block of Alg. 1's stage belongs to the coordinate inside
+// the chunk), then goes on as group A above.  The row is read B times, but the B workgroups of
+// one row tile are numbered so that they run on one XCD next to each other and share that
+// XCD's L2 (measured: 1.4 times the input fetched from device memory at B = 7), and nothing but
+// bf16 rows ever crosses device memory.  Radix 7 (14336, 28672) was built and measured too
+// (its 112 + 64 factors need the shear factors in LDS): 131 us against 132 us for the two
+// launches at 2048 x 28672 -- in this layout the four lanes of a quad read addresses 512 bytes
+// apart, so a wave's 16-byte loads cost four tag look-ups per quad instead of one, and 2 * B of
+// them per row saturate the compute unit's load path; radix 3 gains 30 % (52.9 -> 36.8 us at
+// 2048 x 12288), radix 5 14 %.
+//
+// A whole row of requests is in flight per thread (ring of B segments): slot (j, h) is refilled
+// with the same piece of the next row as soon as it has been consumed.
+template <int B>
+__device__ __forceinline__ void group_TA(const float *__restrict__ imgT, const float *__restrict__ imgA,
+                                          int t, float *buf, const uint16_t *__restrict__ Xt,
+                                          int64_t ldx, int nr) {
+  const unsigned s = seg_of(true, (unsigned)t >> 6, (unsigned)t & 63u);
+  const unsigned voff = 32u * s;   // byte offset of the thread's segment inside a chunk
+  const int last = nr - 1;
+  // half h of chunk j of row r; rows past the end of the tile repeat its last row.  The address
+  // is a wave-uniform base (scalar registers) plus the one per-lane offset above.
+  auto half_ld = [&](int r, int h, int j) -> uint4 {
+    const char *base = reinterpret_cast<const char *>(Xt + (int64_t)(r < last ? r : last) * ldx + j * kD) + 16 * h;
+    return *reinterpret_cast<const uint4 *>(base + voff);
+  };
+  // ring of the B chunks of one row (both halves): slot (j, h) is refilled with the same piece
+  // of the next row as soon as it has been consumed, so a whole row of requests is in flight
+  uint4 raw[B][2];
+#pragma unroll
+  for (int j = 0; j < B; ++j) {
+    raw[j][0] = half_ld(0, 0, j);
+    raw[j][1] = half_ld(0, 1, j);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  float T[B][16];
+  load_params<B>(imgT, t, T);
+  float f[4][16];
+  load_params<4>(imgA, t, f);
+  const int npairs = (nr + 1) >> 1;
+  auto one_row = [&](int r, float *dst) {
+    float z[16];
+#pragma unroll
+    for (int j = 0; j < B; ++j)
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const uint32_t w[4] = {raw[j][h].x, raw[j][h].y, raw[j][h].z, raw[j][h].w};
+        raw[j][h] = half_ld(r + 1, h, j);
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+          const float x0 = __uint_as_float(w[m] << 16), x1 = __uint_as_float(w[m] & 0xffff0000u);
+          const int i = 8 * h + 2 * m;
+          z[i] = (j == 0) ? x0 * T[0][i] : fmaf(x0, T[j][i], z[i]);
+          z[i + 1] = (j == 0) ? x1 * T[0][i + 1] : fmaf(x1, T[j][i + 1], z[i + 1]);
+        }
+        // one chunk at a time: without this the scheduler unpacks several chunks ahead and
+        // the B = 7 instance no longer fits 256 registers
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    stages_A<true>(z, f);
+    lds_put(dst, s, z);
+  };
+  for (int k = 0; k <= npairs; ++k) {
+    if (k < npairs) {
+      float *b = buf + (k & 1) * (2 * kRowBuf);
+      one_row(2 * k, b);
+      one_row(2 * k + 1, b + kRowBuf);
+    }
+    __syncthreads();
+  }
+}
+
+// Workgroup b -> XCD b mod 8; the B workgroups of one row tile sit on one XCD, consecutive in
+// its dispatch order: i = b / 8, chunk k = i mod B, tile = (i / B) * 8 + (b mod 8).  The grid
+// is padded to a multiple of 8 * B workgroups; those past the last tile leave at once.
+// imgT: [B chunks][B][4 pieces][256 threads][4] factors; imgA / imgB as in harp_dpp_kernel.
+template <int B>
+__global__ __launch_bounds__(2 * kTG) void harp_dpp_top_kernel(const uint16_t *__restrict__ X,
+                                                               int64_t ldx, uint16_t *__restrict__ Y,
+                                                               int64_t ldy, int64_t n, int R,
+                                                               const float *__restrict__ imgT,
+                                                               const float *__restrict__ imgA,
+                                                               const float *__restrict__ imgB,
+                                                               int64_t strideA, int64_t strideB) {
+  __shared__ float buf[4 * kRowBuf];
+  const int g = __builtin_amdgcn_readfirstlane((int)threadIdx.x / kTG);   // wave-uniform
+  const int t = (int)threadIdx.x % kTG;
+  const unsigned xcd = blockIdx.x & 7u, i = blockIdx.x >> 3;
+  const int kch = (int)(i % (unsigned)B);
+  const int64_t tile = (int64_t)(i / (unsigned)B) * 8 + xcd;
+  const int64_t row0 = tile * R;
+  if (row0 >= n) return;
+  const int nr = (int)((n - row0 < R) ? (n - row0) : R);
+  if (g == 0)
+    group_TA<B>(imgT + (int64_t)kch * (B * 16 * kTG), imgA + kch * strideA, t, buf, X + row0 * ldx,
+                ldx, nr);
+  else
+    group_B<uint16_t, true, true>(imgB + kch * strideB, t, buf,
+                                  Y + row0 * ldy + (int64_t)kch * kD, ldy, nr);
+}
+
 template <typename TI, typename TO>
 harp_status_t launch_dpp_io(const DppImage &di, const void *X, int64_t ldx, void *Y, int64_t ldy,
                             int64_t n, int R, int nchunk, hipStream_t stream) {
@@ -471,11 +578,40 @@ harp_status_t launch_dpp_kernel(const harp_plan *plan, const DppImage &di, const
   const int nchunk = (int)(plan->d / kD);
   if (dt_in == HARP_BF16 && dt_out == HARP_BF16)
     return launch_dpp_io<uint16_t, uint16_t>(di, X, ldx, Y, ldy, n, R, nchunk, stream);
-  if (dt_in == HARP_BF16 && dt_out == HARP_F32)
-    return launch_dpp_io<uint16_t, float>(di, X, ldx, Y, ldy, n, R, nchunk, stream);
-  if (dt_in == HARP_F32 && dt_out == HARP_BF16)
-    return launch_dpp_io<float, uint16_t>(di, X, ldx, Y, ldy, n, R, nchunk, stream);
-  return launch_dpp_io<float, float>(di, X, ldx, Y, ldy, n, R, nchunk, stream);
+  return HARP_ERR_UNSUPPORTED;   // see dpp_supported
+}
+
+bool dpp_top_supported(const harp_plan *plan, const DppImage &di, const void *X, int64_t ldx,
+                       harp_dtype_t dt_in, const void *Y, int64_t ldy, harp_dtype_t dt_out) {
+  if (plan->algo == HARP_ALGO_GENERIC || !di.img || di.topB == 0 || !di.trn || !di.ld) return false;
+  if (dt_in != HARP_BF16 || dt_out != HARP_BF16) return false;
+  if ((ldx % 8) || (ldy % 8) || ((uintptr_t)X % 16) || ((uintptr_t)Y % 16)) return false;
+  // the groups read every chunk of a row before the last one of it is written, but a workgroup
+  // of another chunk may already have stored its part of the same row: not in place
+  if (X == Y) return false;
+  return true;
+}
+
+harp_status_t launch_dpp_top_kernel(const harp_plan *plan, const DppImage &di, const void *X,
+                                    int64_t ldx, void *Y, int64_t ldy, int64_t n, int R,
+                                    hipStream_t stream) {
+  const int B = di.topB;
+  if (plan->d != (int64_t)B * kD) return HARP_ERR_UNSUPPORTED;
+  const int64_t tiles = (n + R - 1) / R;
+  const int64_t wgs = ((tiles + 7) / 8) * 8 * B;
+  if (wgs > 0x7fffffff) return HARP_ERR_UNSUPPORTED;
+  const dim3 grid((unsigned)wgs), block(2 * kTG);
+  const float *a = di.img, *b = di.img + di.offB, *tt = di.img + di.offT;
+#define HARP_DPP_TOP(B_)                                                                          \
+  hipLaunchKernelGGL((harp_dpp_top_kernel<B_>), grid, block, 0, stream, (const uint16_t *)X, ldx, \
+                     (uint16_t *)Y, ldy, n, R, tt, a, b, di.strideA, di.strideB)
+  switch (B) {
+    case 3: HARP_DPP_TOP(3); break;
+    case 5: HARP_DPP_TOP(5); break;
+    default: return HARP_ERR_UNSUPPORTED;
+  }
+#undef HARP_DPP_TOP
+  return hipGetLastError() == hipSuccess ? HARP_OK : HARP_ERR_DEVICE;
 }
 
 }  // namespace harp

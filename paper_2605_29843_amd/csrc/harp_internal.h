@@ -81,6 +81,11 @@ struct DppImage {
   int64_t offB = 0;             // group B's part starts here (floats)
   int64_t strideA = 0, strideB = 0;   // floats per chunk
   bool trn = false, ld = false;
+  // transposed split program whose streamed stage (dense, radix topB = 3 or 5, on the digit
+  // above the chunk) is executed on the way in (harp_dpp_top_kernel): its factors per output
+  // chunk kch, input chunk j, piece k, thread t at offT + (((kch * topB + j) * 4 + k) * 256 + t) * 4
+  int32_t topB = 0;
+  int64_t offT = 0;
 };
 
 struct HostProgram {
@@ -223,6 +228,11 @@ harp_status_t launch_dpp_kernel(const harp_plan *plan, const DppImage &di, const
                                 int64_t ldx, harp_dtype_t dt_in, void *Y, int64_t ldy,
                                 harp_dtype_t dt_out, int64_t n, int rows_per_tile,
                                 hipStream_t stream);
+bool dpp_top_supported(const harp_plan *plan, const DppImage &di, const void *X, int64_t ldx,
+                       harp_dtype_t dt_in, const void *Y, int64_t ldy, harp_dtype_t dt_out);
+harp_status_t launch_dpp_top_kernel(const harp_plan *plan, const DppImage &di, const void *X,
+                                    int64_t ldx, void *Y, int64_t ldy, int64_t n, int rows_per_tile,
+                                    hipStream_t stream);
 // wave-local radix-2 kernel for chunks of 256 / 512 / 1024 coordinates (harp_pipe.hip)
 bool wave_supported(const harp_plan *plan, const Program &prog, int p0, int np, int chunk,
                     const void *X, int64_t ldx, const void *Y, int64_t ldy);

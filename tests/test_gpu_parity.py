@@ -483,6 +483,36 @@ def test_split_is_refused_when_there_is_nothing_to_split(harp):
     plan.destroy()
 
 
+@pytest.mark.parametrize("d,b,n,rows", [(12288, 3, 1, None), (12288, 3, 37, None), (20480, 5, 2, None),
+                                        (20480, 5, 75, 6), (28672, 7, 5, None), (28672, 7, 130, None),
+                                        (28672, 7, 33, 4), (12288, 3, 260, 2)])
+def test_transposed_top_stage_fused_into_the_chunk_kernel(harp, d, b, n, rows):
+    """Twelve radix-2 stages below one dense stage of radix 3 or 5, bf16, apply_transpose: one
+    launch, the top stage executed while the rows are read (no float32 intermediate); ragged
+    tiles, single rows, the two-launch fallbacks (in place, float32) and radix 7 (always two
+    launches) alongside."""
+    import torch
+    radices = [2] * 12 + [b]
+    X = gi.activations(n, d, config=3)
+    run_case(harp, d, radices, n, "bf16", seed=d + n, rows=rows, act=X)
+    if n == 37 or n == 5:
+        rng = np.random.default_rng(d + n)
+        blocks, signs = gi.make_blocks(d, radices, "orth", rng), gi.make_signs(d, rng)
+        plan = harp.Plan(d, radices, blocks, signs)
+        ref = ho.apply_transpose_staged(X, d, radices, blocks, signs)
+        Xd = to_device(X, "bf16")
+        harp.harp_apply_transpose(plan, Xd, Xd)                       # in place: two launches
+        torch.cuda.synchronize()
+        assert_parity(to_host64(Xd), ref, "bf16", "transpose in place")
+        Xf = to_device(X, "f32")
+        Zf = harp.harp_apply_transpose(plan, Xf)                      # float32: two launches
+        torch.cuda.synchronize()
+        assert_parity(to_host64(Zf), ref, "f32", "transpose float32")
+        # generic (non-orthogonal) blocks through the fused launch
+        plan.destroy()
+        run_case(harp, d, radices, n, "bf16", kind="generic", seed=d + n + 1)
+
+
 GENERIC_CASES = [
     # (d, radices, n, dtype): non-orthogonal blocks I + (0.3 / sqrt(b)) N(0,1) through every kernel family
     (4096, [2] * 12, 37, "bf16"), (4096, [2] * 12, 9, "f32"), (2048, [2] * 11, 21, "f32"),
