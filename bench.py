@@ -30,7 +30,8 @@ KERNEL_SYMBOL = {"dpp_radix2": "harp_dpp_kernel",
                  "tile_generic": "harp_tile_kernel", "split_pipe_stream": "harp_pipe_kernel",
                  "split_chunk_stream": "harp_tile_kernel", "wave_radix2": "harp_wave_kernel",
                  "split_wave_stream": "harp_wave_kernel", "radix_tile": "harp_radix_kernel",
-                 "split_radix_stream": "harp_radix_kernel"}
+                 "split_radix_stream": "harp_radix_kernel", "radix_tile_int8": "harp_radix_kernel",
+                 "split_radix_stream_int8": "harp_radix_kernel"}
 
 
 # kernels one call of harp_apply launches, by the path name harp_plan_kernel_name reports
@@ -109,6 +110,9 @@ def main():
                          "layer widths of the Llama-2 / Llama-3 families under the radix-2 and "
                          "the greedy radix-8 schedules, and rotate_weight over their layer "
                          "shapes (stderr)")
+    ap.add_argument("--int8", action="store_true",
+                    help="only the int8-parameter lines of --shapes: blocks rebuilt at plan creation "
+                         "against blocks rebuilt inside the kernel (stderr)")
     ap.add_argument("--settle-ms", type=float, default=100.0,
                     help="untimed set-up before the warm-up steps: the same step run for this many "
                          "milliseconds so that the shader clock has settled whatever --warmup is "
@@ -490,6 +494,45 @@ def main():
                       f"parameters {pk.param_bytes() / 1e6:6.2f} MB  [{pk.kernel_name(2048)}]",
                       file=sys.stderr, flush=True)
                 pk.destroy()
+            del Xs, Ys
+    if args.shapes or args.int8:
+        # Int8-stored parameters (appendix "Int8 storage of HARP parameters"): the same codes as a
+        # plan whose blocks are rebuilt once on the host, and as a plan whose chain kernel
+        # rebuilds them from the int8 image in every launch; bf16, n = 2048.
+        rngq = np.random.default_rng(2)
+
+        def timed3(fn, reps=100):
+            warm_clocks(fn, seconds=0.03)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(reps):
+                fn()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) * 1e3 / reps
+
+        for dd, rr in ((4096, [8] * 4), (512, [8] * 3), (1024, [4] * 5), (8192, [8] * 4 + [2])):
+            th = [(0.5 * rngq.standard_normal((dd // b, b * (b - 1) // 2))).astype(np.float32) for b in rr]
+            cq, sq = harp.harp_theta_quantize_int8(dd, rr, th)
+            sg = gi.make_signs(dd, rngq)
+            Xs = [torch.randn(2048, dd, device="cuda").to(torch.bfloat16) for _ in range(8)]
+            Ys = [torch.empty_like(x) for x in Xs]
+            cnt = [0]
+            for nm, fl in (("blocks rebuilt at plan creation", 0),
+                           ("blocks rebuilt in the kernel", harp.HARP_THETA_IN_KERNEL)):
+                pq = harp.Plan.from_theta_int8(dd, rr, cq, sq, None, sg, flags=fl)
+
+                def fwd():
+                    harp.harp_apply(pq, Xs[cnt[0] % 8], Ys[cnt[0] % 8], stream)
+                    cnt[0] += 1
+
+                def trn():
+                    harp.harp_apply_transpose(pq, Xs[cnt[0] % 8], Ys[cnt[0] % 8], stream)
+                    cnt[0] += 1
+                tf, tt = timed3(fwd), timed3(trn)
+                print(f"[shapes] int8 theta d={dd:6d} {str(rr):22s} {nm:32s} apply {tf:7.1f} us  "
+                      f"transpose {tt:7.1f} us  [{pq.kernel_name(2048)}]", file=sys.stderr, flush=True)
+                pq.destroy()
             del Xs, Ys
     if args.decode:
         for dd, rr in ((4096, [2] * 12), (12288, [2] * 12 + [3]), (14336, [2] * 11 + [7])):

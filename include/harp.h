@@ -57,7 +57,10 @@ typedef enum {
 /* flags for harp_plan_create */
 enum {
   HARP_VALIDATE_ORTHO = 1u,  /* reject blocks with max |K^T K - I| > 1e-5 (checked in float64) */
-  HARP_BLOCKS_ON_DEVICE = 2u /* blocks[t] and signs are device pointers (copied back to build) */
+  HARP_BLOCKS_ON_DEVICE = 2u, /* blocks[t] and signs are device pointers (copied back to build) */
+  /* harp_plan_create_from_theta_int8 only: also keep the int8 codes on the device and rebuild
+   * the blocks inside the kernel for the stages that have such a kernel (see there) */
+  HARP_THETA_IN_KERNEL = 4u
 };
 
 /* kernel selection, for tests and tuning (harp_plan_set_algo) */
@@ -246,9 +249,23 @@ harp_status_t harp_grad_blocks(const harp_plan_t *plan, const void *X, int64_t l
  *   codes[t]   D_t * p_t int8 values in [-127, 127];   scales[t]   D_t floats (>= 0).
  * harp_theta_dequantize_int8 returns HARP_ERR_INVALID_ARG for a code of -128 or a negative or
  * non-finite scale, harp_theta_quantize_int8 for a non-finite parameter.
- * harp_plan_create_from_theta_int8 = dequantize, then harp_plan_create_from_theta: the
- * orthogonal blocks are rebuilt once, when the plan is created (the kernels keep a block's
- * values on chip for a whole launch, so rebuilding them per launch would save no traffic).
+ * harp_plan_create_from_theta_int8 = dequantize, then harp_plan_create_from_theta: by default
+ * the orthogonal blocks are rebuilt once, when the plan is created (most kernels keep a
+ * block's values on chip for a whole launch, so rebuilding them per launch would save no
+ * traffic).
+ * With HARP_THETA_IN_KERNEL the plan also keeps the codes, scales and sign bits on the device
+ * (b_t (b_t-1)/2 + 5 bytes per block instead of 4 b_t^2), and harp_apply / harp_apply_transpose
+ * rebuild the blocks at run time (the run-time reconstruction of the same appendix) wherever a
+ * kernel for it exists: chains of equal radix 4 or 8 with the
+ * Hadamard or the identity mixer, on rows or row chunks of 4^k / 8^k <= 4096 coordinates (the
+ * paper's default radix-8 schedules).  Each thread dequantizes its block's codes (s q in
+ * float32), inverts I + A by Gauss-Jordan elimination in float32 registers (no pivoting is
+ * needed: I + A is positive definite for skew-symmetric A), forms Q = 2 (I + A)^{-1} - I,
+ * applies the mixer and the signs.  The rebuilt block differs from the float64 one by about
+ * 5e-7 for |a| <= 1 and 2e-5 for |a| ~ 10, so the float32 tolerance of the other paths holds
+ * for moderate parameters only.  Other stages of such a plan, harp_rotate_weight and
+ * harp_grad_blocks use the blocks built at plan creation.  harp_plan_theta_in_kernel reports
+ * whether a plan carries the run-time image (1) or not (0; -1 for NULL).
  */
 harp_status_t harp_theta_quantize_int8(int64_t d, int32_t m, const int32_t *radices,
                                        const float *const *theta, int8_t *const *codes_out,
@@ -262,6 +279,7 @@ harp_status_t harp_plan_create_from_theta_int8(harp_plan_t **out, int64_t d, int
                                                const int32_t *mixer_kinds,
                                                const float *const *mixers, const int8_t *signs,
                                                uint32_t flags);
+int32_t harp_plan_theta_in_kernel(const harp_plan_t *plan);
 
 /*
  * Kronecker fallback (Sec. 3, "Mixed-Radix dimensions and Kronecker fallback", the equation

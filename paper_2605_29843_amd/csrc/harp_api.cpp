@@ -912,6 +912,78 @@ const HostProgram *select_program(const harp_plan *plan, Direction dir, int64_t 
 
 }  // namespace harp
 
+// Int8 images for the run-time reconstruction (HARP_THETA_IN_KERNEL).  A stage qualifies when
+// its radix is 4 or 8 and its mixer the Hadamard matrix or the identity; its image is attached
+// to every PASS_SMALL pass of that stage in every program, and the chain kernel of harp_radix.hip
+// takes the reconstructing variant when all passes of its chunk carry one.
+harp_status_t harp::plan_attach_theta_int8(harp_plan *plan, const int8_t *const *codes,
+                                           const float *const *scales,
+                                           const int32_t *mixer_kinds, const int8_t *signs) {
+  if (!plan || !codes || !scales) return HARP_ERR_INVALID_ARG;
+  if (plan->tied_K > 0) return HARP_OK;
+  const int m = plan->m;
+  const int64_t d = plan->d;
+  bool any = false;
+  for (int t = 0; t < m; ++t) {
+    const int b = plan->radices[t];
+    const int kind = mixer_kinds ? mixer_kinds[t] : HARP_MIXER_HADAMARD;
+    if ((b != 4 && b != 8) || (kind != HARP_MIXER_HADAMARD && kind != HARP_MIXER_IDENTITY)) continue;
+    const int64_t nq = d / b;
+    const int npar = b * (b - 1) / 2;
+    const int rec = (b == 8) ? 32 : 8;           // bytes per block
+    const int pieces = (b == 8) ? 2 : 1, psz = rec / pieces;
+    std::vector<uint8_t> img((size_t)nq * rec + (size_t)nq * 4, 0);
+    const bool with_signs = signs && plan->strides[t] == 1;   // stage 0
+    for (int64_t c = 0; c < nq; ++c) {
+      uint8_t r[32] = {0};
+      for (int i = 0; i < npar; ++i) r[i] = (uint8_t)codes[t][(size_t)c * npar + i];
+      if (with_signs)
+        for (int j = 0; j < b; ++j)
+          if (signs[c * b + j] < 0) r[npar] |= (uint8_t)(1u << j);
+      for (int k = 0; k < pieces; ++k)
+        memcpy(img.data() + ((size_t)k * nq + c) * psz, r + k * psz, psz);
+      memcpy(img.data() + (size_t)nq * rec + (size_t)c * 4, &scales[t][c], 4);
+    }
+    void *dimg = nullptr;
+    if (hipMalloc(&dimg, img.size()) != hipSuccess) return HARP_ERR_OOM;
+    plan->dev_allocs.push_back(dimg);
+    if (hipMemcpy(dimg, img.data(), img.size(), hipMemcpyHostToDevice) != hipSuccess)
+      return HARP_ERR_DEVICE;
+    const int32_t fl = (kind == HARP_MIXER_HADAMARD ? 1 : 0) | (with_signs ? 2 : 0);
+    for (int algo = HARP_ALGO_GENERIC; algo <= HARP_ALGO_SPLIT; ++algo)
+      for (int dir = 0; dir < 2; ++dir) {
+        HostProgram &hp = plan->prog[algo][dir];
+        if (!hp.ok) continue;
+        // A radix-2 pass in the two-shear or lifting form leaves scales or signs pending on its
+        // coordinates, which the plan builder folds into the rows of the next dense block: a
+        // block behind such a pass is not the one the codes describe.
+        bool clean = true;
+        for (int p = 0; p < hp.prog.npass; ++p) {
+          PassDesc &pd = hp.prog.pass[p];
+          if (pd.kind == PASS_POW2_LIFT || pd.kind == PASS_POW2_LIFT_LD ||
+              pd.kind == PASS_POW2_SCALED || pd.kind == PASS_POW2_SCALED_LD)
+            clean = false;
+          if (!clean) continue;
+          if (pd.kind != PASS_SMALL || pd.b != b || pd.S != plan->strides[t] || pd.tied) continue;
+          pd.q8 = dimg;
+          pd.q8_flags = fl;
+          any = true;
+        }
+      }
+  }
+  if (!any) return HARP_OK;
+  for (int algo = HARP_ALGO_GENERIC; algo <= HARP_ALGO_SPLIT; ++algo)
+    for (int dir = 0; dir < 2; ++dir) {
+      HostProgram &hp = plan->prog[algo][dir];
+      if (!hp.ok || !hp.dev) continue;
+      if (hipMemcpy(const_cast<Program *>(hp.dev), &hp.prog, sizeof(Program),
+                    hipMemcpyHostToDevice) != hipSuccess)
+        return HARP_ERR_DEVICE;
+    }
+  plan->theta_in_kernel = true;
+  return HARP_OK;
+}
+
 harp_status_t harp::plan_create_impl(harp_plan **out, int64_t d, int32_t m, const int32_t *radices,
                                      const float *const *blocks, const int8_t *signs,
                                      uint32_t flags, int32_t tied_K) {
@@ -1355,6 +1427,9 @@ harp_status_t harp_greedy_schedule(int64_t d, int32_t b_base, int32_t b_max, int
 int64_t harp_plan_dim(const harp_plan_t *plan) { return plan ? plan->d : -1; }
 int32_t harp_plan_tied_slices(const harp_plan_t *plan) { return plan ? plan->tied_K : -1; }
 int32_t harp_plan_num_stages(const harp_plan_t *plan) { return plan ? plan->m : -1; }
+int32_t harp_plan_theta_in_kernel(const harp_plan_t *plan) {
+  return plan ? (plan->theta_in_kernel ? 1 : 0) : -1;
+}
 
 int64_t harp_plan_param_count(const harp_plan_t *plan) {
   if (!plan) return -1;
@@ -1401,7 +1476,8 @@ const char *harp_plan_kernel_name(const harp_plan_t *plan, int64_t n, harp_dtype
     return "wave_radix2";
   if (hp && hp->n_chunk == hp->prog.npass &&
       radix_supported(plan, hp->prog, 0, hp->prog.npass, hp->chunk, nullptr, 8, nullptr, 8))
-    return "radix_tile";
+    return radix_rebuilds_in_kernel(plan, hp->prog, 0, hp->prog.npass, hp->chunk) ? "radix_tile_int8"
+                                                                                  : "radix_tile";
   if (hp && hp->n_chunk != hp->prog.npass) {
     const int p0 = hp->chunk_first ? 0 : hp->prog.npass - hp->n_chunk;
     if (pipe_supported(plan, hp->prog, p0, hp->n_chunk, hp->chunk, nullptr, 8, nullptr, 8))
@@ -1409,7 +1485,9 @@ const char *harp_plan_kernel_name(const harp_plan_t *plan, int64_t n, harp_dtype
     if (wave_supported(plan, hp->prog, p0, hp->n_chunk, hp->chunk, nullptr, 8, nullptr, 8))
       return "split_wave_stream";
     if (radix_supported(plan, hp->prog, p0, hp->n_chunk, hp->chunk, nullptr, 8, nullptr, 8))
-      return "split_radix_stream";
+      return radix_rebuilds_in_kernel(plan, hp->prog, p0, hp->n_chunk, hp->chunk)
+                 ? "split_radix_stream_int8"
+                 : "split_radix_stream";
   }
   return nm;
 }

@@ -55,6 +55,15 @@ struct PassDesc {
   // followed by the same tiles in float32; SMALL, radix 4 / 8: a
   // second copy of params, four values per 16-byte load ([V/4][nq][4] floats); else null
   const void *aux;
+  // SMALL, radix 4 / 8, plans created with HARP_THETA_IN_KERNEL: the stage's int8 image (device)
+  // or null.  Radix 8: 16-byte piece k < 2 of block c at ((k * nq) + c) * 16 bytes -- the 28 codes
+  // of the strict upper triangle row by row, then one byte of sign bits (bit r set: coordinate r
+  // of the block carries a -1 sign; stage 0 only), three bytes of padding -- followed by nq
+  // float32 scales.  Radix 4: one 8-byte piece per block (6 codes, sign bits, padding), then the
+  // scales.  q8_flags bit 0: Hadamard mixer (else identity), bit 1: apply the sign bits.
+  const void *q8;
+  int32_t q8_flags;
+  int32_t q8_pad;
 };
 
 constexpr int kMaxPasses = HARP_MAX_STAGES;
@@ -184,6 +193,7 @@ struct harp_plan {
   std::vector<harp::ColStage> col[2];
   std::vector<harp::ColPassHost> colpass[2];
   const int8_t *dev_signs = nullptr;   // device copy of the signs (null: all +1)
+  bool theta_in_kernel = false;        // some pass carries an int8 image (HARP_THETA_IN_KERNEL)
 };
 
 namespace harp {
@@ -244,9 +254,16 @@ harp_status_t launch_wave_kernel(const harp_plan *plan, const HostProgram &hp, i
 harp_status_t plan_create_impl(harp_plan **out, int64_t d, int32_t m, const int32_t *radices,
                                const float *const *blocks, const int8_t *signs, uint32_t flags,
                                int32_t tied_K);
+// Attach the int8 images of the stages that have a run-time reconstruction kernel (equal-radix
+// chains of radix 4 / 8, Hadamard or identity mixer) to a plan built from the same codes
+// (harp_api.cpp); returns HARP_OK also when no stage qualifies.
+harp_status_t plan_attach_theta_int8(harp_plan *plan, const int8_t *const *codes,
+                                     const float *const *scales, const int32_t *mixer_kinds,
+                                     const int8_t *signs);
 // tile kernel for chains of equal radix 4 or 8 on chunks of 4^m / 8^m coordinates (harp_radix.hip)
 bool radix_supported(const harp_plan *plan, const Program &prog, int p0, int np, int chunk,
                      const void *X, int64_t ldx, const void *Y, int64_t ldy);
+bool radix_rebuilds_in_kernel(const harp_plan *plan, const Program &prog, int p0, int np, int chunk);
 harp_status_t launch_radix_kernel(const harp_plan *plan, const HostProgram &hp, int p0, int np,
                                   int chunk, const void *X, int64_t ldx, harp_dtype_t dt_in,
                                   void *Y, int64_t ldy, harp_dtype_t dt_out, int64_t n,

@@ -135,6 +135,112 @@ __device__ __forceinline__ void block_mul(const float (&x)[B], const float (&prm
     for (int c = 0; c < B; ++c) y[c] = fmaf(x[r], prm[r * B + c], y[c]);
 }
 
+// ---- run-time reconstruction of a block from its int8 codes --------------------------------
+// (appendix "Int8 storage of HARP parameters"; block definition of Sec. 3: B = Q(theta) G,
+// Q = (I + A)^{-1} (I - A) for the skew-symmetric A whose strict upper triangle, row by row, is
+// a = s q.)  Q = 2 (I + A)^{-1} - I; the inverse by in-place Gauss-Jordan elimination without
+// pivoting: every leading principal minor of I + A is positive because its symmetric part is I.
+// With the Hadamard mixer G = H / sqrt(B): row i of Q G = (2 / sqrt(B)) WHT(row i of the
+// inverse) - H[i] / sqrt(B).
+template <int B>
+struct Q8Raw {
+  static constexpr int NW = (B == 8) ? 8 : 2;   // dwords of codes, sign bits and padding
+  uint32_t w[NW];
+  float s;
+};
+
+template <int B>
+__device__ __forceinline__ void q8_request(const PassDesc &pd, unsigned qg, Q8Raw<B> &raw) {
+  const unsigned nq = (unsigned)pd.nq;
+  const char *base = reinterpret_cast<const char *>(pd.q8);
+  if (B == 8) {
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+      const uint4 v = *reinterpret_cast<const uint4 *>(base + ((size_t)k * nq + qg) * 16);
+      raw.w[4 * k] = v.x; raw.w[4 * k + 1] = v.y; raw.w[4 * k + 2] = v.z; raw.w[4 * k + 3] = v.w;
+    }
+    raw.s = *reinterpret_cast<const float *>(base + (size_t)nq * 32 + (size_t)qg * 4);
+  } else {
+    const uint2 v = *reinterpret_cast<const uint2 *>(base + (size_t)qg * 8);
+    raw.w[0] = v.x; raw.w[1] = v.y;
+    raw.s = *reinterpret_cast<const float *>(base + (size_t)nq * 8 + (size_t)qg * 4);
+  }
+}
+
+// prm[r * B + c] = entry [r][c] of the block as this direction uses it (TRN: the transpose),
+// with the signs of stage 0 on the rows of the forward block
+template <int B, bool TRN>
+__device__ __forceinline__ void q8_rebuild(const Q8Raw<B> &raw, int flags, float (&prm)[B * B]) {
+  constexpr int NP = B * (B - 1) / 2;
+  float m[B][B];
+  {
+    int k = 0;
+#pragma unroll
+    for (int i = 0; i < B; ++i) {
+      m[i][i] = 1.0f;
+#pragma unroll
+      for (int j = i + 1; j < B; ++j, ++k) {
+        const int code = (int)(int8_t)(raw.w[k >> 2] >> (8 * (k & 3)));
+        const float a = raw.s * (float)code;
+        m[i][j] = a;
+        m[j][i] = -a;
+      }
+    }
+  }
+#pragma unroll
+  for (int c = 0; c < B; ++c) {
+    const float p = 1.0f / m[c][c];
+    m[c][c] = 1.0f;
+#pragma unroll
+    for (int j = 0; j < B; ++j) m[c][j] *= p;
+#pragma unroll
+    for (int r = 0; r < B; ++r) {
+      if (r == c) continue;
+      const float f = m[r][c];
+      m[r][c] = 0.0f;
+#pragma unroll
+      for (int j = 0; j < B; ++j) m[r][j] = fmaf(-f, m[c][j], m[r][j]);
+    }
+  }
+  if (flags & 1) {
+    // Walsh-Hadamard transform of every row (Sylvester order), then the affine map above
+    const float g = (B == 8) ? 0.35355339059327379f : 0.5f;   // 1 / sqrt(B)
+#pragma unroll
+    for (int i = 0; i < B; ++i) {
+#pragma unroll
+      for (int h = 1; h < B; h <<= 1)
+#pragma unroll
+        for (int j = 0; j < B; ++j)
+          if (!(j & h)) {
+            const float u = m[i][j], v = m[i][j | h];
+            m[i][j] = u + v;
+            m[i][j | h] = u - v;
+          }
+#pragma unroll
+      for (int j = 0; j < B; ++j)
+        m[i][j] = fmaf(m[i][j], 2.0f * g, (__builtin_popcount(i & j) & 1) ? g : -g);
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < B; ++i)
+#pragma unroll
+      for (int j = 0; j < B; ++j) m[i][j] = fmaf(m[i][j], 2.0f, i == j ? -1.0f : 0.0f);
+  }
+  if (flags & 2) {
+    const uint32_t bits = (raw.w[NP >> 2] >> (8 * (NP & 3))) & 0xffu;
+#pragma unroll
+    for (int i = 0; i < B; ++i) {
+      const uint32_t flip = ((bits >> i) & 1u) << 31;
+#pragma unroll
+      for (int j = 0; j < B; ++j) m[i][j] = __uint_as_float(__float_as_uint(m[i][j]) ^ flip);
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < B; ++r)
+#pragma unroll
+    for (int c = 0; c < B; ++c) prm[r * B + c] = TRN ? m[c][r] : m[r][c];
+}
+
 // One stage on the rows of the tile.  MODE 0: inputs from the prefetched device-memory words
 // `raw`, outputs to LDS; 1: LDS in place; 2: inputs from LDS, outputs to device memory.
 // CONTIG: the stage's stride is 1 (16-byte accesses); it can only be the first or last stage.
@@ -204,7 +310,8 @@ __device__ __forceinline__ void radix_pass(float *tile, int dpad, int nr, int S,
 // Passes prog.pass[p0 .. p0+np), np >= 2, are single stages of radix B with strides that are
 // powers of B inside the chunk, ascending (TRN false: the first stage has stride 1) or
 // descending (TRN: the last one has).  blockDim.x * BPT = chunk / B blocks per stage and row.
-template <typename TI, typename TO, int B, int BPT, bool TRN>
+// Q8: the blocks are rebuilt from the passes' int8 images instead of being read (BPT == 1).
+template <typename TI, typename TO, int B, int BPT, bool TRN, bool Q8 = false>
 __global__ __launch_bounds__(512) void harp_radix_kernel(const TI *__restrict__ X, int64_t ldx,
                                                          TO *__restrict__ Y, int64_t ldy,
                                                          int64_t n, int R, int nchunk, int chunk,
@@ -254,6 +361,28 @@ __global__ __launch_bounds__(512) void harp_radix_kernel(const TI *__restrict__ 
       for (int m = 0; m < B; ++m) raw[r][u][m] = 0u;
       if (r < nr) In::template load<!TRN>(Xt + (int64_t)r * ldx + base0, S0, raw[r][u]);
     }
+  }
+  if constexpr (Q8) {
+    // codes of the next stage in flight while this stage's block is rebuilt and applied
+    const unsigned qg = (unsigned)kch * nqc + tid;
+    Q8Raw<B> rc, rn;
+    q8_request<B>(prog.pass[p0], qg, rc);
+    q8_request<B>(prog.pass[p0 + 1], qg, rn);
+    q8_rebuild<B, TRN>(rc, prog.pass[p0].q8_flags, cur[0]);
+    radix_pass<TI, TO, B, BPT, 0, !TRN>(tile, dpad, nr, S0, tid, NT, nqc, cur, raw, Yt, ldy);
+    __syncthreads();
+    for (int p = 1; p < np - 1; ++p) {
+      rc = rn;
+      q8_request<B>(prog.pass[p0 + p + 1], qg, rn);
+      q8_rebuild<B, TRN>(rc, prog.pass[p0 + p].q8_flags, cur[0]);
+      radix_pass<TI, TO, B, BPT, 1, false>(tile, dpad, nr, prog.pass[p0 + p].S, tid, NT, nqc, cur,
+                                           raw, Yt, ldy);
+      __syncthreads();
+    }
+    q8_rebuild<B, TRN>(rn, prog.pass[p0 + np - 1].q8_flags, cur[0]);
+    radix_pass<TI, TO, B, BPT, 2, TRN>(tile, dpad, nr, prog.pass[p0 + np - 1].S, tid, NT, nqc, cur,
+                                       raw, Yt, ldy);
+    return;
   }
   load_params(prog.pass[p0], cur);
   load_params(prog.pass[p0 + 1], nxt);     // in flight during the first stage
@@ -440,6 +569,7 @@ harp_status_t launch_mixed_io(const harp_plan *plan, const HostProgram &hp, int 
 struct RadixShape {
   int B, np, nt, bpt;
   bool trn, ok;
+  bool q8 = false;   // every pass carries an int8 image: the reconstructing variant can run
 };
 
 RadixShape radix_decode(const Program &pg, int p0, int np, int chunk) {
@@ -471,10 +601,12 @@ RadixShape radix_decode(const Program &pg, int p0, int np, int chunk) {
   rs.nt = nt;
   rs.bpt = bpt;
   rs.ok = true;
+  rs.q8 = (bpt == 1);
+  for (int p = 0; p < np; ++p) rs.q8 = rs.q8 && ps[p].q8 != nullptr;
   return rs;
 }
 
-template <typename TI, typename TO, int B, int BPT, bool TRN>
+template <typename TI, typename TO, int B, int BPT, bool TRN, bool Q8 = false>
 harp_status_t launch_radix_inst(const harp_plan *plan, const HostProgram &hp, int p0, int np,
                                 int chunk, int nt, const void *X, int64_t ldx, void *Y,
                                 int64_t ldy, int64_t n, hipStream_t stream) {
@@ -488,7 +620,7 @@ harp_status_t launch_radix_inst(const harp_plan *plan, const HostProgram &hp, in
   const int64_t tiles = ((n + R - 1) / R) * nchunk;
   if (tiles > 0x7fffffff) return HARP_ERR_UNSUPPORTED;
   const size_t lds = (size_t)R * dpad * 4;
-  auto kern = harp_radix_kernel<TI, TO, B, BPT, TRN>;
+  auto kern = harp_radix_kernel<TI, TO, B, BPT, TRN, Q8>;
   static thread_local int attr_done_dev = -1;   // per instantiation
   if (attr_done_dev != plan->device) {
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -513,6 +645,16 @@ harp_status_t launch_radix_io(const harp_plan *plan, const HostProgram &hp, int 
                                                       Y, ldy, n, stream)                         \
           : launch_radix_inst<TI, TO, B_, BPT_, false>(plan, hp, p0, rs.np, chunk, rs.nt, X,     \
                                                        ldx, Y, ldy, n, stream))
+#define HARP_RADIX_CASE_Q8(B_)                                                                     \
+  (rs.trn ? launch_radix_inst<TI, TO, B_, 1, true, true>(plan, hp, p0, rs.np, chunk, rs.nt, X, ldx, \
+                                                         Y, ldy, n, stream)                         \
+          : launch_radix_inst<TI, TO, B_, 1, false, true>(plan, hp, p0, rs.np, chunk, rs.nt, X,     \
+                                                          ldx, Y, ldy, n, stream))
+  if (rs.q8 && plan->theta_in_kernel) {
+    if (rs.B == 8) return HARP_RADIX_CASE_Q8(8);
+    return HARP_RADIX_CASE_Q8(4);
+  }
+#undef HARP_RADIX_CASE_Q8
   if (rs.B == 8) return HARP_RADIX_CASE(8, 1);
   if (rs.bpt == 1) return HARP_RADIX_CASE(4, 1);
   return HARP_RADIX_CASE(4, 2);
@@ -528,6 +670,11 @@ bool radix_supported(const harp_plan *plan, const Program &pg, int p0, int np, i
   // 16-byte accesses of the contiguous stage for either element type
   if ((ldx % 8) || (ldy % 8) || ((uintptr_t)X % 16) || ((uintptr_t)Y % 16)) return false;
   return (size_t)(chunk + (chunk >> 6) * 8) * 4 <= (size_t)plan->lds_bytes;
+}
+
+// true when launch_radix_kernel would take the variant that rebuilds the blocks from int8 codes
+bool radix_rebuilds_in_kernel(const harp_plan *plan, const Program &pg, int p0, int np, int chunk) {
+  return plan->theta_in_kernel && radix_decode(pg, p0, np, chunk).q8;
 }
 
 harp_status_t launch_radix_kernel(const harp_plan *plan, const HostProgram &hp, int p0, int np,

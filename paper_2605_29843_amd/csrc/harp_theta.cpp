@@ -245,6 +245,8 @@ harp_status_t harp_plan_create_from_theta_int8(harp_plan_t **out, int64_t d, int
                                                uint32_t flags) {
   if (!out) return HARP_ERR_INVALID_ARG;
   if (flags & HARP_BLOCKS_ON_DEVICE) return HARP_ERR_INVALID_ARG;   // codes are read on the host
+  const bool in_kernel = (flags & HARP_THETA_IN_KERNEL) != 0;
+  flags &= ~(uint32_t)HARP_THETA_IN_KERNEL;
   harp_status_t st = check_schedule(d, m, radices);
   if (st != HARP_OK) return st;
   if (d > (int64_t)1 << 24) return HARP_ERR_UNSUPPORTED;
@@ -259,8 +261,15 @@ harp_status_t harp_plan_create_from_theta_int8(harp_plan_t **out, int64_t d, int
     }
     st = harp_theta_dequantize_int8(d, m, radices, codes, scales, outp.data());
     if (st != HARP_OK) return st;
-    return harp_plan_create_from_theta(out, d, m, radices, inp.data(), mixer_kinds, mixers, signs,
-                                       flags);
+    st = harp_plan_create_from_theta(out, d, m, radices, inp.data(), mixer_kinds, mixers, signs,
+                                     flags);
+    if (st != HARP_OK || !in_kernel) return st;
+    st = harp::plan_attach_theta_int8(*out, codes, scales, mixer_kinds, signs);
+    if (st != HARP_OK) {
+      harp_plan_destroy(*out);
+      *out = nullptr;
+    }
+    return st;
   } catch (const std::bad_alloc &) {
     return HARP_ERR_OOM;
   }

@@ -24,7 +24,7 @@ LIB_PATH = os.path.join(_PKG, "libharp.so")
 HARP_OK, HARP_ERR_INVALID_ARG, HARP_ERR_BAD_SCHEDULE, HARP_ERR_NOT_ORTHOGONAL, \
     HARP_ERR_UNSUPPORTED, HARP_ERR_OOM, HARP_ERR_DEVICE = range(7)
 HARP_F32, HARP_BF16 = 0, 1
-HARP_VALIDATE_ORTHO, HARP_BLOCKS_ON_DEVICE = 1, 2
+HARP_VALIDATE_ORTHO, HARP_BLOCKS_ON_DEVICE, HARP_THETA_IN_KERNEL = 1, 2, 4
 HARP_ALGO_AUTO, HARP_ALGO_GENERIC, HARP_ALGO_FUSED, HARP_ALGO_SPLIT = 0, 1, 2, 3
 HARP_MAX_RADIX, HARP_MAX_STAGES = 64, 64
 HARP_MIXER_IDENTITY, HARP_MIXER_HADAMARD, HARP_MIXER_CUSTOM = 0, 1, 2
@@ -45,6 +45,7 @@ _SIGS = {
     "harp_plan_create_kronecker": (_i32, [C.POINTER(_vp), _i32, _vp, _i64, _i32, C.POINTER(_i32),
                                           C.POINTER(_vp), _vp, _u32]),
     "harp_plan_tied_slices": (_i32, [_vp]),
+    "harp_plan_theta_in_kernel": (_i32, [_vp]),
     "harp_plan_create_from_theta": (_i32, [C.POINTER(_vp), _i64, _i32, C.POINTER(_i32), C.POINTER(_vp),
                                            C.POINTER(_i32), C.POINTER(_vp), _vp, _u32]),
     "harp_theta_quantize_int8": (_i32, [_i64, _i32, C.POINTER(_i32), C.POINTER(_vp), C.POINTER(_vp),
@@ -351,6 +352,9 @@ class Plan:
 
     def tied_slices(self) -> int:
         return int(lib.harp_plan_tied_slices(self._h))
+
+    def theta_in_kernel(self) -> bool:
+        return int(lib.harp_plan_theta_in_kernel(self._h)) == 1
 
     # -- lifetime
     def destroy(self):

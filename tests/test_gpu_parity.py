@@ -795,6 +795,52 @@ def test_plan_from_int8_theta(harp, d, radices):
     plan.destroy()
 
 
+@pytest.mark.parametrize("d,radices,mix_kind,n,with_signs", [
+    (4096, [8] * 4, None, 19, True),            # the default radix-8 schedule, Hadamard mixer
+    (4096, [8] * 4, "identity", 8, False),
+    (512, [8] * 3, None, 33, True),
+    (1024, [4] * 5, None, 21, True),            # radix 4: six codes per block
+    (256, [4] * 4, "identity", 5, True),
+    (8192, [8] * 4 + [2], None, 37, True),      # chunk of 8^4 + one streamed radix-2 stage
+    (5120, [8, 8, 8, 5, 2], "mixed", 9, True),  # no reconstructing kernel for this chunk: host blocks
+])
+def test_int8_theta_rebuilt_inside_the_kernel(harp, d, radices, mix_kind, n, with_signs):
+    """HARP_THETA_IN_KERNEL: the chain kernel reads the int8 codes and rebuilds every block in
+    registers (dequantise, Gauss-Jordan inverse of I + A, mixer, signs); the result is compared
+    with the processor whose blocks the oracle rebuilds from the same codes in float64, and the
+    plan without the flag (blocks rebuilt on the host) must give the same kernel family."""
+    import torch
+    rng = np.random.default_rng(d + 7 * len(radices) + n)
+    thetas = [(0.5 * rng.standard_normal((d // b, b * (b - 1) // 2))).astype(np.float32) for b in radices]
+    thetas[0][3] = 0.0                            # an all-zero block: scale 0, Q = I
+    if mix_kind == "mixed":
+        mix = ["identity" if b & (b - 1) else None for b in radices]
+    else:
+        mix = [mix_kind] * len(radices)
+    signs = gi.make_signs(d, rng) if with_signs else None
+    codes, scales = ho.quantize_theta_int8(d, radices, thetas)
+    plan = harp.Plan.from_theta_int8(d, radices, codes, scales, mix, signs,
+                                     flags=harp.HARP_VALIDATE_ORTHO | harp.HARP_THETA_IN_KERNEL)
+    say(f"int8 theta in kernel d={d} radices={radices} mixers={mix_kind} kernel={plan.kernel_name(n)} "
+        f"in_kernel={plan.theta_in_kernel()}")
+    assert plan.theta_in_kernel()
+    if mix_kind != "mixed":     # the reconstructing variant is the one that runs
+        assert plan.kernel_name(n) in ("radix_tile_int8", "split_radix_stream_int8")
+    else:
+        assert not plan.kernel_name(n).endswith("_int8")
+    X = gi.round_to_bf16(rng.standard_normal((n, d)).astype(np.float32))
+    blocks = ho.blocks_from_theta(d, radices, ho.dequantize_theta_int8(d, radices, codes, scales), mix)
+    Yref = ho.apply_staged(X, d, radices, blocks, signs)
+    Zref = ho.apply_transpose_staged(X, d, radices, blocks, signs)
+    for dtype in ("f32", "bf16"):
+        Y = to_host64(harp.harp_apply(plan, to_device(X, dtype)))
+        Z = to_host64(harp.harp_apply_transpose(plan, to_device(X, dtype)))
+        torch.cuda.synchronize()
+        assert_parity(Y, Yref, dtype, "apply")
+        assert_parity(Z, Zref, dtype, "apply_transpose")
+    plan.destroy()
+
+
 def test_kronecker_fallback_plan(harp):
     """d = 12 * 1024: T_d = (H~_12 / sqrt(12)) (x) T_1024 built by harp_kronecker_blocks."""
     import torch
