@@ -96,9 +96,12 @@ bool stage_orthogonal_2x2(const float *K, int64_t D) {
 
 // scaled == true: radix-2 stages before the last take the two-shear form; returns false when a
 // block has a (near-)zero diagonal or a pending scale leaves the safe range.
+// dense_t >= 0: stage dense_t of a forward program is kept dense although it is not the last
+// (the end of the slices of a plan with tied parameters; the end of the chunk whose output
+// travels as block-scaled halves), so that no scale is pending behind it.
 bool build_effective(const harp_plan *plan, const std::vector<const float *> &blocks,
                      const int8_t *signs, int algo, Direction dir, bool scaled,
-                     std::vector<StageEff> &out) {
+                     std::vector<StageEff> &out, int dense_t = -1) {
   const int m = plan->m;
   const int64_t d = plan->d;
   const double kScaleMax = 1152921504606846976.0;   // 2^60
@@ -122,8 +125,9 @@ bool build_effective(const harp_plan *plan, const std::vector<const float *> &bl
     };
     // Tied parameters, forward: the last stage of the slices is dense as well, so that no
     // pending scale (a function of the coordinate inside the slice) reaches the table, whose
-    // blocks then really are one matrix.
-    const bool slice_end = (plan->tied_K > 0 && dir == DIR_FWD && t == m - 2);
+    // blocks then really are one matrix.  Likewise the last stage of a chunk whose output is
+    // stored as block-scaled halves: those need values of the row's own size.
+    const bool slice_end = (dir == DIR_FWD && t == dense_t);
     const bool pow2_stage = (algo != HARP_ALGO_GENERIC && b == 2 && !last && !slice_end);
     if (pow2_stage && scaled) {
       se.form = FORM_SCALED;
@@ -240,7 +244,7 @@ void pack_mfma_block(const float *K, int b, uint16_t *out, float *out32) {
 // transposed one), all in the two-shear form except that the last may be the program's dense
 // last stage.  eff[i0 .. i0 + 12) are those stages in execution order.  Appends to `image`.
 void build_dpp_image(const harp_plan *plan, const std::vector<StageEff> &eff, int i0, Direction dir,
-                     HostProgram &hp, std::vector<float> &image) {
+                     HostProgram &hp, std::vector<float> &image, int dense_i = -1) {
   constexpr int L = 12, D = 1 << L, TG = D / 16;
   hp.dpp = DppImage();
   const int m = plan->m;
@@ -251,7 +255,8 @@ void build_dpp_image(const harp_plan *plan, const std::vector<StageEff> &eff, in
     const int digit = (dir == DIR_FWD) ? e : L - 1 - e;
     if (se.b != 2 || se.s != ((int64_t)1 << digit)) return;
     if (se.form == FORM_SCALED) continue;
-    if (se.form == FORM_DENSE && e == L - 1 && i0 + e == m - 1) {
+    // (dense_i: the chunk's last stage kept dense in a forward split program, see build_program)
+    if (se.form == FORM_DENSE && e == L - 1 && (i0 + e == m - 1 || i0 + e == dense_i)) {
       ld = true;
       continue;
     }
@@ -314,11 +319,6 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
   const bool tied = plan->tied_K > 0;
   if (tied && algo != HARP_ALGO_SPLIT) return false;
   if (tied) signs = nullptr;
-  std::vector<StageEff> eff;
-  if (!build_effective(plan, blocks, signs, algo, dir, true, eff)) {
-    if (tied) return false;
-    build_effective(plan, blocks, signs, algo, dir, false, eff);
-  }
 
   Program &pg = hp.prog;
   pg.npass = 0;
@@ -365,6 +365,20 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
     // tied: the chunk is exactly one slice, the table is the one streamed stage (matrix cores)
     if (tied && (chunk != plan->tied_n2 || tb != m - 1 || plan->radices[m - 1] < 9)) return false;
   }
+  // Block-scaled half intermediate (bf16 callers): one streamed stage of radix >= 3 (dense in
+  // both directions, so nothing is pending behind it going down), orthogonal blocks, and a
+  // dense stage at the end of the chunk going up.
+  // (only where both kernels of the pair handle the format: chunks of 4096 on the DPP kernel or
+  // of 256 / 512 / 1024 on the wave kernel, and the small-radix streamed kernel)
+  hp.z16 = (algo == HARP_ALGO_SPLIT && !tied && plan->orthogonal && tb == m - 1 &&
+            plan->radices[m - 1] >= 3 && plan->radices[m - 1] <= 8 && d % 32 == 0 &&
+            (chunk == 4096 || chunk == 1024 || chunk == 512 || chunk == 256));
+  const int dense_t = tied ? m - 2 : ((hp.z16 && plan->radices[tb - 1] == 2) ? tb - 1 : -1);
+  std::vector<StageEff> eff;
+  if (!build_effective(plan, blocks, signs, algo, dir, true, eff, dense_t)) {
+    if (tied) return false;
+    build_effective(plan, blocks, signs, algo, dir, false, eff, dense_t);
+  }
   auto local = [&](int i) { return eff[i].t < tb; };
   hp.chunk = (int32_t)chunk;
   hp.n_chunk = 0;
@@ -384,7 +398,7 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
         ++len;
       bool last_dense = false;
       // (tied parameters, forward: the dense stage that ends the slices, see build_effective)
-      const int dense_at = (tied && dir == DIR_FWD) ? m - 2 : m - 1;
+      const int dense_at = (dense_t >= 0 && dir == DIR_FWD) ? dense_t : m - 1;
       if (lift && i + len == dense_at && eff[dense_at].b == 2 && eff[dense_at].form == FORM_DENSE &&
           local(dense_at) == local(i)) {
         ++len;
@@ -563,6 +577,12 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
   hp.dpp = DppImage();
   if (algo == HARP_ALGO_FUSED && chunk == 4096 && tb == 12 && m == 12)
     build_dpp_image(plan, eff, 0, dir, hp, image);
+  // Split programs whose intermediate may travel as block-scaled halves: the chunks of 4096 of a
+  // bf16 caller run on the DPP kernel too (a thread's 16 coordinates are one segment of that
+  // format in both of its layouts).
+  if (algo == HARP_ALGO_SPLIT && hp.z16 && chunk == 4096 && tb == 12 && m == 13 &&
+      !(dir == DIR_TRN && (eff[0].b == 3 || eff[0].b == 5)))   // (those: the image built below)
+    build_dpp_image(plan, eff, dir == DIR_FWD ? 0 : 1, dir, hp, image, dir == DIR_FWD ? dense_t : -1);
   // Transposed split program of twelve radix-2 stages below one dense stage of radix 3 or 5
   // (12288, 20480; radix 7 measured no gain): that stage runs first and is executed by the DPP kernel's first
   // group on the way in (harp_dpp_top_kernel).  Its factors: for output chunk kch, input chunk
@@ -610,6 +630,14 @@ size_t esize(harp_dtype_t dt) { return dt == HARP_BF16 ? 2 : 4; }
 // 32 .. 512 MB on the 14336 / 28672 shapes), a multiple of 256 rows when that many fit.
 int64_t slab_rows_cap(int64_t d) {
   int64_t slab = ((int64_t)128 << 20) / (d * 4);
+  if (slab >= 512) slab = (slab / 256) * 256;
+  if (slab < 1) slab = 1;
+  return slab;
+}
+
+// the same for the block-scaled half form of the intermediate (about half the bytes per row)
+int64_t slab_rows_cap_z16(int64_t d) {
+  int64_t slab = ((int64_t)128 << 20) / (z16_ld(d) * 2);
   if (slab >= 512) slab = (slab / 256) * 256;
   if (slab < 1) slab = 1;
   return slab;
@@ -679,6 +707,32 @@ harp_status_t run_chunk_passes(const harp_plan_t *plan, const HostProgram &hp, i
                             stream);
 }
 
+// The intermediate of a split program as block-scaled halves (2 bytes per coordinate instead of
+// 4) for bf16 callers: one streamed dense stage of radix 3..8 next to the wave or the DPP
+// kernel, for plans whose blocks are orthogonal (intermediate values then have the size of the
+// row's own, and the format's 2^-12 per value is an eighth of the caller's own rounding).
+bool split_uses_z16(const harp_plan_t *plan, const HostProgram &hp, const void *X, int64_t ldx,
+                    harp_dtype_t dt_in, const void *Y, int64_t ldy, harp_dtype_t dt_out) {
+  if (!hp.z16 || dt_in != HARP_BF16 || dt_out != HARP_BF16) return false;
+  const int np = hp.prog.npass;
+  if (np - hp.n_chunk != 1) return false;
+  const int p0 = hp.chunk_first ? 0 : 1, ps = hp.chunk_first ? hp.n_chunk : 0;
+  const int64_t zl = z16_ld(plan->d);
+  const void *cx = hp.chunk_first ? X : nullptr, *cy = hp.chunk_first ? nullptr : Y;
+  const int64_t clx = hp.chunk_first ? ldx : zl, cly = hp.chunk_first ? zl : ldy;
+  const harp_dtype_t zt = (harp_dtype_t)kDtZ16;
+  // chunk kernels that read or write the format: the wave kernel and the DPP kernel
+  if (!wave_supported(plan, hp.prog, p0, hp.n_chunk, hp.chunk, cx, clx, cy, cly) &&
+      !dpp_supported(plan, hp.dpp, hp.chunk, cx, clx, hp.chunk_first ? dt_in : zt, cy, cly,
+                     hp.chunk_first ? zt : dt_out))
+    return false;
+  // streamed stage: the small-radix kernel (the matrix-core kernel was measured with this
+  // format and is not faster with it: it is bound by its LDS transposes, not by bytes)
+  const void *sx = hp.chunk_first ? nullptr : X, *sy = hp.chunk_first ? Y : nullptr;
+  return stream_z16_supported(hp.prog.pass[ps], sx, hp.chunk_first ? zl : ldx, sy,
+                              hp.chunk_first ? ldy : zl);
+}
+
 // Split program on rows [0, n): the chunk-local passes run fused on chip, every other pass is
 // streamed through the float32 intermediate Z, which holds `slab` rows; rows are processed slab
 // by slab so that Z stays small (it is written by one launch and read by the next: cache
@@ -703,10 +757,15 @@ harp_status_t apply_dir(const harp_plan_t *plan, Direction dir, const void *X, i
     return launch_dpp_top_kernel(plan, hp.dpp, X, ldx, Y, ldy, n,
                                  choose_pipe_rows(plan, n, plan->d / hp.chunk, hp.chunk), stream);
   const int64_t d = plan->d;
-  const int64_t slab_cap = slab_rows_cap(d);
+  const bool z16 = split_uses_z16(plan, hp, X, ldx, dt_in, Y, ldy, dt_out);
+  const int64_t slab_cap = z16 ? slab_rows_cap_z16(d) : slab_rows_cap(d);
   const int64_t slab = slab_cap > n ? n : slab_cap;
+  const size_t row_bytes = z16 ? (size_t)z16_ld(d) * 2 : (size_t)d * 4;
+  // one buffer per stream serves both forms: its full size is the larger of the two slabs
+  const size_t cap = std::max((size_t)slab_rows_cap(d) * d * 4,
+                              hp.z16 ? (size_t)slab_rows_cap_z16(d) * z16_ld(d) * 2 : (size_t)0);
   float *Z = nullptr;
-  harp_status_t zst = plan_scratch(plan, stream, (size_t)slab * d * 4, (size_t)slab_cap * d * 4, &Z);
+  harp_status_t zst = plan_scratch(plan, stream, (size_t)slab * row_bytes, cap, &Z);
   if (zst != HARP_OK) return zst;
   return run_split(plan, hp, X, ldx, dt_in, Y, ldy, dt_out, n, Z, slab, stream);
 }
@@ -719,6 +778,10 @@ harp_status_t run_split(const harp_plan_t *plan, const HostProgram &hp, const vo
   const int nstream = np - hp.n_chunk;
   const int nseg = nstream + 1;
   const bool allow_narrow = (dt_in == HARP_BF16 || dt_out == HARP_BF16);
+  // bf16 on both sides, one streamed dense stage: the intermediate as block-scaled halves
+  const bool z16 = split_uses_z16(plan, hp, X, ldx, dt_in, Y, ldy, dt_out);
+  const harp_dtype_t z_dt = z16 ? (harp_dtype_t)kDtZ16 : HARP_F32;
+  const int64_t z_ld = z16 ? z16_ld(d) : d;
   harp_status_t st = HARP_OK;
   for (int64_t r0 = 0; r0 < n && st == HARP_OK; r0 += slab) {
     const int64_t nr = (n - r0 < slab) ? n - r0 : slab;
@@ -728,8 +791,8 @@ harp_status_t run_split(const harp_plan_t *plan, const HostProgram &hp, const vo
     for (int seg = 0; seg < nseg && st == HARP_OK; ++seg) {
       const bool last = (seg == nseg - 1);
       void *dst = last ? (void *)((char *)Y + (size_t)r0 * ldy * esize(dt_out)) : (void *)Z;
-      const int64_t dst_ld = last ? ldy : d;
-      const harp_dtype_t dst_dt = last ? dt_out : HARP_F32;
+      const int64_t dst_ld = last ? ldy : z_ld;
+      const harp_dtype_t dst_dt = last ? dt_out : z_dt;
       const bool is_chunk = hp.chunk_first ? (seg == 0) : last;
       if (is_chunk) {
         const int p0 = hp.chunk_first ? 0 : nstream;
@@ -1062,19 +1125,26 @@ harp_status_t harp::plan_create_impl(harp_plan **out, int64_t d, int32_t m, cons
           st = HARP_ERR_INVALID_ARG;
           break;
         }
-      if (st == HARP_OK && (flags & HARP_VALIDATE_ORTHO)) {
-        for (int64_t c = 0; c < D && st == HARP_OK; ++c) {
+      // orthogonality of every block (always recorded: kernels that rely on intermediate values
+      // having the size of the row's own ask for it; an error only with HARP_VALIDATE_ORTHO)
+      bool ortho = true;
+      if (st == HARP_OK) {
+        for (int64_t c = 0; c < D && ortho; ++c) {
           const float *k = K + c * b * b;
-          for (int i = 0; i < b && st == HARP_OK; ++i)
+          for (int i = 0; i < b && ortho; ++i)
             for (int j = i; j < b; ++j) {
               double acc = 0.0;
               for (int r = 0; r < b; ++r) acc += (double)k[r * b + i] * (double)k[r * b + j];
               if (std::fabs(acc - (i == j ? 1.0 : 0.0)) > 1e-5) {
-                st = HARP_ERR_NOT_ORTHOGONAL;
+                ortho = false;
                 break;
               }
             }
         }
+      }
+      if (!ortho) {
+        plan->orthogonal = false;
+        if (flags & HARP_VALIDATE_ORTHO) st = HARP_ERR_NOT_ORTHOGONAL;
       }
     }
     // ---- device side -------------------------------------------------------------

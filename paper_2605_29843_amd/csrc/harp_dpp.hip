@@ -33,6 +33,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "harp_internal.h"
 
 namespace harp {
@@ -219,6 +221,39 @@ struct Seg16<float> {
   }
 };
 
+// 16 block-scaled halves = one aligned segment of the intermediate of a split program; ep = the
+// segment's exponent byte
+template <>
+struct Seg16<zh16> {
+  static constexpr int NRAW = 9;
+  __device__ static __forceinline__ void load(const zh16 *p, const uint8_t *ep, uint32_t (&raw)[NRAW]) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const uint4 v = reinterpret_cast<const uint4 *>(p)[h];
+      raw[4 * h] = v.x; raw[4 * h + 1] = v.y; raw[4 * h + 2] = v.z; raw[4 * h + 3] = v.w;
+    }
+    raw[8] = *ep;
+  }
+  __device__ static __forceinline__ void unpack(const uint32_t (&raw)[NRAW], float (&x)[16]) {
+    const float sc = z16_up(raw[8]);
+#pragma unroll
+    for (int m = 0; m < 8; ++m) z16_unpack(raw[m], sc, x[2 * m], x[2 * m + 1]);
+  }
+  __device__ static __forceinline__ void store(zh16 *p, uint8_t *ep, const float (&x)[16]) {
+    float mx = fabsf(x[0]);
+#pragma unroll
+    for (int e = 1; e < 16; ++e) mx = fmaxf(mx, fabsf(x[e]));
+    const uint32_t ex = z16_exponent(mx);
+    const float f = z16_down(ex);
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+      reinterpret_cast<uint4 *>(p)[h] =
+          make_uint4(z16_pack(x[8 * h] * f, x[8 * h + 1] * f), z16_pack(x[8 * h + 2] * f, x[8 * h + 3] * f),
+                     z16_pack(x[8 * h + 4] * f, x[8 * h + 5] * f), z16_pack(x[8 * h + 6] * f, x[8 * h + 7] * f));
+    *ep = (uint8_t)ex;
+  }
+};
+
 // NS stages' parameters of this thread: value q of piece k of stage e at img[((e * 4 + k) * 256 + t) * 4 + q]
 template <int NS>
 __device__ __forceinline__ void load_params(const float *__restrict__ img, int t, float (&f)[NS][16]) {
@@ -273,36 +308,44 @@ __device__ __forceinline__ void stages_A(float (&x)[16], const float (&f)[TRN ? 
 }
 
 // PF = pairs of rows requested ahead of the one being computed
+// Et (block-scaled half rows only): exponent byte of the chunk's first segment in the tile's
+// first row; the rows' exponents are 2 ldx bytes apart.
 template <typename TI, bool TRN, int PF>
 __device__ __forceinline__ void group_A(const float *__restrict__ img, int t, float *buf,
-                                         const TI *__restrict__ Xt, int64_t ldx, int nr) {
+                                         const TI *__restrict__ Xt, int64_t ldx, int nr,
+                                         const uint8_t *__restrict__ Et) {
   constexpr int NS = TRN ? 4 : 8;
   using In = Seg16<TI>;
   constexpr int NRAW = In::NRAW;
+  constexpr bool kZ = std::is_same<TI, zh16>::value;
   const unsigned s = seg_of(TRN, (unsigned)t >> 6, (unsigned)t & 63u);
   const TI *xp = Xt + 16u * s;
   const int last = nr - 1;
   // rows past the end of the tile read its last row again (same address, nothing depends on it),
   // so that every load is unconditional
   auto row_ptr = [&](int r) { return xp + (int64_t)(r < last ? r : last) * ldx; };
+  auto load_row = [&](int r, uint32_t (&raw)[NRAW]) {
+    if constexpr (kZ) In::load(row_ptr(r), Et + (int64_t)(r < last ? r : last) * (2 * ldx) + s, raw);
+    else In::load(row_ptr(r), raw);
+  };
   uint32_t pre[2 * PF][NRAW];
-  In::load(row_ptr(0), pre[0]);
-  In::load(row_ptr(1), pre[1]);
+  load_row(0, pre[0]);
+  load_row(1, pre[1]);
   __builtin_amdgcn_sched_barrier(0);
   float f[NS][16];
   load_params<NS>(img, t, f);
 #pragma unroll
   for (int q = 1; q < PF; ++q) {
-    In::load(row_ptr(2 * q), pre[2 * q]);
-    In::load(row_ptr(2 * q + 1), pre[2 * q + 1]);
+    load_row(2 * q, pre[2 * q]);
+    load_row(2 * q + 1, pre[2 * q + 1]);
   }
   const int npairs = (nr + 1) >> 1;
   auto step = [&](int k, int q) {
     float xa[16], xb[16];
     In::unpack(pre[2 * q], xa);
     In::unpack(pre[2 * q + 1], xb);
-    In::load(row_ptr(2 * (k + PF)), pre[2 * q]);
-    In::load(row_ptr(2 * (k + PF) + 1), pre[2 * q + 1]);
+    load_row(2 * (k + PF), pre[2 * q]);
+    load_row(2 * (k + PF) + 1, pre[2 * q + 1]);
     float *b = buf + (k & 1) * (2 * kRowBuf);
     stages_A<TRN>(xa, f);
     lds_put(b, s, xa);
@@ -363,8 +406,10 @@ __device__ __forceinline__ void stages_B(float (&x)[16], const ParamsB<TRN, LD> 
 
 template <typename TO, bool TRN, bool LD>
 __device__ __forceinline__ void group_B(const float *__restrict__ img, int t, const float *buf,
-                                         TO *__restrict__ Yt, int64_t ldy, int nr) {
+                                         TO *__restrict__ Yt, int64_t ldy, int nr,
+                                         uint8_t *__restrict__ Et) {
   using Out = Seg16<TO>;
+  constexpr bool kZ = std::is_same<TO, zh16>::value;
   using PB = ParamsB<TRN, LD>;
   const unsigned s = seg_of(!TRN, (unsigned)t >> 6, (unsigned)t & 63u);
   TO *yp = Yt + 16u * s;
@@ -382,9 +427,13 @@ __device__ __forceinline__ void group_B(const float *__restrict__ img, int t, co
     lds_get(b, s, xa);
     lds_get(b + kRowBuf, s, xb);
     stages_B<TRN, LD>(xa, pb);
-    Out::store(yp + (int64_t)r0 * ldy, xa);
+    if constexpr (kZ) Out::store(yp + (int64_t)r0 * ldy, Et + (int64_t)r0 * (2 * ldy) + s, xa);
+    else Out::store(yp + (int64_t)r0 * ldy, xa);
     stages_B<TRN, LD>(xb, pb);
-    if (r0 + 1 < nr) Out::store(yp + (int64_t)(r0 + 1) * ldy, xb);
+    if (r0 + 1 < nr) {
+      if constexpr (kZ) Out::store(yp + (int64_t)(r0 + 1) * ldy, Et + (int64_t)(r0 + 1) * (2 * ldy) + s, xb);
+      else Out::store(yp + (int64_t)(r0 + 1) * ldy, xb);
+    }
   };
   // steps 0 (nothing to do yet) and 1 outside the loop: straight-line code in which each stage
   // waits for its own parameters only
@@ -414,10 +463,14 @@ __global__ __launch_bounds__(2 * kTG) void harp_dpp_kernel(const TI *__restrict_
   const int kch = (int)(blockIdx.x % (unsigned)nchunk);
   const int64_t row0 = (int64_t)(blockIdx.x / (unsigned)nchunk) * R;
   const int nr = (int)((n - row0 < R) ? (n - row0) : R);
+  // block-scaled half rows: d halves, then the row's exponent bytes (one per 16 coordinates)
+  const int64_t d = (int64_t)nchunk * kD;
   if (g == 0)
-    group_A<TI, TRN, kPrefetchPairs>(imgA + kch * strideA, t, buf, X + row0 * ldx + (int64_t)kch * kD, ldx, nr);
+    group_A<TI, TRN, kPrefetchPairs>(imgA + kch * strideA, t, buf, X + row0 * ldx + (int64_t)kch * kD, ldx, nr,
+                                     reinterpret_cast<const uint8_t *>(X + row0 * ldx + d) + kch * (kD / 16));
   else
-    group_B<TO, TRN, LD>(imgB + kch * strideB, t, buf, Y + row0 * ldy + (int64_t)kch * kD, ldy, nr);
+    group_B<TO, TRN, LD>(imgB + kch * strideB, t, buf, Y + row0 * ldy + (int64_t)kch * kD, ldy, nr,
+                         reinterpret_cast<uint8_t *>(Y + row0 * ldy + d) + kch * (kD / 16));
 }
 
 // ------------------------------------------------------------------------------------------
@@ -524,7 +577,7 @@ __global__ __launch_bounds__(2 * kTG) void harp_dpp_top_kernel(const uint16_t *_
                 ldx, nr);
   else
     group_B<uint16_t, true, true>(imgB + kch * strideB, t, buf,
-                                  Y + row0 * ldy + (int64_t)kch * kD, ldy, nr);
+                                  Y + row0 * ldy + (int64_t)kch * kD, ldy, nr, nullptr);
 }
 
 template <typename TI, typename TO>
@@ -566,7 +619,12 @@ bool dpp_supported(const harp_plan *plan, const DppImage &di, int chunk, const v
   // bytes apart from its neighbours', the one slow access pattern of this chip (measured:
   // float32 rows 18.2 -> 21.7 us, the float32 intermediate of a 28672-wide split program
   // 250 -> 297 us); those cases keep the three-group kernel, which re-lays rows out in LDS
-  if (dt_in != HARP_BF16 || dt_out != HARP_BF16) return false;
+  // (block-scaled halves, the intermediate of a split program for bf16 callers, are 32 bytes per
+  // lane like bf16: written going up, read going down)
+  const bool plain = (dt_in == HARP_BF16 && dt_out == HARP_BF16);
+  const bool zout = (dt_in == HARP_BF16 && (int)dt_out == kDtZ16 && !di.trn && di.ld);
+  const bool zin = ((int)dt_in == kDtZ16 && dt_out == HARP_BF16 && di.trn);
+  if (!plain && !zout && !zin) return false;
   // 16-byte row accesses for either element type
   if ((ldx % 8) || (ldy % 8) || ((uintptr_t)X % 16) || ((uintptr_t)Y % 16)) return false;
   return true;
@@ -578,6 +636,10 @@ harp_status_t launch_dpp_kernel(const harp_plan *plan, const DppImage &di, const
   const int nchunk = (int)(plan->d / kD);
   if (dt_in == HARP_BF16 && dt_out == HARP_BF16)
     return launch_dpp_io<uint16_t, uint16_t>(di, X, ldx, Y, ldy, n, R, nchunk, stream);
+  if (dt_in == HARP_BF16 && (int)dt_out == kDtZ16 && !di.trn && di.ld)
+    return launch_dpp_io<uint16_t, zh16>(di, X, ldx, Y, ldy, n, R, nchunk, stream);
+  if ((int)dt_in == kDtZ16 && dt_out == HARP_BF16 && di.trn)
+    return launch_dpp_io<zh16, uint16_t>(di, X, ldx, Y, ldy, n, R, nchunk, stream);
   return HARP_ERR_UNSUPPORTED;   // see dpp_supported
 }
 

@@ -109,6 +109,9 @@ struct HostProgram {
   // split program of a row that also fits one chunk (radix-2 stages + one radix-3 stage): it
   // only pays for large forward batches, see select_program
   bool optional = false;
+  // the float32 intermediate may be replaced by block-scaled halves for bf16 callers (set by the
+  // plan builder: orthogonal blocks, no scale pending where the intermediate is written)
+  bool z16 = false;
 };
 
 enum Direction { DIR_FWD = 0, DIR_TRN = 1 };
@@ -150,6 +153,42 @@ struct ColStage {
 };
 
 
+
+// ---- block-scaled half-precision intermediate of split programs ("Z16") --------------------
+// Between the chunk kernel and the one streamed stage of a split program a bf16 caller's rows
+// may travel as IEEE half-precision values with one shared power-of-two scale per aligned
+// segment of 16 coordinates instead of float32: a row of the buffer is d halves followed by
+// d / 16 exponent bytes (row pitch z16_ld(d) halves).  Byte e of a segment is the biased
+// float32 exponent of its largest magnitude (at most 253); a stored half h stands for
+// h * 2^(e - 127), so the largest element of a segment is stored in [1, 2) and every element
+// with a relative error of at most 2^-12 of itself or 2^-25 of that largest element.
+struct zh16 {
+  uint16_t v;
+};
+constexpr int kDtZ16 = 2;   // internal element-type tag next to HARP_F32 / HARP_BF16
+inline int64_t z16_ld(int64_t d) { return (d + d / 32 + 7) / 8 * 8; }
+
+#if defined(__HIPCC__)
+__device__ __forceinline__ uint32_t z16_exponent(float largest_magnitude) {
+  const uint32_t e = (__float_as_uint(largest_magnitude) >> 23) & 0xffu;
+  return e > 253u ? 253u : e;
+}
+__device__ __forceinline__ float z16_down(uint32_t e) { return __uint_as_float((254u - e) << 23); }
+__device__ __forceinline__ float z16_up(uint32_t e) { return __uint_as_float(e << 23); }
+__device__ __forceinline__ uint32_t z16_pack(float a, float b) {
+  typedef float f2v __attribute__((ext_vector_type(2)));
+  typedef _Float16 h2v __attribute__((ext_vector_type(2)));
+  const f2v v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, h2v));
+}
+__device__ __forceinline__ void z16_unpack(uint32_t w, float scale, float &a, float &b) {
+  typedef float f2v __attribute__((ext_vector_type(2)));
+  typedef _Float16 h2v __attribute__((ext_vector_type(2)));
+  const f2v v = __builtin_convertvector(__builtin_bit_cast(h2v, w), f2v);
+  a = v.x * scale;
+  b = v.y * scale;
+}
+#endif
 
 struct LaunchCfg {
   int rows_per_tile;
@@ -193,6 +232,7 @@ struct harp_plan {
   std::vector<harp::ColStage> col[2];
   std::vector<harp::ColPassHost> colpass[2];
   const int8_t *dev_signs = nullptr;   // device copy of the signs (null: all +1)
+  bool orthogonal = true;              // every block satisfies |K^T K - I| <= 1e-5
   bool theta_in_kernel = false;        // some pass carries an int8 image (HARP_THETA_IN_KERNEL)
 };
 
@@ -211,6 +251,8 @@ harp_status_t launch_stream_pass(const harp_plan *plan, const HostProgram &hp, i
                                  const void *X, int64_t ldx, harp_dtype_t dt_in, void *Y,
                                  int64_t ldy, harp_dtype_t dt_out, int64_t n, bool allow_narrow,
                                  hipStream_t stream);
+bool stream_z16_supported(const PassDesc &pd, const void *X, int64_t ldx, const void *Y,
+                          int64_t ldy);
 // large-radix stage on the matrix cores (harp_mfma.hip)
 bool mfma_pass_supported(const PassDesc &pd, const void *X, int64_t ldx, const void *Y,
                          int64_t ldy);

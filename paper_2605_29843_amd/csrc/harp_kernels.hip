@@ -528,6 +528,111 @@ __global__ __launch_bounds__(256) void harp_stream_kernel(const TI *__restrict__
   }
 }
 
+// The same stage between a bf16 side and the block-scaled half intermediate (2 bytes per
+// coordinate on both sides).  A thread owns TWO neighbouring sub-tensors (coordinates lo, lo + 1
+// of every j: one 32-bit access per j and row), eight lanes share a segment of 16 coordinates
+// and its exponent byte.  ZIN: halves in, bf16 out (the stage is the last of a forward
+// program); otherwise bf16 in, halves out (the first of a transposed one): the segment's
+// largest magnitude is found with three DPP steps (lane ^ 1, lane ^ 2, mirror of the eight).
+// Two rows in flight as above; S and the sub-tensor count are even, S a multiple of 16.
+template <class OP, bool ZIN>
+__global__ __launch_bounds__(256) void harp_stream_z16_kernel(const uint16_t *__restrict__ X,
+                                                              int64_t ldx, uint16_t *__restrict__ Y,
+                                                              int64_t ldy, int64_t n,
+                                                              int rows_per_block,
+                                                              const float *__restrict__ params,
+                                                              int nq, int S, int d) {
+  constexpr int P = OP::P, NV = OP::NV;
+  const int q = 2 * (blockIdx.x * 256 + threadIdx.x);
+  if (q >= nq) return;
+  float prm[2][NV];
+#pragma unroll
+  for (int v = 0; v < NV; ++v) {
+    prm[0][v] = params[(size_t)v * nq + q];
+    prm[1][v] = params[(size_t)v * nq + q + 1];
+  }
+  const int hi = q / S, lo = q - hi * S;
+  const unsigned base = (unsigned)hi * P * S + lo;
+  const int64_t r0 = (int64_t)blockIdx.y * rows_per_block;
+  const int nr = (int)((r0 + rows_per_block < n) ? rows_per_block : n - r0);
+  const uint16_t *xp = X + r0 * ldx;
+  uint16_t *yp = Y + r0 * ldy;
+  struct Raw {
+    uint32_t w[P];
+    uint32_t e[ZIN ? P : 1];
+  };
+  auto request = [&](const uint16_t *xr, Raw &raw) {
+#pragma unroll
+    for (int j = 0; j < P; ++j) {
+      raw.w[j] = *reinterpret_cast<const uint32_t *>(xr + base + (unsigned)(j * S));
+      if (ZIN) raw.e[j] = reinterpret_cast<const uint8_t *>(xr + d)[(base + (unsigned)(j * S)) >> 4];
+    }
+  };
+  auto finish = [&](const Raw &raw, uint16_t *yr) {
+    float x0[P], x1[P];
+#pragma unroll
+    for (int j = 0; j < P; ++j) {
+      if (ZIN) {
+        z16_unpack(raw.w[j], z16_up(raw.e[j]), x0[j], x1[j]);
+      } else {
+        x0[j] = __uint_as_float(raw.w[j] << 16);
+        x1[j] = __uint_as_float(raw.w[j] & 0xffff0000u);
+      }
+    }
+    OP::apply(x0, prm[0]);
+    OP::apply(x1, prm[1]);
+    if (ZIN) {
+#pragma unroll
+      for (int j = 0; j < P; ++j)
+        *reinterpret_cast<uint32_t *>(yr + base + (unsigned)(j * S)) = pack_bf16x2(x0[j], x1[j]);
+    } else {
+      // largest magnitude of every segment: the P reductions run side by side (as bit patterns
+      // of non-negative floats, which order like unsigned integers)
+      uint32_t mx[P];
+#pragma unroll
+      for (int j = 0; j < P; ++j) mx[j] = __float_as_uint(fmaxf(fabsf(x0[j]), fabsf(x1[j])));
+#pragma unroll
+      for (int j = 0; j < P; ++j)
+        mx[j] = max(mx[j], (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mx[j], 0xB1 /* quad_perm [1,0,3,2] */, 0xf, 0xf, false));
+#pragma unroll
+      for (int j = 0; j < P; ++j)
+        mx[j] = max(mx[j], (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mx[j], 0x4E /* quad_perm [2,3,0,1] */, 0xf, 0xf, false));
+#pragma unroll
+      for (int j = 0; j < P; ++j)
+        mx[j] = max(mx[j], (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mx[j], 0x141 /* row_half_mirror */, 0xf, 0xf, false));
+#pragma unroll
+      for (int j = 0; j < P; ++j) {
+        uint32_t ex = mx[j] >> 23;
+        ex = ex > 253u ? 253u : ex;
+        mx[j] = ex;
+        const float f = z16_down(ex);
+        *reinterpret_cast<uint32_t *>(yr + base + (unsigned)(j * S)) = z16_pack(x0[j] * f, x1[j] * f);
+      }
+      if ((threadIdx.x & 7) == 0) {
+#pragma unroll
+        for (int j = 0; j < P; ++j)
+          reinterpret_cast<uint8_t *>(yr + d)[(base + (unsigned)(j * S)) >> 4] = (uint8_t)mx[j];
+      }
+    }
+  };
+  Raw a, b;
+  request(xp, a);
+  for (int r = 0; r < nr; r += 2) {
+    const uint16_t *xb = (r + 1 < nr) ? xp + ldx : xp;
+    uint16_t *yb = (r + 1 < nr) ? yp + ldy : yp;
+    request(xb, b);
+    __builtin_amdgcn_sched_barrier(0);
+    finish(a, yp);
+    __builtin_amdgcn_sched_barrier(0);
+    xp = (r + 2 < nr) ? xb + ldx : xb;
+    request(xp, a);
+    __builtin_amdgcn_sched_barrier(0);
+    finish(b, yb);
+    __builtin_amdgcn_sched_barrier(0);
+    yp = yb + ldy;
+  }
+}
+
 // run-time radix (9..64): parameters are re-read for every row (slow, correctness path)
 template <int BMAX>
 __global__ __launch_bounds__(256) void harp_stream_generic_kernel(
@@ -607,6 +712,23 @@ harp_status_t launch_stream_op(const harp_plan *plan, const PassDesc &pd, const 
   if (!ib && ob) return launch_stream_typed<OP, float, uint16_t>(plan, pd, X, ldx, Y, ldy, n, stream);
   if (!ib && !ob) return launch_stream_typed<OP, float, float>(plan, pd, X, ldx, Y, ldy, n, stream);
   return HARP_ERR_UNSUPPORTED;
+}
+
+// dense stage of radix 3..8 between a bf16 side and the block-scaled half intermediate
+template <class OP>
+harp_status_t launch_stream_z16_op(const harp_plan *plan, const PassDesc &pd, const void *X,
+                                   int64_t ldx, void *Y, int64_t ldy, int64_t n, bool zin,
+                                   hipStream_t stream) {
+  const StreamGrid g = stream_grid(pd.nq / 2, plan, n);
+  if (zin)
+    hipLaunchKernelGGL((harp_stream_z16_kernel<OP, true>), dim3(g.gx, g.gy), dim3(256), 0, stream,
+                       (const uint16_t *)X, ldx, (uint16_t *)Y, ldy, n, g.rpb, pd.params, pd.nq, pd.S,
+                       (int)plan->d);
+  else
+    hipLaunchKernelGGL((harp_stream_z16_kernel<OP, false>), dim3(g.gx, g.gy), dim3(256), 0, stream,
+                       (const uint16_t *)X, ldx, (uint16_t *)Y, ldy, n, g.rpb, pd.params, pd.nq, pd.S,
+                       (int)plan->d);
+  return hipGetLastError() == hipSuccess ? HARP_OK : HARP_ERR_DEVICE;
 }
 
 template <bool DESC, int FORM>
@@ -842,6 +964,17 @@ harp_status_t launch_tile_kernel(const harp_plan *plan, const Program *prog, int
   return launch_tile_typed<float, uint16_t>(plan, prog, p0, p1, chunk, X, ldx, Y, ldy, n, stream);
 }
 
+// the streamed stage has a kernel for the block-scaled half intermediate: one dense stage of
+// radix 3..8 whose stride is a multiple of 16, rows that allow 32-bit accesses
+bool stream_z16_supported(const PassDesc &pd, const void *X, int64_t ldx, const void *Y,
+                          int64_t ldy) {
+  if (pd.kind != PASS_SMALL || pd.b < 3 || pd.b > 8 || pd.tied) return false;
+  if (pd.S % 16 != 0 || (pd.nq & 1)) return false;
+  if ((ldx % 2) || (ldy % 2) || ((uintptr_t)X % 4) || ((uintptr_t)Y % 4)) return false;
+  if ((int64_t)pd.P * pd.S >= (int64_t)1 << 31) return false;
+  return true;
+}
+
 harp_status_t launch_stream_pass(const harp_plan *plan, const HostProgram &hp, int p,
                                  const void *X, int64_t ldx, harp_dtype_t dt_in, void *Y,
                                  int64_t ldy, harp_dtype_t dt_out, int64_t n, bool allow_narrow,
@@ -851,6 +984,19 @@ harp_status_t launch_stream_pass(const harp_plan *plan, const HostProgram &hp, i
   if (!plan->no_mfma && mfma_pass_supported(pd, X, ldx, Y, ldy))
     return launch_mfma_pass(plan, pd, X, ldx, dt_in, Y, ldy, dt_out, n, allow_narrow, stream);
   if (pd.tied) return HARP_ERR_UNSUPPORTED;   // only the matrix-core kernel reads a tied table
+  if ((int)dt_in == kDtZ16 || (int)dt_out == kDtZ16) {
+    if (!stream_z16_supported(pd, X, ldx, Y, ldy)) return HARP_ERR_UNSUPPORTED;
+    const bool zin = (int)dt_in == kDtZ16;
+    if ((zin && dt_out != HARP_BF16) || (!zin && dt_in != HARP_BF16)) return HARP_ERR_UNSUPPORTED;
+    switch (pd.b) {
+      case 3: return launch_stream_z16_op<OpSmall<3>>(plan, pd, X, ldx, Y, ldy, n, zin, stream);
+      case 4: return launch_stream_z16_op<OpSmall<4>>(plan, pd, X, ldx, Y, ldy, n, zin, stream);
+      case 5: return launch_stream_z16_op<OpSmall<5>>(plan, pd, X, ldx, Y, ldy, n, zin, stream);
+      case 6: return launch_stream_z16_op<OpSmall<6>>(plan, pd, X, ldx, Y, ldy, n, zin, stream);
+      case 7: return launch_stream_z16_op<OpSmall<7>>(plan, pd, X, ldx, Y, ldy, n, zin, stream);
+      default: return launch_stream_z16_op<OpSmall<8>>(plan, pd, X, ldx, Y, ldy, n, zin, stream);
+    }
+  }
   const int ib = dt_in == HARP_BF16, ob = dt_out == HARP_BF16;
   switch (pd.kind) {
     case PASS_POW2_DENSE:

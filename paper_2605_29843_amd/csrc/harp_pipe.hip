@@ -26,6 +26,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "harp_internal.h"
 
 namespace harp {
@@ -134,6 +136,43 @@ struct RowIo<uint16_t, true> {      // 16 contiguous bf16 (or 2 x 8): two 16-byt
     for (int h = 0; h < 2; ++h)
       *reinterpret_cast<uint4 *>(yr + off(8 * h)) =
           make_uint4(w[4 * h], w[4 * h + 1], w[4 * h + 2], w[4 * h + 3]);
+  }
+};
+
+// 16 contiguous block-scaled halves = one aligned segment: two 16-byte accesses and the
+// segment's exponent byte, which lies d halves behind the start of the row (xr = row start)
+template <>
+struct RowIo<zh16, true> {
+  static constexpr int NRAW = 9;
+  template <class OFF>
+  __device__ static __forceinline__ void load_z(const zh16 *xr, OFF off, int d, uint32_t (&raw)[NRAW]) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const uint4 v = *reinterpret_cast<const uint4 *>(xr + off(8 * h));
+      raw[4 * h + 0] = v.x; raw[4 * h + 1] = v.y; raw[4 * h + 2] = v.z; raw[4 * h + 3] = v.w;
+    }
+    raw[8] = reinterpret_cast<const uint8_t *>(xr + d)[off(0) >> 4];
+  }
+  __device__ static __forceinline__ void unpack(const uint32_t (&raw)[NRAW], float (&x)[16]) {
+    const float sc = z16_up(raw[8]);
+#pragma unroll
+    for (int m = 0; m < 8; ++m) z16_unpack(raw[m], sc, x[2 * m], x[2 * m + 1]);
+  }
+  template <class OFF>
+  __device__ static __forceinline__ void store_z(zh16 *yr, OFF off, int d, const float (&x)[16]) {
+    float mx = fabsf(x[0]);
+#pragma unroll
+    for (int e = 1; e < 16; ++e) mx = fmaxf(mx, fabsf(x[e]));
+    const uint32_t ex = z16_exponent(mx);
+    const float f = z16_down(ex);
+    uint32_t w[8];
+#pragma unroll
+    for (int m = 0; m < 8; ++m) w[m] = z16_pack(x[2 * m] * f, x[2 * m + 1] * f);
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+      *reinterpret_cast<uint4 *>(yr + off(8 * h)) =
+          make_uint4(w[4 * h], w[4 * h + 1], w[4 * h + 2], w[4 * h + 3]);
+    reinterpret_cast<uint8_t *>(yr + d)[off(0) >> 4] = (uint8_t)ex;
   }
 };
 
@@ -449,6 +488,28 @@ struct WaveStoreLayout {
   }
   // pieces whose coordinates lie inside the row (valid = coordinates of the window inside it)
   __device__ __forceinline__ void store(TO *yw, const float (&x)[16], int valid) const;
+  // block-scaled halves (yrow = start of the row, w0 = first coordinate of the window): a piece
+  // is half a segment, the other half belongs to the neighbouring lane
+  __device__ __forceinline__ void store_z16(zh16 *yrow, unsigned w0, int d, const float (&x)[16],
+                                            int valid) const {
+#pragma unroll
+    for (int g = 0; g < 2; ++g) {
+      float mx = fabsf(x[8 * g]);
+#pragma unroll
+      for (int e = 1; e < 8; ++e) mx = fmaxf(mx, fabsf(x[8 * g + e]));
+      const float other = __uint_as_float((uint32_t)__builtin_amdgcn_update_dpp(
+          0, (int)__float_as_uint(mx), 0xB1 /* quad_perm [1,0,3,2] */, 0xf, 0xf, false));
+      const uint32_t ex = z16_exponent(fmaxf(mx, other));
+      const float f = z16_down(ex);
+      const unsigned c = (unsigned)g * 512u + 8u * t;
+      if ((int)c < valid) {
+        *reinterpret_cast<uint4 *>(yrow + w0 + c) =
+            make_uint4(z16_pack(x[8 * g] * f, x[8 * g + 1] * f), z16_pack(x[8 * g + 2] * f, x[8 * g + 3] * f),
+                       z16_pack(x[8 * g + 4] * f, x[8 * g + 5] * f), z16_pack(x[8 * g + 6] * f, x[8 * g + 7] * f));
+        if (!(t & 1u)) reinterpret_cast<uint8_t *>(yrow + d)[(w0 + c) >> 4] = (uint8_t)ex;
+      }
+    }
+  }
   // bf16 only: sign bits of the packed elements flipped where flip[m] has them set
   __device__ __forceinline__ void store_flipped(uint16_t *yw, const float (&x)[16], int valid,
                                                 const uint32_t (&flip)[8]) const {
@@ -574,6 +635,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void ha
   using In = RowIo<TI, true>;
   using Out = RowIo<TO, true>;
   constexpr int NRAW = In::NRAW;
+  constexpr bool kZIn = std::is_same<TI, zh16>::value, kZOut = std::is_same<TO, zh16>::value;
   // Rows requested ahead: two, but one when the input is float32 and there are three passes.
   // That combination (the transposed chunk kernels of split programs) otherwise needs 264 to
   // 277 registers per thread, past the 256 at which a second wave still fits on a SIMD, and ran
@@ -584,7 +646,10 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void ha
   for (int s = 0; s < PF; ++s) {
 #pragma unroll
     for (int m = 0; m < NRAW; ++m) pre[s][m] = 0u;
-    if (active && s < nr) In::load(X + (row0 + s) * ldx, goff, pre[s]);
+    if (active && s < nr) {
+      if constexpr (kZIn) In::load_z(X + (row0 + s) * ldx, goff, d, pre[s]);
+      else In::load(X + (row0 + s) * ldx, goff, pre[s]);
+    }
   }
 
   for (int r0 = 0; r0 < nr; r0 += PF) {
@@ -601,7 +666,10 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void ha
       } else {
         In::unpack(pre[s], x);
       }
-      if (active && r + PF < nr) In::load(X + (row0 + r + PF) * ldx, goff, pre[s]);
+      if (active && r + PF < nr) {
+        if constexpr (kZIn) In::load_z(X + (row0 + r + PF) * ldx, goff, d, pre[s]);
+        else In::load(X + (row0 + r + PF) * ldx, goff, pre[s]);
+      }
       if (kFlipIn && !kPackedFlip) flip_f32(x);
 
       if (!(K0 == 4 && LS0 == 0)) wave_exchange(x, buf, io, pa);
@@ -621,6 +689,12 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void ha
           if (active) Out::store_flipped(Y + (row0 + r) * ldy, goff, x, sgw);
         } else {
           sl.store_flipped(Y + (row0 + r) * ldy + w0, x, valid, sgw);
+        }
+      } else if constexpr (kZOut) {
+        if (kLastIsIo) {
+          if (active) Out::store_z(Y + (row0 + r) * ldy, goff, d, x);
+        } else {
+          sl.store_z16(Y + (row0 + r) * ldy, (unsigned)w0, d, x, valid);
         }
       } else if (kLastIsIo) {
         if (active) Out::store(Y + (row0 + r) * ldy, goff, x);
@@ -863,6 +937,13 @@ harp_status_t launch_wave_kernel(const harp_plan *plan, const HostProgram &hp, i
     if (dt_in == HARP_F32 && dt_out == HARP_BF16) return launch_wave_tied_io<float, uint16_t>(a, logc, trn, sgn);
     return launch_wave_tied_io<float, float>(a, logc, trn, sgn);
   }
+  // block-scaled half intermediate of a split program: written going up, read going down
+  if ((int)dt_out == kDtZ16)
+    return (dt_in == HARP_BF16 && !trn) ? launch_wave_io<uint16_t, zh16>(a, logc, false, ld, sc)
+                                        : HARP_ERR_UNSUPPORTED;
+  if ((int)dt_in == kDtZ16)
+    return (dt_out == HARP_BF16 && trn) ? launch_wave_io<zh16, uint16_t>(a, logc, true, ld, sc)
+                                        : HARP_ERR_UNSUPPORTED;
   if (dt_in == HARP_BF16 && dt_out == HARP_BF16)
     return launch_wave_io<uint16_t, uint16_t>(a, logc, trn, ld, sc);
   if (dt_in == HARP_BF16 && dt_out == HARP_F32)
