@@ -31,12 +31,15 @@ KERNEL_SYMBOL = {"dpp_radix2": "harp_dpp_kernel",
                  "split_chunk_stream": "harp_tile_kernel", "wave_radix2": "harp_wave_kernel",
                  "split_wave_stream": "harp_wave_kernel", "radix_tile": "harp_radix_kernel",
                  "split_radix_stream": "harp_radix_kernel", "radix_tile_int8": "harp_radix_kernel",
-                 "split_radix_stream_int8": "harp_radix_kernel"}
+                 "split_radix_stream_int8": "harp_radix_kernel",
+                 "split_dpp_stream_h16": "harp_dpp_kernel", "split_wave_stream_h16": "harp_wave_kernel"}
 
 
 # kernels one call of harp_apply launches, by the path name harp_plan_kernel_name reports
 KERNELS_OF = {"split_wave_stream": ["harp_wave_kernel", "harp_stream_mfma_kernel"],
-              "split_pipe_stream": ["harp_pipe_kernel", "harp_stream_kernel"]}
+              "split_pipe_stream": ["harp_pipe_kernel", "harp_stream_kernel"],
+              "split_dpp_stream_h16": ["harp_dpp_kernel", "harp_stream_z16_kernel"],
+              "split_wave_stream_h16": ["harp_wave_kernel", "harp_stream_z16_kernel"]}
 
 
 def cpu_baseline(w, sample_rows: int):

@@ -1550,6 +1550,9 @@ const char *harp_plan_kernel_name(const harp_plan_t *plan, int64_t n, harp_dtype
                                                                                   : "radix_tile";
   if (hp && hp->n_chunk != hp->prog.npass) {
     const int p0 = hp->chunk_first ? 0 : hp->prog.npass - hp->n_chunk;
+    // bf16 callers: the intermediate as block-scaled halves
+    if (split_uses_z16(plan, *hp, nullptr, 8, dt, nullptr, 8, dt))
+      return hp->chunk == 4096 ? "split_dpp_stream_h16" : "split_wave_stream_h16";
     if (pipe_supported(plan, hp->prog, p0, hp->n_chunk, hp->chunk, nullptr, 8, nullptr, 8))
       return "split_pipe_stream";
     if (wave_supported(plan, hp->prog, p0, hp->n_chunk, hp->chunk, nullptr, 8, nullptr, 8))

@@ -474,6 +474,52 @@ def test_chunk_of_a_llama13b_ffn_row_ends_behind_its_radix2_stages(harp):
     run_case(harp, d, radices, 19, "f32", seed=77, act=gi.activations(19, d, config=3, bf16=False))
 
 
+@pytest.mark.parametrize("d,radices", [
+    (12288, [2] * 12 + [3]),      # DPP kernel on chunks of 4096 + streamed radix 3
+    (28672, [2] * 12 + [7]),      # ... + streamed radix 7
+    (5120, [2] * 10 + [5]),       # wave kernel on chunks of 1024 + streamed radix 5
+    (7168, [2] * 10 + [7]),       # wave kernel on chunks of 1024 + streamed radix 7
+    (2048 * 3, [2] * 9 + [4, 3]), # two streamed stages: keeps the float32 intermediate
+])
+def test_half_precision_intermediate_of_split_programs(harp, d, radices):
+    """bf16 callers of a split program with one streamed small-radix stage: the intermediate
+    travels as block-scaled halves (one power-of-two scale per 16 coordinates).  Rows chosen to
+    stress that format -- zero rows, one-hot rows, rows 1e-30 and 1e18 in size (the two-shear form is specified for |x| < 2^64), a lone outlier of
+    1e5 next to ordinary values, chunks of a row 1e12 apart in scale -- must still meet the bf16
+    bar against the float64 oracle, in both directions; float32 callers keep float32."""
+    import torch
+    rng = np.random.default_rng(d)
+    blocks = gi.make_blocks(d, radices, "orth", rng)
+    signs = gi.make_signs(d, rng)
+    plan = harp.Plan(d, radices, blocks, signs)
+    one_streamed = radices[-2] == 2
+    name16, name32 = plan.kernel_name(64, harp.HARP_BF16), plan.kernel_name(64, harp.HARP_F32)
+    say(f"half intermediate d={d} radices={radices}: bf16 -> {name16}, f32 -> {name32}")
+    assert name16.endswith("_h16") == one_streamed, name16
+    assert not name32.endswith("_h16"), name32
+    g = rng.standard_normal
+    rows = [np.zeros(d), np.eye(1, d, 5)[0], 3e4 * np.eye(1, d, d - 1)[0], 1e-30 * g(d), 1e18 * g(d)]
+    r = g(d)
+    r[d // 3] = 1e5
+    rows.append(r)
+    r = g(d) * np.where((np.arange(d) // 256) % 2 == 0, 1e6, 1e-6)
+    rows.append(r)
+    r = g(d)
+    r[::16] *= 3e3                 # one large value in every segment of the input
+    rows.append(r)
+    X = np.concatenate([np.stack(rows), gi.activations(27, d, config=3, bf16=True).astype(np.float64)])
+    X = gi.round_to_bf16(X.astype(np.float32))
+    Yref = ho.apply_staged(X, d, radices, blocks, signs)
+    Zref = ho.apply_transpose_staged(X, d, radices, blocks, signs)
+    Y = to_host64(harp.harp_apply(plan, to_device(X, "bf16")))
+    Z = to_host64(harp.harp_apply_transpose(plan, to_device(X, "bf16")))
+    torch.cuda.synchronize()
+    assert_parity(Y, Yref, "bf16", "apply")
+    assert_parity(Z, Zref, "bf16", "apply_transpose")
+    assert not Y[0].any() and not Z[0].any()       # a zero row stays exactly zero
+    plan.destroy()
+
+
 def test_split_is_refused_when_there_is_nothing_to_split(harp):
     rng = np.random.default_rng(1)
     plan = harp.Plan(4096, [2] * 12, gi.make_blocks(4096, [2] * 12, "orth", rng))
