@@ -244,8 +244,8 @@ void pack_mfma_block(const float *K, int b, uint16_t *out, float *out32) {
 // transposed one), all in the two-shear form except that the last may be the program's dense
 // last stage.  eff[i0 .. i0 + 12) are those stages in execution order.  Appends to `image`.
 void build_dpp_image(const harp_plan *plan, const std::vector<StageEff> &eff, int i0, Direction dir,
-                     HostProgram &hp, std::vector<float> &image, int dense_i = -1) {
-  constexpr int L = 12, D = 1 << L, TG = D / 16;
+                     HostProgram &hp, std::vector<float> &image, int dense_i = -1, int L = 12) {
+  const int D = 1 << L, TG = D / 16;   // L = 12, or 11 (chunks of 2048, 128 threads per group)
   hp.dpp = DppImage();
   const int m = plan->m;
   if (i0 < 0 || i0 + L > m || plan->d % D) return;
@@ -264,7 +264,7 @@ void build_dpp_image(const harp_plan *plan, const std::vector<StageEff> &eff, in
   }
   if (dir == DIR_TRN && !ld) return;
   const bool trn = (dir == DIR_TRN);
-  const int nsa = trn ? 4 : 8;                 // shear stages of group A
+  const int nsa = trn ? L - 8 : 8;             // shear stages of group A
   const int nsb = L - nsa - (ld ? 1 : 0);      // shear stages of group B
   const int64_t nchunk = plan->d / D;
   const int64_t strideA = (int64_t)nsa * D, strideB = (int64_t)(nsb + (ld ? 2 : 0)) * D;
@@ -286,7 +286,7 @@ void build_dpp_image(const harp_plan *plan, const std::vector<StageEff> &eff, in
         for (int k = 0; k < 4; ++k)
           for (int t = 0; t < TG; ++t)
             for (int q = 0; q < 4; ++q) {
-              const int64_t i = kch * D + 16 * (int64_t)dpp_segment_of(high, (unsigned)t) + 4 * k + q;
+              const int64_t i = kch * D + 16 * (int64_t)dpp_segment_of(high, (unsigned)t, L) + 4 * k + q;
               const int64_t c = block_of(se, i);
               const int r = (int)((i / se.s) & 1);
               const size_t slot = ((size_t)(ee * 4 + k) * TG + t) * 4 + q;
@@ -306,6 +306,7 @@ void build_dpp_image(const harp_plan *plan, const std::vector<StageEff> &eff, in
   hp.dpp.strideB = strideB;
   hp.dpp.trn = trn;
   hp.dpp.ld = ld;
+  hp.dpp.logd = L;
 }
 
 bool build_program(const harp_plan *plan, const std::vector<const float *> &blocks,
@@ -372,7 +373,7 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
   // of 256 / 512 / 1024 on the wave kernel, and the small-radix streamed kernel)
   hp.z16 = (algo == HARP_ALGO_SPLIT && !tied && plan->orthogonal && tb == m - 1 &&
             plan->radices[m - 1] >= 3 && plan->radices[m - 1] <= 8 && d % 32 == 0 &&
-            (chunk == 4096 || chunk == 1024 || chunk == 512 || chunk == 256));
+            (chunk == 4096 || chunk == 2048 || chunk == 1024 || chunk == 512 || chunk == 256));
   const int dense_t = tied ? m - 2 : ((hp.z16 && plan->radices[tb - 1] == 2) ? tb - 1 : -1);
   std::vector<StageEff> eff;
   if (!build_effective(plan, blocks, signs, algo, dir, true, eff, dense_t)) {
@@ -577,12 +578,16 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
   hp.dpp = DppImage();
   if (algo == HARP_ALGO_FUSED && chunk == 4096 && tb == 12 && m == 12)
     build_dpp_image(plan, eff, 0, dir, hp, image);
+  if (algo == HARP_ALGO_FUSED && chunk == 2048 && tb == 11 && m == 11)
+    build_dpp_image(plan, eff, 0, dir, hp, image, -1, 11);
   // Split programs whose intermediate may travel as block-scaled halves: the chunks of 4096 of a
   // bf16 caller run on the DPP kernel too (a thread's 16 coordinates are one segment of that
   // format in both of its layouts).
   if (algo == HARP_ALGO_SPLIT && hp.z16 && chunk == 4096 && tb == 12 && m == 13 &&
       !(dir == DIR_TRN && (eff[0].b == 3 || eff[0].b == 5)))   // (those: the image built below)
     build_dpp_image(plan, eff, dir == DIR_FWD ? 0 : 1, dir, hp, image, dir == DIR_FWD ? dense_t : -1);
+  if (algo == HARP_ALGO_SPLIT && hp.z16 && chunk == 2048 && tb == 11 && m == 12)
+    build_dpp_image(plan, eff, dir == DIR_FWD ? 0 : 1, dir, hp, image, dir == DIR_FWD ? dense_t : -1, 11);
   // Transposed split program of twelve radix-2 stages below one dense stage of radix 3 or 5
   // (12288, 20480; radix 7 measured no gain): that stage runs first and is executed by the DPP kernel's first
   // group on the way in (harp_dpp_top_kernel).  Its factors: for output chunk kch, input chunk
@@ -1552,7 +1557,7 @@ const char *harp_plan_kernel_name(const harp_plan_t *plan, int64_t n, harp_dtype
     const int p0 = hp->chunk_first ? 0 : hp->prog.npass - hp->n_chunk;
     // bf16 callers: the intermediate as block-scaled halves
     if (split_uses_z16(plan, *hp, nullptr, 8, dt, nullptr, 8, dt))
-      return hp->chunk == 4096 ? "split_dpp_stream_h16" : "split_wave_stream_h16";
+      return hp->chunk >= 2048 ? "split_dpp_stream_h16" : "split_wave_stream_h16";
     if (pipe_supported(plan, hp->prog, p0, hp->n_chunk, hp->chunk, nullptr, 8, nullptr, 8))
       return "split_pipe_stream";
     if (wave_supported(plan, hp->prog, p0, hp->n_chunk, hp->chunk, nullptr, 8, nullptr, 8))

@@ -44,6 +44,16 @@ namespace {
 constexpr int kLogD = 12, kD = 1 << kLogD, kTG = kD / 16;       // 256 threads per group
 constexpr int kPlane = 260;                                       // 256 floats + 4 of padding
 constexpr int kRowBuf = (kD / 256) * kPlane;                      // floats per buffered row
+// The same kernel on rows or chunks of 2048 coordinates (eleven stages; LOGD = 11): 128 threads
+// per group; layout L as above with one wave bit (digit 10); layout H: the DPP digits are 8, 9,
+// 10 and (unused as a stage) 4, lane bits 4,5 are digits 5,6, the wave is digit 7.  Group A of a
+// forward program still runs digits 0..7, group B the three digits 8..10; transposed: A runs
+// 10..8, B 7..0.
+template <int LOGD>
+struct Geo {
+  static constexpr int D = 1 << LOGD, TG = D / 16, ROWBUF = (D / 256) * kPlane;
+  static constexpr int NHI = LOGD - 8;   // stages on the digits above 7
+};
 constexpr int kPrefetchPairs = 1;
 constexpr int kSleepB = 0;
 
@@ -56,9 +66,13 @@ __device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
 }
 
 // Segment (run of 16 coordinates) of thread (wave w, lane l) in the two layouts.
+template <int LOGD = 12>
 __device__ __forceinline__ unsigned seg_of(bool high, unsigned w, unsigned l) {
   const unsigned low4 = l & 15u;
   const unsigned e = low4 ^ (((low4 >> 2) & 1u) * 3u);   // digit values of the four DPP digits
+  if (LOGD == 11)
+    return high ? ((e >> 3) | ((l >> 4) << 1) | (w << 3) | ((e & 7u) << 4))
+                : (e | ((l >> 4) << 4) | (w << 6));
   return high ? ((l >> 4) | (w << 2) | (e << 4)) : (e | ((l >> 4) << 4) | (w << 6));
 }
 
@@ -255,14 +269,14 @@ struct Seg16<zh16> {
 };
 
 // NS stages' parameters of this thread: value q of piece k of stage e at img[((e * 4 + k) * 256 + t) * 4 + q]
-template <int NS>
+template <int NS, int TG = kTG>
 __device__ __forceinline__ void load_params(const float *__restrict__ img, int t, float (&f)[NS][16]) {
   const float4 *p = reinterpret_cast<const float4 *>(img);
 #pragma unroll
   for (int e = 0; e < NS; ++e) {
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-      const float4 v = p[(e * 4 + k) * kTG + t];
+      const float4 v = p[(e * 4 + k) * TG + t];
       f[e][4 * k] = v.x; f[e][4 * k + 1] = v.y; f[e][4 * k + 2] = v.z; f[e][4 * k + 3] = v.w;
     }
     // keep the requests in stage order (vector loads return in order, and the first step waits
@@ -288,9 +302,9 @@ __device__ __forceinline__ void lds_get(const float *row, unsigned s, float (&x)
 // ---- group A: device memory -> stages -> LDS -----------------------------------------------
 // forward: eight shear stages (register digits 0..3, DPP digits 0..3 of layout L);
 // transposed: four shear stages (DPP digits 3..0 of layout H)
-template <bool TRN>
-__device__ __forceinline__ void stages_A(float (&x)[16], const float (&f)[TRN ? 4 : 8][16]) {
-  if (!TRN) {
+template <bool TRN, int LOGD = 12>
+__device__ __forceinline__ void stages_A(float (&x)[16], const float (&f)[TRN ? LOGD - 8 : 8][16]) {
+  if constexpr (!TRN) {
     reg_shear<0>(x, f[0]);
     reg_shear<1>(x, f[1]);
     reg_shear<2>(x, f[2]);
@@ -299,6 +313,10 @@ __device__ __forceinline__ void stages_A(float (&x)[16], const float (&f)[TRN ? 
     dpp_shear<1>(x, f[5]);
     dpp_shear<2>(x, f[6]);
     dpp_shear<3>(x, f[7]);
+  } else if constexpr (LOGD == 11) {
+    dpp_shear<2>(x, f[0]);
+    dpp_shear<1>(x, f[1]);
+    dpp_shear<0>(x, f[2]);
   } else {
     dpp_shear<3>(x, f[0]);
     dpp_shear<2>(x, f[1]);
@@ -310,15 +328,16 @@ __device__ __forceinline__ void stages_A(float (&x)[16], const float (&f)[TRN ? 
 // PF = pairs of rows requested ahead of the one being computed
 // Et (block-scaled half rows only): exponent byte of the chunk's first segment in the tile's
 // first row; the rows' exponents are 2 ldx bytes apart.
-template <typename TI, bool TRN, int PF>
+template <typename TI, bool TRN, int PF, int LOGD = 12>
 __device__ __forceinline__ void group_A(const float *__restrict__ img, int t, float *buf,
                                          const TI *__restrict__ Xt, int64_t ldx, int nr,
                                          const uint8_t *__restrict__ Et) {
-  constexpr int NS = TRN ? 4 : 8;
+  constexpr int NS = TRN ? LOGD - 8 : 8;
+  constexpr int kRowBuf = Geo<LOGD>::ROWBUF;
   using In = Seg16<TI>;
   constexpr int NRAW = In::NRAW;
   constexpr bool kZ = std::is_same<TI, zh16>::value;
-  const unsigned s = seg_of(TRN, (unsigned)t >> 6, (unsigned)t & 63u);
+  const unsigned s = seg_of<LOGD>(TRN, (unsigned)t >> 6, (unsigned)t & 63u);
   const TI *xp = Xt + 16u * s;
   const int last = nr - 1;
   // rows past the end of the tile read its last row again (same address, nothing depends on it),
@@ -333,7 +352,7 @@ __device__ __forceinline__ void group_A(const float *__restrict__ img, int t, fl
   load_row(1, pre[1]);
   __builtin_amdgcn_sched_barrier(0);
   float f[NS][16];
-  load_params<NS>(img, t, f);
+  load_params<NS, Geo<LOGD>::TG>(img, t, f);
 #pragma unroll
   for (int q = 1; q < PF; ++q) {
     load_row(2 * q, pre[2 * q]);
@@ -347,9 +366,9 @@ __device__ __forceinline__ void group_A(const float *__restrict__ img, int t, fl
     load_row(2 * (k + PF), pre[2 * q]);
     load_row(2 * (k + PF) + 1, pre[2 * q + 1]);
     float *b = buf + (k & 1) * (2 * kRowBuf);
-    stages_A<TRN>(xa, f);
+    stages_A<TRN, LOGD>(xa, f);
     lds_put(b, s, xa);
-    stages_A<TRN>(xb, f);
+    stages_A<TRN, LOGD>(xb, f);
     lds_put(b + kRowBuf, s, xb);
   };
   // The first PF steps stand outside the loop: straight-line code after the loads above, in
@@ -376,16 +395,21 @@ __device__ __forceinline__ void group_A(const float *__restrict__ img, int t, fl
 // forward: DPP digits 0..3 of layout H (the last one dense with LD); transposed: DPP digits
 // 3..0 of layout L, then register digits 3..0 (the last one dense; a transposed program
 // always ends inside the chunk)
-template <bool TRN, bool LD>
+template <bool TRN, bool LD, int LOGD = 12>
 struct ParamsB {
-  static constexpr int NS = (TRN ? 8 : 4) - (LD ? 1 : 0);
+  static constexpr int NS = (TRN ? 8 : LOGD - 8) - (LD ? 1 : 0);
   float f[NS][16];
   float md[2][16];            // dense stage (LD only): own-coordinate and partner factors
 };
 
-template <bool TRN, bool LD>
-__device__ __forceinline__ void stages_B(float (&x)[16], const ParamsB<TRN, LD> &pb) {
-  if (!TRN) {
+template <bool TRN, bool LD, int LOGD = 12>
+__device__ __forceinline__ void stages_B(float (&x)[16], const ParamsB<TRN, LD, LOGD> &pb) {
+  if constexpr (!TRN && LOGD == 11) {
+    dpp_shear<0>(x, pb.f[0]);
+    dpp_shear<1>(x, pb.f[1]);
+    if constexpr (LD) dpp_dense<2>(x, pb.md[0], pb.md[1]);
+    else dpp_shear<2>(x, pb.f[2]);
+  } else if constexpr (!TRN) {
     dpp_shear<0>(x, pb.f[0]);
     dpp_shear<1>(x, pb.f[1]);
     dpp_shear<2>(x, pb.f[2]);
@@ -404,21 +428,22 @@ __device__ __forceinline__ void stages_B(float (&x)[16], const ParamsB<TRN, LD> 
   }
 }
 
-template <typename TO, bool TRN, bool LD>
+template <typename TO, bool TRN, bool LD, int LOGD = 12>
 __device__ __forceinline__ void group_B(const float *__restrict__ img, int t, const float *buf,
                                          TO *__restrict__ Yt, int64_t ldy, int nr,
                                          uint8_t *__restrict__ Et) {
   using Out = Seg16<TO>;
   constexpr bool kZ = std::is_same<TO, zh16>::value;
-  using PB = ParamsB<TRN, LD>;
-  const unsigned s = seg_of(!TRN, (unsigned)t >> 6, (unsigned)t & 63u);
+  constexpr int kRowBuf = Geo<LOGD>::ROWBUF, kTG = Geo<LOGD>::TG;
+  using PB = ParamsB<TRN, LD, LOGD>;
+  const unsigned s = seg_of<LOGD>(!TRN, (unsigned)t >> 6, (unsigned)t & 63u);
   TO *yp = Yt + 16u * s;
   PB pb;
   // Group A's requests go first: this group needs its parameters one step later, and both share
   // the compute unit's one load path.
   __builtin_amdgcn_s_sleep(kSleepB);
-  load_params<PB::NS>(img, t, pb.f);
-  if constexpr (LD) load_params<2>(img + PB::NS * 16 * kTG, t, pb.md);
+  load_params<PB::NS, kTG>(img, t, pb.f);
+  if constexpr (LD) load_params<2, kTG>(img + PB::NS * 16 * kTG, t, pb.md);
   const int npairs = (nr + 1) >> 1;
   auto step = [&](int k) {
     const float *b = buf + ((k - 1) & 1) * (2 * kRowBuf);
@@ -426,10 +451,10 @@ __device__ __forceinline__ void group_B(const float *__restrict__ img, int t, co
     float xa[16], xb[16];
     lds_get(b, s, xa);
     lds_get(b + kRowBuf, s, xb);
-    stages_B<TRN, LD>(xa, pb);
+    stages_B<TRN, LD, LOGD>(xa, pb);
     if constexpr (kZ) Out::store(yp + (int64_t)r0 * ldy, Et + (int64_t)r0 * (2 * ldy) + s, xa);
     else Out::store(yp + (int64_t)r0 * ldy, xa);
-    stages_B<TRN, LD>(xb, pb);
+    stages_B<TRN, LD, LOGD>(xb, pb);
     if (r0 + 1 < nr) {
       if constexpr (kZ) Out::store(yp + (int64_t)(r0 + 1) * ldy, Et + (int64_t)(r0 + 1) * (2 * ldy) + s, xb);
       else Out::store(yp + (int64_t)(r0 + 1) * ldy, xb);
@@ -450,14 +475,15 @@ __device__ __forceinline__ void group_B(const float *__restrict__ img, int t, co
 
 // Workgroup -> (chunk kch, tile of R rows).  imgA / imgB: the two groups' parameter images of
 // chunk 0; chunk kch's follow at kch * strideA / strideB floats.
-template <typename TI, typename TO, bool TRN, bool LD>
-__global__ __launch_bounds__(2 * kTG) void harp_dpp_kernel(const TI *__restrict__ X, int64_t ldx,
+template <typename TI, typename TO, bool TRN, bool LD, int LOGD = 12>
+__global__ __launch_bounds__(2 * Geo<LOGD>::TG) void harp_dpp_kernel(const TI *__restrict__ X, int64_t ldx,
                                                            TO *__restrict__ Y, int64_t ldy,
                                                            int64_t n, int R, int nchunk,
                                                            const float *__restrict__ imgA,
                                                            const float *__restrict__ imgB,
                                                            int64_t strideA, int64_t strideB) {
-  __shared__ float buf[4 * kRowBuf];
+  constexpr int kD = Geo<LOGD>::D, kTG = Geo<LOGD>::TG;
+  __shared__ float buf[4 * Geo<LOGD>::ROWBUF];
   const int g = __builtin_amdgcn_readfirstlane((int)threadIdx.x / kTG);   // wave-uniform
   const int t = (int)threadIdx.x % kTG;
   const int kch = (int)(blockIdx.x % (unsigned)nchunk);
@@ -466,11 +492,11 @@ __global__ __launch_bounds__(2 * kTG) void harp_dpp_kernel(const TI *__restrict_
   // block-scaled half rows: d halves, then the row's exponent bytes (one per 16 coordinates)
   const int64_t d = (int64_t)nchunk * kD;
   if (g == 0)
-    group_A<TI, TRN, kPrefetchPairs>(imgA + kch * strideA, t, buf, X + row0 * ldx + (int64_t)kch * kD, ldx, nr,
-                                     reinterpret_cast<const uint8_t *>(X + row0 * ldx + d) + kch * (kD / 16));
+    group_A<TI, TRN, kPrefetchPairs, LOGD>(imgA + kch * strideA, t, buf, X + row0 * ldx + (int64_t)kch * kD, ldx, nr,
+                                           reinterpret_cast<const uint8_t *>(X + row0 * ldx + d) + kch * (kD / 16));
   else
-    group_B<TO, TRN, LD>(imgB + kch * strideB, t, buf, Y + row0 * ldy + (int64_t)kch * kD, ldy, nr,
-                         reinterpret_cast<uint8_t *>(Y + row0 * ldy + d) + kch * (kD / 16));
+    group_B<TO, TRN, LD, LOGD>(imgB + kch * strideB, t, buf, Y + row0 * ldy + (int64_t)kch * kD, ldy, nr,
+                               reinterpret_cast<uint8_t *>(Y + row0 * ldy + d) + kch * (kD / 16));
 }
 
 // ------------------------------------------------------------------------------------------
@@ -580,15 +606,15 @@ __global__ __launch_bounds__(2 * kTG) void harp_dpp_top_kernel(const uint16_t *_
                                   Y + row0 * ldy + (int64_t)kch * kD, ldy, nr, nullptr);
 }
 
-template <typename TI, typename TO>
+template <typename TI, typename TO, int LOGD = 12>
 harp_status_t launch_dpp_io(const DppImage &di, const void *X, int64_t ldx, void *Y, int64_t ldy,
                             int64_t n, int R, int nchunk, hipStream_t stream) {
   const int64_t tiles = ((n + R - 1) / R) * nchunk;
   if (tiles > 0x7fffffff) return HARP_ERR_UNSUPPORTED;
-  const dim3 grid((unsigned)tiles), block(2 * kTG);
+  const dim3 grid((unsigned)tiles), block(2 * Geo<LOGD>::TG);
   const float *a = di.img, *b = di.img + di.offB;
-#define HARP_DPP_LAUNCH(TRN_, LD_)                                                              \
-  hipLaunchKernelGGL((harp_dpp_kernel<TI, TO, TRN_, LD_>), grid, block, 0, stream, (const TI *)X, \
+#define HARP_DPP_LAUNCH(TRN_, LD_)                                                                    \
+  hipLaunchKernelGGL((harp_dpp_kernel<TI, TO, TRN_, LD_, LOGD>), grid, block, 0, stream, (const TI *)X, \
                      ldx, (TO *)Y, ldy, n, R, nchunk, a, b, di.strideA, di.strideB)
   if (di.trn) {
     if (!di.ld) return HARP_ERR_UNSUPPORTED;
@@ -605,16 +631,19 @@ harp_status_t launch_dpp_io(const DppImage &di, const void *X, int64_t ldx, void
 }  // namespace
 
 // Thread (group, t) of the kernel owns this segment; the plan builder lays the image out with it.
-unsigned dpp_segment_of(bool high_layout, unsigned t) {
+unsigned dpp_segment_of(bool high_layout, unsigned t, int logd) {
   const unsigned w = t >> 6, l = t & 63u;
   const unsigned low4 = l & 15u;
   const unsigned e = low4 ^ (((low4 >> 2) & 1u) * 3u);
+  if (logd == 11)
+    return high_layout ? ((e >> 3) | ((l >> 4) << 1) | (w << 3) | ((e & 7u) << 4))
+                       : (e | ((l >> 4) << 4) | (w << 6));
   return high_layout ? ((l >> 4) | (w << 2) | (e << 4)) : (e | ((l >> 4) << 4) | (w << 6));
 }
 
 bool dpp_supported(const harp_plan *plan, const DppImage &di, int chunk, const void *X, int64_t ldx,
                    harp_dtype_t dt_in, const void *Y, int64_t ldy, harp_dtype_t dt_out) {
-  if (plan->algo == HARP_ALGO_GENERIC || !di.img || chunk != kD) return false;
+  if (plan->algo == HARP_ALGO_GENERIC || !di.img || chunk != (1 << di.logd)) return false;
   // bf16 rows on both sides only: a thread's 16 float32 coordinates are four 16-byte pieces 64
   // bytes apart from its neighbours', the one slow access pattern of this chip (measured:
   // float32 rows 18.2 -> 21.7 us, the float32 intermediate of a 28672-wide split program
@@ -633,7 +662,16 @@ bool dpp_supported(const harp_plan *plan, const DppImage &di, int chunk, const v
 harp_status_t launch_dpp_kernel(const harp_plan *plan, const DppImage &di, const void *X,
                                 int64_t ldx, harp_dtype_t dt_in, void *Y, int64_t ldy,
                                 harp_dtype_t dt_out, int64_t n, int R, hipStream_t stream) {
-  const int nchunk = (int)(plan->d / kD);
+  const int nchunk = (int)(plan->d >> di.logd);
+  if (di.logd == 11) {
+    if (dt_in == HARP_BF16 && dt_out == HARP_BF16)
+      return launch_dpp_io<uint16_t, uint16_t, 11>(di, X, ldx, Y, ldy, n, R, nchunk, stream);
+    if (dt_in == HARP_BF16 && (int)dt_out == kDtZ16 && !di.trn && di.ld)
+      return launch_dpp_io<uint16_t, zh16, 11>(di, X, ldx, Y, ldy, n, R, nchunk, stream);
+    if ((int)dt_in == kDtZ16 && dt_out == HARP_BF16 && di.trn)
+      return launch_dpp_io<zh16, uint16_t, 11>(di, X, ldx, Y, ldy, n, R, nchunk, stream);
+    return HARP_ERR_UNSUPPORTED;
+  }
   if (dt_in == HARP_BF16 && dt_out == HARP_BF16)
     return launch_dpp_io<uint16_t, uint16_t>(di, X, ldx, Y, ldy, n, R, nchunk, stream);
   if (dt_in == HARP_BF16 && (int)dt_out == kDtZ16 && !di.trn && di.ld)
@@ -645,7 +683,8 @@ harp_status_t launch_dpp_kernel(const harp_plan *plan, const DppImage &di, const
 
 bool dpp_top_supported(const harp_plan *plan, const DppImage &di, const void *X, int64_t ldx,
                        harp_dtype_t dt_in, const void *Y, int64_t ldy, harp_dtype_t dt_out) {
-  if (plan->algo == HARP_ALGO_GENERIC || !di.img || di.topB == 0 || !di.trn || !di.ld) return false;
+  if (plan->algo == HARP_ALGO_GENERIC || !di.img || di.topB == 0 || !di.trn || !di.ld || di.logd != 12)
+    return false;
   if (dt_in != HARP_BF16 || dt_out != HARP_BF16) return false;
   if ((ldx % 8) || (ldy % 8) || ((uintptr_t)X % 16) || ((uintptr_t)Y % 16)) return false;
   // the groups read every chunk of a row before the last one of it is written, but a workgroup

@@ -90,6 +90,7 @@ struct DppImage {
   int64_t offB = 0;             // group B's part starts here (floats)
   int64_t strideA = 0, strideB = 0;   // floats per chunk
   bool trn = false, ld = false;
+  int32_t logd = 12;            // log2 of the chunk: 12, or 11 (eleven stages, 128 threads per group)
   // transposed split program whose streamed stage (dense, radix topB = 3 or 5, on the digit
   // above the chunk) is executed on the way in (harp_dpp_top_kernel): its factors per output
   // chunk kch, input chunk j, piece k, thread t at offT + (((kch * topB + j) * 4 + k) * 256 + t) * 4
@@ -273,7 +274,7 @@ harp_status_t launch_pipe_kernel(const harp_plan *plan, const HostProgram &hp, i
                                  int64_t ldy, harp_dtype_t dt_out, int64_t n, int rows_per_tile,
                                  hipStream_t stream);
 // two-group DPP kernel for radix-2 chains in the two-shear form on chunks of 4096 (harp_dpp.hip)
-unsigned dpp_segment_of(bool high_layout, unsigned t);
+unsigned dpp_segment_of(bool high_layout, unsigned t, int logd = 12);
 bool dpp_supported(const harp_plan *plan, const DppImage &di, int chunk, const void *X, int64_t ldx,
                    harp_dtype_t dt_in, const void *Y, int64_t ldy, harp_dtype_t dt_out);
 harp_status_t launch_dpp_kernel(const harp_plan *plan, const DppImage &di, const void *X,

@@ -268,13 +268,15 @@ def test_pipelined_radix2_kernel_4096(harp, n, rows, with_signs):
 
 
 @pytest.mark.parametrize("d,dtype,n", [(2048, "bf16", 45), (2048, "f32", 19), (4096, "f32", 33),
-                                       (2048, "bf16", 1), (4096, "f32", 2)])
+                                       (2048, "bf16", 1), (4096, "f32", 2), (2048, "bf16", 1031),
+                                       (2048, "bf16", 2)])
 def test_pipelined_kernel_other_sizes_and_types(harp, d, dtype, n):
     radices = [2] * int(np.log2(d))
     rng = np.random.default_rng(d + n)
     plan = harp.Plan(d, radices, gi.make_blocks(d, radices, "orth", rng))
-    # 4096: two wave groups with in-wave (DPP) digit exchanges; 2048: three wave groups
-    assert plan.kernel_name() == ("dpp_radix2" if d == 4096 else "pipe_radix2")
+    # bf16 rows: two wave groups with in-wave (DPP) digit exchanges; float32 rows: three groups
+    assert plan.kernel_name(n, harp.HARP_BF16) == "dpp_radix2"
+    assert plan.kernel_name(n, harp.HARP_F32) == "pipe_radix2"
     plan.destroy()
     run_case(harp, d, radices, n, dtype, seed=d + n)
 
@@ -477,6 +479,7 @@ def test_chunk_of_a_llama13b_ffn_row_ends_behind_its_radix2_stages(harp):
 @pytest.mark.parametrize("d,radices", [
     (12288, [2] * 12 + [3]),      # DPP kernel on chunks of 4096 + streamed radix 3
     (28672, [2] * 12 + [7]),      # ... + streamed radix 7
+    (14336, [2] * 11 + [7]),      # DPP kernel on chunks of 2048 + streamed radix 7
     (5120, [2] * 10 + [5]),       # wave kernel on chunks of 1024 + streamed radix 5
     (7168, [2] * 10 + [7]),       # wave kernel on chunks of 1024 + streamed radix 7
     (2048 * 3, [2] * 9 + [4, 3]), # two streamed stages: keeps the float32 intermediate
