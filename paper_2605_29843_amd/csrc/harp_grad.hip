@@ -256,9 +256,63 @@ __device__ __forceinline__ void grad_run_blocks(const GradRun &run, int base, in
   (void)D;
 }
 
-template <int K>
+// The E coordinates x[e s] of an item, float32 or bf16 (the caller's own rows in the first and
+// last run, so that no separate conversion pass is needed); vec: stride 1 and aligned rows, the
+// item is contiguous and moves with 16-byte accesses.
+template <int E, typename T>
+__device__ __forceinline__ void grad_load_item(const T *x, int s, bool vec, float (&v)[E]) {
+  if (vec) {
+    if constexpr (sizeof(T) == 4) {
+#pragma unroll
+      for (int q = 0; q < E / 4; ++q) {
+        const float4 f = *reinterpret_cast<const float4 *>(x + 4 * q);
+        v[4 * q] = f.x; v[4 * q + 1] = f.y; v[4 * q + 2] = f.z; v[4 * q + 3] = f.w;
+      }
+    } else if constexpr (E == 8) {
+      const uint4 r = *reinterpret_cast<const uint4 *>(x);
+      const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        v[2 * i] = __uint_as_float(w[i] << 16);
+        v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+      }
+    } else {
+      const uint2 r = *reinterpret_cast<const uint2 *>(x);
+      v[0] = __uint_as_float(r.x << 16); v[1] = __uint_as_float(r.x & 0xffff0000u);
+      v[2] = __uint_as_float(r.y << 16); v[3] = __uint_as_float(r.y & 0xffff0000u);
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < E; ++e) v[e] = grad_widen(x[(size_t)e * s]);
+  }
+}
+template <int E, typename T>
+__device__ __forceinline__ void grad_store_item(T *y, int s, bool vec, const float (&v)[E]) {
+  if (vec) {
+    if constexpr (sizeof(T) == 4) {
+#pragma unroll
+      for (int q = 0; q < E / 4; ++q)
+        *reinterpret_cast<float4 *>(y + 4 * q) = make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
+    } else {
+      uint16_t h[E];
+#pragma unroll
+      for (int e = 0; e < E; ++e) grad_narrow(v[e], &h[e]);
+      if constexpr (E == 8)
+        *reinterpret_cast<uint4 *>(y) = make_uint4(h[0] | ((uint32_t)h[1] << 16), h[2] | ((uint32_t)h[3] << 16),
+                                                    h[4] | ((uint32_t)h[5] << 16), h[6] | ((uint32_t)h[7] << 16));
+      else
+        *reinterpret_cast<uint2 *>(y) = make_uint2(h[0] | ((uint32_t)h[1] << 16), h[2] | ((uint32_t)h[3] << 16));
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < E; ++e) grad_narrow(v[e], y + (size_t)e * s);
+  }
+}
+
+// TX: element type of the run's input rows (leading dimension ldx)
+template <int K, typename TX = float>
 __global__ __launch_bounds__(kGradThreads) void harp_grad_fwd_run_kernel(
-    const float *__restrict__ X, float *__restrict__ Y, int64_t ld, int64_t n, int rows,
+    const TX *__restrict__ X, int64_t ldx, float *__restrict__ Y, int64_t ld, int64_t n, int rows,
     GradRun run, int nitems, int s, int aligned) {
   constexpr int E = 1 << K, H = E / 2;
   const int q = blockIdx.x * kGradThreads + threadIdx.x;
@@ -272,28 +326,18 @@ __global__ __launch_bounds__(kGradThreads) void harp_grad_fwd_run_kernel(
   // the next row is requested before the work on the current one
   // stride 1: the item's coordinates are contiguous (16-byte accesses when the row allows it)
   const bool vec = aligned && (s == 1) && (E % 4 == 0) && (ld % 4 == 0);
-  auto load_item = [&](const float *x, float (&v)[E]) {
-    if (vec) {
-#pragma unroll
-      for (int q = 0; q < E / 4; ++q) {
-        const float4 f = *reinterpret_cast<const float4 *>(x + 4 * q);
-        v[4 * q] = f.x; v[4 * q + 1] = f.y; v[4 * q + 2] = f.z; v[4 * q + 3] = f.w;
-      }
-    } else {
-#pragma unroll
-      for (int e = 0; e < E; ++e) v[e] = x[(size_t)e * s];
-    }
-  };
+  const bool vecx = vec && ldx % (16 / (int)sizeof(TX)) == 0 && (uintptr_t)X % 16 == 0;
+  auto load_item = [&](const TX *x, float (&v)[E]) { grad_load_item<E, TX>(x, s, vecx, v); };
   float nx[E];
 #pragma unroll
   for (int e = 0; e < E; ++e) nx[e] = 0.f;
-  if (r0 < r1) load_item(X + r0 * ld + base, nx);
+  if (r0 < r1) load_item(X + r0 * ldx + base, nx);
   for (int64_t row = r0; row < r1; ++row) {
     float *y = Y + row * ld + base;
     float v[E];
 #pragma unroll
     for (int e = 0; e < E; ++e) v[e] = nx[e];
-    if (row + 1 < r1) load_item(X + (row + 1) * ld + base, nx);
+    if (row + 1 < r1) load_item(X + (row + 1) * ldx + base, nx);
 #pragma unroll
     for (int i = 0; i < K; ++i)
 #pragma unroll
@@ -316,11 +360,15 @@ __global__ __launch_bounds__(kGradThreads) void harp_grad_fwd_run_kernel(
 }
 
 // partial sums of sub-stage i go to partial[i * pstride + (chunk * 4 + v) * D + c], D = d / 2
-template <int K>
+// TX: element type of the run's input rows X; the gradient is read from Gin (TGI) and the
+// gradient passed back is written to Gout (TGO): the same float32 matrix in place, or the
+// caller's G on the way in (last run) and the caller's dX on the way out (first run).  A thread
+// reads its item of a row before it writes it, and no other thread touches that item.
+template <int K, typename TX = float, typename TGI = float, typename TGO = float>
 __global__ __launch_bounds__(kGradThreads) void harp_grad_bwd_run_kernel(
-    const float *__restrict__ X, float *__restrict__ Gm, int64_t ld, int64_t n, int rows,
-    GradRun run, int nitems, int s, int D, float *__restrict__ partial, size_t pstride,
-    int aligned) {
+    const TX *__restrict__ X, int64_t ldx, const TGI *Gin, int64_t ldgi, TGO *Gout, int64_t ldgo,
+    int64_t ld, int64_t n, int rows, GradRun run, int nitems, int s, int D,
+    float *__restrict__ partial, size_t pstride, int aligned) {
   constexpr int E = 1 << K, H = E / 2;
   const int q = blockIdx.x * kGradThreads + threadIdx.x;
   if (q >= nitems) return;
@@ -337,27 +385,18 @@ __global__ __launch_bounds__(kGradThreads) void harp_grad_bwd_run_kernel(
   const int64_t r0 = (int64_t)blockIdx.y * rows;
   const int64_t r1 = (r0 + rows < n) ? r0 + rows : n;
   const bool vec = aligned && (s == 1) && (E % 4 == 0) && (ld % 4 == 0);
-  auto load_item = [&](const float *x, float (&v)[E]) {
-    if (vec) {
-#pragma unroll
-      for (int q = 0; q < E / 4; ++q) {
-        const float4 f = *reinterpret_cast<const float4 *>(x + 4 * q);
-        v[4 * q] = f.x; v[4 * q + 1] = f.y; v[4 * q + 2] = f.z; v[4 * q + 3] = f.w;
-      }
-    } else {
-#pragma unroll
-      for (int e = 0; e < E; ++e) v[e] = x[(size_t)e * s];
-    }
-  };
+  const bool vecx = vec && ldx % (16 / (int)sizeof(TX)) == 0 && (uintptr_t)X % 16 == 0;
+  const bool vecgi = vec && ldgi % (16 / (int)sizeof(TGI)) == 0 && (uintptr_t)Gin % 16 == 0;
+  const bool vecgo = vec && ldgo % (16 / (int)sizeof(TGO)) == 0 && (uintptr_t)Gout % 16 == 0;
   float nx[E], ng[E];
 #pragma unroll
   for (int e = 0; e < E; ++e) nx[e] = ng[e] = 0.f;
   if (r0 < r1) {
-    load_item(X + r0 * ld + base, nx);
-    load_item(Gm + r0 * ld + base, ng);
+    grad_load_item<E, TX>(X + r0 * ldx + base, s, vecx, nx);
+    grad_load_item<E, TGI>(Gin + r0 * ldgi + base, s, vecgi, ng);
   }
   for (int64_t row = r0; row < r1; ++row) {
-    float *g = Gm + row * ld + base;
+    TGO *g = Gout + row * ldgo + base;
     float xs[K][E], gv[E];
 #pragma unroll
     for (int e = 0; e < E; ++e) {
@@ -365,8 +404,8 @@ __global__ __launch_bounds__(kGradThreads) void harp_grad_bwd_run_kernel(
       gv[e] = ng[e];
     }
     if (row + 1 < r1) {   // the next row (its g is not written by anyone before this thread does)
-      load_item(X + (row + 1) * ld + base, nx);
-      load_item(Gm + (row + 1) * ld + base, ng);
+      grad_load_item<E, TX>(X + (row + 1) * ldx + base, s, vecx, nx);
+      grad_load_item<E, TGI>(Gin + (row + 1) * ldgi + base, s, vecgi, ng);
     }
     // inputs of the inner stages, recomputed
 #pragma unroll
@@ -395,15 +434,7 @@ __global__ __launch_bounds__(kGradThreads) void harp_grad_bwd_run_kernel(
         gv[e1] = fmaf(g1, kv[i][p][3], g0 * kv[i][p][2]);
       }
     }
-    if (vec) {
-#pragma unroll
-      for (int q = 0; q < E / 4; ++q)
-        *reinterpret_cast<float4 *>(g + 4 * q) =
-            make_float4(gv[4 * q], gv[4 * q + 1], gv[4 * q + 2], gv[4 * q + 3]);
-    } else {
-#pragma unroll
-      for (int e = 0; e < E; ++e) g[(size_t)e * s] = gv[e];
-    }
+    grad_store_item<E, TGO>(g, s, vecgo, gv);
   }
 #pragma unroll
   for (int i = 0; i < K; ++i)
@@ -418,10 +449,18 @@ __global__ __launch_bounds__(kGradThreads) void harp_grad_bwd_run_kernel(
 // threads per value each add a contiguous eighth of the chunks (ascending), then the eight
 // sums are added in ascending order.  For stage 0 the image holds diag(sigma) K_0, so row r of
 // its gradient takes the sign of coordinate c b + r.
+// blockIdx.y = sub-stage of a run (its partial sums start pstride floats further on).
+struct GradReduceOut {
+  float *dK[3];
+  const int8_t *signs[3];
+};
 __global__ __launch_bounds__(kGradThreads) void harp_grad_reduce_kernel(
-    const float *__restrict__ partial, int nchunks, int D, int b, const int8_t *__restrict__ signs,
-    float *__restrict__ dK) {
+    const float *__restrict__ partial_all, size_t pstride, int nchunks, int D, int b,
+    GradReduceOut out) {
   __shared__ float part[8][32];
+  const float *__restrict__ partial = partial_all + (size_t)blockIdx.y * pstride;
+  const int8_t *__restrict__ signs = out.signs[blockIdx.y];
+  float *__restrict__ dK = out.dK[blockIdx.y];
   const int bb = b * b;
   const int64_t total = (int64_t)D * bb;
   const int lane = threadIdx.x & 31, slice = threadIdx.x >> 5;
@@ -576,13 +615,19 @@ harp_status_t launch_grad(const harp_plan *plan, const void *X, int64_t ldx, con
     for (int i = 0; i < 3; ++i) run.blocks[i] = stages[sg.t0 + std::min(i, sg.k - 1)].blocks;
     return run;
   };
+  // A run of radix-2 stages at the start reads the caller's X itself (forward and backward), one
+  // at the end reads the caller's G, and the first run writes dX: no separate conversion pass.
+  const bool bf = (dt == HARP_BF16);
+  const bool first_run = seg[0].k > 1, last_run = seg[nseg - 1].k > 1;
+  const bool dx_direct = first_run && dX != nullptr;
   if (n > 0) {
-    if (dt == HARP_BF16) {
-      launch_convert((const uint16_t *)X, ldx, act, d, n, d, st);
-      launch_convert((const uint16_t *)G, ldg, g, d, n, d, st);
-    } else {
-      launch_convert((const float *)X, ldx, act, d, n, d, st);
-      launch_convert((const float *)G, ldg, g, d, n, d, st);
+    if (!first_run) {
+      if (bf) launch_convert((const uint16_t *)X, ldx, act, d, n, d, st);
+      else launch_convert((const float *)X, ldx, act, d, n, d, st);
+    }
+    if (!last_run) {
+      if (bf) launch_convert((const uint16_t *)G, ldg, g, d, n, d, st);
+      else launch_convert((const float *)G, ldg, g, d, n, d, st);
     }
     for (int i = 0; i + 1 < nseg; ++i) {
       const ColStage &cs = stages[seg[i].t0];
@@ -591,12 +636,23 @@ harp_status_t launch_grad(const harp_plan *plan, const void *X, int64_t ldx, con
       if (seg[i].k > 1) {
         const int nitems = (int)(d >> seg[i].k);
         const dim3 grid((nitems + kGradThreads - 1) / kGradThreads, nchunks);
-        if (seg[i].k == 3)
-          hipLaunchKernelGGL((harp_grad_fwd_run_kernel<3>), grid, dim3(kGradThreads), 0, st, in, out,
-                             d, n, rows, run_of(seg[i]), nitems, cs.s, aligned);
-        else
-          hipLaunchKernelGGL((harp_grad_fwd_run_kernel<2>), grid, dim3(kGradThreads), 0, st, in, out,
-                             d, n, rows, run_of(seg[i]), nitems, cs.s, aligned);
+#define HARP_GRAD_FWD_RUN(KK)                                                                       \
+  do {                                                                                              \
+    if (i == 0 && bf)                                                                               \
+      hipLaunchKernelGGL((harp_grad_fwd_run_kernel<KK, uint16_t>), grid, dim3(kGradThreads), 0, st, \
+                         (const uint16_t *)X, ldx, out, d, n, rows, run_of(seg[i]), nitems, cs.s,   \
+                         aligned);                                                                  \
+    else if (i == 0)                                                                                \
+      hipLaunchKernelGGL((harp_grad_fwd_run_kernel<KK, float>), grid, dim3(kGradThreads), 0, st,    \
+                         (const float *)X, ldx, out, d, n, rows, run_of(seg[i]), nitems, cs.s,      \
+                         aligned);                                                                  \
+    else                                                                                            \
+      hipLaunchKernelGGL((harp_grad_fwd_run_kernel<KK, float>), grid, dim3(kGradThreads), 0, st,    \
+                         in, d, out, d, n, rows, run_of(seg[i]), nitems, cs.s, aligned);            \
+  } while (0)
+        if (seg[i].k == 3) HARP_GRAD_FWD_RUN(3);
+        else HARP_GRAD_FWD_RUN(2);
+#undef HARP_GRAD_FWD_RUN
       } else if (cs.b > 8) {
         const int D = (int)(d / cs.b);
 #define HARP_GRAD_BIG_FWD(BM)                                                                     \
@@ -620,12 +676,28 @@ harp_status_t launch_grad(const harp_plan *plan, const void *X, int64_t ldx, con
       if (seg[i].k > 1) {
         const int nitems = (int)(d >> seg[i].k);
         const dim3 grid((nitems + kGradThreads - 1) / kGradThreads, nchunks);
-        if (seg[i].k == 3)
-          hipLaunchKernelGGL((harp_grad_bwd_run_kernel<3>), grid, dim3(kGradThreads), 0, st, in, g, d,
-                             n, rows, run_of(seg[i]), nitems, cs.s, (int)(d / 2), partial, pstride, aligned);
-        else
-          hipLaunchKernelGGL((harp_grad_bwd_run_kernel<2>), grid, dim3(kGradThreads), 0, st, in, g, d,
-                             n, rows, run_of(seg[i]), nitems, cs.s, (int)(d / 2), partial, pstride, aligned);
+        // what this run reads and writes: the caller's rows at either end, float32 copies between
+        const bool xc = (i == 0), gic = (i == nseg - 1), goc = (i == 0) && dx_direct;
+#define HARP_GRAD_BWD_RUN(KK, TX_, TGI_, TGO_)                                                       \
+  hipLaunchKernelGGL((harp_grad_bwd_run_kernel<KK, TX_, TGI_, TGO_>), grid, dim3(kGradThreads), 0,   \
+                     st, xc ? (const TX_ *)X : (const TX_ *)in, xc ? ldx : d,                        \
+                     gic ? (const TGI_ *)G : (const TGI_ *)g, gic ? ldg : d,                         \
+                     goc ? (TGO_ *)dX : (TGO_ *)g, goc ? lddx : d, d, n, rows, run_of(seg[i]),      \
+                     nitems, cs.s, (int)(d / 2), partial, pstride, aligned)
+#define HARP_GRAD_BWD_TYPES(KK)                                                          \
+  do {                                                                                   \
+    if (!bf) HARP_GRAD_BWD_RUN(KK, float, float, float);                                 \
+    else if (xc && gic && goc) HARP_GRAD_BWD_RUN(KK, uint16_t, uint16_t, uint16_t);      \
+    else if (xc && gic) HARP_GRAD_BWD_RUN(KK, uint16_t, uint16_t, float);                \
+    else if (xc && goc) HARP_GRAD_BWD_RUN(KK, uint16_t, float, uint16_t);                \
+    else if (xc) HARP_GRAD_BWD_RUN(KK, uint16_t, float, float);                          \
+    else if (gic) HARP_GRAD_BWD_RUN(KK, float, uint16_t, float);                         \
+    else HARP_GRAD_BWD_RUN(KK, float, float, float);                                     \
+  } while (0)
+        if (seg[i].k == 3) HARP_GRAD_BWD_TYPES(3);
+        else HARP_GRAD_BWD_TYPES(2);
+#undef HARP_GRAD_BWD_TYPES
+#undef HARP_GRAD_BWD_RUN
       } else if (cs.b > 8) {
         const int D = (int)(d / cs.b);
         const dim3 grid((D + 63) / 64, nchunks_big, (cs.b + 3) / 4);
@@ -644,20 +716,23 @@ harp_status_t launch_grad(const harp_plan *plan, const void *X, int64_t ldx, con
 #undef HARP_GRAD_BWD
       }
     }
-    for (int j = 0; j < seg[i].k; ++j) {
-      const int t = seg[i].t0 + j;
-      const int b = stages[t].b;
+    // the run's sub-stages in one reduction launch
+    {
+      const int b = stages[seg[i].t0].b;
       const int D = (int)(d / b);
       const int64_t total = (int64_t)D * b * b;
       const unsigned gx = (unsigned)std::min<int64_t>((total + 31) / 32, 8192);
-      hipLaunchKernelGGL(harp_grad_reduce_kernel, dim3(gx), dim3(kGradThreads), 0, st,
-                         partial + (size_t)j * pstride,
-                         n > 0 ? (b > 8 ? nchunks_big : nchunks) : 0, D, b,
-                         t == 0 ? plan->dev_signs : nullptr, dK[t]);
+      GradReduceOut ro{};
+      for (int j = 0; j < seg[i].k; ++j) {
+        ro.dK[j] = dK[seg[i].t0 + j];
+        ro.signs[j] = (seg[i].t0 + j == 0) ? plan->dev_signs : nullptr;
+      }
+      hipLaunchKernelGGL(harp_grad_reduce_kernel, dim3(gx, (unsigned)seg[i].k), dim3(kGradThreads), 0, st,
+                         partial, pstride, n > 0 ? (b > 8 ? nchunks_big : nchunks) : 0, D, b, ro);
     }
   }
-  if (dX && n > 0) {
-    if (dt == HARP_BF16) launch_convert(g, d, (uint16_t *)dX, lddx, n, d, st);
+  if (dX && n > 0 && !dx_direct) {
+    if (bf) launch_convert(g, d, (uint16_t *)dX, lddx, n, d, st);
     else launch_convert(g, d, (float *)dX, lddx, n, d, st);
   }
   return hipGetLastError() == hipSuccess ? HARP_OK : HARP_ERR_DEVICE;
