@@ -580,6 +580,8 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
     build_dpp_image(plan, eff, 0, dir, hp, image);
   if (algo == HARP_ALGO_FUSED && chunk == 2048 && tb == 11 && m == 11)
     build_dpp_image(plan, eff, 0, dir, hp, image, -1, 11);
+  if (algo == HARP_ALGO_FUSED && chunk == 1024 && tb == 10 && m == 10)
+    build_dpp_image(plan, eff, 0, dir, hp, image, -1, 10);
   // Split programs whose intermediate may travel as block-scaled halves: the chunks of 4096 of a
   // bf16 caller run on the DPP kernel too (a thread's 16 coordinates are one segment of that
   // format in both of its layouts).
@@ -588,6 +590,8 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
     build_dpp_image(plan, eff, dir == DIR_FWD ? 0 : 1, dir, hp, image, dir == DIR_FWD ? dense_t : -1);
   if (algo == HARP_ALGO_SPLIT && hp.z16 && chunk == 2048 && tb == 11 && m == 12)
     build_dpp_image(plan, eff, dir == DIR_FWD ? 0 : 1, dir, hp, image, dir == DIR_FWD ? dense_t : -1, 11);
+  if (algo == HARP_ALGO_SPLIT && hp.z16 && chunk == 1024 && tb == 10 && m == 11)
+    build_dpp_image(plan, eff, dir == DIR_FWD ? 0 : 1, dir, hp, image, dir == DIR_FWD ? dense_t : -1, 10);
   // Transposed split program of twelve radix-2 stages below one dense stage of radix 3 or 5
   // (12288, 20480; radix 7 measured no gain): that stage runs first and is executed by the DPP kernel's first
   // group on the way in (harp_dpp_top_kernel).  Its factors: for output chunk kch, input chunk
@@ -948,7 +952,8 @@ namespace harp {
 // otherwise several waves of nearly equal tiles.
 int choose_pipe_rows(const harp_plan *plan, int64_t n, int64_t nchunk, int chunk) {
   if (plan->rows_override > 0) return plan->rows_override;
-  const int64_t slots = (int64_t)(plan->num_cu > 0 ? plan->num_cu : 256) * (chunk <= 2048 ? 2 : 1);
+  const int64_t slots =
+      (int64_t)(plan->num_cu > 0 ? plan->num_cu : 256) * (chunk <= 1024 ? 4 : (chunk <= 2048 ? 2 : 1));
   const int64_t waves = (n * nchunk + slots * 32 - 1) / (slots * 32);
   int64_t per_chunk = (slots * waves) / nchunk;   // workgroups available to one chunk index
   if (per_chunk < 1) per_chunk = 1;
@@ -1557,7 +1562,10 @@ const char *harp_plan_kernel_name(const harp_plan_t *plan, int64_t n, harp_dtype
     const int p0 = hp->chunk_first ? 0 : hp->prog.npass - hp->n_chunk;
     // bf16 callers: the intermediate as block-scaled halves
     if (split_uses_z16(plan, *hp, nullptr, 8, dt, nullptr, 8, dt))
-      return hp->chunk >= 2048 ? "split_dpp_stream_h16" : "split_wave_stream_h16";
+      return dpp_supported(plan, hp->dpp, hp->chunk, nullptr, 8, hp->chunk_first ? dt : (harp_dtype_t)kDtZ16,
+                           nullptr, 8, hp->chunk_first ? (harp_dtype_t)kDtZ16 : dt)
+                 ? "split_dpp_stream_h16"
+                 : "split_wave_stream_h16";
     if (pipe_supported(plan, hp->prog, p0, hp->n_chunk, hp->chunk, nullptr, 8, nullptr, 8))
       return "split_pipe_stream";
     if (wave_supported(plan, hp->prog, p0, hp->n_chunk, hp->chunk, nullptr, 8, nullptr, 8))

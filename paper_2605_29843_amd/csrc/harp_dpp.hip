@@ -48,7 +48,8 @@ constexpr int kRowBuf = (kD / 256) * kPlane;                      // floats per 
 // per group; layout L as above with one wave bit (digit 10); layout H: the DPP digits are 8, 9,
 // 10 and (unused as a stage) 4, lane bits 4,5 are digits 5,6, the wave is digit 7.  Group A of a
 // forward program still runs digits 0..7, group B the three digits 8..10; transposed: A runs
-// 10..8, B 7..0.
+// 10..8, B 7..0.  And on 1024 coordinates (ten stages; LOGD = 10): one wave per group; layout H:
+// the DPP digits are 8, 9 and (unused as stages) 4, 5, lane bits 4,5 are digits 6,7.
 template <int LOGD>
 struct Geo {
   static constexpr int D = 1 << LOGD, TG = D / 16, ROWBUF = (D / 256) * kPlane;
@@ -73,6 +74,8 @@ __device__ __forceinline__ unsigned seg_of(bool high, unsigned w, unsigned l) {
   if (LOGD == 11)
     return high ? ((e >> 3) | ((l >> 4) << 1) | (w << 3) | ((e & 7u) << 4))
                 : (e | ((l >> 4) << 4) | (w << 6));
+  if (LOGD == 10)
+    return high ? ((e >> 2) | ((l >> 4) << 2) | ((e & 3u) << 4)) : (e | ((l >> 4) << 4));
   return high ? ((l >> 4) | (w << 2) | (e << 4)) : (e | ((l >> 4) << 4) | (w << 6));
 }
 
@@ -317,6 +320,9 @@ __device__ __forceinline__ void stages_A(float (&x)[16], const float (&f)[TRN ? 
     dpp_shear<2>(x, f[0]);
     dpp_shear<1>(x, f[1]);
     dpp_shear<0>(x, f[2]);
+  } else if constexpr (LOGD == 10) {
+    dpp_shear<1>(x, f[0]);
+    dpp_shear<0>(x, f[1]);
   } else {
     dpp_shear<3>(x, f[0]);
     dpp_shear<2>(x, f[1]);
@@ -409,6 +415,10 @@ __device__ __forceinline__ void stages_B(float (&x)[16], const ParamsB<TRN, LD, 
     dpp_shear<1>(x, pb.f[1]);
     if constexpr (LD) dpp_dense<2>(x, pb.md[0], pb.md[1]);
     else dpp_shear<2>(x, pb.f[2]);
+  } else if constexpr (!TRN && LOGD == 10) {
+    dpp_shear<0>(x, pb.f[0]);
+    if constexpr (LD) dpp_dense<1>(x, pb.md[0], pb.md[1]);
+    else dpp_shear<1>(x, pb.f[1]);
   } else if constexpr (!TRN) {
     dpp_shear<0>(x, pb.f[0]);
     dpp_shear<1>(x, pb.f[1]);
@@ -638,6 +648,8 @@ unsigned dpp_segment_of(bool high_layout, unsigned t, int logd) {
   if (logd == 11)
     return high_layout ? ((e >> 3) | ((l >> 4) << 1) | (w << 3) | ((e & 7u) << 4))
                        : (e | ((l >> 4) << 4) | (w << 6));
+  if (logd == 10)
+    return high_layout ? ((e >> 2) | ((l >> 4) << 2) | ((e & 3u) << 4)) : (e | ((l >> 4) << 4));
   return high_layout ? ((l >> 4) | (w << 2) | (e << 4)) : (e | ((l >> 4) << 4) | (w << 6));
 }
 
@@ -663,15 +675,19 @@ harp_status_t launch_dpp_kernel(const harp_plan *plan, const DppImage &di, const
                                 int64_t ldx, harp_dtype_t dt_in, void *Y, int64_t ldy,
                                 harp_dtype_t dt_out, int64_t n, int R, hipStream_t stream) {
   const int nchunk = (int)(plan->d >> di.logd);
-  if (di.logd == 11) {
-    if (dt_in == HARP_BF16 && dt_out == HARP_BF16)
-      return launch_dpp_io<uint16_t, uint16_t, 11>(di, X, ldx, Y, ldy, n, R, nchunk, stream);
-    if (dt_in == HARP_BF16 && (int)dt_out == kDtZ16 && !di.trn && di.ld)
-      return launch_dpp_io<uint16_t, zh16, 11>(di, X, ldx, Y, ldy, n, R, nchunk, stream);
-    if ((int)dt_in == kDtZ16 && dt_out == HARP_BF16 && di.trn)
-      return launch_dpp_io<zh16, uint16_t, 11>(di, X, ldx, Y, ldy, n, R, nchunk, stream);
-    return HARP_ERR_UNSUPPORTED;
-  }
+#define HARP_DPP_BY_TYPE(LOGD_)                                                                 \
+  do {                                                                                          \
+    if (dt_in == HARP_BF16 && dt_out == HARP_BF16)                                              \
+      return launch_dpp_io<uint16_t, uint16_t, LOGD_>(di, X, ldx, Y, ldy, n, R, nchunk, stream); \
+    if (dt_in == HARP_BF16 && (int)dt_out == kDtZ16 && !di.trn && di.ld)                        \
+      return launch_dpp_io<uint16_t, zh16, LOGD_>(di, X, ldx, Y, ldy, n, R, nchunk, stream);    \
+    if ((int)dt_in == kDtZ16 && dt_out == HARP_BF16 && di.trn)                                  \
+      return launch_dpp_io<zh16, uint16_t, LOGD_>(di, X, ldx, Y, ldy, n, R, nchunk, stream);    \
+    return HARP_ERR_UNSUPPORTED;                                                                \
+  } while (0)
+  if (di.logd == 11) HARP_DPP_BY_TYPE(11);
+  if (di.logd == 10) HARP_DPP_BY_TYPE(10);
+#undef HARP_DPP_BY_TYPE
   if (dt_in == HARP_BF16 && dt_out == HARP_BF16)
     return launch_dpp_io<uint16_t, uint16_t>(di, X, ldx, Y, ldy, n, R, nchunk, stream);
   if (dt_in == HARP_BF16 && (int)dt_out == kDtZ16 && !di.trn && di.ld)

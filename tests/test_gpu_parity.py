@@ -281,14 +281,16 @@ def test_pipelined_kernel_other_sizes_and_types(harp, d, dtype, n):
     run_case(harp, d, radices, n, dtype, seed=d + n)
 
 
-@pytest.mark.parametrize("d,n", [(256, 70), (512, 33), (1024, 129), (256, 1), (1024, 3)])
+@pytest.mark.parametrize("d,n", [(256, 70), (512, 33), (1024, 129), (256, 1), (1024, 3), (1024, 2500)])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_wave_local_kernel_short_rows(harp, d, n, dtype):
     """Radix-2 chains on rows of 256 / 512 / 1024: one wave per 1024-coordinate window."""
     radices = [2] * int(np.log2(d))
     rng = np.random.default_rng(d)
     plan = harp.Plan(d, radices, gi.make_blocks(d, radices, "orth", rng))
-    assert plan.kernel_name() == "wave_radix2"
+    # (bf16 rows of 1024: the two-group DPP kernel, one wave per group)
+    assert plan.kernel_name(n, harp.HARP_F32) == "wave_radix2"
+    assert plan.kernel_name(n, harp.HARP_BF16) == ("dpp_radix2" if d == 1024 else "wave_radix2")
     plan.destroy()
     run_case(harp, d, radices, n, dtype, seed=d + n)
     run_case(harp, d, radices, n, dtype, seed=d + n + 1, rows=3, with_signs=False)
