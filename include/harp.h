@@ -23,8 +23,12 @@
  * vector is on the left of the block, blocks are numbered alpha-major, and the signs
  * act on the input coordinates of apply.
  *
- * All entry points return a status code; none throws, aborts or synchronises the
- * device.  Argument errors are detected before any HIP call.  A plan is immutable
+ * All entry points return a status code; none throws or aborts.  The launch entry points
+ * (harp_apply, harp_apply_transpose, harp_apply_noalloc, harp_rotate_weight(_inverse),
+ * harp_grad_blocks) only enqueue work on the caller's stream and never wait for the device;
+ * the plan constructors copy their images with blocking copies, and the first call of a
+ * split program on a stream allocates its intermediate (see harp_apply).  Argument errors
+ * are detected before any HIP call.  A plan is immutable
  * after creation and may be used concurrently from several host threads and streams.
  */
 #ifndef HARP_H_
