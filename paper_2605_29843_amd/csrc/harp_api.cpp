@@ -371,8 +371,9 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
   // dense stage at the end of the chunk going up.
   // (only where both kernels of the pair handle the format: chunks of 4096 on the DPP kernel or
   // of 256 / 512 / 1024 on the wave kernel, and the small-radix streamed kernel)
-  hp.z16 = (algo == HARP_ALGO_SPLIT && !tied && plan->orthogonal && tb == m - 1 &&
-            plan->radices[m - 1] >= 3 && plan->radices[m - 1] <= 8 && d % 32 == 0 &&
+  bool tops_small = (tb < m);   // every streamed stage of radix 3..8
+  for (int t = tb; t < m; ++t) tops_small = tops_small && plan->radices[t] >= 3 && plan->radices[t] <= 8;
+  hp.z16 = (algo == HARP_ALGO_SPLIT && !tied && plan->orthogonal && tops_small && d % 64 == 0 &&
             (chunk == 4096 || chunk == 2048 || chunk == 1024 || chunk == 512 || chunk == 256));
   const int dense_t = tied ? m - 2 : ((hp.z16 && plan->radices[tb - 1] == 2) ? tb - 1 : -1);
   std::vector<StageEff> eff;
@@ -724,8 +725,9 @@ bool split_uses_z16(const harp_plan_t *plan, const HostProgram &hp, const void *
                     harp_dtype_t dt_in, const void *Y, int64_t ldy, harp_dtype_t dt_out) {
   if (!hp.z16 || dt_in != HARP_BF16 || dt_out != HARP_BF16) return false;
   const int np = hp.prog.npass;
-  if (np - hp.n_chunk != 1) return false;
-  const int p0 = hp.chunk_first ? 0 : 1, ps = hp.chunk_first ? hp.n_chunk : 0;
+  const int nstream = np - hp.n_chunk;
+  if (nstream < 1) return false;
+  const int p0 = hp.chunk_first ? 0 : nstream, ps = hp.chunk_first ? hp.n_chunk : 0;
   const int64_t zl = z16_ld(plan->d);
   const void *cx = hp.chunk_first ? X : nullptr, *cy = hp.chunk_first ? nullptr : Y;
   const int64_t clx = hp.chunk_first ? ldx : zl, cly = hp.chunk_first ? zl : ldy;
@@ -737,9 +739,19 @@ bool split_uses_z16(const harp_plan_t *plan, const HostProgram &hp, const void *
     return false;
   // streamed stage: the small-radix kernel (the matrix-core kernel was measured with this
   // format and is not faster with it: it is bound by its LDS transposes, not by bytes)
-  const void *sx = hp.chunk_first ? nullptr : X, *sy = hp.chunk_first ? Y : nullptr;
-  return stream_z16_supported(hp.prog.pass[ps], sx, hp.chunk_first ? zl : ldx, sy,
-                              hp.chunk_first ? ldy : zl);
+  // (several streamed trips: the ones between two intermediates run in place on the halves)
+  for (int k = 0; k < nstream; ++k) {
+    const bool first = (k == 0), last = (k == nstream - 1);
+    const bool from_caller = !hp.chunk_first && first, to_caller = hp.chunk_first && last;
+    if (!stream_z16_supported(hp.prog.pass[ps + k], from_caller ? X : nullptr, from_caller ? ldx : zl,
+                              to_caller ? Y : nullptr, to_caller ? ldy : zl))
+      return false;
+    // a trip with halves on both sides exists in the LDS-staged kernel only
+    if (!from_caller && !to_caller &&
+        (hp.prog.pass[ps + k].S % 256 != 0 || hp.prog.pass[ps + k].nq % 256 != 0))
+      return false;
+  }
+  return true;
 }
 
 // Split program on rows [0, n): the chunk-local passes run fused on chip, every other pass is

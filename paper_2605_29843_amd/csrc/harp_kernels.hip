@@ -642,55 +642,73 @@ __global__ __launch_bounds__(256) void harp_stream_z16_kernel(const uint16_t *__
 // magnitude by itself and writes 32 bytes of halves and the exponent byte (no cross-lane step).
 // Two barriers per pair of rows; two pairs are requested ahead; several workgroups share a
 // compute unit, so their phases overlap.
-template <int B, bool ZIN>
-__global__ __launch_bounds__(256) void harp_stream_z16_lds_kernel(const uint16_t *__restrict__ X,
-                                                                  int64_t ldx,
-                                                                  uint16_t *__restrict__ Y,
-                                                                  int64_t ldy, int64_t n,
+// OP: the stage (or chain of stages) on the P coordinates base + j S of a sub-tensor; ZI / ZO:
+// block-scaled halves on the way in / out (otherwise bf16).  With halves on both sides (a trip
+// between two intermediates) the launch may run in place: a workgroup reads and writes exactly
+// the coordinates of its own strip, and requests rows ahead of the ones it writes.
+template <class OP, bool ZI, bool ZO>
+__global__ __launch_bounds__(256) void harp_stream_z16_lds_kernel(const uint16_t *X, int64_t ldx,
+                                                                  uint16_t *Y, int64_t ldy, int64_t n,
                                                                   int rows_per_block,
                                                                   const float *__restrict__ params,
                                                                   int nq, int S, int d) {
-  constexpr int NP = 32 * B;                  // 16-byte input pieces per row (<= 256)
-  __shared__ uint16_t s_in[2][B][256];        // the pair's rows as loaded
-  __shared__ uint32_t s_ex[2][B][4];          // ZIN: their exponent bytes
-  __shared__ float s_out[2][B][ZIN ? 128 : 256];   // ZIN: bf16 pairs; else float32 results
+  constexpr int P = OP::P, NV = OP::NV;
+  constexpr int NP = 32 * P;                  // 16-byte input pieces per row
+  constexpr int PPT = (NP + 255) / 256;       // ... per thread (1 or 2)
+  static_assert(PPT <= 2 && 4 * P <= 256, "sub-tensors of at most 16 coordinates");
+  __shared__ uint16_t s_in[2][P][256];        // the pair's rows as loaded
+  __shared__ uint32_t s_ex[2][P][4];          // ZI: their exponent bytes
+  __shared__ float s_out[2][P][ZO ? 256 : 128];   // float32 results, or bf16 pairs
   const int t = threadIdx.x;
   const int q0 = blockIdx.x * 256;
   const int hi = q0 / S;
-  const unsigned strip = (unsigned)hi * B * S + (unsigned)(q0 - hi * S);   // first coordinate, j = 0
-  float prm[B * B];
+  const unsigned strip = (unsigned)hi * P * S + (unsigned)(q0 - hi * S);   // first coordinate, j = 0
+  float prm[NV];
 #pragma unroll
-  for (int v = 0; v < B * B; ++v) prm[v] = params[(size_t)v * nq + q0 + t];
+  for (int v = 0; v < NV; ++v) prm[v] = params[(size_t)v * nq + q0 + t];
   const int64_t r0 = (int64_t)blockIdx.y * rows_per_block;
   const int nr = (int)((r0 + rows_per_block < n) ? rows_per_block : n - r0);
   const int last = nr - 1;
   const uint16_t *xb = X + r0 * ldx;
   uint16_t *yb = Y + r0 * ldy;
-  // This thread's input piece: 8 coordinates of chunk pj at offset pc of the strip, and (ZIN)
-  // its four exponent bytes.  Threads beyond the last piece take the last piece a second time
+  // This thread's input pieces: 8 coordinates of chunk pj at offset pc of the strip, and (ZI)
+  // four exponent bytes.  Threads beyond the last piece take the last piece a second time
   // (same address, same value to the same LDS slot), so that no access is conditional.
-  const int tp = t < NP ? t : NP - 1, te = t < 4 * B ? t : 4 * B - 1;
-  const int pj = tp >> 5, pc = (tp & 31) * 8;
-  const unsigned poff = strip + (unsigned)pj * S + pc;
+  // (first piece t, second piece t + 256 where a row has more than 256 pieces; scalars, not
+  // arrays: arrays passed to the helpers below by reference ended up in scratch memory)
+  const int tpa = t < NP ? t : NP - 1, tpb = (t + 256) < NP ? (t + 256) : NP - 1;
+  const int pja = tpa >> 5, pca = (tpa & 31) * 8, pjb = tpb >> 5, pcb = (tpb & 31) * 8;
+  const unsigned poffa = strip + (unsigned)pja * S + pca, poffb = strip + (unsigned)pjb * S + pcb;
+  const int te = t < 4 * P ? t : 4 * P - 1;
   const unsigned eoff = (strip + (unsigned)(te >> 2) * S) / 16 + 4 * (te & 3);
   // pairs k and k + 1 in named registers
-  uint4 a0, a1, b0, b1;
+  uint4 a0, a1, b0, b1, a0x, a1x, b0x, b1x;   // ..x: the second piece (PPT == 2)
+  a0x = a1x = b0x = b1x = make_uint4(0u, 0u, 0u, 0u);
   uint32_t ea0 = 0, ea1 = 0, eb0 = 0, eb1 = 0;
-  auto request = [&](int pair, uint4 &w0, uint4 &w1, uint32_t &e0, uint32_t &e1) {
+  auto request = [&](int pair, uint4 &w0, uint4 &w1, uint4 &w0x, uint4 &w1x, uint32_t &e0, uint32_t &e1) {
     const int r = 2 * pair;
     const uint16_t *x0 = xb + (int64_t)(r < last ? r : last) * ldx;   // past the end: the last row again
     const uint16_t *x1 = xb + (int64_t)(r + 1 < last ? r + 1 : last) * ldx;
-    w0 = *reinterpret_cast<const uint4 *>(x0 + poff);
-    w1 = *reinterpret_cast<const uint4 *>(x1 + poff);
-    if constexpr (ZIN) {
+    w0 = *reinterpret_cast<const uint4 *>(x0 + poffa);
+    w1 = *reinterpret_cast<const uint4 *>(x1 + poffa);
+    if constexpr (PPT == 2) {
+      w0x = *reinterpret_cast<const uint4 *>(x0 + poffb);
+      w1x = *reinterpret_cast<const uint4 *>(x1 + poffb);
+    }
+    if constexpr (ZI) {
       e0 = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const uint8_t *>(x0 + d) + eoff);
       e1 = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const uint8_t *>(x1 + d) + eoff);
     }
   };
-  auto stage = [&](const uint4 &w0, const uint4 &w1, uint32_t e0, uint32_t e1) {
-    *reinterpret_cast<uint4 *>(&s_in[0][pj][pc]) = w0;
-    *reinterpret_cast<uint4 *>(&s_in[1][pj][pc]) = w1;
-    if constexpr (ZIN) {
+  auto stage = [&](const uint4 &w0, const uint4 &w1, const uint4 &w0x, const uint4 &w1x, uint32_t e0,
+                   uint32_t e1) {
+    *reinterpret_cast<uint4 *>(&s_in[0][pja][pca]) = w0;
+    *reinterpret_cast<uint4 *>(&s_in[1][pja][pca]) = w1;
+    if constexpr (PPT == 2) {
+      *reinterpret_cast<uint4 *>(&s_in[0][pjb][pcb]) = w0x;
+      *reinterpret_cast<uint4 *>(&s_in[1][pjb][pcb]) = w1x;
+    }
+    if constexpr (ZI) {
       s_ex[0][te >> 2][te & 3] = e0;
       s_ex[1][te >> 2][te & 3] = e1;
     }
@@ -698,34 +716,28 @@ __global__ __launch_bounds__(256) void harp_stream_z16_lds_kernel(const uint16_t
   auto compute = [&]() {
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      float x[B], y[B];
+      float x[P];
 #pragma unroll
-      for (int j = 0; j < B; ++j) {
+      for (int j = 0; j < P; ++j) {
         const uint32_t v = s_in[h][j][t];
-        if (ZIN) {
+        if (ZI) {
           const uint32_t ex = reinterpret_cast<const uint8_t *>(&s_ex[h][j][0])[t >> 4];
           x[j] = (float)__builtin_bit_cast(_Float16, (uint16_t)v) * z16_up(ex);
         } else {
           x[j] = __uint_as_float(v << 16);
         }
       }
+      OP::apply(x, prm);
 #pragma unroll
-      for (int r2 = 0; r2 < B; ++r2) {
-        float acc = x[0] * prm[r2];
-#pragma unroll
-        for (int r = 1; r < B; ++r) acc = fmaf(x[r], prm[r * B + r2], acc);
-        y[r2] = acc;
-      }
-#pragma unroll
-      for (int j = 0; j < B; ++j) {
-        if (ZIN) reinterpret_cast<uint16_t *>(&s_out[h][j][0])[t] = narrow_bf16(y[j]);
-        else s_out[h][j][t] = y[j];
+      for (int j = 0; j < P; ++j) {
+        if (ZO) s_out[h][j][t] = x[j];
+        else reinterpret_cast<uint16_t *>(&s_out[h][j][0])[t] = narrow_bf16(x[j]);
       }
     }
   };
   auto put = [&](int pair) {
-    if (ZIN) {
-      // 16-byte pieces of bf16: 2 rows x B chunks x 32 pieces
+    if (!ZO) {
+      // 16-byte pieces of bf16: 2 rows x P chunks x 32 pieces
       for (int p = t; p < 2 * NP; p += 256) {
         const int h = p / NP, pp = p - h * NP, j = pp >> 5, c = (pp & 31) * 8;
         const int r = 2 * pair + h;
@@ -734,9 +746,9 @@ __global__ __launch_bounds__(256) void harp_stream_z16_lds_kernel(const uint16_t
               *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(&s_out[h][j][0]) + c);
       }
     } else {
-      // whole segments: 2 rows x B chunks x 16 segments of 16 float32 results
-      for (int sg = t; sg < 2 * 16 * B; sg += 256) {
-        const int h = sg / (16 * B), ss = sg - h * 16 * B, j = ss >> 4, c = (ss & 15) * 16;
+      // whole segments: 2 rows x P chunks x 16 segments of 16 float32 results
+      for (int sg = t; sg < 2 * 16 * P; sg += 256) {
+        const int h = sg / (16 * P), ss = sg - h * 16 * P, j = ss >> 4, c = (ss & 15) * 16;
         const int r = 2 * pair + h;
         float v[16];
 #pragma unroll
@@ -763,23 +775,23 @@ __global__ __launch_bounds__(256) void harp_stream_z16_lds_kernel(const uint16_t
     }
   };
   const int npairs = (nr + 1) >> 1;
-  request(0, a0, a1, ea0, ea1);
-  request(1, b0, b1, eb0, eb1);
-  stage(a0, a1, ea0, ea1);
+  request(0, a0, a1, a0x, a1x, ea0, ea1);
+  request(1, b0, b1, b0x, b1x, eb0, eb1);
+  stage(a0, a1, a0x, a1x, ea0, ea1);
   __syncthreads();
   for (int k = 0; k < npairs; k += 2) {
-    request(k + 2, a0, a1, ea0, ea1);   // pair k is staged already
-    compute();                          // pair k: s_in -> s_out
-    __syncthreads();                    // s_out complete, s_in free
+    request(k + 2, a0, a1, a0x, a1x, ea0, ea1);   // pair k is staged already
+    compute();                                    // pair k: s_in -> s_out
+    __syncthreads();                              // s_out complete, s_in free
     put(k);
-    stage(b0, b1, eb0, eb1);            // pair k + 1
-    __syncthreads();                    // s_in complete, s_out free
+    stage(b0, b1, b0x, b1x, eb0, eb1);            // pair k + 1
+    __syncthreads();                              // s_in complete, s_out free
     if (k + 1 >= npairs) break;
-    request(k + 3, b0, b1, eb0, eb1);
+    request(k + 3, b0, b1, b0x, b1x, eb0, eb1);
     compute();
     __syncthreads();
     put(k + 1);
-    stage(a0, a1, ea0, ea1);
+    stage(a0, a1, a0x, a1x, ea0, ea1);
     __syncthreads();
   }
 }
@@ -866,9 +878,9 @@ harp_status_t launch_stream_op(const harp_plan *plan, const PassDesc &pd, const 
 }
 
 // dense stage of radix 3..8 between a bf16 side and the block-scaled half intermediate
-template <int B>
+template <class OP>
 harp_status_t launch_stream_z16_lds(const harp_plan *plan, const PassDesc &pd, const void *X,
-                                    int64_t ldx, void *Y, int64_t ldy, int64_t n, bool zin,
+                                    int64_t ldx, void *Y, int64_t ldy, int64_t n, bool zin, bool zout,
                                     hipStream_t stream) {
   const unsigned gx = (unsigned)(pd.nq / 256);
   // about 8 workgroups per compute unit, rows in pairs, at least 8 rows each
@@ -879,28 +891,36 @@ harp_status_t launch_stream_z16_lds(const harp_plan *plan, const PassDesc &pd, c
   int64_t rpb = (n + gy - 1) / gy;
   rpb = (rpb + 1) / 2 * 2;
   gy = (n + rpb - 1) / rpb;
-  if (zin)
-    hipLaunchKernelGGL((harp_stream_z16_lds_kernel<B, true>), dim3(gx, (unsigned)gy), dim3(256), 0, stream,
-                       (const uint16_t *)X, ldx, (uint16_t *)Y, ldy, n, (int)rpb, pd.params, pd.nq, pd.S,
-                       (int)plan->d);
-  else
-    hipLaunchKernelGGL((harp_stream_z16_lds_kernel<B, false>), dim3(gx, (unsigned)gy), dim3(256), 0, stream,
-                       (const uint16_t *)X, ldx, (uint16_t *)Y, ldy, n, (int)rpb, pd.params, pd.nq, pd.S,
-                       (int)plan->d);
+#define HARP_Z16_LDS(ZI_, ZO_)                                                                            \
+  hipLaunchKernelGGL((harp_stream_z16_lds_kernel<OP, ZI_, ZO_>), dim3(gx, (unsigned)gy), dim3(256), 0,     \
+                     stream, (const uint16_t *)X, ldx, (uint16_t *)Y, ldy, n, (int)rpb, pd.params, pd.nq, \
+                     pd.S, (int)plan->d)
+  if (zin && zout) HARP_Z16_LDS(true, true);
+  else if (zin) HARP_Z16_LDS(true, false);
+  else if (zout) HARP_Z16_LDS(false, true);
+  else return HARP_ERR_UNSUPPORTED;
+#undef HARP_Z16_LDS
   return hipGetLastError() == hipSuccess ? HARP_OK : HARP_ERR_DEVICE;
+}
+
+// whether the LDS-staged kernel can run this pass (strides and strips of whole 256-coordinate
+// runs, 16-byte aligned rows)
+bool z16_lds_ok(const harp_plan *plan, const PassDesc &pd, const void *X, int64_t ldx, const void *Y,
+                int64_t ldy) {
+  return pd.S % 256 == 0 && pd.nq % 256 == 0 && ldx % 8 == 0 && ldy % 8 == 0 && (uintptr_t)X % 16 == 0 &&
+         (uintptr_t)Y % 16 == 0 && plan->d % 64 == 0;
 }
 
 template <class OP>
 harp_status_t launch_stream_z16_op(const harp_plan *plan, const PassDesc &pd, const void *X,
-                                   int64_t ldx, void *Y, int64_t ldy, int64_t n, bool zin,
+                                   int64_t ldx, void *Y, int64_t ldy, int64_t n, bool zin, bool zout,
                                    hipStream_t stream) {
-  // Writing the halves (the stage runs first): the LDS-staged kernel, when strides and strips are
-  // whole 256-coordinate runs and rows 16-byte aligned (2048 x 14336: 37.5 -> 30 us).  Reading
-  // them, the two kernels measured within 3 % of each other (radix 3 and 28672 faster from
-  // registers, 14336 from LDS): the register kernel.
-  if (!zin && pd.S % 256 == 0 && pd.nq % 256 == 0 && ldx % 8 == 0 && ldy % 8 == 0 && (uintptr_t)X % 16 == 0 &&
-      (uintptr_t)Y % 16 == 0 && plan->d % 64 == 0)
-    return launch_stream_z16_lds<OP::P>(plan, pd, X, ldx, Y, ldy, n, zin, stream);
+  // Writing the halves (the stage runs first), or halves on both sides: the LDS-staged kernel
+  // (2048 x 14336: 37.5 -> 30 us).  Reading them into bf16, the two kernels measured within 3 %
+  // of each other (radix 3 and 28672 faster from registers, 14336 from LDS): the register kernel.
+  const bool lds_ok = z16_lds_ok(plan, pd, X, ldx, Y, ldy);
+  if (zout && lds_ok) return launch_stream_z16_lds<OP>(plan, pd, X, ldx, Y, ldy, n, zin, zout, stream);
+  if (zin && zout) return HARP_ERR_UNSUPPORTED;
   const StreamGrid g = stream_grid(pd.nq / 2, plan, n);
   if (zin)
     hipLaunchKernelGGL((harp_stream_z16_kernel<OP, true>), dim3(g.gx, g.gy), dim3(256), 0, stream,
@@ -1150,7 +1170,12 @@ harp_status_t launch_tile_kernel(const harp_plan *plan, const Program *prog, int
 // radix 3..8 whose stride is a multiple of 16, rows that allow 32-bit accesses
 bool stream_z16_supported(const PassDesc &pd, const void *X, int64_t ldx, const void *Y,
                           int64_t ldy) {
-  if (pd.kind != PASS_SMALL || pd.b < 3 || pd.b > 8 || pd.tied) return false;
+  const bool chain = (pd.kind == PASS_SMALL_CHAIN && pd.b == 3 && pd.k == 2);   // LDS-staged kernel only
+  if (!chain && (pd.kind != PASS_SMALL || pd.b < 3 || pd.b > 8)) return false;
+  if (pd.tied) return false;
+  if (chain && (pd.S % 256 != 0 || pd.nq % 256 != 0 || ldx % 8 || ldy % 8 || (uintptr_t)X % 16 ||
+                (uintptr_t)Y % 16))
+    return false;
   if (pd.S % 16 != 0 || (pd.nq & 1)) return false;
   if ((ldx % 2) || (ldy % 2) || ((uintptr_t)X % 4) || ((uintptr_t)Y % 4)) return false;
   if ((int64_t)pd.P * pd.S >= (int64_t)1 << 31) return false;
@@ -1168,15 +1193,21 @@ harp_status_t launch_stream_pass(const harp_plan *plan, const HostProgram &hp, i
   if (pd.tied) return HARP_ERR_UNSUPPORTED;   // only the matrix-core kernel reads a tied table
   if ((int)dt_in == kDtZ16 || (int)dt_out == kDtZ16) {
     if (!stream_z16_supported(pd, X, ldx, Y, ldy)) return HARP_ERR_UNSUPPORTED;
-    const bool zin = (int)dt_in == kDtZ16;
-    if ((zin && dt_out != HARP_BF16) || (!zin && dt_in != HARP_BF16)) return HARP_ERR_UNSUPPORTED;
+    const bool zin = (int)dt_in == kDtZ16, zout = (int)dt_out == kDtZ16;
+    if ((!zin && dt_in != HARP_BF16) || (!zout && dt_out != HARP_BF16)) return HARP_ERR_UNSUPPORTED;
+    if (zin && zout && !z16_lds_ok(plan, pd, X, ldx, Y, ldy)) return HARP_ERR_UNSUPPORTED;
+    if (pd.kind == PASS_SMALL_CHAIN) {
+      if (!z16_lds_ok(plan, pd, X, ldx, Y, ldy)) return HARP_ERR_UNSUPPORTED;
+      return pd.desc ? launch_stream_z16_lds<OpSmallChain<3, 2, true>>(plan, pd, X, ldx, Y, ldy, n, zin, zout, stream)
+                     : launch_stream_z16_lds<OpSmallChain<3, 2, false>>(plan, pd, X, ldx, Y, ldy, n, zin, zout, stream);
+    }
     switch (pd.b) {
-      case 3: return launch_stream_z16_op<OpSmall<3>>(plan, pd, X, ldx, Y, ldy, n, zin, stream);
-      case 4: return launch_stream_z16_op<OpSmall<4>>(plan, pd, X, ldx, Y, ldy, n, zin, stream);
-      case 5: return launch_stream_z16_op<OpSmall<5>>(plan, pd, X, ldx, Y, ldy, n, zin, stream);
-      case 6: return launch_stream_z16_op<OpSmall<6>>(plan, pd, X, ldx, Y, ldy, n, zin, stream);
-      case 7: return launch_stream_z16_op<OpSmall<7>>(plan, pd, X, ldx, Y, ldy, n, zin, stream);
-      default: return launch_stream_z16_op<OpSmall<8>>(plan, pd, X, ldx, Y, ldy, n, zin, stream);
+      case 3: return launch_stream_z16_op<OpSmall<3>>(plan, pd, X, ldx, Y, ldy, n, zin, zout, stream);
+      case 4: return launch_stream_z16_op<OpSmall<4>>(plan, pd, X, ldx, Y, ldy, n, zin, zout, stream);
+      case 5: return launch_stream_z16_op<OpSmall<5>>(plan, pd, X, ldx, Y, ldy, n, zin, zout, stream);
+      case 6: return launch_stream_z16_op<OpSmall<6>>(plan, pd, X, ldx, Y, ldy, n, zin, zout, stream);
+      case 7: return launch_stream_z16_op<OpSmall<7>>(plan, pd, X, ldx, Y, ldy, n, zin, zout, stream);
+      default: return launch_stream_z16_op<OpSmall<8>>(plan, pd, X, ldx, Y, ldy, n, zin, zout, stream);
     }
   }
   const int ib = dt_in == HARP_BF16, ob = dt_out == HARP_BF16;

@@ -473,7 +473,9 @@ def test_chunk_of_a_llama13b_ffn_row_ends_behind_its_radix2_stages(harp):
     d, radices = 13824, [2] * 9 + [3, 3, 3]
     rng = np.random.default_rng(7)
     plan = harp.Plan(d, radices, gi.make_blocks(d, radices, "orth", rng))
-    assert plan.kernel_name(2048) == "split_wave_stream", plan.kernel_name(2048)
+    assert plan.kernel_name(2048, harp.HARP_F32) == "split_wave_stream", plan.kernel_name(2048, harp.HARP_F32)
+    # (bf16 callers: the same kernels with the half-precision intermediate on both trips)
+    assert plan.kernel_name(2048, harp.HARP_BF16) == "split_wave_stream_h16"
     plan.destroy()
     run_case(harp, d, radices, 19, "f32", seed=77, act=gi.activations(19, d, config=3, bf16=False))
 
@@ -484,7 +486,8 @@ def test_chunk_of_a_llama13b_ffn_row_ends_behind_its_radix2_stages(harp):
     (14336, [2] * 11 + [7]),      # DPP kernel on chunks of 2048 + streamed radix 7
     (5120, [2] * 10 + [5]),       # wave kernel on chunks of 1024 + streamed radix 5
     (7168, [2] * 10 + [7]),       # wave kernel on chunks of 1024 + streamed radix 7
-    (2048 * 3, [2] * 9 + [4, 3]), # two streamed stages: keeps the float32 intermediate
+    (2048 * 3, [2] * 9 + [4, 3]), # two streamed trips: halves on both sides of the first one
+    (13824, [2] * 9 + [3, 3, 3]), # wave kernel on chunks of 512, two radix-3 stages in one trip, one more
 ])
 def test_half_precision_intermediate_of_split_programs(harp, d, radices):
     """bf16 callers of a split program with one streamed small-radix stage: the intermediate
@@ -497,10 +500,9 @@ def test_half_precision_intermediate_of_split_programs(harp, d, radices):
     blocks = gi.make_blocks(d, radices, "orth", rng)
     signs = gi.make_signs(d, rng)
     plan = harp.Plan(d, radices, blocks, signs)
-    one_streamed = radices[-2] == 2
     name16, name32 = plan.kernel_name(64, harp.HARP_BF16), plan.kernel_name(64, harp.HARP_F32)
     say(f"half intermediate d={d} radices={radices}: bf16 -> {name16}, f32 -> {name32}")
-    assert name16.endswith("_h16") == one_streamed, name16
+    assert name16.endswith("_h16"), name16
     assert not name32.endswith("_h16"), name32
     g = rng.standard_normal
     rows = [np.zeros(d), np.eye(1, d, 5)[0], 3e4 * np.eye(1, d, d - 1)[0], 1e-30 * g(d), 1e18 * g(d)]
