@@ -527,6 +527,36 @@ def test_half_precision_intermediate_of_split_programs(harp, d, radices):
     plan.destroy()
 
 
+@pytest.mark.parametrize("d,radices", [(14336, [2] * 11 + [7]), (5120, [2] * 10 + [5]),
+                                       (13824, [2] * 9 + [3, 3, 3]), (12288, [2] * 12 + [3])])
+@pytest.mark.parametrize("n,ld_pad", [(0, 0), (1, 0), (2, 0), (3, 8), (5, 24), (67, 8), (6, 3)])
+def test_half_precision_intermediate_edges(harp, d, radices, n, ld_pad):
+    """Split programs of bf16 callers at the edges: no rows, one row, odd row counts (rows move in
+    pairs), padded rows (the padding must not be written) and a padding that breaks the 16-byte
+    alignment of the rows (the library must fall back to kernels that do not need it)."""
+    run_case(harp, d, radices, n, "bf16", seed=d + 31 * n + ld_pad, ld_pad=ld_pad)
+
+
+def test_half_precision_intermediate_in_place(harp):
+    """harp_apply with Y == X on a split program whose intermediate travels as halves."""
+    import torch
+    d, radices, n = 14336, [2] * 11 + [7], 21
+    rng = np.random.default_rng(5)
+    blocks, signs = gi.make_blocks(d, radices, "orth", rng), gi.make_signs(d, rng)
+    plan = harp.Plan(d, radices, blocks, signs)
+    X = gi.round_to_bf16(rng.standard_normal((n, d)).astype(np.float32))
+    Xd = to_device(X, "bf16")
+    harp.harp_apply(plan, Xd, Xd)
+    torch.cuda.synchronize()
+    assert_parity(to_host64(Xd), ho.apply_staged(X, d, radices, blocks, signs), "bf16", "apply in place")
+    Xd = to_device(X, "bf16")
+    harp.harp_apply_transpose(plan, Xd, Xd)
+    torch.cuda.synchronize()
+    assert_parity(to_host64(Xd), ho.apply_transpose_staged(X, d, radices, blocks, signs), "bf16",
+                  "apply_transpose in place")
+    plan.destroy()
+
+
 def test_split_is_refused_when_there_is_nothing_to_split(harp):
     rng = np.random.default_rng(1)
     plan = harp.Plan(4096, [2] * 12, gi.make_blocks(4096, [2] * 12, "orth", rng))
