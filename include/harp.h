@@ -64,7 +64,11 @@ enum {
   HARP_BLOCKS_ON_DEVICE = 2u, /* blocks[t] and signs are device pointers (copied back to build) */
   /* harp_plan_create_from_theta_int8 only: also keep the int8 codes on the device and rebuild
    * the blocks inside the kernel for the stages that have such a kernel (see there) */
-  HARP_THETA_IN_KERNEL = 4u
+  HARP_THETA_IN_KERNEL = 4u,
+  /* keep every intermediate of this plan in float32: split programs (harp_apply) and the
+   * workspace of harp_rotate_weight otherwise carry bf16 callers' data between launches as
+   * half-precision values with one power-of-two scale per 16 coordinates (see harp_rotate_weight) */
+  HARP_F32_INTERMEDIATES = 8u
 };
 
 /* kernel selection, for tests and tuning (harp_plan_set_algo) */
@@ -90,7 +94,7 @@ typedef enum {
  *            holds D_t = d / b_t blocks of b_t * b_t float32, block c row-major:
  *            blocks[t][c*b*b + r*b + r2] = K_t[c][r][r2], used as  v'[r2] = sum_r v[r] K[r][r2].
  *   signs    d int8 values in {+1, -1}, or NULL for all +1.
- *   flags    OR of HARP_VALIDATE_ORTHO, HARP_BLOCKS_ON_DEVICE.
+ *   flags    OR of HARP_VALIDATE_ORTHO, HARP_BLOCKS_ON_DEVICE, HARP_F32_INTERMEDIATES.
  * The plan copies everything it needs into device memory it owns (on the current HIP
  * device); the caller's arrays may be freed on return.
  */
@@ -165,6 +169,15 @@ int64_t harp_apply_noalloc_max_rows(const harp_plan_t *plan);
  * workspace: device scratch of at least the size reported by
  * harp_rotate_weight_workspace_size (may be NULL when that size is 0).
  * The inverse map  W = U_U * Wout * U_V^T  is harp_rotate_weight_inverse.
+ * Arithmetic is float32 and the result is rounded once, at the last store.  Between the launches
+ * of a call the matrix lies in the workspace as float32 -- or, for HARP_BF16 matrices between
+ * processors whose blocks are all orthogonal (checked at plan creation), with d_in a multiple
+ * of 128 and 16-byte aligned workspace, as half-precision values with one power-of-two scale
+ * per 16 consecutive columns of a row: each of the at most two trips then changes an entry by at
+ * most 2^-12 of itself (or 2^-25 of the largest of its 16 neighbours), an eighth of the rounding
+ * the bf16 result receives anyway.  That error is relative to the entry between the launches,
+ * i.e. to the scale of its column while plan_U's stages are still to come; HARP_F32_INTERMEDIATES
+ * on either plan keeps the workspace in float32.
  */
 harp_status_t harp_rotate_weight_workspace_size(const harp_plan_t *plan_U,
                                                 const harp_plan_t *plan_V, int64_t d_out,

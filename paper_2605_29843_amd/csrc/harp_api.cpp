@@ -373,7 +373,7 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
   // of 256 / 512 / 1024 on the wave kernel, and the small-radix streamed kernel)
   bool tops_small = (tb < m);   // every streamed stage of radix 3..8
   for (int t = tb; t < m; ++t) tops_small = tops_small && plan->radices[t] >= 3 && plan->radices[t] <= 8;
-  hp.z16 = (algo == HARP_ALGO_SPLIT && !tied && plan->orthogonal && tops_small && d % 64 == 0 &&
+  hp.z16 = (algo == HARP_ALGO_SPLIT && !tied && plan->orthogonal && !plan->f32_only && tops_small && d % 64 == 0 &&
             (chunk == 4096 || chunk == 2048 || chunk == 1024 || chunk == 512 || chunk == 256));
   const int dense_t = tied ? m - 2 : ((hp.z16 && plan->radices[tb - 1] == 2) ? tb - 1 : -1);
   std::vector<StageEff> eff;
@@ -861,46 +861,82 @@ harp_status_t rotate_impl(const harp_plan_t *pu, const harp_plan_t *pv, Directio
   // bf16 matrix is rounded once, at the final store.
   const std::vector<ColPassHost> &cps = pu->colpass[dir];
   if (!cps.empty()) {
-    float *A = (float *)ws;   // [d_out, d_in] float32
+    float *A = (float *)ws;   // [d_out, d_in] float32, or block-scaled halves (see below)
     // plan_V as a split program with one streamed small-radix stage: that stage acts on the
     // columns and commutes with plan_U's stages, so it rides along with one column pass instead
     // of taking its own trip through device memory.  Forward: chunk passes of plan_V, then the
     // column passes; inverse: the column passes, then plan_V's chunk passes.
     const HostProgram *vhp = pv ? select_program(pv, dir, d_out, nullptr) : nullptr;
+    // Workspace format.  A bf16 matrix between orthogonal processors travels through the
+    // workspace as block-scaled halves (one power-of-two scale per 16 columns of a row, 2.06
+    // bytes per entry instead of 4): each trip adds at most 2^-12 of an entry (or 2^-25 of its
+    // segment's largest) where the caller's own element type rounds by 2^-9, and the matrix is
+    // still rounded to bf16 once, at the last store.  It needs whole 128-column tiles in every
+    // column pass and, on plan_V's side, the two-group DPP kernel, which reads and writes the
+    // format (writing it going up, reading it going down); otherwise float32 as before.
+    const harp_dtype_t ZT = (harp_dtype_t)kDtZ16;
+    const int64_t zl = z16_ld(d_in);
+    bool zws = dt == HARP_BF16 && pu->orthogonal && (!pv || pv->orthogonal) && !pu->f32_only &&
+               !(pv && pv->f32_only) &&
+               (cps.size() > 1 || pv) && (uintptr_t)ws % 16 == 0;
+    for (size_t p = 0; p < cps.size() && zws; ++p)
+      zws = col_z16_supported(cps[p].pass, W, ldw, Wout, ldo, d_out, d_in) &&
+            col_z16_supported(cps[p].pass, A, zl, A, zl, d_out, d_in);
+    // plan_V's on-chip passes with the halves on the workspace side
+    auto chunk_z16_ok = [&]() {
+      return dir == DIR_FWD ? dpp_supported(pv, vhp->dpp, vhp->chunk, W, ldw, HARP_BF16, A, zl, ZT)
+                            : dpp_supported(pv, vhp->dpp, vhp->chunk, A, zl, ZT, Wout, ldo, HARP_BF16);
+    };
+    if (zws && pv && (!vhp || !chunk_z16_ok())) zws = false;
     int fuse = -1;
     const PassDesc *vp = nullptr;
-    if (vhp && vhp->n_chunk + 1 == vhp->prog.npass) {
-      vp = &vhp->prog.pass[vhp->chunk_first ? vhp->n_chunk : 0];
-      for (int p = (int)cps.size() - 1; p >= 0 && fuse < 0; --p) {
+    const bool one_streamed = vhp && vhp->n_chunk + 1 == vhp->prog.npass;
+    auto find_fuse = [&](bool z) {
+      const harp_dtype_t wt = z ? ZT : HARP_F32;
+      const int64_t wld = z ? zl : d_in;
+      for (int p = (int)cps.size() - 1; p >= 0; --p) {
         const bool first = (p == 0), last = (p + 1 == (int)cps.size());
         // what this pass reads and writes in the fused order
         const bool reads_w = (dir == DIR_TRN) && first;
         const bool writes_out = (dir == DIR_FWD) && last;
         const void *src = reads_w ? W : (const void *)A;
         const void *dst = writes_out ? (const void *)Wout : (const void *)A;
-        if (colrow_supported(pu, cps[p].pass, *vp, src, reads_w ? ldw : d_in,
-                             reads_w ? dt : HARP_F32, dst, writes_out ? ldo : d_in,
-                             writes_out ? dt : HARP_F32, d_out, d_in))
-          fuse = p;
+        if (colrow_supported(pu, cps[p].pass, *vp, src, reads_w ? ldw : wld, reads_w ? dt : wt, dst,
+                             writes_out ? ldo : wld, writes_out ? dt : wt, d_out, d_in))
+          return p;
       }
+      return -1;
+    };
+    if (one_streamed) {
+      vp = &vhp->prog.pass[vhp->chunk_first ? vhp->n_chunk : 0];
+      if (zws) {
+        fuse = find_fuse(true);
+        if (fuse < 0) zws = false;
+      }
+      if (fuse < 0) fuse = find_fuse(false);
+    } else if (zws && pv && vhp->n_chunk != vhp->prog.npass) {
+      zws = false;   // several streamed trips: plan_V runs on its own, through float32
     }
+    if (zws && pv && fuse < 0 && vhp->n_chunk != vhp->prog.npass) zws = false;
+    const harp_dtype_t wt = zws ? ZT : HARP_F32;
+    const int64_t wld = zws ? zl : d_in;
     const void *src = W;
     int64_t src_ld = ldw;
     harp_dtype_t src_dt = dt;
     if (fuse >= 0) {
       const int c0 = vhp->chunk_first ? 0 : 1;
       if (dir == DIR_FWD) {
-        st = run_chunk_passes(pv, *vhp, c0, c0 + vhp->n_chunk, W, ldw, dt, A, d_in, HARP_F32, d_out, s);
+        st = run_chunk_passes(pv, *vhp, c0, c0 + vhp->n_chunk, W, ldw, dt, A, wld, wt, d_out, s);
         if (st != HARP_OK) return st;
         src = A;
-        src_ld = d_in;
-        src_dt = HARP_F32;
+        src_ld = wld;
+        src_dt = wt;
       }
       for (size_t p = 0; p < cps.size(); ++p) {
         const bool to_out = (dir == DIR_FWD) && (p + 1 == cps.size());
         void *dst = to_out ? Wout : (void *)A;
-        const int64_t dst_ld = to_out ? ldo : d_in;
-        const harp_dtype_t dst_dt = to_out ? dt : HARP_F32;
+        const int64_t dst_ld = to_out ? ldo : wld;
+        const harp_dtype_t dst_dt = to_out ? dt : wt;
         if ((int)p == fuse)
           st = launch_colrow_pass(pu, cps[p].dev, cps[p].pass, *vp, src, src_ld, src_dt, dst, dst_ld,
                                   dst_dt, d_out, d_in, s);
@@ -913,21 +949,27 @@ harp_status_t rotate_impl(const harp_plan_t *pu, const harp_plan_t *pv, Directio
         src_dt = dst_dt;
       }
       if (dir == DIR_TRN)
-        st = run_chunk_passes(pv, *vhp, c0, c0 + vhp->n_chunk, A, d_in, HARP_F32, Wout, ldo, dt, d_out, s);
+        st = run_chunk_passes(pv, *vhp, c0, c0 + vhp->n_chunk, A, wld, wt, Wout, ldo, dt, d_out, s);
       return st;
     }
-    if (pv) {
-      st = apply_dir(pv, dir, W, ldw, dt, A, d_in, HARP_F32, d_out, stream);
+    // plan_V on its own: before the column passes, or (halves, inverse map: the DPP kernel reads
+    // the format only going down) behind them -- the two sides commute
+    const bool v_last = zws && pv && dir == DIR_TRN;
+    if (pv && !v_last) {
+      if (zws)
+        st = run_chunk_passes(pv, *vhp, 0, vhp->prog.npass, W, ldw, dt, A, wld, wt, d_out, s);
+      else
+        st = apply_dir(pv, dir, W, ldw, dt, A, d_in, HARP_F32, d_out, stream);
       if (st != HARP_OK) return st;
       src = A;
-      src_ld = d_in;
-      src_dt = HARP_F32;
+      src_ld = wld;
+      src_dt = wt;
     }
     for (size_t p = 0; p < cps.size(); ++p) {
-      const bool last = (p + 1 == cps.size());
+      const bool last = (p + 1 == cps.size()) && !v_last;
       void *dst = last ? Wout : (void *)A;
-      const int64_t dst_ld = last ? ldo : d_in;
-      const harp_dtype_t dst_dt = last ? dt : HARP_F32;
+      const int64_t dst_ld = last ? ldo : wld;
+      const harp_dtype_t dst_dt = last ? dt : wt;
       st = launch_col_pass(pu, cps[p].dev, cps[p].pass, src, src_ld, src_dt, dst, dst_ld, dst_dt,
                            d_out, d_in, s);
       if (st != HARP_OK) return st;
@@ -935,7 +977,9 @@ harp_status_t rotate_impl(const harp_plan_t *pu, const harp_plan_t *pv, Directio
       src_ld = dst_ld;
       src_dt = dst_dt;
     }
-    return HARP_OK;
+    if (v_last)
+      st = run_chunk_passes(pv, *vhp, 0, vhp->prog.npass, A, wld, wt, Wout, ldo, dt, d_out, s);
+    return st;
   }
   // Otherwise: (U^T M)^T = M^T U, i.e. the rows of M^T go through plan_U as a row processor.
   const size_t mat = (size_t)d_out * d_in * 4;
@@ -1073,7 +1117,8 @@ harp_status_t harp::plan_create_impl(harp_plan **out, int64_t d, int32_t m, cons
                                      const float *const *blocks, const int8_t *signs,
                                      uint32_t flags, int32_t tied_K) {
   if (!out || !radices || !blocks) return HARP_ERR_INVALID_ARG;
-  if (flags & ~(uint32_t)(HARP_VALIDATE_ORTHO | HARP_BLOCKS_ON_DEVICE)) return HARP_ERR_INVALID_ARG;
+  if (flags & ~(uint32_t)(HARP_VALIDATE_ORTHO | HARP_BLOCKS_ON_DEVICE | HARP_F32_INTERMEDIATES))
+    return HARP_ERR_INVALID_ARG;
   if (d < 2) return HARP_ERR_INVALID_ARG;
   if (m < 1 || m > HARP_MAX_STAGES) return HARP_ERR_BAD_SCHEDULE;
   int64_t prod = 1;
@@ -1169,6 +1214,7 @@ harp_status_t harp::plan_create_impl(harp_plan **out, int64_t d, int32_t m, cons
         if (flags & HARP_VALIDATE_ORTHO) st = HARP_ERR_NOT_ORTHOGONAL;
       }
     }
+    plan->f32_only = (flags & HARP_F32_INTERMEDIATES) != 0;
     // ---- device side -------------------------------------------------------------
     if (st == HARP_OK) {
       int dev = 0;

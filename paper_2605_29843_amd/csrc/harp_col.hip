@@ -43,29 +43,38 @@ __device__ __forceinline__ uint32_t f32_to_bf16(float f) {   // round to nearest
 
 // Two adjacent elements as loaded (no arithmetic on them until they are needed, so that the
 // loads of the next tile stay in flight during the work on the current one).
+// zh16 = block-scaled halves (the workspace of bf16 callers): the pair's two halves plus the
+// exponent byte of its 16-column segment, which lies `eoff` bytes behind the pair (eight lanes
+// share a segment and read the same byte).  Other element types ignore eoff.
 template <typename T> struct ColRaw;
 template <> struct ColRaw<float> { float2 v; };
 template <> struct ColRaw<uint16_t> { uint32_t lo, hi; };   // VEC: both in lo
+template <> struct ColRaw<zh16> { uint32_t h, e; };
 
 template <typename T, bool VEC>
-__device__ __forceinline__ void col_load(ColRaw<T> &r, const T *p, bool v0, bool v1);
+__device__ __forceinline__ void col_load(ColRaw<T> &r, const T *p, bool v0, bool v1, int eoff);
 template <>
-__device__ __forceinline__ void col_load<float, true>(ColRaw<float> &r, const float *p, bool v0, bool) {
+__device__ __forceinline__ void col_load<float, true>(ColRaw<float> &r, const float *p, bool v0, bool, int) {
   r.v = v0 ? *reinterpret_cast<const float2 *>(p) : make_float2(0.f, 0.f);
 }
 template <>
-__device__ __forceinline__ void col_load<float, false>(ColRaw<float> &r, const float *p, bool v0, bool v1) {
+__device__ __forceinline__ void col_load<float, false>(ColRaw<float> &r, const float *p, bool v0, bool v1, int) {
   r.v = make_float2(v0 ? p[0] : 0.f, v1 ? p[1] : 0.f);
 }
 template <>
-__device__ __forceinline__ void col_load<uint16_t, true>(ColRaw<uint16_t> &r, const uint16_t *p, bool v0, bool) {
+__device__ __forceinline__ void col_load<uint16_t, true>(ColRaw<uint16_t> &r, const uint16_t *p, bool v0, bool, int) {
   r.lo = v0 ? *reinterpret_cast<const uint32_t *>(p) : 0u;
   r.hi = 0u;
 }
 template <>
-__device__ __forceinline__ void col_load<uint16_t, false>(ColRaw<uint16_t> &r, const uint16_t *p, bool v0, bool v1) {
+__device__ __forceinline__ void col_load<uint16_t, false>(ColRaw<uint16_t> &r, const uint16_t *p, bool v0, bool v1, int) {
   r.lo = v0 ? (uint32_t)p[0] : 0u;
   r.hi = v1 ? (uint32_t)p[1] : 0u;
+}
+template <>
+__device__ __forceinline__ void col_load<zh16, true>(ColRaw<zh16> &r, const zh16 *p, bool, bool, int eoff) {
+  r.h = *reinterpret_cast<const uint32_t *>(p);
+  r.e = reinterpret_cast<const uint8_t *>(p)[eoff];
 }
 template <bool VEC>
 __device__ __forceinline__ float2 col_widen(const ColRaw<float> &r) { return r.v; }
@@ -74,27 +83,51 @@ __device__ __forceinline__ float2 col_widen(const ColRaw<uint16_t> &r) {
   if (VEC) return make_float2(__uint_as_float(r.lo << 16), __uint_as_float(r.lo & 0xffff0000u));
   return make_float2(__uint_as_float(r.lo << 16), __uint_as_float(r.hi << 16));
 }
+template <bool VEC>
+__device__ __forceinline__ float2 col_widen(const ColRaw<zh16> &r) {
+  float2 v;
+  z16_unpack(r.h, z16_up(r.e), v.x, v.y);
+  return v;
+}
 
 template <typename T, bool VEC>
-__device__ __forceinline__ void col_store(T *p, float2 v, bool v0, bool v1);
+__device__ __forceinline__ void col_store(T *p, float2 v, bool v0, bool v1, int eoff);
 template <>
-__device__ __forceinline__ void col_store<float, true>(float *p, float2 v, bool v0, bool) {
+__device__ __forceinline__ void col_store<float, true>(float *p, float2 v, bool v0, bool, int) {
   if (v0) *reinterpret_cast<float2 *>(p) = v;
 }
 template <>
-__device__ __forceinline__ void col_store<float, false>(float *p, float2 v, bool v0, bool v1) {
+__device__ __forceinline__ void col_store<float, false>(float *p, float2 v, bool v0, bool v1, int) {
   if (v0) p[0] = v.x;
   if (v1) p[1] = v.y;
 }
 template <>
-__device__ __forceinline__ void col_store<uint16_t, true>(uint16_t *p, float2 v, bool v0, bool) {
+__device__ __forceinline__ void col_store<uint16_t, true>(uint16_t *p, float2 v, bool v0, bool, int) {
   if (v0) *reinterpret_cast<uint32_t *>(p) = f32_to_bf16(v.x) | (f32_to_bf16(v.y) << 16);
 }
 template <>
-__device__ __forceinline__ void col_store<uint16_t, false>(uint16_t *p, float2 v, bool v0, bool v1) {
+__device__ __forceinline__ void col_store<uint16_t, false>(uint16_t *p, float2 v, bool v0, bool v1, int) {
   if (v0) p[0] = (uint16_t)f32_to_bf16(v.x);
   if (v1) p[1] = (uint16_t)f32_to_bf16(v.y);
 }
+// The eight lanes of a segment find its largest magnitude with three DPP steps (bit patterns of
+// non-negative floats order like unsigned integers); every one of them writes the exponent byte
+// (same address, same value), so that no store is conditional.  Unguarded tiles only: every lane
+// of an aligned group of eight holds a pair of the same segment.
+template <>
+__device__ __forceinline__ void col_store<zh16, true>(zh16 *p, float2 v, bool, bool, int eoff) {
+  uint32_t mx = __float_as_uint(fmaxf(fabsf(v.x), fabsf(v.y)));
+  mx = max(mx, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mx, 0xB1 /* quad_perm [1,0,3,2] */, 0xf, 0xf, false));
+  mx = max(mx, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mx, 0x4E /* quad_perm [2,3,0,1] */, 0xf, 0xf, false));
+  mx = max(mx, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mx, 0x141 /* row_half_mirror */, 0xf, 0xf, false));
+  uint32_t ex = mx >> 23;
+  ex = ex > 253u ? 253u : ex;
+  const float f = z16_down(ex);
+  *reinterpret_cast<uint32_t *>(p) = z16_pack(v.x * f, v.y * f);
+  reinterpret_cast<uint8_t *>(p)[eoff] = (uint8_t)ex;
+}
+template <typename T> struct IsZ16 { static constexpr bool value = false; };
+template <> struct IsZ16<zh16> { static constexpr bool value = true; };
 
 // One stage of compile-time radix B on the tile.  Wave w takes blocks w, w + 4, ...; block
 // (a, bp), a < P / (B sp), bp < sp, couples tile rows a B sp + r sp + bp; its values sit at
@@ -235,6 +268,7 @@ template <typename TI, typename TO, bool VEC, int NRW>
 __global__ __launch_bounds__(kColThreads) void harp_col_kernel(
     const ColPass *__restrict__ passp, const TI *src, int64_t lds_, TO *dst, int64_t ldd,
     int64_t ncols, unsigned ctiles, unsigned ntiles, unsigned tpw) {
+  // (block-scaled half rows: the exponent bytes of a row follow its ncols halves)
   extern __shared__ float2 tile[];   // [P][64] float2, then npar floats of block values
   const ColPass &cp = *passp;
   const int lane = (int)threadIdx.x & 63;
@@ -254,6 +288,7 @@ __global__ __launch_bounds__(kColThreads) void harp_col_kernel(
     int hi, lo;
     int64_t row0, col;
     bool v0, v1;
+    int eoff;   // bytes from a pair of block-scaled halves to its segment's exponent byte
   };
   auto locate = [&](unsigned t) -> TilePos {
     TilePos tp;
@@ -264,6 +299,7 @@ __global__ __launch_bounds__(kColThreads) void harp_col_kernel(
     tp.col = (int64_t)ct * kColCols + 2 * lane;
     tp.v0 = !GUARD || tp.col < ncols;
     tp.v1 = !GUARD || tp.col + 1 < ncols;
+    tp.eoff = (int)((ncols - tp.col) * 2 + (tp.col >> 4));
     return tp;
   };
   // Block values of a tile: value e of the pass's list is image[fix[e] + hi * fa[e] + lo * fb[e]]
@@ -303,14 +339,14 @@ __global__ __launch_bounds__(kColThreads) void harp_col_kernel(
     if (exact) {
 #pragma unroll
       for (int u = 0; u < NR; ++u) {
-        if (!GUARD || wave + kColWaves * u < P) col_load<TI, VEC>(pre[u], rp, tp.v0, tp.v1);
+        if (!GUARD || wave + kColWaves * u < P) col_load<TI, VEC>(pre[u], rp, tp.v0, tp.v1, tp.eoff);
         rp += step;
       }
     } else {
       const TI *rlast = rp + (int64_t)ulast_v * step;
 #pragma unroll
       for (int u = 0; u < NR; ++u) {
-        col_load<TI, VEC>(pre[u], rp, tp.v0, tp.v1);
+        col_load<TI, VEC>(pre[u], rp, tp.v0, tp.v1, tp.eoff);
         rp = (rp + step < rlast) ? rp + step : rlast;
       }
     }
@@ -348,7 +384,7 @@ __global__ __launch_bounds__(kColThreads) void harp_col_kernel(
 #pragma unroll
       for (int u = 0; u < NR; ++u) {
         if (!GUARD || wave + kColWaves * u < P)
-          col_store<TO, VEC>(wp, tp0[u * (kColWaves * 64)], cur.v0, cur.v1);
+          col_store<TO, VEC>(wp, tp0[u * (kColWaves * 64)], cur.v0, cur.v1, cur.eoff);
         wp += wstep;
       }
     } else {
@@ -356,7 +392,7 @@ __global__ __launch_bounds__(kColThreads) void harp_col_kernel(
       int su = 0;
 #pragma unroll
       for (int u = 0; u < NR; ++u) {
-        col_store<TO, VEC>(wp, tp0[su * (kColWaves * 64)], cur.v0, cur.v1);
+        col_store<TO, VEC>(wp, tp0[su * (kColWaves * 64)], cur.v0, cur.v1, cur.eoff);
         wp = (wp + wstep < wlast) ? wp + wstep : wlast;
         su = (su + 1 < ulast_v) ? su + 1 : ulast_v;
       }
@@ -402,13 +438,16 @@ __global__ __launch_bounds__(kColThreads, 2) void harp_colrow_kernel(
   const unsigned ct = blockIdx.x % nct;
   const unsigned t0 = ct * nrt + (blockIdx.x / nct) * tpw;
   const int c0 = (int)ct * 32;
-  int cidx[NCC];
+  // (lanes past the end of a tile row repeat the pairs of its last eight lanes, so that every
+  // aligned group of eight lanes holds one whole 16-column segment)
+  int cidx[NCC], eoff[NCC];
   int64_t gcol[NCC];
 #pragma unroll
   for (int cc = 0; cc < NCC; ++cc) {
     const int i = cc * 64 + lane;
-    cidx[cc] = i < RP ? i : RP - 1;
+    cidx[cc] = i < RP ? i : RP - 8 + (lane & 7);
     gcol[cc] = (int64_t)(cidx[cc] / 16) * Sv + c0 + 2 * (cidx[cc] % 16);
+    eoff[cc] = (int)(((int64_t)BV * Sv - gcol[cc]) * 2 + (gcol[cc] >> 4));
   }
   // block of the row stage for column c0 + j (value v of block q at vparams[v * vnq + q])
   const int j = (int)threadIdx.x & 31, rg = (int)threadIdx.x >> 5;
@@ -448,7 +487,7 @@ __global__ __launch_bounds__(kColThreads, 2) void harp_colrow_kernel(
 #pragma unroll
     for (int u = 0; u < NRW; ++u) {
 #pragma unroll
-      for (int cc = 0; cc < NCC; ++cc) col_load<TI, true>(pre[u][cc], rp + gcol[cc], true, true);
+      for (int cc = 0; cc < NCC; ++cc) col_load<TI, true>(pre[u][cc], rp + gcol[cc], true, true, eoff[cc]);
       rp += step;
     }
   };
@@ -491,7 +530,7 @@ __global__ __launch_bounds__(kColThreads, 2) void harp_colrow_kernel(
     for (int u = 0; u < NRW; ++u) {
 #pragma unroll
       for (int cc = 0; cc < NCC; ++cc)
-        col_store<TO, true>(wp + gcol[cc], tp0[u * (kColWaves * RP) + cidx[cc]], true, true);
+        col_store<TO, true>(wp + gcol[cc], tp0[u * (kColWaves * RP) + cidx[cc]], true, true, eoff[cc]);
       wp += wstep;
     }
   };
@@ -526,14 +565,25 @@ harp_status_t launch_col_tiles(const harp_plan *plan, const ColPass *dpass, cons
   const int64_t grid = (tiles + tpw - 1) / tpw;
   typedef void (*kern_t)(const ColPass *, const TI *, int64_t, TO *, int64_t, int64_t, unsigned,
                          unsigned, unsigned);
-  static const kern_t table[7] = {harp_col_kernel<TI, TO, false, 0>, harp_col_kernel<TI, TO, true, 0>,
-                                  harp_col_kernel<TI, TO, true, 32>, harp_col_kernel<TI, TO, true, 16>,
-                                  harp_col_kernel<TI, TO, true, 8>,  harp_col_kernel<TI, TO, true, 4>,
-                                  harp_col_kernel<TI, TO, true, 2>};
   // unguarded: the variant with the fewest row steps per wave that covers P
   const int which = !fast ? (vec ? 1 : 0)
                           : (hp.P > 64 ? 2 : (hp.P > 32 ? 3 : (hp.P > 16 ? 4 : (hp.P > 8 ? 5 : 6))));
-  const kern_t kern = table[which];
+  kern_t kern = nullptr;
+  if constexpr (IsZ16<TI>::value || IsZ16<TO>::value) {
+    // block-scaled halves exist in the unguarded variants only
+    static const kern_t table[7] = {nullptr, nullptr,
+                                    harp_col_kernel<TI, TO, true, 32>, harp_col_kernel<TI, TO, true, 16>,
+                                    harp_col_kernel<TI, TO, true, 8>,  harp_col_kernel<TI, TO, true, 4>,
+                                    harp_col_kernel<TI, TO, true, 2>};
+    kern = table[which];
+  } else {
+    static const kern_t table[7] = {harp_col_kernel<TI, TO, false, 0>, harp_col_kernel<TI, TO, true, 0>,
+                                    harp_col_kernel<TI, TO, true, 32>, harp_col_kernel<TI, TO, true, 16>,
+                                    harp_col_kernel<TI, TO, true, 8>,  harp_col_kernel<TI, TO, true, 4>,
+                                    harp_col_kernel<TI, TO, true, 2>};
+    kern = table[which];
+  }
+  if (!kern) return HARP_ERR_UNSUPPORTED;
   static thread_local int attr_done_dev[7] = {-1, -1, -1, -1, -1, -1, -1};   // per instantiation
   if (attr_done_dev[which] != plan->device) {
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -560,6 +610,7 @@ harp_status_t launch_col_typed(const harp_plan *plan, const ColPass *dpass, cons
                    ((uintptr_t)src % (2 * ei) == 0) && ((uintptr_t)dst % (2 * eo) == 0);
   const bool shape_ok = vec && hp.P >= kColWaves && hp.P <= kColMaxP;
   const int64_t full = shape_ok ? (ncols / kColCols) * kColCols : 0;
+  if ((IsZ16<TI>::value || IsZ16<TO>::value) && full != ncols) return HARP_ERR_UNSUPPORTED;
   harp_status_t st = HARP_OK;
   if (full > 0)
     st = launch_col_tiles<TI, TO>(plan, dpass, hp, (const TI *)src, lds_, (TO *)dst, ldd, nrows,
@@ -736,6 +787,14 @@ harp_status_t launch_col_pass(const harp_plan *plan, const ColPass *dpass, const
                               harp_dtype_t dt_dst, int64_t nrows, int64_t ncols,
                               hipStream_t stream) {
   if (nrows % hp.P != 0) return HARP_ERR_INVALID_ARG;
+  const bool zs = (int)dt_src == kDtZ16, zd = (int)dt_dst == kDtZ16;
+  if (zs && zd)
+    return launch_col_typed<zh16, zh16>(plan, dpass, hp, src, lds_, dst, ldd, nrows, ncols, stream);
+  if (zs && dt_dst == HARP_BF16)
+    return launch_col_typed<zh16, uint16_t>(plan, dpass, hp, src, lds_, dst, ldd, nrows, ncols, stream);
+  if (zd && dt_src == HARP_BF16)
+    return launch_col_typed<uint16_t, zh16>(plan, dpass, hp, src, lds_, dst, ldd, nrows, ncols, stream);
+  if (zs || zd) return HARP_ERR_UNSUPPORTED;
   if (dt_src == HARP_F32 && dt_dst == HARP_F32)
     return launch_col_typed<float, float>(plan, dpass, hp, src, lds_, dst, ldd, nrows, ncols, stream);
   if (dt_src == HARP_BF16 && dt_dst == HARP_F32)
@@ -743,6 +802,16 @@ harp_status_t launch_col_pass(const harp_plan *plan, const ColPass *dpass, const
   if (dt_src == HARP_F32 && dt_dst == HARP_BF16)
     return launch_col_typed<float, uint16_t>(plan, dpass, hp, src, lds_, dst, ldd, nrows, ncols, stream);
   return launch_col_typed<uint16_t, uint16_t>(plan, dpass, hp, src, lds_, dst, ldd, nrows, ncols, stream);
+}
+
+// A column pass with block-scaled halves on either side runs in the unguarded variants only:
+// whole 128-column tiles, aligned pairs, 4 <= P <= 128.
+bool col_z16_supported(const ColPass &hp, const void *src, int64_t lds_, const void *dst,
+                       int64_t ldd, int64_t nrows, int64_t ncols) {
+  if (ncols % kColCols != 0 || nrows % hp.P != 0) return false;
+  if (hp.P < kColWaves || hp.P > kColMaxP) return false;
+  if (lds_ % 2 || ldd % 2 || (uintptr_t)src % 4 || (uintptr_t)dst % 4) return false;
+  return true;
 }
 
 // The fused launch applies when: the column pass has exactly 32 or 64 rows per tile; the row
@@ -756,8 +825,11 @@ bool colrow_supported(const harp_plan *plan, const ColPass &hp, const PassDesc &
   if (nrows % hp.P != 0) return false;
   if (vp.kind != PASS_SMALL || vp.b < 3 || vp.b > 8) return false;
   if ((int64_t)vp.b * vp.S != ncols || vp.nq != vp.S || vp.S % 32 != 0) return false;
-  const size_t ei = dt_src == HARP_BF16 ? 2 : 4, eo = dt_dst == HARP_BF16 ? 2 : 4;
+  const size_t ei = dt_src == HARP_F32 ? 4 : 2, eo = dt_dst == HARP_F32 ? 4 : 2;
   if (lds_ % 2 || ldd % 2 || (uintptr_t)src % (2 * ei) || (uintptr_t)dst % (2 * eo)) return false;
+  // block-scaled halves: the workspace of a bf16 matrix (the other side bf16 or halves as well)
+  const bool zs = (int)dt_src == kDtZ16, zd = (int)dt_dst == kDtZ16;
+  if ((zs && dt_dst == HARP_F32) || (zd && dt_src == HARP_F32)) return false;
   const size_t shmem = (size_t)hp.P * vp.b * 16 * sizeof(float2) + (size_t)kColMaxPar * sizeof(float);
   return shmem <= (size_t)plan->lds_bytes;
 }
@@ -766,6 +838,13 @@ harp_status_t launch_colrow_pass(const harp_plan *plan, const ColPass *dpass, co
                                  const PassDesc &vp, const void *src, int64_t lds_,
                                  harp_dtype_t dt_src, void *dst, int64_t ldd, harp_dtype_t dt_dst,
                                  int64_t nrows, int64_t ncols, hipStream_t stream) {
+  if ((int)dt_src == kDtZ16 && dt_dst == HARP_BF16)
+    return launch_colrow_typed<zh16, uint16_t>(plan, dpass, hp, vp, src, lds_, dst, ldd, nrows, ncols, stream);
+  if (dt_src == HARP_BF16 && (int)dt_dst == kDtZ16)
+    return launch_colrow_typed<uint16_t, zh16>(plan, dpass, hp, vp, src, lds_, dst, ldd, nrows, ncols, stream);
+  if ((int)dt_src == kDtZ16 && (int)dt_dst == kDtZ16)
+    return launch_colrow_typed<zh16, zh16>(plan, dpass, hp, vp, src, lds_, dst, ldd, nrows, ncols, stream);
+  if ((int)dt_src == kDtZ16 || (int)dt_dst == kDtZ16) return HARP_ERR_UNSUPPORTED;
   if (dt_src == HARP_F32 && dt_dst == HARP_F32)
     return launch_colrow_typed<float, float>(plan, dpass, hp, vp, src, lds_, dst, ldd, nrows, ncols, stream);
   if (dt_src == HARP_BF16 && dt_dst == HARP_F32)

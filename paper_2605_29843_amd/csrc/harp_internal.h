@@ -234,6 +234,7 @@ struct harp_plan {
   std::vector<harp::ColPassHost> colpass[2];
   const int8_t *dev_signs = nullptr;   // device copy of the signs (null: all +1)
   bool orthogonal = true;              // every block satisfies |K^T K - I| <= 1e-5
+  bool f32_only = false;               // HARP_F32_INTERMEDIATES: no block-scaled half intermediates
   bool theta_in_kernel = false;        // some pass carries an int8 image (HARP_THETA_IN_KERNEL)
 };
 
@@ -319,6 +320,9 @@ harp_status_t launch_col_pass(const harp_plan *plan, const ColPass *dpass, const
                               int64_t lds_, harp_dtype_t dt_src, void *dst, int64_t ldd,
                               harp_dtype_t dt_dst, int64_t nrows, int64_t ncols,
                               hipStream_t stream);
+// block-scaled halves (kDtZ16) on either side of a column pass: unguarded tiles only
+bool col_z16_supported(const ColPass &hp, const void *src, int64_t lds_, const void *dst,
+                       int64_t ldd, int64_t nrows, int64_t ncols);
 // column pass fused with the row-side processor's streamed small-radix stage (harp_col.hip)
 bool colrow_supported(const harp_plan *plan, const ColPass &hp, const PassDesc &vp, const void *src,
                       int64_t lds_, harp_dtype_t dt_src, const void *dst, int64_t ldd,

@@ -314,7 +314,7 @@ harp_status_t harp_plan_create_kronecker(harp_plan_t **out, int32_t K, const flo
                                          const float *const *blocks2, const int8_t *signs,
                                          uint32_t flags) {
   if (!out || !table || !radices2 || !blocks2) return HARP_ERR_INVALID_ARG;
-  if (flags & ~(uint32_t)HARP_VALIDATE_ORTHO) return HARP_ERR_INVALID_ARG;
+  if (flags & ~(uint32_t)(HARP_VALIDATE_ORTHO | HARP_F32_INTERMEDIATES)) return HARP_ERR_INVALID_ARG;
   if (K < 2 || n2 < 2 || m2 < 1) return HARP_ERR_INVALID_ARG;
   if (K > HARP_MAX_RADIX || m2 + 1 > HARP_MAX_STAGES) return HARP_ERR_UNSUPPORTED;
   if (n2 > ((int64_t)1 << 24) / K) return HARP_ERR_UNSUPPORTED;

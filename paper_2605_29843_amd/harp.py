@@ -24,7 +24,7 @@ LIB_PATH = os.path.join(_PKG, "libharp.so")
 HARP_OK, HARP_ERR_INVALID_ARG, HARP_ERR_BAD_SCHEDULE, HARP_ERR_NOT_ORTHOGONAL, \
     HARP_ERR_UNSUPPORTED, HARP_ERR_OOM, HARP_ERR_DEVICE = range(7)
 HARP_F32, HARP_BF16 = 0, 1
-HARP_VALIDATE_ORTHO, HARP_BLOCKS_ON_DEVICE, HARP_THETA_IN_KERNEL = 1, 2, 4
+HARP_VALIDATE_ORTHO, HARP_BLOCKS_ON_DEVICE, HARP_THETA_IN_KERNEL, HARP_F32_INTERMEDIATES = 1, 2, 4, 8
 HARP_ALGO_AUTO, HARP_ALGO_GENERIC, HARP_ALGO_FUSED, HARP_ALGO_SPLIT = 0, 1, 2, 3
 HARP_MAX_RADIX, HARP_MAX_STAGES = 64, 64
 HARP_MIXER_IDENTITY, HARP_MIXER_HADAMARD, HARP_MIXER_CUSTOM = 0, 1, 2

@@ -12,6 +12,11 @@ float32 rounding of the path is relative to the summands, not to the result: tho
 `mag` = the same processor applied to |X| with |blocks| (an entrywise bound on the summands of
 every output, from `summand_magnitude`), and the tolerance grows by 2e-6 * mag (a chain of
 m <= 30 float32 stages accumulates at most about m * 6e-8 of it).
+
+`rho` replaces the scale floor where the processor does not act along the rows of the array
+that is compared: in U^T W the vectors that plan_U transforms are the COLUMNS of W, so the
+same bar read along the direction of the transform has rho_j = ||W[:,j]||_2 / sqrt(d_out) (a
+column's norm is preserved by an orthogonal U, so it is known without the full result).
 """
 import numpy as np
 
@@ -38,9 +43,10 @@ def ulp_bf16(y: np.ndarray) -> np.ndarray:
     return np.where(a > 0, 2.0 ** (e - 7), 2.0 ** -133)
 
 
-def tolerance(Yref: np.ndarray, dtype: str) -> np.ndarray:
+def tolerance(Yref: np.ndarray, dtype: str, rho=None) -> np.ndarray:
     d = Yref.shape[1]
-    rho = np.linalg.norm(Yref, axis=1, keepdims=True) / np.sqrt(d)
+    if rho is None:
+        rho = np.linalg.norm(Yref, axis=1, keepdims=True) / np.sqrt(d)
     floor = np.maximum(np.abs(Yref), rho)
     if dtype == "bf16":
         return ulp_bf16(Yref) + 4e-3 * floor
@@ -55,11 +61,11 @@ def summand_magnitude(X, d, radices, blocks, transpose=False):
     return fn(np.abs(np.asarray(X, dtype=np.float64)), d, radices, ab, None)
 
 
-def assert_parity(Y: np.ndarray, Yref: np.ndarray, dtype: str, what: str = "", mag=None):
+def assert_parity(Y: np.ndarray, Yref: np.ndarray, dtype: str, what: str = "", mag=None, rho=None):
     assert Y.shape == Yref.shape, (Y.shape, Yref.shape)
     assert np.all(np.isfinite(Y)), f"{what}: non-finite output"
     err = np.abs(Y - Yref)
-    tol = tolerance(Yref, dtype)
+    tol = tolerance(Yref, dtype, rho)
     if mag is not None:
         tol = tol + 2e-6 * mag
     ratio = err / np.maximum(tol, 1e-300)

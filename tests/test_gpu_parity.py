@@ -525,6 +525,11 @@ def test_half_precision_intermediate_of_split_programs(harp, d, radices):
     assert_parity(Z, Zref, "bf16", "apply_transpose")
     assert not Y[0].any() and not Z[0].any()       # a zero row stays exactly zero
     plan.destroy()
+    # float32 intermediates on request
+    pf = harp.Plan(d, radices, blocks, signs, flags=harp.HARP_F32_INTERMEDIATES)
+    assert not pf.kernel_name(64, harp.HARP_BF16).endswith("_h16")
+    assert_parity(to_host64(harp.harp_apply(pf, to_device(X, "bf16"))), Yref, "bf16", "apply, float32 intermediate")
+    pf.destroy()
 
 
 @pytest.mark.parametrize("d,radices", [(14336, [2] * 11 + [7]), (5120, [2] * 10 + [5]),
@@ -1255,6 +1260,70 @@ def test_rotate_weight_with_streamed_row_stage(harp, dtype, do, ru, di, rv):
     torch.cuda.synchronize()
     err = float((back.float() - Wd.float()).abs().max()) / float(Wd.float().abs().max())
     assert err < (2e-2 if dtype == "bf16" else 1e-4), err
+    pu.destroy()
+    pv.destroy()
+
+
+@pytest.mark.parametrize("do,ru,di,rv", [
+    (1024, [2] * 10, 4096, [2] * 12),        # two column passes; plan_V in one launch (4096)
+    (2048, [8, 8, 8, 4], 2048, [2] * 11),    # radix-8 column passes; plan_V on 2048 coordinates
+    (256, [2] * 8, 1024, [2] * 10),          # plan_V on 1024 coordinates
+    (896, [2] * 7 + [7], 14336, [2] * 11 + [7]),   # row stage fused into a column pass
+    (640, [2] * 7 + [5], 5120, [2] * 10 + [5])])
+def test_rotate_weight_half_precision_workspace(harp, do, ru, di, rv):
+    """bf16 matrices between orthogonal processors travel through the workspace as block-scaled
+    halves: both maps, one-sided calls and in place, rows recomputed by the oracle."""
+    import torch
+    rng = np.random.default_rng(do * 7 + di)
+    bu, bv = gi.make_blocks(do, ru, "orth", rng), gi.make_blocks(di, rv, "orth", rng)
+    su, sv = gi.make_signs(do, rng), gi.make_signs(di, rng)
+    # heavy-tailed entries with a few large columns and rows
+    W = rng.standard_t(3, size=(do, di)) * 0.02
+    W[:, rng.choice(di, 5, replace=False)] *= 20.0
+    W[rng.choice(do, 3, replace=False), :] *= 8.0
+    W = gi.round_to_bf16(W.astype(np.float32))
+    pu, pv = harp.Plan(do, ru, bu, su), harp.Plan(di, rv, bv, sv)
+    say("rotate_weight, half-precision workspace", do, di)
+    Wd = to_device(W, "bf16")
+    out = harp.harp_rotate_weight(pu, pv, Wd)
+    inv = harp.harp_rotate_weight_inverse(pu, pv, Wd)
+    out_u = harp.harp_rotate_weight(pu, None, Wd)
+    inv_u = harp.harp_rotate_weight_inverse(pu, None, Wd)
+    torch.cuda.synchronize()
+    step = max(1, do // 37)
+    rows = sorted(set(list(range(0, do, step)) + [1, do - 1]))
+    E = np.zeros((len(rows), do))
+    E[np.arange(len(rows)), rows] = 1.0
+    W64 = W.astype(np.float64)
+    UtW = ho.apply_transpose_staged(E, do, ru, bu, su) @ W64     # rows of U^T W
+    UW = ho.apply_staged(E, do, ru, bu, su) @ W64                # rows of U W
+    idx = torch.tensor(rows).cuda()
+    assert_parity(to_host64(out[idx]), ho.apply_staged(UtW, di, rv, bv, sv), "bf16", "U^T W V rows")
+    assert_parity(to_host64(inv[idx]), ho.apply_transpose_staged(UW, di, rv, bv, sv), "bf16", "U W V^T rows")
+    # one-sided: plan_U transforms the columns of W, and the bar's scale floor is the column's
+    # (with columns 20 times the others a row's scale says nothing about the entries of that
+    # column; between the launches an entry carries 2^-12 of itself)
+    colscale = np.linalg.norm(W64, axis=0, keepdims=True) / np.sqrt(do)
+    assert_parity(to_host64(out_u[idx]), UtW, "bf16", "U^T W rows", rho=colscale)
+    assert_parity(to_host64(inv_u[idx]), UW, "bf16", "U W rows", rho=colscale)
+    # float32 intermediates on request: the one-sided result then meets the bar with the row's
+    # scale as well
+    pf = harp.Plan(do, ru, bu, su, flags=harp.HARP_F32_INTERMEDIATES)
+    out_f = harp.harp_rotate_weight(pf, None, Wd)
+    torch.cuda.synchronize()
+    assert_parity(to_host64(out_f[idx]), UtW, "bf16", "U^T W rows, float32 workspace")
+    pf.destroy()
+    # the Frobenius norm is preserved
+    nw = float(torch.linalg.matrix_norm(Wd.float()))
+    for t in (out, inv, out_u, inv_u):
+        assert abs(float(torch.linalg.matrix_norm(t.float())) - nw) / nw < 2e-3
+    # in place
+    W2 = Wd.clone()
+    harp.harp_rotate_weight(pu, pv, W2, W2)
+    W3 = Wd.clone()
+    harp.harp_rotate_weight_inverse(pu, None, W3, W3)
+    torch.cuda.synchronize()
+    assert torch.equal(W2, out) and torch.equal(W3, inv_u)
     pu.destroy()
     pv.destroy()
 
