@@ -129,6 +129,22 @@ __device__ __forceinline__ void col_store<zh16, true>(zh16 *p, float2 v, bool, b
 template <typename T> struct IsZ16 { static constexpr bool value = false; };
 template <> struct IsZ16<zh16> { static constexpr bool value = true; };
 
+// Workgroup id -> logical id such that G logically consecutive workgroups (neighbouring column
+// positions of the same rows: they share 128-byte lines -- of exponent bytes, and of data where a
+// tile row is shorter than a line) run on one XCD next to each other in dispatch order, so the
+// line is fetched from device memory once, into that XCD's L2 (workgroup b runs on XCD b mod 8).
+// The grid is a multiple of 8 G (checked by the launcher); G == 0: identity.
+__device__ __forceinline__ unsigned xcd_grouped(unsigned b, unsigned G) {
+  if (G == 0) return b;
+  const unsigned xcd = b & 7u, k = b >> 3;
+  return ((k / G) * 8u + xcd) * G + (k % G);
+}
+inline unsigned xcd_group_size(int64_t positions, int64_t grid, int cap) {
+  for (int g = cap; g >= 2; g >>= 1)
+    if (positions % g == 0 && grid % (8 * g) == 0) return (unsigned)g;
+  return 0;
+}
+
 // One stage of compile-time radix B on the tile.  Wave w takes blocks w, w + 4, ...; block
 // (a, bp), a < P / (B sp), bp < sp, couples tile rows a B sp + r sp + bp; its values sit at
 // prm[(a sp + bp) * BBP ..] (BBP = B * B rounded up to a multiple of 4).
@@ -256,7 +272,7 @@ __device__ __forceinline__ void col_ops(float2 *tile, const float *prm, const Co
   }
 }
 
-// A workgroup walks over `tpw` consecutive tiles; the rows of the next tile are requested into
+// A workgroup walks over `tpw` row tiles at one column position; the rows of the next tile are requested into
 // registers (up to 32 rows per wave) before the work on the current one starts.
 // NRW > 0 (fast variant): 4 <= P <= 4 NRW, every column tile is full and pairs of columns are
 // aligned; every wave takes NRW row steps (those past its last row repeat that row) and no
@@ -267,7 +283,7 @@ __device__ __forceinline__ void col_ops(float2 *tile, const float *prm, const Co
 template <typename TI, typename TO, bool VEC, int NRW>
 __global__ __launch_bounds__(kColThreads) void harp_col_kernel(
     const ColPass *__restrict__ passp, const TI *src, int64_t lds_, TO *dst, int64_t ldd,
-    int64_t ncols, unsigned ctiles, unsigned ntiles, unsigned tpw) {
+    int64_t ncols, unsigned ctiles, unsigned ntiles, unsigned tpw, unsigned xg) {
   // (block-scaled half rows: the exponent bytes of a row follow its ncols halves)
   extern __shared__ float2 tile[];   // [P][64] float2, then npar floats of block values
   const ColPass &cp = *passp;
@@ -292,7 +308,9 @@ __global__ __launch_bounds__(kColThreads) void harp_col_kernel(
   };
   auto locate = [&](unsigned t) -> TilePos {
     TilePos tp;
-    const unsigned ct = t % ctiles, rt = t / ctiles;   // rt = hi * S + lo
+    // tile t = (run * ctiles + ct) * tpw + step: a workgroup stays at one column position and
+    // walks down tpw row tiles; consecutive workgroups take neighbouring column positions
+    const unsigned u = t / tpw, ct = u % ctiles, rt = (u / ctiles) * tpw + t % tpw;   // rt = hi * S + lo
     tp.hi = (int)(rt / (unsigned)S);
     tp.lo = (int)(rt % (unsigned)S);
     tp.row0 = (int64_t)tp.hi * P * S + tp.lo;
@@ -352,7 +370,7 @@ __global__ __launch_bounds__(kColThreads) void harp_col_kernel(
     }
   };
 
-  const unsigned t0 = blockIdx.x * tpw;
+  const unsigned t0 = xcd_grouped(blockIdx.x, xg) * tpw;
   const unsigned t1 = (t0 + tpw < ntiles) ? t0 + tpw : ntiles;
   if (t0 >= t1) return;
   // registers -> LDS: rows and block values of the tile whose request is outstanding
@@ -424,7 +442,8 @@ __global__ __launch_bounds__(kColThreads) void harp_col_kernel(
 template <typename TI, typename TO, int BV, int NRW>
 __global__ __launch_bounds__(kColThreads, 2) void harp_colrow_kernel(
     const ColPass *__restrict__ passp, const TI *src, int64_t lds_, TO *dst, int64_t ldd,
-    const float *__restrict__ vparams, int vnq, int Sv, unsigned nrt, unsigned nct, unsigned tpw) {
+    const float *__restrict__ vparams, int vnq, int Sv, unsigned nrt, unsigned nct, unsigned tpw,
+    unsigned xg) {
   extern __shared__ float2 tile[];   // [P][BV * 16] float2, then the block values of the column steps
   constexpr int RP = BV * 16, NCC = (RP + 63) / 64;
   const ColPass &cp = *passp;
@@ -435,8 +454,9 @@ __global__ __launch_bounds__(kColThreads, 2) void harp_colrow_kernel(
   // Workgroup -> (column position ct, tpw consecutive row tiles).  Consecutive workgroups take
   // consecutive column positions, so the 128-byte pieces that are in flight at the same time
   // are neighbours in memory; tiles are numbered t = ct * nrt + rt inside the kernel.
-  const unsigned ct = blockIdx.x % nct;
-  const unsigned t0 = ct * nrt + (blockIdx.x / nct) * tpw;
+  const unsigned wg = xcd_grouped(blockIdx.x, xg);
+  const unsigned ct = wg % nct;
+  const unsigned t0 = ct * nrt + (wg / nct) * tpw;
   const int c0 = (int)ct * 32;
   // (lanes past the end of a tile row repeat the pairs of its last eight lanes, so that every
   // aligned group of eight lanes holds one whole 16-column segment)
@@ -562,9 +582,14 @@ harp_status_t launch_col_tiles(const harp_plan *plan, const ColPass *dpass, cons
   const int64_t slots = (int64_t)(plan->num_cu > 0 ? plan->num_cu : 256) * 2;
   int64_t tpw = tiles / (slots * 4);
   tpw = std::max<int64_t>(1, std::min<int64_t>(tpw, 16));
-  const int64_t grid = (tiles + tpw - 1) / tpw;
+  // (a divisor of the number of row tiles: every workgroup walks down whole runs)
+  const int64_t nrt = nrows / hp.P;
+  while (nrt % tpw != 0) --tpw;
+  const int64_t grid = tiles / tpw;
+  // 16 neighbouring column tiles share a 128-byte line of exponent bytes
+  const unsigned xg = xcd_group_size(ctiles, grid, 16);
   typedef void (*kern_t)(const ColPass *, const TI *, int64_t, TO *, int64_t, int64_t, unsigned,
-                         unsigned, unsigned);
+                         unsigned, unsigned, unsigned);
   // unguarded: the variant with the fewest row steps per wave that covers P
   const int which = !fast ? (vec ? 1 : 0)
                           : (hp.P > 64 ? 2 : (hp.P > 32 ? 3 : (hp.P > 16 ? 4 : (hp.P > 8 ? 5 : 6))));
@@ -595,7 +620,7 @@ harp_status_t launch_col_tiles(const harp_plan *plan, const ColPass *dpass, cons
     attr_done_dev[which] = plan->device;
   }
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kColThreads), shmem, stream, dpass, src, lds_,
-                     dst, ldd, ncols, (unsigned)ctiles, (unsigned)tiles, (unsigned)tpw);
+                     dst, ldd, ncols, (unsigned)ctiles, (unsigned)tiles, (unsigned)tpw, xg);
   return hipGetLastError() == hipSuccess ? HARP_OK : HARP_ERR_DEVICE;
 }
 
@@ -634,8 +659,10 @@ harp_status_t launch_colrow_bv(const harp_plan *plan, const ColPass *dpass, cons
     if (nrt % c == 0) { tpw = c; break; }
   const int64_t grid = (nrt / tpw) * nct;
   if (grid <= 0 || grid > 0x7fffffff) return HARP_ERR_UNSUPPORTED;
+  // 2 neighbouring column positions share a line of halves, 64 a line of exponent bytes
+  const unsigned xg = xcd_group_size(nct, grid, 64);
   typedef void (*kern_t)(const ColPass *, const TI *, int64_t, TO *, int64_t, const float *, int, int,
-                         unsigned, unsigned, unsigned);
+                         unsigned, unsigned, unsigned, unsigned);
   const kern_t kern = hp.P == 64 ? (kern_t)harp_colrow_kernel<TI, TO, BV, 16>
                                  : (kern_t)harp_colrow_kernel<TI, TO, BV, 8>;
   static thread_local int attr_done_dev[2] = {-1, -1};   // per instantiation
@@ -651,7 +678,7 @@ harp_status_t launch_colrow_bv(const harp_plan *plan, const ColPass *dpass, cons
   }
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kColThreads), shmem, stream, dpass, src, lds_,
                      dst, ldd, vp.params, (int)vp.nq, (int)vp.S, (unsigned)nrt, (unsigned)nct,
-                     (unsigned)tpw);
+                     (unsigned)tpw, xg);
   (void)ncols;
   return hipGetLastError() == hipSuccess ? HARP_OK : HARP_ERR_DEVICE;
 }
