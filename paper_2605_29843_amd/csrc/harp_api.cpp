@@ -1342,6 +1342,56 @@ harp_status_t harp::plan_create_impl(harp_plan **out, int64_t d, int32_t m, cons
         st = HARP_ERR_DEVICE;
         break;
       }
+      // Gradient path: a stage of radix 9..64 (and its transpose, for the gradient passed back)
+      // runs on the matrix cores like the streamed stage of a split program, from the same
+      // dense blocks as the vector kernels (float32 operand tiles; the image also carries the
+      // bf16 tiles the kernel's other variant reads).
+      if (dir == DIR_FWD) {
+        plan->grad_mfma[0].assign(eff.size(), PassDesc{});
+        plan->grad_mfma[1].assign(eff.size(), PassDesc{});
+        for (size_t t = 0; t < eff.size() && st == HARP_OK; ++t) {
+          const StageEff &se = eff[t];
+          const int b = se.b;
+          if (b < 9 || b > HARP_MAX_RADIX || se.s % 16 != 0) continue;
+          const int64_t nq = d / b;
+          const int KT = (b + 15) / 16;
+          const size_t per = (size_t)KT * KT * 2 * 64 * 4, per32 = (size_t)KT * KT * 64 * 4;
+          std::vector<uint16_t> a(per * nq + 2 * per32 * nq);
+          std::vector<float> kt((size_t)b * b);
+          for (int tr = 0; tr < 2 && st == HARP_OK; ++tr) {
+            float *a32 = reinterpret_cast<float *>(a.data() + per * nq);
+            for (int64_t q = 0; q < nq; ++q) {
+              const float *K = se.dense.data() + (size_t)q * b * b;
+              if (tr)
+                for (int r = 0; r < b; ++r)
+                  for (int r2 = 0; r2 < b; ++r2) kt[(size_t)r * b + r2] = K[(size_t)r2 * b + r];
+              pack_mfma_block(tr ? kt.data() : K, b, a.data() + per * q, a32 + per32 * q);
+            }
+            void *da = nullptr;
+            if (hipMalloc(&da, a.size() * 2) != hipSuccess) {
+              st = HARP_ERR_OOM;
+              break;
+            }
+            plan->dev_allocs.push_back(da);
+            if (hipMemcpy(da, a.data(), a.size() * 2, hipMemcpyHostToDevice) != hipSuccess) {
+              st = HARP_ERR_DEVICE;
+              break;
+            }
+            PassDesc pd{};
+            pd.kind = PASS_GENERIC;
+            pd.b = b;
+            pd.k = 1;
+            pd.P = b;
+            pd.S = (int32_t)se.s;
+            pd.nq = (int32_t)nq;
+            pd.nqp = (int32_t)nq;
+            pd.V = b * b;
+            pd.aux = da;
+            plan->grad_mfma[tr][t] = pd;
+          }
+        }
+        if (st != HARP_OK) break;
+      }
       if (!col_ok || !build_col_passes(plan, (Direction)dir, plan->colpass[dir])) {
         plan->colpass[dir].clear();
         continue;

@@ -218,6 +218,153 @@ __global__ __launch_bounds__(kGradThreads) void harp_grad_dk_big_kernel(
     if (r < b) partial[((size_t)blockIdx.y * (b * b) + r * b + r2) * D + c] = acc[r];
 }
 
+// The same sums on the matrix cores: dK[c] = sum over rows of x[idx]^T g[idx] is a b x rows x b
+// product per block (v_mfma_f32_16x16x4_f32, unsplit float32 operands: the k index is the row).
+// Needs 16 consecutive blocks to be 16 consecutive coordinates (s a multiple of 16).  A workgroup
+// of 16 waves owns 16 consecutive blocks and one row chunk and walks down its rows 8 at a time:
+// coalesced 16-byte loads of x and g (next step prefetched in registers) -> two LDS tiles
+// [r][block][row] -> wave w multiplies the tiles of its block, KT x KT accumulator tiles in
+// registers for the whole chunk.  At the end the accumulators pass through LDS tile by tile
+// so that the partial sums leave in runs of 16 consecutive blocks (64 bytes).  Rows past the end
+// of the chunk enter as zeros.  Workgroups that share 128-byte lines (two neighbouring block
+// tiles) are numbered onto one XCD.
+constexpr int kDkRows = 8;                  // rows per step
+constexpr int kDkLS = kDkRows + 1;          // LDS stride between consecutive blocks
+constexpr int kDkJS = 16 * kDkLS + 4;       // LDS stride between consecutive r
+
+template <int KT>
+__global__ __launch_bounds__(1024) void harp_grad_dk_mfma_kernel(
+    const float *__restrict__ X, const float *__restrict__ Gm, int64_t ld, int64_t n, int rows,
+    int D, int s, int b, int gx, int paired, float *__restrict__ partial) {
+  typedef float f4v __attribute__((ext_vector_type(4)));
+  constexpr int MAXG = (kDkRows * 16 * KT * 4 + 1023) / 1024;
+  constexpr int TILE = 16 * KT * kDkJS;
+  __shared__ float lds[2 * TILE];
+  float *tx = lds, *tg = lds + TILE;
+  const int tid = threadIdx.x;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l = tid & 63, g = l >> 4, c16 = l & 15;
+  unsigned wg = blockIdx.x;
+  if (paired) {
+    const unsigned xcd = wg & 7u, k = wg >> 3;
+    wg = ((k >> 1) * 8u + xcd) * 2u + (k & 1u);
+  }
+  const int qx = (int)(wg % (unsigned)gx), chunk = (int)(wg / (unsigned)gx);
+  const int q0 = qx * 16;
+  const int64_t base = (int64_t)(q0 / s) * b * s + q0 % s;
+  const int64_t r_begin = (int64_t)chunk * rows;
+  const int64_t r_end = (r_begin + rows < n) ? r_begin + rows : n;
+
+  const int ngroups = kDkRows * b * 4;   // (row, r, quarter of the 16 blocks) per step
+  unsigned off[MAXG];
+  int grow[MAXG], slot[MAXG];
+#pragma unroll
+  for (int u = 0; u < MAXG; ++u) {
+    const int gi = (tid + u * 1024) % ngroups;
+    const int lo4 = gi & 3, rem = gi >> 2;
+    const int row = rem & (kDkRows - 1), j = rem / kDkRows;
+    grow[u] = row;
+    off[u] = (unsigned)(row * (int)ld + j * s + lo4 * 4);
+    slot[u] = j * kDkJS + (lo4 * 4) * kDkLS + row;
+  }
+  float4 px[MAXG], pg[MAXG];
+  auto fetch = [&](int64_t r0, int left) {
+    const float *xc = X + r0 * ld + base, *gc = Gm + r0 * ld + base;
+    if (left >= kDkRows) {
+#pragma unroll
+      for (int u = 0; u < MAXG; ++u) {
+        px[u] = *reinterpret_cast<const float4 *>(xc + off[u]);
+        pg[u] = *reinterpret_cast<const float4 *>(gc + off[u]);
+      }
+    } else {
+#pragma unroll
+      for (int u = 0; u < MAXG; ++u) {
+        px[u] = pg[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (grow[u] < left) {
+          px[u] = *reinterpret_cast<const float4 *>(xc + off[u]);
+          pg[u] = *reinterpret_cast<const float4 *>(gc + off[u]);
+        }
+      }
+    }
+  };
+  auto commit = [&]() {
+#pragma unroll
+    for (int u = 0; u < MAXG; ++u) {
+      float *a = tx + slot[u], *c = tg + slot[u];
+      a[0] = px[u].x; a[kDkLS] = px[u].y; a[2 * kDkLS] = px[u].z; a[3 * kDkLS] = px[u].w;
+      c[0] = pg[u].x; c[kDkLS] = pg[u].y; c[2 * kDkLS] = pg[u].z; c[3 * kDkLS] = pg[u].w;
+    }
+  };
+  f4v acc[KT][KT];
+#pragma unroll
+  for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < KT; ++nt) acc[mt][nt] = (f4v){0.f, 0.f, 0.f, 0.f};
+
+  if (r_begin < r_end) {
+    fetch(r_begin, (int)(r_end - r_begin));
+    for (int64_t r0 = r_begin; r0 < r_end; r0 += kDkRows) {
+      commit();
+      __syncthreads();
+      const int64_t rn = r0 + kDkRows;
+      if (rn < r_end) fetch(rn, (int)(r_end - rn));
+#pragma unroll
+      for (int ks = 0; ks < kDkRows / 4; ++ks) {
+        float a[KT], bv[KT];
+#pragma unroll
+        for (int t = 0; t < KT; ++t) {
+          const int j = 16 * t + c16;
+          const int at = (j < b ? j : 0) * kDkJS + w * kDkLS + 4 * ks + g;
+          a[t] = (j < b) ? tx[at] : 0.f;
+          bv[t] = (j < b) ? tg[at] : 0.f;
+        }
+#pragma unroll
+        for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+          for (int nt = 0; nt < KT; ++nt)
+            acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[mt], bv[nt], acc[mt][nt], 0, 0, 0);
+      }
+      __syncthreads();   // every wave has read its operands: the tiles are free again
+    }
+  }
+  // accumulator tile (mt, nt) of all 16 blocks -> LDS [m][n][block] -> 64-byte runs
+  float *so = lds;
+  const int e = tid >> 2, quarter = tid & 3;
+  const int em = e >> 4, en = e & 15;
+#pragma unroll
+  for (int mt = 0; mt < KT; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < KT; ++nt) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) so[((4 * g + i) * 16 + c16) * 16 + w] = acc[mt][nt][i];
+      __syncthreads();
+      const int r = 16 * mt + em, r2 = 16 * nt + en;
+      if (r < b && r2 < b) {
+        const float4 v = *reinterpret_cast<const float4 *>(so + e * 16 + 4 * quarter);
+        *reinterpret_cast<float4 *>(partial + ((size_t)chunk * (b * b) + r * b + r2) * D + q0 + 4 * quarter) = v;
+      }
+      __syncthreads();
+    }
+}
+
+template <int KT>
+static void launch_dk_mfma(const float *X, const float *Gm, int64_t ld, int64_t n, int rows, int nchunks,
+                           int D, int s, int b, float *partial, hipStream_t st) {
+  const int gx = D / 16;
+  const int64_t total = (int64_t)gx * nchunks;
+  const int paired = (gx % 2 == 0) && (total % 16 == 0);
+  hipLaunchKernelGGL((harp_grad_dk_mfma_kernel<KT>), dim3((unsigned)total), dim3(1024), 0, st, X, Gm, ld, n,
+                     rows, D, s, b, gx, paired, partial);
+}
+
+static bool dk_mfma_supported(int b, int s, int D, const void *X, const void *Gm, int64_t ld,
+                              const void *partial, int64_t nchunks) {
+  if (b < 9 || b > 64 || s % 16 != 0 || D % 16 != 0) return false;
+  if (ld % 4 != 0 || ld >= ((int64_t)1 << 26)) return false;
+  if ((uintptr_t)X % 16 || (uintptr_t)Gm % 16 || (uintptr_t)partial % 16) return false;
+  return (int64_t)(D / 16) * nchunks <= 0x7fffffff;
+}
+
 // the instantiation whose BMAX covers radix b
 #define HARP_GRAD_BIG(b, CALL)            \
   do {                                    \
@@ -653,6 +800,11 @@ harp_status_t launch_grad(const harp_plan *plan, const void *X, int64_t ldx, con
         if (seg[i].k == 3) HARP_GRAD_FWD_RUN(3);
         else HARP_GRAD_FWD_RUN(2);
 #undef HARP_GRAD_FWD_RUN
+      } else if (cs.b > 8 && mfma_pass_supported(plan->grad_mfma[0][seg[i].t0], in, d, out, d)) {
+        // the stage on the matrix cores (float32 operands), as in a split program
+        if (launch_mfma_pass(plan, plan->grad_mfma[0][seg[i].t0], in, d, HARP_F32, out, d, HARP_F32, n,
+                             false, st) != HARP_OK)
+          return HARP_ERR_DEVICE;
       } else if (cs.b > 8) {
         const int D = (int)(d / cs.b);
 #define HARP_GRAD_BIG_FWD(BM)                                                                     \
@@ -701,13 +853,29 @@ harp_status_t launch_grad(const harp_plan *plan, const void *X, int64_t ldx, con
       } else if (cs.b > 8) {
         const int D = (int)(d / cs.b);
         const dim3 grid((D + 63) / 64, nchunks_big, (cs.b + 3) / 4);
+        // gradient passed back: the transposed blocks on the matrix cores where the stage allows
+        const bool mf = mfma_pass_supported(plan->grad_mfma[1][seg[i].t0], g, d, g2, d);
+        const bool dkm = dk_mfma_supported(cs.b, cs.s, D, in, g, d, partial, nchunks_big);
+        if (dkm) {
+          switch ((cs.b + 15) / 16) {
+            case 1: launch_dk_mfma<1>(in, g, d, n, rows_big, nchunks_big, D, cs.s, cs.b, partial, st); break;
+            case 2: launch_dk_mfma<2>(in, g, d, n, rows_big, nchunks_big, D, cs.s, cs.b, partial, st); break;
+            case 3: launch_dk_mfma<3>(in, g, d, n, rows_big, nchunks_big, D, cs.s, cs.b, partial, st); break;
+            default: launch_dk_mfma<4>(in, g, d, n, rows_big, nchunks_big, D, cs.s, cs.b, partial, st); break;
+          }
+        }
 #define HARP_GRAD_BIG_BWD(BM)                                                                      \
-  hipLaunchKernelGGL((harp_grad_dk_big_kernel<BM>), grid, dim3(kGradThreads), 0, st, in, g, d, n,  \
-                     rows_big, D, cs.s, cs.b, partial);                                            \
-  hipLaunchKernelGGL((harp_grad_apply_big_kernel<BM, true>), grid, dim3(kGradThreads), 0, st, g,   \
-                     g2, d, n, rows_big, cs.blocks, D, cs.s, cs.b)
+  if (!dkm)                                                                                        \
+    hipLaunchKernelGGL((harp_grad_dk_big_kernel<BM>), grid, dim3(kGradThreads), 0, st, in, g, d, n, \
+                       rows_big, D, cs.s, cs.b, partial);                                          \
+  if (!mf)                                                                                         \
+    hipLaunchKernelGGL((harp_grad_apply_big_kernel<BM, true>), grid, dim3(kGradThreads), 0, st, g, \
+                       g2, d, n, rows_big, cs.blocks, D, cs.s, cs.b)
         HARP_GRAD_BIG(cs.b, HARP_GRAD_BIG_BWD);
 #undef HARP_GRAD_BIG_BWD
+        if (mf && launch_mfma_pass(plan, plan->grad_mfma[1][seg[i].t0], g, d, HARP_F32, g2, d, HARP_F32, n,
+                                   false, st) != HARP_OK)
+          return HARP_ERR_DEVICE;
         std::swap(g, g2);
       } else {
         const int D = (int)(d / cs.b);

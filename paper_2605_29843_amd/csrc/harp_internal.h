@@ -231,6 +231,10 @@ struct harp_plan {
   int64_t tied_n2 = 0;
   // column-mode image (every plan) and passes (empty when some radix exceeds 8) per direction
   std::vector<harp::ColStage> col[2];
+  // gradient path, stages of radix 9..64 whose stride is a multiple of 16: the blocks of
+  // col[DIR_FWD][t] ([0][t]) and their transposes ([1][t]) as matrix-core operand tiles
+  // (aux == nullptr: none)
+  std::vector<harp::PassDesc> grad_mfma[2];
   std::vector<harp::ColPassHost> colpass[2];
   const int8_t *dev_signs = nullptr;   // device copy of the signs (null: all +1)
   bool orthogonal = true;              // every block satisfies |K^T K - I| <= 1e-5

@@ -49,7 +49,11 @@ def assert_dk_parity(dK, ref, X, G, what):
     (4096, [2] * 12, 130, "orth"),
     # a stage of radix above 8 (leftover prime): first, last, in the middle, with signs on it
     (44, [4, 11], 9, "generic"), (344, [2, 2, 2, 43], 70, "orth"), (572, [13, 4, 11], 21, "generic"),
-    (1376, [2] * 5 + [43], 130, "orth"), (128, [2, 64], 5, "generic")])
+    (1376, [2] * 5 + [43], 130, "orth"), (128, [2, 64], 5, "generic"),
+    # ... at a stride that is a multiple of 16, in the middle: the stage and the gradient passed
+    # back through it both run on the matrix cores
+    (704, [4, 4, 11, 2, 2], 50, "generic"), (1408, [2] * 4 + [11, 8], 33, "orth"),
+    (320, [4, 4, 20], 75, "generic"), (1024, [2, 2, 2, 2, 64], 12, "orth")])
 def test_grad_blocks_matches_the_oracle(harp, d, radices, n, kind, dtype):
     import torch
     rng = np.random.default_rng(d + n)
