@@ -379,6 +379,13 @@ def main():
             gb = 4 * do * di * 2 / (us * 1e-6) / 1e9   # two sides, each reads and writes W once
             print(f"[extra] rotate_weight 8192 x 28672 bf16: {us:.0f} us, {gb:.0f} GB/s "
                   f"({gb / HBM_PEAK_GBS:.1%})", file=sys.stderr, flush=True)
+            e0.record(stream)
+            for _ in range(10):
+                harp.harp_rotate_weight_inverse(pu, pv, Wm, Wo, ws, stream)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / 10
+            print(f"[extra] rotate_weight_inverse 8192 x 28672 bf16: {us:.0f} us", file=sys.stderr, flush=True)
         except Exception as e:  # noqa: BLE001
             print(f"[extra] rotate_weight: {e}", file=sys.stderr, flush=True)
         try:   # gradient with respect to the blocks at the benchmark shape
@@ -399,6 +406,29 @@ def main():
                   f"({gb / HBM_PEAK_GBS:.1%})", file=sys.stderr, flush=True)
         except Exception as e:  # noqa: BLE001
             print(f"[extra] grad_blocks: {e}", file=sys.stderr, flush=True)
+        try:   # the same at 2048 x 11008 (eight radix-2 stages and the radix-43 stage)
+            dg, rg = 11008, [2] * 8 + [43]
+            bg, sg = gi.processor(dg, rg, config=2, salt=3)
+            pg = harp.Plan(dg, rg, bg, sg)
+            Xg = torch.randn(2048, dg, device="cuda").to(torch.bfloat16)
+            Gg = torch.randn(2048, dg, device="cuda").to(torch.bfloat16)
+            wsg = torch.empty(harp.harp_grad_blocks_workspace_size(pg, 2048), dtype=torch.uint8, device="cuda")
+            for _ in range(5):
+                harp.harp_grad_blocks(pg, Xg, Gg, True, wsg, stream)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(20):
+                harp.harp_grad_blocks(pg, Xg, Gg, True, wsg, stream)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / 20
+            gb = (3 * 2048 * dg * 2 + sum(dg * b for b in rg) * 4) / (us * 1e-6) / 1e9
+            print(f"[extra] grad_blocks 2048 x {dg} bf16: {us:.0f} us, {gb:.0f} GB/s algorithmic "
+                  f"({gb / HBM_PEAK_GBS:.1%})", file=sys.stderr, flush=True)
+            pg.destroy()
+        except Exception as e:  # noqa: BLE001
+            print(f"[extra] grad_blocks 11008: {e}", file=sys.stderr, flush=True)
     if args.shapes:
         r2 = {4096: [2] * 12, 5120: [2] * 10 + [5], 8192: [2] * 13, 11008: [2] * 8 + [43],
               13824: [2] * 9 + [3, 3, 3], 14336: [2] * 11 + [7], 28672: [2] * 12 + [7]}
