@@ -18,6 +18,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <type_traits>
 
 #include "harp_internal.h"
 
@@ -431,6 +432,154 @@ __global__ __launch_bounds__(kColThreads) void harp_col_kernel(
   work(t1 - 1);
 }
 
+// ------------------------------------------------------------------------------------------
+// Column pass of LOGP consecutive radix-2 stages on the tile-row bits 0 .. LOGP-1 (ascending, or
+// descending with DESC), P = 2^LOGP rows per tile, with the tile in REGISTERS: a wave owns
+// NR = P / 4 rows of the tile (two columns per lane) in one of two layouts,
+//     layout A: tile rows w NR + u   (the wave index is the top two bits: stages on bits
+//               0 .. LOGP-3 pair rows of the same wave),
+//     layout B: tile rows w + 4 u    (the wave index is the low two bits: stages on bits
+//               2 .. LOGP-1 pair rows of the same wave),
+// so an ascending pass runs LOGP-2 stages in layout A, exchanges the tile through LDS once, and
+// runs the last two stages in layout B (a descending pass: LOGP-2 stages in layout B, exchange,
+// two in layout A).  One LDS round trip per tile instead of one per group of three stages plus
+// the two that staged the tile in and out, three barriers per tile instead of five.  The block
+// values travel with the tile as in harp_col_kernel and are read from LDS at wave-uniform
+// addresses.  Unguarded tiles only (whole 128-column tiles, aligned pairs).
+struct Col2Stages {
+  int32_t poff[8];   // offset of stage `bit`'s block values in the tile's list (floats)
+};
+
+// one stage on bit UB of the in-wave row index; block of the pair whose lower row is u0:
+// number qa + qs * (u0 with bit UB removed), four values k00 k01 k10 k11 at prm4[..]
+template <int NR, int UB>
+__device__ __forceinline__ void col2_stage(float2 (&x)[NR], const float4 *prm4, int qa, int qs) {
+#pragma unroll
+  for (int p = 0; p < NR / 2; ++p) {
+    const int u0 = ((p >> UB) << (UB + 1)) | (p & ((1 << UB) - 1)), u1 = u0 | (1 << UB);
+    const float4 k = prm4[qa + qs * p];   // p is u0 with bit UB removed
+    const float2 a = x[u0], b = x[u1];
+    x[u0] = make_float2(fmaf(b.x, k.z, a.x * k.x), fmaf(b.y, k.z, a.y * k.x));
+    x[u1] = make_float2(fmaf(b.x, k.w, a.x * k.y), fmaf(b.y, k.w, a.y * k.y));
+  }
+}
+
+// the stages of one layout: FIRST .. FIRST + N - 1 ascending, or FIRST down to FIRST - N + 1
+template <int NR, int LOGP, bool LAYOUT_B, int FIRST, int N, bool DESC>
+__device__ __forceinline__ void col2_stages(float2 (&x)[NR], const float *prm, const Col2Stages &cs,
+                                            int wave) {
+  if constexpr (N > 0) {
+    constexpr int bit = FIRST;
+    constexpr int UB = LAYOUT_B ? bit - 2 : bit;
+    const float4 *prm4 = reinterpret_cast<const float4 *>(prm + cs.poff[bit]);
+    if constexpr (LAYOUT_B) col2_stage<NR, UB>(x, prm4, wave, 4);
+    else col2_stage<NR, UB>(x, prm4, wave * (NR / 2), 1);
+    // one stage at a time: hoisting the next stage's block values above this stage's arithmetic
+    // costs up to 64 registers, which the 128-row instances do not have
+    __builtin_amdgcn_sched_barrier(0);
+    col2_stages<NR, LOGP, LAYOUT_B, DESC ? FIRST - 1 : FIRST + 1, N - 1, DESC>(x, prm, cs, wave);
+  }
+}
+
+template <typename TI, typename TO, int LOGP, bool DESC>
+__global__ __launch_bounds__(kColThreads) void harp_col2_kernel(
+    const ColPass *__restrict__ passp, const TI *src, int64_t lds_, TO *dst, int64_t ldd,
+    int64_t ncols, unsigned ctiles, unsigned ntiles, unsigned tpw, unsigned xg, Col2Stages cs) {
+  constexpr int P = 1 << LOGP, NR = P / kColWaves;
+  extern __shared__ float2 tile[];   // [P][64] float2, then npar floats of block values
+  const ColPass &cp = *passp;
+  const int lane = (int)threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+  const int S = cp.S;
+  // first and second layout of a tile: ascending A then B, descending B then A
+  constexpr bool kFirstB = DESC;
+  struct TilePos {
+    int hi, lo;
+    int64_t row0, col;
+    int eoff;
+  };
+  auto locate = [&](unsigned t) -> TilePos {
+    TilePos tp;
+    const unsigned u = t / tpw, ct = u % ctiles, rt = (u / ctiles) * tpw + t % tpw;   // rt = hi * S + lo
+    tp.hi = (int)(rt / (unsigned)S);
+    tp.lo = (int)(rt % (unsigned)S);
+    tp.row0 = (int64_t)tp.hi * P * S + tp.lo;
+    tp.col = (int64_t)ct * kColCols + 2 * lane;
+    tp.eoff = (int)((ncols - tp.col) * 2 + (tp.col >> 4));
+    return tp;
+  };
+  float *prm = reinterpret_cast<float *>(tile + P * 64);
+  typedef const __attribute__((address_space(1))) float *gfloat_t;
+  typedef const __attribute__((address_space(1))) uint32_t *gtab_t;
+  gfloat_t image = (gfloat_t)cp.image;
+  gtab_t ptab = (gtab_t)cp.ptab;
+  const int npar = cp.npar;
+  unsigned dfix[kColParPerThread], dfa[kColParPerThread], dfb[kColParPerThread];
+#pragma unroll
+  for (int k = 0; k < kColParPerThread; ++k) {
+    const int e = (int)threadIdx.x + kColThreads * k;
+    const bool ok = e < npar;
+    const unsigned fa = ok ? ptab[npar + e] : 0xffffffffu;
+    const bool real = fa != 0xffffffffu;
+    dfix[k] = real ? ptab[e] : 0u;
+    dfa[k] = real ? fa : 0u;
+    dfb[k] = real ? ptab[2 * npar + e] : 0u;
+  }
+  float ppre[kColParPerThread];
+  ColRaw<TI> pre[NR];
+  // tile row of register u in a layout, as (first row, step) in units of tile rows
+  const int firstB = wave, firstA = wave * NR;
+  auto request = [&](const TilePos &tp) __attribute__((always_inline)) {
+#pragma unroll
+    for (int k = 0; k < kColParPerThread; ++k)
+      ppre[k] = image[dfix[k] + (unsigned)tp.hi * dfa[k] + (unsigned)tp.lo * dfb[k]];
+    const TI *rp = src + (tp.row0 + (int64_t)(kFirstB ? firstB : firstA) * S) * lds_ + tp.col;
+    const int64_t step = (int64_t)(kFirstB ? kColWaves : 1) * S * lds_;
+#pragma unroll
+    for (int u = 0; u < NR; ++u) {
+      col_load<TI, true>(pre[u], rp, true, true, tp.eoff);
+      rp += step;
+    }
+  };
+  const unsigned t0 = xcd_grouped(blockIdx.x, xg) * tpw;
+  const unsigned t1 = (t0 + tpw < ntiles) ? t0 + tpw : ntiles;
+  if (t0 >= t1) return;
+  float2 *colp = tile + lane;
+  request(locate(t0));
+  for (unsigned t = t0; t < t1; ++t) {
+    const TilePos cur = locate(t);
+    float2 x[NR];
+#pragma unroll
+    for (int u = 0; u < NR; ++u) x[u] = col_widen<true>(pre[u]);
+#pragma unroll
+    for (int k = 0; k < kColParPerThread; ++k) prm[(int)threadIdx.x + kColThreads * k] = ppre[k];
+    __syncthreads();   // the tile's block values are in LDS
+    // the next tile (after the last one: that tile once more, so that the sequence of requests,
+    // stages and stores is the same in every iteration and no access is conditional)
+    request(locate(t + 1 < t1 ? t + 1 : t));
+    if constexpr (!DESC) col2_stages<NR, LOGP, false, 0, LOGP - 2, false>(x, prm, cs, wave);
+    else col2_stages<NR, LOGP, true, LOGP - 1, LOGP - 2, true>(x, prm, cs, wave);
+    // exchange: rows of the first layout out, rows of the second layout in
+#pragma unroll
+    for (int u = 0; u < NR; ++u)
+      colp[(kFirstB ? firstB + kColWaves * u : firstA + u) * 64] = x[u];
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < NR; ++u)
+      x[u] = colp[(kFirstB ? firstA + u : firstB + kColWaves * u) * 64];
+    if constexpr (!DESC) col2_stages<NR, LOGP, true, LOGP - 2, 2, false>(x, prm, cs, wave);
+    else col2_stages<NR, LOGP, false, 1, 2, true>(x, prm, cs, wave);
+    TO *wp = dst + (cur.row0 + (int64_t)(kFirstB ? firstA : firstB) * S) * ldd + cur.col;
+    const int64_t wstep = (int64_t)(kFirstB ? 1 : kColWaves) * S * ldd;
+#pragma unroll
+    for (int u = 0; u < NR; ++u) {
+      col_store<TO, true>(wp, x[u], true, true, cur.eoff);
+      wp += wstep;
+    }
+    __syncthreads();   // every wave is done with the block values and the exchange buffer
+  }
+}
+
 // Column pass fused with ONE stage of the row-side processor (plan_V's streamed stage of radix
 // BV on the top digit: it couples the columns lo + r Sv, r < BV, of a row with block lo, and
 // commutes with every stage of plan_U).  A tile is P rows x BV segments of 32 columns (row
@@ -567,6 +716,44 @@ __global__ __launch_bounds__(kColThreads, 2) void harp_colrow_kernel(
   work(t0 + tpw - 1);
 }
 
+// Does the pass consist of radix-2 stages on the tile-row bits 0 .. k-1 in ascending or descending
+// order, 32 <= P = 2^k <= 128?  Then it runs with the tile in registers (harp_col2_kernel).
+static bool col2_pass(const ColPass &hp, Col2Stages &cs, int &logp, bool &desc) {
+  int k = 0;
+  while ((1 << k) < hp.P) ++k;
+  if ((1 << k) != hp.P || k < 5 || k > 7) return false;
+  int bits[8], n = 0;
+  for (int oi = 0; oi < hp.nops; ++oi) {
+    const ColOp &op = hp.op[oi];
+    if (op.b != 2 || op.sp < 1 || (op.sp & (op.sp - 1))) return false;
+    int b0 = 0;
+    while ((1 << b0) < op.sp) ++b0;
+    for (int i = 0; i < op.k; ++i) {
+      const int bit = b0 + op.dp[i];
+      if (n >= 8 || bit < 0 || bit >= k || (op.poff[i] & 3)) return false;
+      bits[n++] = bit;
+      cs.poff[bit] = op.poff[i];
+    }
+  }
+  if (n != k) return false;
+  bool asc = true, dsc = true;
+  for (int i = 0; i < k; ++i) {
+    asc = asc && bits[i] == i;
+    dsc = dsc && bits[i] == k - 1 - i;
+  }
+  if (!asc && !dsc) return false;
+  logp = k;
+  desc = dsc && !asc;
+  return true;
+}
+
+template <typename TI, typename TO>
+struct Col2Types {   // element types the register-tile kernel is built for
+  static constexpr bool value =
+      (std::is_same<TI, TO>::value && !std::is_same<TI, zh16>::value) ||            // float / bf16 in place
+      IsZ16<TI>::value || IsZ16<TO>::value;                                         // the halves
+};
+
 template <typename TI, typename TO>
 harp_status_t launch_col_tiles(const harp_plan *plan, const ColPass *dpass, const ColPass &hp,
                                const TI *src, int64_t lds_, TO *dst, int64_t ldd, int64_t nrows,
@@ -588,6 +775,33 @@ harp_status_t launch_col_tiles(const harp_plan *plan, const ColPass *dpass, cons
   const int64_t grid = tiles / tpw;
   // 16 neighbouring column tiles share a 128-byte line of exponent bytes
   const unsigned xg = xcd_group_size(ctiles, grid, 16);
+  if constexpr (Col2Types<TI, TO>::value) {
+    Col2Stages cs{};
+    int logp = 0;
+    bool desc = false;
+    if (fast && col2_pass(hp, cs, logp, desc)) {
+      typedef void (*kern2_t)(const ColPass *, const TI *, int64_t, TO *, int64_t, int64_t, unsigned,
+                              unsigned, unsigned, unsigned, Col2Stages);
+      static const kern2_t table2[6] = {harp_col2_kernel<TI, TO, 5, false>, harp_col2_kernel<TI, TO, 5, true>,
+                                        harp_col2_kernel<TI, TO, 6, false>, harp_col2_kernel<TI, TO, 6, true>,
+                                        harp_col2_kernel<TI, TO, 7, false>, harp_col2_kernel<TI, TO, 7, true>};
+      const int w2 = (logp - 5) * 2 + (desc ? 1 : 0);
+      const kern2_t kern2 = table2[w2];
+      static thread_local int attr2_done_dev[6] = {-1, -1, -1, -1, -1, -1};   // per instantiation
+      if (attr2_done_dev[w2] != plan->device) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern2),
+                                hipFuncAttributeMaxDynamicSharedMemorySize,
+                                plan->lds_bytes) != hipSuccess) {
+          (void)hipGetLastError();
+          return HARP_ERR_DEVICE;
+        }
+        attr2_done_dev[w2] = plan->device;
+      }
+      hipLaunchKernelGGL(kern2, dim3((unsigned)grid), dim3(kColThreads), shmem, stream, dpass, src, lds_,
+                         dst, ldd, ncols, (unsigned)ctiles, (unsigned)tiles, (unsigned)tpw, xg, cs);
+      return hipGetLastError() == hipSuccess ? HARP_OK : HARP_ERR_DEVICE;
+    }
+  }
   typedef void (*kern_t)(const ColPass *, const TI *, int64_t, TO *, int64_t, int64_t, unsigned,
                          unsigned, unsigned, unsigned);
   // unguarded: the variant with the fewest row steps per wave that covers P
@@ -839,6 +1053,14 @@ bool col_z16_supported(const ColPass &hp, const void *src, int64_t lds_, const v
   if (hp.P < kColWaves || hp.P > kColMaxP) return false;
   if (lds_ % 2 || ldd % 2 || (uintptr_t)src % 4 || (uintptr_t)dst % 4) return false;
   return true;
+}
+
+// Would this pass run with the tile in registers (harp_col2_kernel) on whole column tiles?
+bool col_pass_in_registers(const ColPass &hp, int64_t ncols) {
+  Col2Stages cs{};
+  int logp = 0;
+  bool desc = false;
+  return ncols % kColCols == 0 && col2_pass(hp, cs, logp, desc);
 }
 
 // The fused launch applies when: the column pass has exactly 32 or 64 rows per tile; the row

@@ -327,6 +327,8 @@ harp_status_t launch_col_pass(const harp_plan *plan, const ColPass *dpass, const
 // block-scaled halves (kDtZ16) on either side of a column pass: unguarded tiles only
 bool col_z16_supported(const ColPass &hp, const void *src, int64_t lds_, const void *dst,
                        int64_t ldd, int64_t nrows, int64_t ncols);
+// a pass of radix-2 stages on 32 / 64 / 128-row tiles that runs with the tile in registers
+bool col_pass_in_registers(const ColPass &hp, int64_t ncols);
 // column pass fused with the row-side processor's streamed small-radix stage (harp_col.hip)
 bool colrow_supported(const harp_plan *plan, const ColPass &hp, const PassDesc &vp, const void *src,
                       int64_t lds_, harp_dtype_t dt_src, const void *dst, int64_t ldd,
