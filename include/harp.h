@@ -173,7 +173,7 @@ int64_t harp_apply_noalloc_max_rows(const harp_plan_t *plan);
  * of a call the matrix lies in the workspace as float32 -- or, for HARP_BF16 matrices between
  * processors whose blocks are all orthogonal (checked at plan creation), with d_in a multiple
  * of 128 and 16-byte aligned workspace, as half-precision values with one power-of-two scale
- * per 16 consecutive columns of a row: each of the at most two trips then changes an entry by at
+ * per 16 consecutive columns of a row: each of the at most three trips then changes an entry by at
  * most 2^-12 of itself (or 2^-25 of the largest of its 16 neighbours), an eighth of the rounding
  * the bf16 result receives anyway.  That error is relative to the entry between the launches,
  * i.e. to the scale of its column while plan_U's stages are still to come; HARP_F32_INTERMEDIATES
