@@ -1268,6 +1268,8 @@ def test_rotate_weight_with_streamed_row_stage(harp, dtype, do, ru, di, rv):
     (1024, [2] * 10, 4096, [2] * 12),        # two column passes; plan_V in one launch (4096)
     (2048, [8, 8, 8, 4], 2048, [2] * 11),    # radix-8 column passes; plan_V on 2048 coordinates
     (256, [2] * 8, 1024, [2] * 10),          # plan_V on 1024 coordinates
+    (128, [2] * 7, 4096, [2] * 12),          # one column pass of 128 rows (bf16 -> bf16 when one-sided)
+    (32, [2] * 5, 2048, [2] * 11),           # ... of 32 rows
     (896, [2] * 7 + [7], 14336, [2] * 11 + [7]),   # row stage fused into a column pass
     (640, [2] * 7 + [5], 5120, [2] * 10 + [5])])
 def test_rotate_weight_half_precision_workspace(harp, do, ru, di, rv):
