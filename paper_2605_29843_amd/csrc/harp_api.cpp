@@ -101,7 +101,7 @@ bool stage_orthogonal_2x2(const float *K, int64_t D) {
 // travels as block-scaled halves), so that no scale is pending behind it.
 bool build_effective(const harp_plan *plan, const std::vector<const float *> &blocks,
                      const int8_t *signs, int algo, Direction dir, bool scaled,
-                     std::vector<StageEff> &out, int dense_t = -1) {
+                     std::vector<StageEff> &out, int dense_t = -1, int dense_both = -1) {
   const int m = plan->m;
   const int64_t d = plan->d;
   const double kScaleMax = 1152921504606846976.0;   // 2^60
@@ -127,7 +127,9 @@ bool build_effective(const harp_plan *plan, const std::vector<const float *> &bl
     // pending scale (a function of the coordinate inside the slice) reaches the table, whose
     // blocks then really are one matrix.  Likewise the last stage of a chunk whose output is
     // stored as block-scaled halves: those need values of the row's own size.
-    const bool slice_end = (dir == DIR_FWD && t == dense_t);
+    // (dense_both: a radix-2 stage streamed on its own above the chunk, with the halves on one side
+    // of it in either direction)
+    const bool slice_end = (dir == DIR_FWD && t == dense_t) || t == dense_both;
     const bool pow2_stage = (algo != HARP_ALGO_GENERIC && b == 2 && !last && !slice_end);
     if (pow2_stage && scaled) {
       se.form = FORM_SCALED;
@@ -373,13 +375,18 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
   // of 256 / 512 / 1024 on the wave kernel, and the small-radix streamed kernel)
   bool tops_small = (tb < m);   // every streamed stage of radix 3..8
   for (int t = tb; t < m; ++t) tops_small = tops_small && plan->radices[t] >= 3 && plan->radices[t] <= 8;
+  // ... or one radix-2 stage on the top digit (8192 = 2^13): kept dense in both directions, it is
+  // streamed by the same kernels as a radix-2 "small" stage
+  const bool top2 = (algo == HARP_ALGO_SPLIT && !tied && tb == m - 1 && plan->radices[m - 1] == 2);
+  tops_small = tops_small || top2;
   hp.z16 = (algo == HARP_ALGO_SPLIT && !tied && plan->orthogonal && !plan->f32_only && tops_small && d % 64 == 0 &&
             (chunk == 4096 || chunk == 2048 || chunk == 1024 || chunk == 512 || chunk == 256));
   const int dense_t = tied ? m - 2 : ((hp.z16 && plan->radices[tb - 1] == 2) ? tb - 1 : -1);
   std::vector<StageEff> eff;
-  if (!build_effective(plan, blocks, signs, algo, dir, true, eff, dense_t)) {
+  const int dense_both = (top2 && hp.z16) ? m - 1 : -1;
+  if (!build_effective(plan, blocks, signs, algo, dir, true, eff, dense_t, dense_both)) {
     if (tied) return false;
-    build_effective(plan, blocks, signs, algo, dir, false, eff, dense_t);
+    build_effective(plan, blocks, signs, algo, dir, false, eff, dense_t, dense_both);
   }
   auto local = [&](int i) { return eff[i].t < tb; };
   hp.chunk = (int32_t)chunk;
@@ -587,18 +594,18 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
   // bf16 caller run on the DPP kernel too (a thread's 16 coordinates are one segment of that
   // format in both of its layouts).
   if (algo == HARP_ALGO_SPLIT && hp.z16 && chunk == 4096 && tb == 12 && m == 13 &&
-      !(dir == DIR_TRN && (eff[0].b == 3 || eff[0].b == 5)))   // (those: the image built below)
+      !(dir == DIR_TRN && (eff[0].b == 2 || eff[0].b == 3 || eff[0].b == 5)))   // (those: the image built below)
     build_dpp_image(plan, eff, dir == DIR_FWD ? 0 : 1, dir, hp, image, dir == DIR_FWD ? dense_t : -1);
   if (algo == HARP_ALGO_SPLIT && hp.z16 && chunk == 2048 && tb == 11 && m == 12)
     build_dpp_image(plan, eff, dir == DIR_FWD ? 0 : 1, dir, hp, image, dir == DIR_FWD ? dense_t : -1, 11);
   if (algo == HARP_ALGO_SPLIT && hp.z16 && chunk == 1024 && tb == 10 && m == 11)
     build_dpp_image(plan, eff, dir == DIR_FWD ? 0 : 1, dir, hp, image, dir == DIR_FWD ? dense_t : -1, 10);
-  // Transposed split program of twelve radix-2 stages below one dense stage of radix 3 or 5
-  // (12288, 20480; radix 7 measured no gain): that stage runs first and is executed by the DPP kernel's first
+  // Transposed split program of twelve radix-2 stages below one dense stage of radix 2, 3 or 5
+  // (8192, 12288, 20480; radix 7 measured no gain): that stage runs first and is executed by the DPP kernel's first
   // group on the way in (harp_dpp_top_kernel).  Its factors: for output chunk kch, input chunk
   // j and coordinate c of the chunk, entry [j][kch] of block c as this direction uses it.
   if (algo == HARP_ALGO_SPLIT && dir == DIR_TRN && !tied && chunk == 4096 && tb == 12 && m == 13 &&
-      (eff[0].b == 3 || eff[0].b == 5) && eff[0].form == FORM_DENSE &&
+      (eff[0].b == 2 || eff[0].b == 3 || eff[0].b == 5) && eff[0].form == FORM_DENSE &&
       eff[0].s == 4096 && d == 4096 * (int64_t)eff[0].b) {
     build_dpp_image(plan, eff, 1, dir, hp, image);
     if (hp.dpp.host_off >= 0) {
@@ -907,17 +914,22 @@ harp_status_t rotate_impl(const harp_plan_t *pu, const harp_plan_t *pv, Directio
       }
       return -1;
     };
+    // (the streamed stage on its own trip between halves and the caller's matrix)
+    bool own_trip = false;
     if (one_streamed) {
       vp = &vhp->prog.pass[vhp->chunk_first ? vhp->n_chunk : 0];
       if (zws) {
+        const bool fwd = (dir == DIR_FWD);
         fuse = find_fuse(true);
-        if (fuse < 0) zws = false;
+        own_trip = stream_z16_supported(*vp, fwd ? (const void *)A : W, fwd ? zl : ldw,
+                                        fwd ? Wout : (void *)A, fwd ? ldo : zl);
+        if (fuse < 0 && !own_trip) zws = false;
       }
-      if (fuse < 0) fuse = find_fuse(false);
+      if (fuse < 0 && !zws) fuse = find_fuse(false);
     } else if (zws && pv && vhp->n_chunk != vhp->prog.npass) {
       zws = false;   // several streamed trips: plan_V runs on its own, through float32
     }
-    if (zws && pv && fuse < 0 && vhp->n_chunk != vhp->prog.npass) zws = false;
+    if (zws && pv && fuse < 0 && !own_trip && vhp->n_chunk != vhp->prog.npass) zws = false;
     const harp_dtype_t wt = zws ? ZT : HARP_F32;
     const int64_t wld = zws ? zl : d_in;
     const void *src = W;
@@ -928,13 +940,13 @@ harp_status_t rotate_impl(const harp_plan_t *pu, const harp_plan_t *pv, Directio
     // of riding along with a column pass on the LDS-tile kernel: at 8192 x 28672 the forward map
     // measured 0.90 against 0.93 ms, the inverse the same either way.  Forward: chunks, column
     // passes, streamed stage; inverse: streamed stage, column passes, chunks.
-    if (fuse >= 0 && zws) {
+    // (also when no column pass can take the stage along: a radix-2 stage on the top digit)
+    if (zws && own_trip) {
       bool regs = true;
       for (size_t p = 0; p < cps.size(); ++p) regs = regs && col_pass_in_registers(cps[p].pass, d_in);
       const int ps = vhp->chunk_first ? vhp->n_chunk : 0, c0 = vhp->chunk_first ? 0 : 1;
       const bool fwd = (dir == DIR_FWD);
-      if (regs && stream_z16_supported(vhp->prog.pass[ps], fwd ? (const void *)A : W, fwd ? zl : ldw,
-                                       fwd ? Wout : (void *)A, fwd ? ldo : zl)) {
+      if (regs || fuse < 0) {
         if (fwd)
           st = run_chunk_passes(pv, *vhp, c0, c0 + vhp->n_chunk, W, ldw, dt, A, zl, ZT, d_out, s);
         else

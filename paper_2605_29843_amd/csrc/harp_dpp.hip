@@ -510,8 +510,8 @@ __global__ __launch_bounds__(2 * Geo<LOGD>::TG) void harp_dpp_kernel(const TI *_
 }
 
 // ------------------------------------------------------------------------------------------
-// Transposed split programs whose one streamed stage is a dense stage of radix B = 3 or 5 on the
-// digit above the chunk (12288 = 4096 * 3, 20480 = 4096 * 5): that stage runs first, so it is
+// Transposed split programs whose one streamed stage is a dense stage of radix B = 2, 3 or 5 on the
+// digit above the chunk (8192 = 4096 * 2, 12288 = 4096 * 3, 20480 = 4096 * 5): that stage runs first, so it is
 // executed on the way in instead of taking its own trip through a float32 intermediate in
 // device memory.  For the workgroup's chunk k the first group reads its 16 coordinates from ALL
 // B chunks of the row and forms z[i] = sum_j x[j * 4096 + i] * K_i[j][k] with the B factors of
@@ -723,6 +723,7 @@ harp_status_t launch_dpp_top_kernel(const harp_plan *plan, const DppImage &di, c
   hipLaunchKernelGGL((harp_dpp_top_kernel<B_>), grid, block, 0, stream, (const uint16_t *)X, ldx, \
                      (uint16_t *)Y, ldy, n, R, tt, a, b, di.strideA, di.strideB)
   switch (B) {
+    case 2: HARP_DPP_TOP(2); break;
     case 3: HARP_DPP_TOP(3); break;
     case 5: HARP_DPP_TOP(5); break;
     default: return HARP_ERR_UNSUPPORTED;

@@ -1171,7 +1171,9 @@ harp_status_t launch_tile_kernel(const harp_plan *plan, const Program *prog, int
 bool stream_z16_supported(const PassDesc &pd, const void *X, int64_t ldx, const void *Y,
                           int64_t ldy) {
   const bool chain = (pd.kind == PASS_SMALL_CHAIN && pd.b == 3 && pd.k == 2);   // LDS-staged kernel only
-  if (!chain && (pd.kind != PASS_SMALL || pd.b < 3 || pd.b > 8)) return false;
+  // one dense radix-2 stage: its four values per block lie in the image like a radix-2 "small" stage
+  const bool dense2 = (pd.kind == PASS_POW2_DENSE && pd.k == 1 && pd.P == 2 && pd.V == 4);
+  if (!chain && !dense2 && (pd.kind != PASS_SMALL || pd.b < 3 || pd.b > 8)) return false;
   if (pd.tied) return false;
   if (chain && (pd.S % 256 != 0 || pd.nq % 256 != 0 || ldx % 8 || ldy % 8 || (uintptr_t)X % 16 ||
                 (uintptr_t)Y % 16))
@@ -1202,6 +1204,7 @@ harp_status_t launch_stream_pass(const harp_plan *plan, const HostProgram &hp, i
                      : launch_stream_z16_lds<OpSmallChain<3, 2, false>>(plan, pd, X, ldx, Y, ldy, n, zin, zout, stream);
     }
     switch (pd.b) {
+      case 2: return launch_stream_z16_op<OpSmall<2>>(plan, pd, X, ldx, Y, ldy, n, zin, zout, stream);
       case 3: return launch_stream_z16_op<OpSmall<3>>(plan, pd, X, ldx, Y, ldy, n, zin, zout, stream);
       case 4: return launch_stream_z16_op<OpSmall<4>>(plan, pd, X, ldx, Y, ldy, n, zin, zout, stream);
       case 5: return launch_stream_z16_op<OpSmall<5>>(plan, pd, X, ldx, Y, ldy, n, zin, zout, stream);

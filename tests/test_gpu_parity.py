@@ -482,6 +482,7 @@ def test_chunk_of_a_llama13b_ffn_row_ends_behind_its_radix2_stages(harp):
 
 @pytest.mark.parametrize("d,radices", [
     (12288, [2] * 12 + [3]),      # DPP kernel on chunks of 4096 + streamed radix 3
+    (8192, [2] * 13),             # ... + one streamed radix-2 stage (kept dense in both directions)
     (28672, [2] * 12 + [7]),      # ... + streamed radix 7
     (14336, [2] * 11 + [7]),      # DPP kernel on chunks of 2048 + streamed radix 7
     (5120, [2] * 10 + [5]),       # wave kernel on chunks of 1024 + streamed radix 5
@@ -533,7 +534,8 @@ def test_half_precision_intermediate_of_split_programs(harp, d, radices):
 
 
 @pytest.mark.parametrize("d,radices", [(14336, [2] * 11 + [7]), (5120, [2] * 10 + [5]),
-                                       (13824, [2] * 9 + [3, 3, 3]), (12288, [2] * 12 + [3])])
+                                       (13824, [2] * 9 + [3, 3, 3]), (12288, [2] * 12 + [3]),
+                                       (8192, [2] * 13)])
 @pytest.mark.parametrize("n,ld_pad", [(0, 0), (1, 0), (2, 0), (3, 8), (5, 24), (67, 8), (6, 3)])
 def test_half_precision_intermediate_edges(harp, d, radices, n, ld_pad):
     """Split programs of bf16 callers at the edges: no rows, one row, odd row counts (rows move in
@@ -1271,6 +1273,7 @@ def test_rotate_weight_with_streamed_row_stage(harp, dtype, do, ru, di, rv):
     (128, [2] * 7, 4096, [2] * 12),          # one column pass of 128 rows (bf16 -> bf16 when one-sided)
     (32, [2] * 5, 2048, [2] * 11),           # ... of 32 rows
     (896, [2] * 7 + [7], 14336, [2] * 11 + [7]),   # row stage fused into a column pass
+    (448, [2] * 6 + [7], 8192, [2] * 13),          # plan_V with a radix-2 stage on its top digit: own trip
     (640, [2] * 7 + [5], 5120, [2] * 10 + [5])])
 def test_rotate_weight_half_precision_workspace(harp, do, ru, di, rv):
     """bf16 matrices between orthogonal processors travel through the workspace as block-scaled
