@@ -466,7 +466,8 @@ def main():
                     gbs = 2 * 2048 * dd * tdt.itemsize / 1e3   # bytes read + written, per us -> GB/s
                     print(f"[shapes] {fam:8s} d={dd:6d} {str(tdt)[6:]:8s} apply {tf:7.1f} us "
                           f"({gbs / tf:5.0f} GB/s)  transpose {tt:7.1f} us ({gbs / tt:5.0f} GB/s)  "
-                          f"[{ps.kernel_name(2048)}]", file=sys.stderr, flush=True)
+                          f"[{ps.kernel_name(2048, harp.HARP_BF16 if tdt == torch.bfloat16 else harp.HARP_F32)}]",
+                          file=sys.stderr, flush=True)
                     del Xs, Ys
                 ps.destroy()
             for do, di in ((4096, 4096), (11008, 4096), (4096, 11008), (5120, 13824), (13824, 5120),

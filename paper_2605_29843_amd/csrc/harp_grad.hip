@@ -228,7 +228,7 @@ __global__ __launch_bounds__(kGradThreads) void harp_grad_dk_big_kernel(
 // so that the partial sums leave in runs of 16 consecutive blocks (64 bytes).  Rows past the end
 // of the chunk enter as zeros.  Workgroups that share 128-byte lines (two neighbouring block
 // tiles) are numbered onto one XCD.
-constexpr int kDkRows = 8;                  // rows per step
+constexpr int kDkRows = 8;                  // rows per step (16 measured 1 % faster at 2048 x 11008 for twice the LDS)
 constexpr int kDkLS = kDkRows + 1;          // LDS stride between consecutive blocks
 constexpr int kDkJS = 16 * kDkLS + 4;       // LDS stride between consecutive r
 
