@@ -327,7 +327,7 @@ def main():
         out["cpu_baseline"] = cpu_baseline(w, sample_rows=min(n, 2048))
     if args.extra:
         for name in ("llama7b_4096_r8", "down_11008_r2x8_43", "ffn_14336_r2x11_7", "ffn70b_28672_r2x12_7",
-                     "llama13b_5120_r2x10_5", "ffn13b_13824_r2x9_27"):
+                     "llama13b_5120_r2x10_5", "ffn13b_13824_r2x9_27", "hidden70b_8192_r2"):
             try:
                 we = gi.workload(name)
                 pe = harp.Plan(we["d"], we["radices"], we["blocks"], we["signs"])

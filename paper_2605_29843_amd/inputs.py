@@ -225,6 +225,9 @@ WORKLOADS = {
                                   act=dict(dist="student_t", outlier_frac=0.01, outlier_scale=20.0)),
     "ffn13b_13824_r2x9_27": dict(config=3, n=2048, d=13824, radices=[2] * 9 + [3, 3, 3], dtype="bf16",
                                  act=dict(dist="student_t", outlier_frac=0.01, outlier_scale=20.0)),
+    # hidden size of the 70B models (8192 = 2^13): same recipe as config 5's activations
+    "hidden70b_8192_r2": dict(config=5, n=2048, d=8192, radices=[2] * 13, dtype="bf16",
+                              act=dict(dist="student_t", outlier_frac=0.01, outlier_scale=20.0)),
     "ffn70b_28672_r2x12_7": dict(config=5, n=4096, d=28672, radices=[2] * 12 + [7], dtype="bf16",
                                  act=dict(dist="student_t", outlier_frac=0.01, outlier_scale=20.0)),
 }
