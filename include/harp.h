@@ -129,6 +129,13 @@ harp_status_t harp_plan_destroy(harp_plan_t *plan);
  * HARP_F32 callers that stage runs on the float32 matrix instruction with unsplit operands
  * (float32 products and sums, in another order than the vector path).  Setting the
  * environment variable HARP_NO_MFMA=1 selects the float32 vector path for every caller.
+ * Second exception, HARP_BF16 callers only: when every block of the plan is orthogonal and the
+ * stages above the on-chip chunk have radix 2 .. 8, the intermediate between the launches holds
+ * half-precision values with one power-of-two scale per 16 coordinates instead of float32 (each
+ * value within 2^-12 of itself or 2^-25 of the largest of its 16 neighbours: an eighth of the
+ * rounding of the bf16 result); HARP_F32_INTERMEDIATES at plan creation keeps float32.  A
+ * transposed call whose one stage above a 4096-chunk has radix 2, 3 or 5 (d = 8192, 12288,
+ * 20480) runs in one launch without any intermediate when Y is not X.
  */
 harp_status_t harp_apply(const harp_plan_t *plan, const void *X, int64_t ldx, void *Y,
                          int64_t ldy, int64_t n, harp_dtype_t dt, void *stream);
