@@ -596,30 +596,33 @@ bool build_program(const harp_plan *plan, const std::vector<const float *> &bloc
   if (algo == HARP_ALGO_SPLIT && hp.z16 && chunk == 4096 && tb == 12 && m == 13 &&
       !(dir == DIR_TRN && (eff[0].b == 2 || eff[0].b == 3 || eff[0].b == 5)))   // (those: the image built below)
     build_dpp_image(plan, eff, dir == DIR_FWD ? 0 : 1, dir, hp, image, dir == DIR_FWD ? dense_t : -1);
-  if (algo == HARP_ALGO_SPLIT && hp.z16 && chunk == 2048 && tb == 11 && m == 12)
+  const bool top_one_launch = (dir == DIR_TRN && (eff[0].b == 2 || eff[0].b == 3 || eff[0].b == 5));
+  if (algo == HARP_ALGO_SPLIT && hp.z16 && chunk == 2048 && tb == 11 && m == 12 && !top_one_launch)
     build_dpp_image(plan, eff, dir == DIR_FWD ? 0 : 1, dir, hp, image, dir == DIR_FWD ? dense_t : -1, 11);
-  if (algo == HARP_ALGO_SPLIT && hp.z16 && chunk == 1024 && tb == 10 && m == 11)
+  if (algo == HARP_ALGO_SPLIT && hp.z16 && chunk == 1024 && tb == 10 && m == 11 && !top_one_launch)
     build_dpp_image(plan, eff, dir == DIR_FWD ? 0 : 1, dir, hp, image, dir == DIR_FWD ? dense_t : -1, 10);
-  // Transposed split program of twelve radix-2 stages below one dense stage of radix 2, 3 or 5
-  // (8192, 12288, 20480; radix 7 measured no gain): that stage runs first and is executed by the DPP kernel's first
+  // Transposed split program of ten, eleven or twelve radix-2 stages below one dense stage of radix
+  // 2, 3 or 5 (5120, 6144, 10240, 8192, 12288, 20480; radix 7 measured no gain): that stage runs first and is executed by the DPP kernel's first
   // group on the way in (harp_dpp_top_kernel).  Its factors: for output chunk kch, input chunk
   // j and coordinate c of the chunk, entry [j][kch] of block c as this direction uses it.
-  if (algo == HARP_ALGO_SPLIT && dir == DIR_TRN && !tied && chunk == 4096 && tb == 12 && m == 13 &&
+  if (algo == HARP_ALGO_SPLIT && dir == DIR_TRN && !tied &&
+      (chunk == 4096 || chunk == 2048 || chunk == 1024) && chunk == ((int64_t)1 << tb) && m == tb + 1 &&
       (eff[0].b == 2 || eff[0].b == 3 || eff[0].b == 5) && eff[0].form == FORM_DENSE &&
-      eff[0].s == 4096 && d == 4096 * (int64_t)eff[0].b) {
-    build_dpp_image(plan, eff, 1, dir, hp, image);
+      eff[0].s == chunk && d == chunk * (int64_t)eff[0].b) {
+    const int L = tb, TG = (int)(chunk / 16);
+    build_dpp_image(plan, eff, 1, dir, hp, image, -1, L);
     if (hp.dpp.host_off >= 0) {
       const int b = eff[0].b;
       const size_t off = image.size();
-      image.resize(off + (size_t)b * b * 4096);
+      image.resize(off + (size_t)b * b * chunk);
       float *tp = image.data() + off;
       for (int kch = 0; kch < b; ++kch)
         for (int j = 0; j < b; ++j)
           for (int k = 0; k < 4; ++k)
-            for (int t = 0; t < 256; ++t)
+            for (int t = 0; t < TG; ++t)
               for (int q = 0; q < 4; ++q) {
-                const int64_t c = 16 * (int64_t)dpp_segment_of(true, (unsigned)t) + 4 * k + q;
-                tp[((((size_t)kch * b + j) * 4 + k) * 256 + t) * 4 + q] =
+                const int64_t c = 16 * (int64_t)dpp_segment_of(true, (unsigned)t, L) + 4 * k + q;
+                tp[((((size_t)kch * b + j) * 4 + k) * TG + t) * 4 + q] =
                     eff[0].dense[((size_t)c * b + j) * b + kch];
               }
       hp.dpp.topB = b;

@@ -528,11 +528,12 @@ __global__ __launch_bounds__(2 * Geo<LOGD>::TG) void harp_dpp_kernel(const TI *_
 //
 // A whole row of requests is in flight per thread (ring of B segments): slot (j, h) is refilled
 // with the same piece of the next row as soon as it has been consumed.
-template <int B>
+template <int B, int LOGD = 12>
 __device__ __forceinline__ void group_TA(const float *__restrict__ imgT, const float *__restrict__ imgA,
                                           int t, float *buf, const uint16_t *__restrict__ Xt,
                                           int64_t ldx, int nr) {
-  const unsigned s = seg_of(true, (unsigned)t >> 6, (unsigned)t & 63u);
+  constexpr int kD = Geo<LOGD>::D, kTG = Geo<LOGD>::TG, kRowBuf = Geo<LOGD>::ROWBUF;
+  const unsigned s = seg_of<LOGD>(true, (unsigned)t >> 6, (unsigned)t & 63u);
   const unsigned voff = 32u * s;   // byte offset of the thread's segment inside a chunk
   const int last = nr - 1;
   // half h of chunk j of row r; rows past the end of the tile repeat its last row.  The address
@@ -551,9 +552,9 @@ __device__ __forceinline__ void group_TA(const float *__restrict__ imgT, const f
   }
   __builtin_amdgcn_sched_barrier(0);
   float T[B][16];
-  load_params<B>(imgT, t, T);
-  float f[4][16];
-  load_params<4>(imgA, t, f);
+  load_params<B, kTG>(imgT, t, T);
+  float f[LOGD - 8][16];
+  load_params<LOGD - 8, kTG>(imgA, t, f);
   const int npairs = (nr + 1) >> 1;
   auto one_row = [&](int r, float *dst) {
     float z[16];
@@ -574,7 +575,7 @@ __device__ __forceinline__ void group_TA(const float *__restrict__ imgT, const f
         // the B = 7 instance no longer fits 256 registers
         __builtin_amdgcn_sched_barrier(0);
       }
-    stages_A<true>(z, f);
+    stages_A<true, LOGD>(z, f);
     lds_put(dst, s, z);
   };
   for (int k = 0; k <= npairs; ++k) {
@@ -591,15 +592,16 @@ __device__ __forceinline__ void group_TA(const float *__restrict__ imgT, const f
 // its dispatch order: i = b / 8, chunk k = i mod B, tile = (i / B) * 8 + (b mod 8).  The grid
 // is padded to a multiple of 8 * B workgroups; those past the last tile leave at once.
 // imgT: [B chunks][B][4 pieces][256 threads][4] factors; imgA / imgB as in harp_dpp_kernel.
-template <int B>
-__global__ __launch_bounds__(2 * kTG) void harp_dpp_top_kernel(const uint16_t *__restrict__ X,
+template <int B, int LOGD = 12>
+__global__ __launch_bounds__(2 * Geo<LOGD>::TG) void harp_dpp_top_kernel(const uint16_t *__restrict__ X,
                                                                int64_t ldx, uint16_t *__restrict__ Y,
                                                                int64_t ldy, int64_t n, int R,
                                                                const float *__restrict__ imgT,
                                                                const float *__restrict__ imgA,
                                                                const float *__restrict__ imgB,
                                                                int64_t strideA, int64_t strideB) {
-  __shared__ float buf[4 * kRowBuf];
+  constexpr int kD = Geo<LOGD>::D, kTG = Geo<LOGD>::TG;
+  __shared__ float buf[4 * Geo<LOGD>::ROWBUF];
   const int g = __builtin_amdgcn_readfirstlane((int)threadIdx.x / kTG);   // wave-uniform
   const int t = (int)threadIdx.x % kTG;
   const unsigned xcd = blockIdx.x & 7u, i = blockIdx.x >> 3;
@@ -609,11 +611,11 @@ __global__ __launch_bounds__(2 * kTG) void harp_dpp_top_kernel(const uint16_t *_
   if (row0 >= n) return;
   const int nr = (int)((n - row0 < R) ? (n - row0) : R);
   if (g == 0)
-    group_TA<B>(imgT + (int64_t)kch * (B * 16 * kTG), imgA + kch * strideA, t, buf, X + row0 * ldx,
-                ldx, nr);
+    group_TA<B, LOGD>(imgT + (int64_t)kch * (B * 16 * kTG), imgA + kch * strideA, t, buf, X + row0 * ldx,
+                      ldx, nr);
   else
-    group_B<uint16_t, true, true>(imgB + kch * strideB, t, buf,
-                                  Y + row0 * ldy + (int64_t)kch * kD, ldy, nr, nullptr);
+    group_B<uint16_t, true, true, LOGD>(imgB + kch * strideB, t, buf,
+                                        Y + row0 * ldy + (int64_t)kch * kD, ldy, nr, nullptr);
 }
 
 template <typename TI, typename TO, int LOGD = 12>
@@ -699,7 +701,8 @@ harp_status_t launch_dpp_kernel(const harp_plan *plan, const DppImage &di, const
 
 bool dpp_top_supported(const harp_plan *plan, const DppImage &di, const void *X, int64_t ldx,
                        harp_dtype_t dt_in, const void *Y, int64_t ldy, harp_dtype_t dt_out) {
-  if (plan->algo == HARP_ALGO_GENERIC || !di.img || di.topB == 0 || !di.trn || !di.ld || di.logd != 12)
+  if (plan->algo == HARP_ALGO_GENERIC || !di.img || di.topB == 0 || !di.trn || !di.ld ||
+      (di.logd != 12 && di.logd != 11 && di.logd != 10))
     return false;
   if (dt_in != HARP_BF16 || dt_out != HARP_BF16) return false;
   if ((ldx % 8) || (ldy % 8) || ((uintptr_t)X % 16) || ((uintptr_t)Y % 16)) return false;
@@ -713,21 +716,26 @@ harp_status_t launch_dpp_top_kernel(const harp_plan *plan, const DppImage &di, c
                                     int64_t ldx, void *Y, int64_t ldy, int64_t n, int R,
                                     hipStream_t stream) {
   const int B = di.topB;
-  if (plan->d != (int64_t)B * kD) return HARP_ERR_UNSUPPORTED;
+  if (plan->d != ((int64_t)B << di.logd)) return HARP_ERR_UNSUPPORTED;
   const int64_t tiles = (n + R - 1) / R;
   const int64_t wgs = ((tiles + 7) / 8) * 8 * B;
   if (wgs > 0x7fffffff) return HARP_ERR_UNSUPPORTED;
-  const dim3 grid((unsigned)wgs), block(2 * kTG);
+  const dim3 grid((unsigned)wgs), block(2 * (1 << (di.logd - 4)));
   const float *a = di.img, *b = di.img + di.offB, *tt = di.img + di.offT;
-#define HARP_DPP_TOP(B_)                                                                          \
-  hipLaunchKernelGGL((harp_dpp_top_kernel<B_>), grid, block, 0, stream, (const uint16_t *)X, ldx, \
+#define HARP_DPP_TOP(B_, L_)                                                                            \
+  hipLaunchKernelGGL((harp_dpp_top_kernel<B_, L_>), grid, block, 0, stream, (const uint16_t *)X, ldx, \
                      (uint16_t *)Y, ldy, n, R, tt, a, b, di.strideA, di.strideB)
-  switch (B) {
-    case 2: HARP_DPP_TOP(2); break;
-    case 3: HARP_DPP_TOP(3); break;
-    case 5: HARP_DPP_TOP(5); break;
-    default: return HARP_ERR_UNSUPPORTED;
+#define HARP_DPP_TOP_B(L_)                       \
+  switch (B) {                                   \
+    case 2: HARP_DPP_TOP(2, L_); break;          \
+    case 3: HARP_DPP_TOP(3, L_); break;          \
+    case 5: HARP_DPP_TOP(5, L_); break;          \
+    default: return HARP_ERR_UNSUPPORTED;        \
   }
+  if (di.logd == 12) { HARP_DPP_TOP_B(12) }
+  else if (di.logd == 11) { HARP_DPP_TOP_B(11) }
+  else { HARP_DPP_TOP_B(10) }
+#undef HARP_DPP_TOP_B
 #undef HARP_DPP_TOP
   return hipGetLastError() == hipSuccess ? HARP_OK : HARP_ERR_DEVICE;
 }

@@ -485,7 +485,9 @@ def test_chunk_of_a_llama13b_ffn_row_ends_behind_its_radix2_stages(harp):
     (8192, [2] * 13),             # ... + one streamed radix-2 stage (kept dense in both directions)
     (28672, [2] * 12 + [7]),      # ... + streamed radix 7
     (14336, [2] * 11 + [7]),      # DPP kernel on chunks of 2048 + streamed radix 7
-    (5120, [2] * 10 + [5]),       # wave kernel on chunks of 1024 + streamed radix 5
+    (5120, [2] * 10 + [5]),       # DPP kernel on chunks of 1024 + streamed radix 5 (transposed: one launch)
+    (6144, [2] * 11 + [3]),       # chunks of 2048, radix 3 (transposed: one launch)
+    (10240, [2] * 11 + [5]),      # chunks of 2048, radix 5
     (7168, [2] * 10 + [7]),       # wave kernel on chunks of 1024 + streamed radix 7
     (2048 * 3, [2] * 9 + [4, 3]), # two streamed trips: halves on both sides of the first one
     (13824, [2] * 9 + [3, 3, 3]), # wave kernel on chunks of 512, two radix-3 stages in one trip, one more
