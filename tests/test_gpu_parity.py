@@ -1368,3 +1368,36 @@ def test_rotate_weight_llama70b_shape_sampled(harp):
     assert abs(no - nw) / nw < 1e-3
     pu.destroy()
     pv.destroy()
+
+
+def test_rotate_weight_llama70b_gate_shape_sampled(harp):
+    """W 28672 x 8192 bf16 (the transposed 70B shape): plan_U with a radix-7 stage among its column
+    passes, plan_V = 2^13 whose top stage takes its own trip; rows recomputed by the oracle, both maps."""
+    import torch
+    do, di = 28672, 8192
+    ru, rv = [2] * 12 + [7], [2] * 13
+    bu, su = gi.processor(do, ru, config=5, salt=3)
+    bv, sv = gi.processor(di, rv, config=5, salt=4)
+    W = gi.weights(do, di, config=5)
+    pu, pv = harp.Plan(do, ru, bu, su), harp.Plan(di, rv, bv, sv)
+    say("rotate_weight 28672x8192 bf16")
+    Wd = to_device(W, "bf16")
+    out = harp.harp_rotate_weight(pu, pv, Wd)
+    inv = harp.harp_rotate_weight_inverse(pu, pv, Wd)
+    torch.cuda.synchronize()
+    k = np.arange(96)
+    rows = [int(r) for r in (298 * k + 7 * (k % 13)) % do]
+    rows = sorted(set(rows + [0, do - 1]))
+    E = np.zeros((len(rows), do))
+    E[np.arange(len(rows)), rows] = 1.0
+    W64 = W.astype(np.float64)
+    ref = ho.apply_staged(ho.apply_transpose_staged(E, do, ru, bu, su) @ W64, di, rv, bv, sv)
+    refi = ho.apply_transpose_staged(ho.apply_staged(E, do, ru, bu, su) @ W64, di, rv, bv, sv)
+    idx = torch.tensor(rows).cuda()
+    assert_parity(to_host64(out[idx]), ref, "bf16", "U^T W V rows")
+    assert_parity(to_host64(inv[idx]), refi, "bf16", "U W V^T rows")
+    nw = float(torch.linalg.matrix_norm(Wd.float()))
+    for t in (out, inv):
+        assert abs(float(torch.linalg.matrix_norm(t.float())) - nw) / nw < 1e-3
+    pu.destroy()
+    pv.destroy()
